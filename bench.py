@@ -1,0 +1,334 @@
+#!/usr/bin/env python3
+"""Benchmark of the update-phase hot path on one MI355X.
+
+A step is one pass of the whole resident hot path over the 125 M-parameter workload (16 subgroups of 7 812 500
+elements, loss scale 1024, one +inf gradient every 50th step): the gradient pass (non-finite check + L2 norm + clip
+factor) followed by the fused AdamW update of every subgroup, all state resident in HBM before the clock starts.  The
+JSON line also carries the roofline of the dominant kernel (measured with events around each of its launches), the
+CPU oracle timed on the host cores, and - as additional information - the tiered pipeline on the 1.3 B-parameter
+host-tier workload (effective PCIe GB/s per direction).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+PCIE_NOMINAL_GBS = 64.0      # PCIe 5.0 x16 per direction, nominal
+BYTES_PER_PARAM_STEP = 28    # read p, m, v (12) + g (2); write p, m, v (12) + bf16 p (2)
+BYTES_PER_PARAM_NORM = 2     # read g
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def resident_bench(args, torch, B, W, np):
+    wl = W.CONFIGS[args.workload]
+    assert wl.n_host == 0, "the resident benchmark needs an all-HBM workload"
+    d = torch.device("cuda:0")
+    N, M = wl.n_total, wl.sub_elems
+    t0 = time.time()
+    flat = {k: torch.empty(N, dtype=torch.float32, device=d) for k in ("p", "m", "v")}
+    flat["g"] = torch.empty(N, dtype=torch.int16, device=d)
+    flat["p16"] = torch.zeros(N, dtype=torch.int16, device=d)
+    hp_ = np.empty(M, np.float32)
+    hg_ = np.empty(M, np.uint16)
+    for k in range(wl.n_sub):
+        W.fill_state(wl, k, hp_, None, None, threads=args.threads)
+        flat["p"][k * M:(k + 1) * M].copy_(torch.from_numpy(hp_))
+        W.fill_grads(wl, k, 0, hg_, threads=args.threads)
+        flat["g"][k * M:(k + 1) * M].copy_(torch.from_numpy(hg_.view(np.int16)))
+    flat["m"].zero_()
+    flat["v"].zero_()
+    table = B.SubgroupTable(B.subgroup(*(flat[key][k * M:(k + 1) * M] for key in ("p", "m", "v", "g", "p16")), n=M)
+                            for k in range(wl.n_sub))
+    ws_bytes = B.mlpo_norm_workspace_bytes()
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=d)
+    scal = torch.zeros(4, dtype=torch.float32, device=d)
+    inf_bits = torch.tensor([0x7F80], dtype=torch.int16, device=d)
+    saved = torch.zeros(1, dtype=torch.int16, device=d)
+    hp = B.HParams(**wl.hp.__dict__)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    log(f"[bench] {wl.name}: {N} params resident, setup {time.time() - t0:.1f}s")
+
+    total = args.warmup + args.steps
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    k_start = [ev() for _ in range(args.steps)]
+    k_end = [ev() for _ in range(args.steps)]
+    n_start = [ev() for _ in range(args.steps)]
+    t_begin, t_end = ev(), ev()
+    applied = 0
+    applied_timed = 0
+    with torch.cuda.stream(stream):
+        for s in range(total):
+            timed = s >= args.warmup
+            if s == args.warmup:
+                stream.synchronize()
+                torch.cuda.synchronize()
+                t_begin.record(stream)
+            inject = wl.injects(s)
+            if inject:
+                idx = wl.inject_index(s)
+                saved.copy_(flat["g"][idx:idx + 1])
+                flat["g"][idx:idx + 1].copy_(inf_bits)
+            i = s - args.warmup
+            if timed:
+                n_start[i].record(stream)
+            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, stream)
+            if timed:
+                k_start[i].record(stream)
+            B.mlpo_adamw_step(table, hp, applied + 1, scal, stream)
+            if timed:
+                k_end[i].record(stream)
+            if inject:
+                flat["g"][idx:idx + 1].copy_(saved)
+            else:
+                applied += 1            # the host mirrors the injection schedule: no read-back of the flag
+                applied_timed += int(timed)
+        t_end.record(stream)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    elapsed_ms = t_begin.elapsed_time(t_end)
+    flag = int(scal.cpu().numpy()[3:4].view(np.uint32)[0])
+    assert flag == (1 if wl.injects(total - 1) else 0)
+    assert bool(torch.isfinite(flat["p"]).all().item()), "state went non-finite"
+
+    inj_timed = [wl.injects(s) for s in range(args.warmup, total)]
+    k_ms = [k_start[i].elapsed_time(k_end[i]) for i in range(args.steps) if not inj_timed[i]]
+    n_ms = [n_start[i].elapsed_time(k_start[i]) for i in range(args.steps)]
+    k_avg = sum(k_ms) / max(len(k_ms), 1)
+    n_avg = sum(n_ms) / len(n_ms)
+    achieved = BYTES_PER_PARAM_STEP * N / (k_avg * 1e-3) / 1e9
+    value = applied_timed * N / (elapsed_ms * 1e-3) / 1e9
+    res = {
+        "metric": "AdamW update throughput, HBM-resident (Gparams/s)",
+        "value": round(value, 3),
+        "unit": "Gparams/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(elapsed_ms / args.steps, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "params": N, "subgroups": wl.n_sub, "subgroup_elems": M,
+                   "loss_scale": wl.loss_scale, "inf_every": wl.inject_every, "applied_steps": applied_timed,
+                   "state": "fp32 p/m/v + bf16 grads + bf16 params, all in HBM"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "adamw_v4_kernel", "avg_launch_ms": round(k_avg, 5),
+                     "min_launch_ms": round(min(k_ms), 5), "bytes_per_launch": BYTES_PER_PARAM_STEP * N},
+        "norm_pass": {"avg_ms": round(n_avg, 5),
+                      "achieved_GBs": round(BYTES_PER_PARAM_NORM * N / (n_avg * 1e-3) / 1e9, 1)},
+        "step_hbm_frac": round((BYTES_PER_PARAM_STEP + BYTES_PER_PARAM_NORM) * N * applied_timed
+                               / (elapsed_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+    del flat, table
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(args, W, np):
+    """The oracle as it stands, all host threads, on the first subgroups of the same workload."""
+    import oracle
+    wl = W.CONFIGS[args.workload]
+    n_sg = min(wl.n_sub, args.cpu_subgroups)
+    M = wl.sub_elems
+    host = []
+    for k in range(n_sg):
+        s = {"p": np.empty(M, np.float32), "m": np.zeros(M, np.float32), "v": np.zeros(M, np.float32),
+             "g": np.empty(M, np.uint16), "p16": np.zeros(M, np.uint16)}
+        W.fill_state(wl, k, s["p"], None, None, threads=args.threads)
+        W.fill_grads(wl, k, 0, s["g"], threads=args.threads)
+        host.append(s)
+    ohp = oracle.HParams(**wl.hp.__dict__)
+
+    def one_step(t):
+        sumsq, flag = 0.0, 0
+        for s in host:
+            a, b = oracle.grad_stats_chunked(s["g"], wl.inv_scale)
+            sumsq += a
+            flag |= b
+        _, _, gmul = oracle.norm_finish(sumsq, wl.inv_scale, wl.max_norm)
+        for s in host:
+            oracle.adamw_f32(s["p"], s["m"], s["v"], s["g"], s["p16"], ohp, t, gmul, chunked=True)
+
+    one_step(1)  # page in
+    t0 = time.perf_counter()
+    one_step(2)
+    dt1 = time.perf_counter() - t0
+    reps = max(2, min(200, int(args.cpu_seconds / max(dt1, 1e-3))))
+    t0 = time.perf_counter()
+    for r in range(reps):
+        one_step(3 + r)
+    dt = time.perf_counter() - t0
+    n = n_sg * M
+    return {"value": round(reps * n / dt / 1e9, 4), "unit": "Gparams/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {n_sg} of {wl.n_sub} subgroups ({n} params) x {reps} steps (norm pass + update), "
+                      f"{dt:.1f} s wall"}
+
+
+def streamed_bench(args, torch, B, W, np):
+    wl = W.CONFIGS[args.streamed]
+    d = torch.device("cuda:0")
+    M = wl.sub_elems
+    t0 = time.time()
+    sgs, keep = [], []
+    hg_ = np.empty(M, np.uint16)
+    g_flat = torch.empty(wl.n_total, dtype=torch.int16, device=d)
+    p16_flat = torch.zeros(wl.n_total, dtype=torch.int16, device=d)
+    for k in range(wl.n_sub):
+        host = wl.tier(k) == 1
+        if host:
+            p, m, v = (torch.empty(M, dtype=torch.float32, pin_memory=True) for _ in range(3))
+            W.fill_state(wl, k, p.numpy(), m.numpy(), v.numpy(), threads=args.threads)
+        else:
+            p, m, v = (torch.empty(M, dtype=torch.float32, device=d) for _ in range(3))
+            tmp = np.empty(M, np.float32)
+            W.fill_state(wl, k, tmp, None, None, threads=args.threads)
+            p.copy_(torch.from_numpy(tmp))
+            m.zero_()
+            v.zero_()
+        W.fill_grads(wl, k, 0, hg_, threads=args.threads)
+        g_flat[k * M:(k + 1) * M].copy_(torch.from_numpy(hg_.view(np.int16)))
+        keep.append((p, m, v))
+        sgs.append(B.subgroup(p, m, v, g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M], n=M,
+                              tier=wl.tier(k)))
+    table = B.SubgroupTable(sgs)
+    ws_bytes = B.mlpo_norm_workspace_bytes()
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=d)
+    scal = torch.zeros(4, dtype=torch.float32, device=d)
+    hp = B.HParams(**wl.hp.__dict__)
+    h2d, cmp_, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    log(f"[bench] {wl.name}: {wl.n_host} host-tier + {wl.n_sub - wl.n_host} HBM subgroups of {M}, "
+        f"setup {time.time() - t0:.1f}s")
+    n_host_params = wl.n_host * M
+    out = {"workload": wl.name, "host_tier_params": n_host_params, "bytes_per_direction_per_step": 12 * n_host_params,
+           "pcie_nominal_GBs": PCIE_NOMINAL_GBS, "runs": []}
+    # plain pinned copies of one subgroup array, for reference: each direction alone, then both at once
+    ref = torch.empty(M, dtype=torch.float32, device=d)
+    ref2 = torch.empty(M, dtype=torch.float32, device=d)
+    hsrc, hdst = keep[0][0], keep[0][1]
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps
+
+    def up():
+        with torch.cuda.stream(h2d):
+            ref.copy_(hsrc, non_blocking=True)
+
+    def down():
+        with torch.cuda.stream(d2h):
+            hdst.copy_(ref2, non_blocking=True)
+
+    saved_m = hdst.clone()
+    bytes_arr = 4 * M
+    out["memcpy_h2d_GBs"] = round(bytes_arr / timed(up) / 1e9, 2)
+    out["memcpy_d2h_GBs"] = round(bytes_arr / timed(down) / 1e9, 2)
+    out["memcpy_duplex_GBs_per_dir"] = round(bytes_arr / timed(lambda: (up(), down())) / 1e9, 2)
+    hdst.copy_(saved_m)
+    del saved_m, ref, ref2
+
+    applied = 0
+    for n_slots, chunk in args.stream_variants:
+        need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
+        stg = torch.empty(need, dtype=torch.uint8, device=d)
+        cfg = B.stream_cfg(n_slots, stg, need, h2d, cmp_, d2h, chunk)
+        times = []
+        for s in range(args.stream_warmup + wl.steps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
+            ok = B.mlpo_stream_update(table, None, hp, applied + 1, scal, cfg)
+            cmp_.synchronize()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t
+            assert ok
+            applied += 1
+            if s >= args.stream_warmup:
+                times.append(dt)
+        mean = sum(times) / len(times)
+        gbs = 12 * n_host_params / mean / 1e9
+        out["runs"].append({"n_slots": n_slots, "chunk_elems": chunk, "steps": len(times),
+                            "ms_per_step": round(mean * 1e3, 2), "min_ms": round(min(times) * 1e3, 2),
+                            "pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
+                            "frac_of_duplex_memcpy": round(gbs / out["memcpy_duplex_GBs_per_dir"], 4),
+                            "Gparams_s": round(wl.n_total / mean / 1e9, 3)})
+        log(f"[bench] streamed slots={n_slots} chunk={chunk}: {out['runs'][-1]}")
+        del stg, cfg
+    best = max(out["runs"], key=lambda r: r["pcie_GBs_per_dir"])
+    out["best"] = best
+    return out
+
+
+def parse_variants(text):
+    res = []
+    for part in text.split(","):
+        a, _, b = part.partition(":")
+        res.append((int(a), int(b or 0)))
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
+    ap.add_argument("--stream-variants", default="3:0,3:16777216,4:16777216",
+                    help="comma list of n_slots:chunk_elems")
+    ap.add_argument("--stream-warmup", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-subgroups", type=int, default=8)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--threads", type=int, default=16)
+    ap.add_argument("--option", action="append", default=[], help="library tuning option key=value")
+    args = ap.parse_args()
+    args.stream_variants = parse_variants(args.stream_variants)
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2509_02480_amd import binding as B
+    from paper_2509_02480_amd import workloads as W
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    B.lib()  # fails loudly if the HIP library is not built
+    for opt in args.option:
+        k, _, v = opt.partition("=")
+        B.mlpo_set_option(k, int(v))
+    res = resident_bench(args, torch, B, W, np)
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(args, W, np)
+    else:
+        res["cpu_baseline"] = None
+    if args.streamed != "none":
+        res["streamed"] = streamed_bench(args, torch, B, W, np)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,178 @@
+/*
+ * mlpo.h - C ABI of the MI355X (gfx950) update-phase library for MLP-Offload (arXiv 2509.02480).
+ *
+ * The library runs the per-subgroup body of the paper's update phase (Algorithm 1: wait for the subgroup, upcast its
+ * half-precision gradients on the fly, update the fp32 master parameters / momentum / variance, push the
+ * half-precision parameters, flush, prefetch the next) with the GPU as the place of the update, HBM as the fast tier
+ * and pinned host memory as the slow tier - the generalisation to a GPU-CPU tier pair that Section 3.2 "Unified
+ * Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers" mentions.
+ *
+ * Conventions
+ *   - Every call returns 0 (MLPO_OK) or a negative code; mlpo_last_error() gives the text for the calling thread.
+ *   - The caller owns every buffer.  The library allocates no device or host memory for user data, keeps no pointer
+ *     after the work it enqueued has completed, and never frees anything passed in.
+ *   - Calls enqueue work on the given HIP streams (passed as void*, i.e. a hipStream_t; NULL is the default stream)
+ *     and return without waiting, except where stated.
+ *   - "device" pointers are HBM addresses valid on the current HIP device; "pinned host" pointers are page-locked
+ *     host memory (hipHostMalloc) mapped into the device's address space; "host" pointers are ordinary host memory
+ *     read only during the call.
+ *   - fp32 arrays must be 4-byte aligned and bf16 arrays 2-byte aligned.  The fast kernels are used for a subgroup
+ *     whose p, m, v are 16-byte aligned and whose g, p16 are 8-byte aligned; anything else takes a slower
+ *     element-wise kernel with identical results.
+ *   - bf16 values are passed as raw uint16_t bit patterns (upper half of the IEEE fp32 word).
+ */
+#ifndef MLPO_H
+#define MLPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MLPO_OK 0
+#define MLPO_EINVAL (-1) /* NULL / misaligned pointer, bad size, bad hyper-parameter, bad tier */
+#define MLPO_EHIP (-2)   /* a HIP runtime call failed; mlpo_last_error() names it */
+#define MLPO_ENOMEM (-3) /* a caller-provided workspace or staging buffer is too small */
+
+/* AdamW hyper-parameters, fp32 as stored.  bias_correction != 0 applies the 1 - beta^t corrections. */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t bias_correction;
+} mlpo_adamw_hparams;
+
+/* One subgroup (Section 2 "Sharded Model and Optimizer States Into Subgroups"): n elements of fp32 master parameters
+ * p, momentum m, variance v, the bf16 gradients g that drive the update and the bf16 working copy p16 that receives
+ * the downcast parameters.  g and p16 are always device memory.  tier says where p, m, v live:
+ * MLPO_TIER_HBM (device) or MLPO_TIER_HOST (pinned host). */
+#define MLPO_TIER_HBM 0
+#define MLPO_TIER_HOST 1
+typedef struct {
+    float* p;
+    float* m;
+    float* v;
+    const uint16_t* g;
+    uint16_t* p16;
+    uint64_t n;
+    int32_t tier;
+    int32_t reserved; /* must be 0 */
+} mlpo_subgroup;
+
+/* The four scalars that link the gradient pass to the update, kept in device memory so that no host round trip is
+ * needed between the two (16 bytes, 16-byte aligned). */
+typedef struct {
+    float norm;         /* L2 norm of the unscaled gradients of all subgroups */
+    float clip_coef;    /* max_norm / (norm + 1e-6) if clipping is on and norm > max_norm, else 1 */
+    float gmul;         /* inv_scale * clip_coef: the factor the update applies to every raw gradient */
+    uint32_t found_inf; /* 1 if any gradient is +-inf or NaN (the whole step must then be skipped), else 0 */
+} mlpo_step_scalars;
+
+/* Text of the last error on the calling thread ("" if none).  The pointer stays valid until the thread's next
+ * failing call. */
+const char* mlpo_last_error(void);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int32_t mlpo_version(void);
+
+/* Bytes of device workspace mlpo_grad_unscale_norm needs (a constant; 256-byte alignment required). */
+size_t mlpo_norm_workspace_bytes(void);
+
+/*
+ * Gradient pass before the update (mixed-precision convention; the paper's text stops at "gradients are upscaled to
+ * FP32 and used by the optimizer", Section 2 "Mixed Precision Training"): over the gradients of ALL n_sg subgroups
+ *   found_inf = any g_i with its bf16 exponent field all ones,
+ *   norm      = sqrt( sum_i ((double)(f32(g_i) * inv_scale))^2 ), rounded to fp32,
+ *   clip_coef, gmul as described at mlpo_step_scalars.
+ * The sum is taken in fp64 in a fixed order: the result is deterministic for a given argument list.
+ *
+ *   sg, n_sg     host array of subgroups; only .g and .n are read (n may be 0).  n_sg >= 0.
+ *   inv_scale    1 / loss scale, finite and > 0.
+ *   max_norm     clipping bound; <= 0 turns clipping off.
+ *   workspace    device, >= mlpo_norm_workspace_bytes(), 256-byte aligned; contents need not be preserved or cleared.
+ *   out          device, 16-byte aligned; written by the last kernel enqueued.
+ *   stream       hipStream_t.
+ * Errors: MLPO_EINVAL (arguments), MLPO_ENOMEM (workspace_bytes too small), MLPO_EHIP.
+ */
+int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scale, float max_norm, void* workspace,
+                           size_t workspace_bytes, mlpo_step_scalars* out, void* stream);
+
+/*
+ * AdamW on HBM-resident subgroups, in place, with the gradient upcast and the parameter downcast fused in
+ * (Algorithm 1's convert / update / push steps; Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion").
+ * With the per-step scalars (computed on the host in fp64 and rounded once to fp32)
+ *   omb1 = 1 - beta1, omb2 = 1 - beta2, bc1 = 1 - beta1^step, bc2 = 1 - beta2^step (both 1 without bias correction),
+ *   step_size = lr / bc1, sqbc2 = sqrt(bc2), decay = 1 - lr * weight_decay
+ * every element does, each operation rounded to fp32 once and none fused:
+ *   g  = f32(g_bf16) * gmul
+ *   m' = beta1 * m + omb1 * g
+ *   v' = beta2 * v + omb2 * (g * g)
+ *   p' = p * decay - step_size * (m' / (sqrt(v') / sqbc2 + eps))
+ *   p16 = bf16(p') rounded to nearest, ties to even
+ *
+ *   sg, n_sg     host array; every tier must be MLPO_TIER_HBM; all pointers device; n may be 0.
+ *   hp           host pointer.  lr, eps, weight_decay finite and >= 0; 0 <= beta < 1.
+ *   step         1-based count of applied steps including this one (>= 1).
+ *   scalars      device pointer to the record written by mlpo_grad_unscale_norm, or NULL.  When given, the kernel
+ *                reads gmul from it and does nothing at all if found_inf is set (no state, no p16 is written);
+ *                when NULL, gmul = 1 and the step is always applied.
+ *   stream       hipStream_t.
+ * The caller advances its step count only for applied steps.
+ * Errors: MLPO_EINVAL, MLPO_EHIP.
+ */
+int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hparams* hp, int64_t step,
+                    const mlpo_step_scalars* scalars, void* stream);
+
+/* Configuration of the tiered pipeline. */
+typedef struct {
+    int32_t n_slots;      /* staging slots = bound on subgroups (or chunks) in flight; 1..MLPO_MAX_SLOTS */
+    int32_t reserved;     /* must be 0 */
+    uint64_t chunk_elems; /* 0: a whole subgroup per transfer; else transfers of this many elements (multiple of 4) */
+    void* staging;        /* device, 256-byte aligned, caller-owned */
+    size_t staging_bytes; /* >= mlpo_stream_staging_bytes(...) */
+    void* h2d;            /* hipStream_t for host-to-device copies */
+    void* compute;        /* hipStream_t for kernels */
+    void* d2h;            /* hipStream_t for device-to-host copies */
+} mlpo_stream_cfg;
+
+#define MLPO_MAX_SLOTS 8
+
+/* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier). */
+size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems);
+
+/*
+ * One update phase over subgroups of both tiers (Algorithm 1, with the fetch / update / flush overlap of Section 3.4
+ * and the bound on subgroups in flight that Section 3.2 "Optimized Virtual Tier Concurrency Control" motivates).
+ * HBM-tier subgroups are updated in place as in mlpo_adamw_step.  Each host-tier subgroup (or chunk of one) is
+ * copied host-to-device into a free staging slot on the h2d stream, updated there on the compute stream (g and p16
+ * are read/written at their device homes), and copied back on the d2h stream; a slot is reused only after its copy
+ * back has completed, so at most n_slots transfers are in flight.  Results are bit-identical to the resident path
+ * whatever n_slots, chunk_elems and order are.
+ *
+ *   order        host array, a permutation of 0..n_sg-1 giving the processing order, or NULL for ascending.
+ *   scalars      device pointer or NULL, as for mlpo_adamw_step.  When given, the call first copies the record to the
+ *                host (a 16-byte copy and a wait on the compute stream) because the transfers are issued from the
+ *                host: a step with found_inf set moves no data at all.
+ *   applied      host pointer or NULL; receives 1 if the step was enqueued, 0 if it was skipped.
+ *   cfg          host pointer.  The three streams may be distinct (needed for overlap) or equal.
+ * On return everything is enqueued; the compute stream is made to wait for the last copy back, so synchronising
+ * cfg->compute alone is enough to see the final state.  Calls sharing a staging buffer must not overlap.
+ * Errors: MLPO_EINVAL, MLPO_ENOMEM (staging too small), MLPO_EHIP.
+ */
+int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
+                       int64_t step, const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, int32_t* applied);
+
+/* Tuning knobs for measurements (process-wide; not needed for correct results).  Unknown keys give MLPO_EINVAL.
+ *   "adamw_grid_per_cu"  blocks per compute unit of the persistent update grid (default in the source)
+ *   "adamw_variant"      kernel variant index
+ *   "norm_grid_per_cu"   blocks per compute unit of the gradient pass
+ */
+int mlpo_set_option(const char* key, int64_t value);
+
+/* Releases the events the pipeline caches (optional; safe to call when idle). */
+int mlpo_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLPO_H */

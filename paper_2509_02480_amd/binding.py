@@ -1,0 +1,194 @@
+"""ctypes binding of libmlpo.so: the same entry points as include/mlpo.h, argument marshalling only.
+
+Every step of the update runs in the library's HIP kernels; nothing here computes.  Tensors may be anything with a
+``data_ptr()`` (torch tensors on the device or in pinned host memory) or plain integer addresses; streams anything
+with a ``cuda_stream`` attribute (torch.cuda.Stream) or an integer hipStream_t handle.  There is no fallback: if the
+library has not been built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Iterable, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmlpo.so")
+
+MLPO_OK, MLPO_EINVAL, MLPO_EHIP, MLPO_ENOMEM = 0, -1, -2, -3
+TIER_HBM, TIER_HOST = 0, 1
+MAX_SLOTS = 8
+
+EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm",
+           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_set_option", "mlpo_shutdown")
+
+
+class MlpoError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"mlpo error {code}: {text}")
+        self.code = code
+
+
+class HParamsC(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("bias_correction", C.c_int32)]
+
+
+class SubgroupC(C.Structure):
+    _fields_ = [("p", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p), ("g", C.c_void_p), ("p16", C.c_void_p),
+                ("n", C.c_uint64), ("tier", C.c_int32), ("reserved", C.c_int32)]
+
+
+class StepScalarsC(C.Structure):
+    _fields_ = [("norm", C.c_float), ("clip_coef", C.c_float), ("gmul", C.c_float), ("found_inf", C.c_uint32)]
+
+
+class StreamCfgC(C.Structure):
+    _fields_ = [("n_slots", C.c_int32), ("reserved", C.c_int32), ("chunk_elems", C.c_uint64),
+                ("staging", C.c_void_p), ("staging_bytes", C.c_size_t), ("h2d", C.c_void_p), ("compute", C.c_void_p),
+                ("d2h", C.c_void_p)]
+
+
+@dataclass
+class HParams:
+    lr: float = 1e-4
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.01
+    bias_correction: bool = True
+
+    def c(self) -> HParamsC:
+        return HParamsC(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.bias_correction))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it is missing: there is no other implementation to fall back to."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; "
+                               "g.build()' at the repository root)")
+        L = C.CDLL(LIB_PATH)
+        L.mlpo_last_error.restype = C.c_char_p
+        L.mlpo_last_error.argtypes = []
+        L.mlpo_version.restype = C.c_int32
+        L.mlpo_version.argtypes = []
+        L.mlpo_norm_workspace_bytes.restype = C.c_size_t
+        L.mlpo_norm_workspace_bytes.argtypes = []
+        L.mlpo_grad_unscale_norm.restype = C.c_int
+        L.mlpo_grad_unscale_norm.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_size_t,
+                                             C.c_void_p, C.c_void_p]
+        L.mlpo_adamw_step.restype = C.c_int
+        L.mlpo_adamw_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(HParamsC), C.c_int64, C.c_void_p, C.c_void_p]
+        L.mlpo_stream_staging_bytes.restype = C.c_size_t
+        L.mlpo_stream_staging_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64]
+        L.mlpo_stream_update.restype = C.c_int
+        L.mlpo_stream_update.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(HParamsC), C.c_int64,
+                                         C.c_void_p, C.POINTER(StreamCfgC), C.POINTER(C.c_int32)]
+        L.mlpo_set_option.restype = C.c_int
+        L.mlpo_set_option.argtypes = [C.c_char_p, C.c_int64]
+        L.mlpo_shutdown.restype = C.c_int
+        L.mlpo_shutdown.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != MLPO_OK:
+        raise MlpoError(rc, lib().mlpo_last_error().decode("utf-8", "replace"))
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    return int(x)
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    h = getattr(s, "cuda_stream", s)
+    return int(h) or None
+
+
+def subgroup(p, m, v, g, p16, n: Optional[int] = None, tier: int = TIER_HBM) -> SubgroupC:
+    """One descriptor from five buffers (tensors or addresses).  ``n`` defaults to the gradient tensor's length."""
+    if n is None:
+        n = g.numel()
+    return SubgroupC(_ptr(p), _ptr(m), _ptr(v), _ptr(g), _ptr(p16), int(n), int(tier), 0)
+
+
+class SubgroupTable:
+    """A contiguous host array of descriptors, built once and passed to many calls."""
+
+    def __init__(self, subgroups: Iterable[SubgroupC]):
+        sgs = list(subgroups)
+        self.n = len(sgs)
+        self.array = (SubgroupC * max(self.n, 1))(*sgs)
+
+    def __len__(self) -> int:
+        return self.n
+
+
+def _table(sgs) -> SubgroupTable:
+    return sgs if isinstance(sgs, SubgroupTable) else SubgroupTable(sgs)
+
+
+def mlpo_version() -> int:
+    return int(lib().mlpo_version())
+
+
+def mlpo_norm_workspace_bytes() -> int:
+    return int(lib().mlpo_norm_workspace_bytes())
+
+
+def mlpo_grad_unscale_norm(sgs, inv_scale: float, max_norm: float, workspace, workspace_bytes: int, out,
+                           stream=None) -> None:
+    t = _table(sgs)
+    _check(lib().mlpo_grad_unscale_norm(t.array, t.n, inv_scale, max_norm, _ptr(workspace), workspace_bytes,
+                                        _ptr(out), _stream(stream)))
+
+
+def mlpo_adamw_step(sgs, hp: HParams, step: int, scalars=None, stream=None) -> None:
+    t = _table(sgs)
+    h = hp.c() if isinstance(hp, HParams) else hp
+    _check(lib().mlpo_adamw_step(t.array, t.n, C.byref(h), step, _ptr(scalars), _stream(stream)))
+
+
+def mlpo_stream_staging_bytes(sgs, n_slots: int, chunk_elems: int = 0) -> int:
+    t = _table(sgs)
+    return int(lib().mlpo_stream_staging_bytes(t.array, t.n, n_slots, chunk_elems))
+
+
+def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chunk_elems: int = 0) -> StreamCfgC:
+    return StreamCfgC(n_slots, 0, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d), _stream(compute),
+                      _stream(d2h))
+
+
+def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: int, scalars, cfg: StreamCfgC) -> bool:
+    """Returns True if the step was enqueued, False if it was skipped because of a non-finite gradient."""
+    t = _table(sgs)
+    h = hp.c() if isinstance(hp, HParams) else hp
+    ordp = None
+    if order is not None:
+        ordp = (C.c_int32 * max(len(order), 1))(*order)
+        if len(order) != t.n:
+            raise ValueError("order must have one entry per subgroup")
+    applied = C.c_int32(-1)
+    _check(lib().mlpo_stream_update(t.array, t.n, ordp, C.byref(h), step, _ptr(scalars), C.byref(cfg),
+                                    C.byref(applied)))
+    return bool(applied.value)
+
+
+def mlpo_set_option(key: str, value: int) -> None:
+    _check(lib().mlpo_set_option(key.encode(), value))
+
+
+def mlpo_shutdown() -> None:
+    _check(lib().mlpo_shutdown())

@@ -1,0 +1,342 @@
+// C ABI of libmlpo: argument checking, per-step scalars, and the tiered fetch / update / flush pipeline.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "mlpo_internal.h"
+
+namespace mlpo {
+
+// ---- errors -----------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// ---- tuning / device ------------------------------------------------------------
+Tuning& tuning() {
+    static Tuning t = {/*adamw_grid_per_cu=*/8, /*adamw_variant=*/0, /*norm_grid_per_cu=*/8};
+    return t;
+}
+
+int num_cus() {
+    static std::mutex mu;
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    std::lock_guard<std::mutex> lk(mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+// ---- hyper-parameters -------------------------------------------------------------
+int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step) {
+    if (hp == nullptr) return fail(MLPO_EINVAL, "hparams is NULL");
+    if (step < 1) return fail(MLPO_EINVAL, "step must be >= 1 (got %lld)", (long long)step);
+    if (!(isfinite(hp->lr) && hp->lr >= 0.0f)) return fail(MLPO_EINVAL, "lr must be finite and >= 0");
+    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f)) return fail(MLPO_EINVAL, "beta1 must be in [0, 1)");
+    if (!(hp->beta2 >= 0.0f && hp->beta2 < 1.0f)) return fail(MLPO_EINVAL, "beta2 must be in [0, 1)");
+    if (!(isfinite(hp->eps) && hp->eps >= 0.0f)) return fail(MLPO_EINVAL, "eps must be finite and >= 0");
+    if (!(isfinite(hp->weight_decay) && hp->weight_decay >= 0.0f))
+        return fail(MLPO_EINVAL, "weight_decay must be finite and >= 0");
+    return MLPO_OK;
+}
+
+// The scalars of one step: exact expressions evaluated in double, then one rounding to fp32 each.
+AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step) {
+    const double beta1 = hp.beta1, beta2 = hp.beta2;
+    double corr1 = 1.0, corr2 = 1.0;
+    if (hp.bias_correction != 0) {
+        corr1 -= pow(beta1, (double)step);
+        corr2 -= pow(beta2, (double)step);
+    }
+    AdamwConsts c;
+    c.beta1 = hp.beta1;
+    c.beta2 = hp.beta2;
+    c.omb1 = (float)(1.0 - beta1);
+    c.omb2 = (float)(1.0 - beta2);
+    c.eps = hp.eps;
+    c.step_size = (float)((double)hp.lr / corr1);
+    c.sqbc2 = (float)sqrt(corr2);
+    c.decay = (float)(1.0 - (double)hp.lr * (double)hp.weight_decay);
+    return c;
+}
+
+// ---- subgroup checks ----------------------------------------------------------------
+static bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+static int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, int allow_host) {
+    if (n_sg < 0) return fail(MLPO_EINVAL, "n_sg is negative");
+    if (n_sg > 0 && sg == nullptr) return fail(MLPO_EINVAL, "subgroup array is NULL");
+    for (int32_t i = 0; i < n_sg; ++i) {
+        const mlpo_subgroup& s = sg[i];
+        if (s.n > ((uint64_t)1 << 48)) return fail(MLPO_EINVAL, "subgroup %d: n is implausibly large", i);
+        if (s.n != 0 && s.g == nullptr) return fail(MLPO_EINVAL, "subgroup %d: g is NULL", i);
+        if (misaligned(s.g, 2)) return fail(MLPO_EINVAL, "subgroup %d: g is not 2-byte aligned", i);
+        if (grads_only) continue;
+        if (s.reserved != 0) return fail(MLPO_EINVAL, "subgroup %d: reserved field is not 0", i);
+        if (s.tier != MLPO_TIER_HBM && s.tier != MLPO_TIER_HOST)
+            return fail(MLPO_EINVAL, "subgroup %d: unknown tier %d", i, s.tier);
+        if (s.tier == MLPO_TIER_HOST && !allow_host)
+            return fail(MLPO_EINVAL, "subgroup %d is host-tier: use mlpo_stream_update", i);
+        if (s.n != 0 && (s.p == nullptr || s.m == nullptr || s.v == nullptr || s.p16 == nullptr))
+            return fail(MLPO_EINVAL, "subgroup %d: NULL state pointer", i);
+        if (misaligned(s.p, 4) || misaligned(s.m, 4) || misaligned(s.v, 4))
+            return fail(MLPO_EINVAL, "subgroup %d: p/m/v not 4-byte aligned", i);
+        if (misaligned(s.p16, 2)) return fail(MLPO_EINVAL, "subgroup %d: p16 is not 2-byte aligned", i);
+    }
+    return MLPO_OK;
+}
+
+// ---- pipeline events --------------------------------------------------------------------
+struct SlotEvents {
+    hipEvent_t h2d_done, upd_done, d2h_done;
+};
+struct EventCache {
+    std::mutex mu;
+    int device = -1;
+    std::vector<SlotEvents> slots;
+    hipEvent_t fence = nullptr;   // orders streams at the start and end of a call
+    hipEvent_t fence2 = nullptr;
+};
+static EventCache& events() {
+    static EventCache c;
+    return c;
+}
+
+static int release_events_locked(EventCache& c) {
+    for (auto& s : c.slots) {
+        (void)hipEventDestroy(s.h2d_done);
+        (void)hipEventDestroy(s.upd_done);
+        (void)hipEventDestroy(s.d2h_done);
+    }
+    c.slots.clear();
+    if (c.fence) (void)hipEventDestroy(c.fence);
+    if (c.fence2) (void)hipEventDestroy(c.fence2);
+    c.fence = c.fence2 = nullptr;
+    c.device = -1;
+    return MLPO_OK;
+}
+
+static int ensure_events_locked(EventCache& c, int n_slots) {
+    int dev = 0;
+    MLPO_HIP(hipGetDevice(&dev));
+    if (c.device != dev) release_events_locked(c);
+    c.device = dev;
+    if (c.fence == nullptr) MLPO_HIP(hipEventCreateWithFlags(&c.fence, hipEventDisableTiming));
+    if (c.fence2 == nullptr) MLPO_HIP(hipEventCreateWithFlags(&c.fence2, hipEventDisableTiming));
+    while ((int)c.slots.size() < n_slots) {
+        SlotEvents s;
+        MLPO_HIP(hipEventCreateWithFlags(&s.h2d_done, hipEventDisableTiming));
+        MLPO_HIP(hipEventCreateWithFlags(&s.upd_done, hipEventDisableTiming));
+        MLPO_HIP(hipEventCreateWithFlags(&s.d2h_done, hipEventDisableTiming));
+        c.slots.push_back(s);
+    }
+    return MLPO_OK;
+}
+
+static uint64_t round_up4(uint64_t x) { return (x + 3u) & ~(uint64_t)3u; }
+
+// Elements per staging slot: the largest transfer unit among host-tier subgroups, rounded so that the three arrays
+// of a slot keep 16-byte alignment.
+static uint64_t slot_elems_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems) {
+    uint64_t mx = 0;
+    for (int32_t i = 0; i < n_sg; ++i)
+        if (sg[i].tier == MLPO_TIER_HOST && sg[i].n > mx) mx = sg[i].n;
+    if (chunk_elems != 0 && chunk_elems < mx) mx = chunk_elems;
+    return round_up4(mx);
+}
+
+}  // namespace mlpo
+
+using namespace mlpo;
+
+extern "C" {
+
+const char* mlpo_last_error(void) { return g_err; }
+
+int32_t mlpo_version(void) { return 100; }
+
+size_t mlpo_norm_workspace_bytes(void) { return grad_norm_workspace_bytes(); }
+
+int mlpo_set_option(const char* key, int64_t value) {
+    if (key == nullptr) return fail(MLPO_EINVAL, "key is NULL");
+    if (value < -1 || value > 1024) return fail(MLPO_EINVAL, "value out of range");
+    if (strcmp(key, "adamw_grid_per_cu") == 0) tuning().adamw_grid_per_cu = (int)value;
+    else if (strcmp(key, "adamw_variant") == 0) tuning().adamw_variant = (int)value;
+    else if (strcmp(key, "norm_grid_per_cu") == 0) tuning().norm_grid_per_cu = (int)value;
+    else return fail(MLPO_EINVAL, "unknown option '%s'", key);
+    return MLPO_OK;
+}
+
+int mlpo_shutdown(void) {
+    EventCache& c = events();
+    std::lock_guard<std::mutex> lk(c.mu);
+    return release_events_locked(c);
+}
+
+int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scale, float max_norm, void* workspace,
+                           size_t workspace_bytes, mlpo_step_scalars* out, void* stream) {
+    int rc = validate_subgroups(sg, n_sg, /*grads_only=*/true, 1);
+    if (rc != MLPO_OK) return rc;
+    if (!(isfinite(inv_scale) && inv_scale > 0.0f)) return fail(MLPO_EINVAL, "inv_scale must be finite and > 0");
+    if (isnan(max_norm)) return fail(MLPO_EINVAL, "max_norm is NaN");
+    if (workspace == nullptr || misaligned(workspace, 256))
+        return fail(MLPO_EINVAL, "workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < grad_norm_workspace_bytes())
+        return fail(MLPO_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, grad_norm_workspace_bytes());
+    if (out == nullptr || misaligned(out, 16)) return fail(MLPO_EINVAL, "out is NULL or not 16-byte aligned");
+    return launch_grad_norm(sg, n_sg, inv_scale, max_norm, workspace, out, static_cast<hipStream_t>(stream));
+}
+
+int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hparams* hp, int64_t step,
+                    const mlpo_step_scalars* scalars, void* stream) {
+    int rc = validate_subgroups(sg, n_sg, false, /*allow_host=*/0);
+    if (rc != MLPO_OK) return rc;
+    rc = validate_hparams(hp, step);
+    if (rc != MLPO_OK) return rc;
+    if (scalars != nullptr && misaligned(scalars, 16)) return fail(MLPO_EINVAL, "scalars not 16-byte aligned");
+    if (n_sg == 0) return MLPO_OK;
+    const AdamwConsts c = make_consts(*hp, step);
+    std::vector<SgView> views((size_t)n_sg);
+    for (int32_t i = 0; i < n_sg; ++i) views[i] = SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n};
+    return launch_adamw(views.data(), n_sg, c, scalars, static_cast<hipStream_t>(stream));
+}
+
+size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems) {
+    if (sg == nullptr || n_sg <= 0 || n_slots <= 0) return 0;
+    return (size_t)(slot_elems_for(sg, n_sg, chunk_elems) * 12u * (uint64_t)n_slots);
+}
+
+int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
+                       int64_t step, const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, int32_t* applied) {
+    int rc = validate_subgroups(sg, n_sg, false, /*allow_host=*/1);
+    if (rc != MLPO_OK) return rc;
+    rc = validate_hparams(hp, step);
+    if (rc != MLPO_OK) return rc;
+    if (scalars != nullptr && misaligned(scalars, 16)) return fail(MLPO_EINVAL, "scalars not 16-byte aligned");
+    if (cfg == nullptr) return fail(MLPO_EINVAL, "cfg is NULL");
+    if (cfg->reserved != 0) return fail(MLPO_EINVAL, "cfg reserved field is not 0");
+    if (cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS)
+        return fail(MLPO_EINVAL, "n_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->n_slots);
+    if (cfg->chunk_elems % 4 != 0) return fail(MLPO_EINVAL, "chunk_elems must be a multiple of 4");
+    if (order != nullptr) {
+        std::vector<char> seen((size_t)n_sg, 0);
+        for (int32_t i = 0; i < n_sg; ++i) {
+            if (order[i] < 0 || order[i] >= n_sg || seen[(size_t)order[i]])
+                return fail(MLPO_EINVAL, "order is not a permutation of 0..n_sg-1");
+            seen[(size_t)order[i]] = 1;
+        }
+    }
+    const uint64_t slot_elems = slot_elems_for(sg, n_sg, cfg->chunk_elems);
+    const uint64_t need = slot_elems * 12u * (uint64_t)cfg->n_slots;
+    if (need > 0) {
+        if (cfg->staging == nullptr || misaligned(cfg->staging, 256))
+            return fail(MLPO_EINVAL, "staging is NULL or not 256-byte aligned");
+        if (cfg->staging_bytes < need)
+            return fail(MLPO_ENOMEM, "staging has %zu bytes, %llu needed", cfg->staging_bytes,
+                        (unsigned long long)need);
+    }
+    if (applied != nullptr) *applied = 1;
+    if (n_sg == 0) return MLPO_OK;
+
+    hipStream_t s_h2d = static_cast<hipStream_t>(cfg->h2d);
+    hipStream_t s_cmp = static_cast<hipStream_t>(cfg->compute);
+    hipStream_t s_d2h = static_cast<hipStream_t>(cfg->d2h);
+
+    // The transfers are issued from the host, so the skip decision has to be known here.
+    if (scalars != nullptr) {
+        mlpo_step_scalars h;
+        MLPO_HIP(hipMemcpyAsync(&h, scalars, sizeof h, hipMemcpyDeviceToHost, s_cmp));
+        MLPO_HIP(hipStreamSynchronize(s_cmp));
+        if (h.found_inf != 0u) {
+            if (applied != nullptr) *applied = 0;
+            return MLPO_OK;
+        }
+    }
+
+    const AdamwConsts c = make_consts(*hp, step);
+
+    // HBM-tier subgroups first: their kernel runs while the first fetches are in flight.
+    std::vector<SgView> resident;
+    std::vector<int32_t> host_ids;
+    for (int32_t k = 0; k < n_sg; ++k) {
+        const int32_t i = order ? order[k] : k;
+        if (sg[i].n == 0) continue;
+        if (sg[i].tier == MLPO_TIER_HBM)
+            resident.push_back(SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n});
+        else
+            host_ids.push_back(i);
+    }
+
+    EventCache& ec = events();
+    std::lock_guard<std::mutex> lk(ec.mu);
+    if (!host_ids.empty()) {
+        rc = ensure_events_locked(ec, cfg->n_slots);
+        if (rc != MLPO_OK) return rc;
+        // Work enqueued earlier on the flush and compute streams (a previous step's copy back, the gradient pass)
+        // must be complete before this step's first fetch overwrites a staging slot or reads the host tier.
+        MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
+        MLPO_HIP(hipStreamWaitEvent(s_h2d, ec.fence, 0));
+        MLPO_HIP(hipEventRecord(ec.fence2, s_cmp));
+        MLPO_HIP(hipStreamWaitEvent(s_h2d, ec.fence2, 0));
+    }
+    if (!resident.empty()) {
+        rc = launch_adamw(resident.data(), (int)resident.size(), c, scalars, s_cmp);
+        if (rc != MLPO_OK) return rc;
+    }
+
+    float* staging = static_cast<float*>(cfg->staging);
+    uint64_t piece = 0;
+    for (int32_t i : host_ids) {
+        const mlpo_subgroup& s = sg[i];
+        for (uint64_t off = 0; off < s.n; off += slot_elems, ++piece) {
+            const uint64_t len = (s.n - off < slot_elems) ? (s.n - off) : slot_elems;
+            const size_t bytes = (size_t)len * sizeof(float);
+            const int k = (int)(piece % (uint64_t)cfg->n_slots);
+            SlotEvents& ev = ec.slots[(size_t)k];
+            float* sp = staging + (uint64_t)k * 3u * slot_elems;
+            float* sm = sp + slot_elems;
+            float* sv = sm + slot_elems;
+            // fetch: only into a slot whose previous occupant has been flushed
+            if (piece >= (uint64_t)cfg->n_slots) MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.d2h_done, 0));
+            MLPO_HIP(hipMemcpyAsync(sp, s.p + off, bytes, hipMemcpyHostToDevice, s_h2d));
+            MLPO_HIP(hipMemcpyAsync(sm, s.m + off, bytes, hipMemcpyHostToDevice, s_h2d));
+            MLPO_HIP(hipMemcpyAsync(sv, s.v + off, bytes, hipMemcpyHostToDevice, s_h2d));
+            MLPO_HIP(hipEventRecord(ev.h2d_done, s_h2d));
+            // update in the slot; gradients and bf16 parameters stay at their device homes
+            MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.h2d_done, 0));
+            const SgView view{sp, sm, sv, s.g + off, s.p16 + off, len};
+            rc = launch_adamw(&view, 1, c, scalars, s_cmp);
+            if (rc != MLPO_OK) return rc;
+            MLPO_HIP(hipEventRecord(ev.upd_done, s_cmp));
+            // flush
+            MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
+            MLPO_HIP(hipMemcpyAsync(s.p + off, sp, bytes, hipMemcpyDeviceToHost, s_d2h));
+            MLPO_HIP(hipMemcpyAsync(s.m + off, sm, bytes, hipMemcpyDeviceToHost, s_d2h));
+            MLPO_HIP(hipMemcpyAsync(s.v + off, sv, bytes, hipMemcpyDeviceToHost, s_d2h));
+            MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
+        }
+    }
+    if (!host_ids.empty()) {
+        // join: the compute stream sees the end of the last flush
+        MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
+        MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
+    }
+    return MLPO_OK;
+}
+
+}  // extern "C"

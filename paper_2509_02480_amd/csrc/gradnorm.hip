@@ -1,0 +1,229 @@
+// Gradient pass before the update: non-finite check, L2 norm of the unscaled gradients, clip factor (gfx950).
+//
+// Pass 1 streams the bf16 gradients of a table of subgroups once (2 bytes per element, 128-bit loads after peeling
+// each subgroup's unaligned head, grid-stride persistent blocks).  Every lane widens its gradients, multiplies by
+// 1/loss-scale in fp32 and accumulates the squares in fp64; the non-finite test is an integer test of the bf16
+// exponent field.  Lanes are combined by wavefront shuffles, wavefronts through LDS, and each block writes one fp64
+// partial and one flag.  Pass 2 (one block) adds the partials in a fixed order and derives norm, clip coefficient and
+// the gradient multiplier.  No atomics: the result depends only on the argument list, not on scheduling.
+#include <math.h>
+
+#include "mlpo_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace mlpo {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 256;
+constexpr int kUnroll = 4;
+constexpr uint32_t kTile = kBlock * 8 * kUnroll;  // body elements per tile
+constexpr int kMaxSg = 96;
+constexpr int kMaxGrid = 4096;
+
+struct NormBatch {
+    const uint16_t* body[kMaxSg];  // 16-byte aligned start of the vector body
+    uint64_t n_body[kMaxSg];       // elements from body to the end of the subgroup
+    uint32_t tile_begin[kMaxSg + 1];
+    uint8_t head[kMaxSg];  // elements before body (0..7), handled by the first tile
+    int32_t n_sg;
+};
+
+// Workspace layout (device).
+struct Workspace {
+    double running_sum;
+    uint32_t running_flag;
+    uint32_t pad[61];
+    double partial[kMaxGrid];
+    uint32_t flag[kMaxGrid];
+};
+static_assert(offsetof(Workspace, partial) == 256, "layout");
+
+__device__ __forceinline__ void accum_word(uint32_t w, float inv_scale, double& acc, uint32_t& bad) {
+    bad |= (uint32_t)((w & 0x7F80u) == 0x7F80u) | (uint32_t)((w & 0x7F800000u) == 0x7F800000u);
+    const float u0 = __uint_as_float(w << 16) * inv_scale;
+    const float u1 = __uint_as_float(w & 0xFFFF0000u) * inv_scale;
+    acc = fma((double)u0, (double)u0, acc);
+    acc = fma((double)u1, (double)u1, acc);
+}
+
+__device__ __forceinline__ void accum_half(uint16_t h, float inv_scale, double& acc, uint32_t& bad) {
+    bad |= (uint32_t)((h & 0x7F80u) == 0x7F80u);
+    const float u = __uint_as_float((uint32_t)h << 16) * inv_scale;
+    acc = fma((double)u, (double)u, acc);
+}
+
+__global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, const float inv_scale,
+                                                            Workspace* __restrict__ ws) {
+    const uint32_t total = b.tile_begin[b.n_sg];
+    const uint32_t tid = threadIdx.x;
+    double acc = 0.0;
+    uint32_t bad = 0;
+    int s = 0;
+    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        while (tile >= b.tile_begin[s + 1]) ++s;
+        const uint32_t t_in = tile - b.tile_begin[s];
+        const uint16_t* __restrict__ body = b.body[s];
+        const uint64_t n_body = b.n_body[s];
+        if (t_in == 0 && tid < b.head[s]) accum_half(*(body - 1 - tid), inv_scale, acc, bad);
+        const uint64_t base = (uint64_t)t_in * kTile;
+        const u32x4* __restrict__ q = reinterpret_cast<const u32x4*>(body + base);
+        if (n_body >= base + kTile) {
+            u32x4 w[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) w[u] = __builtin_nontemporal_load(q + u * kBlock + tid);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                accum_word(w[u].x, inv_scale, acc, bad);
+                accum_word(w[u].y, inv_scale, acc, bad);
+                accum_word(w[u].z, inv_scale, acc, bad);
+                accum_word(w[u].w, inv_scale, acc, bad);
+            }
+        } else if (n_body > base) {
+            const uint64_t rem = n_body - base;  // < kTile
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint32_t i = u * kBlock + tid;
+                const uint64_t e = (uint64_t)i * 8;
+                if (e + 8 <= rem) {
+                    const u32x4 w = __builtin_nontemporal_load(q + i);
+                    accum_word(w.x, inv_scale, acc, bad);
+                    accum_word(w.y, inv_scale, acc, bad);
+                    accum_word(w.z, inv_scale, acc, bad);
+                    accum_word(w.w, inv_scale, acc, bad);
+                } else if (e < rem) {
+                    for (uint64_t j = base + e; j < n_body; ++j) accum_half(body[j], inv_scale, acc, bad);
+                }
+            }
+        }
+    }
+    // lanes -> wavefront (shuffle), wavefronts -> block (LDS), fixed order throughout
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        acc += __shfl_down(acc, off, 64);
+        bad |= (uint32_t)__shfl_down((int)bad, off, 64);
+    }
+    __shared__ double s_acc[kBlock / 64];
+    __shared__ uint32_t s_bad[kBlock / 64];
+    if ((tid & 63u) == 0) {
+        s_acc[tid >> 6] = acc;
+        s_bad[tid >> 6] = bad;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double t = s_acc[0];
+        uint32_t f = s_bad[0];
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) {
+            t += s_acc[w];
+            f |= s_bad[w];
+        }
+        ws->partial[blockIdx.x] = t;
+        ws->flag[blockIdx.x] = f;
+    }
+}
+
+// One block: folds n_partials partials into the running sum; on the last group derives the outputs.
+__global__ void __launch_bounds__(kBlock) grad_finish_kernel(Workspace* __restrict__ ws, const int n_partials,
+                                                             const int first, const int last, const float inv_scale,
+                                                             const float max_norm, mlpo_step_scalars* __restrict__ out) {
+    const uint32_t tid = threadIdx.x;
+    double acc = 0.0;
+    uint32_t bad = 0;
+    for (int i = tid; i < n_partials; i += kBlock) {
+        acc += ws->partial[i];
+        bad |= ws->flag[i];
+    }
+    __shared__ double s_acc[kBlock];
+    __shared__ uint32_t s_bad[kBlock];
+    s_acc[tid] = acc;
+    s_bad[tid] = bad;
+    __syncthreads();
+    for (int w = kBlock / 2; w > 0; w >>= 1) {
+        if ((int)tid < w) {
+            s_acc[tid] += s_acc[tid + w];
+            s_bad[tid] |= s_bad[tid + w];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        double sum = s_acc[0];
+        uint32_t f = s_bad[0];
+        if (!first) {
+            sum += ws->running_sum;
+            f |= ws->running_flag;
+        }
+        if (last) {
+            const float norm = (float)sqrt(sum);
+            float coef = 1.0f;
+            if (max_norm > 0.0f && norm > max_norm) coef = max_norm / (norm + 1e-6f);
+            out->norm = norm;
+            out->clip_coef = coef;
+            out->gmul = inv_scale * coef;
+            out->found_inf = f ? 1u : 0u;
+        } else {
+            ws->running_sum = sum;
+            ws->running_flag = f;
+        }
+    }
+}
+
+int flush(const NormBatch& b, bool first, bool last, float inv_scale, float max_norm, Workspace* ws,
+          mlpo_step_scalars* out, hipStream_t st) {
+    const uint32_t total = b.tile_begin[b.n_sg];
+    uint32_t grid = 0;
+    if (total > 0) {
+        const int cus = num_cus();
+        if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
+        int per_cu = tuning().norm_grid_per_cu;
+        if (per_cu <= 0) per_cu = 8;
+        uint64_t cap = (uint64_t)cus * (uint64_t)per_cu;
+        if (cap > (uint64_t)kMaxGrid) cap = kMaxGrid;
+        grid = total < cap ? total : (uint32_t)cap;
+        hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws);
+        MLPO_HIP(hipGetLastError());
+    }
+    hipLaunchKernelGGL(grad_finish_kernel, dim3(1), dim3(kBlock), 0, st, ws, (int)grid, first ? 1 : 0, last ? 1 : 0,
+                       inv_scale, max_norm, out);
+    MLPO_HIP(hipGetLastError());
+    return MLPO_OK;
+}
+
+}  // namespace
+
+size_t grad_norm_workspace_bytes() { return sizeof(Workspace); }
+
+int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float max_norm, void* workspace,
+                     mlpo_step_scalars* out, hipStream_t stream) {
+    Workspace* ws = static_cast<Workspace*>(workspace);
+    NormBatch b;
+    b.n_sg = 0;
+    b.tile_begin[0] = 0;
+    bool first = true;
+    for (int i = 0; i < n_sg; ++i) {
+        const uint64_t n = sg[i].n;
+        if (n == 0) continue;
+        const uintptr_t addr = reinterpret_cast<uintptr_t>(sg[i].g);
+        uint64_t head = ((16u - (addr & 15u)) & 15u) / 2u;
+        if (head > n) head = n;
+        const uint64_t n_body = n - head;
+        uint64_t tiles = (n_body + kTile - 1) / kTile;
+        if (tiles == 0) tiles = 1;  // a subgroup that is all head still needs its first tile
+        if (tiles > 0x7FFFFFFFull) return fail(MLPO_EINVAL, "subgroup %d too large", i);
+        if (b.n_sg == kMaxSg || (uint64_t)b.tile_begin[b.n_sg] + tiles > 0xFFFFFFFFull) {
+            const int rc = flush(b, first, false, inv_scale, max_norm, ws, out, stream);
+            if (rc != MLPO_OK) return rc;
+            first = false;
+            b.n_sg = 0;
+        }
+        b.body[b.n_sg] = sg[i].g + head;
+        b.n_body[b.n_sg] = n_body;
+        b.head[b.n_sg] = (uint8_t)head;
+        b.tile_begin[b.n_sg + 1] = b.tile_begin[b.n_sg] + (uint32_t)tiles;
+        ++b.n_sg;
+    }
+    return flush(b, first, true, inv_scale, max_norm, ws, out, stream);
+}
+
+}  // namespace mlpo

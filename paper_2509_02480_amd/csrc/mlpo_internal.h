@@ -1,0 +1,55 @@
+// Internal declarations shared by the translation units of libmlpo (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mlpo.h"
+
+namespace mlpo {
+
+// ---- error reporting -------------------------------------------------------
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+#define MLPO_HIP(call)                                                                   \
+    do {                                                                                 \
+        hipError_t e_ = (call);                                                          \
+        if (e_ != hipSuccess) return ::mlpo::fail(MLPO_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- tuning knobs ------------------------------------------------------------
+struct Tuning {
+    int adamw_grid_per_cu;
+    int adamw_variant;
+    int norm_grid_per_cu;
+};
+Tuning& tuning();
+int num_cus();  // compute units of the current device (cached); <= 0 on failure
+
+// ---- per-step scalars of the update, derived on the host ---------------------
+struct AdamwConsts {
+    float beta1, beta2, omb1, omb2, eps, step_size, sqbc2, decay;
+};
+int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step);
+AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step);
+
+// ---- kernel-side view of a subgroup -------------------------------------------
+struct SgView {
+    float* p;
+    float* m;
+    float* v;
+    const uint16_t* g;
+    uint16_t* p16;
+    uint64_t n;
+};
+
+// Enqueues the fused update over `n` views (all device memory) on `stream`.  Views are split between the 128-bit
+// kernel and the element-wise kernel by alignment; any number of views is accepted (several launches if needed).
+int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_step_scalars* scalars,
+                 hipStream_t stream);
+
+// Enqueues the gradient pass (see mlpo_grad_unscale_norm).
+int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float max_norm, void* workspace,
+                     mlpo_step_scalars* out, hipStream_t stream);
+size_t grad_norm_workspace_bytes();
+
+}  // namespace mlpo

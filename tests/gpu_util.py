@@ -1,0 +1,135 @@
+"""Helpers for the GPU parity tests: device buffers from numpy subgroups, one GPU step through the C ABI, comparison
+with the oracle to the stated bars.  torch is used for device / pinned memory and streams only."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2509_02480_amd import binding as B
+
+FLT_MIN = float(np.finfo(np.float32).tiny)
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def to_dev_u16(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(a.view(np.int16)).to(dev())
+
+
+def from_dev_u16(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint16)
+
+
+class Scratch:
+    """Norm workspace and the 16-byte scalar record, allocated once."""
+
+    def __init__(self):
+        self.ws_bytes = B.mlpo_norm_workspace_bytes()
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev())
+        self.scalars = torch.zeros(4, dtype=torch.float32, device=dev())
+        assert self.ws.data_ptr() % 256 == 0 and self.scalars.data_ptr() % 16 == 0
+
+    def read(self):
+        h = self.scalars.cpu().numpy()
+        return {"norm": np.float32(h[0]), "clip_coef": np.float32(h[1]), "gmul": np.float32(h[2]),
+                "found_inf": int(h[3:4].view(np.uint32)[0])}
+
+
+class DeviceSubgroups:
+    """Device (and pinned-host) copies of a list of numpy subgroups.
+
+    flat=True lays all subgroups out as consecutive slices of five flat buffers (the way a runtime shards one flat
+    partition), so slices inherit whatever alignment their offsets give them; flat=False allocates each separately.
+    ``tiers[k] == 1`` puts p, m, v of subgroup k in pinned host memory."""
+
+    def __init__(self, host_sgs, tiers=None, flat=True, elem_offset=0):
+        self.n_sg = len(host_sgs)
+        self.tiers = list(tiers) if tiers is not None else [0] * self.n_sg
+        self.sizes = [s["p"].size for s in host_sgs]
+        self.t = []
+        d = dev()
+        if flat:
+            tot = sum(self.sizes) + elem_offset
+            big = {k: torch.empty(tot, dtype=torch.float32, device=d) for k in ("p", "m", "v")}
+            big.update({k: torch.empty(tot, dtype=torch.int16, device=d) for k in ("g", "p16")})
+            self._keep = big
+        off = elem_offset
+        for k, s in enumerate(host_sgs):
+            n = self.sizes[k]
+            ent = {}
+            for key in ("p", "m", "v"):
+                src = torch.from_numpy(s[key])
+                if self.tiers[k] == 1:
+                    ent[key] = torch.empty(n, dtype=torch.float32, pin_memory=True)
+                    ent[key].copy_(src)
+                elif flat:
+                    ent[key] = big[key][off:off + n]
+                    ent[key].copy_(src)
+                else:
+                    ent[key] = src.to(d)
+            for key in ("g", "p16"):
+                src = torch.from_numpy(s[key].view(np.int16))
+                if flat:
+                    ent[key] = big[key][off:off + n]
+                    ent[key].copy_(src)
+                else:
+                    ent[key] = src.to(d)
+            off += n
+            self.t.append(ent)
+        torch.cuda.synchronize()
+        self.table = B.SubgroupTable(
+            B.subgroup(e["p"], e["m"], e["v"], e["g"], e["p16"], n=self.sizes[k], tier=self.tiers[k])
+            for k, e in enumerate(self.t))
+
+    def set_grads(self, k, g_bits: np.ndarray):
+        self.t[k]["g"].copy_(torch.from_numpy(g_bits.view(np.int16)))
+
+    def fetch(self, k):
+        torch.cuda.synchronize()
+        e = self.t[k]
+        return {"p": e["p"].cpu().numpy().copy(), "m": e["m"].cpu().numpy().copy(), "v": e["v"].cpu().numpy().copy(),
+                "p16": from_dev_u16(e["p16"]).copy()}
+
+
+def gpu_step(ds: DeviceSubgroups, scratch: Scratch, hp: B.HParams, steps_applied: int, inv_scale=1.0, max_norm=0.0,
+             stream=None, use_scalars=True):
+    """norm pass + resident update through the C ABI; returns (applied, scalars dict)."""
+    st = stream if stream is not None else torch.cuda.current_stream()
+    B.mlpo_grad_unscale_norm(ds.table, inv_scale, max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars, st)
+    B.mlpo_adamw_step(ds.table, hp, steps_applied + 1, scratch.scalars if use_scalars else None, st)
+    torch.cuda.synchronize()
+    sc = scratch.read()
+    return sc["found_inf"] == 0, sc
+
+
+def max_rel_err(a: np.ndarray, b: np.ndarray) -> float:
+    """max |a - b| / max(|b|, FLT_MIN), NaN-safe (a NaN on one side only counts as infinite error)."""
+    if a.size == 0:
+        return 0.0
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    both_nan = np.isnan(a64) & np.isnan(b64)
+    same_inf = np.isinf(a64) & (a64 == b64)
+    with np.errstate(invalid="ignore"):
+        err = np.abs(a64 - b64) / np.maximum(np.abs(b64), FLT_MIN)
+    err = np.where(both_nan | same_inf, 0.0, err)
+    err = np.where(np.isnan(err), np.inf, err)
+    return float(err.max())
+
+
+def assert_state_parity(got: dict, want: dict, label="", tol=1e-6):
+    """The bars of the benchmark spec: fp32 state within 1e-6 max relative error, bf16 copy bit-exact.  Because both sides
+    round every operation identically the fp32 state is expected to be bit-identical; the count of differing words is
+    reported in the failure text."""
+    for key in ("p", "m", "v"):
+        e = max_rel_err(got[key], want[key])
+        ndiff = int((got[key].view(np.uint32) != want[key].view(np.uint32)).sum())
+        assert e <= tol, f"{label} {key}: max rel err {e:.3e}, {ndiff} words differ"
+    bad = np.nonzero(got["p16"] != want["p16"])[0]
+    assert bad.size == 0, f"{label} p16: {bad.size} mismatches, first at {bad[:5]}"
+
+
+def hp_pair(oracle, **kw):
+    """The same hyper-parameters for the oracle and for the library."""
+    return oracle.HParams(**kw), B.HParams(**kw)

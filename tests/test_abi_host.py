@@ -1,0 +1,124 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header declares, and turns bad
+arguments into error codes before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2509_02480_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000  # never dereferenced: validation fails first, or n == 0
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "mlpo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mlpo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = header_functions()
+    assert set(names) == set(B.EXPORTS)
+    dll = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(dll, n) is not None
+
+
+def test_version_and_workspace_size():
+    assert B.mlpo_version() >= 100
+    assert B.mlpo_norm_workspace_bytes() >= 4096
+
+
+def sg(n=8, tier=0, **kw):
+    d = dict(p=FAKE, m=FAKE + 4096, v=FAKE + 8192, g=FAKE + 12288, p16=FAKE + 16384)
+    d.update(kw)
+    return B.SubgroupC(d["p"], d["m"], d["v"], d["g"], d["p16"], n, tier, 0)
+
+
+def expect(code, fn, *a, **k):
+    with pytest.raises(B.MlpoError) as e:
+        fn(*a, **k)
+    assert e.value.code == code, str(e.value)
+    assert str(e.value)
+
+
+@pytest.mark.parametrize("kw", [dict(lr=-1.0), dict(lr=float("nan")), dict(beta1=1.0), dict(beta2=-0.1),
+                                dict(eps=float("inf")), dict(weight_decay=-1e-3)])
+def test_bad_hyperparameters(kw):
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [], B.HParams(**kw), 1)
+
+
+def test_bad_step_and_pointers():
+    hp = B.HParams()
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [], hp, 0)
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(p=0)], hp, 1)
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(g=0)], hp, 1)
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(p=FAKE + 2)], hp, 1)      # fp32 not 4-byte aligned
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(g=FAKE + 1)], hp, 1)      # bf16 not 2-byte aligned
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(tier=1)], hp, 1)          # host tier needs the pipeline
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(tier=7)], hp, 1)
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg()], hp, 1, scalars=FAKE + 4)  # scalars not 16-byte aligned
+    bad = sg()
+    bad.reserved = 1
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [bad], hp, 1)
+    # nothing to do is not an error
+    B.mlpo_adamw_step([], hp, 1)
+    rc = B.lib().mlpo_adamw_step(None, -1, C.byref(hp.c()), 1, None, None)
+    assert rc == B.MLPO_EINVAL
+    rc = B.lib().mlpo_adamw_step(None, 1, C.byref(hp.c()), 1, None, None)
+    assert rc == B.MLPO_EINVAL
+    rc = B.lib().mlpo_adamw_step(None, 0, None, 1, None, None)
+    assert rc == B.MLPO_EINVAL
+
+
+def test_norm_argument_errors():
+    ws = B.mlpo_norm_workspace_bytes()
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg()], 0.0, 0.0, FAKE, ws, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg()], float("inf"), 0.0, FAKE, ws, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg()], 1.0, float("nan"), FAKE, ws, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg()], 1.0, 0.0, 0, ws, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg()], 1.0, 0.0, FAKE + 64, ws, FAKE)
+    expect(B.MLPO_ENOMEM, B.mlpo_grad_unscale_norm, [sg()], 1.0, 0.0, FAKE, ws - 1, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg()], 1.0, 0.0, FAKE, ws, 0)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg()], 1.0, 0.0, FAKE, ws, FAKE + 8)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg(g=0)], 1.0, 0.0, FAKE, ws, FAKE)
+
+
+def cfg(n_slots=3, staging=FAKE, staging_bytes=1 << 30, chunk=0):
+    return B.stream_cfg(n_slots, staging, staging_bytes, None, None, None, chunk)
+
+
+def test_stream_argument_errors():
+    hp = B.HParams()
+    host = [sg(n=1000, tier=1), sg(n=500, tier=0)]
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, cfg(n_slots=0))
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, cfg(n_slots=B.MAX_SLOTS + 1))
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, cfg(chunk=6))
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, cfg(staging=0))
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, cfg(staging=FAKE + 16))
+    expect(B.MLPO_ENOMEM, B.mlpo_stream_update, host, None, hp, 1, None, cfg(staging_bytes=3 * 12 * 1000 - 1))
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, [0, 0], hp, 1, None, cfg())
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, [0, 2], hp, 1, None, cfg())
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 0, None, cfg())
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, B.HParams(beta1=2.0), 1, None, cfg())
+    rc = B.lib().mlpo_stream_update(None, 0, None, C.byref(hp.c()), 1, None, None, None)
+    assert rc == B.MLPO_EINVAL
+    # an empty list is a no-op that counts as applied
+    assert B.mlpo_stream_update([], None, hp, 1, None, cfg()) is True
+
+
+def test_staging_size_formula():
+    host = [sg(n=1000, tier=1), sg(n=4001, tier=1), sg(n=10 ** 6, tier=0)]
+    assert B.mlpo_stream_staging_bytes(host, 3) == 3 * 12 * 4004          # rounded to a multiple of 4 elements
+    assert B.mlpo_stream_staging_bytes(host, 2, 1024) == 2 * 12 * 1024
+    assert B.mlpo_stream_staging_bytes(host, 2, 8000) == 2 * 12 * 4004
+    assert B.mlpo_stream_staging_bytes([sg(tier=0)], 4) == 0
+
+
+def test_options():
+    B.mlpo_set_option("adamw_grid_per_cu", 8)
+    expect(B.MLPO_EINVAL, B.mlpo_set_option, "no_such_option", 1)
+    expect(B.MLPO_EINVAL, B.mlpo_set_option, "adamw_variant", 10 ** 6)
+    B.mlpo_shutdown()

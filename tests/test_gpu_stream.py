@@ -1,0 +1,142 @@
+"""GPU parity of the tiered pipeline (mlpo_stream_update): host-tier subgroups fetched into staging slots, updated and
+flushed back, HBM-tier subgroups updated in place.  The result must be bit-identical to the oracle (and hence to the
+resident path) whatever the number of slots, the chunking and the processing order are - the paper's statement that the
+order of independent subgroup updates is inconsequential (Section 3.2 "Cache-Friendly Ordering") and that subgroup
+size does not affect results (Section 4.1 "Runtime Configurations")."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2509_02480_amd import binding as B  # noqa: E402
+from paper_2509_02480_amd import workloads as W  # noqa: E402
+
+from gpu_util import DeviceSubgroups, Scratch, assert_state_parity, dev, hp_pair  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def scratch():
+    assert torch.cuda.is_available()
+    return Scratch()
+
+
+@pytest.fixture(scope="module")
+def streams():
+    return torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+
+
+def stream_step(ds, scratch, ghp, steps_applied, wl, streams, n_slots, chunk, order, staging_holder, norm=True):
+    h2d, cmp_, d2h = streams
+    need = B.mlpo_stream_staging_bytes(ds.table, n_slots, chunk)
+    if staging_holder.get("bytes", -1) < need:
+        staging_holder["t"] = torch.empty(max(need, 256), dtype=torch.uint8, device=dev())
+        staging_holder["bytes"] = need
+    cfg = B.stream_cfg(n_slots, staging_holder["t"], staging_holder["t"].numel(), h2d, cmp_, d2h, chunk)
+    torch.cuda.synchronize()
+    scal = None
+    if norm:
+        B.mlpo_grad_unscale_norm(ds.table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                 cmp_)
+        scal = scratch.scalars
+    applied = B.mlpo_stream_update(ds.table, order, ghp, steps_applied + 1, scal, cfg)
+    cmp_.synchronize()          # documented: the compute stream joins the last flush
+    return applied
+
+
+@pytest.mark.parametrize("n_slots,chunk,order_kind", [
+    (1, 0, "asc"), (2, 0, "asc"), (3, 0, "desc"), (4, 0, "perm"),
+    (3, 4096, "asc"), (2, 10_000, "perm"), (4, 1 << 20, "desc"), (8, 33_332, "asc"),
+])
+def test_mixed_tiers_match_oracle(oracle, scratch, streams, n_slots, chunk, order_kind):
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("mix", n_sub=7, sub_elems=100_001, n_host=4, loss_scale=256.0, max_norm=0.05, steps=3)
+    host = W.host_subgroups(wl, warm=True)
+    tiers = [wl.tier(k) for k in range(wl.n_sub)]
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False)
+    rng = np.random.default_rng(n_slots)
+    hold = {}
+    applied = 0
+    for s in range(wl.steps):
+        order = {"asc": None, "desc": list(range(wl.n_sub))[::-1], "perm": [int(x) for x in rng.permutation(wl.n_sub)]}[
+            order_kind]
+        if s > 0:
+            for k, sg in enumerate(host):
+                W.fill_grads(wl, k, s, sg["g"])
+                ds.set_grads(k, sg["g"])
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, applied, wl.inv_scale, wl.max_norm, order=order)
+        ok_g = stream_step(ds, scratch, ghp, applied, wl, streams, n_slots, chunk, order, hold)
+        assert ok_g == ok_o is True
+        sc = scratch.read()
+        assert abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5 and sc["gmul"] == gmul_o
+        applied += 1
+        for k in range(wl.n_sub):
+            assert_state_parity(ds.fetch(k), host[k], f"slots={n_slots} chunk={chunk} step={s} sg={k}")
+
+
+def test_skip_moves_nothing(oracle, scratch, streams):
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("sskip", n_sub=4, sub_elems=50_000, n_host=2)
+    host = W.host_subgroups(wl, warm=True)
+    host[3]["g"][77] = 0xFF80
+    for sg in host:
+        sg["p16"][:] = 0x4321
+    ds = DeviceSubgroups(host, tiers=[1, 1, 0, 0], flat=False)
+    hold = {}
+    assert stream_step(ds, scratch, ghp, 0, wl, streams, 3, 0, None, hold) is False
+    assert scratch.read()["found_inf"] == 1
+    # staging was never written: fill it with a pattern first and look again
+    hold["t"].fill_(0x5A)
+    assert stream_step(ds, scratch, ghp, 0, wl, streams, 3, 0, None, hold) is False
+    assert bool((hold["t"] == 0x5A).all().item())
+    for k in range(wl.n_sub):
+        got = ds.fetch(k)
+        for key in ("p", "m", "v"):
+            assert np.array_equal(got[key].view(np.uint32), host[k][key].view(np.uint32))
+        assert np.array_equal(got["p16"], host[k]["p16"])
+
+
+def test_streamed_equals_resident_bitwise(oracle, scratch, streams):
+    # the same inputs once all-resident and once all-host with an awkward chunk size: identical bits
+    _, ghp = hp_pair(oracle)
+    wl = W.Workload("eq", n_sub=3, sub_elems=250_003, n_host=3, steps=2)
+    host = W.host_subgroups(wl, warm=True)
+    a = DeviceSubgroups(host, tiers=[0, 0, 0], flat=True)
+    b = DeviceSubgroups(host, tiers=[1, 1, 1], flat=False)
+    hold = {}
+    for s in range(wl.steps):
+        B.mlpo_adamw_step(a.table, ghp, s + 1, None, torch.cuda.current_stream())
+        stream_step(b, scratch, ghp, s, wl, streams, 2, 65_536, [2, 0, 1], hold, norm=False)
+    for k in range(wl.n_sub):
+        ga, gb = a.fetch(k), b.fetch(k)
+        for key in ("p", "m", "v", "p16"):
+            assert np.array_equal(ga[key].view(np.uint8), gb[key].view(np.uint8)), (k, key)
+
+
+def test_same_stream_for_everything(oracle, scratch):
+    # the three roles may share one stream (no overlap, same result)
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("one", n_sub=3, sub_elems=30_000, n_host=2)
+    host = W.host_subgroups(wl, warm=True)
+    ds = DeviceSubgroups(host, tiers=[1, 1, 0], flat=False)
+    s = torch.cuda.Stream()
+    hold = {}
+    assert stream_step(ds, scratch, ghp, 0, wl, (s, s, s), 2, 8192, None, hold)
+    oracle.step(host, ohp, 0)
+    for k in range(wl.n_sub):
+        assert_state_parity(ds.fetch(k), host[k], f"one-stream sg={k}")
+
+
+def test_config3_shape_scaled(oracle, scratch, streams):
+    # config 3's structure (13 host-tier subgroups, all state in pinned memory, 2-4 slots) at 1/100 of its size
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("C3/100", n_sub=13, sub_elems=1_000_000, n_host=13, steps=5, fresh_grads=False)
+    host = W.host_subgroups(wl, warm=False, threads=8)
+    ds = DeviceSubgroups(host, tiers=[1] * 13, flat=False)
+    hold = {}
+    for s in range(wl.steps):
+        oracle.step(host, ohp, s)
+        assert stream_step(ds, scratch, ghp, s, wl, streams, 2 + s % 3, 0, None, hold)
+    for k in range(wl.n_sub):
+        assert_state_parity(ds.fetch(k), host[k], f"C3/100 sg={k}")
