@@ -30,26 +30,39 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def resident_bench(args, torch, B, W, np):
+def resident_bench(args, torch, B, W, np, tile):
+    """Times args.steps whole steps on the resident workload with the fp32 state in the given layout
+    (tile = 0: three planar arrays; tile = T: the library's tiled layout)."""
     wl = W.CONFIGS[args.workload]
     assert wl.n_host == 0, "the resident benchmark needs an all-HBM workload"
     d = torch.device("cuda:0")
     N, M = wl.n_total, wl.sub_elems
     t0 = time.time()
-    flat = {k: torch.empty(N, dtype=torch.float32, device=d) for k in ("p", "m", "v")}
-    flat["g"] = torch.empty(N, dtype=torch.int16, device=d)
-    flat["p16"] = torch.zeros(N, dtype=torch.int16, device=d)
+    g_flat = torch.empty(N, dtype=torch.int16, device=d)
+    p16_flat = torch.zeros(N, dtype=torch.int16, device=d)
+    if tile:
+        per = B.mlpo_state_floats(M, tile)
+        state = torch.zeros(per * wl.n_sub, dtype=torch.float32, device=d)
+        pad = torch.zeros(per // 3, dtype=torch.float32, device=d)
+    else:
+        flat = {k: torch.zeros(N, dtype=torch.float32, device=d) for k in ("p", "m", "v")}
     hp_ = np.empty(M, np.float32)
     hg_ = np.empty(M, np.uint16)
+    sgs = []
     for k in range(wl.n_sub):
-        W.fill_state(wl, k, hp_, None, None, threads=args.threads)
-        flat["p"][k * M:(k + 1) * M].copy_(torch.from_numpy(hp_))
+        W.fill_state(wl, k, hp_, None, None, threads=args.threads)   # m = v = 0
         W.fill_grads(wl, k, 0, hg_, threads=args.threads)
-        flat["g"][k * M:(k + 1) * M].copy_(torch.from_numpy(hg_.view(np.int16)))
-    flat["m"].zero_()
-    flat["v"].zero_()
-    table = B.SubgroupTable(B.subgroup(*(flat[key][k * M:(k + 1) * M] for key in ("p", "m", "v", "g", "p16")), n=M)
-                            for k in range(wl.n_sub))
+        gk, hk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
+        gk.copy_(torch.from_numpy(hg_.view(np.int16)))
+        if tile:
+            sk = state[k * per:(k + 1) * per]
+            pad[:M].copy_(torch.from_numpy(hp_))
+            sk.view(-1, 3, tile)[:, 0, :].copy_(pad.view(-1, tile))      # p into its slots of the tiled buffer
+            sgs.append(B.tiled_subgroup(sk, gk, hk, n=M, tile_elems=tile))
+        else:
+            flat["p"][k * M:(k + 1) * M].copy_(torch.from_numpy(hp_))
+            sgs.append(B.subgroup(*(flat[key][k * M:(k + 1) * M] for key in ("p", "m", "v")), gk, hk, n=M))
+    table = B.SubgroupTable(sgs)
     ws_bytes = B.mlpo_norm_workspace_bytes()
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=d)
     scal = torch.zeros(4, dtype=torch.float32, device=d)
@@ -58,7 +71,8 @@ def resident_bench(args, torch, B, W, np):
     hp = B.HParams(**wl.hp.__dict__)
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
-    log(f"[bench] {wl.name}: {N} params resident, setup {time.time() - t0:.1f}s")
+    log(f"[bench] {wl.name} layout={'tiled T=%d' % tile if tile else 'planar'}: {N} params resident, "
+        f"setup {time.time() - t0:.1f}s")
 
     total = args.warmup + args.steps
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
@@ -78,8 +92,8 @@ def resident_bench(args, torch, B, W, np):
             inject = wl.injects(s)
             if inject:
                 idx = wl.inject_index(s)
-                saved.copy_(flat["g"][idx:idx + 1])
-                flat["g"][idx:idx + 1].copy_(inf_bits)
+                saved.copy_(g_flat[idx:idx + 1])
+                g_flat[idx:idx + 1].copy_(inf_bits)
             i = s - args.warmup
             if timed:
                 n_start[i].record(stream)
@@ -90,7 +104,7 @@ def resident_bench(args, torch, B, W, np):
             if timed:
                 k_end[i].record(stream)
             if inject:
-                flat["g"][idx:idx + 1].copy_(saved)
+                g_flat[idx:idx + 1].copy_(saved)
             else:
                 applied += 1            # the host mirrors the injection schedule: no read-back of the flag
                 applied_timed += int(timed)
@@ -100,7 +114,7 @@ def resident_bench(args, torch, B, W, np):
     elapsed_ms = t_begin.elapsed_time(t_end)
     flag = int(scal.cpu().numpy()[3:4].view(np.uint32)[0])
     assert flag == (1 if wl.injects(total - 1) else 0)
-    assert bool(torch.isfinite(flat["p"]).all().item()), "state went non-finite"
+    assert bool(torch.isfinite(state if tile else flat["p"]).all().item()), "state went non-finite"
 
     inj_timed = [wl.injects(s) for s in range(args.warmup, total)]
     k_ms = [k_start[i].elapsed_time(k_end[i]) for i in range(args.steps) if not inj_timed[i]]
@@ -108,35 +122,71 @@ def resident_bench(args, torch, B, W, np):
     k_avg = sum(k_ms) / max(len(k_ms), 1)
     n_avg = sum(n_ms) / len(n_ms)
     achieved = BYTES_PER_PARAM_STEP * N / (k_avg * 1e-3) / 1e9
-    value = applied_timed * N / (elapsed_ms * 1e-3) / 1e9
-    res = {
-        "metric": "AdamW update throughput, HBM-resident (Gparams/s)",
-        "value": round(value, 3),
-        "unit": "Gparams/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+    out = {
+        "layout": f"tiled T={tile}" if tile else "planar",
+        "value": round(applied_timed * N / (elapsed_ms * 1e-3) / 1e9, 3),
         "ms_per_step": round(elapsed_ms / args.steps, 5),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": wl.name, "params": N, "subgroups": wl.n_sub, "subgroup_elems": M,
-                   "loss_scale": wl.loss_scale, "inf_every": wl.inject_every, "applied_steps": applied_timed,
-                   "state": "fp32 p/m/v + bf16 grads + bf16 params, all in HBM"},
+        "applied_steps": applied_timed,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": "adamw_v4_kernel", "avg_launch_ms": round(k_avg, 5),
-                     "min_launch_ms": round(min(k_ms), 5), "bytes_per_launch": BYTES_PER_PARAM_STEP * N},
+                     "min_launch_ms": round(min(k_ms), 5), "launches_timed": len(k_ms),
+                     "bytes_per_launch": BYTES_PER_PARAM_STEP * N},
         "norm_pass": {"avg_ms": round(n_avg, 5),
                       "achieved_GBs": round(BYTES_PER_PARAM_NORM * N / (n_avg * 1e-3) / 1e9, 1)},
         "step_hbm_frac": round((BYTES_PER_PARAM_STEP + BYTES_PER_PARAM_NORM) * N * applied_timed
                                / (elapsed_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
     }
-    del flat, table
+    del table, sgs, g_flat, p16_flat
+    if tile:
+        del state, pad
+    else:
+        del flat
     torch.cuda.empty_cache()
+    return out
+
+
+def resident_result(args, wl, primary, others):
+    res = {
+        "metric": "AdamW update throughput, HBM-resident (Gparams/s)",
+        "value": primary["value"],
+        "unit": "Gparams/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": primary["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "params": wl.n_total, "subgroups": wl.n_sub, "subgroup_elems": wl.sub_elems,
+                   "loss_scale": wl.loss_scale, "inf_every": wl.inject_every,
+                   "applied_steps": primary["applied_steps"], "state_layout": primary["layout"],
+                   "state": "fp32 p/m/v + bf16 grads + bf16 params, all in HBM"},
+        "roofline": primary["roofline"],
+        "norm_pass": primary["norm_pass"],
+        "step_hbm_frac": primary["step_hbm_frac"],
+    }
+    if others:
+        res["other_layouts"] = others
     return res
+
+
+def calibration_copies(torch):
+    """Plain kernels of known traffic, run only so that a counter-collecting profiler run of this script has a
+    reference to scale its HBM byte counters with: a 1 GiB device-to-device copy (reads 1 GiB, writes 1 GiB) and a
+    1 GiB in-place scale (same)."""
+    d = torch.device("cuda:0")
+    n = (1 << 30) // 4
+    x = torch.ones(n, dtype=torch.float32, device=d)
+    y = torch.empty_like(x)
+    for _ in range(3):
+        y.copy_(x)
+        x.mul_(1.0)
+    torch.cuda.synchronize()
+    del x, y
+    torch.cuda.empty_cache()
 
 
 def cpu_baseline(args, W, np):
@@ -186,25 +236,25 @@ def streamed_bench(args, torch, B, W, np):
     t0 = time.time()
     sgs, keep = [], []
     hg_ = np.empty(M, np.uint16)
+    T = args.tile
+    per = B.mlpo_state_floats(M, T)
     g_flat = torch.empty(wl.n_total, dtype=torch.int16, device=d)
     p16_flat = torch.zeros(wl.n_total, dtype=torch.int16, device=d)
+    tmp = np.zeros(per // 3, np.float32)
     for k in range(wl.n_sub):
-        host = wl.tier(k) == 1
-        if host:
-            p, m, v = (torch.empty(M, dtype=torch.float32, pin_memory=True) for _ in range(3))
-            W.fill_state(wl, k, p.numpy(), m.numpy(), v.numpy(), threads=args.threads)
+        # fp32 state in the tiled layout: one buffer per subgroup, pinned host memory or HBM by tier; m = v = 0
+        W.fill_state(wl, k, tmp[:M], None, None, threads=args.threads)
+        if wl.tier(k) == 1:
+            st = torch.zeros(per, dtype=torch.float32, pin_memory=True)
+            st.numpy().reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
         else:
-            p, m, v = (torch.empty(M, dtype=torch.float32, device=d) for _ in range(3))
-            tmp = np.empty(M, np.float32)
-            W.fill_state(wl, k, tmp, None, None, threads=args.threads)
-            p.copy_(torch.from_numpy(tmp))
-            m.zero_()
-            v.zero_()
+            st = torch.zeros(per, dtype=torch.float32, device=d)
+            st.view(-1, 3, T)[:, 0, :].copy_(torch.from_numpy(tmp).view(-1, T))
         W.fill_grads(wl, k, 0, hg_, threads=args.threads)
         g_flat[k * M:(k + 1) * M].copy_(torch.from_numpy(hg_.view(np.int16)))
-        keep.append((p, m, v))
-        sgs.append(B.subgroup(p, m, v, g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M], n=M,
-                              tier=wl.tier(k)))
+        keep.append(st)
+        sgs.append(B.tiled_subgroup(st, g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M], n=M,
+                                    tier=wl.tier(k), tile_elems=T))
     table = B.SubgroupTable(sgs)
     ws_bytes = B.mlpo_norm_workspace_bytes()
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=d)
@@ -215,12 +265,13 @@ def streamed_bench(args, torch, B, W, np):
     log(f"[bench] {wl.name}: {wl.n_host} host-tier + {wl.n_sub - wl.n_host} HBM subgroups of {M}, "
         f"setup {time.time() - t0:.1f}s")
     n_host_params = wl.n_host * M
-    out = {"workload": wl.name, "host_tier_params": n_host_params, "bytes_per_direction_per_step": 12 * n_host_params,
+    out = {"workload": wl.name, "state_layout": f"tiled T={T}", "host_tier_params": n_host_params, "bytes_per_direction_per_step": 12 * n_host_params,
            "pcie_nominal_GBs": PCIE_NOMINAL_GBS, "runs": []}
     # plain pinned copies of one subgroup array, for reference: each direction alone, then both at once
     ref = torch.empty(M, dtype=torch.float32, device=d)
     ref2 = torch.empty(M, dtype=torch.float32, device=d)
-    hsrc, hdst = keep[0][0], keep[0][1]
+    host_k = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
+    hsrc, hdst = keep[host_k[0]][:M], keep[host_k[-1]][:M]
 
     def timed(fn, reps=3):
         fn()
@@ -293,6 +344,9 @@ def main():
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2")
+    ap.add_argument("--layout", default="both", choices=["tiled", "planar", "both"],
+                    help="fp32 state layout(s) to time; the first is the headline figure")
+    ap.add_argument("--tile", type=int, default=8192, help="tile_elems of the tiled layout")
     ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
     ap.add_argument("--stream-variants", default="3:0,3:16777216,4:16777216",
                     help="comma list of n_slots:chunk_elems")
@@ -302,6 +356,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--option", action="append", default=[], help="library tuning option key=value")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run 1 GiB copy kernels (reference traffic for profiler byte counters)")
     args = ap.parse_args()
     args.stream_variants = parse_variants(args.stream_variants)
     if args.gpus != 1:
@@ -320,7 +376,11 @@ def main():
     for opt in args.option:
         k, _, v = opt.partition("=")
         B.mlpo_set_option(k, int(v))
-    res = resident_bench(args, torch, B, W, np)
+    layouts = {"tiled": [args.tile], "planar": [0], "both": [args.tile, 0]}[args.layout]
+    runs = [resident_bench(args, torch, B, W, np, t) for t in layouts]
+    res = resident_result(args, W.CONFIGS[args.workload], runs[0], runs[1:])
+    if args.calib_copy:
+        calibration_copies(torch)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(args, W, np)
     else:

@@ -44,10 +44,21 @@ typedef struct {
 
 /* One subgroup (Section 2 "Sharded Model and Optimizer States Into Subgroups"): n elements of fp32 master parameters
  * p, momentum m, variance v, the bf16 gradients g that drive the update and the bf16 working copy p16 that receives
- * the downcast parameters.  g and p16 are always device memory.  tier says where p, m, v live:
- * MLPO_TIER_HBM (device) or MLPO_TIER_HOST (pinned host). */
+ * the downcast parameters.  g and p16 are always device memory and always plain arrays of n elements.  tier says
+ * where p, m, v live: MLPO_TIER_HBM (device) or MLPO_TIER_HOST (pinned host).
+ *
+ * Layout of the fp32 state, chosen by tile_elems:
+ *   0      planar: p, m, v are three independent arrays of n floats.
+ *   T > 0  tiled: the state of the subgroup is ONE buffer of mlpo_state_floats(n, T) floats that starts at p and
+ *          holds, for every run of T consecutive elements, T floats of p, then T of m, then T of v:
+ *          x[i] of array X in {p, m, v} lives at X + (i / T) * 3T + (i % T), with m == p + T and v == p + 2T
+ *          (checked).  T must be a multiple of 1024, p 256-byte aligned, g and p16 8-byte aligned.  With T = 8192
+ *          (MLPO_TILE_DEFAULT) the three values an element needs sit close together in the same HBM channel and
+ *          the whole update sweeps one address stream instead of three: the layout the library is fastest on.  A host-tier tiled subgroup also
+ *          moves as one transfer per direction instead of three. */
 #define MLPO_TIER_HBM 0
 #define MLPO_TIER_HOST 1
+#define MLPO_TILE_DEFAULT 8192
 typedef struct {
     float* p;
     float* m;
@@ -56,8 +67,11 @@ typedef struct {
     uint16_t* p16;
     uint64_t n;
     int32_t tier;
-    int32_t reserved; /* must be 0 */
+    int32_t tile_elems;
 } mlpo_subgroup;
+
+/* Floats in the state buffer of a tiled subgroup: ceil(n / tile_elems) * 3 * tile_elems (3 * n if tile_elems is 0). */
+uint64_t mlpo_state_floats(uint64_t n, int32_t tile_elems);
 
 /* The four scalars that link the gradient pass to the update, kept in device memory so that no host round trip is
  * needed between the two (16 bytes, 16-byte aligned). */
@@ -127,7 +141,8 @@ int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hpar
 typedef struct {
     int32_t n_slots;      /* staging slots = bound on subgroups (or chunks) in flight; 1..MLPO_MAX_SLOTS */
     int32_t reserved;     /* must be 0 */
-    uint64_t chunk_elems; /* 0: a whole subgroup per transfer; else transfers of this many elements (multiple of 4) */
+    uint64_t chunk_elems; /* 0: a whole subgroup per transfer; else transfers of this many elements (a multiple of 4,
+                             and of every tile_elems in use) */
     void* staging;        /* device, 256-byte aligned, caller-owned */
     size_t staging_bytes; /* >= mlpo_stream_staging_bytes(...) */
     void* h2d;            /* hipStream_t for host-to-device copies */

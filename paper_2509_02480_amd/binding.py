@@ -19,7 +19,10 @@ MLPO_OK, MLPO_EINVAL, MLPO_EHIP, MLPO_ENOMEM = 0, -1, -2, -3
 TIER_HBM, TIER_HOST = 0, 1
 MAX_SLOTS = 8
 
-EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm",
+TILE_DEFAULT = 8192
+
+EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_norm_workspace_bytes",
+           "mlpo_grad_unscale_norm",
            "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_set_option", "mlpo_shutdown")
 
 
@@ -36,7 +39,7 @@ class HParamsC(C.Structure):
 
 class SubgroupC(C.Structure):
     _fields_ = [("p", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p), ("g", C.c_void_p), ("p16", C.c_void_p),
-                ("n", C.c_uint64), ("tier", C.c_int32), ("reserved", C.c_int32)]
+                ("n", C.c_uint64), ("tier", C.c_int32), ("tile_elems", C.c_int32)]
 
 
 class StepScalarsC(C.Structure):
@@ -77,6 +80,8 @@ def lib():
         L.mlpo_last_error.argtypes = []
         L.mlpo_version.restype = C.c_int32
         L.mlpo_version.argtypes = []
+        L.mlpo_state_floats.restype = C.c_uint64
+        L.mlpo_state_floats.argtypes = [C.c_uint64, C.c_int32]
         L.mlpo_norm_workspace_bytes.restype = C.c_size_t
         L.mlpo_norm_workspace_bytes.argtypes = []
         L.mlpo_grad_unscale_norm.restype = C.c_int
@@ -117,11 +122,25 @@ def _stream(s) -> Optional[int]:
     return int(h) or None
 
 
-def subgroup(p, m, v, g, p16, n: Optional[int] = None, tier: int = TIER_HBM) -> SubgroupC:
+def subgroup(p, m, v, g, p16, n: Optional[int] = None, tier: int = TIER_HBM, tile_elems: int = 0) -> SubgroupC:
     """One descriptor from five buffers (tensors or addresses).  ``n`` defaults to the gradient tensor's length."""
     if n is None:
         n = g.numel()
-    return SubgroupC(_ptr(p), _ptr(m), _ptr(v), _ptr(g), _ptr(p16), int(n), int(tier), 0)
+    return SubgroupC(_ptr(p), _ptr(m), _ptr(v), _ptr(g), _ptr(p16), int(n), int(tier), int(tile_elems))
+
+
+def tiled_subgroup(state, g, p16, n: Optional[int] = None, tier: int = TIER_HBM,
+                   tile_elems: int = TILE_DEFAULT) -> SubgroupC:
+    """Descriptor of a subgroup whose fp32 state is one tiled buffer (see mlpo.h): m and v follow from ``state``."""
+    if n is None:
+        n = g.numel()
+    base = _ptr(state)
+    return SubgroupC(base, base + 4 * tile_elems, base + 8 * tile_elems, _ptr(g), _ptr(p16), int(n), int(tier),
+                     int(tile_elems))
+
+
+def mlpo_state_floats(n: int, tile_elems: int) -> int:
+    return int(lib().mlpo_state_floats(n, tile_elems))
 
 
 class SubgroupTable:

@@ -1,7 +1,9 @@
 // Fused mixed-precision AdamW over a table of subgroups (gfx950).
 //
-// One launch covers many subgroups: the subgroup table travels by value in the kernel arguments, the element range
-// of every subgroup is cut into tiles, and a persistent grid walks the concatenated tile list with a grid stride.
+// One launch covers many subgroups: the subgroup table travels by value in the kernel arguments and the element range
+// of every subgroup is cut into tiles.  Either every block takes one tile, or a persistent grid walks the tile list
+// with a grid stride and issues the loads of its next tile before it computes and stores the current one (on this
+// architecture one counter tracks loads and stores in order, so loads issued after stores would wait for them).
 // Each lane moves 128-bit words: per four elements three 16-byte loads (p, m, v), one 8-byte load (four bf16
 // gradients), three 16-byte stores and one 8-byte store (four bf16 parameters) - 28 bytes per element, the whole
 // traffic of the step.  The gradient is widened in registers and never stored (Section 3.2 "Delayed In-place
@@ -24,12 +26,37 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBlock = 256;
-constexpr int kMaxSg = 40;  // subgroups per launch; keeps the argument block well under the 4 KiB limit
+constexpr int kMaxSg = 28;  // subgroups per launch; keeps the argument block well under the 4 KiB limit
 
-struct Batch {
-    SgView sg[kMaxSg];
+// A subgroup as the 128-bit kernel sees it: counts are in groups of four elements.  The first tile of a subgroup is
+// a short "head" of head4 groups chosen on the host so that every later tile starts on an address boundary of p
+// (whole cache lines per wavefront access, no line shared between two blocks).  For the tiled state layout (p, m, v
+// interleaved in runs of T elements inside one buffer) a kernel tile never straddles a layout tile, so the block
+// computes one offset for its whole tile.
+struct VecView {
+    f32x4* p;
+    f32x4* m;
+    f32x4* v;
+    const u32x2* g;
+    u32x2* h;
+    uint64_t n4;
+    uint32_t head4;
+    uint32_t tiles_per_T;  // 0: planar.  Else kernel tiles per layout tile (tiled state, head4 == 0)
+    uint32_t S4;           // tiled: distance between layout tiles of one array, in groups of four
+    uint32_t pad;
+};
+struct VecBatch {
+    VecView sg[kMaxSg];
     uint32_t tile_begin[kMaxSg + 1];  // prefix sums of tiles per subgroup
+    int32_t n_sg;
+};
+
+// Element-wise view for whatever the 128-bit kernel cannot take (unaligned subgroups, tails of 1-3 elements).
+constexpr int kBlock1 = 256;
+constexpr int kUnroll1 = 4;
+struct ScalarBatch {
+    SgView sg[kMaxSg];
+    uint32_t tile_begin[kMaxSg + 1];
     int32_t n_sg;
 };
 
@@ -89,103 +116,178 @@ __device__ __forceinline__ u32x2 update_four(f32x4& p, f32x4& m, f32x4& v, u32x2
     return out;
 }
 
-// 128-bit kernel: p, m, v 16-byte aligned, g, p16 8-byte aligned.
-template <int UNROLL, bool NT>
-__global__ void __launch_bounds__(kBlock) adamw_v4_kernel(const Batch b, const AdamwConsts c,
-                                                          const mlpo_step_scalars* __restrict__ sc) {
+struct Tile {
+    f32x4* p;
+    f32x4* m;
+    f32x4* v;
+    const u32x2* g;
+    u32x2* h;
+    uint32_t cnt;  // groups of four in this tile
+};
+
+template <int T4>
+__device__ __forceinline__ Tile locate(const VecBatch& b, uint32_t tile, int& s) {
+    while (tile >= b.tile_begin[s + 1]) ++s;
+    const VecView& d = b.sg[s];
+    const uint32_t t_in = tile - b.tile_begin[s];
+    const uint32_t head4 = d.head4;
+    uint64_t q0;
+    uint64_t left;
+    if (head4 != 0u && t_in == 0u) {
+        q0 = 0;
+        left = head4;
+    } else {
+        q0 = (uint64_t)(t_in - (head4 != 0u ? 1u : 0u)) * T4 + head4;
+        left = d.n4 - q0;
+    }
+    uint64_t off = q0;  // where the state of group q0 lives, relative to each array's base
+    if (d.tiles_per_T != 0u) {
+        const uint32_t j = t_in / d.tiles_per_T;
+        const uint32_t r = t_in - j * d.tiles_per_T;
+        off = (uint64_t)j * d.S4 + (uint64_t)r * T4;
+    }
+    Tile t;
+    t.p = d.p + off;
+    t.m = d.m + off;
+    t.v = d.v + off;
+    t.g = d.g + q0;
+    t.h = d.h + q0;
+    t.cnt = left < (uint64_t)T4 ? (uint32_t)left : (uint32_t)T4;
+    return t;
+}
+
+template <int BLOCK, int UNROLL, bool NT>
+struct Regs {
+    f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
+    u32x2 G[UNROLL];
+
+    __device__ __forceinline__ void load(const Tile& t, uint32_t tid) {
+        if (t.cnt == BLOCK * UNROLL) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t i = u * BLOCK + tid;
+                P[u] = ld<NT>(t.p + i);
+                M[u] = ld<NT>(t.m + i);
+                V[u] = ld<NT>(t.v + i);
+                G[u] = ld<NT>(t.g + i);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t i = u * BLOCK + tid;
+                if (i < t.cnt) {
+                    P[u] = ld<NT>(t.p + i);
+                    M[u] = ld<NT>(t.m + i);
+                    V[u] = ld<NT>(t.v + i);
+                    G[u] = ld<NT>(t.g + i);
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ void update_store(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
+        if (t.cnt == BLOCK * UNROLL) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t i = u * BLOCK + tid;
+                const u32x2 H = update_four(P[u], M[u], V[u], G[u], gmul, c);
+                st<NT>(t.p + i, P[u]);
+                st<NT>(t.m + i, M[u]);
+                st<NT>(t.v + i, V[u]);
+                st<NT>(t.h + i, H);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint32_t i = u * BLOCK + tid;
+                if (i < t.cnt) {
+                    const u32x2 H = update_four(P[u], M[u], V[u], G[u], gmul, c);
+                    st<NT>(t.p + i, P[u]);
+                    st<NT>(t.m + i, M[u]);
+                    st<NT>(t.v + i, V[u]);
+                    st<NT>(t.h + i, H);
+                }
+            }
+        }
+    }
+};
+
+// 128-bit kernel: p, m, v 16-byte aligned, g, p16 8-byte aligned, element counts multiples of four.
+// PERSIST = false: one tile per block.  PERSIST = true: grid-stride over tiles, next tile's loads in flight while the
+// current tile is computed and stored.
+template <int BLOCK, int UNROLL, bool NT, bool PERSIST>
+__global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const AdamwConsts c,
+                                                         const mlpo_step_scalars* __restrict__ sc) {
     float gmul = 1.0f;
     if (sc != nullptr) {
         if (sc->found_inf != 0u) return;  // skipped step: nothing is read or written
         gmul = sc->gmul;
     }
-    constexpr uint32_t kTile = kBlock * 4 * UNROLL;
+    constexpr int T4 = BLOCK * UNROLL;
     const uint32_t total = b.tile_begin[b.n_sg];
     const uint32_t tid = threadIdx.x;
+    uint32_t tile = blockIdx.x;
+    if (tile >= total) return;
     int s = 0;
-    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
-        while (tile >= b.tile_begin[s + 1]) ++s;
-        const SgView& d = b.sg[s];
-        const uint64_t base = (uint64_t)(tile - b.tile_begin[s]) * kTile;
-        const uint64_t n = d.n;
-        f32x4* __restrict__ p4 = reinterpret_cast<f32x4*>(d.p + base);
-        f32x4* __restrict__ m4 = reinterpret_cast<f32x4*>(d.m + base);
-        f32x4* __restrict__ v4 = reinterpret_cast<f32x4*>(d.v + base);
-        const u32x2* __restrict__ g2 = reinterpret_cast<const u32x2*>(d.g + base);
-        u32x2* __restrict__ h2 = reinterpret_cast<u32x2*>(d.p16 + base);
-        if (n - base >= kTile) {
-            f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
-            u32x2 G[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint32_t i = u * kBlock + tid;
-                P[u] = ld<NT>(p4 + i);
-                M[u] = ld<NT>(m4 + i);
-                V[u] = ld<NT>(v4 + i);
-                G[u] = ld<NT>(g2 + i);
+    if constexpr (!PERSIST) {
+        // blocks are far apart in the table: find the subgroup by bisection instead of walking
+        int lo = 0, hi = b.n_sg;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (tile >= b.tile_begin[mid]) lo = mid; else hi = mid;
+        }
+        s = lo;
+        const Tile t = locate<T4>(b, tile, s);
+        Regs<BLOCK, UNROLL, NT> r;
+        r.load(t, tid);
+        r.update_store(t, tid, gmul, c);
+    } else {
+        Tile cur = locate<T4>(b, tile, s);
+        Regs<BLOCK, UNROLL, NT> rc;
+        rc.load(cur, tid);
+        for (;;) {
+            const uint32_t next = tile + gridDim.x;
+            const bool more = next < total && next > tile;
+            Tile nxt = cur;
+            Regs<BLOCK, UNROLL, NT> rn;
+            if (more) {
+                nxt = locate<T4>(b, next, s);
+                rn.load(nxt, tid);
             }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint32_t i = u * kBlock + tid;
-                const u32x2 H = update_four(P[u], M[u], V[u], G[u], gmul, c);
-                st<NT>(p4 + i, P[u]);
-                st<NT>(m4 + i, M[u]);
-                st<NT>(v4 + i, V[u]);
-                st<NT>(h2 + i, H);
-            }
-        } else {
-            const uint64_t rem = n - base;  // < kTile
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint32_t i = u * kBlock + tid;
-                const uint64_t e = (uint64_t)i * 4;
-                if (e + 4 <= rem) {
-                    f32x4 P = ld<NT>(p4 + i), M = ld<NT>(m4 + i), V = ld<NT>(v4 + i);
-                    const u32x2 H = update_four(P, M, V, ld<NT>(g2 + i), gmul, c);
-                    st<NT>(p4 + i, P);
-                    st<NT>(m4 + i, M);
-                    st<NT>(v4 + i, V);
-                    st<NT>(h2 + i, H);
-                } else if (e < rem) {
-                    for (uint64_t j = base + e; j < n; ++j) {
-                        float pp = d.p[j], mm = d.m[j], vv = d.v[j];
-                        const float graw = __uint_as_float((uint32_t)d.g[j] << 16);
-                        d.p16[j] = (uint16_t)update_one(pp, mm, vv, graw, gmul, c);
-                        d.p[j] = pp;
-                        d.m[j] = mm;
-                        d.v[j] = vv;
-                    }
-                }
-            }
+            rc.update_store(cur, tid, gmul, c);
+            if (!more) break;
+            cur = nxt;
+            rc = rn;
+            tile = next;
         }
     }
 }
 
-// Element-wise kernel for subgroups whose pointers do not meet the 128-bit kernel's alignment.
-template <int UNROLL>
-__global__ void __launch_bounds__(kBlock) adamw_v1_kernel(const Batch b, const AdamwConsts c,
-                                                          const mlpo_step_scalars* __restrict__ sc) {
+// Element-wise kernel, one tile per block.
+__global__ void __launch_bounds__(kBlock1) adamw_v1_kernel(const ScalarBatch b, const AdamwConsts c,
+                                                           const mlpo_step_scalars* __restrict__ sc) {
     float gmul = 1.0f;
     if (sc != nullptr) {
         if (sc->found_inf != 0u) return;
         gmul = sc->gmul;
     }
-    constexpr uint32_t kTile = kBlock * UNROLL;
-    const uint32_t total = b.tile_begin[b.n_sg];
+    constexpr uint32_t kTile = kBlock1 * kUnroll1;
+    const uint32_t tile = blockIdx.x;
+    if (tile >= b.tile_begin[b.n_sg]) return;
     int s = 0;
-    for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
-        while (tile >= b.tile_begin[s + 1]) ++s;
-        const SgView& d = b.sg[s];
-        const uint64_t base = (uint64_t)(tile - b.tile_begin[s]) * kTile;
+    while (tile >= b.tile_begin[s + 1]) ++s;
+    const SgView& d = b.sg[s];
+    const uint64_t base = (uint64_t)(tile - b.tile_begin[s]) * kTile;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint64_t j = base + (uint32_t)(u * kBlock) + threadIdx.x;
-            if (j < d.n) {
-                float pp = d.p[j], mm = d.m[j], vv = d.v[j];
-                const float graw = __uint_as_float((uint32_t)d.g[j] << 16);
-                d.p16[j] = (uint16_t)update_one(pp, mm, vv, graw, gmul, c);
-                d.p[j] = pp;
-                d.m[j] = mm;
-                d.v[j] = vv;
-            }
+    for (int u = 0; u < kUnroll1; ++u) {
+        const uint64_t j = base + (uint32_t)(u * kBlock1) + threadIdx.x;
+        if (j < d.n) {
+            float pp = d.p[j], mm = d.m[j], vv = d.v[j];
+            const float graw = __uint_as_float((uint32_t)d.g[j] << 16);
+            d.p16[j] = (uint16_t)update_one(pp, mm, vv, graw, gmul, c);
+            d.p[j] = pp;
+            d.m[j] = mm;
+            d.v[j] = vv;
         }
     }
 }
@@ -196,84 +298,163 @@ bool vec_aligned(const SgView& s) {
 }
 
 struct Variant {
+    int block;
     int unroll;
     bool nt;
+    bool persist;
 };
-constexpr Variant kVariants[] = {{2, true}, {1, true}, {4, true}, {2, false}, {1, false}, {4, false}};
+constexpr Variant kVariants[] = {
+    {256, 2, true, false},  {256, 1, true, false},  {256, 4, true, false}, {512, 1, true, false},
+    {512, 2, true, false},  {1024, 1, true, false}, {256, 2, false, false}, {256, 1, false, false},
+    {256, 1, true, true},   {256, 2, true, true},   {512, 1, true, true},  {512, 2, true, true},
+    {1024, 1, true, true},  {256, 2, false, true},
+};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
-template <int UNROLL, bool NT>
-void launch_v4(const Batch& b, uint32_t grid, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
-    hipLaunchKernelGGL((adamw_v4_kernel<UNROLL, NT>), dim3(grid), dim3(kBlock), 0, st, b, c, sc);
+// Tuning value -1 (the default) picks by size: large tiles once there is enough work to fill the chip many times
+// over, small ones below that so that a short launch still spreads over all compute units.
+int variant_index(uint64_t total_elems, bool tiled) {
+    const int vi = tuning().adamw_variant;
+    if (vi >= 0 && vi < kNumVariants) return vi;
+    if (tiled) return 1;
+    return total_elems >= ((uint64_t)1 << 24) ? 2 : 1;
 }
 
-int launch_batch(const Batch& b, bool vec, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
+template <int BLOCK, int UNROLL, bool NT, bool PERSIST>
+void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
+    hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc);
+}
+
+int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
     const uint32_t total = b.tile_begin[b.n_sg];
     if (total == 0) return MLPO_OK;
-    const int cus = num_cus();
-    if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
-    const int per_cu = tuning().adamw_grid_per_cu;
     uint32_t grid = total;
-    if (per_cu > 0) {
+    if (kVariants[vi].persist) {
+        const int cus = num_cus();
+        if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
+        int per_cu = tuning().adamw_grid_per_cu;
+        if (per_cu <= 0) per_cu = 8;
         const uint64_t cap = (uint64_t)cus * (uint64_t)per_cu;
         if (cap < grid) grid = (uint32_t)cap;
     }
-    if (!vec) {
-        hipLaunchKernelGGL((adamw_v1_kernel<4>), dim3(grid), dim3(kBlock), 0, st, b, c, sc);
-    } else {
-        int vi = tuning().adamw_variant;
-        if (vi < 0 || vi >= kNumVariants) vi = 0;
-        switch (vi) {
-            case 0: launch_v4<2, true>(b, grid, c, sc, st); break;
-            case 1: launch_v4<1, true>(b, grid, c, sc, st); break;
-            case 2: launch_v4<4, true>(b, grid, c, sc, st); break;
-            case 3: launch_v4<2, false>(b, grid, c, sc, st); break;
-            case 4: launch_v4<1, false>(b, grid, c, sc, st); break;
-            default: launch_v4<4, false>(b, grid, c, sc, st); break;
-        }
+    switch (vi) {
+        case 0: launch_v4<256, 2, true, false>(b, grid, c, sc, st); break;
+        case 1: launch_v4<256, 1, true, false>(b, grid, c, sc, st); break;
+        case 2: launch_v4<256, 4, true, false>(b, grid, c, sc, st); break;
+        case 3: launch_v4<512, 1, true, false>(b, grid, c, sc, st); break;
+        case 4: launch_v4<512, 2, true, false>(b, grid, c, sc, st); break;
+        case 5: launch_v4<1024, 1, true, false>(b, grid, c, sc, st); break;
+        case 6: launch_v4<256, 2, false, false>(b, grid, c, sc, st); break;
+        case 7: launch_v4<256, 1, false, false>(b, grid, c, sc, st); break;
+        case 8: launch_v4<256, 1, true, true>(b, grid, c, sc, st); break;
+        case 9: launch_v4<256, 2, true, true>(b, grid, c, sc, st); break;
+        case 10: launch_v4<512, 1, true, true>(b, grid, c, sc, st); break;
+        case 11: launch_v4<512, 2, true, true>(b, grid, c, sc, st); break;
+        case 12: launch_v4<1024, 1, true, true>(b, grid, c, sc, st); break;
+        default: launch_v4<256, 2, false, true>(b, grid, c, sc, st); break;
     }
     MLPO_HIP(hipGetLastError());
     return MLPO_OK;
 }
 
-uint32_t tile_elems(bool vec) {
-    if (!vec) return kBlock * 4;
-    int vi = tuning().adamw_variant;
-    if (vi < 0 || vi >= kNumVariants) vi = 0;
-    return (uint32_t)kBlock * 4u * (uint32_t)kVariants[vi].unroll;
+int launch_scalar_batch(const ScalarBatch& b, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
+    const uint32_t total = b.tile_begin[b.n_sg];
+    if (total == 0) return MLPO_OK;
+    hipLaunchKernelGGL(adamw_v1_kernel, dim3(total), dim3(kBlock1), 0, st, b, c, sc);
+    MLPO_HIP(hipGetLastError());
+    return MLPO_OK;
 }
+
+constexpr uint64_t kMaxTiles = 0x7FFFFFFFull;  // grid.x limit
 
 }  // namespace
 
 int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_step_scalars* scalars,
                  hipStream_t stream) {
-    for (int pass = 0; pass < 2; ++pass) {
-        const bool vec = (pass == 0);
-        const uint32_t te = tile_elems(vec);
-        Batch b;
-        b.n_sg = 0;
-        b.tile_begin[0] = 0;
-        for (int i = 0; i < n; ++i) {
-            const SgView& s = views[i];
-            if (s.n == 0 || vec_aligned(s) != vec) continue;
-            const uint64_t tiles = (s.n + te - 1) / te;
-            if (tiles > 0x7FFFFFFFull) return fail(MLPO_EINVAL, "subgroup %d too large (%llu elements)", i,
-                                                   (unsigned long long)s.n);
-            if (b.n_sg == kMaxSg || (uint64_t)b.tile_begin[b.n_sg] + tiles > 0xFFFFFFFFull) {
-                const int rc = launch_batch(b, vec, c, scalars, stream);
-                if (rc != MLPO_OK) return rc;
-                b.n_sg = 0;
-            }
-            b.sg[b.n_sg] = s;
-            b.tile_begin[b.n_sg + 1] = b.tile_begin[b.n_sg] + (uint32_t)tiles;
-            ++b.n_sg;
+    uint64_t total_elems = 0;
+    bool any_tiled = false;
+    for (int i = 0; i < n; ++i) {
+        total_elems += views[i].n;
+        any_tiled = any_tiled || views[i].tile_elems != 0;
+    }
+    int vi = variant_index(total_elems, any_tiled);
+    for (int i = 0; i < n; ++i)  // a kernel tile must divide every layout tile; the 1024-element variant always does
+        if (views[i].tile_elems != 0 &&
+            (uint64_t)views[i].tile_elems % ((uint64_t)kVariants[vi].block * kVariants[vi].unroll * 4u) != 0)
+            vi = 1;
+    const Variant& var = kVariants[vi];
+    const uint64_t t4 = (uint64_t)var.block * (uint64_t)var.unroll;
+    uint64_t align = (uint64_t)tuning().adamw_align_bytes;
+    if (align < 16 || (align & (align - 1)) != 0) align = 16;  // 16 = no head tile
+    if (align > 4096) align = 4096;                            // a head must fit in the smallest tile
+    constexpr uint64_t kTile1 = (uint64_t)kBlock1 * kUnroll1;
+
+    VecBatch vb;
+    vb.n_sg = 0;
+    vb.tile_begin[0] = 0;
+    ScalarBatch sb;
+    sb.n_sg = 0;
+    sb.tile_begin[0] = 0;
+
+    auto push_scalar = [&](const SgView& s) -> int {
+        const uint64_t tiles = (s.n + kTile1 - 1) / kTile1;
+        if (tiles > kMaxTiles) return fail(MLPO_EINVAL, "subgroup too large (%llu elements)", (unsigned long long)s.n);
+        if (sb.n_sg == kMaxSg || (uint64_t)sb.tile_begin[sb.n_sg] + tiles > kMaxTiles) {
+            const int rc = launch_scalar_batch(sb, c, scalars, stream);
+            if (rc != MLPO_OK) return rc;
+            sb.n_sg = 0;
         }
-        if (b.n_sg > 0) {
-            const int rc = launch_batch(b, vec, c, scalars, stream);
+        sb.sg[sb.n_sg] = s;
+        sb.tile_begin[sb.n_sg + 1] = sb.tile_begin[sb.n_sg] + (uint32_t)tiles;
+        ++sb.n_sg;
+        return MLPO_OK;
+    };
+
+    for (int i = 0; i < n; ++i) {
+        const SgView& s = views[i];
+        if (s.n == 0) continue;
+        if (!vec_aligned(s)) {
+            const int rc = push_scalar(s);
+            if (rc != MLPO_OK) return rc;
+            continue;
+        }
+        const uint64_t n4 = s.n / 4;
+        const uint64_t tail = s.n - n4 * 4;
+        if (tail != 0) {  // the last 1-3 elements go to the element-wise kernel
+            const uint64_t o = n4 * 4;
+            uint64_t po = o;  // position of element o in the state arrays
+            if (s.tile_elems != 0) po = (o / (uint64_t)s.tile_elems) * 3u * (uint64_t)s.tile_elems + o % (uint64_t)s.tile_elems;
+            const int rc = push_scalar(SgView{s.p + po, s.m + po, s.v + po, s.g + o, s.p16 + o, tail, 0});
             if (rc != MLPO_OK) return rc;
         }
+        if (n4 == 0) continue;
+        uint64_t head4 = ((align - (reinterpret_cast<uintptr_t>(s.p) & (align - 1))) & (align - 1)) / 16;
+        if (head4 >= n4 || s.tile_elems != 0) head4 = 0;  // tiled buffers are 256-byte aligned by contract
+        const uint64_t tiles = (head4 != 0 ? 1 : 0) + (n4 - head4 + t4 - 1) / t4;
+        if (tiles > kMaxTiles) return fail(MLPO_EINVAL, "subgroup %d too large (%llu elements)", i,
+                                           (unsigned long long)s.n);
+        if (vb.n_sg == kMaxSg || (uint64_t)vb.tile_begin[vb.n_sg] + tiles > kMaxTiles) {
+            const int rc = launch_vec_batch(vb, vi, c, scalars, stream);
+            if (rc != MLPO_OK) return rc;
+            vb.n_sg = 0;
+        }
+        VecView& d = vb.sg[vb.n_sg];
+        d.p = reinterpret_cast<f32x4*>(s.p);
+        d.m = reinterpret_cast<f32x4*>(s.m);
+        d.v = reinterpret_cast<f32x4*>(s.v);
+        d.g = reinterpret_cast<const u32x2*>(s.g);
+        d.h = reinterpret_cast<u32x2*>(s.p16);
+        d.n4 = n4;
+        d.head4 = (uint32_t)head4;
+        d.tiles_per_T = s.tile_elems != 0 ? (uint32_t)((uint64_t)s.tile_elems / 4 / t4) : 0u;
+        d.S4 = s.tile_elems != 0 ? (uint32_t)(3u * (uint64_t)s.tile_elems / 4) : 0u;
+        d.pad = 0;
+        vb.tile_begin[vb.n_sg + 1] = vb.tile_begin[vb.n_sg] + (uint32_t)tiles;
+        ++vb.n_sg;
     }
-    return MLPO_OK;
+    int rc = launch_vec_batch(vb, vi, c, scalars, stream);
+    if (rc != MLPO_OK) return rc;
+    return launch_scalar_batch(sb, c, scalars, stream);
 }
 
 }  // namespace mlpo

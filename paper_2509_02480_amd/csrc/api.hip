@@ -2,6 +2,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stddef.h>
 #include <string.h>
 
 #include <mutex>
@@ -24,7 +25,8 @@ int fail(int code, const char* fmt, ...) {
 
 // ---- tuning / device ------------------------------------------------------------
 Tuning& tuning() {
-    static Tuning t = {/*adamw_grid_per_cu=*/8, /*adamw_variant=*/0, /*norm_grid_per_cu=*/8};
+    static Tuning t = {/*adamw_grid_per_cu=*/8, /*adamw_variant=*/-1, /*norm_grid_per_cu=*/8,
+                       /*adamw_align_bytes=*/256, /*stream_split=*/1};
     return t;
 }
 
@@ -87,7 +89,6 @@ static int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_
         if (s.n != 0 && s.g == nullptr) return fail(MLPO_EINVAL, "subgroup %d: g is NULL", i);
         if (misaligned(s.g, 2)) return fail(MLPO_EINVAL, "subgroup %d: g is not 2-byte aligned", i);
         if (grads_only) continue;
-        if (s.reserved != 0) return fail(MLPO_EINVAL, "subgroup %d: reserved field is not 0", i);
         if (s.tier != MLPO_TIER_HBM && s.tier != MLPO_TIER_HOST)
             return fail(MLPO_EINVAL, "subgroup %d: unknown tier %d", i, s.tier);
         if (s.tier == MLPO_TIER_HOST && !allow_host)
@@ -97,6 +98,15 @@ static int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_
         if (misaligned(s.p, 4) || misaligned(s.m, 4) || misaligned(s.v, 4))
             return fail(MLPO_EINVAL, "subgroup %d: p/m/v not 4-byte aligned", i);
         if (misaligned(s.p16, 2)) return fail(MLPO_EINVAL, "subgroup %d: p16 is not 2-byte aligned", i);
+        if (s.tile_elems < 0 || s.tile_elems % 1024 != 0)
+            return fail(MLPO_EINVAL, "subgroup %d: tile_elems must be 0 or a positive multiple of 1024", i);
+        if (s.tile_elems > 0 && s.n != 0) {
+            if (misaligned(s.p, 256)) return fail(MLPO_EINVAL, "subgroup %d: tiled state must be 256-byte aligned", i);
+            if (s.m != s.p + s.tile_elems || s.v != s.p + 2 * (ptrdiff_t)s.tile_elems)
+                return fail(MLPO_EINVAL, "subgroup %d: tiled state needs m == p + T and v == p + 2T", i);
+            if (misaligned(s.g, 8) || misaligned(s.p16, 8))
+                return fail(MLPO_EINVAL, "subgroup %d: tiled state needs 8-byte aligned g and p16", i);
+        }
     }
     return MLPO_OK;
 }
@@ -148,16 +158,38 @@ static int ensure_events_locked(EventCache& c, int n_slots) {
     return MLPO_OK;
 }
 
-static uint64_t round_up4(uint64_t x) { return (x + 3u) & ~(uint64_t)3u; }
+static uint64_t round_up(uint64_t x, uint64_t to) { return (x + to - 1) / to * to; }
 
-// Elements per staging slot: the largest transfer unit among host-tier subgroups, rounded so that the three arrays
-// of a slot keep 16-byte alignment.
-static uint64_t slot_elems_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems) {
+// One logical transfer issued as `pieces` consecutive copies on the same stream.
+static int copy_split(void* dst, const void* src, size_t bytes, hipMemcpyKind kind, hipStream_t st, int pieces) {
+    if (pieces < 1) pieces = 1;
+    size_t each = (bytes / (size_t)pieces + 255) & ~(size_t)255;
+    size_t done = 0;
+    while (done < bytes) {
+        const size_t len = bytes - done < each ? bytes - done : each;
+        MLPO_HIP(hipMemcpyAsync(static_cast<char*>(dst) + done, static_cast<const char*>(src) + done, len, kind, st));
+        done += len;
+    }
+    return MLPO_OK;
+}
+
+// Floats one host-tier subgroup needs in a staging slot when moved in pieces of at most chunk_elems elements
+// (0 = whole): three arrays, each rounded so that the arrays of a slot keep their alignment (planar) or to whole
+// layout tiles (tiled).
+static uint64_t slot_floats_of(const mlpo_subgroup& s, uint64_t chunk_elems) {
+    uint64_t len = s.n;
+    if (chunk_elems != 0 && chunk_elems < len) len = chunk_elems;
+    return 3u * round_up(len, s.tile_elems > 0 ? (uint64_t)s.tile_elems : 64u);
+}
+
+static uint64_t slot_floats_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems) {
     uint64_t mx = 0;
     for (int32_t i = 0; i < n_sg; ++i)
-        if (sg[i].tier == MLPO_TIER_HOST && sg[i].n > mx) mx = sg[i].n;
-    if (chunk_elems != 0 && chunk_elems < mx) mx = chunk_elems;
-    return round_up4(mx);
+        if (sg[i].tier == MLPO_TIER_HOST) {
+            const uint64_t f = slot_floats_of(sg[i], chunk_elems);
+            if (f > mx) mx = f;
+        }
+    return mx;
 }
 
 }  // namespace mlpo
@@ -174,10 +206,12 @@ size_t mlpo_norm_workspace_bytes(void) { return grad_norm_workspace_bytes(); }
 
 int mlpo_set_option(const char* key, int64_t value) {
     if (key == nullptr) return fail(MLPO_EINVAL, "key is NULL");
-    if (value < -1 || value > 1024) return fail(MLPO_EINVAL, "value out of range");
+    if (value < -1 || value > 65536) return fail(MLPO_EINVAL, "value out of range");
     if (strcmp(key, "adamw_grid_per_cu") == 0) tuning().adamw_grid_per_cu = (int)value;
     else if (strcmp(key, "adamw_variant") == 0) tuning().adamw_variant = (int)value;
     else if (strcmp(key, "norm_grid_per_cu") == 0) tuning().norm_grid_per_cu = (int)value;
+    else if (strcmp(key, "adamw_align_bytes") == 0) tuning().adamw_align_bytes = (int)value;
+    else if (strcmp(key, "stream_split") == 0) tuning().stream_split = (int)value;
     else return fail(MLPO_EINVAL, "unknown option '%s'", key);
     return MLPO_OK;
 }
@@ -212,13 +246,18 @@ int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hpar
     if (n_sg == 0) return MLPO_OK;
     const AdamwConsts c = make_consts(*hp, step);
     std::vector<SgView> views((size_t)n_sg);
-    for (int32_t i = 0; i < n_sg; ++i) views[i] = SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n};
+    for (int32_t i = 0; i < n_sg; ++i) views[i] = SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems};
     return launch_adamw(views.data(), n_sg, c, scalars, static_cast<hipStream_t>(stream));
+}
+
+uint64_t mlpo_state_floats(uint64_t n, int32_t tile_elems) {
+    if (tile_elems <= 0) return 3u * n;
+    return round_up(n, (uint64_t)tile_elems) * 3u;
 }
 
 size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems) {
     if (sg == nullptr || n_sg <= 0 || n_slots <= 0) return 0;
-    return (size_t)(slot_elems_for(sg, n_sg, chunk_elems) * 12u * (uint64_t)n_slots);
+    return (size_t)(slot_floats_for(sg, n_sg, chunk_elems) * 4u * (uint64_t)n_slots);
 }
 
 int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
@@ -241,8 +280,11 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
             seen[(size_t)order[i]] = 1;
         }
     }
-    const uint64_t slot_elems = slot_elems_for(sg, n_sg, cfg->chunk_elems);
-    const uint64_t need = slot_elems * 12u * (uint64_t)cfg->n_slots;
+    for (int32_t i = 0; i < n_sg; ++i)
+        if (sg[i].tier == MLPO_TIER_HOST && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
+            return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
+    const uint64_t slot_floats = slot_floats_for(sg, n_sg, cfg->chunk_elems);
+    const uint64_t need = slot_floats * 4u * (uint64_t)cfg->n_slots;
     if (need > 0) {
         if (cfg->staging == nullptr || misaligned(cfg->staging, 256))
             return fail(MLPO_EINVAL, "staging is NULL or not 256-byte aligned");
@@ -277,7 +319,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
         const int32_t i = order ? order[k] : k;
         if (sg[i].n == 0) continue;
         if (sg[i].tier == MLPO_TIER_HBM)
-            resident.push_back(SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n});
+            resident.push_back(SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems});
         else
             host_ids.push_back(i);
     }
@@ -303,31 +345,54 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     uint64_t piece = 0;
     for (int32_t i : host_ids) {
         const mlpo_subgroup& s = sg[i];
-        for (uint64_t off = 0; off < s.n; off += slot_elems, ++piece) {
-            const uint64_t len = (s.n - off < slot_elems) ? (s.n - off) : slot_elems;
-            const size_t bytes = (size_t)len * sizeof(float);
+        const bool tiled = s.tile_elems > 0;
+        const uint64_t T = tiled ? (uint64_t)s.tile_elems : 0;
+        const uint64_t step_elems = (cfg->chunk_elems != 0 && cfg->chunk_elems < s.n) ? cfg->chunk_elems : s.n;
+        for (uint64_t off = 0; off < s.n; off += step_elems, ++piece) {
+            const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
             const int k = (int)(piece % (uint64_t)cfg->n_slots);
             SlotEvents& ev = ec.slots[(size_t)k];
-            float* sp = staging + (uint64_t)k * 3u * slot_elems;
-            float* sm = sp + slot_elems;
-            float* sv = sm + slot_elems;
+            float* slot = staging + (uint64_t)k * slot_floats;
             // fetch: only into a slot whose previous occupant has been flushed
             if (piece >= (uint64_t)cfg->n_slots) MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.d2h_done, 0));
-            MLPO_HIP(hipMemcpyAsync(sp, s.p + off, bytes, hipMemcpyHostToDevice, s_h2d));
-            MLPO_HIP(hipMemcpyAsync(sm, s.m + off, bytes, hipMemcpyHostToDevice, s_h2d));
-            MLPO_HIP(hipMemcpyAsync(sv, s.v + off, bytes, hipMemcpyHostToDevice, s_h2d));
+            SgView view;
+            if (tiled) {
+                // whole layout tiles travel as one contiguous block: p, m, v of the same elements stay together
+                const size_t bytes = (size_t)(round_up(len, T) * 3u) * sizeof(float);
+                float* src = s.p + (off / T) * 3u * T;
+                rc = copy_split(slot, src, bytes, hipMemcpyHostToDevice, s_h2d, tuning().stream_split);
+                if (rc != MLPO_OK) return rc;
+                view = SgView{slot, slot + T, slot + 2 * T, s.g + off, s.p16 + off, len, s.tile_elems};
+            } else {
+                const size_t bytes = (size_t)len * sizeof(float);
+                const uint64_t arr = round_up(len, 64);
+                float* sp = slot;
+                float* sm = sp + arr;
+                float* sv = sm + arr;
+                MLPO_HIP(hipMemcpyAsync(sp, s.p + off, bytes, hipMemcpyHostToDevice, s_h2d));
+                MLPO_HIP(hipMemcpyAsync(sm, s.m + off, bytes, hipMemcpyHostToDevice, s_h2d));
+                MLPO_HIP(hipMemcpyAsync(sv, s.v + off, bytes, hipMemcpyHostToDevice, s_h2d));
+                view = SgView{sp, sm, sv, s.g + off, s.p16 + off, len, 0};
+            }
             MLPO_HIP(hipEventRecord(ev.h2d_done, s_h2d));
             // update in the slot; gradients and bf16 parameters stay at their device homes
             MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.h2d_done, 0));
-            const SgView view{sp, sm, sv, s.g + off, s.p16 + off, len};
             rc = launch_adamw(&view, 1, c, scalars, s_cmp);
             if (rc != MLPO_OK) return rc;
             MLPO_HIP(hipEventRecord(ev.upd_done, s_cmp));
             // flush
             MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
-            MLPO_HIP(hipMemcpyAsync(s.p + off, sp, bytes, hipMemcpyDeviceToHost, s_d2h));
-            MLPO_HIP(hipMemcpyAsync(s.m + off, sm, bytes, hipMemcpyDeviceToHost, s_d2h));
-            MLPO_HIP(hipMemcpyAsync(s.v + off, sv, bytes, hipMemcpyDeviceToHost, s_d2h));
+            if (tiled) {
+                const size_t bytes = (size_t)(round_up(len, T) * 3u) * sizeof(float);
+                float* dst = s.p + (off / T) * 3u * T;
+                rc = copy_split(dst, slot, bytes, hipMemcpyDeviceToHost, s_d2h, tuning().stream_split);
+                if (rc != MLPO_OK) return rc;
+            } else {
+                const size_t bytes = (size_t)len * sizeof(float);
+                MLPO_HIP(hipMemcpyAsync(s.p + off, view.p, bytes, hipMemcpyDeviceToHost, s_d2h));
+                MLPO_HIP(hipMemcpyAsync(s.m + off, view.m, bytes, hipMemcpyDeviceToHost, s_d2h));
+                MLPO_HIP(hipMemcpyAsync(s.v + off, view.v, bytes, hipMemcpyDeviceToHost, s_d2h));
+            }
             MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
         }
     }

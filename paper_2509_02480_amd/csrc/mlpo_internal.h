@@ -21,6 +21,8 @@ struct Tuning {
     int adamw_grid_per_cu;
     int adamw_variant;
     int norm_grid_per_cu;
+    int adamw_align_bytes;
+    int stream_split;
 };
 Tuning& tuning();
 int num_cus();  // compute units of the current device (cached); <= 0 on failure
@@ -40,6 +42,7 @@ struct SgView {
     const uint16_t* g;
     uint16_t* p16;
     uint64_t n;
+    int32_t tile_elems;  // 0 = planar p/m/v; T > 0 = tiled state (m == p + T, v == p + 2T, layout tiles 3T apart)
 };
 
 // Enqueues the fused update over `n` views (all device memory) on `stream`.  Views are split between the 128-bit

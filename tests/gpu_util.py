@@ -37,19 +37,42 @@ class Scratch:
                 "found_inf": int(h[3:4].view(np.uint32)[0])}
 
 
+def pack_tiled(p, m, v, T):
+    """The tiled state buffer of mlpo.h from three planar arrays (data movement only)."""
+    n = p.size
+    nt = (n + T - 1) // T
+    buf = np.zeros((nt, 3, T), np.float32)
+    for j, a in enumerate((p, m, v)):
+        pad = np.zeros(nt * T, np.float32)
+        pad[:n] = a
+        buf[:, j, :] = pad.reshape(nt, T)
+    return buf.reshape(-1)
+
+
+def unpack_tiled(buf, n, T):
+    nt = (n + T - 1) // T
+    b = np.asarray(buf).reshape(nt, 3, T)
+    return tuple(b[:, j, :].reshape(-1)[:n].copy() for j in range(3))
+
+
 class DeviceSubgroups:
     """Device (and pinned-host) copies of a list of numpy subgroups.
 
     flat=True lays all subgroups out as consecutive slices of five flat buffers (the way a runtime shards one flat
     partition), so slices inherit whatever alignment their offsets give them; flat=False allocates each separately.
-    ``tiers[k] == 1`` puts p, m, v of subgroup k in pinned host memory."""
+    ``tiers[k] == 1`` puts p, m, v of subgroup k in pinned host memory.  ``tile`` > 0 stores the fp32 state of every
+    subgroup in the tiled layout (one buffer per subgroup) instead of three planar arrays."""
 
-    def __init__(self, host_sgs, tiers=None, flat=True, elem_offset=0):
+    def __init__(self, host_sgs, tiers=None, flat=True, elem_offset=0, tile=0):
         self.n_sg = len(host_sgs)
         self.tiers = list(tiers) if tiers is not None else [0] * self.n_sg
         self.sizes = [s["p"].size for s in host_sgs]
         self.t = []
+        self.tile = tile
         d = dev()
+        if tile:
+            self._init_tiled(host_sgs, d)
+            return
         if flat:
             tot = sum(self.sizes) + elem_offset
             big = {k: torch.empty(tot, dtype=torch.float32, device=d) for k in ("p", "m", "v")}
@@ -83,12 +106,35 @@ class DeviceSubgroups:
             B.subgroup(e["p"], e["m"], e["v"], e["g"], e["p16"], n=self.sizes[k], tier=self.tiers[k])
             for k, e in enumerate(self.t))
 
+    def _init_tiled(self, host_sgs, d):
+        T = self.tile
+        descs = []
+        for k, s in enumerate(host_sgs):
+            n = self.sizes[k]
+            packed = torch.from_numpy(pack_tiled(s["p"], s["m"], s["v"], T))
+            assert packed.numel() == B.mlpo_state_floats(n, T)
+            if self.tiers[k] == 1:
+                state = torch.empty(max(packed.numel(), 1), dtype=torch.float32, pin_memory=True)[:packed.numel()]
+                state.copy_(packed)
+            else:
+                state = packed.to(d) if packed.numel() else torch.empty(0, dtype=torch.float32, device=d)
+            ent = {"state": state, "g": torch.from_numpy(s["g"].view(np.int16)).to(d),
+                   "p16": torch.from_numpy(s["p16"].view(np.int16)).to(d)}
+            self.t.append(ent)
+            descs.append(B.tiled_subgroup(state, ent["g"], ent["p16"], n=n, tier=self.tiers[k], tile_elems=T)
+                         if n else B.subgroup(0, 0, 0, 0, 0, n=0, tier=self.tiers[k], tile_elems=T))
+        torch.cuda.synchronize()
+        self.table = B.SubgroupTable(descs)
+
     def set_grads(self, k, g_bits: np.ndarray):
         self.t[k]["g"].copy_(torch.from_numpy(g_bits.view(np.int16)))
 
     def fetch(self, k):
         torch.cuda.synchronize()
         e = self.t[k]
+        if self.tile:
+            p, m, v = unpack_tiled(e["state"].cpu().numpy(), self.sizes[k], self.tile)
+            return {"p": p, "m": m, "v": v, "p16": from_dev_u16(e["p16"]).copy()}
         return {"p": e["p"].cpu().numpy().copy(), "m": e["m"].cpu().numpy().copy(), "v": e["v"].cpu().numpy().copy(),
                 "p16": from_dev_u16(e["p16"]).copy()}
 

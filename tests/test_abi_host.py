@@ -60,9 +60,16 @@ def test_bad_step_and_pointers():
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(tier=1)], hp, 1)          # host tier needs the pipeline
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(tier=7)], hp, 1)
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg()], hp, 1, scalars=FAKE + 4)  # scalars not 16-byte aligned
-    bad = sg()
-    bad.reserved = 1
-    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [bad], hp, 1)
+    # tiled state: T a multiple of 1024, 256-byte aligned buffer, m and v where the layout puts them
+    T = 2048
+    ok = B.tiled_subgroup(FAKE, FAKE + (1 << 20), FAKE + (2 << 20), n=0, tile_elems=T)
+    B.mlpo_adamw_step([ok], hp, 1)                                        # n == 0: nothing dereferenced
+    for bad in (B.tiled_subgroup(FAKE, FAKE + (1 << 20), FAKE + (2 << 20), n=8, tile_elems=1000),
+                B.tiled_subgroup(FAKE + 64, FAKE + (1 << 20), FAKE + (2 << 20), n=8, tile_elems=T),
+                B.tiled_subgroup(FAKE, FAKE + (1 << 20) + 2, FAKE + (2 << 20), n=8, tile_elems=T),
+                B.SubgroupC(FAKE, FAKE + 4 * T, FAKE + 8 * T + 4, FAKE + (1 << 20), FAKE + (2 << 20), 8, 0, T),
+                B.SubgroupC(FAKE, FAKE + 4 * T, FAKE + 8 * T, FAKE + (1 << 20), FAKE + (2 << 20), 8, 0, -1024)):
+        expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [bad], hp, 1)
     # nothing to do is not an error
     B.mlpo_adamw_step([], hp, 1)
     rc = B.lib().mlpo_adamw_step(None, -1, C.byref(hp.c()), 1, None, None)
@@ -99,6 +106,8 @@ def test_stream_argument_errors():
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, cfg(staging=0))
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, cfg(staging=FAKE + 16))
     expect(B.MLPO_ENOMEM, B.mlpo_stream_update, host, None, hp, 1, None, cfg(staging_bytes=3 * 12 * 1000 - 1))
+    tiled = [B.tiled_subgroup(FAKE, FAKE + (1 << 30), FAKE + (2 << 30), n=5000, tier=1, tile_elems=2048)]
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, tiled, None, hp, 1, None, cfg(chunk=1024))   # not a multiple of T
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, [0, 0], hp, 1, None, cfg())
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, [0, 2], hp, 1, None, cfg())
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 0, None, cfg())
@@ -111,10 +120,15 @@ def test_stream_argument_errors():
 
 def test_staging_size_formula():
     host = [sg(n=1000, tier=1), sg(n=4001, tier=1), sg(n=10 ** 6, tier=0)]
-    assert B.mlpo_stream_staging_bytes(host, 3) == 3 * 12 * 4004          # rounded to a multiple of 4 elements
+    assert B.mlpo_stream_staging_bytes(host, 3) == 3 * 12 * 4032          # arrays rounded to 64 elements (256 bytes)
     assert B.mlpo_stream_staging_bytes(host, 2, 1024) == 2 * 12 * 1024
-    assert B.mlpo_stream_staging_bytes(host, 2, 8000) == 2 * 12 * 4004
+    assert B.mlpo_stream_staging_bytes(host, 2, 8000) == 2 * 12 * 4032
     assert B.mlpo_stream_staging_bytes([sg(tier=0)], 4) == 0
+    tiled = [B.tiled_subgroup(FAKE, FAKE + (1 << 30), FAKE + (2 << 30), n=5000, tier=1, tile_elems=2048)]
+    assert B.mlpo_stream_staging_bytes(tiled, 2) == 2 * 12 * 6144         # whole layout tiles
+    assert B.mlpo_stream_staging_bytes(tiled, 2, 4096) == 2 * 12 * 4096
+    assert B.mlpo_state_floats(5000, 2048) == 3 * 6144 and B.mlpo_state_floats(5000, 0) == 15000
+    assert B.mlpo_state_floats(0, 2048) == 0 and B.mlpo_state_floats(2048, 2048) == 3 * 2048
 
 
 def test_options():

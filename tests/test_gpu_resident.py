@@ -22,10 +22,10 @@ def scratch():
     return Scratch()
 
 
-def run_workload(oracle, scratch, wl, warm, flat=True, elem_offset=0, check_every_step=False, threads=8):
+def run_workload(oracle, scratch, wl, warm, flat=True, elem_offset=0, check_every_step=False, threads=8, tile=0):
     ohp, ghp = hp_pair(oracle, **wl.hp.__dict__)
     host = W.host_subgroups(wl, warm=warm, threads=threads)
-    ds = DeviceSubgroups(host, flat=flat, elem_offset=elem_offset)
+    ds = DeviceSubgroups(host, flat=flat, elem_offset=elem_offset, tile=tile)
     applied_o = applied_g = 0
     for s in range(wl.steps):
         if s > 0 and wl.fresh_grads:
@@ -56,42 +56,52 @@ def run_workload(oracle, scratch, wl, warm, flat=True, elem_offset=0, check_ever
     return applied_g
 
 
+TILES = [0, B.TILE_DEFAULT, 1024]   # planar, the default tiled layout, the smallest tile
+
+
+@pytest.mark.parametrize("tile", TILES)
 @pytest.mark.parametrize("warm", [False, True])
-def test_config1_three_steps(oracle, scratch, warm):
-    assert run_workload(oracle, scratch, W.C1, warm, check_every_step=True) == 3
+def test_config1_three_steps(oracle, scratch, warm, tile):
+    assert run_workload(oracle, scratch, W.C1, warm, check_every_step=True, tile=tile) == 3
 
 
-def test_config2_shape_small_with_inf_injection(oracle, scratch):
+@pytest.mark.parametrize("tile", TILES)
+def test_config2_shape_small_with_inf_injection(oracle, scratch, tile):
     # config 2's structure at 1/25 of its size: 16 slices of one flat buffer whose length is a multiple of 4 but not
     # of 8 (odd slices start 8-byte- but not 16-byte-aligned in bf16), loss scale 1024, +inf on the fifth step
     wl = W.Workload("C2/25", n_sub=16, sub_elems=312_500, loss_scale=1024.0, steps=10, inject_every=50)
     assert wl.sub_elems % 4 == 0 and wl.sub_elems % 8 != 0
-    assert run_workload(oracle, scratch, wl, warm=False, check_every_step=True) == 9
+    assert run_workload(oracle, scratch, wl, warm=False, check_every_step=True, tile=tile) == 9
 
 
-def test_config2_full_size(oracle, scratch):
-    # the benchmark workload itself, every element compared after the last step and around the skipped step
-    assert run_workload(oracle, scratch, W.C2, warm=False, threads=16) == 9
+@pytest.mark.parametrize("tile", [0, B.TILE_DEFAULT])
+def test_config2_full_size(oracle, scratch, tile):
+    # the benchmark workload itself in both layouts the benchmark times, every element compared after the last step
+    # and around the skipped step
+    assert run_workload(oracle, scratch, W.C2, warm=False, threads=16, tile=tile) == 9
 
 
 @pytest.mark.parametrize("n", [0, 1, 2, 3, 4, 5, 7, 8, 63, 64, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096,
                                4097, 8191, 8192, 8193, 12289, 100_003])
-@pytest.mark.parametrize("flat,offset", [(False, 0), (True, 1), (True, 2)])
-def test_ragged_sizes_and_alignments(oracle, scratch, n, flat, offset):
-    # two subgroups of n and n+1 elements: tails, tile edges, and (with an odd element offset) the element-wise kernel
+@pytest.mark.parametrize("flat,offset,tile", [(False, 0, 0), (True, 1, 0), (True, 2, 0), (False, 0, 1024),
+                                              (False, 0, 4096)])
+def test_ragged_sizes_and_alignments(oracle, scratch, n, flat, offset, tile):
+    # two subgroups of n and n+1 elements: tails, tile edges, (with an odd element offset) the element-wise kernel,
+    # and tiled state whose last layout tile is partly filled
     ohp, ghp = hp_pair(oracle)
     wl = W.Workload("r", n_sub=1, sub_elems=2 * n + 1, max_norm=0.01, seed=n)
     whole = W.host_subgroups(wl, warm=True)[0]
     host = [{k: a[:n].copy() for k, a in whole.items()}, {k: a[n:].copy() for k, a in whole.items()}]
-    ds = DeviceSubgroups(host, flat=flat, elem_offset=offset)
+    ds = DeviceSubgroups(host, flat=flat, elem_offset=offset, tile=tile)
     ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, 5, 1.0, wl.max_norm)
     ok_g, sc = gpu_step(ds, scratch, ghp, 5, 1.0, wl.max_norm)
     assert ok_g and ok_o and abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5
     for k in range(2):
-        assert_state_parity(ds.fetch(k), host[k], f"n={n} flat={flat} off={offset} sg={k}")
+        assert_state_parity(ds.fetch(k), host[k], f"n={n} flat={flat} off={offset} tile={tile} sg={k}")
 
 
-def test_many_subgroups_span_several_launches(oracle, scratch):
+@pytest.mark.parametrize("tile", [0, 2048])
+def test_many_subgroups_span_several_launches(oracle, scratch, tile):
     # more subgroups than one argument block holds, of uneven sizes including empty ones
     ohp, ghp = hp_pair(oracle)
     rng = np.random.default_rng(0)
@@ -102,7 +112,7 @@ def test_many_subgroups_span_several_launches(oracle, scratch):
     whole = W.host_subgroups(wl, warm=True)[0]
     cuts = np.cumsum([0] + sizes)
     host = [{k: a[cuts[i]:cuts[i + 1]].copy() for k, a in whole.items()} for i in range(len(sizes))]
-    ds = DeviceSubgroups(host, flat=True)
+    ds = DeviceSubgroups(host, flat=True, tile=tile)
     ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, 0, wl.inv_scale, 0.0)
     ok_g, sc = gpu_step(ds, scratch, ghp, 0, wl.inv_scale, 0.0)
     assert ok_g and abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5 and sc["gmul"] == gmul_o
@@ -157,7 +167,8 @@ def test_special_values(oracle, scratch):
     assert np.array_equal(got["p16"], host[0]["p16"])
 
 
-def test_skip_leaves_every_bit_untouched(oracle, scratch):
+@pytest.mark.parametrize("tile", [0, 2048])
+def test_skip_leaves_every_bit_untouched(oracle, scratch, tile):
     ohp, ghp = hp_pair(oracle)
     wl = W.Workload("skip", n_sub=4, sub_elems=70_003)
     for bad, where in ((0x7F80, (0, 0)), (0xFF80, (3, 70_002)), (0x7FC0, (1, 4097)), (0xFFFF, (2, 12345))):
@@ -165,7 +176,7 @@ def test_skip_leaves_every_bit_untouched(oracle, scratch):
         host[where[0]]["g"][where[1]] = bad
         for sg in host:
             sg["p16"][:] = 0x1234
-        ds = DeviceSubgroups(host, flat=True, elem_offset=1 if bad == 0x7FC0 else 0)
+        ds = DeviceSubgroups(host, flat=True, elem_offset=1 if bad == 0x7FC0 else 0, tile=tile)
         ok_g, sc = gpu_step(ds, scratch, ghp, 0)
         ok_o, _, flag_o, _ = oracle.step(host, ohp, 0)
         assert not ok_g and not ok_o and sc["found_inf"] == 1 == flag_o

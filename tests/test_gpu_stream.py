@@ -45,16 +45,18 @@ def stream_step(ds, scratch, ghp, steps_applied, wl, streams, n_slots, chunk, or
     return applied
 
 
-@pytest.mark.parametrize("n_slots,chunk,order_kind", [
-    (1, 0, "asc"), (2, 0, "asc"), (3, 0, "desc"), (4, 0, "perm"),
-    (3, 4096, "asc"), (2, 10_000, "perm"), (4, 1 << 20, "desc"), (8, 33_332, "asc"),
+@pytest.mark.parametrize("n_slots,chunk,order_kind,tile", [
+    (1, 0, "asc", 0), (2, 0, "asc", 0), (3, 0, "desc", 0), (4, 0, "perm", 0),
+    (3, 4096, "asc", 0), (2, 10_000, "perm", 0), (4, 1 << 20, "desc", 0), (8, 33_332, "asc", 0),
+    (1, 0, "asc", 2048), (3, 0, "perm", 8192), (2, 8192, "desc", 2048), (4, 16_384, "perm", 8192),
+    (3, 1 << 20, "asc", 1024),
 ])
-def test_mixed_tiers_match_oracle(oracle, scratch, streams, n_slots, chunk, order_kind):
+def test_mixed_tiers_match_oracle(oracle, scratch, streams, n_slots, chunk, order_kind, tile):
     ohp, ghp = hp_pair(oracle)
     wl = W.Workload("mix", n_sub=7, sub_elems=100_001, n_host=4, loss_scale=256.0, max_norm=0.05, steps=3)
     host = W.host_subgroups(wl, warm=True)
     tiers = [wl.tier(k) for k in range(wl.n_sub)]
-    ds = DeviceSubgroups(host, tiers=tiers, flat=False)
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=tile)
     rng = np.random.default_rng(n_slots)
     hold = {}
     applied = 0
@@ -72,17 +74,18 @@ def test_mixed_tiers_match_oracle(oracle, scratch, streams, n_slots, chunk, orde
         assert abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5 and sc["gmul"] == gmul_o
         applied += 1
         for k in range(wl.n_sub):
-            assert_state_parity(ds.fetch(k), host[k], f"slots={n_slots} chunk={chunk} step={s} sg={k}")
+            assert_state_parity(ds.fetch(k), host[k], f"slots={n_slots} chunk={chunk} tile={tile} step={s} sg={k}")
 
 
-def test_skip_moves_nothing(oracle, scratch, streams):
+@pytest.mark.parametrize("tile", [0, 4096])
+def test_skip_moves_nothing(oracle, scratch, streams, tile):
     ohp, ghp = hp_pair(oracle)
     wl = W.Workload("sskip", n_sub=4, sub_elems=50_000, n_host=2)
     host = W.host_subgroups(wl, warm=True)
     host[3]["g"][77] = 0xFF80
     for sg in host:
         sg["p16"][:] = 0x4321
-    ds = DeviceSubgroups(host, tiers=[1, 1, 0, 0], flat=False)
+    ds = DeviceSubgroups(host, tiers=[1, 1, 0, 0], flat=False, tile=tile)
     hold = {}
     assert stream_step(ds, scratch, ghp, 0, wl, streams, 3, 0, None, hold) is False
     assert scratch.read()["found_inf"] == 1
@@ -97,13 +100,15 @@ def test_skip_moves_nothing(oracle, scratch, streams):
         assert np.array_equal(got["p16"], host[k]["p16"])
 
 
-def test_streamed_equals_resident_bitwise(oracle, scratch, streams):
-    # the same inputs once all-resident and once all-host with an awkward chunk size: identical bits
+@pytest.mark.parametrize("tile", [0, 8192])
+def test_streamed_equals_resident_bitwise(oracle, scratch, streams, tile):
+    # the same inputs once all-resident (planar) and once all-host with an awkward chunk size (planar or tiled):
+    # identical bits
     _, ghp = hp_pair(oracle)
     wl = W.Workload("eq", n_sub=3, sub_elems=250_003, n_host=3, steps=2)
     host = W.host_subgroups(wl, warm=True)
     a = DeviceSubgroups(host, tiers=[0, 0, 0], flat=True)
-    b = DeviceSubgroups(host, tiers=[1, 1, 1], flat=False)
+    b = DeviceSubgroups(host, tiers=[1, 1, 1], flat=False, tile=tile)
     hold = {}
     for s in range(wl.steps):
         B.mlpo_adamw_step(a.table, ghp, s + 1, None, torch.cuda.current_stream())
@@ -128,12 +133,13 @@ def test_same_stream_for_everything(oracle, scratch):
         assert_state_parity(ds.fetch(k), host[k], f"one-stream sg={k}")
 
 
-def test_config3_shape_scaled(oracle, scratch, streams):
+@pytest.mark.parametrize("tile", [0, 8192])
+def test_config3_shape_scaled(oracle, scratch, streams, tile):
     # config 3's structure (13 host-tier subgroups, all state in pinned memory, 2-4 slots) at 1/100 of its size
     ohp, ghp = hp_pair(oracle)
     wl = W.Workload("C3/100", n_sub=13, sub_elems=1_000_000, n_host=13, steps=5, fresh_grads=False)
     host = W.host_subgroups(wl, warm=False, threads=8)
-    ds = DeviceSubgroups(host, tiers=[1] * 13, flat=False)
+    ds = DeviceSubgroups(host, tiers=[1] * 13, flat=False, tile=tile)
     hold = {}
     for s in range(wl.steps):
         oracle.step(host, ohp, s)
