@@ -300,9 +300,13 @@ def streamed_bench(args, torch, B, W, np):
 
     applied = 0
     for n_slots, chunk in args.stream_variants:
-        need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
-        stg = torch.empty(need, dtype=torch.uint8, device=d)
-        cfg = B.stream_cfg(n_slots, stg, need, h2d, cmp_, d2h, chunk)
+        if n_slots == "d":      # direct mode: chunk holds the number of persistent workgroups
+            stg = None
+            cfg = B.direct_cfg(h2d, cmp_, chunk)
+        else:
+            need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
+            stg = torch.empty(need, dtype=torch.uint8, device=d)
+            cfg = B.stream_cfg(n_slots, stg, need, h2d, cmp_, d2h, chunk)
         times = []
         for s in range(args.stream_warmup + wl.steps):
             torch.cuda.synchronize()
@@ -318,12 +322,14 @@ def streamed_bench(args, torch, B, W, np):
                 times.append(dt)
         mean = sum(times) / len(times)
         gbs = 12 * n_host_params / mean / 1e9
-        out["runs"].append({"n_slots": n_slots, "chunk_elems": chunk, "steps": len(times),
+        desc = ({"mode": "direct", "direct_blocks": chunk} if n_slots == "d"
+                else {"mode": "staged", "n_slots": n_slots, "chunk_elems": chunk})
+        out["runs"].append({**desc, "steps": len(times),
                             "ms_per_step": round(mean * 1e3, 2), "min_ms": round(min(times) * 1e3, 2),
                             "pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
                             "frac_of_duplex_memcpy": round(gbs / out["memcpy_duplex_GBs_per_dir"], 4),
                             "Gparams_s": round(wl.n_total / mean / 1e9, 3)})
-        log(f"[bench] streamed slots={n_slots} chunk={chunk}: {out['runs'][-1]}")
+        log(f"[bench] streamed {out['runs'][-1]}")
         del stg, cfg
     best = max(out["runs"], key=lambda r: r["pcie_GBs_per_dir"])
     out["best"] = best
@@ -334,7 +340,7 @@ def parse_variants(text):
     res = []
     for part in text.split(","):
         a, _, b = part.partition(":")
-        res.append((int(a), int(b or 0)))
+        res.append(("d" if a == "d" else int(a), int(b or 0)))
     return res
 
 
@@ -348,8 +354,8 @@ def main():
                     help="fp32 state layout(s) to time; the first is the headline figure")
     ap.add_argument("--tile", type=int, default=8192, help="tile_elems of the tiled layout")
     ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
-    ap.add_argument("--stream-variants", default="3:0,3:16777216,4:16777216",
-                    help="comma list of n_slots:chunk_elems")
+    ap.add_argument("--stream-variants", default="3:0,3:16777216,4:16777216,d:64,d:128",
+                    help="comma list of n_slots:chunk_elems (staged mode) or d:blocks (direct mode)")
     ap.add_argument("--stream-warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-subgroups", type=int, default=8)

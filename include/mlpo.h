@@ -137,17 +137,27 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
 int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hparams* hp, int64_t step,
                     const mlpo_step_scalars* scalars, void* stream);
 
-/* Configuration of the tiered pipeline. */
+/* Configuration of the tiered pipeline.
+ * mode MLPO_STREAM_STAGED: host-tier subgroups are fetched into device staging slots by asynchronous copies, updated
+ *   there and flushed back (three stages on three streams, at most n_slots subgroups or chunks in flight).
+ * mode MLPO_STREAM_DIRECT: the update kernel reads and writes the pinned host state in place over the link; there is
+ *   no staging and nothing to copy.  The bound on what is in flight is direct_blocks, the number of persistent
+ *   workgroups working on the host tier at once; the rest of the GPU updates the HBM-tier subgroups meanwhile.  The
+ *   host-tier kernel is enqueued on the h2d stream, the HBM-tier kernel on the compute stream. */
+#define MLPO_STREAM_STAGED 0
+#define MLPO_STREAM_DIRECT 1
 typedef struct {
-    int32_t n_slots;      /* staging slots = bound on subgroups (or chunks) in flight; 1..MLPO_MAX_SLOTS */
-    int32_t reserved;     /* must be 0 */
-    uint64_t chunk_elems; /* 0: a whole subgroup per transfer; else transfers of this many elements (a multiple of 4,
-                             and of every tile_elems in use) */
-    void* staging;        /* device, 256-byte aligned, caller-owned */
-    size_t staging_bytes; /* >= mlpo_stream_staging_bytes(...) */
-    void* h2d;            /* hipStream_t for host-to-device copies */
-    void* compute;        /* hipStream_t for kernels */
-    void* d2h;            /* hipStream_t for device-to-host copies */
+    int32_t n_slots;       /* staged: staging slots = bound on subgroups (or chunks) in flight; 1..MLPO_MAX_SLOTS */
+    int32_t mode;          /* MLPO_STREAM_STAGED or MLPO_STREAM_DIRECT */
+    uint64_t chunk_elems;  /* staged: 0 = a whole subgroup per transfer; else transfers of this many elements (a
+                              multiple of 4, and of every tile_elems in use) */
+    void* staging;         /* staged: device, 256-byte aligned, caller-owned */
+    size_t staging_bytes;  /* staged: >= mlpo_stream_staging_bytes(...) */
+    void* h2d;             /* hipStream_t for host-to-device copies (direct: for the host-tier kernel) */
+    void* compute;         /* hipStream_t for kernels */
+    void* d2h;             /* hipStream_t for device-to-host copies */
+    int32_t direct_blocks; /* direct: persistent workgroups on the host tier; 0 = default (64); at most 4096 */
+    int32_t reserved;      /* must be 0 */
 } mlpo_stream_cfg;
 
 #define MLPO_MAX_SLOTS 8
@@ -158,11 +168,12 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
 /*
  * One update phase over subgroups of both tiers (Algorithm 1, with the fetch / update / flush overlap of Section 3.4
  * and the bound on subgroups in flight that Section 3.2 "Optimized Virtual Tier Concurrency Control" motivates).
- * HBM-tier subgroups are updated in place as in mlpo_adamw_step.  Each host-tier subgroup (or chunk of one) is
- * copied host-to-device into a free staging slot on the h2d stream, updated there on the compute stream (g and p16
- * are read/written at their device homes), and copied back on the d2h stream; a slot is reused only after its copy
- * back has completed, so at most n_slots transfers are in flight.  Results are bit-identical to the resident path
- * whatever n_slots, chunk_elems and order are.
+ * HBM-tier subgroups are updated in place as in mlpo_adamw_step.  In staged mode each host-tier subgroup (or chunk of
+ * one) is copied host-to-device into a free staging slot on the h2d stream, updated there on the compute stream (g
+ * and p16 are read/written at their device homes), and copied back on the d2h stream; a slot is reused only after its
+ * copy back has completed, so at most n_slots transfers are in flight.  In direct mode the kernel works on the host
+ * state in place.  Results are bit-identical to the resident path whatever mode, n_slots, chunk_elems, direct_blocks
+ * and order are.
  *
  *   order        host array, a permutation of 0..n_sg-1 giving the processing order, or NULL for ascending.
  *   scalars      device pointer or NULL, as for mlpo_adamw_step.  When given, the call first copies the record to the

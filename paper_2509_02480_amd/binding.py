@@ -47,9 +47,9 @@ class StepScalarsC(C.Structure):
 
 
 class StreamCfgC(C.Structure):
-    _fields_ = [("n_slots", C.c_int32), ("reserved", C.c_int32), ("chunk_elems", C.c_uint64),
+    _fields_ = [("n_slots", C.c_int32), ("mode", C.c_int32), ("chunk_elems", C.c_uint64),
                 ("staging", C.c_void_p), ("staging_bytes", C.c_size_t), ("h2d", C.c_void_p), ("compute", C.c_void_p),
-                ("d2h", C.c_void_p)]
+                ("d2h", C.c_void_p), ("direct_blocks", C.c_int32), ("reserved", C.c_int32)]
 
 
 @dataclass
@@ -75,6 +75,13 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; "
                                "g.build()' at the repository root)")
+        # Stream handles and device pointers are only meaningful inside one HIP runtime.  PyTorch wheels carry their
+        # own copy of it, so when torch is installed it is imported first: the library then binds to the runtime
+        # torch uses instead of bringing a second one into the process.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         L.mlpo_last_error.restype = C.c_char_p
         L.mlpo_last_error.argtypes = []
@@ -185,9 +192,19 @@ def mlpo_stream_staging_bytes(sgs, n_slots: int, chunk_elems: int = 0) -> int:
     return int(lib().mlpo_stream_staging_bytes(t.array, t.n, n_slots, chunk_elems))
 
 
+STREAM_STAGED, STREAM_DIRECT = 0, 1
+
+
 def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chunk_elems: int = 0) -> StreamCfgC:
-    return StreamCfgC(n_slots, 0, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d), _stream(compute),
-                      _stream(d2h))
+    """Staged mode: host-tier subgroups travel through ``n_slots`` device staging slots."""
+    return StreamCfgC(n_slots, STREAM_STAGED, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d),
+                      _stream(compute), _stream(d2h), 0, 0)
+
+
+def direct_cfg(host_stream, compute, direct_blocks: int = 0) -> StreamCfgC:
+    """Direct mode: the kernel updates the pinned host state in place with ``direct_blocks`` persistent workgroups."""
+    return StreamCfgC(0, STREAM_DIRECT, 0, None, 0, _stream(host_stream), _stream(compute), _stream(compute),
+                      direct_blocks, 0)
 
 
 def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: int, scalars, cfg: StreamCfgC) -> bool:

@@ -310,6 +310,7 @@ constexpr Variant kVariants[] = {
     {1024, 1, true, true},  {256, 2, false, true},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+constexpr int kPersistVariant = 8;  // 256 threads, one group of four per lane, grid-stride with prefetch
 
 // Tuning value -1 (the default) picks by size: large tiles once there is enough work to fill the chip many times
 // over, small ones below that so that a short launch still spreads over all compute units.
@@ -325,11 +326,14 @@ void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlp
     hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc);
 }
 
-int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
+int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
+                     int persist_blocks) {
     const uint32_t total = b.tile_begin[b.n_sg];
     if (total == 0) return MLPO_OK;
     uint32_t grid = total;
-    if (kVariants[vi].persist) {
+    if (persist_blocks > 0) {
+        if ((uint32_t)persist_blocks < grid) grid = (uint32_t)persist_blocks;
+    } else if (kVariants[vi].persist) {
         const int cus = num_cus();
         if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
         int per_cu = tuning().adamw_grid_per_cu;
@@ -370,7 +374,7 @@ constexpr uint64_t kMaxTiles = 0x7FFFFFFFull;  // grid.x limit
 }  // namespace
 
 int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_step_scalars* scalars,
-                 hipStream_t stream) {
+                 hipStream_t stream, int persist_blocks) {
     uint64_t total_elems = 0;
     bool any_tiled = false;
     for (int i = 0; i < n; ++i) {
@@ -378,6 +382,8 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         any_tiled = any_tiled || views[i].tile_elems != 0;
     }
     int vi = variant_index(total_elems, any_tiled);
+    // A caller-fixed number of persistent blocks (the direct host-tier mode) needs the grid-stride kernel.
+    if (persist_blocks > 0 && !kVariants[vi].persist) vi = kPersistVariant;
     for (int i = 0; i < n; ++i)  // a kernel tile must divide every layout tile; the 1024-element variant always does
         if (views[i].tile_elems != 0 &&
             (uint64_t)views[i].tile_elems % ((uint64_t)kVariants[vi].block * kVariants[vi].unroll * 4u) != 0)
@@ -434,7 +440,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         if (tiles > kMaxTiles) return fail(MLPO_EINVAL, "subgroup %d too large (%llu elements)", i,
                                            (unsigned long long)s.n);
         if (vb.n_sg == kMaxSg || (uint64_t)vb.tile_begin[vb.n_sg] + tiles > kMaxTiles) {
-            const int rc = launch_vec_batch(vb, vi, c, scalars, stream);
+            const int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks);
             if (rc != MLPO_OK) return rc;
             vb.n_sg = 0;
         }
@@ -452,7 +458,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         vb.tile_begin[vb.n_sg + 1] = vb.tile_begin[vb.n_sg] + (uint32_t)tiles;
         ++vb.n_sg;
     }
-    int rc = launch_vec_batch(vb, vi, c, scalars, stream);
+    int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks);
     if (rc != MLPO_OK) return rc;
     return launch_scalar_batch(sb, c, scalars, stream);
 }

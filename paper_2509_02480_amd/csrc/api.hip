@@ -269,7 +269,12 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     if (scalars != nullptr && misaligned(scalars, 16)) return fail(MLPO_EINVAL, "scalars not 16-byte aligned");
     if (cfg == nullptr) return fail(MLPO_EINVAL, "cfg is NULL");
     if (cfg->reserved != 0) return fail(MLPO_EINVAL, "cfg reserved field is not 0");
-    if (cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS)
+    if (cfg->mode != MLPO_STREAM_STAGED && cfg->mode != MLPO_STREAM_DIRECT)
+        return fail(MLPO_EINVAL, "unknown mode %d", cfg->mode);
+    const bool direct = cfg->mode == MLPO_STREAM_DIRECT;
+    if (direct && (cfg->direct_blocks < 0 || cfg->direct_blocks > 4096))
+        return fail(MLPO_EINVAL, "direct_blocks must be 0..4096 (got %d)", cfg->direct_blocks);
+    if (!direct && (cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS))
         return fail(MLPO_EINVAL, "n_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->n_slots);
     if (cfg->chunk_elems % 4 != 0) return fail(MLPO_EINVAL, "chunk_elems must be a multiple of 4");
     if (order != nullptr) {
@@ -283,8 +288,8 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     for (int32_t i = 0; i < n_sg; ++i)
         if (sg[i].tier == MLPO_TIER_HOST && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
             return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
-    const uint64_t slot_floats = slot_floats_for(sg, n_sg, cfg->chunk_elems);
-    const uint64_t need = slot_floats * 4u * (uint64_t)cfg->n_slots;
+    const uint64_t slot_floats = direct ? 0 : slot_floats_for(sg, n_sg, cfg->chunk_elems);
+    const uint64_t need = direct ? 0 : slot_floats * 4u * (uint64_t)cfg->n_slots;
     if (need > 0) {
         if (cfg->staging == nullptr || misaligned(cfg->staging, 256))
             return fail(MLPO_EINVAL, "staging is NULL or not 256-byte aligned");
@@ -314,18 +319,43 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
 
     // HBM-tier subgroups first: their kernel runs while the first fetches are in flight.
     std::vector<SgView> resident;
+    std::vector<SgView> host_views;
     std::vector<int32_t> host_ids;
     for (int32_t k = 0; k < n_sg; ++k) {
         const int32_t i = order ? order[k] : k;
         if (sg[i].n == 0) continue;
         if (sg[i].tier == MLPO_TIER_HBM)
             resident.push_back(SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems});
-        else
+        else {
             host_ids.push_back(i);
+            host_views.push_back(SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems});
+        }
     }
 
     EventCache& ec = events();
     std::lock_guard<std::mutex> lk(ec.mu);
+    if (direct) {
+        // The host tier is updated in place by a bounded number of persistent workgroups; it is enqueued first so
+        // that those workgroups are resident before the HBM-tier kernel fills the rest of the chip.
+        if (!host_views.empty()) {
+            rc = ensure_events_locked(ec, 0);
+            if (rc != MLPO_OK) return rc;
+            MLPO_HIP(hipEventRecord(ec.fence2, s_cmp));  // gradients and scalars come from the compute stream
+            MLPO_HIP(hipStreamWaitEvent(s_h2d, ec.fence2, 0));
+            const int blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 64;
+            rc = launch_adamw(host_views.data(), (int)host_views.size(), c, scalars, s_h2d, blocks);
+            if (rc != MLPO_OK) return rc;
+        }
+        if (!resident.empty()) {
+            rc = launch_adamw(resident.data(), (int)resident.size(), c, scalars, s_cmp);
+            if (rc != MLPO_OK) return rc;
+        }
+        if (!host_views.empty()) {
+            MLPO_HIP(hipEventRecord(ec.fence, s_h2d));
+            MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
+        }
+        return MLPO_OK;
+    }
     if (!host_ids.empty()) {
         rc = ensure_events_locked(ec, cfg->n_slots);
         if (rc != MLPO_OK) return rc;

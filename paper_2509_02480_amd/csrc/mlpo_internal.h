@@ -45,10 +45,12 @@ struct SgView {
     int32_t tile_elems;  // 0 = planar p/m/v; T > 0 = tiled state (m == p + T, v == p + 2T, layout tiles 3T apart)
 };
 
-// Enqueues the fused update over `n` views (all device memory) on `stream`.  Views are split between the 128-bit
-// kernel and the element-wise kernel by alignment; any number of views is accepted (several launches if needed).
+// Enqueues the fused update over `n` views (memory the device can address) on `stream`.  Views are split between
+// the 128-bit kernel and the element-wise kernel by alignment; any number of views is accepted (several launches if
+// needed).  persist_blocks > 0 runs the 128-bit kernel as that many persistent blocks (used when the state sits in
+// pinned host memory and the number of workgroups on the link is to be bounded); 0 lets the launcher choose.
 int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_step_scalars* scalars,
-                 hipStream_t stream);
+                 hipStream_t stream, int persist_blocks = 0);
 
 // Enqueues the gradient pass (see mlpo_grad_unscale_norm).
 int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float max_norm, void* workspace,

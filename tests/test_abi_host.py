@@ -112,6 +112,14 @@ def test_stream_argument_errors():
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, [0, 2], hp, 1, None, cfg())
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 0, None, cfg())
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, B.HParams(beta1=2.0), 1, None, cfg())
+    bad_mode = cfg()
+    bad_mode.mode = 2
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, bad_mode)
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, B.direct_cfg(None, None, 5000))
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, B.direct_cfg(None, None, -1))
+    res = cfg()
+    res.reserved = 1
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, res)
     rc = B.lib().mlpo_stream_update(None, 0, None, C.byref(hp.c()), 1, None, None, None)
     assert rc == B.MLPO_EINVAL
     # an empty list is a no-op that counts as applied

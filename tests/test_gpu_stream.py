@@ -27,13 +27,17 @@ def streams():
     return torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
 
 
-def stream_step(ds, scratch, ghp, steps_applied, wl, streams, n_slots, chunk, order, staging_holder, norm=True):
+def stream_step(ds, scratch, ghp, steps_applied, wl, streams, n_slots, chunk, order, staging_holder, norm=True,
+                direct_blocks=None):
     h2d, cmp_, d2h = streams
-    need = B.mlpo_stream_staging_bytes(ds.table, n_slots, chunk)
-    if staging_holder.get("bytes", -1) < need:
-        staging_holder["t"] = torch.empty(max(need, 256), dtype=torch.uint8, device=dev())
-        staging_holder["bytes"] = need
-    cfg = B.stream_cfg(n_slots, staging_holder["t"], staging_holder["t"].numel(), h2d, cmp_, d2h, chunk)
+    if direct_blocks is not None:
+        cfg = B.direct_cfg(h2d, cmp_, direct_blocks)
+    else:
+        need = B.mlpo_stream_staging_bytes(ds.table, n_slots, chunk)
+        if staging_holder.get("bytes", -1) < need:
+            staging_holder["t"] = torch.empty(max(need, 256), dtype=torch.uint8, device=dev())
+            staging_holder["bytes"] = need
+        cfg = B.stream_cfg(n_slots, staging_holder["t"], staging_holder["t"].numel(), h2d, cmp_, d2h, chunk)
     torch.cuda.synchronize()
     scal = None
     if norm:
@@ -75,6 +79,63 @@ def test_mixed_tiers_match_oracle(oracle, scratch, streams, n_slots, chunk, orde
         applied += 1
         for k in range(wl.n_sub):
             assert_state_parity(ds.fetch(k), host[k], f"slots={n_slots} chunk={chunk} tile={tile} step={s} sg={k}")
+
+
+@pytest.mark.parametrize("blocks,order_kind,tile,flat_off", [
+    (0, "asc", 0, None), (1, "perm", 0, None), (64, "desc", 8192, None), (300, "perm", 2048, None),
+    (4096, "asc", 1024, None), (16, "asc", 0, 1),
+])
+def test_direct_mode_matches_oracle(oracle, scratch, streams, blocks, order_kind, tile, flat_off):
+    # the host tier updated in place over the link by a bounded number of persistent workgroups
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("dir", n_sub=7, sub_elems=100_001, n_host=4, loss_scale=256.0, max_norm=0.05, steps=3)
+    host = W.host_subgroups(wl, warm=True)
+    tiers = [wl.tier(k) for k in range(wl.n_sub)]
+    if flat_off is not None:
+        # host-tier state that is only 4-byte aligned (a view one element into a pinned buffer): element-wise kernel
+        ds = DeviceSubgroups(host, tiers=tiers, flat=False)
+        keep = []
+        descs = []
+        for k, e in enumerate(ds.t):
+            if tiers[k] == 1:
+                for key in ("p", "m", "v"):
+                    buf = torch.empty(e[key].numel() + flat_off, dtype=torch.float32, pin_memory=True)
+                    buf[flat_off:].copy_(e[key])
+                    keep.append(buf)
+                    e[key] = buf[flat_off:]
+            descs.append(B.subgroup(e["p"], e["m"], e["v"], e["g"], e["p16"], n=ds.sizes[k], tier=tiers[k]))
+        ds.table = B.SubgroupTable(descs)
+    else:
+        ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=tile)
+    rng = np.random.default_rng(blocks)
+    applied = 0
+    for s in range(wl.steps):
+        order = {"asc": None, "desc": list(range(wl.n_sub))[::-1], "perm": [int(x) for x in rng.permutation(wl.n_sub)]}[
+            order_kind]
+        if s > 0:
+            for k, sg in enumerate(host):
+                W.fill_grads(wl, k, s, sg["g"])
+                ds.set_grads(k, sg["g"])
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, applied, wl.inv_scale, wl.max_norm, order=order)
+        ok_g = stream_step(ds, scratch, ghp, applied, wl, streams, 0, 0, order, {}, direct_blocks=blocks)
+        assert ok_g == ok_o is True
+        assert scratch.read()["gmul"] == gmul_o
+        applied += 1
+        for k in range(wl.n_sub):
+            assert_state_parity(ds.fetch(k), host[k], f"direct blocks={blocks} tile={tile} step={s} sg={k}")
+
+
+def test_direct_skip_leaves_host_state_untouched(oracle, scratch, streams):
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("dskip", n_sub=3, sub_elems=40_000, n_host=2)
+    host = W.host_subgroups(wl, warm=True)
+    host[0]["g"][123] = 0x7F80
+    ds = DeviceSubgroups(host, tiers=[1, 1, 0], flat=False, tile=2048)
+    assert stream_step(ds, scratch, ghp, 0, wl, streams, 0, 0, None, {}, direct_blocks=8) is False
+    for k in range(wl.n_sub):
+        got = ds.fetch(k)
+        for key in ("p", "m", "v"):
+            assert np.array_equal(got[key].view(np.uint32), host[k][key].view(np.uint32))
 
 
 @pytest.mark.parametrize("tile", [0, 4096])
