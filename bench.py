@@ -26,6 +26,20 @@ BYTES_PER_PARAM_STEP = 28    # read p, m, v (12) + g (2); write p, m, v (12) + b
 BYTES_PER_PARAM_NORM = 2     # read g
 
 
+def recorded_traffic(layout):
+    """HBM bytes per launch of the update kernel as counted by the profiler (profiles/hbm_traffic.json), or None if
+    the kernel source has changed since the counters were taken."""
+    import hashlib
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
+        src = open(os.path.join(ROOT, "paper_2509_02480_amd", "csrc", "adamw.hip"), "rb").read()
+        if hashlib.sha256(src).hexdigest() != rec["adamw_hip_sha256"]:
+            return None
+        return rec["traffic_bytes_per_launch"].get(layout)
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -75,11 +89,7 @@ def resident_bench(args, torch, B, W, np, tile):
         f"setup {time.time() - t0:.1f}s")
 
     total = args.warmup + args.steps
-    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
-    k_start = [ev() for _ in range(args.steps)]
-    k_end = [ev() for _ in range(args.steps)]
-    n_start = [ev() for _ in range(args.steps)]
-    t_begin, t_end = ev(), ev()
+    t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     applied = 0
     applied_timed = 0
     with torch.cuda.stream(stream):
@@ -88,21 +98,17 @@ def resident_bench(args, torch, B, W, np, tile):
             if s == args.warmup:
                 stream.synchronize()
                 torch.cuda.synchronize()
+                # from here on every launch of the two streaming kernels carries its own begin / end timestamps
+                # (HIP events attached to the dispatch on this stream)
+                B.mlpo_set_option("time_kernels", 1)
                 t_begin.record(stream)
             inject = wl.injects(s)
             if inject:
                 idx = wl.inject_index(s)
                 saved.copy_(g_flat[idx:idx + 1])
                 g_flat[idx:idx + 1].copy_(inf_bits)
-            i = s - args.warmup
-            if timed:
-                n_start[i].record(stream)
             B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, stream)
-            if timed:
-                k_start[i].record(stream)
             B.mlpo_adamw_step(table, hp, applied + 1, scal, stream)
-            if timed:
-                k_end[i].record(stream)
             if inject:
                 g_flat[idx:idx + 1].copy_(saved)
             else:
@@ -116,11 +122,14 @@ def resident_bench(args, torch, B, W, np, tile):
     assert flag == (1 if wl.injects(total - 1) else 0)
     assert bool(torch.isfinite(state if tile else flat["p"]).all().item()), "state went non-finite"
 
+    upd_ms = B.mlpo_kernel_times(0)
+    nrm_ms = B.mlpo_kernel_times(1)
+    B.mlpo_set_option("time_kernels", 0)
+    assert len(upd_ms) == args.steps and len(nrm_ms) == args.steps, (len(upd_ms), len(nrm_ms))
     inj_timed = [wl.injects(s) for s in range(args.warmup, total)]
-    k_ms = [k_start[i].elapsed_time(k_end[i]) for i in range(args.steps) if not inj_timed[i]]
-    n_ms = [n_start[i].elapsed_time(k_start[i]) for i in range(args.steps)]
+    k_ms = [upd_ms[i] for i in range(args.steps) if not inj_timed[i]]   # a skipped step's launch exits at once
     k_avg = sum(k_ms) / max(len(k_ms), 1)
-    n_avg = sum(n_ms) / len(n_ms)
+    n_avg = sum(nrm_ms) / len(nrm_ms)
     achieved = BYTES_PER_PARAM_STEP * N / (k_avg * 1e-3) / 1e9
     out = {
         "layout": f"tiled T={tile}" if tile else "planar",
@@ -128,11 +137,13 @@ def resident_bench(args, torch, B, W, np, tile):
         "ms_per_step": round(elapsed_ms / args.steps, 5),
         "applied_steps": applied_timed,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": recorded_traffic(f"tiled T={tile}" if tile else "planar")
+                     if wl.name == W.C2.name else None,
                      "kernel": "adamw_v4_kernel", "avg_launch_ms": round(k_avg, 5),
                      "min_launch_ms": round(min(k_ms), 5), "launches_timed": len(k_ms),
                      "bytes_per_launch": BYTES_PER_PARAM_STEP * N},
-        "norm_pass": {"avg_ms": round(n_avg, 5),
+        "norm_pass": {"kernel": "grad_stats_kernel", "avg_launch_ms": round(n_avg, 5),
                       "achieved_GBs": round(BYTES_PER_PARAM_NORM * N / (n_avg * 1e-3) / 1e9, 1)},
         "step_hbm_frac": round((BYTES_PER_PARAM_STEP + BYTES_PER_PARAM_NORM) * N * applied_timed
                                / (elapsed_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

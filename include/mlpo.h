@@ -192,8 +192,23 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
  *   "adamw_grid_per_cu"  blocks per compute unit of the persistent update grid (default in the source)
  *   "adamw_variant"      kernel variant index
  *   "norm_grid_per_cu"   blocks per compute unit of the gradient pass
+ *   "adamw_align_bytes"  address boundary the planar update kernel aligns its tiles to (power of two, 16..4096)
+ *   "direct_variant"     kernel variant of the direct host-tier mode
+ *   "stream_split"       copies a staged tiled transfer is issued as
+ *   "adamw_flags", "norm_flags"  cache-policy bits of the bf16 streams
+ *   "time_kernels"       see mlpo_kernel_times
  */
 int mlpo_set_option(const char* key, int64_t value);
+
+/*
+ * Per-kernel timing, for measurement.  After mlpo_set_option("time_kernels", 1) every launch of the fused update
+ * kernel (which = 0) and of the gradient pass's streaming kernel (which = 1) is stamped with HIP events that carry the
+ * dispatch's own begin and end on the device.  mlpo_kernel_times waits for the recorded launches, writes their
+ * durations in milliseconds to ms[0..cap) in launch order (host memory), stores the number written in *count and
+ * forgets them.  At most 16384 launches per kind are kept between calls.  Setting the option to 0 turns it off.
+ * Errors: MLPO_EINVAL, MLPO_EHIP.
+ */
+int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count);
 
 /* Releases the events the pipeline caches (optional; safe to call when idle). */
 int mlpo_shutdown(void);

@@ -23,7 +23,8 @@ TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_norm_workspace_bytes",
            "mlpo_grad_unscale_norm",
-           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_set_option", "mlpo_shutdown")
+           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_set_option", "mlpo_kernel_times",
+           "mlpo_shutdown")
 
 
 class MlpoError(RuntimeError):
@@ -103,6 +104,8 @@ def lib():
                                          C.c_void_p, C.POINTER(StreamCfgC), C.POINTER(C.c_int32)]
         L.mlpo_set_option.restype = C.c_int
         L.mlpo_set_option.argtypes = [C.c_char_p, C.c_int64]
+        L.mlpo_kernel_times.restype = C.c_int
+        L.mlpo_kernel_times.argtypes = [C.c_int32, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
         L.mlpo_shutdown.restype = C.c_int
         L.mlpo_shutdown.argtypes = []
         _lib = L
@@ -224,6 +227,14 @@ def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: i
 
 def mlpo_set_option(key: str, value: int) -> None:
     _check(lib().mlpo_set_option(key.encode(), value))
+
+
+def mlpo_kernel_times(which: int, cap: int = 16384) -> list:
+    """Durations (ms) of the launches recorded since the last call; see mlpo.h."""
+    buf = (C.c_float * max(cap, 1))()
+    n = C.c_int32(0)
+    _check(lib().mlpo_kernel_times(which, buf, cap, C.byref(n)))
+    return [buf[i] for i in range(n.value)]
 
 
 def mlpo_shutdown() -> None:

@@ -14,6 +14,7 @@
 // Arithmetic: every operation is an individually rounded fp32 operation (no contraction into fused multiply-add,
 // IEEE division and square root, denormals kept) so that results can be compared bit for bit with a plain CPU
 // evaluation of the same sequence.
+#include <hip/hip_ext.h>
 #include <math.h>
 
 #include "mlpo_internal.h"
@@ -161,7 +162,7 @@ struct Regs {
     f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
     u32x2 G[UNROLL];
 
-    __device__ __forceinline__ void load(const Tile& t, uint32_t tid) {
+    __device__ __forceinline__ void load(const Tile& t, uint32_t tid, uint32_t flags) {
         if (t.cnt == BLOCK * UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -169,7 +170,7 @@ struct Regs {
                 P[u] = ld<NT>(t.p + i);
                 M[u] = ld<NT>(t.m + i);
                 V[u] = ld<NT>(t.v + i);
-                G[u] = ld<NT>(t.g + i);
+                G[u] = (flags & 1u) ? ld<false>(t.g + i) : ld<NT>(t.g + i);
             }
         } else {
 #pragma unroll
@@ -185,7 +186,8 @@ struct Regs {
         }
     }
 
-    __device__ __forceinline__ void update_store(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
+    __device__ __forceinline__ void update_store(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c,
+                                                 uint32_t flags) {
         if (t.cnt == BLOCK * UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -194,7 +196,7 @@ struct Regs {
                 st<NT>(t.p + i, P[u]);
                 st<NT>(t.m + i, M[u]);
                 st<NT>(t.v + i, V[u]);
-                st<NT>(t.h + i, H);
+                if (flags & 2u) st<false>(t.h + i, H); else st<NT>(t.h + i, H);
             }
         } else {
 #pragma unroll
@@ -217,7 +219,8 @@ struct Regs {
 // current tile is computed and stored.
 template <int BLOCK, int UNROLL, bool NT, bool PERSIST>
 __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const AdamwConsts c,
-                                                         const mlpo_step_scalars* __restrict__ sc) {
+                                                         const mlpo_step_scalars* __restrict__ sc,
+                                                         const uint32_t flags) {
     float gmul = 1.0f;
     if (sc != nullptr) {
         if (sc->found_inf != 0u) return;  // skipped step: nothing is read or written
@@ -239,12 +242,12 @@ __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const
         s = lo;
         const Tile t = locate<T4>(b, tile, s);
         Regs<BLOCK, UNROLL, NT> r;
-        r.load(t, tid);
-        r.update_store(t, tid, gmul, c);
+        r.load(t, tid, flags);
+        r.update_store(t, tid, gmul, c, flags);
     } else {
         Tile cur = locate<T4>(b, tile, s);
         Regs<BLOCK, UNROLL, NT> rc;
-        rc.load(cur, tid);
+        rc.load(cur, tid, flags);
         for (;;) {
             const uint32_t next = tile + gridDim.x;
             const bool more = next < total && next > tile;
@@ -252,9 +255,9 @@ __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const
             Regs<BLOCK, UNROLL, NT> rn;
             if (more) {
                 nxt = locate<T4>(b, next, s);
-                rn.load(nxt, tid);
+                rn.load(nxt, tid, flags);
             }
-            rc.update_store(cur, tid, gmul, c);
+            rc.update_store(cur, tid, gmul, c, flags);
             if (!more) break;
             cur = nxt;
             rc = rn;
@@ -323,7 +326,13 @@ int variant_index(uint64_t total_elems, bool tiled) {
 
 template <int BLOCK, int UNROLL, bool NT, bool PERSIST>
 void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
-    hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc);
+    hipEvent_t t0, t1;
+    if (timing_enabled() && timing_acquire(kTimedUpdate, &t0, &t1))
+        hipExtLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, t0, t1, 0,
+                              b, c, sc, (uint32_t)tuning().adamw_flags);
+    else
+        hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc,
+                           (uint32_t)tuning().adamw_flags);
 }
 
 int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
@@ -383,7 +392,10 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
     }
     int vi = variant_index(total_elems, any_tiled);
     // A caller-fixed number of persistent blocks (the direct host-tier mode) needs the grid-stride kernel.
-    if (persist_blocks > 0 && !kVariants[vi].persist) vi = kPersistVariant;
+    if (persist_blocks > 0 && !kVariants[vi].persist) {
+        vi = tuning().direct_variant;
+        if (vi < 0 || vi >= kNumVariants || !kVariants[vi].persist) vi = kPersistVariant;
+    }
     for (int i = 0; i < n; ++i)  // a kernel tile must divide every layout tile; the 1024-element variant always does
         if (views[i].tile_elems != 0 &&
             (uint64_t)views[i].tile_elems % ((uint64_t)kVariants[vi].block * kVariants[vi].unroll * 4u) != 0)

@@ -26,7 +26,8 @@ int fail(int code, const char* fmt, ...) {
 // ---- tuning / device ------------------------------------------------------------
 Tuning& tuning() {
     static Tuning t = {/*adamw_grid_per_cu=*/8, /*adamw_variant=*/-1, /*norm_grid_per_cu=*/8,
-                       /*adamw_align_bytes=*/256, /*stream_split=*/1};
+                       /*adamw_align_bytes=*/256, /*stream_split=*/1,
+                       /*adamw_flags=*/0, /*norm_flags=*/0, /*direct_variant=*/8};
     return t;
 }
 
@@ -42,6 +43,57 @@ int num_cus() {
         cached[dev] = n;
     }
     return cached[dev];
+}
+
+// ---- per-kernel timing ---------------------------------------------------------------
+namespace {
+struct TimedLaunch {
+    hipEvent_t start, stop;
+};
+struct TimingState {
+    std::mutex mu;
+    bool enabled = false;
+    std::vector<TimedLaunch> rec[2];
+    std::vector<TimedLaunch> pool;
+};
+TimingState& timing() {
+    static TimingState t;
+    return t;
+}
+constexpr size_t kMaxTimed = 16384;
+}  // namespace
+
+bool timing_enabled() { return timing().enabled; }
+
+bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop) {
+    TimingState& t = timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    if (!t.enabled || which < 0 || which > 1 || t.rec[which].size() >= kMaxTimed) return false;
+    TimedLaunch e;
+    if (!t.pool.empty()) {
+        e = t.pool.back();
+        t.pool.pop_back();
+    } else {
+        if (hipEventCreate(&e.start) != hipSuccess) return false;
+        if (hipEventCreate(&e.stop) != hipSuccess) {
+            (void)hipEventDestroy(e.start);
+            return false;
+        }
+    }
+    t.rec[which].push_back(e);
+    *start = e.start;
+    *stop = e.stop;
+    return true;
+}
+
+static void timing_set(bool on) {
+    TimingState& t = timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    for (auto& r : t.rec) {
+        for (auto& e : r) t.pool.push_back(e);
+        r.clear();
+    }
+    t.enabled = on;
 }
 
 // ---- hyper-parameters -------------------------------------------------------------
@@ -212,7 +264,30 @@ int mlpo_set_option(const char* key, int64_t value) {
     else if (strcmp(key, "norm_grid_per_cu") == 0) tuning().norm_grid_per_cu = (int)value;
     else if (strcmp(key, "adamw_align_bytes") == 0) tuning().adamw_align_bytes = (int)value;
     else if (strcmp(key, "stream_split") == 0) tuning().stream_split = (int)value;
+    else if (strcmp(key, "adamw_flags") == 0) tuning().adamw_flags = (int)value;
+    else if (strcmp(key, "norm_flags") == 0) tuning().norm_flags = (int)value;
+    else if (strcmp(key, "direct_variant") == 0) tuning().direct_variant = (int)value;
+    else if (strcmp(key, "time_kernels") == 0) timing_set(value != 0);
     else return fail(MLPO_EINVAL, "unknown option '%s'", key);
+    return MLPO_OK;
+}
+
+int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count) {
+    if (which < 0 || which > 1) return fail(MLPO_EINVAL, "which must be 0 (update kernel) or 1 (gradient pass)");
+    if (count == nullptr || cap < 0 || (cap > 0 && ms == nullptr)) return fail(MLPO_EINVAL, "bad output arguments");
+    TimingState& t = timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    int32_t n = 0;
+    for (auto& e : t.rec[which]) {
+        if (n < cap) {
+            MLPO_HIP(hipEventSynchronize(e.stop));
+            MLPO_HIP(hipEventElapsedTime(&ms[n], e.start, e.stop));
+            ++n;
+        }
+        t.pool.push_back(e);
+    }
+    t.rec[which].clear();
+    *count = n;
     return MLPO_OK;
 }
 

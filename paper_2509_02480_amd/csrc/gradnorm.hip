@@ -6,6 +6,7 @@
 // exponent field.  Lanes are combined by wavefront shuffles, wavefronts through LDS, and each block writes one fp64
 // partial and one flag.  Pass 2 (one block) adds the partials in a fixed order and derives norm, clip coefficient and
 // the gradient multiplier.  No atomics: the result depends only on the argument list, not on scheduling.
+#include <hip/hip_ext.h>
 #include <math.h>
 
 #include "mlpo_internal.h"
@@ -56,7 +57,7 @@ __device__ __forceinline__ void accum_half(uint16_t h, float inv_scale, double& 
 }
 
 __global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, const float inv_scale,
-                                                            Workspace* __restrict__ ws) {
+                                                            Workspace* __restrict__ ws, const uint32_t flags) {
     const uint32_t total = b.tile_begin[b.n_sg];
     const uint32_t tid = threadIdx.x;
     double acc = 0.0;
@@ -73,7 +74,8 @@ __global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, c
         if (n_body >= base + kTile) {
             u32x4 w[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) w[u] = __builtin_nontemporal_load(q + u * kBlock + tid);
+            for (int u = 0; u < kUnroll; ++u)
+                w[u] = (flags & 1u) ? q[u * kBlock + tid] : __builtin_nontemporal_load(q + u * kBlock + tid);
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 accum_word(w[u].x, inv_scale, acc, bad);
@@ -181,7 +183,13 @@ int flush(const NormBatch& b, bool first, bool last, float inv_scale, float max_
         uint64_t cap = (uint64_t)cus * (uint64_t)per_cu;
         if (cap > (uint64_t)kMaxGrid) cap = kMaxGrid;
         grid = total < cap ? total : (uint32_t)cap;
-        hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws);
+        hipEvent_t t0, t1;
+        if (timing_enabled() && timing_acquire(kTimedGradPass, &t0, &t1))
+            hipExtLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, b, inv_scale, ws,
+                                  (uint32_t)tuning().norm_flags);
+        else
+            hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws,
+                               (uint32_t)tuning().norm_flags);
         MLPO_HIP(hipGetLastError());
     }
     hipLaunchKernelGGL(grad_finish_kernel, dim3(1), dim3(kBlock), 0, st, ws, (int)grid, first ? 1 : 0, last ? 1 : 0,

@@ -23,9 +23,20 @@ struct Tuning {
     int norm_grid_per_cu;
     int adamw_align_bytes;
     int stream_split;
+    int adamw_flags;  // bit 0: cacheable loads of g; bit 1: cacheable stores of p16
+    int norm_flags;   // bit 0: cacheable loads of g in the gradient pass
+    int direct_variant;
 };
 Tuning& tuning();
 int num_cus();  // compute units of the current device (cached); <= 0 on failure
+
+// ---- optional per-kernel timing (the dispatch's own start / stop timestamps) ------------------
+// When enabled, launch sites ask for an event pair and launch through hipExtLaunchKernelGGL, which stamps the events
+// with the kernel's begin and end on the device rather than with the time markers reach the queue.
+constexpr int kTimedUpdate = 0;  // the fused AdamW kernel (128-bit variant)
+constexpr int kTimedGradPass = 1;  // pass 1 of the gradient pass
+bool timing_enabled();
+bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop);  // false: not enabled or table full
 
 // ---- per-step scalars of the update, derived on the host ---------------------
 struct AdamwConsts {

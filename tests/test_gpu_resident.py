@@ -284,3 +284,24 @@ def test_downcast_exhaustive_over_all_fp32_patterns(oracle, scratch):
         assert np.array_equal(got, want), f"chunk {c}"
         assert not m.any().item() and not v.any().item()
         print(f"downcast chunk {c + 1}/16 ok", flush=True)
+
+
+def test_kernel_timing_records_every_launch(scratch):
+    wl = W.Workload("time", n_sub=2, sub_elems=1 << 20)
+    host = W.host_subgroups(wl, warm=True)
+    ds = DeviceSubgroups(host, tile=B.TILE_DEFAULT)
+    st = torch.cuda.current_stream()
+    B.mlpo_set_option("time_kernels", 1)
+    try:
+        for t in range(1, 6):
+            B.mlpo_grad_unscale_norm(ds.table, 1.0, 0.0, scratch.ws, scratch.ws_bytes, scratch.scalars, st)
+            B.mlpo_adamw_step(ds.table, B.HParams(), t, scratch.scalars, st)
+        upd, nrm = B.mlpo_kernel_times(0), B.mlpo_kernel_times(1)
+        assert len(upd) == 5 and len(nrm) == 5
+        # 2 M elements move 56 MB per update: between a few microseconds and a millisecond on any working device
+        assert all(0.002 < x < 1.0 for x in upd) and all(0.001 < x < 1.0 for x in nrm)
+        assert B.mlpo_kernel_times(0) == []                       # read-out forgets
+    finally:
+        B.mlpo_set_option("time_kernels", 0)
+    B.mlpo_adamw_step(ds.table, B.HParams(), 6, None, st)
+    assert B.mlpo_kernel_times(0) == []                           # nothing recorded when off
