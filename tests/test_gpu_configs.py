@@ -1,0 +1,145 @@
+"""The large workloads (configs 3-5) at their real subgroup sizes, through mlpo_stream_update with mixed tiers.
+
+At these sizes the oracle cannot afford every element, so it computes what it can one by one: the non-finite flag and
+the norm over all gradients (chunked fp64 sums), and the full AdamW recurrence over windows of each subgroup (first,
+middle and last elements, odd offsets), regenerated from the seeded generator.  Elements are independent
+(Section 3.2 "Cache-Friendly Ordering"), so windows are checked to the same bars as whole arrays: fp32 state max
+relative error 1e-6, bf16 copy and flag bit-exact, norm 1e-5.
+
+Config 3 runs at full size.  Configs 4 and 5 run with one fifth of their subgroups (same subgroup size, same tier
+fractions); set MLPO_FULL_SIZE=1 to run them whole (84 and 105 GB of fp32 state, 43 and 75 GB of it pinned)."""
+import os
+import time
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2509_02480_amd import binding as B  # noqa: E402
+from paper_2509_02480_amd import workloads as W  # noqa: E402
+
+from gpu_util import Scratch, dev, max_rel_err  # noqa: E402
+
+FULL = os.environ.get("MLPO_FULL_SIZE", "0") == "1"
+THREADS = 16
+WIN = 70_001
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def window_starts(M):
+    mid = (M // 2 - 12_345) | 1
+    return [0, mid, M - WIN]
+
+
+def phys_index(lo, hi, T):
+    i = np.arange(lo, hi, dtype=np.int64)
+    return (i // T) * (3 * T) + i % T
+
+
+def run_config(oracle, wl, tile, cfg_kind, n_slots=3, chunk=0, direct_blocks=64):
+    d = dev()
+    M, T = wl.sub_elems, tile
+    per = B.mlpo_state_floats(M, T)
+    ohp = oracle.HParams(**wl.hp.__dict__)
+    ghp = B.HParams(**wl.hp.__dict__)
+    say(f"{wl.name}: {wl.n_sub} subgroups of {M} ({wl.n_host} host-tier), tile {T}, {cfg_kind}")
+    g_flat = torch.empty(wl.n_total, dtype=torch.int16, device=d)
+    p16_flat = torch.zeros(wl.n_total, dtype=torch.int16, device=d)
+    tmp = np.zeros(per // 3, np.float32)
+    hg = np.empty(M, np.uint16)
+    states, descs, wins = [], [], []
+    sumsq, flag = 0.0, 0
+    for k in range(wl.n_sub):
+        W.fill_state(wl, k, tmp[:M], None, None, threads=THREADS)
+        if wl.tier(k) == 1:
+            st = torch.zeros(per, dtype=torch.float32, pin_memory=True)
+            st.numpy().reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
+        else:
+            st = torch.zeros(per, dtype=torch.float32, device=d)
+            st.view(-1, 3, T)[:, 0, :].copy_(torch.from_numpy(tmp).view(-1, T))
+        W.fill_grads(wl, k, 0, hg, threads=THREADS)
+        g_flat[k * M:(k + 1) * M].copy_(torch.from_numpy(hg.view(np.int16)))
+        a, b = oracle.grad_stats_chunked(hg, wl.inv_scale)
+        sumsq += a
+        flag |= b
+        for lo in window_starts(M):
+            wins.append({"k": k, "lo": lo, "p": tmp[lo:lo + WIN].copy(), "m": np.zeros(WIN, np.float32),
+                         "v": np.zeros(WIN, np.float32), "g": hg[lo:lo + WIN].copy(),
+                         "p16": np.zeros(WIN, np.uint16)})
+        states.append(st)
+        descs.append(B.tiled_subgroup(st, g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M], n=M,
+                                      tier=wl.tier(k), tile_elems=T))
+        if k % 5 == 4 or k == wl.n_sub - 1:
+            say(f"  filled subgroup {k + 1}/{wl.n_sub}")
+    assert flag == 0
+    norm_o, coef_o, gmul_o = oracle.norm_finish(sumsq, wl.inv_scale, wl.max_norm)
+    table = B.SubgroupTable(descs)
+    scratch = Scratch()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    if cfg_kind == "direct":
+        cfg, stg = B.direct_cfg(streams[0], streams[1], direct_blocks), None
+    else:
+        need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
+        stg = torch.empty(max(need, 256), dtype=torch.uint8, device=d)
+        cfg = B.stream_cfg(n_slots, stg, stg.numel(), streams[0], streams[1], streams[2], chunk)
+    torch.cuda.synchronize()
+    for s in range(wl.steps):
+        t0 = time.perf_counter()
+        B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                 streams[1])
+        assert B.mlpo_stream_update(table, None, ghp, s + 1, scratch.scalars, cfg)
+        streams[1].synchronize()
+        dt = time.perf_counter() - t0
+        sc = scratch.read()
+        say(f"  step {s}: {dt * 1e3:.1f} ms, norm {sc['norm']:.6g} (oracle {norm_o:.6g}), gmul {sc['gmul']:.6g}")
+        assert sc["found_inf"] == 0
+        assert abs(float(sc["norm"]) - float(norm_o)) <= 1e-5 * float(norm_o)
+        assert sc["gmul"] == gmul_o, "gradient multiplier differs from the oracle's: the state cannot match bit for bit"
+        for w in wins:
+            oracle.adamw_f32(w["p"], w["m"], w["v"], w["g"], w["p16"], ohp, s + 1, gmul_o)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for w in wins:
+        k, lo = w["k"], w["lo"]
+        idx = phys_index(lo, lo + WIN, T)
+        st = states[k]
+        for j, key in enumerate(("p", "m", "v")):
+            if st.is_cuda:
+                got = st[torch.from_numpy(idx + j * T).to(d)].cpu().numpy()
+            else:
+                got = st.numpy()[idx + j * T]
+            e = max_rel_err(got, w[key])
+            worst = max(worst, e)
+            assert e <= 1e-6, f"{wl.name} subgroup {k} window {lo} {key}: max rel err {e:.3e}"
+        got16 = p16_flat[k * M + lo:k * M + lo + WIN].cpu().numpy().view(np.uint16)
+        assert np.array_equal(got16, w["p16"]), f"{wl.name} subgroup {k} window {lo}: p16 differs"
+    say(f"{wl.name}: {len(wins)} windows of {WIN} elements match (worst fp32 relative error {worst:.1e})")
+    # untouched padding of the last layout tile stays zero
+    tail = states[-1][per - 3 * T:].cpu().numpy().reshape(3, T) if states[-1].is_cuda else \
+        states[-1].numpy()[per - 3 * T:].reshape(3, T)
+    used = M - (M // T) * T
+    if used:
+        assert not tail[:, used:].any()
+
+
+@pytest.mark.parametrize("cfg_kind,n_slots,chunk", [("staged", 3, 1 << 24), ("direct", 0, 0)])
+def test_config3_full_size(oracle, cfg_kind, n_slots, chunk):
+    run_config(oracle, W.C3, B.TILE_DEFAULT, cfg_kind, n_slots, chunk)
+
+
+def test_config4_mixed_tiers(oracle):
+    wl = W.C4 if FULL else W.C4.scaled_down(5)
+    run_config(oracle, wl, B.TILE_DEFAULT, "staged", n_slots=4, chunk=1 << 25)
+
+
+@pytest.mark.parametrize("cfg_kind", ["staged", "direct"])
+def test_config5_mixed_tiers_with_clip(oracle, cfg_kind):
+    wl = W.C5 if FULL else W.C5.scaled_down(5)
+    assert wl.max_norm == 1.0 and wl.loss_scale == 65536.0
+    run_config(oracle, wl, B.TILE_DEFAULT, cfg_kind, n_slots=2, chunk=1 << 24)
