@@ -22,6 +22,43 @@ def from_dev_u16(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().view(np.uint16)
 
 
+_hip = None
+
+
+def hip_runtime():
+    """The HIP runtime library this process already uses (the one torch loaded), for exact-size pinned allocations:
+    torch's own pinned allocator rounds every request up to a power of two, which wastes half of the pinnable host
+    memory on multi-gigabyte subgroups."""
+    global _hip
+    if _hip is None:
+        import ctypes as C
+        torch.cuda.init()
+        path = [ln.split()[-1] for ln in open("/proc/self/maps") if "libamdhip64" in ln][0]
+        _hip = C.CDLL(path)
+        _hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+        _hip.hipHostFree.argtypes = [C.c_void_p]
+    return _hip
+
+
+class PinnedF32:
+    """n floats of page-locked host memory (hipHostMalloc), seen as a numpy array and as a CPU torch tensor."""
+
+    def __init__(self, n):
+        import ctypes as C
+        self.ptr = C.c_void_p()
+        rc = hip_runtime().hipHostMalloc(C.byref(self.ptr), max(4 * n, 4), 0)
+        if rc != 0:
+            raise MemoryError(f"hipHostMalloc of {4 * n / 1e9:.2f} GB failed (code {rc})")
+        self.np = np.ctypeslib.as_array((C.c_float * n).from_address(self.ptr.value))
+        self.t = torch.from_numpy(self.np)
+
+    def free(self):
+        if self.ptr is not None:
+            self.np = self.t = None
+            hip_runtime().hipHostFree(self.ptr)
+            self.ptr = None
+
+
 class Scratch:
     """Norm workspace and the 16-byte scalar record, allocated once."""
 
