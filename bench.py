@@ -235,9 +235,20 @@ def cpu_baseline(args, W, np):
         one_step(3 + r)
     dt = time.perf_counter() - t0
     n = n_sg * M
+    # the same oracle routines on one thread (plain, unchunked calls) over the same sample, one step
+    t0 = time.perf_counter()
+    sumsq, flag = 0.0, 0
+    for s in host:
+        sumsq, flag = oracle.grad_stats(s["g"], wl.inv_scale, sumsq, flag)
+    _, _, gmul = oracle.norm_finish(sumsq, wl.inv_scale, wl.max_norm)
+    for s in host:
+        oracle.adamw_f32(s["p"], s["m"], s["v"], s["g"], s["p16"], ohp, 3 + reps, gmul)
+    dt_single = time.perf_counter() - t0
     return {"value": round(reps * n / dt / 1e9, 4), "unit": "Gparams/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"first {n_sg} of {wl.n_sub} subgroups ({n} params) x {reps} steps (norm pass + update), "
-                      f"{dt:.1f} s wall"}
+                      f"{dt:.1f} s wall",
+            "single_thread": {"value": round(n / dt_single / 1e9, 4), "unit": "Gparams/s", "cores": 1,
+                              "sample": f"the same {n} params x 1 step, {dt_single:.1f} s wall"}}
 
 
 def streamed_bench(args, torch, B, W, np):
@@ -303,9 +314,10 @@ def streamed_bench(args, torch, B, W, np):
 
     saved_m = hdst.clone()
     bytes_arr = 4 * M
+    # plain pinned copies of one 400 MB array (torch copy_ = hipMemcpyAsync), each direction alone
     out["memcpy_h2d_GBs"] = round(bytes_arr / timed(up) / 1e9, 2)
     out["memcpy_d2h_GBs"] = round(bytes_arr / timed(down) / 1e9, 2)
-    out["memcpy_duplex_GBs_per_dir"] = round(bytes_arr / timed(lambda: (up(), down())) / 1e9, 2)
+    memcpy_peak = min(out["memcpy_h2d_GBs"], out["memcpy_d2h_GBs"])
     hdst.copy_(saved_m)
     del saved_m, ref, ref2
 
@@ -317,10 +329,12 @@ def streamed_bench(args, torch, B, W, np):
         else:
             need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
             stg = torch.empty(need, dtype=torch.uint8, device=d)
-            cfg = B.stream_cfg(n_slots, stg, need, h2d, cmp_, d2h, chunk)
+            cfg = B.stream_cfg(n_slots, stg, need, None, cmp_, None, chunk)    # the library's own copy streams
         times = []
         for s in range(args.stream_warmup + wl.steps):
             torch.cuda.synchronize()
+            if s == args.stream_warmup:
+                B.mlpo_set_option("time_kernels", 1)
             t = time.perf_counter()
             B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
             ok = B.mlpo_stream_update(table, None, hp, applied + 1, scal, cfg)
@@ -331,14 +345,28 @@ def streamed_bench(args, torch, B, W, np):
             applied += 1
             if s >= args.stream_warmup:
                 times.append(dt)
+        fetch_ms, flush_ms, kern_ms = B.mlpo_kernel_times(2), B.mlpo_kernel_times(3), B.mlpo_kernel_times(0)
+        B.mlpo_kernel_times(1)
+        B.mlpo_set_option("time_kernels", 0)
         mean = sum(times) / len(times)
         gbs = 12 * n_host_params / mean / 1e9
+        # the paper's effective I/O throughput (Section 4.3): 2 * bytes / (read time + write time), averaged over
+        # the transfer units; in direct mode reading and writing both last as long as the kernel that does them
+        if n_slots == "d":
+            eff = [2 * 12 * n_host_params / (2 * k * 1e-3) / 1e9 for k in kern_ms if k > 1.0]
+        else:
+            c = chunk or M
+            units = [12 * min(c, M - o) for _ in range(wl.n_host * len(times)) for o in range(0, M, c)]
+            assert len(units) == len(fetch_ms) == len(flush_ms), (len(units), len(fetch_ms), len(flush_ms))
+            eff = [2 * u / ((a + b) * 1e-3) / 1e9 for u, a, b in zip(units, fetch_ms, flush_ms)]
+        eff_io = round(sum(eff) / len(eff), 2) if eff else None
         desc = ({"mode": "direct", "direct_blocks": chunk} if n_slots == "d"
                 else {"mode": "staged", "n_slots": n_slots, "chunk_elems": chunk})
         out["runs"].append({**desc, "steps": len(times),
                             "ms_per_step": round(mean * 1e3, 2), "min_ms": round(min(times) * 1e3, 2),
                             "pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
-                            "frac_of_duplex_memcpy": round(gbs / out["memcpy_duplex_GBs_per_dir"], 4),
+                            "frac_of_one_way_memcpy": round(gbs / memcpy_peak, 4),
+                            "effective_io_GBs_paper_formula": eff_io,
                             "Gparams_s": round(wl.n_total / mean / 1e9, 3)})
         log(f"[bench] streamed {out['runs'][-1]}")
         del stg, cfg

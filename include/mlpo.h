@@ -155,7 +155,10 @@ typedef struct {
     size_t staging_bytes;  /* staged: >= mlpo_stream_staging_bytes(...) */
     void* h2d;             /* hipStream_t for host-to-device copies (direct: for the host-tier kernel) */
     void* compute;         /* hipStream_t for kernels */
-    void* d2h;             /* hipStream_t for device-to-host copies */
+    void* d2h;             /* hipStream_t for device-to-host copies.  If h2d and d2h are both NULL the library uses a
+                              pair of copy streams of its own (created on first use, kept until mlpo_shutdown); this
+                              is the recommended setting: streams handed out by a framework's pool can share a
+                              hardware queue, and the two copy directions then take turns instead of overlapping */
     int32_t direct_blocks; /* direct: persistent workgroups on the host tier; 0 = default (64); at most 4096 */
     int32_t reserved;      /* must be 0 */
 } mlpo_stream_cfg;
@@ -180,7 +183,8 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
  *                host (a 16-byte copy and a wait on the compute stream) because the transfers are issued from the
  *                host: a step with found_inf set moves no data at all.
  *   applied      host pointer or NULL; receives 1 if the step was enqueued, 0 if it was skipped.
- *   cfg          host pointer.  The three streams may be distinct (needed for overlap) or equal.
+ *   cfg          host pointer.  The three streams may be distinct (needed for overlap) or equal; see the note at
+ *                mlpo_stream_cfg.d2h about leaving the two copy streams to the library.
  * On return everything is enqueued; the compute stream is made to wait for the last copy back, so synchronising
  * cfg->compute alone is enough to see the final state.  Calls sharing a staging buffer must not overlap.
  * Errors: MLPO_EINVAL, MLPO_ENOMEM (staging too small), MLPO_EHIP.
@@ -203,14 +207,17 @@ int mlpo_set_option(const char* key, int64_t value);
 /*
  * Per-kernel timing, for measurement.  After mlpo_set_option("time_kernels", 1) every launch of the fused update
  * kernel (which = 0) and of the gradient pass's streaming kernel (which = 1) is stamped with HIP events that carry the
- * dispatch's own begin and end on the device.  mlpo_kernel_times waits for the recorded launches, writes their
- * durations in milliseconds to ms[0..cap) in launch order (host memory), stores the number written in *count and
- * forgets them.  At most 16384 launches per kind are kept between calls.  Setting the option to 0 turns it off.
+ * dispatch's own begin and end on the device, and every staged-mode transfer is bracketed by event markers on its
+ * copy stream (which = 2: host-to-device fetches, which = 3: device-to-host flushes, one entry per subgroup or chunk;
+ * the effective I/O throughput of Section 4.3 of the paper, 2 * bytes / (read time + write time), follows from them).
+ * mlpo_kernel_times waits for the recorded items, writes their durations in milliseconds to ms[0..cap) in issue order
+ * (host memory), stores the number written in *count and forgets them.  At most 16384 items per kind are kept
+ * between calls.  Setting the option to 0 turns it off.
  * Errors: MLPO_EINVAL, MLPO_EHIP.
  */
 int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count);
 
-/* Releases the events the pipeline caches (optional; safe to call when idle). */
+/* Releases the events and copy streams the pipeline caches (optional; safe to call when idle). */
 int mlpo_shutdown(void);
 
 #ifdef __cplusplus

@@ -53,7 +53,7 @@ struct TimedLaunch {
 struct TimingState {
     std::mutex mu;
     bool enabled = false;
-    std::vector<TimedLaunch> rec[2];
+    std::vector<TimedLaunch> rec[4];
     std::vector<TimedLaunch> pool;
 };
 TimingState& timing() {
@@ -68,7 +68,7 @@ bool timing_enabled() { return timing().enabled; }
 bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop) {
     TimingState& t = timing();
     std::lock_guard<std::mutex> lk(t.mu);
-    if (!t.enabled || which < 0 || which > 1 || t.rec[which].size() >= kMaxTimed) return false;
+    if (!t.enabled || which < 0 || which > 3 || t.rec[which].size() >= kMaxTimed) return false;
     TimedLaunch e;
     if (!t.pool.empty()) {
         e = t.pool.back();
@@ -173,6 +173,8 @@ struct EventCache {
     std::vector<SlotEvents> slots;
     hipEvent_t fence = nullptr;   // orders streams at the start and end of a call
     hipEvent_t fence2 = nullptr;
+    hipStream_t copy_in = nullptr;   // the library's own copy streams, used when the caller passes none
+    hipStream_t copy_out = nullptr;
 };
 static EventCache& events() {
     static EventCache c;
@@ -189,6 +191,9 @@ static int release_events_locked(EventCache& c) {
     if (c.fence) (void)hipEventDestroy(c.fence);
     if (c.fence2) (void)hipEventDestroy(c.fence2);
     c.fence = c.fence2 = nullptr;
+    if (c.copy_in) (void)hipStreamDestroy(c.copy_in);
+    if (c.copy_out) (void)hipStreamDestroy(c.copy_out);
+    c.copy_in = c.copy_out = nullptr;
     c.device = -1;
     return MLPO_OK;
 }
@@ -200,6 +205,8 @@ static int ensure_events_locked(EventCache& c, int n_slots) {
     c.device = dev;
     if (c.fence == nullptr) MLPO_HIP(hipEventCreateWithFlags(&c.fence, hipEventDisableTiming));
     if (c.fence2 == nullptr) MLPO_HIP(hipEventCreateWithFlags(&c.fence2, hipEventDisableTiming));
+    if (c.copy_in == nullptr) MLPO_HIP(hipStreamCreateWithFlags(&c.copy_in, hipStreamNonBlocking));
+    if (c.copy_out == nullptr) MLPO_HIP(hipStreamCreateWithFlags(&c.copy_out, hipStreamNonBlocking));
     while ((int)c.slots.size() < n_slots) {
         SlotEvents s;
         MLPO_HIP(hipEventCreateWithFlags(&s.h2d_done, hipEventDisableTiming));
@@ -264,6 +271,7 @@ int mlpo_set_option(const char* key, int64_t value) {
     else if (strcmp(key, "norm_grid_per_cu") == 0) tuning().norm_grid_per_cu = (int)value;
     else if (strcmp(key, "adamw_align_bytes") == 0) tuning().adamw_align_bytes = (int)value;
     else if (strcmp(key, "stream_split") == 0) tuning().stream_split = (int)value;
+
     else if (strcmp(key, "adamw_flags") == 0) tuning().adamw_flags = (int)value;
     else if (strcmp(key, "norm_flags") == 0) tuning().norm_flags = (int)value;
     else if (strcmp(key, "direct_variant") == 0) tuning().direct_variant = (int)value;
@@ -273,7 +281,7 @@ int mlpo_set_option(const char* key, int64_t value) {
 }
 
 int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count) {
-    if (which < 0 || which > 1) return fail(MLPO_EINVAL, "which must be 0 (update kernel) or 1 (gradient pass)");
+    if (which < 0 || which > 3) return fail(MLPO_EINVAL, "which must be 0..3");
     if (count == nullptr || cap < 0 || (cap > 0 && ms == nullptr)) return fail(MLPO_EINVAL, "bad output arguments");
     TimingState& t = timing();
     std::lock_guard<std::mutex> lk(t.mu);
@@ -409,6 +417,13 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
 
     EventCache& ec = events();
     std::lock_guard<std::mutex> lk(ec.mu);
+    if (cfg->h2d == nullptr && cfg->d2h == nullptr && !host_ids.empty()) {
+        // no copy streams given: use the library's own pair (created on first use, one pair per device)
+        rc = ensure_events_locked(ec, 0);
+        if (rc != MLPO_OK) return rc;
+        s_h2d = ec.copy_in;
+        s_d2h = ec.copy_out;
+    }
     if (direct) {
         // The host tier is updated in place by a bounded number of persistent workgroups; it is enqueued first so
         // that those workgroups are resident before the HBM-tier kernel fills the rest of the chip.
@@ -460,6 +475,10 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
             float* slot = staging + (uint64_t)k * slot_floats;
             // fetch: only into a slot whose previous occupant has been flushed
             if (piece >= (uint64_t)cfg->n_slots) MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.d2h_done, 0));
+            hipEvent_t tf0 = nullptr, tf1 = nullptr, tw0 = nullptr, tw1 = nullptr;
+            const bool timed = timing_enabled() && timing_acquire(kTimedFetch, &tf0, &tf1) &&
+                               timing_acquire(kTimedFlush, &tw0, &tw1);
+            if (timed) MLPO_HIP(hipEventRecord(tf0, s_h2d));
             SgView view;
             if (tiled) {
                 // whole layout tiles travel as one contiguous block: p, m, v of the same elements stay together
@@ -479,6 +498,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
                 MLPO_HIP(hipMemcpyAsync(sv, s.v + off, bytes, hipMemcpyHostToDevice, s_h2d));
                 view = SgView{sp, sm, sv, s.g + off, s.p16 + off, len, 0};
             }
+            if (timed) MLPO_HIP(hipEventRecord(tf1, s_h2d));
             MLPO_HIP(hipEventRecord(ev.h2d_done, s_h2d));
             // update in the slot; gradients and bf16 parameters stay at their device homes
             MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.h2d_done, 0));
@@ -487,6 +507,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
             MLPO_HIP(hipEventRecord(ev.upd_done, s_cmp));
             // flush
             MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
+            if (timed) MLPO_HIP(hipEventRecord(tw0, s_d2h));
             if (tiled) {
                 const size_t bytes = (size_t)(round_up(len, T) * 3u) * sizeof(float);
                 float* dst = s.p + (off / T) * 3u * T;
@@ -498,6 +519,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
                 MLPO_HIP(hipMemcpyAsync(s.m + off, view.m, bytes, hipMemcpyDeviceToHost, s_d2h));
                 MLPO_HIP(hipMemcpyAsync(s.v + off, view.v, bytes, hipMemcpyDeviceToHost, s_d2h));
             }
+            if (timed) MLPO_HIP(hipEventRecord(tw1, s_d2h));
             MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
         }
     }

@@ -35,6 +35,8 @@ int num_cus();  // compute units of the current device (cached); <= 0 on failure
 // with the kernel's begin and end on the device rather than with the time markers reach the queue.
 constexpr int kTimedUpdate = 0;  // the fused AdamW kernel (128-bit variant)
 constexpr int kTimedGradPass = 1;  // pass 1 of the gradient pass
+constexpr int kTimedFetch = 2;     // staged mode: one host-to-device transfer (markers on the copy stream)
+constexpr int kTimedFlush = 3;     // staged mode: one device-to-host transfer
 bool timing_enabled();
 bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop);  // false: not enabled or table full
 

@@ -102,7 +102,7 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
     else:
         need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
         stg = torch.empty(max(need, 256), dtype=torch.uint8, device=d)
-        cfg = B.stream_cfg(n_slots, stg, stg.numel(), streams[0], streams[1], streams[2], chunk)
+        cfg = B.stream_cfg(n_slots, stg, stg.numel(), None, streams[1], None, chunk)
     torch.cuda.synchronize()
     for s in range(wl.steps):
         t0 = time.perf_counter()
