@@ -137,6 +137,26 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
 int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hparams* hp, int64_t step,
                     const mlpo_step_scalars* scalars, void* stream);
 
+#define MLPO_MAX_SLOTS 64
+
+/* Memory of which subgroup each staging slot holds, kept by the caller between steps (host memory; zero-initialise
+ * once, then leave it to the library).  Passing it in mlpo_stream_cfg.cache turns on the cache-friendly processing of
+ * Section 3.2 "Cache-Friendly Ordering": a host-tier subgroup that is still in a slot from the previous step is
+ * updated there with no transfer at all, and a slot is copied back to the host only when another subgroup needs it
+ * (lazy flush).  Reversing the processing order from one step to the next makes the subgroups processed last the
+ * ones processed first next time, so each step moves n_host - n_slots subgroups per direction instead of n_host.
+ * While a subgroup sits dirty in a slot its host copy is stale; mlpo_stream_flush brings the host tier up to date. */
+typedef struct {
+    uint32_t magic;   /* 0 = not yet used */
+    int32_t n_slots;
+    uint64_t clock;   /* logical time of the last update */
+    int32_t owner[MLPO_MAX_SLOTS];       /* index of the subgroup in each slot, -1 = empty */
+    uint8_t dirty[MLPO_MAX_SLOTS];       /* the slot is newer than the host copy */
+    uint64_t stamp[MLPO_MAX_SLOTS];      /* logical time of the slot's last update */
+    const void* owner_p[MLPO_MAX_SLOTS]; /* p of the owning subgroup, to notice a changed subgroup table */
+    uint64_t fetches, flushes, hits;     /* transfers issued and transfers saved since the cache was first used */
+} mlpo_slot_cache;
+
 /* Configuration of the tiered pipeline.
  * mode MLPO_STREAM_STAGED: host-tier subgroups are fetched into device staging slots by asynchronous copies, updated
  *   there and flushed back (three stages on three streams, at most n_slots subgroups or chunks in flight).
@@ -161,9 +181,8 @@ typedef struct {
                               hardware queue, and the two copy directions then take turns instead of overlapping */
     int32_t direct_blocks; /* direct: persistent workgroups on the host tier; 0 = default (64); at most 4096 */
     int32_t reserved;      /* must be 0 */
+    mlpo_slot_cache* cache; /* staged, chunk_elems == 0: slots keep their subgroups between steps; NULL = off */
 } mlpo_stream_cfg;
-
-#define MLPO_MAX_SLOTS 8
 
 /* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier). */
 size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems);
@@ -191,6 +210,14 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
  */
 int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
                        int64_t step, const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, int32_t* applied);
+
+/*
+ * Copies every subgroup that a slot of cfg->cache holds in a newer version than the host back to the host tier
+ * (needed before the host copy is read: a checkpoint, the end of training, a change of the subgroup table).  The
+ * slots keep their subgroups.  sg, n_sg and cfg as passed to mlpo_stream_update.  Enqueues on the flush stream; the
+ * compute stream waits for it.  Errors: MLPO_EINVAL, MLPO_ENOMEM, MLPO_EHIP.
+ */
+int mlpo_stream_flush(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_stream_cfg* cfg);
 
 /* Tuning knobs for measurements (process-wide; not needed for correct results).  Unknown keys give MLPO_EINVAL.
  *   "adamw_grid_per_cu"  blocks per compute unit of the persistent update grid (default in the source)

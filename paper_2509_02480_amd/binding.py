@@ -17,13 +17,14 @@ LIB_PATH = os.path.join(_HERE, "libmlpo.so")
 
 MLPO_OK, MLPO_EINVAL, MLPO_EHIP, MLPO_ENOMEM = 0, -1, -2, -3
 TIER_HBM, TIER_HOST = 0, 1
-MAX_SLOTS = 8
+MAX_SLOTS = 64
 
 TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_norm_workspace_bytes",
            "mlpo_grad_unscale_norm",
-           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_set_option", "mlpo_kernel_times",
+           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_set_option",
+           "mlpo_kernel_times",
            "mlpo_shutdown")
 
 
@@ -47,10 +48,18 @@ class StepScalarsC(C.Structure):
     _fields_ = [("norm", C.c_float), ("clip_coef", C.c_float), ("gmul", C.c_float), ("found_inf", C.c_uint32)]
 
 
+class SlotCacheC(C.Structure):
+    _fields_ = [("magic", C.c_uint32), ("n_slots", C.c_int32), ("clock", C.c_uint64),
+                ("owner", C.c_int32 * MAX_SLOTS), ("dirty", C.c_uint8 * MAX_SLOTS), ("stamp", C.c_uint64 * MAX_SLOTS),
+                ("owner_p", C.c_void_p * MAX_SLOTS), ("fetches", C.c_uint64), ("flushes", C.c_uint64),
+                ("hits", C.c_uint64)]
+
+
 class StreamCfgC(C.Structure):
     _fields_ = [("n_slots", C.c_int32), ("mode", C.c_int32), ("chunk_elems", C.c_uint64),
                 ("staging", C.c_void_p), ("staging_bytes", C.c_size_t), ("h2d", C.c_void_p), ("compute", C.c_void_p),
-                ("d2h", C.c_void_p), ("direct_blocks", C.c_int32), ("reserved", C.c_int32)]
+                ("d2h", C.c_void_p), ("direct_blocks", C.c_int32), ("reserved", C.c_int32),
+                ("cache", C.POINTER(SlotCacheC))]
 
 
 @dataclass
@@ -102,6 +111,8 @@ def lib():
         L.mlpo_stream_update.restype = C.c_int
         L.mlpo_stream_update.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(HParamsC), C.c_int64,
                                          C.c_void_p, C.POINTER(StreamCfgC), C.POINTER(C.c_int32)]
+        L.mlpo_stream_flush.restype = C.c_int
+        L.mlpo_stream_flush.argtypes = [C.c_void_p, C.c_int32, C.POINTER(StreamCfgC)]
         L.mlpo_set_option.restype = C.c_int
         L.mlpo_set_option.argtypes = [C.c_char_p, C.c_int64]
         L.mlpo_kernel_times.restype = C.c_int
@@ -198,16 +209,22 @@ def mlpo_stream_staging_bytes(sgs, n_slots: int, chunk_elems: int = 0) -> int:
 STREAM_STAGED, STREAM_DIRECT = 0, 1
 
 
-def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chunk_elems: int = 0) -> StreamCfgC:
-    """Staged mode: host-tier subgroups travel through ``n_slots`` device staging slots."""
-    return StreamCfgC(n_slots, STREAM_STAGED, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d),
-                      _stream(compute), _stream(d2h), 0, 0)
+def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chunk_elems: int = 0,
+               cache: Optional[SlotCacheC] = None) -> StreamCfgC:
+    """Staged mode: host-tier subgroups travel through ``n_slots`` device staging slots.  ``cache`` (a zero-initialised
+    SlotCacheC kept by the caller) lets slots keep their subgroups between steps."""
+    cfg = StreamCfgC(n_slots, STREAM_STAGED, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d),
+                     _stream(compute), _stream(d2h), 0, 0, None)
+    if cache is not None:
+        cfg.cache = C.pointer(cache)
+        cfg._keep = cache
+    return cfg
 
 
 def direct_cfg(host_stream, compute, direct_blocks: int = 0) -> StreamCfgC:
     """Direct mode: the kernel updates the pinned host state in place with ``direct_blocks`` persistent workgroups."""
     return StreamCfgC(0, STREAM_DIRECT, 0, None, 0, _stream(host_stream), _stream(compute), _stream(compute),
-                      direct_blocks, 0)
+                      direct_blocks, 0, None)
 
 
 def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: int, scalars, cfg: StreamCfgC) -> bool:
@@ -223,6 +240,11 @@ def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: i
     _check(lib().mlpo_stream_update(t.array, t.n, ordp, C.byref(h), step, _ptr(scalars), C.byref(cfg),
                                     C.byref(applied)))
     return bool(applied.value)
+
+
+def mlpo_stream_flush(sgs, cfg: StreamCfgC) -> None:
+    t = _table(sgs)
+    _check(lib().mlpo_stream_flush(t.array, t.n, C.byref(cfg)))
 
 
 def mlpo_set_option(key: str, value: int) -> None:

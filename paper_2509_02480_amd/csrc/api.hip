@@ -251,6 +251,93 @@ static uint64_t slot_floats_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t 
     return mx;
 }
 
+
+// One piece (a whole subgroup or a chunk of one) of a host-tier subgroup and the staging slot it occupies.
+struct Piece {
+    const mlpo_subgroup* s;
+    uint64_t off, len;
+    float* slot;
+};
+
+// Host-to-device transfer of a piece into its slot; returns the kernel's view of the slot.
+static int fetch_piece(const Piece& pc, hipStream_t st, SgView* view) {
+    const mlpo_subgroup& s = *pc.s;
+    if (s.tile_elems > 0) {
+        // whole layout tiles travel as one contiguous block: p, m, v of the same elements stay together
+        const uint64_t T = (uint64_t)s.tile_elems;
+        const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
+        const float* src = s.p + (pc.off / T) * 3u * T;
+        const int rc = copy_split(pc.slot, src, bytes, hipMemcpyHostToDevice, st, tuning().stream_split);
+        if (rc != MLPO_OK) return rc;
+        *view = SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, s.g + pc.off, s.p16 + pc.off, pc.len, s.tile_elems};
+    } else {
+        const size_t bytes = (size_t)pc.len * sizeof(float);
+        const uint64_t arr = round_up(pc.len, 64);
+        float* sp = pc.slot;
+        float* sm = sp + arr;
+        float* sv = sm + arr;
+        MLPO_HIP(hipMemcpyAsync(sp, s.p + pc.off, bytes, hipMemcpyHostToDevice, st));
+        MLPO_HIP(hipMemcpyAsync(sm, s.m + pc.off, bytes, hipMemcpyHostToDevice, st));
+        MLPO_HIP(hipMemcpyAsync(sv, s.v + pc.off, bytes, hipMemcpyHostToDevice, st));
+        *view = SgView{sp, sm, sv, s.g + pc.off, s.p16 + pc.off, pc.len, 0};
+    }
+    return MLPO_OK;
+}
+
+// The view of a slot that already holds the piece.
+static SgView slot_view(const Piece& pc) {
+    const mlpo_subgroup& s = *pc.s;
+    if (s.tile_elems > 0) {
+        const uint64_t T = (uint64_t)s.tile_elems;
+        return SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, s.g + pc.off, s.p16 + pc.off, pc.len, s.tile_elems};
+    }
+    const uint64_t arr = round_up(pc.len, 64);
+    return SgView{pc.slot, pc.slot + arr, pc.slot + 2 * arr, s.g + pc.off, s.p16 + pc.off, pc.len, 0};
+}
+
+// Device-to-host transfer of a piece from its slot back to the host tier.
+static int flush_piece(const Piece& pc, hipStream_t st) {
+    const mlpo_subgroup& s = *pc.s;
+    if (s.tile_elems > 0) {
+        const uint64_t T = (uint64_t)s.tile_elems;
+        const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
+        float* dst = s.p + (pc.off / T) * 3u * T;
+        return copy_split(dst, pc.slot, bytes, hipMemcpyDeviceToHost, st, tuning().stream_split);
+    }
+    const size_t bytes = (size_t)pc.len * sizeof(float);
+    const uint64_t arr = round_up(pc.len, 64);
+    MLPO_HIP(hipMemcpyAsync(s.p + pc.off, pc.slot, bytes, hipMemcpyDeviceToHost, st));
+    MLPO_HIP(hipMemcpyAsync(s.m + pc.off, pc.slot + arr, bytes, hipMemcpyDeviceToHost, st));
+    MLPO_HIP(hipMemcpyAsync(s.v + pc.off, pc.slot + 2 * arr, bytes, hipMemcpyDeviceToHost, st));
+    return MLPO_OK;
+}
+
+constexpr uint32_t kCacheMagic = 0x4D4C5043u;  // "MLPC"
+
+static void cache_reset(mlpo_slot_cache* c, int32_t n_slots) {
+    memset(c, 0, sizeof *c);
+    c->magic = kCacheMagic;
+    c->n_slots = n_slots;
+    for (int k = 0; k < MLPO_MAX_SLOTS; ++k) c->owner[k] = -1;
+}
+
+// Checks that a cache left by earlier calls still describes this subgroup table and this configuration.
+static int cache_check(mlpo_slot_cache* c, const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots) {
+    if (c->magic == 0) {
+        cache_reset(c, n_slots);
+        return MLPO_OK;
+    }
+    if (c->magic != kCacheMagic) return fail(MLPO_EINVAL, "slot cache is neither zero-initialised nor ours");
+    if (c->n_slots != n_slots) return fail(MLPO_EINVAL, "slot cache was built for %d slots, not %d", c->n_slots, n_slots);
+    for (int k = 0; k < n_slots; ++k) {
+        const int32_t o = c->owner[k];
+        if (o < 0) continue;
+        if (o >= n_sg || sg[o].p != c->owner_p[k] || sg[o].tier != MLPO_TIER_HOST)
+            return fail(MLPO_EINVAL, "slot %d holds subgroup %d of a different subgroup table", k, o);
+    }
+    return MLPO_OK;
+}
+
 }  // namespace mlpo
 
 using namespace mlpo;
@@ -277,6 +364,46 @@ int mlpo_set_option(const char* key, int64_t value) {
     else if (strcmp(key, "direct_variant") == 0) tuning().direct_variant = (int)value;
     else if (strcmp(key, "time_kernels") == 0) timing_set(value != 0);
     else return fail(MLPO_EINVAL, "unknown option '%s'", key);
+    return MLPO_OK;
+}
+
+int mlpo_stream_flush(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_stream_cfg* cfg) {
+    int rc = validate_subgroups(sg, n_sg, false, /*allow_host=*/1);
+    if (rc != MLPO_OK) return rc;
+    if (cfg == nullptr || cfg->cache == nullptr) return fail(MLPO_EINVAL, "cfg or its slot cache is NULL");
+    if (cfg->mode != MLPO_STREAM_STAGED || cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS)
+        return fail(MLPO_EINVAL, "not a staged configuration");
+    mlpo_slot_cache* cache = cfg->cache;
+    if (cache->magic == 0) return MLPO_OK;  // never used: nothing is held
+    rc = cache_check(cache, sg, n_sg, cfg->n_slots);
+    if (rc != MLPO_OK) return rc;
+    const uint64_t slot_floats = slot_floats_for(sg, n_sg, 0);
+    if (cfg->staging == nullptr || cfg->staging_bytes < slot_floats * 4u * (uint64_t)cfg->n_slots)
+        return fail(MLPO_ENOMEM, "staging does not match the configuration the cache was filled with");
+    EventCache& ec = events();
+    std::lock_guard<std::mutex> lk(ec.mu);
+    rc = ensure_events_locked(ec, cfg->n_slots);
+    if (rc != MLPO_OK) return rc;
+    hipStream_t s_cmp = static_cast<hipStream_t>(cfg->compute);
+    hipStream_t s_d2h = (cfg->h2d == nullptr && cfg->d2h == nullptr) ? ec.copy_out : static_cast<hipStream_t>(cfg->d2h);
+    float* staging = static_cast<float*>(cfg->staging);
+    bool any = false;
+    for (int k = 0; k < cfg->n_slots; ++k) {
+        if (cache->owner[k] < 0 || !cache->dirty[k]) continue;
+        const mlpo_subgroup& s = sg[cache->owner[k]];
+        SlotEvents& ev = ec.slots[(size_t)k];
+        MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
+        rc = flush_piece(Piece{&s, 0, s.n, staging + (uint64_t)k * slot_floats}, s_d2h);
+        if (rc != MLPO_OK) return rc;
+        MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
+        cache->dirty[k] = 0;
+        ++cache->flushes;
+        any = true;
+    }
+    if (any) {
+        MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
+        MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
+    }
     return MLPO_OK;
 }
 
@@ -380,6 +507,12 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
             return fail(MLPO_ENOMEM, "staging has %zu bytes, %llu needed", cfg->staging_bytes,
                         (unsigned long long)need);
     }
+    if (cfg->cache != nullptr) {
+        if (direct) return fail(MLPO_EINVAL, "a slot cache needs staged mode");
+        if (cfg->chunk_elems != 0) return fail(MLPO_EINVAL, "a slot cache needs whole-subgroup transfers (chunk_elems 0)");
+        rc = cache_check(cfg->cache, sg, n_sg, cfg->n_slots);
+        if (rc != MLPO_OK) return rc;
+    }
     if (applied != nullptr) *applied = 1;
     if (n_sg == 0) return MLPO_OK;
 
@@ -462,11 +595,72 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     }
 
     float* staging = static_cast<float*>(cfg->staging);
+    if (cfg->cache != nullptr) {
+        // Slots keep their subgroup from one step to the next (Section 3.2 "Cache-Friendly Ordering"): a subgroup
+        // found in a slot is updated there without any transfer, and a slot is copied back only when another
+        // subgroup needs it (or on mlpo_stream_flush).  With the order reversed from step to step the subgroups
+        // processed last are the ones processed first next time.
+        mlpo_slot_cache* cache = cfg->cache;
+        for (int32_t i : host_ids) {
+            const mlpo_subgroup& s = sg[i];
+            int k = -1;
+            for (int q = 0; q < cfg->n_slots; ++q)
+                if (cache->owner[q] == i) k = q;
+            const bool hit = k >= 0;
+            if (!hit) {
+                for (int q = 0; q < cfg->n_slots && k < 0; ++q)
+                    if (cache->owner[q] < 0) k = q;
+                if (k < 0) {  // least recently updated slot
+                    k = 0;
+                    for (int q = 1; q < cfg->n_slots; ++q)
+                        if (cache->stamp[q] < cache->stamp[k]) k = q;
+                }
+            }
+            SlotEvents& ev = ec.slots[(size_t)k];
+            float* slot = staging + (uint64_t)k * slot_floats;
+            const Piece pc{&s, 0, s.n, slot};
+            SgView view;
+            if (hit) {
+                // an explicit flush of this slot may still be reading it
+                MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.d2h_done, 0));
+                view = slot_view(pc);
+                ++cache->hits;
+            } else {
+                if (cache->owner[k] >= 0 && cache->dirty[k]) {
+                    const mlpo_subgroup& old = sg[cache->owner[k]];
+                    MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
+                    rc = flush_piece(Piece{&old, 0, old.n, slot}, s_d2h);
+                    if (rc != MLPO_OK) return rc;
+                    MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
+                    ++cache->flushes;
+                }
+                cache->owner[k] = -1;  // until the new occupant is in place
+                cache->dirty[k] = 0;
+                MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.d2h_done, 0));
+                MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.upd_done, 0));
+                rc = fetch_piece(pc, s_h2d, &view);
+                if (rc != MLPO_OK) return rc;
+                MLPO_HIP(hipEventRecord(ev.h2d_done, s_h2d));
+                MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.h2d_done, 0));
+                ++cache->fetches;
+            }
+            rc = launch_adamw(&view, 1, c, scalars, s_cmp);
+            if (rc != MLPO_OK) return rc;
+            MLPO_HIP(hipEventRecord(ev.upd_done, s_cmp));
+            cache->owner[k] = i;
+            cache->owner_p[k] = s.p;
+            cache->dirty[k] = 1;
+            cache->stamp[k] = ++cache->clock;
+        }
+        if (!host_ids.empty()) {
+            MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
+            MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
+        }
+        return MLPO_OK;
+    }
     uint64_t piece = 0;
     for (int32_t i : host_ids) {
         const mlpo_subgroup& s = sg[i];
-        const bool tiled = s.tile_elems > 0;
-        const uint64_t T = tiled ? (uint64_t)s.tile_elems : 0;
         const uint64_t step_elems = (cfg->chunk_elems != 0 && cfg->chunk_elems < s.n) ? cfg->chunk_elems : s.n;
         for (uint64_t off = 0; off < s.n; off += step_elems, ++piece) {
             const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
@@ -479,25 +673,10 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
             const bool timed = timing_enabled() && timing_acquire(kTimedFetch, &tf0, &tf1) &&
                                timing_acquire(kTimedFlush, &tw0, &tw1);
             if (timed) MLPO_HIP(hipEventRecord(tf0, s_h2d));
+            const Piece pc{&s, off, len, slot};
             SgView view;
-            if (tiled) {
-                // whole layout tiles travel as one contiguous block: p, m, v of the same elements stay together
-                const size_t bytes = (size_t)(round_up(len, T) * 3u) * sizeof(float);
-                float* src = s.p + (off / T) * 3u * T;
-                rc = copy_split(slot, src, bytes, hipMemcpyHostToDevice, s_h2d, tuning().stream_split);
-                if (rc != MLPO_OK) return rc;
-                view = SgView{slot, slot + T, slot + 2 * T, s.g + off, s.p16 + off, len, s.tile_elems};
-            } else {
-                const size_t bytes = (size_t)len * sizeof(float);
-                const uint64_t arr = round_up(len, 64);
-                float* sp = slot;
-                float* sm = sp + arr;
-                float* sv = sm + arr;
-                MLPO_HIP(hipMemcpyAsync(sp, s.p + off, bytes, hipMemcpyHostToDevice, s_h2d));
-                MLPO_HIP(hipMemcpyAsync(sm, s.m + off, bytes, hipMemcpyHostToDevice, s_h2d));
-                MLPO_HIP(hipMemcpyAsync(sv, s.v + off, bytes, hipMemcpyHostToDevice, s_h2d));
-                view = SgView{sp, sm, sv, s.g + off, s.p16 + off, len, 0};
-            }
+            rc = fetch_piece(pc, s_h2d, &view);
+            if (rc != MLPO_OK) return rc;
             if (timed) MLPO_HIP(hipEventRecord(tf1, s_h2d));
             MLPO_HIP(hipEventRecord(ev.h2d_done, s_h2d));
             // update in the slot; gradients and bf16 parameters stay at their device homes
@@ -508,17 +687,8 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
             // flush
             MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
             if (timed) MLPO_HIP(hipEventRecord(tw0, s_d2h));
-            if (tiled) {
-                const size_t bytes = (size_t)(round_up(len, T) * 3u) * sizeof(float);
-                float* dst = s.p + (off / T) * 3u * T;
-                rc = copy_split(dst, slot, bytes, hipMemcpyDeviceToHost, s_d2h, tuning().stream_split);
-                if (rc != MLPO_OK) return rc;
-            } else {
-                const size_t bytes = (size_t)len * sizeof(float);
-                MLPO_HIP(hipMemcpyAsync(s.p + off, view.p, bytes, hipMemcpyDeviceToHost, s_d2h));
-                MLPO_HIP(hipMemcpyAsync(s.m + off, view.m, bytes, hipMemcpyDeviceToHost, s_d2h));
-                MLPO_HIP(hipMemcpyAsync(s.v + off, view.v, bytes, hipMemcpyDeviceToHost, s_d2h));
-            }
+            rc = flush_piece(pc, s_d2h);
+            if (rc != MLPO_OK) return rc;
             if (timed) MLPO_HIP(hipEventRecord(tw1, s_d2h));
             MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
         }

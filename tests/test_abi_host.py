@@ -120,6 +120,19 @@ def test_stream_argument_errors():
     res = cfg()
     res.reserved = 1
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, res)
+    # slot cache: staged mode, whole-subgroup transfers, a struct that is zero or ours
+    cache = B.SlotCacheC()
+    with_cache = B.stream_cfg(3, FAKE, 1 << 30, None, None, None, 4096, cache=cache)
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, with_cache)            # chunked
+    d = B.direct_cfg(None, None, 8)
+    d.cache = C.pointer(cache)
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, d)                     # direct mode
+    junk = B.SlotCacheC()
+    junk.magic = 12345
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None,
+           B.stream_cfg(3, FAKE, 1 << 30, None, None, None, 0, cache=junk))
+    expect(B.MLPO_EINVAL, B.mlpo_stream_flush, host, cfg())                                     # no cache
+    B.mlpo_stream_flush(host, B.stream_cfg(3, FAKE, 1 << 30, None, None, None, 0, cache=B.SlotCacheC()))  # unused: ok
     rc = B.lib().mlpo_stream_update(None, 0, None, C.byref(hp.c()), 1, None, None, None)
     assert rc == B.MLPO_EINVAL
     # an empty list is a no-op that counts as applied

@@ -209,3 +209,84 @@ def test_config3_shape_scaled(oracle, scratch, streams, tile):
         assert stream_step(ds, scratch, ghp, s, wl, streams, 2 + s % 3, 0, None, hold)
     for k in range(wl.n_sub):
         assert_state_parity(ds.fetch(k), host[k], f"C3/100 sg={k}")
+
+
+@pytest.mark.parametrize("n_slots,tile", [(1, 0), (2, 2048), (3, 0), (4, 8192), (5, 0), (9, 2048)])
+def test_slot_cache_alternating_order(oracle, scratch, streams, n_slots, tile):
+    """Cache-friendly ordering (Section 3.2): slots keep their subgroups, the order is reversed every step, a slot is
+    copied back only when it is needed for another subgroup.  State must equal the oracle's after a final flush, and
+    the transfer counts must be the ones the scheme promises."""
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("cache", n_sub=7, sub_elems=60_001, n_host=5, loss_scale=16.0, max_norm=0.05, steps=5)
+    H = wl.n_host
+    host = W.host_subgroups(wl, warm=True)
+    tiers = [wl.tier(k) for k in range(wl.n_sub)]
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=tile)
+    initial_last = {k: v.copy() for k, v in ds.fetch(H - 1).items()}
+    cache = B.SlotCacheC()
+    need = B.mlpo_stream_staging_bytes(ds.table, n_slots, 0)
+    stg = torch.empty(need, dtype=torch.uint8, device=dev())
+    cfg = B.stream_cfg(n_slots, stg, need, None, streams[1], None, 0, cache=cache)
+    for s in range(wl.steps):
+        order = list(range(wl.n_sub)) if s % 2 == 0 else list(range(wl.n_sub))[::-1]
+        if s > 0:
+            for k, sg in enumerate(host):
+                W.fill_grads(wl, k, s, sg["g"])
+                ds.set_grads(k, sg["g"])
+        ok_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm, order=order)[0]
+        B.mlpo_grad_unscale_norm(ds.table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                 streams[1])
+        assert B.mlpo_stream_update(ds.table, order, ghp, s + 1, scratch.scalars, cfg) and ok_o
+        streams[1].synchronize()
+        if s == 0:
+            # lazy flush: the subgroup processed last is still only in its slot, its host copy is the old one
+            got = ds.fetch(H - 1)
+            assert all(np.array_equal(got[key], initial_last[key]) for key in ("p", "m", "v"))
+            assert cache.fetches == H and cache.hits == 0
+    kept = min(n_slots, H)
+    assert cache.hits == (wl.steps - 1) * kept
+    assert cache.fetches == H + (wl.steps - 1) * (H - kept)
+    B.mlpo_stream_flush(ds.table, cfg)
+    streams[1].synchronize()
+    assert cache.flushes == cache.fetches          # every stay in a slot ended with exactly one copy back
+    B.mlpo_stream_flush(ds.table, cfg)             # nothing left to do
+    assert cache.flushes == cache.fetches
+    for k in range(wl.n_sub):
+        assert_state_parity(ds.fetch(k), host[k], f"cache slots={n_slots} tile={tile} sg={k}")
+
+
+def test_slot_cache_survives_flush_and_skip(oracle, scratch, streams):
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("cache2", n_sub=4, sub_elems=30_011, n_host=4, steps=4)
+    host = W.host_subgroups(wl, warm=True)
+    ds = DeviceSubgroups(host, tiers=[1] * 4, flat=False, tile=1024)
+    cache = B.SlotCacheC()
+    need = B.mlpo_stream_staging_bytes(ds.table, 2, 0)
+    stg = torch.empty(need, dtype=torch.uint8, device=dev())
+    cfg = B.stream_cfg(2, stg, need, None, streams[1], None, 0, cache=cache)
+    applied = 0
+    for s in range(wl.steps):
+        order = list(range(4)) if s % 2 == 0 else [3, 2, 1, 0]
+        if s == 2:
+            host[1]["g"][5] = 0x7F80               # a step that must be skipped: nothing moves, the cache is kept
+            ds.set_grads(1, host[1]["g"])
+        ok_o = oracle.step(host, ohp, applied, order=order)[0]
+        B.mlpo_grad_unscale_norm(ds.table, 1.0, 0.0, scratch.ws, scratch.ws_bytes, scratch.scalars, streams[1])
+        before = (cache.fetches, cache.flushes, cache.hits)
+        ok_g = B.mlpo_stream_update(ds.table, order, ghp, applied + 1, scratch.scalars, cfg)
+        streams[1].synchronize()
+        assert ok_g == ok_o
+        if not ok_g:
+            assert (cache.fetches, cache.flushes, cache.hits) == before
+            host[1]["g"][5] = 0x3A00
+            ds.set_grads(1, host[1]["g"])
+        applied += int(ok_g)
+        if s == 1:
+            B.mlpo_stream_flush(ds.table, cfg)     # a flush in the middle: host tier current, slots still valid
+            streams[1].synchronize()
+            for k in range(4):
+                assert_state_parity(ds.fetch(k), host[k], f"mid-flush sg={k}")
+    B.mlpo_stream_flush(ds.table, cfg)
+    streams[1].synchronize()
+    for k in range(4):
+        assert_state_parity(ds.fetch(k), host[k], f"cache2 sg={k}")
