@@ -219,6 +219,31 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
  */
 int mlpo_stream_flush(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_stream_cfg* cfg);
 
+/*
+ * Allocation of subgroups to the paths of a virtual tier in proportion to their bandwidth (Eq. 1, Section 3.3):
+ *   T_i = ceil(M * B_i / sum_j B_j), adjusted such that sum_i T_i = M.
+ * The paper does not say how to adjust; here the surplus is taken back one subgroup at a time from the tier that
+ * would finish last (largest T_i / B_i), which keeps the finishing times of the paths as close as integers allow.
+ *   n_subgroups  M >= 0.
+ *   n_tiers      N, 1..64.
+ *   bandwidth    host, N values B_i > 0, any common unit (subgroups or bytes per second).
+ *   capacity     host, N values or NULL: the most subgroups tier i can hold, < 0 = unlimited.  A tier that cannot hold
+ *                its share keeps what it can, and Eq. 1 is applied again to the rest (this is how a small fast tier
+ *                such as HBM enters).
+ *   count        host, N values out: T_i.
+ *   tier_of_subgroup  host, M values out or NULL: the tier of each subgroup id; slower tiers get the lower ids (after
+ *                an ascending pass the high ids are the ones still on the fast tiers, Section 3.2).
+ * Errors: MLPO_EINVAL; MLPO_ENOMEM if the capacities cannot hold M subgroups.
+ */
+int mlpo_assign_tiers(int32_t n_subgroups, int32_t n_tiers, const double* bandwidth, const int32_t* capacity,
+                      int32_t* count, int32_t* tier_of_subgroup);
+
+/*
+ * Online re-estimation of the bandwidths (Section 3.3): after an iteration B_i becomes the average bandwidth observed
+ * on tier i, bytes_moved[i] / seconds[i]; a tier that moved nothing keeps its estimate.  All arrays host, N values.
+ */
+int mlpo_update_bandwidth(int32_t n_tiers, double* bandwidth, const double* bytes_moved, const double* seconds);
+
 /* Tuning knobs for measurements (process-wide; not needed for correct results).  Unknown keys give MLPO_EINVAL.
  *   "adamw_grid_per_cu"  blocks per compute unit of the persistent update grid (default in the source)
  *   "adamw_variant"      kernel variant index

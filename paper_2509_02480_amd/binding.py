@@ -23,7 +23,8 @@ TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_norm_workspace_bytes",
            "mlpo_grad_unscale_norm",
-           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_set_option",
+           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers",
+           "mlpo_update_bandwidth", "mlpo_set_option",
            "mlpo_kernel_times",
            "mlpo_shutdown")
 
@@ -113,6 +114,11 @@ def lib():
                                          C.c_void_p, C.POINTER(StreamCfgC), C.POINTER(C.c_int32)]
         L.mlpo_stream_flush.restype = C.c_int
         L.mlpo_stream_flush.argtypes = [C.c_void_p, C.c_int32, C.POINTER(StreamCfgC)]
+        L.mlpo_assign_tiers.restype = C.c_int
+        L.mlpo_assign_tiers.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.mlpo_update_bandwidth.restype = C.c_int
+        L.mlpo_update_bandwidth.argtypes = [C.c_int32] + [C.POINTER(C.c_double)] * 3
         L.mlpo_set_option.restype = C.c_int
         L.mlpo_set_option.argtypes = [C.c_char_p, C.c_int64]
         L.mlpo_kernel_times.restype = C.c_int
@@ -245,6 +251,24 @@ def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: i
 def mlpo_stream_flush(sgs, cfg: StreamCfgC) -> None:
     t = _table(sgs)
     _check(lib().mlpo_stream_flush(t.array, t.n, C.byref(cfg)))
+
+
+def mlpo_assign_tiers(n_subgroups: int, bandwidth: Sequence[float], capacity: Optional[Sequence[int]] = None):
+    """(counts per tier, tier of each subgroup id) by Eq. 1; see mlpo.h."""
+    n = len(bandwidth)
+    bw = (C.c_double * n)(*bandwidth)
+    cap = (C.c_int32 * n)(*capacity) if capacity is not None else None
+    cnt = (C.c_int32 * n)()
+    tiers = (C.c_int32 * max(n_subgroups, 1))()
+    _check(lib().mlpo_assign_tiers(n_subgroups, n, bw, cap, cnt, tiers))
+    return list(cnt), list(tiers)[:n_subgroups]
+
+
+def mlpo_update_bandwidth(bandwidth: Sequence[float], bytes_moved: Sequence[float], seconds: Sequence[float]):
+    n = len(bandwidth)
+    bw = (C.c_double * n)(*bandwidth)
+    _check(lib().mlpo_update_bandwidth(n, bw, (C.c_double * n)(*bytes_moved), (C.c_double * n)(*seconds)))
+    return list(bw)
 
 
 def mlpo_set_option(key: str, value: int) -> None:
