@@ -250,8 +250,6 @@ int mlpo_update_bandwidth(int32_t n_tiers, double* bandwidth, const double* byte
  *   "norm_grid_per_cu"   blocks per compute unit of the gradient pass
  *   "adamw_align_bytes"  address boundary the planar update kernel aligns its tiles to (power of two, 16..4096)
  *   "direct_variant"     kernel variant of the direct host-tier mode
- *   "stream_split"       copies a staged tiled transfer is issued as
- *   "adamw_flags", "norm_flags"  cache-policy bits of the bf16 streams
  *   "time_kernels"       see mlpo_kernel_times
  */
 int mlpo_set_option(const char* key, int64_t value);

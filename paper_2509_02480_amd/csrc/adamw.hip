@@ -162,7 +162,7 @@ struct Regs {
     f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
     u32x2 G[UNROLL];
 
-    __device__ __forceinline__ void load(const Tile& t, uint32_t tid, uint32_t flags) {
+    __device__ __forceinline__ void load(const Tile& t, uint32_t tid) {
         if (t.cnt == BLOCK * UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -170,7 +170,7 @@ struct Regs {
                 P[u] = ld<NT>(t.p + i);
                 M[u] = ld<NT>(t.m + i);
                 V[u] = ld<NT>(t.v + i);
-                G[u] = (flags & 1u) ? ld<false>(t.g + i) : ld<NT>(t.g + i);
+                G[u] = ld<NT>(t.g + i);
             }
         } else {
 #pragma unroll
@@ -186,8 +186,7 @@ struct Regs {
         }
     }
 
-    __device__ __forceinline__ void update_store(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c,
-                                                 uint32_t flags) {
+    __device__ __forceinline__ void update_store(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
         if (t.cnt == BLOCK * UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -196,7 +195,7 @@ struct Regs {
                 st<NT>(t.p + i, P[u]);
                 st<NT>(t.m + i, M[u]);
                 st<NT>(t.v + i, V[u]);
-                if (flags & 2u) st<false>(t.h + i, H); else st<NT>(t.h + i, H);
+                st<NT>(t.h + i, H);
             }
         } else {
 #pragma unroll
@@ -219,8 +218,7 @@ struct Regs {
 // current tile is computed and stored.
 template <int BLOCK, int UNROLL, bool NT, bool PERSIST>
 __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const AdamwConsts c,
-                                                         const mlpo_step_scalars* __restrict__ sc,
-                                                         const uint32_t flags) {
+                                                         const mlpo_step_scalars* __restrict__ sc) {
     float gmul = 1.0f;
     if (sc != nullptr) {
         if (sc->found_inf != 0u) return;  // skipped step: nothing is read or written
@@ -242,12 +240,12 @@ __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const
         s = lo;
         const Tile t = locate<T4>(b, tile, s);
         Regs<BLOCK, UNROLL, NT> r;
-        r.load(t, tid, flags);
-        r.update_store(t, tid, gmul, c, flags);
+        r.load(t, tid);
+        r.update_store(t, tid, gmul, c);
     } else {
         Tile cur = locate<T4>(b, tile, s);
         Regs<BLOCK, UNROLL, NT> rc;
-        rc.load(cur, tid, flags);
+        rc.load(cur, tid);
         for (;;) {
             const uint32_t next = tile + gridDim.x;
             const bool more = next < total && next > tile;
@@ -255,9 +253,9 @@ __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const
             Regs<BLOCK, UNROLL, NT> rn;
             if (more) {
                 nxt = locate<T4>(b, next, s);
-                rn.load(nxt, tid, flags);
+                rn.load(nxt, tid);
             }
-            rc.update_store(cur, tid, gmul, c, flags);
+            rc.update_store(cur, tid, gmul, c);
             if (!more) break;
             cur = nxt;
             rc = rn;
@@ -307,13 +305,11 @@ struct Variant {
     bool persist;
 };
 constexpr Variant kVariants[] = {
-    {256, 2, true, false},  {256, 1, true, false},  {256, 4, true, false}, {512, 1, true, false},
-    {512, 2, true, false},  {1024, 1, true, false}, {256, 2, false, false}, {256, 1, false, false},
-    {256, 1, true, true},   {256, 2, true, true},   {512, 1, true, true},  {512, 2, true, true},
-    {1024, 1, true, true},  {256, 2, false, true},
+    {256, 2, true, false},  {256, 1, true, false}, {256, 4, true, false}, {512, 1, true, false},
+    {1024, 1, true, false}, {256, 1, false, false}, {256, 1, true, true}, {256, 2, true, true},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kPersistVariant = 8;  // 256 threads, one group of four per lane, grid-stride with prefetch
+constexpr int kPersistVariant = 6;  // 256 threads, one group of four per lane, grid-stride with prefetch
 
 // Tuning value -1 (the default) picks by size: large tiles once there is enough work to fill the chip many times
 // over, small ones below that so that a short launch still spreads over all compute units.
@@ -329,10 +325,9 @@ void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlp
     hipEvent_t t0, t1;
     if (timing_enabled() && timing_acquire(kTimedUpdate, &t0, &t1))
         hipExtLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, t0, t1, 0,
-                              b, c, sc, (uint32_t)tuning().adamw_flags);
+                              b, c, sc);
     else
-        hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc,
-                           (uint32_t)tuning().adamw_flags);
+        hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc);
 }
 
 int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
@@ -355,16 +350,10 @@ int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo
         case 1: launch_v4<256, 1, true, false>(b, grid, c, sc, st); break;
         case 2: launch_v4<256, 4, true, false>(b, grid, c, sc, st); break;
         case 3: launch_v4<512, 1, true, false>(b, grid, c, sc, st); break;
-        case 4: launch_v4<512, 2, true, false>(b, grid, c, sc, st); break;
-        case 5: launch_v4<1024, 1, true, false>(b, grid, c, sc, st); break;
-        case 6: launch_v4<256, 2, false, false>(b, grid, c, sc, st); break;
-        case 7: launch_v4<256, 1, false, false>(b, grid, c, sc, st); break;
-        case 8: launch_v4<256, 1, true, true>(b, grid, c, sc, st); break;
-        case 9: launch_v4<256, 2, true, true>(b, grid, c, sc, st); break;
-        case 10: launch_v4<512, 1, true, true>(b, grid, c, sc, st); break;
-        case 11: launch_v4<512, 2, true, true>(b, grid, c, sc, st); break;
-        case 12: launch_v4<1024, 1, true, true>(b, grid, c, sc, st); break;
-        default: launch_v4<256, 2, false, true>(b, grid, c, sc, st); break;
+        case 4: launch_v4<1024, 1, true, false>(b, grid, c, sc, st); break;
+        case 5: launch_v4<256, 1, false, false>(b, grid, c, sc, st); break;
+        case 6: launch_v4<256, 1, true, true>(b, grid, c, sc, st); break;
+        default: launch_v4<256, 2, true, true>(b, grid, c, sc, st); break;
     }
     MLPO_HIP(hipGetLastError());
     return MLPO_OK;

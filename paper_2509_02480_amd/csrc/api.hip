@@ -25,9 +25,8 @@ int fail(int code, const char* fmt, ...) {
 
 // ---- tuning / device ------------------------------------------------------------
 Tuning& tuning() {
-    static Tuning t = {/*adamw_grid_per_cu=*/8, /*adamw_variant=*/-1, /*norm_grid_per_cu=*/8,
-                       /*adamw_align_bytes=*/256, /*stream_split=*/1,
-                       /*adamw_flags=*/0, /*norm_flags=*/0, /*direct_variant=*/8};
+    static Tuning t = {/*adamw_grid_per_cu=*/8, /*adamw_variant=*/-1, /*norm_grid_per_cu=*/4,
+                       /*adamw_align_bytes=*/256, /*direct_variant=*/6};
     return t;
 }
 
@@ -219,18 +218,6 @@ static int ensure_events_locked(EventCache& c, int n_slots) {
 
 static uint64_t round_up(uint64_t x, uint64_t to) { return (x + to - 1) / to * to; }
 
-// One logical transfer issued as `pieces` consecutive copies on the same stream.
-static int copy_split(void* dst, const void* src, size_t bytes, hipMemcpyKind kind, hipStream_t st, int pieces) {
-    if (pieces < 1) pieces = 1;
-    size_t each = (bytes / (size_t)pieces + 255) & ~(size_t)255;
-    size_t done = 0;
-    while (done < bytes) {
-        const size_t len = bytes - done < each ? bytes - done : each;
-        MLPO_HIP(hipMemcpyAsync(static_cast<char*>(dst) + done, static_cast<const char*>(src) + done, len, kind, st));
-        done += len;
-    }
-    return MLPO_OK;
-}
 
 // Floats one host-tier subgroup needs in a staging slot when moved in pieces of at most chunk_elems elements
 // (0 = whole): three arrays, each rounded so that the arrays of a slot keep their alignment (planar) or to whole
@@ -267,8 +254,7 @@ static int fetch_piece(const Piece& pc, hipStream_t st, SgView* view) {
         const uint64_t T = (uint64_t)s.tile_elems;
         const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
         const float* src = s.p + (pc.off / T) * 3u * T;
-        const int rc = copy_split(pc.slot, src, bytes, hipMemcpyHostToDevice, st, tuning().stream_split);
-        if (rc != MLPO_OK) return rc;
+        MLPO_HIP(hipMemcpyAsync(pc.slot, src, bytes, hipMemcpyHostToDevice, st));
         *view = SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, s.g + pc.off, s.p16 + pc.off, pc.len, s.tile_elems};
     } else {
         const size_t bytes = (size_t)pc.len * sizeof(float);
@@ -302,7 +288,8 @@ static int flush_piece(const Piece& pc, hipStream_t st) {
         const uint64_t T = (uint64_t)s.tile_elems;
         const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
         float* dst = s.p + (pc.off / T) * 3u * T;
-        return copy_split(dst, pc.slot, bytes, hipMemcpyDeviceToHost, st, tuning().stream_split);
+        MLPO_HIP(hipMemcpyAsync(dst, pc.slot, bytes, hipMemcpyDeviceToHost, st));
+        return MLPO_OK;
     }
     const size_t bytes = (size_t)pc.len * sizeof(float);
     const uint64_t arr = round_up(pc.len, 64);
@@ -357,10 +344,7 @@ int mlpo_set_option(const char* key, int64_t value) {
     else if (strcmp(key, "adamw_variant") == 0) tuning().adamw_variant = (int)value;
     else if (strcmp(key, "norm_grid_per_cu") == 0) tuning().norm_grid_per_cu = (int)value;
     else if (strcmp(key, "adamw_align_bytes") == 0) tuning().adamw_align_bytes = (int)value;
-    else if (strcmp(key, "stream_split") == 0) tuning().stream_split = (int)value;
 
-    else if (strcmp(key, "adamw_flags") == 0) tuning().adamw_flags = (int)value;
-    else if (strcmp(key, "norm_flags") == 0) tuning().norm_flags = (int)value;
     else if (strcmp(key, "direct_variant") == 0) tuning().direct_variant = (int)value;
     else if (strcmp(key, "time_kernels") == 0) timing_set(value != 0);
     else return fail(MLPO_EINVAL, "unknown option '%s'", key);

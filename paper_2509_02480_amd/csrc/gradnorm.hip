@@ -57,7 +57,7 @@ __device__ __forceinline__ void accum_half(uint16_t h, float inv_scale, double& 
 }
 
 __global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, const float inv_scale,
-                                                            Workspace* __restrict__ ws, const uint32_t flags) {
+                                                            Workspace* __restrict__ ws) {
     const uint32_t total = b.tile_begin[b.n_sg];
     const uint32_t tid = threadIdx.x;
     double acc = 0.0;
@@ -74,8 +74,7 @@ __global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, c
         if (n_body >= base + kTile) {
             u32x4 w[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                w[u] = (flags & 1u) ? q[u * kBlock + tid] : __builtin_nontemporal_load(q + u * kBlock + tid);
+            for (int u = 0; u < kUnroll; ++u) w[u] = __builtin_nontemporal_load(q + u * kBlock + tid);
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 accum_word(w[u].x, inv_scale, acc, bad);
@@ -179,17 +178,15 @@ int flush(const NormBatch& b, bool first, bool last, float inv_scale, float max_
         const int cus = num_cus();
         if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
         int per_cu = tuning().norm_grid_per_cu;
-        if (per_cu <= 0) per_cu = 8;
+        if (per_cu <= 0) per_cu = 4;
         uint64_t cap = (uint64_t)cus * (uint64_t)per_cu;
         if (cap > (uint64_t)kMaxGrid) cap = kMaxGrid;
         grid = total < cap ? total : (uint32_t)cap;
         hipEvent_t t0, t1;
         if (timing_enabled() && timing_acquire(kTimedGradPass, &t0, &t1))
-            hipExtLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, b, inv_scale, ws,
-                                  (uint32_t)tuning().norm_flags);
+            hipExtLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, b, inv_scale, ws);
         else
-            hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws,
-                               (uint32_t)tuning().norm_flags);
+            hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws);
         MLPO_HIP(hipGetLastError());
     }
     hipLaunchKernelGGL(grad_finish_kernel, dim3(1), dim3(kBlock), 0, st, ws, (int)grid, first ? 1 : 0, last ? 1 : 0,

@@ -22,9 +22,6 @@ struct Tuning {
     int adamw_variant;
     int norm_grid_per_cu;
     int adamw_align_bytes;
-    int stream_split;
-    int adamw_flags;  // bit 0: cacheable loads of g; bit 1: cacheable stores of p16
-    int norm_flags;   // bit 0: cacheable loads of g in the gradient pass
     int direct_variant;
 };
 Tuning& tuning();
