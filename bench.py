@@ -322,11 +322,30 @@ def streamed_bench(args, torch, B, W, np):
     del saved_m, ref, ref2
 
     applied = 0
+    host_g_table = None
     for n_slots, chunk in args.stream_variants:
         cache = None
+        run_table = table
         if n_slots == "d":      # direct mode: chunk holds the number of persistent workgroups
             stg = None
             cfg = B.direct_cfg(h2d, cmp_, chunk)
+        elif n_slots == "dg":   # direct mode with the gradients of host-tier subgroups in pinned host memory too
+            stg = None
+            cfg = B.direct_cfg(h2d, cmp_, chunk)
+            if host_g_table is None:
+                host_g_keep = []
+                sg2 = []
+                for k in range(wl.n_sub):
+                    gk = g_flat[k * M:(k + 1) * M]
+                    if wl.tier(k) == 1:
+                        gk = torch.empty(M, dtype=torch.int16, pin_memory=True)
+                        gk.copy_(g_flat[k * M:(k + 1) * M])
+                        host_g_keep.append(gk)
+                    sg2.append(B.tiled_subgroup(keep[k], gk, p16_flat[k * M:(k + 1) * M], n=M, tier=wl.tier(k),
+                                                tile_elems=T))
+                host_g_table = B.SubgroupTable(sg2)
+                torch.cuda.synchronize()
+            run_table = host_g_table
         elif n_slots == "c":    # staged mode with slots that keep their subgroups; chunk holds the number of slots
             cache = B.SlotCacheC()
             need = B.mlpo_stream_staging_bytes(table, chunk, 0)
@@ -343,10 +362,10 @@ def streamed_bench(args, torch, B, W, np):
                 B.mlpo_set_option("time_kernels", 1)
                 fetches_before = cache.fetches if cache is not None else 0
             t = time.perf_counter()
-            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
+            B.mlpo_grad_unscale_norm(run_table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
             # with a slot cache the processing order alternates (Section 3.2 "Cache-Friendly Ordering")
             order = list(range(wl.n_sub))[::-1] if (cache is not None and s % 2 == 1) else None
-            ok = B.mlpo_stream_update(table, order, hp, applied + 1, scal, cfg)
+            ok = B.mlpo_stream_update(run_table, order, hp, applied + 1, scal, cfg)
             cmp_.synchronize()
             torch.cuda.synchronize()
             dt = time.perf_counter() - t
@@ -361,7 +380,7 @@ def streamed_bench(args, torch, B, W, np):
         gbs = 12 * n_host_params / mean / 1e9
         # the paper's effective I/O throughput (Section 4.3): 2 * bytes / (read time + write time), averaged over
         # the transfer units; in direct mode reading and writing both last as long as the kernel that does them
-        if n_slots == "d":
+        if n_slots in ("d", "dg"):
             eff = [2 * 12 * n_host_params / (2 * k * 1e-3) / 1e9 for k in kern_ms if k > 1.0]
         elif n_slots == "c":
             eff = []                # transfers are not paired one to one when flushes are lazy
@@ -379,6 +398,8 @@ def streamed_bench(args, torch, B, W, np):
                     "of": wl.n_host}
         elif n_slots == "d":
             desc = {"mode": "direct", "direct_blocks": chunk}
+        elif n_slots == "dg":
+            desc = {"mode": "direct, gradients on the host too (16 B/param in, 12 out)", "direct_blocks": chunk}
         else:
             desc = {"mode": "staged", "n_slots": n_slots, "chunk_elems": chunk}
         rec = {**desc, "steps": len(times), "ms_per_step": round(mean * 1e3, 2),
@@ -387,6 +408,9 @@ def streamed_bench(args, torch, B, W, np):
             rec.update({"pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
                         "frac_of_one_way_memcpy": round(gbs / memcpy_peak, 4),
                         "effective_io_GBs_paper_formula": eff_io})
+            if n_slots == "dg":   # the gradients cross the link twice (gradient pass and update): 16 B in, 12 B out
+                rec.update({"pcie_in_GBs": round(16 * n_host_params / mean / 1e9, 2),
+                            "pcie_out_GBs": round(12 * n_host_params / mean / 1e9, 2)})
         else:
             # fewer subgroups cross the link: the useful figure is the step time; the link rate is what was moved
             moved = rec["subgroup_transfers_per_step_per_dir"] / wl.n_host
@@ -404,7 +428,7 @@ def parse_variants(text):
     res = []
     for part in text.split(","):
         a, _, b = part.partition(":")
-        res.append((a if a in ("d", "c") else int(a), int(b or 0)))
+        res.append((a if a in ("d", "c", "dg") else int(a), int(b or 0)))
     return res
 
 
@@ -418,9 +442,10 @@ def main():
                     help="fp32 state layout(s) to time; the first is the headline figure")
     ap.add_argument("--tile", type=int, default=8192, help="tile_elems of the tiled layout")
     ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
-    ap.add_argument("--stream-variants", default="3:0,3:16777216,4:16777216,d:64,d:128,c:4,c:8",
-                    help="comma list of n_slots:chunk_elems (staged mode), d:blocks (direct mode) or c:n_slots "
-                         "(staged mode with slots that keep their subgroups and alternating order)")
+    ap.add_argument("--stream-variants", default="3:0,3:16777216,4:16777216,d:64,d:128,dg:64,c:4,c:8",
+                    help="comma list of n_slots:chunk_elems (staged mode), d:blocks (direct mode), dg:blocks (direct "
+                         "mode, gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep "
+                         "their subgroups and alternating order)")
     ap.add_argument("--stream-warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-subgroups", type=int, default=8)

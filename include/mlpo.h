@@ -44,8 +44,12 @@ typedef struct {
 
 /* One subgroup (Section 2 "Sharded Model and Optimizer States Into Subgroups"): n elements of fp32 master parameters
  * p, momentum m, variance v, the bf16 gradients g that drive the update and the bf16 working copy p16 that receives
- * the downcast parameters.  g and p16 are always device memory and always plain arrays of n elements.  tier says
- * where p, m, v live: MLPO_TIER_HBM (device) or MLPO_TIER_HOST (pinned host).
+ * the downcast parameters.  g and p16 are plain arrays of n elements; p16 is always device memory, g normally too.
+ * tier says where p, m, v live: MLPO_TIER_HBM (device) or MLPO_TIER_HOST (pinned host).
+ * Host-side gradients (the paper keeps the half-precision gradients in a host accumulation buffer, Section 3.2
+ * "Delayed In-place Mixed-Precision Gradient Conversion"): g of a host-tier subgroup may also be pinned host memory
+ * when the subgroup is used with mlpo_grad_unscale_norm and with mlpo_stream_update in direct mode only; both kernels
+ * then read the gradients over the link (2 bytes per element each) and upcast them in registers as always.
  *
  * Layout of the fp32 state, chosen by tile_elems:
  *   0      planar: p, m, v are three independent arrays of n floats.

@@ -290,3 +290,40 @@ def test_slot_cache_survives_flush_and_skip(oracle, scratch, streams):
     streams[1].synchronize()
     for k in range(4):
         assert_state_parity(ds.fetch(k), host[k], f"cache2 sg={k}")
+
+
+def test_direct_mode_with_gradients_on_the_host(oracle, scratch, streams):
+    """The paper's placement of the half-precision gradients (a pinned host buffer, converted on the fly during the
+    update, Section 3.2): host-tier subgroups whose g is pinned host memory, read over the link by the gradient pass
+    and by the direct-mode kernel."""
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("hostg", n_sub=5, sub_elems=80_003, n_host=3, loss_scale=128.0, max_norm=0.02, steps=3)
+    host = W.host_subgroups(wl, warm=True)
+    tiers = [wl.tier(k) for k in range(wl.n_sub)]
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=2048)
+    pinned_g, descs = [], []
+    for k, e in enumerate(ds.t):
+        g = e["g"]
+        if tiers[k] == 1:
+            g = torch.empty(ds.sizes[k], dtype=torch.int16, pin_memory=True)
+            g.copy_(e["g"])
+            pinned_g.append(g)
+        e["g_used"] = g
+        descs.append(B.tiled_subgroup(e["state"], g, e["p16"], n=ds.sizes[k], tier=tiers[k], tile_elems=2048))
+    table = B.SubgroupTable(descs)
+    cfg = B.direct_cfg(streams[0], streams[1], 32)
+    for s in range(wl.steps):
+        if s > 0:
+            for k, sg in enumerate(host):
+                W.fill_grads(wl, k, s, sg["g"])
+                ds.t[k]["g_used"].copy_(torch.from_numpy(sg["g"].view(np.int16)))
+        torch.cuda.synchronize()
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm)
+        B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                 streams[1])
+        assert B.mlpo_stream_update(table, None, ghp, s + 1, scratch.scalars, cfg) and ok_o
+        streams[1].synchronize()
+        sc = scratch.read()
+        assert abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5 and sc["gmul"] == gmul_o
+    for k in range(wl.n_sub):
+        assert_state_parity(ds.fetch(k), host[k], f"host-side gradients sg={k}")
