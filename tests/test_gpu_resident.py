@@ -305,3 +305,89 @@ def test_kernel_timing_records_every_launch(scratch):
         B.mlpo_set_option("time_kernels", 0)
     B.mlpo_adamw_step(ds.table, B.HParams(), 6, None, st)
     assert B.mlpo_kernel_times(0) == []                           # nothing recorded when off
+
+
+def test_every_finite_gradient_pattern(oracle, scratch):
+    # all 65 280 finite bf16 gradient patterns (every exponent, denormals, both zeros) against eight different states
+    ohp, ghp = hp_pair(oracle)
+    pats = np.array([b for b in range(65536) if (b & 0x7F80) != 0x7F80], dtype=np.uint16)
+    rng = np.random.default_rng(5)
+    reps = 8
+    n = pats.size * reps
+    host = [{"p": (rng.standard_normal(n) * 0.02).astype(np.float32),
+             "m": (rng.standard_normal(n) * 3e-4).astype(np.float32),
+             "v": ((rng.standard_normal(n) * 1e-3) ** 2).astype(np.float32),
+             "g": np.tile(pats, reps), "p16": np.zeros(n, np.uint16)}]
+    host[0]["m"][:pats.size] = 0
+    host[0]["v"][:pats.size] = 0
+    for tile in (0, B.TILE_DEFAULT):
+        cur = [{k: a.copy() for k, a in host[0].items()}]
+        ds = DeviceSubgroups(cur, tile=tile)
+        oracle.adamw_f32(cur[0]["p"], cur[0]["m"], cur[0]["v"], cur[0]["g"], cur[0]["p16"], ohp, 3, 0.5)
+        half = torch.tensor([0.0, 1.0, 0.5, 0.0], dtype=torch.float32, device=dev())
+        half[3:4].view(torch.int32).zero_()
+        B.mlpo_adamw_step(ds.table, ghp, 3, half, torch.cuda.current_stream())      # gmul = 0.5 from a scalar record
+        got = ds.fetch(0)
+        for key in ("p", "m", "v"):
+            same = got[key].view(np.uint32) == cur[0][key].view(np.uint32)
+            both_nan = np.isnan(got[key]) & np.isnan(cur[0][key])
+            assert np.all(same | both_nan), f"tile={tile} {key}: {(~(same | both_nan)).sum()} words differ"
+        assert np.array_equal(got["p16"], cur[0]["p16"])
+
+
+def test_subgroup_longer_than_32_bit_indices(oracle, scratch):
+    # one tiled subgroup of 2^32 + 77 777 elements (69 GB of buffers): windows around the 2^31 and 2^32 element
+    # marks and at both ends are checked; inputs are drawn on the device and the windows copied back for the oracle
+    free, _ = torch.cuda.mem_get_info()
+    n = (1 << 32) + 77_777
+    T = B.TILE_DEFAULT
+    per = B.mlpo_state_floats(n, T)
+    if free < 4 * per + 4 * n + (8 << 30):
+        pytest.skip("not enough free device memory for a 2^32-element subgroup")
+    d = dev()
+    gen = torch.Generator(device=d)
+    gen.manual_seed(1234)
+    state = torch.empty(per, dtype=torch.float32, device=d)
+    chunk = 1 << 28
+    for lo in range(0, per, chunk):
+        hi = min(per, lo + chunk)
+        state[lo:hi].normal_(0.0, 0.02, generator=gen)
+    sv = state.view(-1, 3, T)
+    sv[:, 1, :].mul_(0.015)            # momentum ~ N(0, 3e-4)
+    sv[:, 2, :].mul_(0.05).square_()   # variance ~ N(0, 1e-3)^2
+    g = torch.empty(n, dtype=torch.bfloat16, device=d)
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        g[lo:hi].normal_(0.0, 1e-3, generator=gen)
+    g = g.view(torch.int16)
+    p16 = torch.zeros(n, dtype=torch.int16, device=d)
+    table = B.SubgroupTable([B.tiled_subgroup(state, g, p16, n=n, tile_elems=T)])
+    W_ = 50_001
+    starts = [0, (1 << 31) - 25_000, (1 << 32) - 25_000, n - W_]
+    ohp, ghp = hp_pair(oracle)
+
+    def window(lo):
+        i = torch.arange(lo, lo + W_, dtype=torch.int64, device=d)
+        phys = (i // T) * (3 * T) + i % T
+        return {"p": state[phys].cpu().numpy(), "m": state[phys + T].cpu().numpy(), "v": state[phys + 2 * T].cpu().numpy(),
+                "g": g[lo:lo + W_].cpu().numpy().view(np.uint16).copy(),
+                "p16": p16[lo:lo + W_].cpu().numpy().view(np.uint16).copy()}
+
+    want = [window(lo) for lo in starts]
+    B.mlpo_grad_unscale_norm(table, 1.0, 1.0, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                             torch.cuda.current_stream())
+    B.mlpo_adamw_step(table, ghp, 4, scratch.scalars, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    sc = scratch.read()
+    assert sc["found_inf"] == 0
+    # norm of n draws of N(0, 1e-3) rounded to bf16: 1e-3 * sqrt(n) within a fraction of a percent; clip is active
+    assert abs(float(sc["norm"]) / (1e-3 * np.sqrt(n)) - 1) < 5e-3
+    assert sc["clip_coef"] == np.float32(1.0) / (sc["norm"] + np.float32(1e-6)) and sc["gmul"] == sc["clip_coef"]
+    for lo, w in zip(starts, want):
+        oracle.adamw_f32(w["p"], w["m"], w["v"], w["g"], w["p16"], ohp, 4, float(sc["gmul"]))
+        got = window(lo)
+        for key in ("p", "m", "v"):
+            assert np.array_equal(got[key].view(np.uint32), w[key].view(np.uint32)), (lo, key)
+        assert np.array_equal(got["p16"], w["p16"]), lo
+    del state, g, p16
+    torch.cuda.empty_cache()
