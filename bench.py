@@ -442,13 +442,13 @@ def main():
                     help="fp32 state layout(s) to time; the first is the headline figure")
     ap.add_argument("--tile", type=int, default=8192, help="tile_elems of the tiled layout")
     ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
-    ap.add_argument("--stream-variants", default="3:0,3:16777216,4:16777216,d:64,d:128,dg:64,c:4,c:8",
+    ap.add_argument("--stream-variants", default="2:16777216,3:0,3:16777216,4:16777216,d:64,d:128,dg:64,c:4,c:8",
                     help="comma list of n_slots:chunk_elems (staged mode), d:blocks (direct mode), dg:blocks (direct "
                          "mode, gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep "
                          "their subgroups and alternating order)")
-    ap.add_argument("--stream-warmup", type=int, default=1)
+    ap.add_argument("--stream-warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-subgroups", type=int, default=8)
+    ap.add_argument("--cpu-subgroups", type=int, default=9)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--option", action="append", default=[], help="library tuning option key=value")
