@@ -457,7 +457,7 @@ def main():
     args = ap.parse_args()
     args.stream_variants = parse_variants(args.stream_variants)
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+        print("bench.py: the library runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
     import numpy as np

@@ -202,7 +202,7 @@ def max_rel_err(a: np.ndarray, b: np.ndarray) -> float:
 
 
 def assert_state_parity(got: dict, want: dict, label="", tol=1e-6):
-    """The bars of the benchmark spec: fp32 state within 1e-6 max relative error, bf16 copy bit-exact.  Because both sides
+    """The parity bars: fp32 state within 1e-6 max relative error, bf16 copy bit-exact.  Because both sides
     round every operation identically the fp32 state is expected to be bit-identical; the count of differing words is
     reported in the failure text."""
     for key in ("p", "m", "v"):

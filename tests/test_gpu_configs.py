@@ -8,7 +8,7 @@ relative error 1e-6, bf16 copy and flag bit-exact, norm 1e-5.
 
 Config 3 runs at full size.  Configs 4 and 5 run with one fifth of their subgroups (same subgroup size, same tier
 fractions).  With MLPO_FULL_SIZE=1 config 4 runs whole (84 GB of fp32 state, 43 GB of it pinned) and config 5 with
-half of its subgroups (13 host-tier subgroups = 39 GB pinned): the GPU machines pin at most about 70 GB of host memory,
+half of its subgroups (13 host-tier subgroups = 39 GB pinned): the test machines pin at most about 70 GB of host memory,
 less than the 75 GB the whole of config 5 needs."""
 import os
 import time
