@@ -77,6 +77,17 @@ typedef struct {
 /* Floats in the state buffer of a tiled subgroup: ceil(n / tile_elems) * 3 * tile_elems (3 * n if tile_elems is 0). */
 uint64_t mlpo_state_floats(uint64_t n, int32_t tile_elems);
 
+/*
+ * Conversion between the two layouts (for state that arrives planar, e.g. from a checkpoint, or has to leave that
+ * way).  mlpo_state_pack writes the tiled buffer `state` (mlpo_state_floats(n, tile_elems) floats; the unused tail of
+ * the last tile is set to zero) from three arrays of n floats; mlpo_state_unpack does the reverse.  All pointers must
+ * be addressable by the device (device memory or pinned host memory) and 4-byte aligned; source and destination must
+ * not overlap.  One kernel on `stream`.  Errors: MLPO_EINVAL, MLPO_EHIP.
+ */
+int mlpo_state_pack(const float* p, const float* m, const float* v, uint64_t n, int32_t tile_elems, float* state,
+                    void* stream);
+int mlpo_state_unpack(const float* state, uint64_t n, int32_t tile_elems, float* p, float* m, float* v, void* stream);
+
 /* The four scalars that link the gradient pass to the update, kept in device memory so that no host round trip is
  * needed between the two (16 bytes, 16-byte aligned). */
 typedef struct {

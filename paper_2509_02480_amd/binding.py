@@ -21,7 +21,8 @@ MAX_SLOTS = 64
 
 TILE_DEFAULT = 8192
 
-EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_norm_workspace_bytes",
+EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_state_pack", "mlpo_state_unpack",
+           "mlpo_norm_workspace_bytes",
            "mlpo_grad_unscale_norm",
            "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers",
            "mlpo_update_bandwidth", "mlpo_set_option",
@@ -100,6 +101,11 @@ def lib():
         L.mlpo_version.argtypes = []
         L.mlpo_state_floats.restype = C.c_uint64
         L.mlpo_state_floats.argtypes = [C.c_uint64, C.c_int32]
+        L.mlpo_state_pack.restype = C.c_int
+        L.mlpo_state_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.mlpo_state_unpack.restype = C.c_int
+        L.mlpo_state_unpack.argtypes = [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]
         L.mlpo_norm_workspace_bytes.restype = C.c_size_t
         L.mlpo_norm_workspace_bytes.argtypes = []
         L.mlpo_grad_unscale_norm.restype = C.c_int
@@ -168,6 +174,14 @@ def tiled_subgroup(state, g, p16, n: Optional[int] = None, tier: int = TIER_HBM,
 
 def mlpo_state_floats(n: int, tile_elems: int) -> int:
     return int(lib().mlpo_state_floats(n, tile_elems))
+
+
+def mlpo_state_pack(p, m, v, n: int, tile_elems: int, state, stream=None) -> None:
+    _check(lib().mlpo_state_pack(_ptr(p), _ptr(m), _ptr(v), n, tile_elems, _ptr(state), _stream(stream)))
+
+
+def mlpo_state_unpack(state, n: int, tile_elems: int, p, m, v, stream=None) -> None:
+    _check(lib().mlpo_state_unpack(_ptr(state), n, tile_elems, _ptr(p), _ptr(m), _ptr(v), _stream(stream)))
 
 
 class SubgroupTable:

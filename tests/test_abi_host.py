@@ -152,6 +152,14 @@ def test_staging_size_formula():
     assert B.mlpo_state_floats(0, 2048) == 0 and B.mlpo_state_floats(2048, 2048) == 3 * 2048
 
 
+def test_pack_argument_errors():
+    expect(B.MLPO_EINVAL, B.mlpo_state_pack, FAKE, FAKE, FAKE, 10, 1000, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_state_pack, FAKE, FAKE, FAKE, 10, 0, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_state_pack, FAKE, 0, FAKE, 10, 1024, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_state_unpack, FAKE + 2, 10, 1024, FAKE, FAKE, FAKE)
+    B.mlpo_state_pack(0, 0, 0, 0, 1024, 0)          # nothing to do
+
+
 def test_options():
     B.mlpo_set_option("adamw_grid_per_cu", 8)
     expect(B.MLPO_EINVAL, B.mlpo_set_option, "no_such_option", 1)

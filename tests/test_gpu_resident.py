@@ -391,3 +391,30 @@ def test_subgroup_longer_than_32_bit_indices(oracle, scratch):
         assert np.array_equal(got["p16"], w["p16"]), lo
     del state, g, p16
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("n,T", [(0, 1024), (1, 1024), (1023, 1024), (1024, 1024), (5000, 2048), (100_001, 8192),
+                                 (3_000_001, 8192), (70_000, 16384)])
+def test_state_pack_and_unpack(n, T):
+    # layout conversion is data movement: compared bit for bit with the index definition written out in numpy
+    from gpu_util import pack_tiled
+    rng = np.random.default_rng(n)
+    src = [rng.standard_normal(n).astype(np.float32) for _ in range(3)]
+    dv = [torch.from_numpy(a).to(dev()) for a in src]
+    floats = B.mlpo_state_floats(n, T)
+    state = torch.full((max(floats, 1),), 7.0, dtype=torch.float32, device=dev())
+    st = torch.cuda.current_stream()
+    B.mlpo_state_pack(dv[0], dv[1], dv[2], n, T, state, st)
+    torch.cuda.synchronize()
+    want = pack_tiled(src[0], src[1], src[2], T)
+    assert np.array_equal(state.cpu().numpy()[:floats].view(np.uint32), want.view(np.uint32))
+    back = [torch.full((max(n, 1),), -1.0, dtype=torch.float32, device=dev()) for _ in range(3)]
+    B.mlpo_state_unpack(state, n, T, back[0], back[1], back[2], st)
+    torch.cuda.synchronize()
+    for a, bck in zip(src, back):
+        assert np.array_equal(bck.cpu().numpy()[:n].view(np.uint32), a.view(np.uint32))
+    if n:
+        pinned = torch.empty(floats, dtype=torch.float32, pin_memory=True)       # pinned host destination
+        B.mlpo_state_pack(dv[0], dv[1], dv[2], n, T, pinned, st)
+        torch.cuda.synchronize()
+        assert np.array_equal(pinned.numpy().view(np.uint32), want.view(np.uint32))
