@@ -1,4 +1,5 @@
-// C ABI of libmlpo: argument checking, per-step scalars, and the tiered fetch / update / flush pipeline.
+// C ABI of libmlpo: errors, tuning knobs, per-kernel timing, argument checking, per-step scalars and the entry points
+// of the resident path.  The tiered pipeline is in pipeline.hip.
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -129,9 +130,11 @@ AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step) {
 }
 
 // ---- subgroup checks ----------------------------------------------------------------
-static bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
-static int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, int allow_host) {
+uint64_t round_up(uint64_t x, uint64_t to) { return (x + to - 1) / to * to; }
+
+int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, int allow_host) {
     if (n_sg < 0) return fail(MLPO_EINVAL, "n_sg is negative");
     if (n_sg > 0 && sg == nullptr) return fail(MLPO_EINVAL, "subgroup array is NULL");
     for (int32_t i = 0; i < n_sg; ++i) {
@@ -162,169 +165,6 @@ static int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_
     return MLPO_OK;
 }
 
-// ---- pipeline events --------------------------------------------------------------------
-struct SlotEvents {
-    hipEvent_t h2d_done, upd_done, d2h_done;
-};
-struct EventCache {
-    std::mutex mu;
-    int device = -1;
-    std::vector<SlotEvents> slots;
-    hipEvent_t fence = nullptr;   // orders streams at the start and end of a call
-    hipEvent_t fence2 = nullptr;
-    hipStream_t copy_in = nullptr;   // the library's own copy streams, used when the caller passes none
-    hipStream_t copy_out = nullptr;
-};
-static EventCache& events() {
-    static EventCache c;
-    return c;
-}
-
-static int release_events_locked(EventCache& c) {
-    for (auto& s : c.slots) {
-        (void)hipEventDestroy(s.h2d_done);
-        (void)hipEventDestroy(s.upd_done);
-        (void)hipEventDestroy(s.d2h_done);
-    }
-    c.slots.clear();
-    if (c.fence) (void)hipEventDestroy(c.fence);
-    if (c.fence2) (void)hipEventDestroy(c.fence2);
-    c.fence = c.fence2 = nullptr;
-    if (c.copy_in) (void)hipStreamDestroy(c.copy_in);
-    if (c.copy_out) (void)hipStreamDestroy(c.copy_out);
-    c.copy_in = c.copy_out = nullptr;
-    c.device = -1;
-    return MLPO_OK;
-}
-
-static int ensure_events_locked(EventCache& c, int n_slots) {
-    int dev = 0;
-    MLPO_HIP(hipGetDevice(&dev));
-    if (c.device != dev) release_events_locked(c);
-    c.device = dev;
-    if (c.fence == nullptr) MLPO_HIP(hipEventCreateWithFlags(&c.fence, hipEventDisableTiming));
-    if (c.fence2 == nullptr) MLPO_HIP(hipEventCreateWithFlags(&c.fence2, hipEventDisableTiming));
-    if (c.copy_in == nullptr) MLPO_HIP(hipStreamCreateWithFlags(&c.copy_in, hipStreamNonBlocking));
-    if (c.copy_out == nullptr) MLPO_HIP(hipStreamCreateWithFlags(&c.copy_out, hipStreamNonBlocking));
-    while ((int)c.slots.size() < n_slots) {
-        SlotEvents s;
-        MLPO_HIP(hipEventCreateWithFlags(&s.h2d_done, hipEventDisableTiming));
-        MLPO_HIP(hipEventCreateWithFlags(&s.upd_done, hipEventDisableTiming));
-        MLPO_HIP(hipEventCreateWithFlags(&s.d2h_done, hipEventDisableTiming));
-        c.slots.push_back(s);
-    }
-    return MLPO_OK;
-}
-
-static uint64_t round_up(uint64_t x, uint64_t to) { return (x + to - 1) / to * to; }
-
-
-// Floats one host-tier subgroup needs in a staging slot when moved in pieces of at most chunk_elems elements
-// (0 = whole): three arrays, each rounded so that the arrays of a slot keep their alignment (planar) or to whole
-// layout tiles (tiled).
-static uint64_t slot_floats_of(const mlpo_subgroup& s, uint64_t chunk_elems) {
-    uint64_t len = s.n;
-    if (chunk_elems != 0 && chunk_elems < len) len = chunk_elems;
-    return 3u * round_up(len, s.tile_elems > 0 ? (uint64_t)s.tile_elems : 64u);
-}
-
-static uint64_t slot_floats_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems) {
-    uint64_t mx = 0;
-    for (int32_t i = 0; i < n_sg; ++i)
-        if (sg[i].tier == MLPO_TIER_HOST) {
-            const uint64_t f = slot_floats_of(sg[i], chunk_elems);
-            if (f > mx) mx = f;
-        }
-    return mx;
-}
-
-
-// One piece (a whole subgroup or a chunk of one) of a host-tier subgroup and the staging slot it occupies.
-struct Piece {
-    const mlpo_subgroup* s;
-    uint64_t off, len;
-    float* slot;
-};
-
-// Host-to-device transfer of a piece into its slot; returns the kernel's view of the slot.
-static int fetch_piece(const Piece& pc, hipStream_t st, SgView* view) {
-    const mlpo_subgroup& s = *pc.s;
-    if (s.tile_elems > 0) {
-        // whole layout tiles travel as one contiguous block: p, m, v of the same elements stay together
-        const uint64_t T = (uint64_t)s.tile_elems;
-        const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
-        const float* src = s.p + (pc.off / T) * 3u * T;
-        MLPO_HIP(hipMemcpyAsync(pc.slot, src, bytes, hipMemcpyHostToDevice, st));
-        *view = SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, s.g + pc.off, s.p16 + pc.off, pc.len, s.tile_elems};
-    } else {
-        const size_t bytes = (size_t)pc.len * sizeof(float);
-        const uint64_t arr = round_up(pc.len, 64);
-        float* sp = pc.slot;
-        float* sm = sp + arr;
-        float* sv = sm + arr;
-        MLPO_HIP(hipMemcpyAsync(sp, s.p + pc.off, bytes, hipMemcpyHostToDevice, st));
-        MLPO_HIP(hipMemcpyAsync(sm, s.m + pc.off, bytes, hipMemcpyHostToDevice, st));
-        MLPO_HIP(hipMemcpyAsync(sv, s.v + pc.off, bytes, hipMemcpyHostToDevice, st));
-        *view = SgView{sp, sm, sv, s.g + pc.off, s.p16 + pc.off, pc.len, 0};
-    }
-    return MLPO_OK;
-}
-
-// The view of a slot that already holds the piece.
-static SgView slot_view(const Piece& pc) {
-    const mlpo_subgroup& s = *pc.s;
-    if (s.tile_elems > 0) {
-        const uint64_t T = (uint64_t)s.tile_elems;
-        return SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, s.g + pc.off, s.p16 + pc.off, pc.len, s.tile_elems};
-    }
-    const uint64_t arr = round_up(pc.len, 64);
-    return SgView{pc.slot, pc.slot + arr, pc.slot + 2 * arr, s.g + pc.off, s.p16 + pc.off, pc.len, 0};
-}
-
-// Device-to-host transfer of a piece from its slot back to the host tier.
-static int flush_piece(const Piece& pc, hipStream_t st) {
-    const mlpo_subgroup& s = *pc.s;
-    if (s.tile_elems > 0) {
-        const uint64_t T = (uint64_t)s.tile_elems;
-        const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
-        float* dst = s.p + (pc.off / T) * 3u * T;
-        MLPO_HIP(hipMemcpyAsync(dst, pc.slot, bytes, hipMemcpyDeviceToHost, st));
-        return MLPO_OK;
-    }
-    const size_t bytes = (size_t)pc.len * sizeof(float);
-    const uint64_t arr = round_up(pc.len, 64);
-    MLPO_HIP(hipMemcpyAsync(s.p + pc.off, pc.slot, bytes, hipMemcpyDeviceToHost, st));
-    MLPO_HIP(hipMemcpyAsync(s.m + pc.off, pc.slot + arr, bytes, hipMemcpyDeviceToHost, st));
-    MLPO_HIP(hipMemcpyAsync(s.v + pc.off, pc.slot + 2 * arr, bytes, hipMemcpyDeviceToHost, st));
-    return MLPO_OK;
-}
-
-constexpr uint32_t kCacheMagic = 0x4D4C5043u;  // "MLPC"
-
-static void cache_reset(mlpo_slot_cache* c, int32_t n_slots) {
-    memset(c, 0, sizeof *c);
-    c->magic = kCacheMagic;
-    c->n_slots = n_slots;
-    for (int k = 0; k < MLPO_MAX_SLOTS; ++k) c->owner[k] = -1;
-}
-
-// Checks that a cache left by earlier calls still describes this subgroup table and this configuration.
-static int cache_check(mlpo_slot_cache* c, const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots) {
-    if (c->magic == 0) {
-        cache_reset(c, n_slots);
-        return MLPO_OK;
-    }
-    if (c->magic != kCacheMagic) return fail(MLPO_EINVAL, "slot cache is neither zero-initialised nor ours");
-    if (c->n_slots != n_slots) return fail(MLPO_EINVAL, "slot cache was built for %d slots, not %d", c->n_slots, n_slots);
-    for (int k = 0; k < n_slots; ++k) {
-        const int32_t o = c->owner[k];
-        if (o < 0) continue;
-        if (o >= n_sg || sg[o].p != c->owner_p[k] || sg[o].tier != MLPO_TIER_HOST)
-            return fail(MLPO_EINVAL, "slot %d holds subgroup %d of a different subgroup table", k, o);
-    }
-    return MLPO_OK;
-}
-
 }  // namespace mlpo
 
 using namespace mlpo;
@@ -351,46 +191,6 @@ int mlpo_set_option(const char* key, int64_t value) {
     return MLPO_OK;
 }
 
-int mlpo_stream_flush(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_stream_cfg* cfg) {
-    int rc = validate_subgroups(sg, n_sg, false, /*allow_host=*/1);
-    if (rc != MLPO_OK) return rc;
-    if (cfg == nullptr || cfg->cache == nullptr) return fail(MLPO_EINVAL, "cfg or its slot cache is NULL");
-    if (cfg->mode != MLPO_STREAM_STAGED || cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS)
-        return fail(MLPO_EINVAL, "not a staged configuration");
-    mlpo_slot_cache* cache = cfg->cache;
-    if (cache->magic == 0) return MLPO_OK;  // never used: nothing is held
-    rc = cache_check(cache, sg, n_sg, cfg->n_slots);
-    if (rc != MLPO_OK) return rc;
-    const uint64_t slot_floats = slot_floats_for(sg, n_sg, 0);
-    if (cfg->staging == nullptr || cfg->staging_bytes < slot_floats * 4u * (uint64_t)cfg->n_slots)
-        return fail(MLPO_ENOMEM, "staging does not match the configuration the cache was filled with");
-    EventCache& ec = events();
-    std::lock_guard<std::mutex> lk(ec.mu);
-    rc = ensure_events_locked(ec, cfg->n_slots);
-    if (rc != MLPO_OK) return rc;
-    hipStream_t s_cmp = static_cast<hipStream_t>(cfg->compute);
-    hipStream_t s_d2h = (cfg->h2d == nullptr && cfg->d2h == nullptr) ? ec.copy_out : static_cast<hipStream_t>(cfg->d2h);
-    float* staging = static_cast<float*>(cfg->staging);
-    bool any = false;
-    for (int k = 0; k < cfg->n_slots; ++k) {
-        if (cache->owner[k] < 0 || !cache->dirty[k]) continue;
-        const mlpo_subgroup& s = sg[cache->owner[k]];
-        SlotEvents& ev = ec.slots[(size_t)k];
-        MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
-        rc = flush_piece(Piece{&s, 0, s.n, staging + (uint64_t)k * slot_floats}, s_d2h);
-        if (rc != MLPO_OK) return rc;
-        MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
-        cache->dirty[k] = 0;
-        ++cache->flushes;
-        any = true;
-    }
-    if (any) {
-        MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
-        MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
-    }
-    return MLPO_OK;
-}
-
 int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count) {
     if (which < 0 || which > 3) return fail(MLPO_EINVAL, "which must be 0..3");
     if (count == nullptr || cap < 0 || (cap > 0 && ms == nullptr)) return fail(MLPO_EINVAL, "bad output arguments");
@@ -408,12 +208,6 @@ int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count) {
     t.rec[which].clear();
     *count = n;
     return MLPO_OK;
-}
-
-int mlpo_shutdown(void) {
-    EventCache& c = events();
-    std::lock_guard<std::mutex> lk(c.mu);
-    return release_events_locked(c);
 }
 
 int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scale, float max_norm, void* workspace,
@@ -447,242 +241,6 @@ int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hpar
 uint64_t mlpo_state_floats(uint64_t n, int32_t tile_elems) {
     if (tile_elems <= 0) return 3u * n;
     return round_up(n, (uint64_t)tile_elems) * 3u;
-}
-
-size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems) {
-    if (sg == nullptr || n_sg <= 0 || n_slots <= 0) return 0;
-    return (size_t)(slot_floats_for(sg, n_sg, chunk_elems) * 4u * (uint64_t)n_slots);
-}
-
-int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
-                       int64_t step, const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, int32_t* applied) {
-    int rc = validate_subgroups(sg, n_sg, false, /*allow_host=*/1);
-    if (rc != MLPO_OK) return rc;
-    rc = validate_hparams(hp, step);
-    if (rc != MLPO_OK) return rc;
-    if (scalars != nullptr && misaligned(scalars, 16)) return fail(MLPO_EINVAL, "scalars not 16-byte aligned");
-    if (cfg == nullptr) return fail(MLPO_EINVAL, "cfg is NULL");
-    if (cfg->reserved != 0) return fail(MLPO_EINVAL, "cfg reserved field is not 0");
-    if (cfg->mode != MLPO_STREAM_STAGED && cfg->mode != MLPO_STREAM_DIRECT)
-        return fail(MLPO_EINVAL, "unknown mode %d", cfg->mode);
-    const bool direct = cfg->mode == MLPO_STREAM_DIRECT;
-    if (direct && (cfg->direct_blocks < 0 || cfg->direct_blocks > 4096))
-        return fail(MLPO_EINVAL, "direct_blocks must be 0..4096 (got %d)", cfg->direct_blocks);
-    if (!direct && (cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS))
-        return fail(MLPO_EINVAL, "n_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->n_slots);
-    if (cfg->chunk_elems % 4 != 0) return fail(MLPO_EINVAL, "chunk_elems must be a multiple of 4");
-    if (order != nullptr) {
-        std::vector<char> seen((size_t)n_sg, 0);
-        for (int32_t i = 0; i < n_sg; ++i) {
-            if (order[i] < 0 || order[i] >= n_sg || seen[(size_t)order[i]])
-                return fail(MLPO_EINVAL, "order is not a permutation of 0..n_sg-1");
-            seen[(size_t)order[i]] = 1;
-        }
-    }
-    for (int32_t i = 0; i < n_sg; ++i)
-        if (sg[i].tier == MLPO_TIER_HOST && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
-            return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
-    const uint64_t slot_floats = direct ? 0 : slot_floats_for(sg, n_sg, cfg->chunk_elems);
-    const uint64_t need = direct ? 0 : slot_floats * 4u * (uint64_t)cfg->n_slots;
-    if (need > 0) {
-        if (cfg->staging == nullptr || misaligned(cfg->staging, 256))
-            return fail(MLPO_EINVAL, "staging is NULL or not 256-byte aligned");
-        if (cfg->staging_bytes < need)
-            return fail(MLPO_ENOMEM, "staging has %zu bytes, %llu needed", cfg->staging_bytes,
-                        (unsigned long long)need);
-    }
-    if (cfg->cache != nullptr) {
-        if (direct) return fail(MLPO_EINVAL, "a slot cache needs staged mode");
-        if (cfg->chunk_elems != 0) return fail(MLPO_EINVAL, "a slot cache needs whole-subgroup transfers (chunk_elems 0)");
-        rc = cache_check(cfg->cache, sg, n_sg, cfg->n_slots);
-        if (rc != MLPO_OK) return rc;
-    }
-    if (applied != nullptr) *applied = 1;
-    if (n_sg == 0) return MLPO_OK;
-
-    hipStream_t s_h2d = static_cast<hipStream_t>(cfg->h2d);
-    hipStream_t s_cmp = static_cast<hipStream_t>(cfg->compute);
-    hipStream_t s_d2h = static_cast<hipStream_t>(cfg->d2h);
-
-    // The transfers are issued from the host, so the skip decision has to be known here.
-    if (scalars != nullptr) {
-        mlpo_step_scalars h;
-        MLPO_HIP(hipMemcpyAsync(&h, scalars, sizeof h, hipMemcpyDeviceToHost, s_cmp));
-        MLPO_HIP(hipStreamSynchronize(s_cmp));
-        if (h.found_inf != 0u) {
-            if (applied != nullptr) *applied = 0;
-            return MLPO_OK;
-        }
-    }
-
-    const AdamwConsts c = make_consts(*hp, step);
-
-    // HBM-tier subgroups first: their kernel runs while the first fetches are in flight.
-    std::vector<SgView> resident;
-    std::vector<SgView> host_views;
-    std::vector<int32_t> host_ids;
-    for (int32_t k = 0; k < n_sg; ++k) {
-        const int32_t i = order ? order[k] : k;
-        if (sg[i].n == 0) continue;
-        if (sg[i].tier == MLPO_TIER_HBM)
-            resident.push_back(SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems});
-        else {
-            host_ids.push_back(i);
-            host_views.push_back(SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems});
-        }
-    }
-
-    EventCache& ec = events();
-    std::lock_guard<std::mutex> lk(ec.mu);
-    if (cfg->h2d == nullptr && cfg->d2h == nullptr && !host_ids.empty()) {
-        // no copy streams given: use the library's own pair (created on first use, one pair per device)
-        rc = ensure_events_locked(ec, 0);
-        if (rc != MLPO_OK) return rc;
-        s_h2d = ec.copy_in;
-        s_d2h = ec.copy_out;
-    }
-    if (direct) {
-        // The host tier is updated in place by a bounded number of persistent workgroups; it is enqueued first so
-        // that those workgroups are resident before the HBM-tier kernel fills the rest of the chip.
-        if (!host_views.empty()) {
-            rc = ensure_events_locked(ec, 0);
-            if (rc != MLPO_OK) return rc;
-            MLPO_HIP(hipEventRecord(ec.fence2, s_cmp));  // gradients and scalars come from the compute stream
-            MLPO_HIP(hipStreamWaitEvent(s_h2d, ec.fence2, 0));
-            const int blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 64;
-            rc = launch_adamw(host_views.data(), (int)host_views.size(), c, scalars, s_h2d, blocks);
-            if (rc != MLPO_OK) return rc;
-        }
-        if (!resident.empty()) {
-            rc = launch_adamw(resident.data(), (int)resident.size(), c, scalars, s_cmp);
-            if (rc != MLPO_OK) return rc;
-        }
-        if (!host_views.empty()) {
-            MLPO_HIP(hipEventRecord(ec.fence, s_h2d));
-            MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
-        }
-        return MLPO_OK;
-    }
-    if (!host_ids.empty()) {
-        rc = ensure_events_locked(ec, cfg->n_slots);
-        if (rc != MLPO_OK) return rc;
-        // Work enqueued earlier on the flush and compute streams (a previous step's copy back, the gradient pass)
-        // must be complete before this step's first fetch overwrites a staging slot or reads the host tier.
-        MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
-        MLPO_HIP(hipStreamWaitEvent(s_h2d, ec.fence, 0));
-        MLPO_HIP(hipEventRecord(ec.fence2, s_cmp));
-        MLPO_HIP(hipStreamWaitEvent(s_h2d, ec.fence2, 0));
-    }
-    if (!resident.empty()) {
-        rc = launch_adamw(resident.data(), (int)resident.size(), c, scalars, s_cmp);
-        if (rc != MLPO_OK) return rc;
-    }
-
-    float* staging = static_cast<float*>(cfg->staging);
-    if (cfg->cache != nullptr) {
-        // Slots keep their subgroup from one step to the next (Section 3.2 "Cache-Friendly Ordering"): a subgroup
-        // found in a slot is updated there without any transfer, and a slot is copied back only when another
-        // subgroup needs it (or on mlpo_stream_flush).  With the order reversed from step to step the subgroups
-        // processed last are the ones processed first next time.
-        mlpo_slot_cache* cache = cfg->cache;
-        for (int32_t i : host_ids) {
-            const mlpo_subgroup& s = sg[i];
-            int k = -1;
-            for (int q = 0; q < cfg->n_slots; ++q)
-                if (cache->owner[q] == i) k = q;
-            const bool hit = k >= 0;
-            if (!hit) {
-                for (int q = 0; q < cfg->n_slots && k < 0; ++q)
-                    if (cache->owner[q] < 0) k = q;
-                if (k < 0) {  // least recently updated slot
-                    k = 0;
-                    for (int q = 1; q < cfg->n_slots; ++q)
-                        if (cache->stamp[q] < cache->stamp[k]) k = q;
-                }
-            }
-            SlotEvents& ev = ec.slots[(size_t)k];
-            float* slot = staging + (uint64_t)k * slot_floats;
-            const Piece pc{&s, 0, s.n, slot};
-            SgView view;
-            if (hit) {
-                // an explicit flush of this slot may still be reading it
-                MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.d2h_done, 0));
-                view = slot_view(pc);
-                ++cache->hits;
-            } else {
-                if (cache->owner[k] >= 0 && cache->dirty[k]) {
-                    const mlpo_subgroup& old = sg[cache->owner[k]];
-                    MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
-                    rc = flush_piece(Piece{&old, 0, old.n, slot}, s_d2h);
-                    if (rc != MLPO_OK) return rc;
-                    MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
-                    ++cache->flushes;
-                }
-                cache->owner[k] = -1;  // until the new occupant is in place
-                cache->dirty[k] = 0;
-                MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.d2h_done, 0));
-                MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.upd_done, 0));
-                rc = fetch_piece(pc, s_h2d, &view);
-                if (rc != MLPO_OK) return rc;
-                MLPO_HIP(hipEventRecord(ev.h2d_done, s_h2d));
-                MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.h2d_done, 0));
-                ++cache->fetches;
-            }
-            rc = launch_adamw(&view, 1, c, scalars, s_cmp);
-            if (rc != MLPO_OK) return rc;
-            MLPO_HIP(hipEventRecord(ev.upd_done, s_cmp));
-            cache->owner[k] = i;
-            cache->owner_p[k] = s.p;
-            cache->dirty[k] = 1;
-            cache->stamp[k] = ++cache->clock;
-        }
-        if (!host_ids.empty()) {
-            MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
-            MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
-        }
-        return MLPO_OK;
-    }
-    uint64_t piece = 0;
-    for (int32_t i : host_ids) {
-        const mlpo_subgroup& s = sg[i];
-        const uint64_t step_elems = (cfg->chunk_elems != 0 && cfg->chunk_elems < s.n) ? cfg->chunk_elems : s.n;
-        for (uint64_t off = 0; off < s.n; off += step_elems, ++piece) {
-            const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
-            const int k = (int)(piece % (uint64_t)cfg->n_slots);
-            SlotEvents& ev = ec.slots[(size_t)k];
-            float* slot = staging + (uint64_t)k * slot_floats;
-            // fetch: only into a slot whose previous occupant has been flushed
-            if (piece >= (uint64_t)cfg->n_slots) MLPO_HIP(hipStreamWaitEvent(s_h2d, ev.d2h_done, 0));
-            hipEvent_t tf0 = nullptr, tf1 = nullptr, tw0 = nullptr, tw1 = nullptr;
-            const bool timed = timing_enabled() && timing_acquire(kTimedFetch, &tf0, &tf1) &&
-                               timing_acquire(kTimedFlush, &tw0, &tw1);
-            if (timed) MLPO_HIP(hipEventRecord(tf0, s_h2d));
-            const Piece pc{&s, off, len, slot};
-            SgView view;
-            rc = fetch_piece(pc, s_h2d, &view);
-            if (rc != MLPO_OK) return rc;
-            if (timed) MLPO_HIP(hipEventRecord(tf1, s_h2d));
-            MLPO_HIP(hipEventRecord(ev.h2d_done, s_h2d));
-            // update in the slot; gradients and bf16 parameters stay at their device homes
-            MLPO_HIP(hipStreamWaitEvent(s_cmp, ev.h2d_done, 0));
-            rc = launch_adamw(&view, 1, c, scalars, s_cmp);
-            if (rc != MLPO_OK) return rc;
-            MLPO_HIP(hipEventRecord(ev.upd_done, s_cmp));
-            // flush
-            MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
-            if (timed) MLPO_HIP(hipEventRecord(tw0, s_d2h));
-            rc = flush_piece(pc, s_d2h);
-            if (rc != MLPO_OK) return rc;
-            if (timed) MLPO_HIP(hipEventRecord(tw1, s_d2h));
-            MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
-        }
-    }
-    if (!host_ids.empty()) {
-        // join: the compute stream sees the end of the last flush
-        MLPO_HIP(hipEventRecord(ec.fence, s_d2h));
-        MLPO_HIP(hipStreamWaitEvent(s_cmp, ec.fence, 0));
-    }
-    return MLPO_OK;
 }
 
 }  // extern "C"

@@ -42,6 +42,10 @@ struct AdamwConsts {
     float beta1, beta2, omb1, omb2, eps, step_size, sqbc2, decay;
 };
 int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step);
+// Pointer / size / tier checks shared by the entry points; grads_only checks g and n alone.
+int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, int allow_host);
+bool misaligned(const void* p, uintptr_t a);
+uint64_t round_up(uint64_t x, uint64_t to);
 AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step);
 
 // ---- kernel-side view of a subgroup -------------------------------------------
