@@ -70,6 +70,8 @@ def lib():
         L.orc_bf16_to_f32_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
         L.orc_f32_to_bf16_rne_array.restype = None
         L.orc_f32_to_bf16_rne_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+        L.orc_grad_accumulate.restype = None
+        L.orc_grad_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32]
         L.orc_grad_stats.restype = None
         L.orc_grad_stats.argtypes = [C.c_void_p, C.c_uint64, C.c_float, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]
         L.orc_norm_finish.restype = None
@@ -115,6 +117,13 @@ def f32_to_bf16_rne(x: np.ndarray) -> np.ndarray:
     out = np.empty(flat.size, np.uint16)
     lib().orc_f32_to_bf16_rne_array(flat.ctypes.data, out.ctypes.data, flat.size)
     return out.reshape(np.shape(x))
+
+
+def grad_accumulate(acc: np.ndarray, g: np.ndarray, first: bool) -> None:
+    """One micro-batch's bf16 gradients g into the bf16 accumulation buffer acc, in place (copy when ``first``)."""
+    if acc.size != g.size:
+        raise ValueError("acc and g differ in length")
+    lib().orc_grad_accumulate(_chk(acc, np.uint16, True), _chk(g, np.uint16), acc.size, 1 if first else 0)
 
 
 def grad_stats(g: np.ndarray, inv_scale: float, sumsq: float = 0.0, found_inf: int = 0):

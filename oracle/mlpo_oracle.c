@@ -77,6 +77,28 @@ void orc_f32_to_bf16_rne_array(const float* f, uint16_t* h, uint64_t n) {
     for (uint64_t i = 0; i < n; ++i) h[i] = orc_f32_to_bf16_rne(f[i]);
 }
 
+/* ---- gradient accumulation over micro-batches ----------------------------- */
+
+/* The half-precision accumulation buffer of Section 3.2 "Delayed In-place
+ * Mixed-Precision Gradient Conversion" (the buffer the update later upcasts
+ * on the fly): the first micro-batch of a step overwrites it, every later
+ * one is added element by element.  The paper does not print the
+ * arithmetic; the reading taken is the one a half-precision buffer allows:
+ * widen both (exact), one fp32 addition, round back to bf16 (nearest even).
+ * A NaN sum is stored as the canonical quiet NaN 0x7FC0 whatever sign or
+ * payload the addition produced, because IEEE 754 leaves those open. */
+void orc_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n,
+                         int32_t first) {
+    for (uint64_t i = 0; i < n; ++i) {
+        if (first) {
+            acc[i] = g[i];
+            continue;
+        }
+        float sum = orc_bf16_to_f32(acc[i]) + orc_bf16_to_f32(g[i]);
+        acc[i] = (sum != sum) ? (uint16_t)0x7FC0u : orc_f32_to_bf16_rne(sum);
+    }
+}
+
 /* ---- gradient statistics over one subgroup ------------------------------ */
 
 /* Adds to *sumsq the fp64 sum of squares of the unscaled gradients
