@@ -45,11 +45,14 @@ typedef struct {
 /* One subgroup (Section 2 "Sharded Model and Optimizer States Into Subgroups"): n elements of fp32 master parameters
  * p, momentum m, variance v, the bf16 gradients g that drive the update and the bf16 working copy p16 that receives
  * the downcast parameters.  g and p16 are plain arrays of n elements; p16 is always device memory, g normally too.
- * tier says where p, m, v live: MLPO_TIER_HBM (device) or MLPO_TIER_HOST (pinned host).
- * Host-side gradients (the paper keeps the half-precision gradients in a host accumulation buffer, Section 3.2
- * "Delayed In-place Mixed-Precision Gradient Conversion"): g of a host-tier subgroup may also be pinned host memory
- * when the subgroup is used with mlpo_grad_unscale_norm and with mlpo_stream_update in direct mode only; both kernels
- * then read the gradients over the link (2 bytes per element each) and upcast them in registers as always.
+ * tier says where p, m, v live: MLPO_TIER_HBM (device), MLPO_TIER_HOST (pinned host), or MLPO_TIER_HOST_GRADS
+ * (pinned host, and g is pinned host memory as well).
+ * Host-side gradients (the paper keeps the half-precision gradients in a host accumulation buffer and converts them
+ * only when the update needs them, Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"): with
+ * MLPO_TIER_HOST_GRADS, mlpo_grad_unscale_norm reads g over the link (2 bytes per element); mlpo_stream_update in
+ * staged mode brings each piece's gradients into the staging slot together with its state (14 bytes per element in,
+ * 12 out) and in direct mode reads them in place; the upcast happens in registers as always.  A MLPO_TIER_HOST
+ * subgroup whose g is pinned host memory is also accepted by mlpo_grad_unscale_norm and by direct mode.
  *
  * Layout of the fp32 state, chosen by tile_elems:
  *   0      planar: p, m, v are three independent arrays of n floats.
@@ -62,6 +65,7 @@ typedef struct {
  *          moves as one transfer per direction instead of three. */
 #define MLPO_TIER_HBM 0
 #define MLPO_TIER_HOST 1
+#define MLPO_TIER_HOST_GRADS 2
 #define MLPO_TILE_DEFAULT 8192
 typedef struct {
     float* p;
@@ -125,6 +129,25 @@ size_t mlpo_norm_workspace_bytes(void);
  */
 int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scale, float max_norm, void* workspace,
                            size_t workspace_bytes, mlpo_step_scalars* out, void* stream);
+
+/*
+ * Gradient accumulation over micro-batches into the half-precision accumulation buffer that the update later
+ * upcasts on the fly (Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"; Section 4.6 runs 1-16
+ * backward passes per update).  For every i < n:
+ *   first != 0:  acc[i] = g[i]                                  (first micro-batch of a step: no clearing pass needed)
+ *   first == 0:  acc[i] = bf16_rne(f32(acc[i]) + f32(g[i]))     (one fp32 addition; a NaN sum is stored as 0x7FC0)
+ * The sum of two bf16 values rounded this way is the correctly rounded exact sum.
+ *   acc     bf16 accumulation buffer, n elements: device memory, or pinned host memory (then the kernel reads and
+ *           writes it over the link, 2 bytes per element each way).
+ *   g       bf16 gradients of this micro-batch, n elements, device memory (pinned host memory also works).
+ *           Must not overlap acc.  Both 2-byte aligned; the 128-bit path needs acc and g congruent modulo 16 bytes,
+ *           otherwise every element is moved on its own (much slower).
+ *   blocks  0: one workgroup per 8192 elements (device buffers).  > 0: that many persistent workgroups (<= 4096),
+ *           which bounds the requests in flight on the link when acc is on the host; 64 is a good value there.
+ *   stream  hipStream_t.  Asynchronous.  n = 0 is a no-op.
+ * Errors: MLPO_EINVAL, MLPO_EHIP.
+ */
+int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks, void* stream);
 
 /*
  * AdamW on HBM-resident subgroups, in place, with the gradient upcast and the parameter downcast fused in
@@ -207,7 +230,8 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
  * and the bound on subgroups in flight that Section 3.2 "Optimized Virtual Tier Concurrency Control" motivates).
  * HBM-tier subgroups are updated in place as in mlpo_adamw_step.  In staged mode each host-tier subgroup (or chunk of
  * one) is copied host-to-device into a free staging slot on the h2d stream, updated there on the compute stream (g
- * and p16 are read/written at their device homes), and copied back on the d2h stream; a slot is reused only after its
+ * and p16 are read/written at their device homes; the gradients of a MLPO_TIER_HOST_GRADS subgroup travel into the
+ * slot with the state, and with a slot cache they are fetched anew every step), and copied back on the d2h stream; a slot is reused only after its
  * copy back has completed, so at most n_slots transfers are in flight.  In direct mode the kernel works on the host
  * state in place.  Results are bit-identical to the resident path whatever mode, n_slots, chunk_elems, direct_blocks
  * and order are.
@@ -275,6 +299,7 @@ int mlpo_set_option(const char* key, int64_t value);
  * dispatch's own begin and end on the device, and every staged-mode transfer is bracketed by event markers on its
  * copy stream (which = 2: host-to-device fetches, which = 3: device-to-host flushes, one entry per subgroup or chunk;
  * the effective I/O throughput of Section 4.3 of the paper, 2 * bytes / (read time + write time), follows from them).
+ * which = 4: the 128-bit kernel of mlpo_grad_accumulate.
  * mlpo_kernel_times waits for the recorded items, writes their durations in milliseconds to ms[0..cap) in issue order
  * (host memory), stores the number written in *count and forgets them.  At most 16384 items per kind are kept
  * between calls.  Setting the option to 0 turns it off.

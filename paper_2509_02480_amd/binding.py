@@ -16,14 +16,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmlpo.so")
 
 MLPO_OK, MLPO_EINVAL, MLPO_EHIP, MLPO_ENOMEM = 0, -1, -2, -3
-TIER_HBM, TIER_HOST = 0, 1
+TIER_HBM, TIER_HOST, TIER_HOST_GRADS = 0, 1, 2
 MAX_SLOTS = 64
 
 TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_state_pack", "mlpo_state_unpack",
            "mlpo_norm_workspace_bytes",
-           "mlpo_grad_unscale_norm",
+           "mlpo_grad_unscale_norm", "mlpo_grad_accumulate",
            "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers",
            "mlpo_update_bandwidth", "mlpo_set_option",
            "mlpo_kernel_times",
@@ -111,6 +111,8 @@ def lib():
         L.mlpo_grad_unscale_norm.restype = C.c_int
         L.mlpo_grad_unscale_norm.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_size_t,
                                              C.c_void_p, C.c_void_p]
+        L.mlpo_grad_accumulate.restype = C.c_int
+        L.mlpo_grad_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p]
         L.mlpo_adamw_step.restype = C.c_int
         L.mlpo_adamw_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(HParamsC), C.c_int64, C.c_void_p, C.c_void_p]
         L.mlpo_stream_staging_bytes.restype = C.c_size_t
@@ -283,6 +285,13 @@ def mlpo_update_bandwidth(bandwidth: Sequence[float], bytes_moved: Sequence[floa
     bw = (C.c_double * n)(*bandwidth)
     _check(lib().mlpo_update_bandwidth(n, bw, (C.c_double * n)(*bytes_moved), (C.c_double * n)(*seconds)))
     return list(bw)
+
+
+def mlpo_grad_accumulate(acc, g, n: Optional[int] = None, first: bool = False, blocks: int = 0, stream=None) -> None:
+    """One micro-batch's bf16 gradients into the bf16 accumulation buffer; see mlpo.h."""
+    if n is None:
+        n = g.numel()
+    _check(lib().mlpo_grad_accumulate(_ptr(acc), _ptr(g), int(n), 1 if first else 0, int(blocks), _stream(stream)))
 
 
 def mlpo_set_option(key: str, value: int) -> None:

@@ -53,7 +53,7 @@ struct TimedLaunch {
 struct TimingState {
     std::mutex mu;
     bool enabled = false;
-    std::vector<TimedLaunch> rec[4];
+    std::vector<TimedLaunch> rec[kTimedKinds];
     std::vector<TimedLaunch> pool;
 };
 TimingState& timing() {
@@ -68,7 +68,7 @@ bool timing_enabled() { return timing().enabled; }
 bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop) {
     TimingState& t = timing();
     std::lock_guard<std::mutex> lk(t.mu);
-    if (!t.enabled || which < 0 || which > 3 || t.rec[which].size() >= kMaxTimed) return false;
+    if (!t.enabled || which < 0 || which >= kTimedKinds || t.rec[which].size() >= kMaxTimed) return false;
     TimedLaunch e;
     if (!t.pool.empty()) {
         e = t.pool.back();
@@ -143,9 +143,9 @@ int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, i
         if (s.n != 0 && s.g == nullptr) return fail(MLPO_EINVAL, "subgroup %d: g is NULL", i);
         if (misaligned(s.g, 2)) return fail(MLPO_EINVAL, "subgroup %d: g is not 2-byte aligned", i);
         if (grads_only) continue;
-        if (s.tier != MLPO_TIER_HBM && s.tier != MLPO_TIER_HOST)
+        if (s.tier != MLPO_TIER_HBM && !host_tier(s.tier))
             return fail(MLPO_EINVAL, "subgroup %d: unknown tier %d", i, s.tier);
-        if (s.tier == MLPO_TIER_HOST && !allow_host)
+        if (host_tier(s.tier) && !allow_host)
             return fail(MLPO_EINVAL, "subgroup %d is host-tier: use mlpo_stream_update", i);
         if (s.n != 0 && (s.p == nullptr || s.m == nullptr || s.v == nullptr || s.p16 == nullptr))
             return fail(MLPO_EINVAL, "subgroup %d: NULL state pointer", i);
@@ -192,7 +192,7 @@ int mlpo_set_option(const char* key, int64_t value) {
 }
 
 int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count) {
-    if (which < 0 || which > 3) return fail(MLPO_EINVAL, "which must be 0..3");
+    if (which < 0 || which >= kTimedKinds) return fail(MLPO_EINVAL, "which must be 0..%d", kTimedKinds - 1);
     if (count == nullptr || cap < 0 || (cap > 0 && ms == nullptr)) return fail(MLPO_EINVAL, "bad output arguments");
     TimingState& t = timing();
     std::lock_guard<std::mutex> lk(t.mu);
@@ -222,6 +222,17 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
         return fail(MLPO_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, grad_norm_workspace_bytes());
     if (out == nullptr || misaligned(out, 16)) return fail(MLPO_EINVAL, "out is NULL or not 16-byte aligned");
     return launch_grad_norm(sg, n_sg, inv_scale, max_norm, workspace, out, static_cast<hipStream_t>(stream));
+}
+
+int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks, void* stream) {
+    if (n == 0) return MLPO_OK;
+    if (acc == nullptr || g == nullptr) return fail(MLPO_EINVAL, "acc or g is NULL");
+    if (misaligned(acc, 2) || misaligned(g, 2)) return fail(MLPO_EINVAL, "acc or g not 2-byte aligned");
+    if (n > (1ull << 44)) return fail(MLPO_EINVAL, "n too large");
+    if (blocks < 0 || blocks > 4096) return fail(MLPO_EINVAL, "blocks must be 0..4096 (got %d)", blocks);
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(acc), g0 = reinterpret_cast<uintptr_t>(g);
+    if (a0 < g0 + 2 * n && g0 < a0 + 2 * n) return fail(MLPO_EINVAL, "acc and g overlap");
+    return launch_grad_accumulate(acc, g, n, first != 0, blocks, static_cast<hipStream_t>(stream));
 }
 
 int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hparams* hp, int64_t step,

@@ -34,6 +34,8 @@ constexpr int kTimedUpdate = 0;  // the fused AdamW kernel (128-bit variant)
 constexpr int kTimedGradPass = 1;  // pass 1 of the gradient pass
 constexpr int kTimedFetch = 2;     // staged mode: one host-to-device transfer (markers on the copy stream)
 constexpr int kTimedFlush = 3;     // staged mode: one device-to-host transfer
+constexpr int kTimedAccumulate = 4;  // the gradient accumulation kernel (128-bit variant)
+constexpr int kTimedKinds = 5;
 bool timing_enabled();
 bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop);  // false: not enabled or table full
 
@@ -70,5 +72,10 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
 int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float max_norm, void* workspace,
                      mlpo_step_scalars* out, hipStream_t stream);
 size_t grad_norm_workspace_bytes();
+
+// Enqueues acc = first ? g : bf16(acc + g) over n elements; blocks > 0 bounds the persistent grid.
+int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st);
+
+inline bool host_tier(int32_t tier) { return tier == MLPO_TIER_HOST || tier == MLPO_TIER_HOST_GRADS; }
 
 }  // namespace mlpo

@@ -65,19 +65,26 @@ static int ensure_events_locked(EventCache& c, int n_slots) {
 }
 
 
+// Floats the fp32 state of a piece of len elements takes in a staging slot: three arrays, each rounded so that the
+// arrays of a slot keep their alignment (planar) or to whole layout tiles (tiled).
+static uint64_t state_floats_of(const mlpo_subgroup& s, uint64_t len) {
+    return 3u * round_up(len, s.tile_elems > 0 ? (uint64_t)s.tile_elems : 64u);
+}
+
 // Floats one host-tier subgroup needs in a staging slot when moved in pieces of at most chunk_elems elements
-// (0 = whole): three arrays, each rounded so that the arrays of a slot keep their alignment (planar) or to whole
-// layout tiles (tiled).
+// (0 = whole): the state, and behind it the piece's bf16 gradients when those live on the host too.
 static uint64_t slot_floats_of(const mlpo_subgroup& s, uint64_t chunk_elems) {
     uint64_t len = s.n;
     if (chunk_elems != 0 && chunk_elems < len) len = chunk_elems;
-    return 3u * round_up(len, s.tile_elems > 0 ? (uint64_t)s.tile_elems : 64u);
+    uint64_t f = state_floats_of(s, len);
+    if (s.tier == MLPO_TIER_HOST_GRADS) f += round_up(len, 128) / 2u;
+    return f;
 }
 
 static uint64_t slot_floats_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems) {
     uint64_t mx = 0;
     for (int32_t i = 0; i < n_sg; ++i)
-        if (sg[i].tier == MLPO_TIER_HOST) {
+        if (host_tier(sg[i].tier)) {
             const uint64_t f = slot_floats_of(sg[i], chunk_elems);
             if (f > mx) mx = f;
         }
@@ -92,16 +99,35 @@ struct Piece {
     float* slot;
 };
 
+// Where the update reads the piece's gradients: behind the state in the slot when they come from the host with it,
+// else at their device home.
+static const uint16_t* piece_grads(const Piece& pc) {
+    const mlpo_subgroup& s = *pc.s;
+    if (s.tier != MLPO_TIER_HOST_GRADS) return s.g + pc.off;
+    return reinterpret_cast<const uint16_t*>(pc.slot + state_floats_of(s, pc.len));
+}
+
+// Host-to-device transfer of the piece's gradients into its slot (subgroups whose gradients live on the host).
+static int fetch_grads(const Piece& pc, hipStream_t st) {
+    const mlpo_subgroup& s = *pc.s;
+    if (s.tier != MLPO_TIER_HOST_GRADS) return MLPO_OK;
+    MLPO_HIP(hipMemcpyAsync(const_cast<uint16_t*>(piece_grads(pc)), s.g + pc.off, (size_t)pc.len * sizeof(uint16_t),
+                            hipMemcpyHostToDevice, st));
+    return MLPO_OK;
+}
+
 // Host-to-device transfer of a piece into its slot; returns the kernel's view of the slot.
 static int fetch_piece(const Piece& pc, hipStream_t st, SgView* view) {
     const mlpo_subgroup& s = *pc.s;
+    const int rc = fetch_grads(pc, st);
+    if (rc != MLPO_OK) return rc;
     if (s.tile_elems > 0) {
         // whole layout tiles travel as one contiguous block: p, m, v of the same elements stay together
         const uint64_t T = (uint64_t)s.tile_elems;
         const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
         const float* src = s.p + (pc.off / T) * 3u * T;
         MLPO_HIP(hipMemcpyAsync(pc.slot, src, bytes, hipMemcpyHostToDevice, st));
-        *view = SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, s.g + pc.off, s.p16 + pc.off, pc.len, s.tile_elems};
+        *view = SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, piece_grads(pc), s.p16 + pc.off, pc.len, s.tile_elems};
     } else {
         const size_t bytes = (size_t)pc.len * sizeof(float);
         const uint64_t arr = round_up(pc.len, 64);
@@ -111,7 +137,7 @@ static int fetch_piece(const Piece& pc, hipStream_t st, SgView* view) {
         MLPO_HIP(hipMemcpyAsync(sp, s.p + pc.off, bytes, hipMemcpyHostToDevice, st));
         MLPO_HIP(hipMemcpyAsync(sm, s.m + pc.off, bytes, hipMemcpyHostToDevice, st));
         MLPO_HIP(hipMemcpyAsync(sv, s.v + pc.off, bytes, hipMemcpyHostToDevice, st));
-        *view = SgView{sp, sm, sv, s.g + pc.off, s.p16 + pc.off, pc.len, 0};
+        *view = SgView{sp, sm, sv, piece_grads(pc), s.p16 + pc.off, pc.len, 0};
     }
     return MLPO_OK;
 }
@@ -121,10 +147,10 @@ static SgView slot_view(const Piece& pc) {
     const mlpo_subgroup& s = *pc.s;
     if (s.tile_elems > 0) {
         const uint64_t T = (uint64_t)s.tile_elems;
-        return SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, s.g + pc.off, s.p16 + pc.off, pc.len, s.tile_elems};
+        return SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, piece_grads(pc), s.p16 + pc.off, pc.len, s.tile_elems};
     }
     const uint64_t arr = round_up(pc.len, 64);
-    return SgView{pc.slot, pc.slot + arr, pc.slot + 2 * arr, s.g + pc.off, s.p16 + pc.off, pc.len, 0};
+    return SgView{pc.slot, pc.slot + arr, pc.slot + 2 * arr, piece_grads(pc), s.p16 + pc.off, pc.len, 0};
 }
 
 // Device-to-host transfer of a piece from its slot back to the host tier.
@@ -165,7 +191,7 @@ static int cache_check(mlpo_slot_cache* c, const mlpo_subgroup* sg, int32_t n_sg
     for (int k = 0; k < n_slots; ++k) {
         const int32_t o = c->owner[k];
         if (o < 0) continue;
-        if (o >= n_sg || sg[o].p != c->owner_p[k] || sg[o].tier != MLPO_TIER_HOST)
+        if (o >= n_sg || sg[o].p != c->owner_p[k] || !host_tier(sg[o].tier))
             return fail(MLPO_EINVAL, "slot %d holds subgroup %d of a different subgroup table", k, o);
     }
     return MLPO_OK;
@@ -210,7 +236,7 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
         }
     }
     for (int32_t i = 0; i < n_sg; ++i)
-        if (sg[i].tier == MLPO_TIER_HOST && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
+        if (host_tier(sg[i].tier) && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
             return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
     const uint64_t slot_floats = direct ? 0 : slot_floats_for(sg, n_sg, cfg->chunk_elems);
     const uint64_t need = slot_floats * 4u * (uint64_t)(direct ? 0 : cfg->n_slots);
@@ -287,6 +313,14 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
             // an explicit flush of this slot may still be reading it
             MLPO_HIP(hipStreamWaitEvent(st.cmp, ev.d2h_done, 0));
             view = slot_view(pc);
+            if (s.tier == MLPO_TIER_HOST_GRADS) {
+                // the state stayed, this step's gradients still have to come in (after the last update read the old)
+                MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.upd_done, 0));
+                rc = fetch_grads(pc, st.h2d);
+                if (rc != MLPO_OK) return rc;
+                MLPO_HIP(hipEventRecord(ev.h2d_done, st.h2d));
+                MLPO_HIP(hipStreamWaitEvent(st.cmp, ev.h2d_done, 0));
+            }
             ++cache->hits;
         } else {
             if (cache->owner[k] >= 0 && cache->dirty[k]) {

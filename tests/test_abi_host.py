@@ -165,3 +165,28 @@ def test_options():
     expect(B.MLPO_EINVAL, B.mlpo_set_option, "no_such_option", 1)
     expect(B.MLPO_EINVAL, B.mlpo_set_option, "adamw_variant", 10 ** 6)
     B.mlpo_shutdown()
+
+
+def test_grad_accumulate_argument_errors():
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, 0, FAKE, 16)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, 0, 16)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE + 1, FAKE + 4096, 16)          # not 2-byte aligned
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, FAKE + 30, 16)                # ranges overlap
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE + 30, FAKE, 16)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, FAKE + 4096, 16, blocks=-1)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, FAKE + 4096, 16, blocks=5000)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, FAKE + (1 << 50), (1 << 44) + 1)
+    B.mlpo_grad_accumulate(0, 0, 0)                                                   # n = 0: nothing to do
+
+
+def test_staging_size_counts_host_side_gradients():
+    # planar: 3 arrays of round_up(n, 64) floats; with the gradients on the host the slot also holds round_up(n, 128)
+    # bf16 values behind them
+    state_only = [sg(n=1000, tier=B.TIER_HOST)]
+    with_grads = [sg(n=1000, tier=B.TIER_HOST_GRADS)]
+    assert B.mlpo_stream_staging_bytes(state_only, 2, 0) == 2 * 3 * 1024 * 4
+    assert B.mlpo_stream_staging_bytes(with_grads, 2, 0) == 2 * (3 * 1024 * 4 + 1024 * 2)
+    assert B.mlpo_stream_staging_bytes(with_grads, 3, 400) == 3 * (3 * 448 * 4 + 512 * 2)
+    tiled = [B.tiled_subgroup(FAKE, FAKE + (1 << 30), FAKE + (2 << 30), n=5000, tier=B.TIER_HOST_GRADS, tile_elems=2048)]
+    assert B.mlpo_stream_staging_bytes(tiled, 1, 0) == 3 * 6144 * 4 + 5120 * 2
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(tier=B.TIER_HOST_GRADS)], B.HParams(), 1)

@@ -1,0 +1,134 @@
+"""GPU parity of mlpo_grad_accumulate (the half-precision gradient accumulation buffer of Section 3.2 "Delayed
+In-place Mixed-Precision Gradient Conversion") against the oracle: bit-exact on arbitrary bit patterns (non-finite
+values included), for device and pinned-host buffers, every alignment phase, persistent and one-tile-per-workgroup
+grids; then the whole flow the paper describes: micro-batches accumulated into a host buffer, the update reading it."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2509_02480_amd import binding as B  # noqa: E402
+from paper_2509_02480_amd import workloads as W  # noqa: E402
+
+from gpu_util import DeviceSubgroups, Scratch, assert_state_parity, dev, hp_pair  # noqa: E402
+
+
+def bits(rng, n):
+    return rng.integers(0, 0x10000, n, dtype=np.uint32).astype(np.uint16)
+
+
+def to_dev(a):
+    return torch.from_numpy(a.view(np.int16)).to(dev())
+
+
+def back(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 1023, 8191, 8192, 8193, 100_003, (1 << 20) + 5, 3 * 8192 * 4])
+@pytest.mark.parametrize("first", [False, True])
+def test_matches_oracle_on_any_bits(oracle, n, first):
+    rng = np.random.default_rng(n)
+    a, g = bits(rng, n), bits(rng, n)
+    da, dg = to_dev(a), to_dev(g)
+    B.mlpo_grad_accumulate(da, dg, n, first=first)
+    torch.cuda.synchronize()
+    oracle.grad_accumulate(a, g, first)
+    assert np.array_equal(back(da), a)
+    assert np.array_equal(back(dg), g)
+
+
+def test_every_pattern_against_selected_addends(oracle):
+    pats = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    addends = [0x0000, 0x8000, 0x0001, 0x3B80, 0xBB80, 0x3F80, 0xBF80, 0x7B00, 0x7F7F, 0xFF7F, 0x7F80, 0xFF80, 0x7FC1,
+               0x3A83, 0xBA83, 0x0080]
+    a = np.tile(pats, len(addends))
+    g = np.repeat(np.array(addends, np.uint16), pats.size)
+    da, dg = to_dev(a), to_dev(g)
+    B.mlpo_grad_accumulate(da, dg, a.size)
+    torch.cuda.synchronize()
+    oracle.grad_accumulate(a, g, False)
+    got = back(da)
+    bad = np.nonzero(got != a)[0]
+    assert bad.size == 0, [(hex(int(np.tile(pats, len(addends))[i])), hex(int(g[i])), hex(int(got[i])), hex(int(a[i])))
+                           for i in bad[:5]]
+
+
+@pytest.mark.parametrize("off_a,off_g", [(0, 0), (1, 1), (3, 3), (7, 7), (5, 13), (0, 1), (2, 7), (4, 0)])
+def test_alignment_phases(oracle, off_a, off_g):
+    n = 40_000
+    rng = np.random.default_rng(off_a * 16 + off_g)
+    a, g = bits(rng, n), bits(rng, n)
+    guard = 0x1234
+    ba = torch.full((n + 64,), guard, dtype=torch.int16, device=dev())
+    bg = torch.zeros(n + 64, dtype=torch.int16, device=dev())
+    ba[off_a:off_a + n].copy_(to_dev(a))
+    bg[off_g:off_g + n].copy_(to_dev(g))
+    B.mlpo_grad_accumulate(ba[off_a:], bg[off_g:], n)
+    torch.cuda.synchronize()
+    oracle.grad_accumulate(a, g, False)
+    out = back(ba)
+    assert np.array_equal(out[off_a:off_a + n], a)
+    assert np.all(out[:off_a] == guard) and np.all(out[off_a + n:] == guard)   # nothing outside the range is touched
+
+
+@pytest.mark.parametrize("blocks", [0, 1, 7, 64])
+def test_pinned_host_buffer_and_persistent_grids(oracle, blocks):
+    n = 1_000_003
+    rng = np.random.default_rng(blocks)
+    acc = torch.empty(n, dtype=torch.int16, pin_memory=True)
+    ref = np.zeros(n, np.uint16)
+    for j in range(4):
+        g = oracle.f32_to_bf16_rne((rng.standard_normal(n) * 1e-3 * 1024).astype(np.float32))
+        B.mlpo_grad_accumulate(acc, to_dev(g), n, first=(j == 0), blocks=blocks)
+        torch.cuda.synchronize()
+        oracle.grad_accumulate(ref, g, j == 0)
+    assert np.array_equal(acc.numpy().view(np.uint16), ref)
+    assert np.count_nonzero(ref) > n // 2
+
+
+def test_micro_batches_on_the_host_then_update(oracle):
+    """Four micro-batches accumulated into pinned-host buffers, then the gradient pass and a staged update that fetches
+    those gradients with the state (the data placement of Section 3.2): state, bf16 copy, norm and flag as the oracle's
+    on the oracle's own accumulation."""
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("accum", n_sub=4, sub_elems=120_007, n_host=3, loss_scale=512.0, max_norm=0.1, steps=2)
+    host = W.host_subgroups(wl, warm=True)
+    tiers = [B.TIER_HOST_GRADS if wl.tier(k) else B.TIER_HBM for k in range(wl.n_sub)]
+    ds = DeviceSubgroups(host, tiers=[1 if t else 0 for t in tiers], flat=False, tile=2048)
+    accs, descs = [], []
+    for k, e in enumerate(ds.t):
+        acc = torch.empty(ds.sizes[k], dtype=torch.int16, pin_memory=True) if tiers[k] else \
+            torch.empty(ds.sizes[k], dtype=torch.int16, device=dev())
+        accs.append(acc)
+        descs.append(B.tiled_subgroup(e["state"], acc, e["p16"], n=ds.sizes[k], tier=tiers[k], tile_elems=2048))
+    table = B.SubgroupTable(descs)
+    scratch = Scratch()
+    cmp_ = torch.cuda.Stream()
+    need = B.mlpo_stream_staging_bytes(table, 2, 32_768)
+    stg = torch.empty(need, dtype=torch.uint8, device=dev())
+    cfg = B.stream_cfg(2, stg, need, None, cmp_, None, 32_768)
+    micro = np.empty(wl.sub_elems, np.uint16)
+    dmicro = torch.empty(wl.sub_elems, dtype=torch.int16, device=dev())
+    for s in range(wl.steps):
+        for k, sg in enumerate(host):
+            for j in range(4):
+                W.fill_grads(wl, k, 10 * s + j, micro)
+                oracle.grad_accumulate(sg["g"], micro, j == 0)
+                dmicro.copy_(torch.from_numpy(micro.view(np.int16)))
+                torch.cuda.synchronize()
+                B.mlpo_grad_accumulate(accs[k], dmicro, first=(j == 0), blocks=16 if tiers[k] else 0, stream=cmp_)
+                cmp_.synchronize()
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm)
+        B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars, cmp_)
+        assert B.mlpo_stream_update(table, None, ghp, s + 1, scratch.scalars, cfg) and ok_o
+        cmp_.synchronize()
+        sc = scratch.read()
+        assert abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5 and sc["gmul"] == gmul_o
+        for k in range(wl.n_sub):
+            got = accs[k].numpy() if tiers[k] else accs[k].cpu().numpy()
+            assert np.array_equal(got.view(np.uint16), host[k]["g"]), f"accumulated gradients sg={k}"
+    for k in range(wl.n_sub):
+        assert_state_parity(ds.fetch(k), host[k], f"accumulate then update sg={k}")

@@ -327,3 +327,64 @@ def test_direct_mode_with_gradients_on_the_host(oracle, scratch, streams):
         assert abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5 and sc["gmul"] == gmul_o
     for k in range(wl.n_sub):
         assert_state_parity(ds.fetch(k), host[k], f"host-side gradients sg={k}")
+
+
+def _host_grad_table(ds, tiers, tile):
+    """Subgroup table in which the gradients of every host-tier subgroup live in pinned host memory."""
+    descs = []
+    for k, e in enumerate(ds.t):
+        g = e["g"]
+        if tiers[k]:
+            g = torch.empty(ds.sizes[k], dtype=torch.int16, pin_memory=True)
+            g.copy_(e["g"])
+        e["g_used"] = g
+        tier = B.TIER_HOST_GRADS if tiers[k] else B.TIER_HBM
+        if tile:
+            descs.append(B.tiled_subgroup(e["state"], g, e["p16"], n=ds.sizes[k], tier=tier, tile_elems=tile))
+        else:
+            descs.append(B.subgroup(e["p"], e["m"], e["v"], g, e["p16"], n=ds.sizes[k], tier=tier))
+    return B.SubgroupTable(descs)
+
+
+@pytest.mark.parametrize("mode,n_slots,chunk,tile,cached", [
+    ("staged", 1, 0, 0, False), ("staged", 2, 0, 2048, False), ("staged", 3, 4096, 0, False),
+    ("staged", 2, 16_384, 2048, False), ("staged", 4, 33_332, 0, False), ("staged", 2, 0, 2048, True),
+    ("staged", 3, 0, 0, True), ("staged", 5, 0, 8192, True), ("direct", 0, 0, 2048, False), ("direct", 0, 0, 0, False),
+])
+def test_gradients_fetched_from_the_host_with_the_state(oracle, scratch, streams, mode, n_slots, chunk, tile, cached):
+    """Host-tier subgroups whose bf16 gradients sit in pinned host memory too (Section 3.2 "Delayed In-place
+    Mixed-Precision Gradient Conversion"): staged mode brings them into the slot with the state, a slot cache fetches
+    them anew every step, direct mode reads them in place.  Fresh gradients every step, alternating order."""
+    ohp, ghp = hp_pair(oracle)
+    wl = W.Workload("hostg2", n_sub=6, sub_elems=70_001, n_host=4, loss_scale=64.0, max_norm=0.03, steps=4)
+    host = W.host_subgroups(wl, warm=True)
+    tiers = [wl.tier(k) for k in range(wl.n_sub)]
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=tile)
+    table = _host_grad_table(ds, tiers, tile)
+    cache = B.SlotCacheC() if cached else None
+    if mode == "direct":
+        cfg, stg = B.direct_cfg(streams[0], streams[1], 24), None
+    else:
+        need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
+        stg = torch.empty(need, dtype=torch.uint8, device=dev())
+        cfg = B.stream_cfg(n_slots, stg, need, None, streams[1], None, chunk, cache=cache)
+    for s in range(wl.steps):
+        order = list(range(wl.n_sub)) if s % 2 == 0 else list(range(wl.n_sub))[::-1]
+        if s > 0:
+            for k, sg in enumerate(host):
+                W.fill_grads(wl, k, s, sg["g"])
+                ds.t[k]["g_used"].copy_(torch.from_numpy(sg["g"].view(np.int16)))
+        torch.cuda.synchronize()
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm, order=order)
+        B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                 streams[1])
+        assert B.mlpo_stream_update(table, order, ghp, s + 1, scratch.scalars, cfg) and ok_o
+        streams[1].synchronize()
+        sc = scratch.read()
+        assert abs(float(sc["norm"]) / float(norm_o) - 1) <= 1e-5 and sc["gmul"] == gmul_o
+    if cached:
+        assert cache.hits > 0
+        B.mlpo_stream_flush(table, cfg)
+        streams[1].synchronize()
+    for k in range(wl.n_sub):
+        assert_state_parity(ds.fetch(k), host[k], f"{mode} slots={n_slots} chunk={chunk} tile={tile} sg={k}")
