@@ -323,17 +323,16 @@ def streamed_bench(args, torch, B, W, np):
 
     applied = 0
     host_g_table = None
+    micro = None
     for n_slots, chunk in args.stream_variants:
         cache = None
         run_table = table
         if n_slots == "d":      # direct mode: chunk holds the number of persistent workgroups
             stg = None
             cfg = B.direct_cfg(h2d, cmp_, chunk)
-        elif n_slots == "dg":   # direct mode with the gradients of host-tier subgroups in pinned host memory too
-            stg = None
-            cfg = B.direct_cfg(h2d, cmp_, chunk)
+        elif n_slots in ("dg", "sg", "dga"):   # the gradients of host-tier subgroups in pinned host memory too
             if host_g_table is None:
-                host_g_keep = []
+                host_g_keep, host_g_all = [], []
                 sg2 = []
                 for k in range(wl.n_sub):
                     gk = g_flat[k * M:(k + 1) * M]
@@ -341,11 +340,19 @@ def streamed_bench(args, torch, B, W, np):
                         gk = torch.empty(M, dtype=torch.int16, pin_memory=True)
                         gk.copy_(g_flat[k * M:(k + 1) * M])
                         host_g_keep.append(gk)
-                    sg2.append(B.tiled_subgroup(keep[k], gk, p16_flat[k * M:(k + 1) * M], n=M, tier=wl.tier(k),
-                                                tile_elems=T))
+                    host_g_all.append(gk)
+                    sg2.append(B.tiled_subgroup(keep[k], gk, p16_flat[k * M:(k + 1) * M], n=M,
+                                                tier=B.TIER_HOST_GRADS if wl.tier(k) else B.TIER_HBM, tile_elems=T))
                 host_g_table = B.SubgroupTable(sg2)
                 torch.cuda.synchronize()
             run_table = host_g_table
+            if n_slots in ("dg", "dga"):     # direct mode: chunk holds the number of persistent workgroups
+                stg = None
+                cfg = B.direct_cfg(h2d, cmp_, chunk)
+            else:                   # staged mode, 3 slots: the gradients travel into the slot with the state
+                need = B.mlpo_stream_staging_bytes(run_table, 3, chunk)
+                stg = torch.empty(need, dtype=torch.uint8, device=d)
+                cfg = B.stream_cfg(3, stg, need, None, cmp_, None, chunk)
         elif n_slots == "c":    # staged mode with slots that keep their subgroups; chunk holds the number of slots
             cache = B.SlotCacheC()
             need = B.mlpo_stream_staging_bytes(table, chunk, 0)
@@ -361,8 +368,20 @@ def streamed_bench(args, torch, B, W, np):
             if s == args.stream_warmup:
                 B.mlpo_set_option("time_kernels", 1)
                 fetches_before = cache.fetches if cache is not None else 0
+            if n_slots == "dga":
+                # the last micro-batch of the backward pass (outside the update phase, untimed) accumulates into
+                # the host buffers and leaves the gradient statistics behind; zeros keep the gradients as they are
+                if micro is None:
+                    micro = torch.zeros(M, dtype=torch.int16, device=d)
+                for k in range(wl.n_sub):
+                    B.mlpo_grad_accumulate_norm(host_g_all[k], micro, M, False, 64 if wl.tier(k) else 0, wl.inv_scale,
+                                                ws, ws_bytes, begin=(k == 0), stream=cmp_)
+                torch.cuda.synchronize()
             t = time.perf_counter()
-            B.mlpo_grad_unscale_norm(run_table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
+            if n_slots == "dga":
+                B.mlpo_grad_norm_finish(ws, ws_bytes, wl.inv_scale, wl.max_norm, scal, cmp_)
+            else:
+                B.mlpo_grad_unscale_norm(run_table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
             # with a slot cache the processing order alternates (Section 3.2 "Cache-Friendly Ordering")
             order = list(range(wl.n_sub))[::-1] if (cache is not None and s % 2 == 1) else None
             ok = B.mlpo_stream_update(run_table, order, hp, applied + 1, scal, cfg)
@@ -375,20 +394,22 @@ def streamed_bench(args, torch, B, W, np):
                 times.append(dt)
         fetch_ms, flush_ms, kern_ms = B.mlpo_kernel_times(2), B.mlpo_kernel_times(3), B.mlpo_kernel_times(0)
         B.mlpo_kernel_times(1)
+        B.mlpo_kernel_times(4)
         B.mlpo_set_option("time_kernels", 0)
         mean = sum(times) / len(times)
         gbs = 12 * n_host_params / mean / 1e9
         # the paper's effective I/O throughput (Section 4.3): 2 * bytes / (read time + write time), averaged over
         # the transfer units; in direct mode reading and writing both last as long as the kernel that does them
-        if n_slots in ("d", "dg"):
+        if n_slots in ("d", "dg", "dga"):
             eff = [2 * 12 * n_host_params / (2 * k * 1e-3) / 1e9 for k in kern_ms if k > 1.0]
         elif n_slots == "c":
             eff = []                # transfers are not paired one to one when flushes are lazy
         else:
             c = chunk or M
-            units = [12 * min(c, M - o) for _ in range(wl.n_host * len(times)) for o in range(0, M, c)]
+            both = 26 if n_slots == "sg" else 24     # bytes per element fetched + flushed
+            units = [both * min(c, M - o) for _ in range(wl.n_host * len(times)) for o in range(0, M, c)]
             assert len(units) == len(fetch_ms) == len(flush_ms), (len(units), len(fetch_ms), len(flush_ms))
-            eff = [2 * u / ((a + b) * 1e-3) / 1e9 for u, a, b in zip(units, fetch_ms, flush_ms)]
+            eff = [u / ((a + b) * 1e-3) / 1e9 for u, a, b in zip(units, fetch_ms, flush_ms)]
         eff_io = round(sum(eff) / len(eff), 2) if eff else None
         if cache is not None:
             B.mlpo_stream_flush(table, cfg)
@@ -400,6 +421,12 @@ def streamed_bench(args, torch, B, W, np):
             desc = {"mode": "direct", "direct_blocks": chunk}
         elif n_slots == "dg":
             desc = {"mode": "direct, gradients on the host too (16 B/param in, 12 out)", "direct_blocks": chunk}
+        elif n_slots == "dga":
+            desc = {"mode": "direct, gradients on the host too, statistics from the last accumulation "
+                            "(14 B/param in, 12 out)", "direct_blocks": chunk}
+        elif n_slots == "sg":
+            desc = {"mode": "staged, gradients on the host too (16 B/param in, 12 out)", "n_slots": 3,
+                    "chunk_elems": chunk}
         else:
             desc = {"mode": "staged", "n_slots": n_slots, "chunk_elems": chunk}
         rec = {**desc, "steps": len(times), "ms_per_step": round(mean * 1e3, 2),
@@ -408,8 +435,11 @@ def streamed_bench(args, torch, B, W, np):
             rec.update({"pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
                         "frac_of_one_way_memcpy": round(gbs / memcpy_peak, 4),
                         "effective_io_GBs_paper_formula": eff_io})
-            if n_slots == "dg":   # the gradients cross the link twice (gradient pass and update): 16 B in, 12 B out
+            if n_slots in ("dg", "sg"):   # the gradients cross the link twice (gradient pass, update): 16 B in, 12 out
                 rec.update({"pcie_in_GBs": round(16 * n_host_params / mean / 1e9, 2),
+                            "pcie_out_GBs": round(12 * n_host_params / mean / 1e9, 2)})
+            if n_slots == "dga":
+                rec.update({"pcie_in_GBs": round(14 * n_host_params / mean / 1e9, 2),
                             "pcie_out_GBs": round(12 * n_host_params / mean / 1e9, 2)})
         else:
             # fewer subgroups cross the link: the useful figure is the step time; the link rate is what was moved
@@ -421,14 +451,64 @@ def streamed_bench(args, torch, B, W, np):
     # the cached runs move less data, so their "GB/s" is not a link rate: the best link rate is among the others
     best = max((r for r in out["runs"] if "pcie_GBs_per_dir" in r), key=lambda r: r["pcie_GBs_per_dir"])
     out["best"] = best
+    del table, host_g_table, sgs
+    out["grad_accumulate"] = accumulate_bench(torch, B, g_flat, p16_flat, wl)
     return out
+
+
+def accumulate_bench(torch, B, acc_dev, g_dev, wl):
+    """mlpo_grad_accumulate at the shard's size: the accumulation buffer in HBM (6 bytes of HBM traffic per element)
+    and in pinned host memory (2 bytes per element over the link in each direction), 4 micro-batches each."""
+    n = acc_dev.numel()
+    M = wl.sub_elems
+    res = {"elements": n, "micro_batches": 4}
+    B.mlpo_set_option("time_kernels", 1)
+    for j in range(5):          # the first call (first=True: a copy, 4 bytes per element) doubles as warm-up
+        B.mlpo_grad_accumulate(acc_dev, g_dev, n, first=(j == 0))
+    torch.cuda.synchronize()
+    ms = B.mlpo_kernel_times(4)[1:]
+    avg = sum(ms) / len(ms)
+    res["hbm"] = {"avg_launch_ms": round(avg, 4), "achieved_GBs": round(6 * n / avg / 1e6, 1),
+                  "frac_hbm_peak": round(6 * n / avg / 1e6 / HBM_PEAK_GBS, 4), "bytes_per_element": 6}
+    host = torch.empty(wl.n_host * M, dtype=torch.int16, pin_memory=True)
+    nh = host.numel()
+    best = None
+    for blocks in (32, 64, 128):
+        for j in range(5):
+            B.mlpo_grad_accumulate(host, g_dev[:nh], nh, first=(j == 0), blocks=blocks)
+        torch.cuda.synchronize()
+        ms = B.mlpo_kernel_times(4)[1:]
+        avg = sum(ms) / len(ms)
+        rec = {"blocks": blocks, "elements": nh, "avg_launch_ms": round(avg, 3),
+               "pcie_GBs_per_dir": round(2 * nh / avg / 1e6, 2),
+               "frac_nominal": round(2 * nh / avg / 1e6 / PCIE_NOMINAL_GBS, 4)}
+        res.setdefault("pinned_host", []).append(rec)
+        if best is None or rec["pcie_GBs_per_dir"] > best["pcie_GBs_per_dir"]:
+            best = rec
+    ws_bytes = B.mlpo_norm_workspace_bytes()
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=acc_dev.device)
+    for label, buf, nn, blocks in (("hbm_with_statistics", acc_dev, n, 0), ("pinned_host_with_statistics", host, nh, 64)):
+        for j in range(4):
+            B.mlpo_grad_accumulate_norm(buf, g_dev[:nn], nn, False, blocks, 1.0, ws, ws_bytes, True)
+        torch.cuda.synchronize()
+        ms = B.mlpo_kernel_times(4)[1:]
+        avg = sum(ms) / len(ms)
+        res[label] = {"avg_launch_ms": round(avg, 3), "blocks": blocks}
+        if blocks:
+            res[label]["pcie_GBs_per_dir"] = round(2 * nn / avg / 1e6, 2)
+        else:
+            res[label]["achieved_GBs"] = round(6 * nn / avg / 1e6, 1)
+    B.mlpo_set_option("time_kernels", 0)
+    res["pinned_host_best"] = best
+    log(f"[bench] grad_accumulate {res}")
+    return res
 
 
 def parse_variants(text):
     res = []
     for part in text.split(","):
         a, _, b = part.partition(":")
-        res.append((a if a in ("d", "c", "dg") else int(a), int(b or 0)))
+        res.append((a if a in ("d", "c", "dg", "sg", "dga") else int(a), int(b or 0)))
     return res
 
 
@@ -442,10 +522,12 @@ def main():
                     help="fp32 state layout(s) to time; the first is the headline figure")
     ap.add_argument("--tile", type=int, default=8192, help="tile_elems of the tiled layout")
     ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
-    ap.add_argument("--stream-variants", default="2:16777216,3:0,3:16777216,4:16777216,d:64,d:128,dg:64,c:4,c:8",
+    ap.add_argument("--stream-variants", default="2:16777216,3:0,3:16777216,4:16777216,d:64,d:128,dg:64,dga:64,sg:16777216,c:4,c:8",
                     help="comma list of n_slots:chunk_elems (staged mode), d:blocks (direct mode), dg:blocks (direct "
-                         "mode, gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep "
-                         "their subgroups and alternating order)")
+                         "mode, gradients in pinned host memory too), dga:blocks (the same with the gradient statistics "
+                         "left by the last accumulation instead of a gradient pass), sg:chunk_elems (staged mode with 3 slots, "
+                         "gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep their "
+                         "subgroups and alternating order)")
     ap.add_argument("--stream-warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-subgroups", type=int, default=9)

@@ -150,6 +150,31 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
 int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks, void* stream);
 
 /*
+ * The same accumulation, which also gathers the gradient statistics of the finished buffer, for the LAST micro-batch
+ * of a step: the values it stores are the step's gradients, so their sum of squares (unscaled by inv_scale) and
+ * their non-finite flag are taken from registers and mlpo_grad_unscale_norm need not read the buffer again (2 bytes
+ * per element saved: over the link when the buffer is in host memory).  Calls for the pieces of one step (one per
+ * subgroup, say) add up in the workspace in call order; mlpo_grad_norm_finish then writes the same record as
+ * mlpo_grad_unscale_norm would over all the pieces together.
+ *   acc, g, n, first, blocks   as for mlpo_grad_accumulate (first != 0: a step with a single micro-batch).  The grid
+ *                is always persistent here (blocks = 0: eight workgroups per compute unit).
+ *   inv_scale    1 / loss scale; the same value in every call of the step and in mlpo_grad_norm_finish.
+ *   workspace    device, as for mlpo_grad_unscale_norm (same size and alignment); holds the running totals between
+ *                the calls, so nothing else may use it until mlpo_grad_norm_finish has run.
+ *   begin        != 0 in the first call of a step: the running totals start from zero.
+ * n = 0 with begin != 0 just resets the totals.  All calls of a step go to the same stream, or are ordered otherwise.
+ * Errors: MLPO_EINVAL, MLPO_ENOMEM, MLPO_EHIP.
+ */
+int mlpo_grad_accumulate_norm(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks,
+                              float inv_scale, void* workspace, size_t workspace_bytes, int32_t begin, void* stream);
+
+/* Derives norm, clip coefficient, gradient multiplier and flag (see mlpo_grad_unscale_norm) from the totals that the
+ * mlpo_grad_accumulate_norm calls of this step left in workspace, and writes them to out (device, 16-byte aligned).
+ * Errors: MLPO_EINVAL, MLPO_ENOMEM, MLPO_EHIP. */
+int mlpo_grad_norm_finish(void* workspace, size_t workspace_bytes, float inv_scale, float max_norm,
+                          mlpo_step_scalars* out, void* stream);
+
+/*
  * AdamW on HBM-resident subgroups, in place, with the gradient upcast and the parameter downcast fused in
  * (Algorithm 1's convert / update / push steps; Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion").
  * With the per-step scalars (computed on the host in fp64 and rounded once to fp32)

@@ -23,7 +23,7 @@ TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_state_pack", "mlpo_state_unpack",
            "mlpo_norm_workspace_bytes",
-           "mlpo_grad_unscale_norm", "mlpo_grad_accumulate",
+           "mlpo_grad_unscale_norm", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm", "mlpo_grad_norm_finish",
            "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers",
            "mlpo_update_bandwidth", "mlpo_set_option",
            "mlpo_kernel_times",
@@ -113,6 +113,11 @@ def lib():
                                              C.c_void_p, C.c_void_p]
         L.mlpo_grad_accumulate.restype = C.c_int
         L.mlpo_grad_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p]
+        L.mlpo_grad_accumulate_norm.restype = C.c_int
+        L.mlpo_grad_accumulate_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_float,
+                                                C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+        L.mlpo_grad_norm_finish.restype = C.c_int
+        L.mlpo_grad_norm_finish.argtypes = [C.c_void_p, C.c_size_t, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         L.mlpo_adamw_step.restype = C.c_int
         L.mlpo_adamw_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(HParamsC), C.c_int64, C.c_void_p, C.c_void_p]
         L.mlpo_stream_staging_bytes.restype = C.c_size_t
@@ -292,6 +297,20 @@ def mlpo_grad_accumulate(acc, g, n: Optional[int] = None, first: bool = False, b
     if n is None:
         n = g.numel()
     _check(lib().mlpo_grad_accumulate(_ptr(acc), _ptr(g), int(n), 1 if first else 0, int(blocks), _stream(stream)))
+
+
+def mlpo_grad_accumulate_norm(acc, g, n: Optional[int], first: bool, blocks: int, inv_scale: float, workspace,
+                              workspace_bytes: int, begin: bool, stream=None) -> None:
+    """The last micro-batch of a step: accumulate and gather the gradient statistics; see mlpo.h."""
+    if n is None:
+        n = g.numel()
+    _check(lib().mlpo_grad_accumulate_norm(_ptr(acc), _ptr(g), int(n), 1 if first else 0, int(blocks), inv_scale,
+                                           _ptr(workspace), int(workspace_bytes), 1 if begin else 0, _stream(stream)))
+
+
+def mlpo_grad_norm_finish(workspace, workspace_bytes: int, inv_scale: float, max_norm: float, out, stream=None) -> None:
+    _check(lib().mlpo_grad_norm_finish(_ptr(workspace), int(workspace_bytes), inv_scale, max_norm, _ptr(out),
+                                       _stream(stream)))
 
 
 def mlpo_set_option(key: str, value: int) -> None:

@@ -5,7 +5,12 @@
 // 6 bytes per element (4 read, 2 written; 4 for the first micro-batch), so the kernel is shaped like the update:
 // 128-bit non-temporal accesses, one 8192-element tile per workgroup, or a bounded number of persistent workgroups
 // when the buffer sits in pinned host memory and the traffic crosses the link.
+//
+// The last micro-batch of a step can also produce the statistics of the finished buffer (sum of squares of the
+// unscaled values, non-finite flag) from the values it has in registers, which saves the gradient pass its own read
+// of the buffer - over the link when the buffer is on the host.
 #include <hip/hip_ext.h>
+#include <math.h>
 
 #include "mlpo_internal.h"
 
@@ -41,12 +46,61 @@ __device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 g) {
     return r;
 }
 
-// acc and g point at the 16-byte aligned vector body; n8 = number of 8-element vectors in it.
-template <bool FIRST>
+// Statistics of one stored word (two new bf16 values): squares of the unscaled values in fp64, non-finite test on
+// the exponent field - the arithmetic of the gradient pass, applied to values that are in registers anyway.
+__device__ __forceinline__ void stats_word(uint32_t w, float inv_scale, double& sum, uint32_t& bad) {
+    bad |= (uint32_t)((w & 0x7F80u) == 0x7F80u) | (uint32_t)((w & 0x7F800000u) == 0x7F800000u);
+    const float u0 = __uint_as_float(w << 16) * inv_scale;
+    const float u1 = __uint_as_float(w & 0xFFFF0000u) * inv_scale;
+    sum = fma((double)u0, (double)u0, sum);
+    sum = fma((double)u1, (double)u1, sum);
+}
+
+__device__ __forceinline__ void stats_vec(u32x4 r, float inv_scale, double& sum, uint32_t& bad) {
+    stats_word(r.x, inv_scale, sum, bad);
+    stats_word(r.y, inv_scale, sum, bad);
+    stats_word(r.z, inv_scale, sum, bad);
+    stats_word(r.w, inv_scale, sum, bad);
+}
+
+// Lanes -> wavefront (shuffle), wavefronts -> workgroup (LDS), in a fixed order; one partial per workgroup.
+__device__ __forceinline__ void block_partial(double sum, uint32_t bad, NormWorkspace* __restrict__ ws, uint32_t slot) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        sum += __shfl_down(sum, off, 64);
+        bad |= (uint32_t)__shfl_down((int)bad, off, 64);
+    }
+    __shared__ double s_sum[kBlock / 64];
+    __shared__ uint32_t s_bad[kBlock / 64];
+    const uint32_t tid = threadIdx.x;
+    if ((tid & 63u) == 0) {
+        s_sum[tid >> 6] = sum;
+        s_bad[tid >> 6] = bad;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double t = s_sum[0];
+        uint32_t f = s_bad[0];
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) {
+            t += s_sum[w];
+            f |= s_bad[w];
+        }
+        ws->partial[slot] = t;
+        ws->flag[slot] = f;
+    }
+}
+
+// acc and g point at the 16-byte aligned vector body; n8 = number of 8-element vectors in it.  With STATS every
+// workgroup also leaves the statistics of the values it stored in ws->partial / ws->flag [slot0 + blockIdx.x].
+template <bool FIRST, bool STATS>
 __global__ void __launch_bounds__(kBlock) accumulate_v8_kernel(u32x4* __restrict__ acc, const u32x4* __restrict__ g,
-                                                               const uint64_t n8) {
+                                                               const uint64_t n8, const float inv_scale,
+                                                               NormWorkspace* __restrict__ ws, const uint32_t slot0) {
     const uint64_t per_tile = (uint64_t)kBlock * kUnroll;
     const uint64_t tiles = (n8 + per_tile - 1) / per_tile;
+    double sum = 0.0;
+    uint32_t bad = 0;
     for (uint64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
         const uint64_t base = tile * per_tile + threadIdx.x;
         if ((tile + 1) * per_tile <= n8) {
@@ -57,47 +111,67 @@ __global__ void __launch_bounds__(kBlock) accumulate_v8_kernel(u32x4* __restrict
                 if (!FIRST) a[u] = __builtin_nontemporal_load(acc + base + (uint64_t)u * kBlock);
             }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                __builtin_nontemporal_store(FIRST ? b[u] : add_vec(a[u], b[u]), acc + base + (uint64_t)u * kBlock);
+            for (int u = 0; u < kUnroll; ++u) {
+                const u32x4 r = FIRST ? b[u] : add_vec(a[u], b[u]);
+                __builtin_nontemporal_store(r, acc + base + (uint64_t)u * kBlock);
+                if (STATS) stats_vec(r, inv_scale, sum, bad);
+            }
         } else {
             for (int u = 0; u < kUnroll; ++u) {
                 const uint64_t i = base + (uint64_t)u * kBlock;
                 if (i < n8) {
-                    const u32x4 b = __builtin_nontemporal_load(g + i);
-                    if (FIRST) {
-                        __builtin_nontemporal_store(b, acc + i);
-                    } else {
-                        const u32x4 a = __builtin_nontemporal_load(acc + i);
-                        __builtin_nontemporal_store(add_vec(a, b), acc + i);
-                    }
+                    u32x4 r = __builtin_nontemporal_load(g + i);
+                    if (!FIRST) r = add_vec(__builtin_nontemporal_load(acc + i), r);
+                    __builtin_nontemporal_store(r, acc + i);
+                    if (STATS) stats_vec(r, inv_scale, sum, bad);
                 }
             }
         }
     }
+    if (STATS) block_partial(sum, bad, ws, slot0 + blockIdx.x);
 }
 
 // Element-wise form for heads, tails and buffers whose addresses differ modulo 16.
-template <bool FIRST>
+template <bool FIRST, bool STATS>
 __global__ void __launch_bounds__(kBlock) accumulate_v1_kernel(uint16_t* __restrict__ acc,
-                                                               const uint16_t* __restrict__ g, const uint64_t n) {
+                                                               const uint16_t* __restrict__ g, const uint64_t n,
+                                                               const float inv_scale, NormWorkspace* __restrict__ ws,
+                                                               const uint32_t slot0) {
     const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride)
-        acc[i] = FIRST ? g[i] : (uint16_t)add_one(acc[i], g[i]);
+    double sum = 0.0;
+    uint32_t bad = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        const uint32_t r = FIRST ? (uint32_t)g[i] : add_one(acc[i], g[i]);
+        acc[i] = (uint16_t)r;
+        if (STATS) {
+            bad |= (uint32_t)((r & 0x7F80u) == 0x7F80u);
+            const float u = __uint_as_float(r << 16) * inv_scale;
+            sum = fma((double)u, (double)u, sum);
+        }
+    }
+    if (STATS) block_partial(sum, bad, ws, slot0 + blockIdx.x);
 }
 
-template <bool FIRST>
-int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t st) {
+template <bool FIRST, bool STATS>
+int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t st, NormWorkspace* ws,
+           float inv_scale, int* n_partials) {
     const int cus = num_cus();
     if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
-    const uint32_t scalar_cap = blocks > 0 ? (uint32_t)blocks : (uint32_t)cus * 8u;
+    // every workgroup of a statistics launch owns one partial, so those grids are persistent and leave room for
+    // the two single-workgroup launches of head and tail
+    uint32_t persistent = blocks > 0 ? (uint32_t)blocks : (uint32_t)cus * 8u;
+    if (persistent > (uint32_t)kNormMaxPartials - 2u) persistent = (uint32_t)kNormMaxPartials - 2u;
+    uint32_t slot = 0;
     const uintptr_t a_addr = reinterpret_cast<uintptr_t>(acc);
     const uintptr_t g_addr = reinterpret_cast<uintptr_t>(g);
     if (((a_addr ^ g_addr) & 15u) != 0) {
         // no common 16-byte phase: everything goes element by element
         const uint64_t want = (n + kBlock - 1) / kBlock;
-        const uint32_t grid = (uint32_t)(want < scalar_cap ? want : scalar_cap);
-        hipLaunchKernelGGL(accumulate_v1_kernel<FIRST>, dim3(grid), dim3(kBlock), 0, st, acc, g, n);
+        const uint32_t grid = (uint32_t)(want < persistent ? want : persistent);
+        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS>), dim3(grid), dim3(kBlock), 0, st, acc, g, n, inv_scale,
+                           ws, slot);
         MLPO_HIP(hipGetLastError());
+        if (STATS) *n_partials = (int)grid;
         return MLPO_OK;
     }
     uint64_t head = ((16u - (a_addr & 15u)) & 15u) / 2u;
@@ -107,33 +181,46 @@ int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t
     if (n8 > 0) {
         const uint64_t per_tile = (uint64_t)kBlock * kUnroll;
         const uint64_t tiles = (n8 + per_tile - 1) / per_tile;
-        const uint64_t cap = blocks > 0 ? (uint64_t)blocks : 0x7FFFFFFFull;
+        const uint64_t cap = (blocks > 0 || STATS) ? (uint64_t)persistent : 0x7FFFFFFFull;
         const uint32_t grid = (uint32_t)(tiles < cap ? tiles : cap);
         u32x4* av = reinterpret_cast<u32x4*>(acc + head);
         const u32x4* gv = reinterpret_cast<const u32x4*>(g + head);
         hipEvent_t t0, t1;
         if (timing_enabled() && timing_acquire(kTimedAccumulate, &t0, &t1))
-            hipExtLaunchKernelGGL(accumulate_v8_kernel<FIRST>, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, av, gv, n8);
+            hipExtLaunchKernelGGL((accumulate_v8_kernel<FIRST, STATS>), dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, av,
+                                  gv, n8, inv_scale, ws, slot);
         else
-            hipLaunchKernelGGL(accumulate_v8_kernel<FIRST>, dim3(grid), dim3(kBlock), 0, st, av, gv, n8);
+            hipLaunchKernelGGL((accumulate_v8_kernel<FIRST, STATS>), dim3(grid), dim3(kBlock), 0, st, av, gv, n8,
+                               inv_scale, ws, slot);
         MLPO_HIP(hipGetLastError());
+        slot += grid;
     }
     if (head > 0) {
-        hipLaunchKernelGGL(accumulate_v1_kernel<FIRST>, dim3(1), dim3(kBlock), 0, st, acc, g, head);
+        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS>), dim3(1), dim3(kBlock), 0, st, acc, g, head, inv_scale,
+                           ws, slot);
         MLPO_HIP(hipGetLastError());
+        slot += 1;
     }
     if (tail > 0) {
         const uint64_t off = head + n8 * 8u;
-        hipLaunchKernelGGL(accumulate_v1_kernel<FIRST>, dim3(1), dim3(kBlock), 0, st, acc + off, g + off, tail);
+        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS>), dim3(1), dim3(kBlock), 0, st, acc + off, g + off, tail,
+                           inv_scale, ws, slot);
         MLPO_HIP(hipGetLastError());
+        slot += 1;
     }
+    if (STATS) *n_partials = (int)slot;
     return MLPO_OK;
 }
 
 }  // namespace
 
-int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st) {
-    return first ? launch<true>(acc, g, n, blocks, st) : launch<false>(acc, g, n, blocks, st);
+int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st,
+                           NormWorkspace* stats, float inv_scale, int* n_partials) {
+    if (stats != nullptr)
+        return first ? launch<true, true>(acc, g, n, blocks, st, stats, inv_scale, n_partials)
+                     : launch<false, true>(acc, g, n, blocks, st, stats, inv_scale, n_partials);
+    return first ? launch<true, false>(acc, g, n, blocks, st, nullptr, 1.0f, nullptr)
+                 : launch<false, false>(acc, g, n, blocks, st, nullptr, 1.0f, nullptr);
 }
 
 }  // namespace mlpo

@@ -165,6 +165,24 @@ int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, i
     return MLPO_OK;
 }
 
+static int check_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t blocks) {
+    if (acc == nullptr || g == nullptr) return fail(MLPO_EINVAL, "acc or g is NULL");
+    if (misaligned(acc, 2) || misaligned(g, 2)) return fail(MLPO_EINVAL, "acc or g not 2-byte aligned");
+    if (n > (1ull << 44)) return fail(MLPO_EINVAL, "n too large");
+    if (blocks < 0 || blocks > 4096) return fail(MLPO_EINVAL, "blocks must be 0..4096 (got %d)", blocks);
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(acc), g0 = reinterpret_cast<uintptr_t>(g);
+    if (a0 < g0 + 2 * n && g0 < a0 + 2 * n) return fail(MLPO_EINVAL, "acc and g overlap");
+    return MLPO_OK;
+}
+
+static int check_norm_workspace(void* workspace, size_t workspace_bytes) {
+    if (workspace == nullptr || misaligned(workspace, 256))
+        return fail(MLPO_EINVAL, "workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < grad_norm_workspace_bytes())
+        return fail(MLPO_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, grad_norm_workspace_bytes());
+    return MLPO_OK;
+}
+
 }  // namespace mlpo
 
 using namespace mlpo;
@@ -216,23 +234,48 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
     if (rc != MLPO_OK) return rc;
     if (!(isfinite(inv_scale) && inv_scale > 0.0f)) return fail(MLPO_EINVAL, "inv_scale must be finite and > 0");
     if (isnan(max_norm)) return fail(MLPO_EINVAL, "max_norm is NaN");
-    if (workspace == nullptr || misaligned(workspace, 256))
-        return fail(MLPO_EINVAL, "workspace is NULL or not 256-byte aligned");
-    if (workspace_bytes < grad_norm_workspace_bytes())
-        return fail(MLPO_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, grad_norm_workspace_bytes());
+    rc = check_norm_workspace(workspace, workspace_bytes);
+    if (rc != MLPO_OK) return rc;
     if (out == nullptr || misaligned(out, 16)) return fail(MLPO_EINVAL, "out is NULL or not 16-byte aligned");
     return launch_grad_norm(sg, n_sg, inv_scale, max_norm, workspace, out, static_cast<hipStream_t>(stream));
 }
 
 int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks, void* stream) {
     if (n == 0) return MLPO_OK;
-    if (acc == nullptr || g == nullptr) return fail(MLPO_EINVAL, "acc or g is NULL");
-    if (misaligned(acc, 2) || misaligned(g, 2)) return fail(MLPO_EINVAL, "acc or g not 2-byte aligned");
-    if (n > (1ull << 44)) return fail(MLPO_EINVAL, "n too large");
-    if (blocks < 0 || blocks > 4096) return fail(MLPO_EINVAL, "blocks must be 0..4096 (got %d)", blocks);
-    const uintptr_t a0 = reinterpret_cast<uintptr_t>(acc), g0 = reinterpret_cast<uintptr_t>(g);
-    if (a0 < g0 + 2 * n && g0 < a0 + 2 * n) return fail(MLPO_EINVAL, "acc and g overlap");
+    const int rc = check_accumulate(acc, g, n, blocks);
+    if (rc != MLPO_OK) return rc;
     return launch_grad_accumulate(acc, g, n, first != 0, blocks, static_cast<hipStream_t>(stream));
+}
+
+int mlpo_grad_accumulate_norm(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks,
+                              float inv_scale, void* workspace, size_t workspace_bytes, int32_t begin, void* stream) {
+    int rc = check_norm_workspace(workspace, workspace_bytes);
+    if (rc != MLPO_OK) return rc;
+    if (!(isfinite(inv_scale) && inv_scale > 0.0f)) return fail(MLPO_EINVAL, "inv_scale must be finite and > 0");
+    if (n != 0) {
+        rc = check_accumulate(acc, g, n, blocks);
+        if (rc != MLPO_OK) return rc;
+    }
+    NormWorkspace* ws = static_cast<NormWorkspace*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int n_partials = 0;
+    if (n != 0) {
+        rc = launch_grad_accumulate(acc, g, n, first != 0, blocks, st, ws, inv_scale, &n_partials);
+        if (rc != MLPO_OK) return rc;
+    }
+    if (n_partials == 0 && begin == 0) return MLPO_OK;
+    return launch_norm_fold(ws, n_partials, begin != 0, false, inv_scale, 0.0f, nullptr, st);
+}
+
+int mlpo_grad_norm_finish(void* workspace, size_t workspace_bytes, float inv_scale, float max_norm,
+                          mlpo_step_scalars* out, void* stream) {
+    const int rc = check_norm_workspace(workspace, workspace_bytes);
+    if (rc != MLPO_OK) return rc;
+    if (!(isfinite(inv_scale) && inv_scale > 0.0f)) return fail(MLPO_EINVAL, "inv_scale must be finite and > 0");
+    if (isnan(max_norm)) return fail(MLPO_EINVAL, "max_norm is NaN");
+    if (out == nullptr || misaligned(out, 16)) return fail(MLPO_EINVAL, "out is NULL or not 16-byte aligned");
+    return launch_norm_fold(static_cast<NormWorkspace*>(workspace), 0, false, true, inv_scale, max_norm, out,
+                            static_cast<hipStream_t>(stream));
 }
 
 int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hparams* hp, int64_t step,

@@ -22,7 +22,6 @@ constexpr int kBlock = 256;
 constexpr int kUnroll = 4;
 constexpr uint32_t kTile = kBlock * 8 * kUnroll;  // body elements per tile
 constexpr int kMaxSg = 96;
-constexpr int kMaxGrid = 4096;
 
 struct NormBatch {
     const uint16_t* body[kMaxSg];  // 16-byte aligned start of the vector body
@@ -32,15 +31,8 @@ struct NormBatch {
     int32_t n_sg;
 };
 
-// Workspace layout (device).
-struct Workspace {
-    double running_sum;
-    uint32_t running_flag;
-    uint32_t pad[61];
-    double partial[kMaxGrid];
-    uint32_t flag[kMaxGrid];
-};
-static_assert(offsetof(Workspace, partial) == 256, "layout");
+using Workspace = NormWorkspace;
+constexpr int kMaxGrid = kNormMaxPartials;
 
 __device__ __forceinline__ void accum_word(uint32_t w, float inv_scale, double& acc, uint32_t& bad) {
     bad |= (uint32_t)((w & 0x7F80u) == 0x7F80u) | (uint32_t)((w & 0x7F800000u) == 0x7F800000u);
@@ -189,13 +181,18 @@ int flush(const NormBatch& b, bool first, bool last, float inv_scale, float max_
             hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws);
         MLPO_HIP(hipGetLastError());
     }
-    hipLaunchKernelGGL(grad_finish_kernel, dim3(1), dim3(kBlock), 0, st, ws, (int)grid, first ? 1 : 0, last ? 1 : 0,
+    return launch_norm_fold(ws, (int)grid, first, last, inv_scale, max_norm, out, st);
+}
+
+}  // namespace
+
+int launch_norm_fold(NormWorkspace* ws, int n_partials, bool first, bool last, float inv_scale, float max_norm,
+                     mlpo_step_scalars* out, hipStream_t st) {
+    hipLaunchKernelGGL(grad_finish_kernel, dim3(1), dim3(kBlock), 0, st, ws, n_partials, first ? 1 : 0, last ? 1 : 0,
                        inv_scale, max_norm, out);
     MLPO_HIP(hipGetLastError());
     return MLPO_OK;
 }
-
-}  // namespace
 
 size_t grad_norm_workspace_bytes() { return sizeof(Workspace); }
 

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "mlpo.h"
@@ -73,8 +74,27 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
                      mlpo_step_scalars* out, hipStream_t stream);
 size_t grad_norm_workspace_bytes();
 
-// Enqueues acc = first ? g : bf16(acc + g) over n elements; blocks > 0 bounds the persistent grid.
-int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st);
+// Device workspace of the gradient statistics: per-workgroup partial sums of squares (fp64) and non-finite flags,
+// and the running totals that a one-block kernel folds them into in index order.
+constexpr int kNormMaxPartials = 4096;
+struct NormWorkspace {
+    double running_sum;
+    uint32_t running_flag;
+    uint32_t pad[61];
+    double partial[kNormMaxPartials];
+    uint32_t flag[kNormMaxPartials];
+};
+static_assert(offsetof(NormWorkspace, partial) == 256, "layout");
+// Folds partial[0..n_partials) into the running totals (first: the totals start at zero); last: derives norm, clip
+// coefficient, gradient multiplier and flag from the totals and writes them to out (out may be NULL otherwise).
+int launch_norm_fold(NormWorkspace* ws, int n_partials, bool first, bool last, float inv_scale, float max_norm,
+                     mlpo_step_scalars* out, hipStream_t st);
+
+// Enqueues acc = first ? g : bf16(acc + g) over n elements; blocks > 0 bounds the persistent grid.  With stats the
+// kernels also leave the statistics of the new acc values (unscaled by inv_scale) as partials in stats and
+// *n_partials says how many; the grid is then always persistent.
+int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st,
+                           NormWorkspace* stats = nullptr, float inv_scale = 1.0f, int* n_partials = nullptr);
 
 inline bool host_tier(int32_t tier) { return tier == MLPO_TIER_HOST || tier == MLPO_TIER_HOST_GRADS; }
 

@@ -190,3 +190,20 @@ def test_staging_size_counts_host_side_gradients():
     tiled = [B.tiled_subgroup(FAKE, FAKE + (1 << 30), FAKE + (2 << 30), n=5000, tier=B.TIER_HOST_GRADS, tile_elems=2048)]
     assert B.mlpo_stream_staging_bytes(tiled, 1, 0) == 3 * 6144 * 4 + 5120 * 2
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(tier=B.TIER_HOST_GRADS)], B.HParams(), 1)
+
+
+def test_accumulate_norm_argument_errors():
+    ws = B.mlpo_norm_workspace_bytes()
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate_norm, FAKE, FAKE + 4096, 16, False, 0, 1.0, 0, ws, True)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate_norm, FAKE, FAKE + 4096, 16, False, 0, 1.0, FAKE + 64, ws, True)
+    expect(B.MLPO_ENOMEM, B.mlpo_grad_accumulate_norm, FAKE, FAKE + 4096, 16, False, 0, 1.0, FAKE, ws - 1, True)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate_norm, FAKE, FAKE + 4096, 16, False, 0, 0.0, FAKE, ws, True)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate_norm, FAKE, FAKE + 8, 16, False, 0, 1.0, FAKE, ws, True)   # overlap
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate_norm, 0, FAKE + 4096, 16, False, 0, 1.0, FAKE, ws, True)
+    B.mlpo_grad_accumulate_norm(0, 0, 0, False, 0, 1.0, FAKE, ws, False)          # nothing to add, nothing to reset
+    expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, 0, ws, 1.0, 0.0, FAKE)
+    expect(B.MLPO_ENOMEM, B.mlpo_grad_norm_finish, FAKE, 16, 1.0, 0.0, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, FAKE, ws, float("nan"), 0.0, FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, FAKE, ws, 1.0, float("nan"), FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, FAKE, ws, 1.0, 0.0, 0)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, FAKE, ws, 1.0, 0.0, FAKE + 8)

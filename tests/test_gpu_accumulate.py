@@ -132,3 +132,101 @@ def test_micro_batches_on_the_host_then_update(oracle):
             assert np.array_equal(got.view(np.uint16), host[k]["g"]), f"accumulated gradients sg={k}"
     for k in range(wl.n_sub):
         assert_state_parity(ds.fetch(k), host[k], f"accumulate then update sg={k}")
+
+
+def _norm_of(oracle, arrays, inv_scale, max_norm):
+    sumsq, flag = 0.0, 0
+    for a in arrays:
+        sumsq, flag = oracle.grad_stats(a, inv_scale, sumsq, flag)
+    return oracle.norm_finish(sumsq, inv_scale, max_norm) + (flag,)
+
+
+@pytest.mark.parametrize("sizes,first,blocks,max_norm", [
+    ([100_003], False, 0, 0.0), ([100_003], True, 0, 0.5), ([8192 * 4 * 3, 5, 70_001], False, 0, 0.01),
+    ([1, 9, 17], False, 3, 0.0), ([300_000, 0, 123_457, 1 << 20], False, 16, 0.02), ([0, 0], False, 0, 1.0),
+])
+def test_last_micro_batch_also_gives_the_norm(oracle, sizes, first, blocks, max_norm):
+    """mlpo_grad_accumulate_norm over several pieces + mlpo_grad_norm_finish: the accumulated buffers bit-exact, the
+    scalars as the oracle's gradient statistics over the oracle's accumulated buffers."""
+    rng = np.random.default_rng(sum(sizes) + blocks)
+    inv_scale = 1.0 / 256.0
+    scratch = Scratch()
+    accs, gs, dev_acc, dev_g = [], [], [], []
+    for j, n in enumerate(sizes):
+        a = oracle.f32_to_bf16_rne((rng.standard_normal(n) * 0.3).astype(np.float32))
+        g = oracle.f32_to_bf16_rne((rng.standard_normal(n) * 0.3).astype(np.float32))
+        accs.append(a)
+        gs.append(g)
+        if j % 2 == 1 and n:      # every other piece keeps its buffer in pinned host memory
+            t = torch.empty(n, dtype=torch.int16, pin_memory=True)
+            t.copy_(torch.from_numpy(a.view(np.int16)))
+        else:
+            t = to_dev(a)
+        dev_acc.append(t)
+        dev_g.append(to_dev(g))
+    # poison the workspace: begin must reset whatever an earlier step left there
+    scratch.ws.fill_(0xFF)
+    torch.cuda.synchronize()
+    for j, n in enumerate(sizes):
+        B.mlpo_grad_accumulate_norm(dev_acc[j], dev_g[j], n, first, blocks, inv_scale, scratch.ws, scratch.ws_bytes,
+                                    begin=(j == 0))
+    B.mlpo_grad_norm_finish(scratch.ws, scratch.ws_bytes, inv_scale, max_norm, scratch.scalars)
+    torch.cuda.synchronize()
+    for a, g in zip(accs, gs):
+        oracle.grad_accumulate(a, g, first)
+    norm_o, coef_o, gmul_o, flag_o = _norm_of(oracle, accs, inv_scale, max_norm)
+    for j, n in enumerate(sizes):
+        got = dev_acc[j].numpy() if not dev_acc[j].is_cuda else dev_acc[j].cpu().numpy()
+        assert np.array_equal(got.view(np.uint16), accs[j]), f"piece {j}"
+    sc = scratch.read()
+    assert sc["found_inf"] == flag_o == 0
+    assert abs(float(sc["norm"]) - float(norm_o)) <= 1e-5 * float(norm_o)
+    assert sc["clip_coef"] == coef_o and sc["gmul"] == gmul_o
+    # and the separate gradient pass over the same buffers agrees
+    if sum(sizes):
+        table = B.SubgroupTable(B.subgroup(0, 0, 0, t, 0, n=n) for t, n in zip(dev_acc, sizes))
+        other = Scratch()
+        B.mlpo_grad_unscale_norm(table, inv_scale, max_norm, other.ws, other.ws_bytes, other.scalars, None)
+        torch.cuda.synchronize()
+        o = other.read()
+        assert abs(float(o["norm"]) - float(sc["norm"])) <= 2e-7 * float(norm_o) and o["gmul"] == sc["gmul"]
+
+
+def test_norm_of_exact_sums(oracle):
+    # 4^9 ones plus 4^9 ones: every element becomes 2, the norm is exactly 2 * 2^9
+    n = 4 ** 9
+    scratch = Scratch()
+    acc = to_dev(np.full(n, 0x3F80, np.uint16))
+    g = to_dev(np.full(n, 0x3F80, np.uint16))
+    B.mlpo_grad_accumulate_norm(acc, g, n, False, 0, 1.0, scratch.ws, scratch.ws_bytes, True)
+    B.mlpo_grad_norm_finish(scratch.ws, scratch.ws_bytes, 1.0, 0.0, scratch.scalars)
+    torch.cuda.synchronize()
+    sc = scratch.read()
+    assert sc["norm"] == np.float32(1024.0) and sc["found_inf"] == 0 and sc["gmul"] == np.float32(1.0)
+    assert np.all(back(acc) == 0x4000)
+
+
+@pytest.mark.parametrize("where,a_bits,g_bits", [
+    (0, 0x7F7F, 0x7F7F),          # the sum overflows to +inf in the first element
+    (-1, 0x7F80, 0xFF80),         # inf - inf = NaN in the last element (a scalar tail)
+    (12_345, 0x3F80, 0x7FC1),     # a NaN gradient in the vector body
+    (3, 0xFF80, 0x3F80),          # the buffer already held -inf, in the unaligned head
+])
+def test_non_finite_sums_raise_the_flag(oracle, where, a_bits, g_bits):
+    n = 50_001
+    rng = np.random.default_rng(5)
+    a = oracle.f32_to_bf16_rne(rng.standard_normal(n).astype(np.float32))
+    g = oracle.f32_to_bf16_rne(rng.standard_normal(n).astype(np.float32))
+    a[where], g[where] = a_bits, g_bits
+    scratch = Scratch()
+    base_a = torch.zeros(n + 8, dtype=torch.int16, device=dev())
+    base_g = torch.zeros(n + 8, dtype=torch.int16, device=dev())
+    base_a[5:5 + n].copy_(to_dev(a))
+    base_g[5:5 + n].copy_(to_dev(g))
+    B.mlpo_grad_accumulate_norm(base_a[5:], base_g[5:], n, False, 0, 1.0, scratch.ws, scratch.ws_bytes, True)
+    B.mlpo_grad_norm_finish(scratch.ws, scratch.ws_bytes, 1.0, 1.0, scratch.scalars)
+    torch.cuda.synchronize()
+    oracle.grad_accumulate(a, g, False)
+    assert np.array_equal(back(base_a)[5:5 + n], a)
+    _, flag = oracle.grad_stats(a, 1.0)
+    assert flag == 1 and scratch.read()["found_inf"] == 1
