@@ -142,9 +142,9 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
  *   g       bf16 gradients of this micro-batch, n elements, device memory (pinned host memory also works).
  *           Must not overlap acc.  Both 2-byte aligned; the 128-bit path needs acc and g congruent modulo 16 bytes,
  *           otherwise every element is moved on its own (much slower).
- *   blocks  0: one workgroup per 8192 elements (device buffers).  > 0: that many persistent workgroups (<= 4096),
+ *   blocks  0: one workgroup per 2048 elements (device buffers).  > 0: that many persistent workgroups (<= 4096),
  *           which bounds the requests in flight on the link when acc is on the host; 64 is a good value there.
- *   stream  hipStream_t.  Asynchronous.  n = 0 is a no-op.
+ *   stream  hipStream_t.  Asynchronous.  n = 0 is a no-op; n is at most 2^41.
  * Errors: MLPO_EINVAL, MLPO_EHIP.
  */
 int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks, void* stream);

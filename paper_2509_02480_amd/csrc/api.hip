@@ -168,7 +168,7 @@ int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, i
 static int check_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t blocks) {
     if (acc == nullptr || g == nullptr) return fail(MLPO_EINVAL, "acc or g is NULL");
     if (misaligned(acc, 2) || misaligned(g, 2)) return fail(MLPO_EINVAL, "acc or g not 2-byte aligned");
-    if (n > (1ull << 44)) return fail(MLPO_EINVAL, "n too large");
+    if (n > (1ull << 41)) return fail(MLPO_EINVAL, "n too large (at most 2^41 elements per call)");
     if (blocks < 0 || blocks > 4096) return fail(MLPO_EINVAL, "blocks must be 0..4096 (got %d)", blocks);
     const uintptr_t a0 = reinterpret_cast<uintptr_t>(acc), g0 = reinterpret_cast<uintptr_t>(g);
     if (a0 < g0 + 2 * n && g0 < a0 + 2 * n) return fail(MLPO_EINVAL, "acc and g overlap");
