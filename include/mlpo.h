@@ -35,6 +35,7 @@ extern "C" {
 #define MLPO_EINVAL (-1) /* NULL / misaligned pointer, bad size, bad hyper-parameter, bad tier */
 #define MLPO_EHIP (-2)   /* a HIP runtime call failed; mlpo_last_error() names it */
 #define MLPO_ENOMEM (-3) /* a caller-provided workspace or staging buffer is too small */
+#define MLPO_EIO (-4)    /* reading or writing a file-tier subgroup failed; mlpo_last_error() gives errno's text */
 
 /* AdamW hyper-parameters, fp32 as stored.  bias_correction != 0 applies the 1 - beta^t corrections. */
 typedef struct {
@@ -54,6 +55,11 @@ typedef struct {
  * 12 out) and in direct mode reads them in place; the upcast happens in registers as always.  A MLPO_TIER_HOST
  * subgroup whose g is pinned host memory is also accepted by mlpo_grad_unscale_norm and by direct mode.
  *
+ * MLPO_TIER_FILE: the fp32 state lives in a file (the slower alternative path of the offloaded tier, Section 3.2
+ * "Unified Multi-level, Multi-path Asynchronous Offloading Using Virtual Tiers"); p, m, v must be NULL, the layout
+ * must be tiled, and mlpo_stream_cfg.files says where the state is.  g and p16 are device memory.  Accepted by
+ * mlpo_stream_update in direct mode only.
+ *
  * Layout of the fp32 state, chosen by tile_elems:
  *   0      planar: p, m, v are three independent arrays of n floats.
  *   T > 0  tiled: the state of the subgroup is ONE buffer of mlpo_state_floats(n, T) floats that starts at p and
@@ -66,6 +72,7 @@ typedef struct {
 #define MLPO_TIER_HBM 0
 #define MLPO_TIER_HOST 1
 #define MLPO_TIER_HOST_GRADS 2
+#define MLPO_TIER_FILE 3
 #define MLPO_TILE_DEFAULT 8192
 typedef struct {
     float* p;
@@ -132,7 +139,7 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
 
 /*
  * Gradient accumulation over micro-batches into the half-precision accumulation buffer that the update later
- * upcasts on the fly (Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"; Section 4.6 runs 1-16
+ * upcasts on the fly (Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"; Section 4.5 runs 1-16
  * backward passes per update).  For every i < n:
  *   first != 0:  acc[i] = g[i]                                  (first micro-batch of a step: no clearing pass needed)
  *   first == 0:  acc[i] = bf16_rne(f32(acc[i]) + f32(g[i]))     (one fp32 addition; a NaN sum is stored as 0x7FC0)
@@ -220,6 +227,26 @@ typedef struct {
     uint64_t fetches, flushes, hits;     /* transfers issued and transfers saved since the cache was first used */
 } mlpo_slot_cache;
 
+/* Where the fp32 state of a MLPO_TIER_FILE subgroup lives: mlpo_state_floats(n, tile_elems) floats in the tiled
+ * layout, starting offset bytes into the open file fd (offset a multiple of 4096).  The library only calls pread and
+ * pwrite on the descriptor and never closes it.  A descriptor opened with O_DIRECT is served through page-aligned
+ * blocks of the library's own, because memory pinned by the HIP runtime cannot be the target of direct I/O. */
+typedef struct {
+    int32_t fd;
+    int32_t reserved; /* must be 0 */
+    uint64_t offset;
+} mlpo_file_extent;
+
+/* What the file path of one mlpo_stream_update call did: bytes read and written, the time its threads spent
+ * inside pread / pwrite (summed over the threads of a direction) and the wall time from the first read to the end of
+ * the last write.  Section 3.3: the observed bandwidth of a path, B_i = bytes / seconds, is what
+ * mlpo_update_bandwidth takes; bytes_read / wall_seconds is the rate at which the path delivered subgroups. */
+typedef struct {
+    uint64_t bytes_read, bytes_written;
+    double read_seconds, write_seconds;
+    double wall_seconds;
+} mlpo_file_stats;
+
 /* Configuration of the tiered pipeline.
  * mode MLPO_STREAM_STAGED: host-tier subgroups are fetched into device staging slots by asynchronous copies, updated
  *   there and flushed back (three stages on three streams, at most n_slots subgroups or chunks in flight).
@@ -245,10 +272,25 @@ typedef struct {
     int32_t direct_blocks; /* direct: persistent workgroups on the host tier; 0 = default (64); at most 4096 */
     int32_t reserved;      /* must be 0 */
     mlpo_slot_cache* cache; /* staged, chunk_elems == 0: slots keep their subgroups between steps; NULL = off */
+    /* The file path (direct mode; all zero / NULL when no subgroup is MLPO_TIER_FILE): */
+    const mlpo_file_extent* files; /* host array with one entry per subgroup of the table; only the entries of
+                                      MLPO_TIER_FILE subgroups are read */
+    void* bounce;          /* pinned host memory (hipHostMalloc), 4096-byte aligned, caller-owned: file_slots buffers
+                              through which file-tier pieces pass (read from the file, updated in place by the
+                              kernel over the link, written back) */
+    size_t bounce_bytes;   /* >= mlpo_stream_bounce_bytes(...) */
+    int32_t file_slots;    /* 1..MLPO_MAX_SLOTS: bound on file-tier pieces in flight; 3 lets read, update and write
+                              overlap */
+    int32_t file_threads;  /* threads per direction that move the pieces between file and bounce buffers, each an
+                              equal share of every piece; 0 = default (2); at most 16 */
+    mlpo_file_stats* file_stats; /* host pointer or NULL: receives what the file path moved and how long it took */
 } mlpo_stream_cfg;
 
 /* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier). */
 size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems);
+
+/* Bounce bytes needed for the MLPO_TIER_FILE subgroups under this file_slots / chunk_elems (0 if there are none). */
+size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t file_slots, uint64_t chunk_elems);
 
 /*
  * One update phase over subgroups of both tiers (Algorithm 1, with the fetch / update / flush overlap of Section 3.4
@@ -261,6 +303,16 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
  * state in place.  Results are bit-identical to the resident path whatever mode, n_slots, chunk_elems, direct_blocks
  * and order are.
  *
+ * File-tier subgroups (direct mode): reading threads bring pieces of at most chunk_elems elements (0 = whole
+ * subgroups) from the file into free bounce buffers, the update kernel works on a bounce buffer in place over the
+ * link with direct_blocks workgroups, and writing threads put the piece back into the file once its kernel has
+ * finished; a bounce buffer is refilled only after its piece has been written, so at most file_slots pieces are in
+ * flight (the three-stage overlap of Section 3.4 on this path).  Host-tier and file-tier work share the link, so
+ * their kernels go to one stream, in pieces of chunk_elems, a file-tier piece as soon as it has been read and
+ * host-tier pieces in between: the disk works while the link is busy with the host tier (the multi-path overlap of
+ * Section 3.2).  With file-tier subgroups the call returns only when their state is back in the file; the rest is
+ * enqueued as usual.
+ *
  *   order        host array, a permutation of 0..n_sg-1 giving the processing order, or NULL for ascending.
  *   scalars      device pointer or NULL, as for mlpo_adamw_step.  When given, the call first copies the record to the
  *                host (a 16-byte copy and a wait on the compute stream) because the transfers are issued from the
@@ -270,7 +322,8 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
  *                mlpo_stream_cfg.d2h about leaving the two copy streams to the library.
  * On return everything is enqueued; the compute stream is made to wait for the last copy back, so synchronising
  * cfg->compute alone is enough to see the final state.  Calls sharing a staging buffer must not overlap.
- * Errors: MLPO_EINVAL, MLPO_ENOMEM (staging too small), MLPO_EHIP.
+ * Errors: MLPO_EINVAL, MLPO_ENOMEM (staging or bounce too small), MLPO_EHIP, MLPO_EIO (a read or write failed or
+ * was short; the file-tier state is then undefined for the pieces in flight).
  */
 int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
                        int64_t step, const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, int32_t* applied);

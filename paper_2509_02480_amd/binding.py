@@ -15,8 +15,8 @@ from typing import Iterable, Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmlpo.so")
 
-MLPO_OK, MLPO_EINVAL, MLPO_EHIP, MLPO_ENOMEM = 0, -1, -2, -3
-TIER_HBM, TIER_HOST, TIER_HOST_GRADS = 0, 1, 2
+MLPO_OK, MLPO_EINVAL, MLPO_EHIP, MLPO_ENOMEM, MLPO_EIO = 0, -1, -2, -3, -4
+TIER_HBM, TIER_HOST, TIER_HOST_GRADS, TIER_FILE = 0, 1, 2, 3
 MAX_SLOTS = 64
 
 TILE_DEFAULT = 8192
@@ -24,7 +24,7 @@ TILE_DEFAULT = 8192
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_state_pack", "mlpo_state_unpack",
            "mlpo_norm_workspace_bytes",
            "mlpo_grad_unscale_norm", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm", "mlpo_grad_norm_finish",
-           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers",
+           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_bounce_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers",
            "mlpo_update_bandwidth", "mlpo_set_option",
            "mlpo_kernel_times",
            "mlpo_shutdown")
@@ -57,11 +57,22 @@ class SlotCacheC(C.Structure):
                 ("hits", C.c_uint64)]
 
 
+class FileExtentC(C.Structure):
+    _fields_ = [("fd", C.c_int32), ("reserved", C.c_int32), ("offset", C.c_uint64)]
+
+
+class FileStatsC(C.Structure):
+    _fields_ = [("bytes_read", C.c_uint64), ("bytes_written", C.c_uint64), ("read_seconds", C.c_double),
+                ("write_seconds", C.c_double), ("wall_seconds", C.c_double)]
+
+
 class StreamCfgC(C.Structure):
     _fields_ = [("n_slots", C.c_int32), ("mode", C.c_int32), ("chunk_elems", C.c_uint64),
                 ("staging", C.c_void_p), ("staging_bytes", C.c_size_t), ("h2d", C.c_void_p), ("compute", C.c_void_p),
                 ("d2h", C.c_void_p), ("direct_blocks", C.c_int32), ("reserved", C.c_int32),
-                ("cache", C.POINTER(SlotCacheC))]
+                ("cache", C.POINTER(SlotCacheC)), ("files", C.POINTER(FileExtentC)), ("bounce", C.c_void_p),
+                ("bounce_bytes", C.c_size_t), ("file_slots", C.c_int32), ("file_threads", C.c_int32),
+                ("file_stats", C.POINTER(FileStatsC))]
 
 
 @dataclass
@@ -122,6 +133,8 @@ def lib():
         L.mlpo_adamw_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(HParamsC), C.c_int64, C.c_void_p, C.c_void_p]
         L.mlpo_stream_staging_bytes.restype = C.c_size_t
         L.mlpo_stream_staging_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64]
+        L.mlpo_stream_bounce_bytes.restype = C.c_size_t
+        L.mlpo_stream_bounce_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64]
         L.mlpo_stream_update.restype = C.c_int
         L.mlpo_stream_update.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(HParamsC), C.c_int64,
                                          C.c_void_p, C.POINTER(StreamCfgC), C.POINTER(C.c_int32)]
@@ -241,17 +254,39 @@ def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chu
     """Staged mode: host-tier subgroups travel through ``n_slots`` device staging slots.  ``cache`` (a zero-initialised
     SlotCacheC kept by the caller) lets slots keep their subgroups between steps."""
     cfg = StreamCfgC(n_slots, STREAM_STAGED, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d),
-                     _stream(compute), _stream(d2h), 0, 0, None)
+                     _stream(compute), _stream(d2h), 0, 0, None, None, None, 0, 0, 0, None)
     if cache is not None:
         cfg.cache = C.pointer(cache)
         cfg._keep = cache
     return cfg
 
 
-def direct_cfg(host_stream, compute, direct_blocks: int = 0) -> StreamCfgC:
-    """Direct mode: the kernel updates the pinned host state in place with ``direct_blocks`` persistent workgroups."""
-    return StreamCfgC(0, STREAM_DIRECT, 0, None, 0, _stream(host_stream), _stream(compute), _stream(compute),
-                      direct_blocks, 0, None)
+def direct_cfg(host_stream, compute, direct_blocks: int = 0, chunk_elems: int = 0, files=None, bounce=None,
+               bounce_bytes: int = 0, file_slots: int = 0, want_file_stats: bool = False,
+               file_threads: int = 0) -> StreamCfgC:
+    """Direct mode: the kernel updates the pinned host state in place with ``direct_blocks`` persistent workgroups.
+    ``files`` (one (fd, offset) pair or None per subgroup), ``bounce`` (pinned host tensor) and ``file_slots``
+    configure the file path; ``cfg.stats`` then holds what it moved after each call if ``want_file_stats``."""
+    cfg = StreamCfgC(0, STREAM_DIRECT, chunk_elems, None, 0, _stream(host_stream), _stream(compute), _stream(compute),
+                     direct_blocks, 0, None, None, _ptr(bounce), bounce_bytes, file_slots, file_threads, None)
+    if files is not None:
+        arr = (FileExtentC * max(len(files), 1))()
+        for i, f in enumerate(files):
+            if f is not None:
+                arr[i] = FileExtentC(int(f[0]), 0, int(f[1]))
+            else:
+                arr[i] = FileExtentC(-1, 0, 0)
+        cfg.files = arr
+        cfg._files = arr
+    if want_file_stats:
+        cfg.stats = FileStatsC()
+        cfg.file_stats = C.pointer(cfg.stats)
+    return cfg
+
+
+def mlpo_stream_bounce_bytes(sgs, file_slots: int, chunk_elems: int = 0) -> int:
+    t = _table(sgs)
+    return int(lib().mlpo_stream_bounce_bytes(t.array, t.n, file_slots, chunk_elems))
 
 
 def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: int, scalars, cfg: StreamCfgC) -> bool:

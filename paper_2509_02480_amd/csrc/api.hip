@@ -143,10 +143,21 @@ int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, i
         if (s.n != 0 && s.g == nullptr) return fail(MLPO_EINVAL, "subgroup %d: g is NULL", i);
         if (misaligned(s.g, 2)) return fail(MLPO_EINVAL, "subgroup %d: g is not 2-byte aligned", i);
         if (grads_only) continue;
-        if (s.tier != MLPO_TIER_HBM && !host_tier(s.tier))
+        if (s.tier != MLPO_TIER_HBM && !host_tier(s.tier) && s.tier != MLPO_TIER_FILE)
             return fail(MLPO_EINVAL, "subgroup %d: unknown tier %d", i, s.tier);
-        if (host_tier(s.tier) && !allow_host)
+        if (host_tier(s.tier) && allow_host < 1)
             return fail(MLPO_EINVAL, "subgroup %d is host-tier: use mlpo_stream_update", i);
+        if (s.tier == MLPO_TIER_FILE) {
+            if (allow_host < 2) return fail(MLPO_EINVAL, "subgroup %d is file-tier: use mlpo_stream_update", i);
+            if (s.p != nullptr || s.m != nullptr || s.v != nullptr)
+                return fail(MLPO_EINVAL, "subgroup %d: a file-tier subgroup has no p/m/v pointers", i);
+            if (s.tile_elems <= 0 || s.tile_elems % 1024 != 0)
+                return fail(MLPO_EINVAL, "subgroup %d: a file-tier subgroup needs the tiled layout", i);
+            if (s.n != 0 && s.p16 == nullptr) return fail(MLPO_EINVAL, "subgroup %d: p16 is NULL", i);
+            if (misaligned(s.g, 8) || misaligned(s.p16, 8))
+                return fail(MLPO_EINVAL, "subgroup %d: tiled state needs 8-byte aligned g and p16", i);
+            continue;
+        }
         if (s.n != 0 && (s.p == nullptr || s.m == nullptr || s.v == nullptr || s.p16 == nullptr))
             return fail(MLPO_EINVAL, "subgroup %d: NULL state pointer", i);
         if (misaligned(s.p, 4) || misaligned(s.m, 4) || misaligned(s.v, 4))

@@ -1,0 +1,67 @@
+// The file path of the offloaded tier (internal to libmlpo; see filetier.hip).
+#pragma once
+
+#include <condition_variable>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "mlpo_internal.h"
+
+namespace mlpo {
+
+// One piece of a file-tier subgroup: where it lives in the file and the bounce buffer it passes through.
+struct FileJob {
+    int fd;
+    uint64_t file_off;
+    size_t bytes;
+    void* buffer;  // its bounce buffer (pinned host); job i uses buffer i % n_slots
+    SgView view;   // the kernel's view of the piece in that buffer
+};
+
+// Reads the jobs in order into their bounce buffers and writes each back after its kernel has finished, with
+// n_threads threads per direction that each move an equal share of every piece.  Job i may be read once job
+// i - n_slots has been written (the buffer is the same), so at most n_slots pieces are in flight.
+// The owner launches the kernels: it learns from is_read / wait_read that a piece has arrived and reports the event
+// that marks the end of the piece's kernel with hand_to_writer.
+class FilePath {
+  public:
+    FilePath(std::vector<FileJob> jobs, int n_slots, int n_threads, int device);
+    ~FilePath();
+    FilePath(const FilePath&) = delete;
+    FilePath& operator=(const FilePath&) = delete;
+
+    void start();
+    size_t size() const { return jobs_.size(); }
+    const FileJob& job(size_t i) const { return jobs_[i]; }
+    bool is_read(size_t i);                         // never blocks
+    bool wait_read(size_t i);                       // false: the path has stopped and the piece will not arrive
+    bool failed();
+    void hand_to_writer(size_t i, hipEvent_t done);  // done: recorded behind the piece's kernel
+    // Waits for both threads.  false: something failed, *error says what.
+    bool join(mlpo_file_stats* stats, std::string* error);
+
+  private:
+    void read_loop(int r);
+    void write_loop(int r);
+    void join_threads();
+    void fail_with(const std::string& why);
+
+    std::vector<FileJob> jobs_;
+    int n_slots_, n_threads_, device_;
+    std::mutex mu_;
+    std::condition_variable cv_;
+    std::vector<int> read_, launched_, written_;  // read_ / written_: threads that have moved their share
+    std::vector<hipEvent_t> done_;
+    bool stopped_ = false;
+    std::string error_;
+    std::vector<std::thread> threads_;
+    uint64_t bytes_read_ = 0, bytes_written_ = 0;
+    double read_seconds_ = 0.0, write_seconds_ = 0.0, t_begin_ = 0.0, t_end_ = 0.0;
+};
+
+// Argument check of one extent: alignment, a regular file, long enough for state_bytes behind offset.
+int check_file_extent(const mlpo_file_extent& x, uint64_t state_bytes, int index);
+
+}  // namespace mlpo

@@ -45,7 +45,8 @@ struct AdamwConsts {
     float beta1, beta2, omb1, omb2, eps, step_size, sqbc2, decay;
 };
 int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step);
-// Pointer / size / tier checks shared by the entry points; grads_only checks g and n alone.
+// Pointer / size / tier checks shared by the entry points; grads_only checks g and n alone.  allow_host: 0 = only
+// HBM-tier subgroups, 1 = host tiers too, 2 = file tier too.
 int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, int allow_host);
 bool misaligned(const void* p, uintptr_t a);
 uint64_t round_up(uint64_t x, uint64_t to);

@@ -4,8 +4,10 @@
 #include <string.h>
 
 #include <mutex>
+#include <string>
 #include <vector>
 
+#include "filetier.h"
 #include "mlpo_internal.h"
 
 namespace mlpo {
@@ -22,6 +24,8 @@ struct EventCache {
     hipEvent_t fence2 = nullptr;
     hipStream_t copy_in = nullptr;   // the library's own copy streams, used when the caller passes none
     hipStream_t copy_out = nullptr;
+    std::vector<hipEvent_t> file_done;  // one per bounce buffer: the end of the kernel that updated it
+    hipEvent_t pace[2] = {nullptr, nullptr};  // bound the launches queued on the link stream (file path)
 };
 static EventCache& events() {
     static EventCache c;
@@ -41,6 +45,12 @@ static int release_events_locked(EventCache& c) {
     if (c.copy_in) (void)hipStreamDestroy(c.copy_in);
     if (c.copy_out) (void)hipStreamDestroy(c.copy_out);
     c.copy_in = c.copy_out = nullptr;
+    for (hipEvent_t e : c.file_done) (void)hipEventDestroy(e);
+    c.file_done.clear();
+    for (hipEvent_t& e : c.pace) {
+        if (e) (void)hipEventDestroy(e);
+        e = nullptr;
+    }
     c.device = -1;
     return MLPO_OK;
 }
@@ -64,6 +74,17 @@ static int ensure_events_locked(EventCache& c, int n_slots) {
     return MLPO_OK;
 }
 
+
+static int ensure_file_events_locked(EventCache& c, int file_slots) {
+    while ((int)c.file_done.size() < file_slots) {
+        hipEvent_t e;
+        MLPO_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        c.file_done.push_back(e);
+    }
+    for (hipEvent_t& e : c.pace)
+        if (e == nullptr) MLPO_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    return MLPO_OK;
+}
 
 // Floats the fp32 state of a piece of len elements takes in a staging slot: three arrays, each rounded so that the
 // arrays of a slot keep their alignment (planar) or to whole layout tiles (tiled).
@@ -91,6 +112,19 @@ static uint64_t slot_floats_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t 
     return mx;
 }
 
+
+// Bytes of one bounce buffer: the largest piece of any file-tier subgroup (whole layout tiles).
+static uint64_t bounce_slot_bytes(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems) {
+    uint64_t mx = 0;
+    for (int32_t i = 0; i < n_sg; ++i)
+        if (sg[i].tier == MLPO_TIER_FILE && sg[i].tile_elems > 0) {
+            uint64_t len = sg[i].n;
+            if (chunk_elems != 0 && chunk_elems < len) len = chunk_elems;
+            const uint64_t b = state_floats_of(sg[i], len) * sizeof(float);
+            if (b > mx) mx = b;
+        }
+    return round_up(mx, 4096);
+}
 
 // One piece (a whole subgroup or a chunk of one) of a host-tier subgroup and the staging slot it occupies.
 struct Piece {
@@ -203,6 +237,7 @@ struct Plan {
     std::vector<SgView> resident;    // HBM-tier subgroups
     std::vector<SgView> host_views;  // host-tier subgroups as the device sees them in place (direct mode)
     std::vector<int32_t> host_ids;   // their indices in the caller's table
+    std::vector<int32_t> file_ids;   // file-tier subgroups
 };
 
 struct Streams {
@@ -212,7 +247,7 @@ struct Streams {
 static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order,
                              const mlpo_adamw_hparams* hp, int64_t step, const mlpo_step_scalars* scalars,
                              const mlpo_stream_cfg* cfg, uint64_t* slot_floats_out) {
-    int rc = validate_subgroups(sg, n_sg, false, /*allow_host=*/1);
+    int rc = validate_subgroups(sg, n_sg, false, /*allow_host=*/2);
     if (rc != MLPO_OK) return rc;
     rc = validate_hparams(hp, step);
     if (rc != MLPO_OK) return rc;
@@ -235,9 +270,32 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
             seen[(size_t)order[i]] = 1;
         }
     }
-    for (int32_t i = 0; i < n_sg; ++i)
-        if (host_tier(sg[i].tier) && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
+    bool any_file = false;
+    for (int32_t i = 0; i < n_sg; ++i) {
+        const bool offloaded = host_tier(sg[i].tier) || sg[i].tier == MLPO_TIER_FILE;
+        if (offloaded && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
             return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
+        any_file = any_file || sg[i].tier == MLPO_TIER_FILE;
+    }
+    if (cfg->file_threads < 0 || cfg->file_threads > 16)
+        return fail(MLPO_EINVAL, "file_threads must be 0..16 (got %d)", cfg->file_threads);
+    if (any_file) {
+        if (!direct) return fail(MLPO_EINVAL, "file-tier subgroups need direct mode");
+        if (cfg->files == nullptr) return fail(MLPO_EINVAL, "file-tier subgroups but cfg->files is NULL");
+        if (cfg->file_slots < 1 || cfg->file_slots > MLPO_MAX_SLOTS)
+            return fail(MLPO_EINVAL, "file_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->file_slots);
+        if (cfg->bounce == nullptr || misaligned(cfg->bounce, 4096))
+            return fail(MLPO_EINVAL, "bounce is NULL or not 4096-byte aligned");
+        const uint64_t need_bounce = bounce_slot_bytes(sg, n_sg, cfg->chunk_elems) * (uint64_t)cfg->file_slots;
+        if (cfg->bounce_bytes < need_bounce)
+            return fail(MLPO_ENOMEM, "bounce has %zu bytes, %llu needed", cfg->bounce_bytes,
+                        (unsigned long long)need_bounce);
+        for (int32_t i = 0; i < n_sg; ++i)
+            if (sg[i].tier == MLPO_TIER_FILE && sg[i].n != 0) {
+                rc = check_file_extent(cfg->files[i], state_floats_of(sg[i], sg[i].n) * sizeof(float), i);
+                if (rc != MLPO_OK) return rc;
+            }
+    }
     const uint64_t slot_floats = direct ? 0 : slot_floats_for(sg, n_sg, cfg->chunk_elems);
     const uint64_t need = slot_floats * 4u * (uint64_t)(direct ? 0 : cfg->n_slots);
     if (need > 0) {
@@ -277,6 +335,107 @@ static int run_direct(const Plan& plan, const AdamwConsts& c, const mlpo_step_sc
         MLPO_HIP(hipEventRecord(ec.fence, st.h2d));
         MLPO_HIP(hipStreamWaitEvent(st.cmp, ec.fence, 0));
     }
+    return MLPO_OK;
+}
+
+// Direct mode with file-tier subgroups: two paths behind the offloaded tier (Section 3.2 "Unified Multi-level,
+// Multi-path Asynchronous Offloading using Virtual Tiers").  Both end on the link, so their kernels share one stream:
+// host-tier subgroups cut into pieces of chunk_elems, and file-tier pieces, each launched as soon as its read has
+// finished.  At most two launches are queued at a time, so a piece that arrives from the file waits for one
+// host-tier piece at most, and the file keeps working while the link is busy with the host tier.
+static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const AdamwConsts& c,
+                            const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, const Streams& st,
+                            EventCache& ec) {
+    int rc = ensure_file_events_locked(ec, cfg->file_slots);
+    if (rc != MLPO_OK) return rc;
+    int device = 0;
+    MLPO_HIP(hipGetDevice(&device));
+    const int blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 64;
+    const uint64_t chunk = cfg->chunk_elems;
+
+    // the file path's jobs, in processing order
+    uint64_t buf_bytes = 0;
+    for (int32_t i : plan.file_ids) {
+        uint64_t len = sg[i].n;
+        if (chunk != 0 && chunk < len) len = chunk;
+        const uint64_t b = round_up(state_floats_of(sg[i], len) * sizeof(float), 4096);
+        if (b > buf_bytes) buf_bytes = b;
+    }
+    std::vector<FileJob> jobs;
+    for (int32_t i : plan.file_ids) {
+        const mlpo_subgroup& s = sg[i];
+        const uint64_t T = (uint64_t)s.tile_elems;
+        const uint64_t step_elems = (chunk != 0 && chunk < s.n) ? chunk : s.n;
+        for (uint64_t off = 0; off < s.n; off += step_elems) {
+            const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
+            FileJob j;
+            j.fd = cfg->files[i].fd;
+            j.file_off = cfg->files[i].offset + (off / T) * 3u * T * sizeof(float);
+            j.bytes = (size_t)(round_up(len, T) * 3u * sizeof(float));
+            char* buf = static_cast<char*>(cfg->bounce) + (jobs.size() % (size_t)cfg->file_slots) * buf_bytes;
+            float* f = reinterpret_cast<float*>(buf);
+            j.buffer = buf;
+            j.view = SgView{f, f + T, f + 2 * T, s.g + off, s.p16 + off, len, s.tile_elems};
+            jobs.push_back(j);
+        }
+    }
+    // the host path's pieces
+    std::vector<SgView> host_pieces;
+    for (const SgView& v : plan.host_views) {
+        const uint64_t step_elems = (chunk != 0 && chunk < v.n) ? chunk : v.n;
+        for (uint64_t off = 0; off < v.n; off += step_elems) {
+            const uint64_t len = (v.n - off < step_elems) ? (v.n - off) : step_elems;
+            SgView piece = v;
+            if (v.tile_elems > 0) {
+                const uint64_t shift = (off / (uint64_t)v.tile_elems) * 3u * (uint64_t)v.tile_elems;
+                piece.p += shift;
+                piece.m += shift;
+                piece.v += shift;
+            } else {
+                piece.p += off;
+                piece.m += off;
+                piece.v += off;
+            }
+            piece.g += off;
+            piece.p16 += off;
+            piece.n = len;
+            host_pieces.push_back(piece);
+        }
+    }
+
+    MLPO_HIP(hipEventRecord(ec.fence2, st.cmp));  // gradients and scalars come from the compute stream
+    MLPO_HIP(hipStreamWaitEvent(st.h2d, ec.fence2, 0));
+    FilePath files(std::move(jobs), cfg->file_slots, cfg->file_threads > 0 ? cfg->file_threads : 2, device);
+    files.start();
+    if (!plan.resident.empty()) {
+        rc = launch_adamw(plan.resident.data(), (int)plan.resident.size(), c, scalars, st.cmp);
+        if (rc != MLPO_OK) return rc;
+    }
+    size_t next_host = 0, next_file = 0, launched = 0;
+    while (next_host < host_pieces.size() || next_file < files.size()) {
+        if (files.failed()) break;
+        if (next_host >= host_pieces.size() && !files.wait_read(next_file)) break;  // only the file is left
+        if (launched >= 2) MLPO_HIP(hipEventSynchronize(ec.pace[launched % 2]));    // the launch before the last
+        if (next_file < files.size() && files.is_read(next_file)) {
+            const FileJob& j = files.job(next_file);
+            rc = launch_adamw(&j.view, 1, c, scalars, st.h2d, blocks);
+            if (rc != MLPO_OK) return rc;
+            hipEvent_t done = ec.file_done[next_file % (size_t)cfg->file_slots];
+            MLPO_HIP(hipEventRecord(done, st.h2d));
+            files.hand_to_writer(next_file, done);
+            ++next_file;
+        } else {
+            rc = launch_adamw(&host_pieces[next_host], 1, c, scalars, st.h2d, blocks);
+            if (rc != MLPO_OK) return rc;
+            ++next_host;
+        }
+        MLPO_HIP(hipEventRecord(ec.pace[launched % 2], st.h2d));
+        ++launched;
+    }
+    MLPO_HIP(hipEventRecord(ec.fence, st.h2d));
+    MLPO_HIP(hipStreamWaitEvent(st.cmp, ec.fence, 0));
+    std::string err;
+    if (!files.join(cfg->file_stats, &err)) return fail(MLPO_EIO, "%s", err.c_str());
     return MLPO_OK;
 }
 
@@ -407,6 +566,11 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
     return (size_t)(slot_floats_for(sg, n_sg, chunk_elems) * 4u * (uint64_t)n_slots);
 }
 
+size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t file_slots, uint64_t chunk_elems) {
+    if (sg == nullptr || n_sg <= 0 || file_slots <= 0) return 0;
+    return (size_t)(bounce_slot_bytes(sg, n_sg, chunk_elems) * (uint64_t)file_slots);
+}
+
 int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
                        int64_t step, const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, int32_t* applied) {
     uint64_t slot_floats = 0;
@@ -437,6 +601,8 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
         const SgView v{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems};
         if (sg[i].tier == MLPO_TIER_HBM) {
             plan.resident.push_back(v);
+        } else if (sg[i].tier == MLPO_TIER_FILE) {
+            plan.file_ids.push_back(i);
         } else {
             plan.host_ids.push_back(i);
             plan.host_views.push_back(v);
@@ -445,7 +611,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
 
     EventCache& ec = events();
     std::lock_guard<std::mutex> lk(ec.mu);
-    if (plan.host_ids.empty()) {  // nothing on the host tier: this is mlpo_adamw_step
+    if (plan.host_ids.empty() && plan.file_ids.empty()) {  // nothing offloaded: this is mlpo_adamw_step
         if (plan.resident.empty()) return MLPO_OK;
         return launch_adamw(plan.resident.data(), (int)plan.resident.size(), c, scalars, st.cmp);
     }
@@ -457,6 +623,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
         st.h2d = ec.copy_in;
         st.d2h = ec.copy_out;
     }
+    if (direct && !plan.file_ids.empty()) return run_direct_files(sg, plan, c, scalars, cfg, st, ec);
     if (direct) return run_direct(plan, c, scalars, cfg, st, ec);
 
     // Work enqueued earlier on the flush and compute streams (a previous step's copy back, the gradient pass) must

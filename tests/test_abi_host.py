@@ -10,6 +10,7 @@ from paper_2509_02480_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FAKE = 0x7F0000000000  # never dereferenced: validation fails first, or n == 0
+FAKE_PAGE = 0x7F1000000000
 
 
 def header_functions():
@@ -207,3 +208,79 @@ def test_accumulate_norm_argument_errors():
     expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, FAKE, ws, 1.0, float("nan"), FAKE)
     expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, FAKE, ws, 1.0, 0.0, 0)
     expect(B.MLPO_EINVAL, B.mlpo_grad_norm_finish, FAKE, ws, 1.0, 0.0, FAKE + 8)
+
+
+def test_binding_structs_match_the_header(tmp_path):
+    """sizeof and the offsets of the last fields, printed by a C program that includes mlpo.h, against the ctypes
+    mirrors in the binding."""
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text('''
+#include <stdio.h>
+#include <stddef.h>
+#include "mlpo.h"
+int main(void) {
+    printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(mlpo_adamw_hparams), sizeof(mlpo_subgroup),
+           sizeof(mlpo_step_scalars), sizeof(mlpo_slot_cache), sizeof(mlpo_stream_cfg), sizeof(mlpo_file_extent),
+           sizeof(mlpo_file_stats), offsetof(mlpo_stream_cfg, file_stats), offsetof(mlpo_slot_cache, hits),
+           offsetof(mlpo_subgroup, tile_elems));
+    return 0;
+}
+''')
+    exe = tmp_path / "sizes"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.check_call(["gcc", "-I", inc, "-o", str(exe), str(src)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    want = [C.sizeof(B.HParamsC), C.sizeof(B.SubgroupC), C.sizeof(B.StepScalarsC), C.sizeof(B.SlotCacheC),
+            C.sizeof(B.StreamCfgC), C.sizeof(B.FileExtentC), C.sizeof(B.FileStatsC), B.StreamCfgC.file_stats.offset,
+            B.SlotCacheC.hits.offset, B.SubgroupC.tile_elems.offset]
+    assert got == want
+
+
+def test_file_tier_argument_errors(tmp_path):
+    hp = B.HParams()
+    T = 1024
+    n = 3000
+    state_bytes = B.mlpo_state_floats(n, T) * 4
+    path = tmp_path / "state.bin"
+    path.write_bytes(bytes(4096 + state_bytes))
+    fd = os.open(str(path), os.O_RDWR)
+    try:
+        filesg = B.SubgroupC(None, None, None, FAKE, FAKE + (1 << 20), n, B.TIER_FILE, T)
+        need = B.mlpo_stream_bounce_bytes([filesg], 2, 0)
+        assert need == 2 * state_bytes and state_bytes % 4096 == 0
+        assert B.mlpo_stream_bounce_bytes([filesg], 3, 1024) == 3 * 3 * 1024 * 4
+        assert B.mlpo_stream_bounce_bytes([sg(n=1000, tier=1)], 3, 0) == 0
+
+        def cfg(**kw):
+            args = dict(files=[(fd, 4096)], bounce=FAKE_PAGE, bounce_bytes=need, file_slots=2)
+            args.update(kw)
+            return B.direct_cfg(None, None, 8, **args)
+
+        expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [filesg], hp, 1)                            # needs the pipeline
+        staged = B.stream_cfg(2, FAKE, 1 << 30, None, None, None, 0)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, staged)     # needs direct mode
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, B.direct_cfg(None, None, 8))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(file_slots=0))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(file_slots=B.MAX_SLOTS + 1))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(bounce=0))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(bounce=FAKE_PAGE + 512))
+        expect(B.MLPO_ENOMEM, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(bounce_bytes=need - 1))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(files=[(fd, 100)]))   # offset
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(files=[(fd, 8192)]))  # too short
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(files=[(10_000, 0)]))  # bad fd
+        r, w = os.pipe()
+        try:
+            expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(files=[(r, 0)]))  # a pipe
+        finally:
+            os.close(r)
+            os.close(w)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(chunk_elems=1536))     # not k * T
+        with_ptr = B.SubgroupC(FAKE, FAKE + 4 * T, FAKE + 8 * T, FAKE, FAKE + (1 << 20), n, B.TIER_FILE, T)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [with_ptr], None, hp, 1, None, cfg())
+        planar = B.SubgroupC(None, None, None, FAKE, FAKE + (1 << 20), n, B.TIER_FILE, 0)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [planar], None, hp, 1, None, cfg())
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(file_threads=-1))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(file_threads=17))
+    finally:
+        os.close(fd)
