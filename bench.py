@@ -451,9 +451,108 @@ def streamed_bench(args, torch, B, W, np):
     # the cached runs move less data, so their "GB/s" is not a link rate: the best link rate is among the others
     best = max((r for r in out["runs"] if "pcie_GBs_per_dir" in r), key=lambda r: r["pcie_GBs_per_dir"])
     out["best"] = best
+    if args.multipath != "none":
+        ctx = dict(wl=wl, keep=keep, g_flat=g_flat, p16_flat=p16_flat, T=T, M=M, ws=ws, ws_bytes=ws_bytes, scal=scal,
+                   hp=hp, streams=(h2d, cmp_), applied=applied, host_GBs=best["pcie_GBs_per_dir"])
+        out["multipath"] = [multipath_bench(args, torch, B, np, ctx, kind) for kind in args.multipath.split(",")]
     del table, host_g_table, sgs
     out["grad_accumulate"] = accumulate_bench(torch, B, g_flat, p16_flat, wl)
     return out
+
+
+def multipath_bench(args, torch, B, np, ctx, kind):
+    """Two paths behind the offloaded tier (Section 3.2 "Unified Multi-level, Multi-path Asynchronous Offloading using
+    Virtual Tiers"): pinned host memory, limited to ``--pinned-capacity`` subgroups as if no more could be pinned, and
+    a file for the rest - on the machine's disk (kind "disk", O_DIRECT) or in tmpfs (kind "shm": pageable host
+    memory moved by CPU threads).  Eq. 1 (Section 3.3) splits the subgroups, the observed bandwidths re-estimate it."""
+    import os
+    import tempfile
+    wl, keep, T, M = ctx["wl"], ctx["keep"], ctx["T"], ctx["M"]
+    g_flat, p16_flat, cmp_ = ctx["g_flat"], ctx["p16_flat"], ctx["streams"][1]
+    offloaded = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
+    state_bytes = B.mlpo_state_floats(M, T) * 4
+    # Eq. 1 over the two paths, in subgroups per second; the file path's bandwidth is a guess until it has been seen
+    bw = [ctx["host_GBs"] * 1e9 / (state_bytes), args.file_GBs_guess * 1e9 / state_bytes]
+    cap = [min(args.pinned_capacity, len(offloaded)), len(offloaded)]
+    counts, _ = B.mlpo_assign_tiers(len(offloaded), bw, cap)
+    n_file = counts[1]
+    file_ids = offloaded[len(offloaded) - n_file:]
+    root = "/dev/shm" if kind == "shm" else (args.file_dir or tempfile.gettempdir())
+    path = os.path.join(root, f"mlpo_bench_state_{os.getpid()}.bin")
+    res = {"kind": kind, "file": path, "offloaded_subgroups": len(offloaded), "pinned_capacity": cap[0],
+           "eq1_bandwidth_guess_GBs": [round(ctx["host_GBs"], 2), args.file_GBs_guess],
+           "eq1_split_pinned_file": list(counts), "chunk_elems": args.multipath_chunk,
+           "file_slots": args.file_slots, "file_threads": args.file_threads}
+    fd = -1
+    try:
+        with open(path, "wb") as f:
+            for k in file_ids:
+                f.write(keep[k].numpy().tobytes())
+            f.flush()
+            os.fsync(f.fileno())
+        flags = os.O_RDWR | (os.O_DIRECT if kind == "disk" else 0)
+        fd = os.open(path, flags)
+        sgs, files = [], []
+        for k in range(wl.n_sub):
+            gk, pk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
+            if k in file_ids:
+                sgs.append(B.SubgroupC(None, None, None, gk.data_ptr(), pk.data_ptr(), M, B.TIER_FILE, T))
+                files.append((fd, file_ids.index(k) * state_bytes))
+            else:
+                sgs.append(B.tiled_subgroup(keep[k], gk, pk, n=M, tier=wl.tier(k), tile_elems=T))
+                files.append(None)
+        table = B.SubgroupTable(sgs)
+        need = B.mlpo_stream_bounce_bytes(table, args.file_slots, args.multipath_chunk)
+        bounce = torch.empty(need, dtype=torch.uint8, pin_memory=True)
+        cfg = B.direct_cfg(ctx["streams"][0], cmp_, 64, chunk_elems=args.multipath_chunk, files=files, bounce=bounce,
+                           bounce_bytes=need, file_slots=args.file_slots, file_threads=args.file_threads,
+                           want_file_stats=True)
+        times, rd, wr, wall = [], [], [], []
+        applied = ctx["applied"]
+        for s in range(args.stream_warmup + wl.steps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ctx["ws"], ctx["ws_bytes"], ctx["scal"], cmp_)
+            assert B.mlpo_stream_update(table, None, ctx["hp"], applied + 1, ctx["scal"], cfg)
+            cmp_.synchronize()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t
+            applied += 1
+            if s >= args.stream_warmup:
+                times.append(dt)
+                st = cfg.stats
+                rd.append(st.bytes_read / st.read_seconds * max(args.file_threads, 1) if st.read_seconds else 0.0)
+                wr.append(st.bytes_written / st.write_seconds * max(args.file_threads, 1) if st.write_seconds else 0.0)
+                wall.append(st.wall_seconds)
+        ctx["applied"] = applied
+        mean = sum(times) / len(times)
+        n_pinned = len(offloaded) - n_file
+        file_wall = sum(wall) / len(wall)
+        res.update({
+            "steps": len(times), "ms_per_step": round(mean * 1e3, 2), "min_ms": round(min(times) * 1e3, 2),
+            "Gparams_s": round(wl.n_total / mean / 1e9, 3),
+            "file_path_wall_ms": round(file_wall * 1e3, 2),
+            "file_read_GBs_while_reading": round(sum(rd) / len(rd) / 1e9, 2),
+            "file_write_GBs_while_writing": round(sum(wr) / len(wr) / 1e9, 2),
+            "file_path_GBs_per_dir": round(n_file * state_bytes / file_wall / 1e9, 2) if n_file else None,
+            "link_GBs_per_dir": round(len(offloaded) * state_bytes / mean / 1e9, 2),
+            "pinned_only_would_take_ms": round(n_pinned * state_bytes / (ctx["host_GBs"] * 1e9) * 1e3, 2)})
+        if n_file:
+            # Section 3.3: the next iteration's split uses the bandwidths observed in this one
+            # (only the file path was timed on its own; the host path keeps its estimate, as a path that moved
+            # nothing does)
+            new_bw = B.mlpo_update_bandwidth(bw, [0.0, float(n_file)], [0.0, file_wall])
+            res["eq1_bandwidth_observed_GBs"] = [round(x * state_bytes / 1e9, 2) for x in new_bw]
+            res["eq1_split_after_update"] = list(B.mlpo_assign_tiers(len(offloaded), new_bw, cap)[0])
+            res["eq1_split_after_update_without_capacity"] = list(B.mlpo_assign_tiers(len(offloaded), new_bw)[0])
+    finally:
+        torch.cuda.synchronize()
+        if fd >= 0:
+            os.close(fd)
+        if os.path.exists(path):
+            os.unlink(path)
+    log(f"[bench] multipath {res}")
+    return res
 
 
 def accumulate_bench(torch, B, acc_dev, g_dev, wl):
@@ -529,6 +628,16 @@ def main():
                          "gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep their "
                          "subgroups and alternating order)")
     ap.add_argument("--stream-warmup", type=int, default=2)
+    ap.add_argument("--multipath", default="disk,shm",
+                    help="comma list of file kinds for the two-path run on the streamed workload: disk (a file in "
+                         "--file-dir, O_DIRECT), shm (a file in /dev/shm), or 'none'")
+    ap.add_argument("--pinned-capacity", type=int, default=10,
+                    help="subgroups the pinned-host path may hold in the two-path run (the rest go to the file)")
+    ap.add_argument("--file-GBs-guess", type=float, default=3.0, help="initial bandwidth estimate of the file path")
+    ap.add_argument("--file-dir", default="", help="directory for the file path's file (default: the temp dir)")
+    ap.add_argument("--file-slots", type=int, default=3)
+    ap.add_argument("--file-threads", type=int, default=4)
+    ap.add_argument("--multipath-chunk", type=int, default=1 << 24)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-subgroups", type=int, default=9)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)

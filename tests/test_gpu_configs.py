@@ -9,7 +9,8 @@ relative error 1e-6, bf16 copy and flag bit-exact, norm 1e-5.
 Config 3 runs at full size.  Configs 4 and 5 run with one fifth of their subgroups (same subgroup size, same tier
 fractions).  With MLPO_FULL_SIZE=1 config 4 runs whole (84 GB of fp32 state, 43 GB of it pinned) and config 5 with
 half of its subgroups (13 host-tier subgroups = 39 GB pinned): the test machines pin at most about 70 GB of host memory,
-less than the 75 GB the whole of config 5 needs."""
+less than the 75 GB the whole of config 5 needs.  The whole of config 5 runs with the file path: 21 host-tier
+subgroups pinned and 4 in a file."""
 import os
 import time
 
@@ -44,17 +45,24 @@ def phys_index(lo, hi, T):
     return (i // T) * (3 * T) + i % T
 
 
-def run_config(oracle, wl, tile, cfg_kind, n_slots=3, chunk=0, direct_blocks=64):
+def run_config(oracle, wl, tile, cfg_kind, n_slots=3, chunk=0, direct_blocks=64, n_file=0, file_path=None):
+    """n_file > 0 (direct mode): the last n_file host-tier subgroups keep their state in the file file_path instead of
+    pinned memory (the second path of the offloaded tier)."""
     pinned = []
+    fds = []
     try:
-        _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned)
+        _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned, n_file, file_path, fds)
     finally:
         torch.cuda.synchronize()
         for b in pinned:
             b.free()
+        for fd in fds:
+            os.close(fd)
+        if file_path and os.path.exists(file_path):
+            os.unlink(file_path)
 
 
-def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned):
+def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned, n_file=0, file_path=None, fds=None):
     d = dev()
     M, T = wl.sub_elems, tile
     per = B.mlpo_state_floats(M, T)
@@ -67,9 +75,31 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
     hg = np.empty(M, np.uint16)
     states, descs, wins = [], [], []
     sumsq, flag = 0.0, 0
+    host_ids = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
+    file_ids = host_ids[len(host_ids) - n_file:] if n_file else []
+    files = [None] * wl.n_sub
+    fmap = None
+    if file_ids:
+        assert cfg_kind == "direct"
+        with open(file_path, "wb") as f:
+            f.truncate(len(file_ids) * per * 4)
+        try:
+            fds.append(os.open(file_path, os.O_RDWR | os.O_DIRECT))
+        except OSError:                     # tmpfs has no direct I/O
+            fds.append(os.open(file_path, os.O_RDWR))
+        fmap = np.memmap(file_path, dtype=np.float32, mode="r+")
+        say(f"  {len(file_ids)} of the {len(host_ids)} host-tier subgroups live in {file_path}")
     for k in range(wl.n_sub):
         W.fill_state(wl, k, tmp[:M], None, None, threads=THREADS)
-        if wl.tier(k) == 1:
+        if k in file_ids:
+            j = file_ids.index(k)
+            view = fmap[j * per:(j + 1) * per]
+            view[:] = 0
+            view.reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
+            del view
+            files[k] = (fds[0], j * per * 4)
+            st = ("file", j * per)          # read back with plain file reads once the run is over
+        elif wl.tier(k) == 1:
             buf = PinnedF32(per)
             pinned.append(buf)
             st = buf.t
@@ -88,8 +118,12 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
                          "v": np.zeros(WIN, np.float32), "g": hg[lo:lo + WIN].copy(),
                          "p16": np.zeros(WIN, np.uint16)})
         states.append(st)
-        descs.append(B.tiled_subgroup(st, g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M], n=M,
-                                      tier=wl.tier(k), tile_elems=T))
+        if k in file_ids:
+            descs.append(B.SubgroupC(None, None, None, g_flat[k * M:(k + 1) * M].data_ptr(),
+                                     p16_flat[k * M:(k + 1) * M].data_ptr(), M, B.TIER_FILE, T))
+        else:
+            descs.append(B.tiled_subgroup(st, g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M], n=M,
+                                          tier=wl.tier(k), tile_elems=T))
         if k % 5 == 4 or k == wl.n_sub - 1:
             say(f"  filled subgroup {k + 1}/{wl.n_sub}")
     assert flag == 0
@@ -97,7 +131,17 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
     table = B.SubgroupTable(descs)
     scratch = Scratch()
     streams = [torch.cuda.Stream() for _ in range(3)]
-    if cfg_kind == "direct":
+    if fmap is not None:
+        fmap.flush()            # the initial state has to be in the file before direct I/O reads it
+        os.fsync(fds[0])
+        del fmap                # no mapping of the file stays around while it is read and written directly
+    if file_ids:
+        need = B.mlpo_stream_bounce_bytes(table, 3, chunk)
+        bounce = PinnedF32(need // 4)
+        pinned.append(bounce)
+        cfg, stg = B.direct_cfg(streams[0], streams[1], direct_blocks, chunk_elems=chunk, files=files,
+                                bounce=bounce.t, bounce_bytes=need, file_slots=3, file_threads=4), None
+    elif cfg_kind == "direct":
         cfg, stg = B.direct_cfg(streams[0], streams[1], direct_blocks), None
     else:
         need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
@@ -125,7 +169,11 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
         idx = phys_index(lo, lo + WIN, T)
         st = states[k]
         for j, key in enumerate(("p", "m", "v")):
-            if st.is_cuda:
+            if isinstance(st, tuple):               # file tier
+                span = idx + j * T
+                lo_f, hi_f = int(span[0]), int(span[-1]) + 1
+                got = np.fromfile(file_path, dtype=np.float32, count=hi_f - lo_f, offset=4 * (st[1] + lo_f))[span - lo_f]
+            elif st.is_cuda:
                 got = st[torch.from_numpy(idx + j * T).to(d)].cpu().numpy()
             else:
                 got = st.numpy()[idx + j * T]
@@ -136,8 +184,9 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
         assert np.array_equal(got16, w["p16"]), f"{wl.name} subgroup {k} window {lo}: p16 differs"
     say(f"{wl.name}: {len(wins)} windows of {WIN} elements match (worst fp32 relative error {worst:.1e})")
     # untouched padding of the last layout tile stays zero
-    tail = states[-1][per - 3 * T:].cpu().numpy().reshape(3, T) if states[-1].is_cuda else \
-        states[-1].numpy()[per - 3 * T:].reshape(3, T)
+    last = states[-1]
+    assert not isinstance(last, tuple)      # the last subgroup is HBM-tier in every config
+    tail = last[per - 3 * T:].cpu().numpy().reshape(3, T) if last.is_cuda else last.numpy()[per - 3 * T:].reshape(3, T)
     used = M - (M // T) * T
     if used:
         assert not tail[:, used:].any()
@@ -151,6 +200,17 @@ def test_config3_full_size(oracle, cfg_kind, n_slots, chunk):
 def test_config4_mixed_tiers(oracle):
     wl = W.C4 if FULL else W.C4.scaled_down(5)
     run_config(oracle, wl, B.TILE_DEFAULT, "staged", n_slots=4, chunk=1 << 25)
+
+
+def test_config5_with_the_file_path(oracle, tmp_path):
+    """Config 5 with part of the offloaded tier in a file.  With MLPO_FULL_SIZE=1 the config runs WHOLE: 10 subgroups
+    in HBM, 21 in pinned host memory (63 GB, what the test machines can pin) and 4 in a 12 GB file; otherwise one
+    fifth of it with 1 of its 5 host-tier subgroups in a file."""
+    wl = W.C5 if FULL else W.C5.scaled_down(5)
+    n_file = 4 if FULL else 1
+    where = os.environ.get("MLPO_FILE_DIR", str(tmp_path))      # e.g. /dev/shm: pageable host memory as the file
+    run_config(oracle, wl, B.TILE_DEFAULT, "direct", chunk=1 << 24, n_file=n_file,
+               file_path=os.path.join(where, f"mlpo_c5_state_{os.getpid()}.bin"))
 
 
 @pytest.mark.parametrize("cfg_kind", ["staged", "direct"])
