@@ -230,7 +230,9 @@ typedef struct {
 /* Where the fp32 state of a MLPO_TIER_FILE subgroup lives: mlpo_state_floats(n, tile_elems) floats in the tiled
  * layout, starting offset bytes into the open file fd (offset a multiple of 4096).  The library only calls pread and
  * pwrite on the descriptor and never closes it.  A descriptor opened with O_DIRECT is served through page-aligned
- * blocks of the library's own, because memory pinned by the HIP runtime cannot be the target of direct I/O. */
+ * blocks of the library's own, because memory pinned by the HIP runtime cannot be the target of direct I/O; a file
+ * in tmpfs without holes (pageable host memory with a name) is copied through a mapping, which lets all the threads
+ * write at once; anything else is read and written with plain pread / pwrite. */
 typedef struct {
     int32_t fd;
     int32_t reserved; /* must be 0 */

@@ -11,6 +11,11 @@
 
 namespace mlpo {
 
+// How a descriptor's data is moved: pread / pwrite straight into the bounce buffer, the same through page-aligned
+// blocks (O_DIRECT), or copies through a mapping (fully allocated tmpfs files).
+enum class FileIo { kBuffered, kDirect, kMapped };
+FileIo file_io_kind(int fd);
+
 // One piece of a file-tier subgroup: where it lives in the file and the bounce buffer it passes through.
 struct FileJob {
     int fd;
@@ -18,6 +23,7 @@ struct FileJob {
     size_t bytes;
     void* buffer;  // its bounce buffer (pinned host); job i uses buffer i % n_slots
     SgView view;   // the kernel's view of the piece in that buffer
+    FileIo io;
 };
 
 // Reads the jobs in order into their bounce buffers and writes each back after its kernel has finished, with
@@ -32,7 +38,7 @@ class FilePath {
     FilePath(const FilePath&) = delete;
     FilePath& operator=(const FilePath&) = delete;
 
-    void start();
+    bool start();  // false: a thread could not be started (join reports why)
     size_t size() const { return jobs_.size(); }
     const FileJob& job(size_t i) const { return jobs_[i]; }
     bool is_read(size_t i);                         // never blocks

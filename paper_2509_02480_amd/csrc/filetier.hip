@@ -7,10 +7,13 @@
 #include <fcntl.h>
 #include <stdlib.h>
 #include <string.h>
+#include <sys/mman.h>
 #include <sys/stat.h>
+#include <sys/vfs.h>
 #include <unistd.h>
 
 #include <chrono>
+#include <exception>
 
 #include "filetier.h"
 
@@ -73,13 +76,25 @@ struct AlignedBlock {
     }
 };
 
-bool is_direct(int fd) {
-    const int fl = fcntl(fd, F_GETFL);
-    return fl >= 0 && (fl & O_DIRECT) != 0;
+// A fully allocated file in tmpfs is host memory with a name: its pages are copied through a mapping, which -
+// unlike write() on one inode - any number of threads can do at once.  off and bytes are multiples of 4096 here.
+bool copy_mapped(int fd, char* mem, size_t bytes, uint64_t off, bool to_file) {
+    void* m = mmap(nullptr, bytes, to_file ? (PROT_READ | PROT_WRITE) : PROT_READ, MAP_SHARED, fd, (off_t)off);
+    if (m == MAP_FAILED) return false;
+    if (to_file)
+        memcpy(m, mem, bytes);
+    else
+        memcpy(mem, m, bytes);
+    munmap(m, bytes);
+    return true;
 }
 
-bool read_range(int fd, char* dst, size_t bytes, uint64_t off, AlignedBlock& tmp) {
-    if (!is_direct(fd)) return read_fully(fd, dst, bytes, off);
+bool read_range(const FileJob& j, size_t begin, size_t bytes, AlignedBlock& tmp) {
+    const int fd = j.fd;
+    char* dst = static_cast<char*>(j.buffer) + begin;
+    uint64_t off = j.file_off + begin;
+    if (j.io == FileIo::kMapped) return copy_mapped(fd, dst, bytes, off, false);
+    if (j.io == FileIo::kBuffered) return read_fully(fd, dst, bytes, off);
     if (!tmp.ensure()) {
         errno = ENOMEM;
         return false;
@@ -95,8 +110,12 @@ bool read_range(int fd, char* dst, size_t bytes, uint64_t off, AlignedBlock& tmp
     return true;
 }
 
-bool write_range(int fd, const char* src, size_t bytes, uint64_t off, AlignedBlock& tmp) {
-    if (!is_direct(fd)) return write_fully(fd, src, bytes, off);
+bool write_range(const FileJob& j, size_t begin, size_t bytes, AlignedBlock& tmp) {
+    const int fd = j.fd;
+    char* src = static_cast<char*>(j.buffer) + begin;
+    uint64_t off = j.file_off + begin;
+    if (j.io == FileIo::kMapped) return copy_mapped(fd, src, bytes, off, true);
+    if (j.io == FileIo::kBuffered) return write_fully(fd, src, bytes, off);
     if (!tmp.ensure()) {
         errno = ENOMEM;
         return false;
@@ -141,12 +160,18 @@ void FilePath::join_threads() {
         if (t.joinable()) t.join();
 }
 
-void FilePath::start() {
+bool FilePath::start() {
     t_begin_ = now_seconds();
-    for (int r = 0; r < n_threads_; ++r) {
-        threads_.emplace_back(&FilePath::read_loop, this, r);
-        threads_.emplace_back(&FilePath::write_loop, this, r);
+    try {
+        for (int r = 0; r < n_threads_; ++r) {
+            threads_.emplace_back(&FilePath::read_loop, this, r);
+            threads_.emplace_back(&FilePath::write_loop, this, r);
+        }
+    } catch (const std::exception& e) {  // the system refused a thread: nothing may cross the C boundary
+        fail_with(std::string("starting an I/O thread: ") + e.what());
+        return false;
     }
+    return true;
 }
 
 void FilePath::fail_with(const std::string& why) {
@@ -170,7 +195,7 @@ void FilePath::read_loop(int r) {
         size_t begin, len;
         share_of(j.bytes, r, n_threads_, &begin, &len);
         const double t0 = now_seconds();
-        const bool ok = len == 0 || read_range(j.fd, static_cast<char*>(j.buffer) + begin, len, j.file_off + begin, tmp);
+        const bool ok = len == 0 || read_range(j, begin, len, tmp);
         const double t1 = now_seconds();
         if (!ok) {
             const int e = errno;
@@ -207,8 +232,7 @@ void FilePath::write_loop(int r) {
         size_t begin, len;
         share_of(j.bytes, r, n_threads_, &begin, &len);
         const double t0 = now_seconds();
-        const bool ok =
-            len == 0 || write_range(j.fd, static_cast<const char*>(j.buffer) + begin, len, j.file_off + begin, tmp);
+        const bool ok = len == 0 || write_range(j, begin, len, tmp);
         const double t1 = now_seconds();
         if (!ok) {
             const int en = errno;
@@ -261,6 +285,18 @@ bool FilePath::join(mlpo_file_stats* stats, std::string* error) {
         return false;
     }
     return true;
+}
+
+FileIo file_io_kind(int fd) {
+    const int fl = fcntl(fd, F_GETFL);
+    if (fl >= 0 && (fl & O_DIRECT) != 0) return FileIo::kDirect;
+    struct statfs fs;
+    struct stat sb;
+    constexpr long kTmpfsMagic = 0x01021994;
+    if (fstatfs(fd, &fs) == 0 && (long)fs.f_type == kTmpfsMagic && fstat(fd, &sb) == 0 &&
+        (uint64_t)sb.st_blocks * 512u >= (uint64_t)sb.st_size)  // no holes: touching a page cannot fail
+        return FileIo::kMapped;
+    return FileIo::kBuffered;
 }
 
 int check_file_extent(const mlpo_file_extent& x, uint64_t state_bytes, int index) {

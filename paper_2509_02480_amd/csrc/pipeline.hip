@@ -365,6 +365,7 @@ static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const Ada
     for (int32_t i : plan.file_ids) {
         const mlpo_subgroup& s = sg[i];
         const uint64_t T = (uint64_t)s.tile_elems;
+        const FileIo io = file_io_kind(cfg->files[i].fd);
         const uint64_t step_elems = (chunk != 0 && chunk < s.n) ? chunk : s.n;
         for (uint64_t off = 0; off < s.n; off += step_elems) {
             const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
@@ -375,6 +376,7 @@ static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const Ada
             char* buf = static_cast<char*>(cfg->bounce) + (jobs.size() % (size_t)cfg->file_slots) * buf_bytes;
             float* f = reinterpret_cast<float*>(buf);
             j.buffer = buf;
+            j.io = io;
             j.view = SgView{f, f + T, f + 2 * T, s.g + off, s.p16 + off, len, s.tile_elems};
             jobs.push_back(j);
         }
@@ -406,7 +408,11 @@ static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const Ada
     MLPO_HIP(hipEventRecord(ec.fence2, st.cmp));  // gradients and scalars come from the compute stream
     MLPO_HIP(hipStreamWaitEvent(st.h2d, ec.fence2, 0));
     FilePath files(std::move(jobs), cfg->file_slots, cfg->file_threads > 0 ? cfg->file_threads : 2, device);
-    files.start();
+    if (!files.start()) {
+        std::string why;
+        files.join(nullptr, &why);
+        return fail(MLPO_EIO, "%s", why.c_str());
+    }
     if (!plan.resident.empty()) {
         rc = launch_adamw(plan.resident.data(), (int)plan.resident.size(), c, scalars, st.cmp);
         if (rc != MLPO_OK) return rc;

@@ -209,15 +209,23 @@ def test_write_failure_is_reported(oracle, tmp_path):
         shard.close()
 
 
-@pytest.mark.parametrize("threads,direct_io", [(1, True), (3, False), (5, True), (16, False)])
-def test_io_threads_and_buffered_or_direct_descriptors(oracle, tmp_path, threads, direct_io):
-    """1..16 threads per direction, each moving its share of every piece; descriptors with and without O_DIRECT (the
-    latter served through the library's page-aligned blocks)."""
+@pytest.mark.parametrize("threads,direct_io,where", [(1, True, "tmp"), (3, False, "tmp"), (5, True, "tmp"),
+                                                      (16, False, "tmp"), (1, False, "shm"), (4, False, "shm"),
+                                                      (7, False, "shm")])
+def test_io_threads_and_kinds_of_descriptors(oracle, tmp_path, threads, direct_io, where):
+    """1..16 threads per direction, each moving its share of every piece; descriptors with O_DIRECT (served through
+    the library's page-aligned blocks), without (plain pread / pwrite), and files in tmpfs (copied through a
+    mapping)."""
     ohp, ghp = hp_pair(oracle)
     tiers = [F, H, F]
     wl = W.Workload("fileio", n_sub=3, sub_elems=90_001, n_host=0, steps=2)
     host = W.host_subgroups(wl, warm=True)
-    shard = Shard(host, tiers, 2048, str(tmp_path / "state.bin"), direct_io=direct_io)
+    path = str(tmp_path / "state.bin")
+    if where == "shm":
+        if not os.access("/dev/shm", os.W_OK):
+            pytest.skip("no writable /dev/shm")
+        path = f"/dev/shm/mlpo_test_state_{os.getpid()}_{threads}.bin"
+    shard = Shard(host, tiers, 2048, path, direct_io=direct_io)
     streams = (torch.cuda.Stream(), torch.cuda.Stream())
     need = B.mlpo_stream_bounce_bytes(shard.table, 2, 16_384)
     bounce = torch.empty(need, dtype=torch.uint8, pin_memory=True)
@@ -235,3 +243,5 @@ def test_io_threads_and_buffered_or_direct_descriptors(oracle, tmp_path, threads
     finally:
         torch.cuda.synchronize()
         shard.close()
+        if where == "shm" and os.path.exists(path):
+            os.unlink(path)
