@@ -509,7 +509,10 @@ def multipath_bench(args, torch, B, np, ctx, kind):
                            want_file_stats=True)
         times, rd, wr, wall = [], [], [], []
         applied = ctx["applied"]
+        leg_start = time.perf_counter()
         for s in range(args.stream_warmup + wl.steps):
+            if times and time.perf_counter() - leg_start > args.multipath_seconds:
+                break       # a slow disk must not stretch the run: one timed step is enough to report
             torch.cuda.synchronize()
             t = time.perf_counter()
             B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ctx["ws"], ctx["ws_bytes"], ctx["scal"], cmp_)
@@ -638,6 +641,8 @@ def main():
     ap.add_argument("--file-slots", type=int, default=3)
     ap.add_argument("--file-threads", type=int, default=4)
     ap.add_argument("--multipath-chunk", type=int, default=1 << 24)
+    ap.add_argument("--multipath-seconds", type=float, default=20.0,
+                    help="a two-path run stops taking further steps after this long (at least one is timed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-subgroups", type=int, default=9)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
