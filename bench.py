@@ -454,7 +454,13 @@ def streamed_bench(args, torch, B, W, np):
     if args.multipath != "none":
         ctx = dict(wl=wl, keep=keep, g_flat=g_flat, p16_flat=p16_flat, T=T, M=M, ws=ws, ws_bytes=ws_bytes, scal=scal,
                    hp=hp, streams=(h2d, cmp_), applied=applied, host_GBs=best["pcie_GBs_per_dir"])
-        out["multipath"] = [multipath_bench(args, torch, B, np, ctx, kind) for kind in args.multipath.split(",")]
+        out["multipath"] = []
+        for kind in args.multipath.split(","):
+            try:
+                out["multipath"].append(multipath_bench(args, torch, B, np, ctx, kind))
+            except (OSError, MemoryError, RuntimeError) as e:   # no room for the file, no /dev/shm, an I/O error
+                out["multipath"].append({"kind": kind, "error": f"{type(e).__name__}: {e}"})
+                log(f"[bench] multipath {kind} failed: {e}")
     del table, host_g_table, sgs
     out["grad_accumulate"] = accumulate_bench(torch, B, g_flat, p16_flat, wl)
     return out
@@ -490,8 +496,11 @@ def multipath_bench(args, torch, B, np, ctx, kind):
                 f.write(keep[k].numpy().tobytes())
             f.flush()
             os.fsync(f.fileno())
-        flags = os.O_RDWR | (os.O_DIRECT if kind == "disk" else 0)
-        fd = os.open(path, flags)
+        try:
+            fd = os.open(path, os.O_RDWR | (os.O_DIRECT if kind == "disk" else 0))
+        except OSError:         # a file system without direct I/O
+            fd = os.open(path, os.O_RDWR)
+            res["direct_io"] = False
         sgs, files = [], []
         for k in range(wl.n_sub):
             gk, pk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
