@@ -8,6 +8,10 @@
  * Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers" mentions.
  *
  * Conventions
+ *   - mlpo_grad_unscale_norm, mlpo_adamw_step and mlpo_grad_accumulate* only enqueue kernels on the given stream (no
+ *     allocation, no memset, no host wait), so they can be recorded into a HIP graph by stream capture; the
+ *     per-step constants of the update are kernel arguments, so a captured update repeats the step number it was
+ *     captured with (exact for every step when bias_correction is 0).
  *   - Every call returns 0 (MLPO_OK) or a negative code; mlpo_last_error() gives the text for the calling thread.
  *   - The caller owns every buffer.  The library allocates no device or host memory for user data, keeps no pointer
  *     after the work it enqueued has completed, and never frees anything passed in.

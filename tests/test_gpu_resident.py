@@ -424,3 +424,47 @@ def test_state_pack_and_unpack(n, T):
         B.mlpo_state_pack(dv[0], dv[1], dv[2], n, T, pinned, st)
         torch.cuda.synchronize()
         assert np.array_equal(pinned.numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_step_captured_in_a_hip_graph_and_replayed(oracle, scratch):
+    """The resident step only enqueues kernels (no allocation, no memset, no host wait), so it can be captured once
+    and replayed.  Without bias correction the per-step constants do not depend on the step number, so every replay
+    is one more AdamW step on whatever the gradient buffers hold by then.  Replays alternate with eager work (new
+    gradients copied in, state read back), one of them with a non-finite gradient; every replay is checked."""
+    hp_kw = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, bias_correction=False)
+    ohp, ghp = hp_pair(oracle, **hp_kw)
+    wl = W.Workload("graph", n_sub=5, sub_elems=150_001, hp=W.AdamW(**hp_kw), loss_scale=32.0, max_norm=0.02, steps=6)
+    host = W.host_subgroups(wl, warm=True)
+    ds = DeviceSubgroups(host, tile=2048)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        st = torch.cuda.current_stream()
+        B.mlpo_grad_unscale_norm(ds.table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars, st)
+        B.mlpo_adamw_step(ds.table, ghp, 1, scratch.scalars, st)
+    torch.cuda.synchronize()
+    before = [ds.fetch(k) for k in range(wl.n_sub)]
+    for k in range(wl.n_sub):                       # capturing ran nothing
+        assert_state_parity(before[k], host[k], f"after capture sg {k}")
+    applied = 0
+    for s in range(wl.steps):
+        inject = s == 3
+        for k, sg in enumerate(host):
+            W.fill_grads(wl, k, s, sg["g"])
+        if inject:
+            host[2]["g"][4321] = 0xFF80
+        for k, sg in enumerate(host):
+            ds.set_grads(k, sg["g"])
+        torch.cuda.synchronize()
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, applied, wl.inv_scale, wl.max_norm)
+        graph.replay()
+        torch.cuda.synchronize()
+        sc = scratch.read()
+        assert sc["found_inf"] == flag_o == int(inject) and ok_o == (not inject)
+        if ok_o:
+            assert abs(float(sc["norm"]) - float(norm_o)) <= 1e-5 * float(norm_o) and sc["gmul"] == gmul_o
+            applied += 1
+        for k in range(wl.n_sub):
+            assert_state_parity(ds.fetch(k), host[k], f"replay {s} sg {k}")
+    assert applied == wl.steps - 1
