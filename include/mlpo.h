@@ -5,7 +5,8 @@
  * half-precision gradients on the fly, update the fp32 master parameters / momentum / variance, push the
  * half-precision parameters, flush, prefetch the next) with the GPU as the place of the update, HBM as the fast tier
  * and pinned host memory as the slow tier - the generalisation to a GPU-CPU tier pair that Section 3.2 "Unified
- * Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers" mentions.
+ * Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers" mentions - and, optionally, a file as a second
+ * path behind the slow tier.
  *
  * Conventions
  *   - mlpo_grad_unscale_norm, mlpo_adamw_step and mlpo_grad_accumulate* only enqueue kernels on the given stream (no
@@ -60,7 +61,7 @@ typedef struct {
  * subgroup whose g is pinned host memory is also accepted by mlpo_grad_unscale_norm and by direct mode.
  *
  * MLPO_TIER_FILE: the fp32 state lives in a file (the slower alternative path of the offloaded tier, Section 3.2
- * "Unified Multi-level, Multi-path Asynchronous Offloading Using Virtual Tiers"); p, m, v must be NULL, the layout
+ * "Unified Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers"); p, m, v must be NULL, the layout
  * must be tiled, and mlpo_stream_cfg.files says where the state is.  g and p16 are device memory.  Accepted by
  * mlpo_stream_update in direct mode only.
  *
@@ -70,9 +71,9 @@ typedef struct {
  *          holds, for every run of T consecutive elements, T floats of p, then T of m, then T of v:
  *          x[i] of array X in {p, m, v} lives at X + (i / T) * 3T + (i % T), with m == p + T and v == p + 2T
  *          (checked).  T must be a multiple of 1024, p 256-byte aligned, g and p16 8-byte aligned.  With T = 8192
- *          (MLPO_TILE_DEFAULT) the three values an element needs sit close together in the same HBM channel and
- *          the whole update sweeps one address stream instead of three: the layout the library is fastest on.  A host-tier tiled subgroup also
- *          moves as one transfer per direction instead of three. */
+ *          (MLPO_TILE_DEFAULT) the three values an element needs sit close together and the whole update sweeps
+ *          one address stream instead of three: the layout the library is fastest on.  A host-tier tiled subgroup
+ *          also moves as one transfer per direction instead of three. */
 #define MLPO_TIER_HBM 0
 #define MLPO_TIER_HOST 1
 #define MLPO_TIER_HOST_GRADS 2
@@ -123,8 +124,9 @@ int32_t mlpo_version(void);
 size_t mlpo_norm_workspace_bytes(void);
 
 /*
- * Gradient pass before the update (mixed-precision convention; the paper's text stops at "gradients are upscaled to
- * FP32 and used by the optimizer", Section 2 "Mixed Precision Training"): over the gradients of ALL n_sg subgroups
+ * Gradient pass before the update (the usual mixed-precision convention; Section 2 "Mixed Precision Training" of the
+ * paper only says that the half-precision gradients are widened to fp32 for the optimizer): over the gradients of ALL
+ * n_sg subgroups
  *   found_inf = any g_i with its bf16 exponent field all ones,
  *   norm      = sqrt( sum_i ((double)(f32(g_i) * inv_scale))^2 ), rounded to fp32,
  *   clip_coef, gmul as described at mlpo_step_scalars.
@@ -344,7 +346,7 @@ int mlpo_stream_flush(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_stream_c
 
 /*
  * Allocation of subgroups to the paths of a virtual tier in proportion to their bandwidth (Eq. 1, Section 3.3):
- *   T_i = ceil(M * B_i / sum_j B_j), adjusted such that sum_i T_i = M.
+ *   T_i = ceil(M * B_i / sum_j B_j), then corrected so that the T_i add up to M.
  * The paper does not say how to adjust; here the surplus is taken back one subgroup at a time from the tier that
  * would finish last (largest T_i / B_i), which keeps the finishing times of the paths as close as integers allow.
  *   n_subgroups  M >= 0.

@@ -1,6 +1,7 @@
 """Oracle for the subgroup-to-tier allocation of Section 3.3 (Eq. 1) - TEST INFRASTRUCTURE ONLY.
 
-Eq. 1: T_i = ceil(M * B_i / sum_j B_j), "adjusted such that" the T_i sum to M.  The paper leaves the adjustment open;
+Eq. 1: T_i = ceil(M * B_i / sum_j B_j), with the T_i then corrected so that they sum to M.  The paper leaves the
+correction open;
 the reading taken (and written in the library's header) is: while there is a surplus, take one subgroup back from the
 tier that would finish last, i.e. with the largest T_i / B_i; among equals from the tier with the lower bandwidth,
 then the higher index.  Tiers with a capacity keep at most that many subgroups and Eq. 1 is applied again to the rest.
