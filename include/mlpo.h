@@ -268,7 +268,8 @@ typedef struct {
     int32_t n_slots;       /* staged: staging slots = bound on subgroups (or chunks) in flight; 1..MLPO_MAX_SLOTS */
     int32_t mode;          /* MLPO_STREAM_STAGED or MLPO_STREAM_DIRECT */
     uint64_t chunk_elems;  /* staged: 0 = a whole subgroup per transfer; else transfers of this many elements (a
-                              multiple of 4, and of every tile_elems in use) */
+                              multiple of 4, and of every tile_elems in use).  Direct mode with file-tier
+                              subgroups: the size of the pieces both paths work in; otherwise unused there */
     void* staging;         /* staged: device, 256-byte aligned, caller-owned */
     size_t staging_bytes;  /* staged: >= mlpo_stream_staging_bytes(...) */
     void* h2d;             /* hipStream_t for host-to-device copies (direct: for the host-tier kernel) */
@@ -301,13 +302,13 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
 size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t file_slots, uint64_t chunk_elems);
 
 /*
- * One update phase over subgroups of both tiers (Algorithm 1, with the fetch / update / flush overlap of Section 3.4
+ * One update phase over subgroups of all tiers (Algorithm 1, with the fetch / update / flush overlap of Section 3.4
  * and the bound on subgroups in flight that Section 3.2 "Optimized Virtual Tier Concurrency Control" motivates).
  * HBM-tier subgroups are updated in place as in mlpo_adamw_step.  In staged mode each host-tier subgroup (or chunk of
  * one) is copied host-to-device into a free staging slot on the h2d stream, updated there on the compute stream (g
  * and p16 are read/written at their device homes; the gradients of a MLPO_TIER_HOST_GRADS subgroup travel into the
- * slot with the state, and with a slot cache they are fetched anew every step), and copied back on the d2h stream; a slot is reused only after its
- * copy back has completed, so at most n_slots transfers are in flight.  In direct mode the kernel works on the host
+ * slot with the state, and with a slot cache they are fetched anew every step), and copied back on the d2h stream;
+ * a slot is reused only after its copy back has completed, so at most n_slots transfers are in flight.  In direct mode the kernel works on the host
  * state in place.  Results are bit-identical to the resident path whatever mode, n_slots, chunk_elems, direct_blocks
  * and order are.
  *
