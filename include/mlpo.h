@@ -292,7 +292,8 @@ typedef struct {
                               overlap */
     int32_t file_threads;  /* threads per direction that move the pieces between file and bounce buffers, each an
                               equal share of every piece; 0 = default (2); at most 16 */
-    mlpo_file_stats* file_stats; /* host pointer or NULL: receives what the file path moved and how long it took */
+    mlpo_file_stats* file_stats; /* host pointer or NULL: receives what the file path moved and how long it took
+                                    (all zero after a skipped step or when nothing is file-tier) */
 } mlpo_stream_cfg;
 
 /* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier). */

@@ -583,6 +583,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     int rc = check_stream_args(sg, n_sg, order, hp, step, scalars, cfg, &slot_floats);
     if (rc != MLPO_OK) return rc;
     if (applied != nullptr) *applied = 1;
+    if (cfg->file_stats != nullptr) memset(cfg->file_stats, 0, sizeof *cfg->file_stats);  // nothing moved so far
     if (n_sg == 0) return MLPO_OK;
 
     Streams st{static_cast<hipStream_t>(cfg->h2d), static_cast<hipStream_t>(cfg->compute),

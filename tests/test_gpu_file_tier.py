@@ -173,8 +173,10 @@ def test_skipped_step_touches_no_file(oracle, tmp_path):
     try:
         B.mlpo_grad_unscale_norm(shard.table, wl.inv_scale, 0.0, scratch.ws, scratch.ws_bytes, scratch.scalars,
                                  streams[1])
+        cfg.stats.bytes_read = 123          # stale figures from an earlier step must not survive a skipped one
         assert B.mlpo_stream_update(shard.table, None, ghp, 1, scratch.scalars, cfg) is False
         streams[1].synchronize()
+        assert cfg.stats.bytes_read == 0 and cfg.stats.bytes_written == 0 and cfg.stats.wall_seconds == 0.0
         assert open(path, "rb").read() == before
         ok_o, *_ = oracle.step(host, ohp, 0, wl.inv_scale, 0.0)
         assert not ok_o
