@@ -251,145 +251,189 @@ def cpu_baseline(args, W, np):
                               "sample": f"the same {n} params x 1 step, {dt_single:.1f} s wall"}}
 
 
-def streamed_bench(args, torch, B, W, np):
-    wl = W.CONFIGS[args.streamed]
-    d = torch.device("cuda:0")
-    M = wl.sub_elems
-    t0 = time.time()
-    sgs, keep = [], []
-    hg_ = np.empty(M, np.uint16)
-    T = args.tile
-    per = B.mlpo_state_floats(M, T)
-    g_flat = torch.empty(wl.n_total, dtype=torch.int16, device=d)
-    p16_flat = torch.zeros(wl.n_total, dtype=torch.int16, device=d)
-    tmp = np.zeros(per // 3, np.float32)
-    for k in range(wl.n_sub):
-        # fp32 state in the tiled layout: one buffer per subgroup, pinned host memory or HBM by tier; m = v = 0
-        W.fill_state(wl, k, tmp[:M], None, None, threads=args.threads)
-        if wl.tier(k) == 1:
-            st = torch.zeros(per, dtype=torch.float32, pin_memory=True)
-            st.numpy().reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
-        else:
-            st = torch.zeros(per, dtype=torch.float32, device=d)
-            st.view(-1, 3, T)[:, 0, :].copy_(torch.from_numpy(tmp).view(-1, T))
-        W.fill_grads(wl, k, 0, hg_, threads=args.threads)
-        g_flat[k * M:(k + 1) * M].copy_(torch.from_numpy(hg_.view(np.int16)))
-        keep.append(st)
-        sgs.append(B.tiled_subgroup(st, g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M], n=M,
-                                    tier=wl.tier(k), tile_elems=T))
-    table = B.SubgroupTable(sgs)
-    ws_bytes = B.mlpo_norm_workspace_bytes()
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=d)
-    scal = torch.zeros(4, dtype=torch.float32, device=d)
-    hp = B.HParams(**wl.hp.__dict__)
-    h2d, cmp_, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-    torch.cuda.synchronize()
-    log(f"[bench] {wl.name}: {wl.n_host} host-tier + {wl.n_sub - wl.n_host} HBM subgroups of {M}, "
-        f"setup {time.time() - t0:.1f}s")
-    n_host_params = wl.n_host * M
-    out = {"workload": wl.name, "state_layout": f"tiled T={T}", "host_tier_params": n_host_params, "bytes_per_direction_per_step": 12 * n_host_params,
-           "pcie_nominal_GBs": PCIE_NOMINAL_GBS, "runs": []}
-    # plain pinned copies of one subgroup array, for reference: each direction alone, then both at once
-    ref = torch.empty(M, dtype=torch.float32, device=d)
-    ref2 = torch.empty(M, dtype=torch.float32, device=d)
-    host_k = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
-    hsrc, hdst = keep[host_k[0]][:M], keep[host_k[-1]][:M]
+class StreamedBench:
+    """The host-tier workload: state of the host-tier subgroups in pinned memory (tiled layout), gradients and bf16
+    parameters on the device; one timed run per variant of ``--stream-variants``."""
 
-    def timed(fn, reps=3):
-        fn()
+    def __init__(self, args, torch, B, W, np):
+        self.args, self.torch, self.B, self.np = args, torch, B, np
+        self.wl = wl = W.CONFIGS[args.streamed]
+        self.d = d = torch.device("cuda:0")
+        self.M = M = wl.sub_elems
+        self.T = T = args.tile
+        t0 = time.time()
+        per = B.mlpo_state_floats(M, T)
+        self.g_flat = torch.empty(wl.n_total, dtype=torch.int16, device=d)
+        self.p16_flat = torch.zeros(wl.n_total, dtype=torch.int16, device=d)
+        self.keep, sgs = [], []
+        tmp = np.zeros(per // 3, np.float32)
+        hg = np.empty(M, np.uint16)
+        for k in range(wl.n_sub):
+            # fp32 state in the tiled layout: one buffer per subgroup, pinned host memory or HBM by tier; m = v = 0
+            W.fill_state(wl, k, tmp[:M], None, None, threads=args.threads)
+            if wl.tier(k) == 1:
+                st = torch.zeros(per, dtype=torch.float32, pin_memory=True)
+                st.numpy().reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
+            else:
+                st = torch.zeros(per, dtype=torch.float32, device=d)
+                st.view(-1, 3, T)[:, 0, :].copy_(torch.from_numpy(tmp).view(-1, T))
+            W.fill_grads(wl, k, 0, hg, threads=args.threads)
+            self.grads(k).copy_(torch.from_numpy(hg.view(np.int16)))
+            self.keep.append(st)
+            sgs.append(B.tiled_subgroup(st, self.grads(k), self.p16(k), n=M, tier=wl.tier(k), tile_elems=T))
+        self.table = B.SubgroupTable(sgs)
+        self.ws_bytes = B.mlpo_norm_workspace_bytes()
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=d)
+        self.scal = torch.zeros(4, dtype=torch.float32, device=d)
+        self.hp = B.HParams(**wl.hp.__dict__)
+        self.h2d, self.cmp, self.d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        self.applied = 0
+        self.host_g_table = self.host_g_all = self.micro = None
+        self.n_host_params = wl.n_host * M
         torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(reps):
+        log(f"[bench] {wl.name}: {wl.n_host} host-tier + {wl.n_sub - wl.n_host} HBM subgroups of {M}, "
+            f"setup {time.time() - t0:.1f}s")
+
+    def grads(self, k):
+        return self.g_flat[k * self.M:(k + 1) * self.M]
+
+    def p16(self, k):
+        return self.p16_flat[k * self.M:(k + 1) * self.M]
+
+    def memcpy_reference(self):
+        """Plain pinned copies of one 400 MB subgroup array (torch copy_ = hipMemcpyAsync), each direction alone."""
+        torch, M, wl = self.torch, self.M, self.wl
+        ref = torch.empty(M, dtype=torch.float32, device=self.d)
+        ref2 = torch.empty(M, dtype=torch.float32, device=self.d)
+        host_k = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
+        hsrc, hdst = self.keep[host_k[0]][:M], self.keep[host_k[-1]][:M]
+
+        def timed(fn, reps=3):
             fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / reps
-
-    def up():
-        with torch.cuda.stream(h2d):
-            ref.copy_(hsrc, non_blocking=True)
-
-    def down():
-        with torch.cuda.stream(d2h):
-            hdst.copy_(ref2, non_blocking=True)
-
-    saved_m = hdst.clone()
-    bytes_arr = 4 * M
-    # plain pinned copies of one 400 MB array (torch copy_ = hipMemcpyAsync), each direction alone
-    out["memcpy_h2d_GBs"] = round(bytes_arr / timed(up) / 1e9, 2)
-    out["memcpy_d2h_GBs"] = round(bytes_arr / timed(down) / 1e9, 2)
-    memcpy_peak = min(out["memcpy_h2d_GBs"], out["memcpy_d2h_GBs"])
-    hdst.copy_(saved_m)
-    del saved_m, ref, ref2
-
-    applied = 0
-    host_g_table = None
-    micro = None
-    for n_slots, chunk in args.stream_variants:
-        cache = None
-        run_table = table
-        if n_slots == "d":      # direct mode: chunk holds the number of persistent workgroups
-            stg = None
-            cfg = B.direct_cfg(h2d, cmp_, chunk)
-        elif n_slots in ("dg", "sg", "dga"):   # the gradients of host-tier subgroups in pinned host memory too
-            if host_g_table is None:
-                host_g_keep, host_g_all = [], []
-                sg2 = []
-                for k in range(wl.n_sub):
-                    gk = g_flat[k * M:(k + 1) * M]
-                    if wl.tier(k) == 1:
-                        gk = torch.empty(M, dtype=torch.int16, pin_memory=True)
-                        gk.copy_(g_flat[k * M:(k + 1) * M])
-                        host_g_keep.append(gk)
-                    host_g_all.append(gk)
-                    sg2.append(B.tiled_subgroup(keep[k], gk, p16_flat[k * M:(k + 1) * M], n=M,
-                                                tier=B.TIER_HOST_GRADS if wl.tier(k) else B.TIER_HBM, tile_elems=T))
-                host_g_table = B.SubgroupTable(sg2)
-                torch.cuda.synchronize()
-            run_table = host_g_table
-            if n_slots in ("dg", "dga"):     # direct mode: chunk holds the number of persistent workgroups
-                stg = None
-                cfg = B.direct_cfg(h2d, cmp_, chunk)
-            else:                   # staged mode, 3 slots: the gradients travel into the slot with the state
-                need = B.mlpo_stream_staging_bytes(run_table, 3, chunk)
-                stg = torch.empty(need, dtype=torch.uint8, device=d)
-                cfg = B.stream_cfg(3, stg, need, None, cmp_, None, chunk)
-        elif n_slots == "c":    # staged mode with slots that keep their subgroups; chunk holds the number of slots
-            cache = B.SlotCacheC()
-            need = B.mlpo_stream_staging_bytes(table, chunk, 0)
-            stg = torch.empty(need, dtype=torch.uint8, device=d)
-            cfg = B.stream_cfg(chunk, stg, need, None, cmp_, None, 0, cache=cache)
-        else:
-            need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
-            stg = torch.empty(need, dtype=torch.uint8, device=d)
-            cfg = B.stream_cfg(n_slots, stg, need, None, cmp_, None, chunk)    # the library's own copy streams
-        times = []
-        for s in range(args.stream_warmup + wl.steps):
             torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / reps
+
+        def up():
+            with torch.cuda.stream(self.h2d):
+                ref.copy_(hsrc, non_blocking=True)
+
+        def down():
+            with torch.cuda.stream(self.d2h):
+                hdst.copy_(ref2, non_blocking=True)
+
+        saved = hdst.clone()
+        rates = round(4 * M / timed(up) / 1e9, 2), round(4 * M / timed(down) / 1e9, 2)
+        hdst.copy_(saved)
+        return rates
+
+    def table_with_host_gradients(self):
+        """The same subgroups with the gradients of the host-tier ones in pinned host memory too."""
+        if self.host_g_table is None:
+            torch, B, wl = self.torch, self.B, self.wl
+            self.host_g_all, sgs = [], []
+            for k in range(wl.n_sub):
+                gk = self.grads(k)
+                if wl.tier(k) == 1:
+                    gk = torch.empty(self.M, dtype=torch.int16, pin_memory=True)
+                    gk.copy_(self.grads(k))
+                self.host_g_all.append(gk)
+                sgs.append(B.tiled_subgroup(self.keep[k], gk, self.p16(k), n=self.M,
+                                            tier=B.TIER_HOST_GRADS if wl.tier(k) else B.TIER_HBM, tile_elems=self.T))
+            self.host_g_table = B.SubgroupTable(sgs)
+            torch.cuda.synchronize()
+        return self.host_g_table
+
+    def configure(self, kind, arg):
+        """(subgroup table, stream configuration, staging buffer, slot cache) of one variant.  kind is a number of
+        staging slots (staged mode, arg = chunk_elems), "d" / "dg" / "dga" (direct mode, arg = workgroups, with the
+        gradients on the device / on the host / on the host with the statistics left by the last accumulation), "sg"
+        (staged mode with 3 slots and the gradients on the host, arg = chunk_elems) or "c" (staged mode with slots
+        that keep their subgroups, arg = slots)."""
+        torch, B = self.torch, self.B
+        table = self.table_with_host_gradients() if kind in ("dg", "dga", "sg") else self.table
+        if kind in ("d", "dg", "dga"):
+            return table, B.direct_cfg(self.h2d, self.cmp, arg), None, None
+        n_slots, chunk = {"sg": (3, arg), "c": (arg, 0)}.get(kind, (kind, arg))
+        cache = B.SlotCacheC() if kind == "c" else None
+        need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
+        stg = torch.empty(need, dtype=torch.uint8, device=self.d)
+        # no copy streams given: the library's own
+        return table, B.stream_cfg(n_slots, stg, need, None, self.cmp, None, chunk, cache=cache), stg, cache
+
+    def last_micro_batch(self):
+        """The last micro-batch of the backward pass (outside the update phase, untimed) accumulates into the host
+        buffers and leaves the gradient statistics behind; zeros keep the gradients as they are."""
+        torch, B, wl = self.torch, self.B, self.wl
+        if self.micro is None:
+            self.micro = torch.zeros(self.M, dtype=torch.int16, device=self.d)
+        for k in range(wl.n_sub):
+            B.mlpo_grad_accumulate_norm(self.host_g_all[k], self.micro, self.M, False, 64 if wl.tier(k) else 0,
+                                        wl.inv_scale, self.ws, self.ws_bytes, begin=(k == 0), stream=self.cmp)
+        torch.cuda.synchronize()
+
+    def step(self, kind, table, cfg, order):
+        """One update phase: gradient statistics, then the pipeline; returns the wall time."""
+        torch, B, wl = self.torch, self.B, self.wl
+        torch.cuda.synchronize()
+        if kind == "dga":
+            self.last_micro_batch()
+        t = time.perf_counter()
+        if kind == "dga":
+            B.mlpo_grad_norm_finish(self.ws, self.ws_bytes, wl.inv_scale, wl.max_norm, self.scal, self.cmp)
+        else:
+            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, self.ws, self.ws_bytes, self.scal, self.cmp)
+        ok = B.mlpo_stream_update(table, order, self.hp, self.applied + 1, self.scal, cfg)
+        self.cmp.synchronize()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        assert ok
+        self.applied += 1
+        return dt
+
+    def effective_io(self, kind, arg, n_steps, fetch_ms, flush_ms, kern_ms):
+        """The paper's effective I/O throughput (Section 4.3): bytes read + written over read time + write time,
+        averaged over the transfer units; in direct mode reading and writing both last as long as the kernel that
+        does them."""
+        M, wl = self.M, self.wl
+        if kind in ("d", "dg", "dga"):
+            eff = [2 * 12 * self.n_host_params / (2 * k * 1e-3) / 1e9 for k in kern_ms if k > 1.0]
+        elif kind == "c":
+            eff = []                # transfers are not paired one to one when flushes are lazy
+        else:
+            c = arg or M
+            both = 26 if kind == "sg" else 24     # bytes per element fetched + flushed
+            units = [both * min(c, M - o) for _ in range(wl.n_host * n_steps) for o in range(0, M, c)]
+            assert len(units) == len(fetch_ms) == len(flush_ms), (len(units), len(fetch_ms), len(flush_ms))
+            eff = [u / ((a + b) * 1e-3) / 1e9 for u, a, b in zip(units, fetch_ms, flush_ms)]
+        return round(sum(eff) / len(eff), 2) if eff else None
+
+    def describe(self, kind, arg):
+        return {
+            "d": {"mode": "direct", "direct_blocks": arg},
+            "dg": {"mode": "direct, gradients on the host too (16 B/param in, 12 out)", "direct_blocks": arg},
+            "dga": {"mode": "direct, gradients on the host too, statistics from the last accumulation "
+                            "(14 B/param in, 12 out)", "direct_blocks": arg},
+            "sg": {"mode": "staged, gradients on the host too (16 B/param in, 12 out)", "n_slots": 3,
+                   "chunk_elems": arg},
+            "c": {"mode": "staged+slot-cache, alternating order", "n_slots": arg},
+        }.get(kind, {"mode": "staged", "n_slots": kind, "chunk_elems": arg})
+
+    def run_variant(self, kind, arg, memcpy_peak):
+        B, wl, args = self.B, self.wl, self.args
+        table, cfg, stg, cache = self.configure(kind, arg)
+        times, fetches_before = [], 0
+        for s in range(args.stream_warmup + wl.steps):
             if s == args.stream_warmup:
+                self.torch.cuda.synchronize()
                 B.mlpo_set_option("time_kernels", 1)
                 fetches_before = cache.fetches if cache is not None else 0
-            if n_slots == "dga":
-                # the last micro-batch of the backward pass (outside the update phase, untimed) accumulates into
-                # the host buffers and leaves the gradient statistics behind; zeros keep the gradients as they are
-                if micro is None:
-                    micro = torch.zeros(M, dtype=torch.int16, device=d)
-                for k in range(wl.n_sub):
-                    B.mlpo_grad_accumulate_norm(host_g_all[k], micro, M, False, 64 if wl.tier(k) else 0, wl.inv_scale,
-                                                ws, ws_bytes, begin=(k == 0), stream=cmp_)
-                torch.cuda.synchronize()
-            t = time.perf_counter()
-            if n_slots == "dga":
-                B.mlpo_grad_norm_finish(ws, ws_bytes, wl.inv_scale, wl.max_norm, scal, cmp_)
-            else:
-                B.mlpo_grad_unscale_norm(run_table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
             # with a slot cache the processing order alternates (Section 3.2 "Cache-Friendly Ordering")
             order = list(range(wl.n_sub))[::-1] if (cache is not None and s % 2 == 1) else None
-            ok = B.mlpo_stream_update(run_table, order, hp, applied + 1, scal, cfg)
-            cmp_.synchronize()
-            torch.cuda.synchronize()
-            dt = time.perf_counter() - t
-            assert ok
-            applied += 1
+            dt = self.step(kind, table, cfg, order)
             if s >= args.stream_warmup:
                 times.append(dt)
         fetch_ms, flush_ms, kern_ms = B.mlpo_kernel_times(2), B.mlpo_kernel_times(3), B.mlpo_kernel_times(0)
@@ -397,63 +441,47 @@ def streamed_bench(args, torch, B, W, np):
         B.mlpo_kernel_times(4)
         B.mlpo_set_option("time_kernels", 0)
         mean = sum(times) / len(times)
-        gbs = 12 * n_host_params / mean / 1e9
-        # the paper's effective I/O throughput (Section 4.3): 2 * bytes / (read time + write time), averaged over
-        # the transfer units; in direct mode reading and writing both last as long as the kernel that does them
-        if n_slots in ("d", "dg", "dga"):
-            eff = [2 * 12 * n_host_params / (2 * k * 1e-3) / 1e9 for k in kern_ms if k > 1.0]
-        elif n_slots == "c":
-            eff = []                # transfers are not paired one to one when flushes are lazy
-        else:
-            c = chunk or M
-            both = 26 if n_slots == "sg" else 24     # bytes per element fetched + flushed
-            units = [both * min(c, M - o) for _ in range(wl.n_host * len(times)) for o in range(0, M, c)]
-            assert len(units) == len(fetch_ms) == len(flush_ms), (len(units), len(fetch_ms), len(flush_ms))
-            eff = [u / ((a + b) * 1e-3) / 1e9 for u, a, b in zip(units, fetch_ms, flush_ms)]
-        eff_io = round(sum(eff) / len(eff), 2) if eff else None
-        if cache is not None:
-            B.mlpo_stream_flush(table, cfg)
-            cmp_.synchronize()
-            desc = {"mode": "staged+slot-cache, alternating order", "n_slots": chunk,
-                    "subgroup_transfers_per_step_per_dir": round((cache.fetches - fetches_before) / wl.steps, 2),
-                    "of": wl.n_host}
-        elif n_slots == "d":
-            desc = {"mode": "direct", "direct_blocks": chunk}
-        elif n_slots == "dg":
-            desc = {"mode": "direct, gradients on the host too (16 B/param in, 12 out)", "direct_blocks": chunk}
-        elif n_slots == "dga":
-            desc = {"mode": "direct, gradients on the host too, statistics from the last accumulation "
-                            "(14 B/param in, 12 out)", "direct_blocks": chunk}
-        elif n_slots == "sg":
-            desc = {"mode": "staged, gradients on the host too (16 B/param in, 12 out)", "n_slots": 3,
-                    "chunk_elems": chunk}
-        else:
-            desc = {"mode": "staged", "n_slots": n_slots, "chunk_elems": chunk}
-        rec = {**desc, "steps": len(times), "ms_per_step": round(mean * 1e3, 2),
+        gbs = 12 * self.n_host_params / mean / 1e9
+        rec = {**self.describe(kind, arg), "steps": len(times), "ms_per_step": round(mean * 1e3, 2),
                "min_ms": round(min(times) * 1e3, 2), "Gparams_s": round(wl.n_total / mean / 1e9, 3)}
-        if cache is None:
+        if cache is not None:
+            B.mlpo_stream_flush(self.table, cfg)
+            self.cmp.synchronize()
+            # fewer subgroups cross the link: the useful figure is the step time; the link rate is what was moved
+            moved = (cache.fetches - fetches_before) / wl.steps
+            rec.update({"subgroup_transfers_per_step_per_dir": round(moved, 2), "of": wl.n_host,
+                        "link_GBs_per_dir": round(gbs * moved / wl.n_host, 2),
+                        "traffic_vs_uncached": round(moved / wl.n_host, 3)})
+        else:
             rec.update({"pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
                         "frac_of_one_way_memcpy": round(gbs / memcpy_peak, 4),
-                        "effective_io_GBs_paper_formula": eff_io})
-            if n_slots in ("dg", "sg"):   # the gradients cross the link twice (gradient pass, update): 16 B in, 12 out
-                rec.update({"pcie_in_GBs": round(16 * n_host_params / mean / 1e9, 2),
-                            "pcie_out_GBs": round(12 * n_host_params / mean / 1e9, 2)})
-            if n_slots == "dga":
-                rec.update({"pcie_in_GBs": round(14 * n_host_params / mean / 1e9, 2),
-                            "pcie_out_GBs": round(12 * n_host_params / mean / 1e9, 2)})
-        else:
-            # fewer subgroups cross the link: the useful figure is the step time; the link rate is what was moved
-            moved = rec["subgroup_transfers_per_step_per_dir"] / wl.n_host
-            rec.update({"link_GBs_per_dir": round(gbs * moved, 2), "traffic_vs_uncached": round(moved, 3)})
-        out["runs"].append(rec)
-        log(f"[bench] streamed {out['runs'][-1]}")
-        del stg, cfg
+                        "effective_io_GBs_paper_formula": self.effective_io(kind, arg, len(times), fetch_ms, flush_ms,
+                                                                            kern_ms)})
+            # host-side gradients cross the link with the state, and once more for a gradient pass
+            inbound = {"dg": 16, "sg": 16, "dga": 14}.get(kind)
+            if inbound:
+                rec.update({"pcie_in_GBs": round(inbound * self.n_host_params / mean / 1e9, 2),
+                            "pcie_out_GBs": round(12 * self.n_host_params / mean / 1e9, 2)})
+        log(f"[bench] streamed {rec}")
+        return rec
+
+
+def streamed_bench(args, torch, B, W, np):
+    sb = StreamedBench(args, torch, B, W, np)
+    wl = sb.wl
+    out = {"workload": wl.name, "state_layout": f"tiled T={sb.T}", "host_tier_params": sb.n_host_params,
+           "bytes_per_direction_per_step": 12 * sb.n_host_params, "pcie_nominal_GBs": PCIE_NOMINAL_GBS, "runs": []}
+    out["memcpy_h2d_GBs"], out["memcpy_d2h_GBs"] = sb.memcpy_reference()
+    memcpy_peak = min(out["memcpy_h2d_GBs"], out["memcpy_d2h_GBs"])
+    for kind, arg in args.stream_variants:
+        out["runs"].append(sb.run_variant(kind, arg, memcpy_peak))
     # the cached runs move less data, so their "GB/s" is not a link rate: the best link rate is among the others
     best = max((r for r in out["runs"] if "pcie_GBs_per_dir" in r), key=lambda r: r["pcie_GBs_per_dir"])
     out["best"] = best
     if args.multipath != "none":
-        ctx = dict(wl=wl, keep=keep, g_flat=g_flat, p16_flat=p16_flat, T=T, M=M, ws=ws, ws_bytes=ws_bytes, scal=scal,
-                   hp=hp, streams=(h2d, cmp_), applied=applied, host_GBs=best["pcie_GBs_per_dir"])
+        ctx = dict(wl=wl, keep=sb.keep, g_flat=sb.g_flat, p16_flat=sb.p16_flat, T=sb.T, M=sb.M, ws=sb.ws,
+                   ws_bytes=sb.ws_bytes, scal=sb.scal, hp=sb.hp, streams=(sb.h2d, sb.cmp), applied=sb.applied,
+                   host_GBs=best["pcie_GBs_per_dir"])
         out["multipath"] = []
         for kind in args.multipath.split(","):
             try:
@@ -461,7 +489,8 @@ def streamed_bench(args, torch, B, W, np):
             except (OSError, MemoryError, RuntimeError) as e:   # no room for the file, no /dev/shm, an I/O error
                 out["multipath"].append({"kind": kind, "error": f"{type(e).__name__}: {e}"})
                 log(f"[bench] multipath {kind} failed: {e}")
-    del table, host_g_table, sgs
+    g_flat, p16_flat = sb.g_flat, sb.p16_flat
+    sb.table = sb.host_g_table = None
     out["grad_accumulate"] = accumulate_bench(torch, B, g_flat, p16_flat, wl)
     return out
 

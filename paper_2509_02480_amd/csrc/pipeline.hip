@@ -338,29 +338,11 @@ static int run_direct(const Plan& plan, const AdamwConsts& c, const mlpo_step_sc
     return MLPO_OK;
 }
 
-// Direct mode with file-tier subgroups: two paths behind the offloaded tier (Section 3.2 "Unified Multi-level,
-// Multi-path Asynchronous Offloading using Virtual Tiers").  Both end on the link, so their kernels share one stream:
-// host-tier subgroups cut into pieces of chunk_elems, and file-tier pieces, each launched as soon as its read has
-// finished.  At most two launches are queued at a time, so a piece that arrives from the file waits for one
-// host-tier piece at most, and the file keeps working while the link is busy with the host tier.
-static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const AdamwConsts& c,
-                            const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, const Streams& st,
-                            EventCache& ec) {
-    int rc = ensure_file_events_locked(ec, cfg->file_slots);
-    if (rc != MLPO_OK) return rc;
-    int device = 0;
-    MLPO_HIP(hipGetDevice(&device));
-    const int blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 64;
+// The file path's jobs in processing order: every file-tier subgroup cut into pieces of at most `chunk` elements
+// (0 = whole), piece i in bounce buffer i mod file_slots.
+static std::vector<FileJob> file_jobs(const mlpo_subgroup* sg, const Plan& plan, const mlpo_stream_cfg* cfg,
+                                      uint64_t buffer_bytes) {
     const uint64_t chunk = cfg->chunk_elems;
-
-    // the file path's jobs, in processing order
-    uint64_t buf_bytes = 0;
-    for (int32_t i : plan.file_ids) {
-        uint64_t len = sg[i].n;
-        if (chunk != 0 && chunk < len) len = chunk;
-        const uint64_t b = round_up(state_floats_of(sg[i], len) * sizeof(float), 4096);
-        if (b > buf_bytes) buf_bytes = b;
-    }
     std::vector<FileJob> jobs;
     for (int32_t i : plan.file_ids) {
         const mlpo_subgroup& s = sg[i];
@@ -373,7 +355,7 @@ static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const Ada
             j.fd = cfg->files[i].fd;
             j.file_off = cfg->files[i].offset + (off / T) * 3u * T * sizeof(float);
             j.bytes = (size_t)(round_up(len, T) * 3u * sizeof(float));
-            char* buf = static_cast<char*>(cfg->bounce) + (jobs.size() % (size_t)cfg->file_slots) * buf_bytes;
+            char* buf = static_cast<char*>(cfg->bounce) + (jobs.size() % (size_t)cfg->file_slots) * buffer_bytes;
             float* f = reinterpret_cast<float*>(buf);
             j.buffer = buf;
             j.io = io;
@@ -381,33 +363,50 @@ static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const Ada
             jobs.push_back(j);
         }
     }
-    // the host path's pieces
-    std::vector<SgView> host_pieces;
+    return jobs;
+}
+
+// The host path's pieces: every host-tier subgroup as the device sees it in place, cut the same way.
+static std::vector<SgView> host_pieces_of(const Plan& plan, uint64_t chunk) {
+    std::vector<SgView> pieces;
     for (const SgView& v : plan.host_views) {
         const uint64_t step_elems = (chunk != 0 && chunk < v.n) ? chunk : v.n;
         for (uint64_t off = 0; off < v.n; off += step_elems) {
-            const uint64_t len = (v.n - off < step_elems) ? (v.n - off) : step_elems;
             SgView piece = v;
-            if (v.tile_elems > 0) {
-                const uint64_t shift = (off / (uint64_t)v.tile_elems) * 3u * (uint64_t)v.tile_elems;
-                piece.p += shift;
-                piece.m += shift;
-                piece.v += shift;
-            } else {
-                piece.p += off;
-                piece.m += off;
-                piece.v += off;
-            }
+            // chunk is a multiple of the layout tile, so a piece starts at a layout tile boundary
+            const uint64_t shift =
+                v.tile_elems > 0 ? (off / (uint64_t)v.tile_elems) * 3u * (uint64_t)v.tile_elems : off;
+            piece.p += shift;
+            piece.m += shift;
+            piece.v += shift;
             piece.g += off;
             piece.p16 += off;
-            piece.n = len;
-            host_pieces.push_back(piece);
+            piece.n = (v.n - off < step_elems) ? (v.n - off) : step_elems;
+            pieces.push_back(piece);
         }
     }
+    return pieces;
+}
+
+// Direct mode with file-tier subgroups: two paths behind the offloaded tier (Section 3.2 "Unified Multi-level,
+// Multi-path Asynchronous Offloading using Virtual Tiers").  Both end on the link, so their kernels share one stream:
+// host-tier subgroups cut into pieces of chunk_elems, and file-tier pieces, each launched as soon as its read has
+// finished.  At most two launches are queued at a time, so a piece that arrives from the file waits for one
+// host-tier piece at most, and the file keeps working while the link is busy with the host tier.
+static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& plan, const AdamwConsts& c,
+                            const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, const Streams& st,
+                            EventCache& ec) {
+    int rc = ensure_file_events_locked(ec, cfg->file_slots);
+    if (rc != MLPO_OK) return rc;
+    int device = 0;
+    MLPO_HIP(hipGetDevice(&device));
+    const int blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 64;
+    const std::vector<SgView> host_pieces = host_pieces_of(plan, cfg->chunk_elems);
+    FilePath files(file_jobs(sg, plan, cfg, bounce_slot_bytes(sg, n_sg, cfg->chunk_elems)), cfg->file_slots,
+                   cfg->file_threads > 0 ? cfg->file_threads : 2, device);
 
     MLPO_HIP(hipEventRecord(ec.fence2, st.cmp));  // gradients and scalars come from the compute stream
     MLPO_HIP(hipStreamWaitEvent(st.h2d, ec.fence2, 0));
-    FilePath files(std::move(jobs), cfg->file_slots, cfg->file_threads > 0 ? cfg->file_threads : 2, device);
     if (!files.start()) {
         std::string why;
         files.join(nullptr, &why);
@@ -423,8 +422,7 @@ static int run_direct_files(const mlpo_subgroup* sg, const Plan& plan, const Ada
         if (next_host >= host_pieces.size() && !files.wait_read(next_file)) break;  // only the file is left
         if (launched >= 2) MLPO_HIP(hipEventSynchronize(ec.pace[launched % 2]));    // the launch before the last
         if (next_file < files.size() && files.is_read(next_file)) {
-            const FileJob& j = files.job(next_file);
-            rc = launch_adamw(&j.view, 1, c, scalars, st.h2d, blocks);
+            rc = launch_adamw(&files.job(next_file).view, 1, c, scalars, st.h2d, blocks);
             if (rc != MLPO_OK) return rc;
             hipEvent_t done = ec.file_done[next_file % (size_t)cfg->file_slots];
             MLPO_HIP(hipEventRecord(done, st.h2d));
@@ -630,7 +628,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
         st.h2d = ec.copy_in;
         st.d2h = ec.copy_out;
     }
-    if (direct && !plan.file_ids.empty()) return run_direct_files(sg, plan, c, scalars, cfg, st, ec);
+    if (direct && !plan.file_ids.empty()) return run_direct_files(sg, n_sg, plan, c, scalars, cfg, st, ec);
     if (direct) return run_direct(plan, c, scalars, cfg, st, ec);
 
     // Work enqueued earlier on the flush and compute streams (a previous step's copy back, the gradient pass) must
