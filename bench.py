@@ -44,14 +44,10 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def resident_bench(args, torch, B, W, np, tile):
-    """Times args.steps whole steps on the resident workload with the fp32 state in the given layout
-    (tile = 0: three planar arrays; tile = T: the library's tiled layout)."""
-    wl = W.CONFIGS[args.workload]
-    assert wl.n_host == 0, "the resident benchmark needs an all-HBM workload"
+def resident_setup(args, torch, B, W, np, wl, tile):
+    """Device buffers of the resident workload (seeded synthetic state and gradients) and its subgroup table."""
     d = torch.device("cuda:0")
     N, M = wl.n_total, wl.sub_elems
-    t0 = time.time()
     g_flat = torch.empty(N, dtype=torch.int16, device=d)
     p16_flat = torch.zeros(N, dtype=torch.int16, device=d)
     if tile:
@@ -76,18 +72,20 @@ def resident_bench(args, torch, B, W, np, tile):
         else:
             flat["p"][k * M:(k + 1) * M].copy_(torch.from_numpy(hp_))
             sgs.append(B.subgroup(*(flat[key][k * M:(k + 1) * M] for key in ("p", "m", "v")), gk, hk, n=M))
-    table = B.SubgroupTable(sgs)
-    ws_bytes = B.mlpo_norm_workspace_bytes()
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=d)
-    scal = torch.zeros(4, dtype=torch.float32, device=d)
+    return {"table": B.SubgroupTable(sgs), "g_flat": g_flat, "p16_flat": p16_flat,
+            "params": state if tile else flat["p"], "keep": (state, pad) if tile else flat}
+
+
+def resident_timed_steps(args, torch, B, wl, buf, scal, ws):
+    """args.warmup untimed and args.steps timed whole steps (gradient pass + update) on one stream, with the
+    workload's injection schedule; returns (elapsed ms of the timed steps, applied timed steps)."""
+    d = torch.device("cuda:0")
+    table, g_flat = buf["table"], buf["g_flat"]
     inf_bits = torch.tensor([0x7F80], dtype=torch.int16, device=d)
     saved = torch.zeros(1, dtype=torch.int16, device=d)
     hp = B.HParams(**wl.hp.__dict__)
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
-    log(f"[bench] {wl.name} layout={'tiled T=%d' % tile if tile else 'planar'}: {N} params resident, "
-        f"setup {time.time() - t0:.1f}s")
-
     total = args.warmup + args.steps
     t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     applied = 0
@@ -107,7 +105,7 @@ def resident_bench(args, torch, B, W, np, tile):
                 idx = wl.inject_index(s)
                 saved.copy_(g_flat[idx:idx + 1])
                 g_flat[idx:idx + 1].copy_(inf_bits)
-            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, stream)
+            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws.numel(), scal, stream)
             B.mlpo_adamw_step(table, hp, applied + 1, scal, stream)
             if inject:
                 g_flat[idx:idx + 1].copy_(saved)
@@ -117,10 +115,28 @@ def resident_bench(args, torch, B, W, np, tile):
         t_end.record(stream)
     stream.synchronize()
     torch.cuda.synchronize()
-    elapsed_ms = t_begin.elapsed_time(t_end)
+    return t_begin.elapsed_time(t_end), applied_timed
+
+
+def resident_bench(args, torch, B, W, np, tile):
+    """Times args.steps whole steps on the resident workload with the fp32 state in the given layout
+    (tile = 0: three planar arrays; tile = T: the library's tiled layout)."""
+    wl = W.CONFIGS[args.workload]
+    assert wl.n_host == 0, "the resident benchmark needs an all-HBM workload"
+    d = torch.device("cuda:0")
+    N = wl.n_total
+    layout = f"tiled T={tile}" if tile else "planar"
+    t0 = time.time()
+    buf = resident_setup(args, torch, B, W, np, wl, tile)
+    ws = torch.empty(B.mlpo_norm_workspace_bytes(), dtype=torch.uint8, device=d)
+    scal = torch.zeros(4, dtype=torch.float32, device=d)
+    torch.cuda.synchronize()
+    log(f"[bench] {wl.name} layout={layout}: {N} params resident, setup {time.time() - t0:.1f}s")
+    elapsed_ms, applied_timed = resident_timed_steps(args, torch, B, wl, buf, scal, ws)
+    total = args.warmup + args.steps
     flag = int(scal.cpu().numpy()[3:4].view(np.uint32)[0])
     assert flag == (1 if wl.injects(total - 1) else 0)
-    assert bool(torch.isfinite(state if tile else flat["p"]).all().item()), "state went non-finite"
+    assert bool(torch.isfinite(buf["params"]).all().item()), "state went non-finite"
 
     upd_ms = B.mlpo_kernel_times(0)
     nrm_ms = B.mlpo_kernel_times(1)
@@ -132,14 +148,13 @@ def resident_bench(args, torch, B, W, np, tile):
     n_avg = sum(nrm_ms) / len(nrm_ms)
     achieved = BYTES_PER_PARAM_STEP * N / (k_avg * 1e-3) / 1e9
     out = {
-        "layout": f"tiled T={tile}" if tile else "planar",
+        "layout": layout,
         "value": round(applied_timed * N / (elapsed_ms * 1e-3) / 1e9, 3),
         "ms_per_step": round(elapsed_ms / args.steps, 5),
         "applied_steps": applied_timed,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": recorded_traffic(f"tiled T={tile}" if tile else "planar")
-                     if wl.name == W.C2.name else None,
+                     "traffic": recorded_traffic(layout) if wl.name == W.C2.name else None,
                      "kernel": "adamw_v4_kernel", "avg_launch_ms": round(k_avg, 5),
                      "min_launch_ms": round(min(k_ms), 5), "launches_timed": len(k_ms),
                      "bytes_per_launch": BYTES_PER_PARAM_STEP * N},
@@ -148,11 +163,7 @@ def resident_bench(args, torch, B, W, np, tile):
         "step_hbm_frac": round((BYTES_PER_PARAM_STEP + BYTES_PER_PARAM_NORM) * N * applied_timed
                                / (elapsed_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
     }
-    del table, sgs, g_flat, p16_flat
-    if tile:
-        del state, pad
-    else:
-        del flat
+    del buf
     torch.cuda.empty_cache()
     return out
 
