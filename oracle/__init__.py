@@ -70,6 +70,25 @@ def lib():
         L.orc_bf16_to_f32_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
         L.orc_f32_to_bf16_rne_array.restype = None
         L.orc_f32_to_bf16_rne_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+        L.orc_f16_to_f32_array.restype = None
+        L.orc_f16_to_f32_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+        L.orc_f32_to_f16_rne_array.restype = None
+        L.orc_f32_to_f16_rne_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+        L.orc_grad_accumulate_h.restype = None
+        L.orc_grad_accumulate_h.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32]
+        L.orc_grad_stats_h.restype = None
+        L.orc_grad_stats_h.argtypes = [C.c_void_p, C.c_uint64, C.c_float, C.c_int32, C.POINTER(C.c_double),
+                                       C.POINTER(C.c_uint32)]
+        L.orc_adamw_f32_h.restype = None
+        L.orc_adamw_f32_h.argtypes = [C.c_void_p] * 5 + [C.c_uint64, C.POINTER(_HParams), C.c_int64, C.c_float,
+                                                         C.c_int32]
+        L.orc_adamw_f64_h.restype = None
+        L.orc_adamw_f64_h.argtypes = [C.c_void_p] * 4 + [C.c_uint64, C.POINTER(_HParams), C.c_int64, C.c_double,
+                                                         C.c_int32]
+        L.orc_step_h.restype = C.c_int
+        L.orc_step_h.argtypes = [C.POINTER(_Subgroup), C.c_int32, C.c_void_p, C.POINTER(_HParams), C.c_int64,
+                                 C.c_float, C.c_float, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_uint32),
+                                 C.POINTER(C.c_float)]
         L.orc_grad_accumulate.restype = None
         L.orc_grad_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32]
         L.orc_grad_stats.restype = None
@@ -119,18 +138,47 @@ def f32_to_bf16_rne(x: np.ndarray) -> np.ndarray:
     return out.reshape(np.shape(x))
 
 
-def grad_accumulate(acc: np.ndarray, g: np.ndarray, first: bool) -> None:
-    """One micro-batch's bf16 gradients g into the bf16 accumulation buffer acc, in place (copy when ``first``)."""
+HALF = {"bf16": 0, "fp16": 1}      # the two half-precision formats: every routine takes ``half`` = one of the names
+
+
+def f16_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Widen IEEE binary16 bit patterns (uint16) to fp32."""
+    flat = np.ascontiguousarray(bits, dtype=np.uint16).ravel()
+    out = np.empty(flat.size, np.float32)
+    lib().orc_f16_to_f32_array(flat.ctypes.data, out.ctypes.data, flat.size)
+    return out.reshape(np.shape(bits))
+
+
+def f32_to_f16_rne(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to IEEE binary16 bit patterns (nearest, ties to even)."""
+    flat = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    out = np.empty(flat.size, np.uint16)
+    lib().orc_f32_to_f16_rne_array(flat.ctypes.data, out.ctypes.data, flat.size)
+    return out.reshape(np.shape(x))
+
+
+def half_to_f32(bits: np.ndarray, half: str = "bf16") -> np.ndarray:
+    return f16_to_f32(bits) if HALF[half] else bf16_to_f32(bits)
+
+
+def f32_to_half_rne(x: np.ndarray, half: str = "bf16") -> np.ndarray:
+    return f32_to_f16_rne(x) if HALF[half] else f32_to_bf16_rne(x)
+
+
+def grad_accumulate(acc: np.ndarray, g: np.ndarray, first: bool, half: str = "bf16") -> None:
+    """One micro-batch's half-precision gradients g into the accumulation buffer acc, in place (copy when
+    ``first``)."""
     if acc.size != g.size:
         raise ValueError("acc and g differ in length")
-    lib().orc_grad_accumulate(_chk(acc, np.uint16, True), _chk(g, np.uint16), acc.size, 1 if first else 0)
+    lib().orc_grad_accumulate_h(_chk(acc, np.uint16, True), _chk(g, np.uint16), acc.size, 1 if first else 0,
+                                HALF[half])
 
 
-def grad_stats(g: np.ndarray, inv_scale: float, sumsq: float = 0.0, found_inf: int = 0):
+def grad_stats(g: np.ndarray, inv_scale: float, sumsq: float = 0.0, found_inf: int = 0, half: str = "bf16"):
     """(sum of squares of unscaled gradients in fp64, non-finite flag), accumulated onto the values passed in."""
     s = C.c_double(sumsq)
     f = C.c_uint32(found_inf)
-    lib().orc_grad_stats(_chk(g, np.uint16), g.size, inv_scale, C.byref(s), C.byref(f))
+    lib().orc_grad_stats_h(_chk(g, np.uint16), g.size, inv_scale, HALF[half], C.byref(s), C.byref(f))
     return s.value, f.value
 
 
@@ -148,23 +196,29 @@ def adamw_consts(hp: HParams, step: int) -> dict:
     return {k: np.float32(getattr(c, k)) for k, _ in _Consts._fields_}
 
 
-def adamw_f32(p, m, v, g, p16, hp: HParams, step: int, gmul: float = 1.0, chunked: bool = False) -> None:
-    """One applied AdamW step in place on fp32 p, m, v from bf16 g; writes bf16 p16.  step is 1-based."""
+def adamw_f32(p, m, v, g, p16, hp: HParams, step: int, gmul: float = 1.0, chunked: bool = False,
+              half: str = "bf16") -> None:
+    """One applied AdamW step in place on fp32 p, m, v from half-precision g; writes the half-precision p16.
+    step is 1-based.  The chunked (multi-threaded, timing only) form exists for bf16."""
     n = p.size
     assert m.size == n and v.size == n and g.size == n and p16.size == n
     h = hp._c()
-    fn = lib().orc_adamw_f32_chunked if chunked else lib().orc_adamw_f32
-    fn(_chk(p, np.float32, True), _chk(m, np.float32, True), _chk(v, np.float32, True), _chk(g, np.uint16),
-       _chk(p16, np.uint16, True), n, C.byref(h), step, float(np.float32(gmul)))
+    args = (_chk(p, np.float32, True), _chk(m, np.float32, True), _chk(v, np.float32, True), _chk(g, np.uint16),
+            _chk(p16, np.uint16, True), n, C.byref(h), step, float(np.float32(gmul)))
+    if chunked:
+        assert half == "bf16"
+        lib().orc_adamw_f32_chunked(*args)
+    else:
+        lib().orc_adamw_f32_h(*args, HALF[half])
 
 
-def adamw_f64(p, m, v, g, hp: HParams, step: int, gmul: float = 1.0) -> None:
+def adamw_f64(p, m, v, g, hp: HParams, step: int, gmul: float = 1.0, half: str = "bf16") -> None:
     """The same step with all state and arithmetic in fp64 (brute-force form used for pinning)."""
     n = p.size
     assert m.size == n and v.size == n and g.size == n
     h = hp._c()
-    lib().orc_adamw_f64(_chk(p, np.float64, True), _chk(m, np.float64, True), _chk(v, np.float64, True),
-                        _chk(g, np.uint16), n, C.byref(h), step, float(gmul))
+    lib().orc_adamw_f64_h(_chk(p, np.float64, True), _chk(m, np.float64, True), _chk(v, np.float64, True),
+                          _chk(g, np.uint16), n, C.byref(h), step, float(gmul), HALF[half])
 
 
 def grad_stats_chunked(g: np.ndarray, inv_scale: float):
@@ -180,7 +234,8 @@ def threads() -> int:
     return lib().orc_threads()
 
 
-def step(subgroups, hp: HParams, steps_applied: int, inv_scale: float = 1.0, max_norm: float = 0.0, order=None):
+def step(subgroups, hp: HParams, steps_applied: int, inv_scale: float = 1.0, max_norm: float = 0.0, order=None,
+         half: str = "bf16"):
     """One whole update step over ``subgroups`` (a list of dicts with numpy arrays p, m, v, g, p16).
 
     Returns (applied, norm, found_inf, gmul).  ``steps_applied`` counts the steps applied before this one."""
@@ -198,6 +253,6 @@ def step(subgroups, hp: HParams, steps_applied: int, inv_scale: float = 1.0, max
         ordp = order.ctypes.data
     h = hp._c()
     nrm, gm, fl = C.c_float(), C.c_float(), C.c_uint32()
-    applied = lib().orc_step(arr, n_sg, ordp, C.byref(h), steps_applied, inv_scale, max_norm, C.byref(nrm),
-                             C.byref(fl), C.byref(gm))
+    applied = lib().orc_step_h(arr, n_sg, ordp, C.byref(h), steps_applied, inv_scale, max_norm, HALF[half],
+                               C.byref(nrm), C.byref(fl), C.byref(gm))
     return bool(applied), np.float32(nrm.value), int(fl.value), np.float32(gm.value)

@@ -77,6 +77,99 @@ void orc_f32_to_bf16_rne_array(const float* f, uint16_t* h, uint64_t n) {
     for (uint64_t i = 0; i < n; ++i) h[i] = orc_f32_to_bf16_rne(f[i]);
 }
 
+/* ---- the other half-precision format ---------------------------------------
+ * The paper allows FP16 or BF16 for gradients and working parameters (Section 2
+ * "Mixed Precision Training"; Algorithm 1 writes FP16).  Every routine below
+ * exists in a form that takes the format: ORC_BF16 (0) or ORC_FP16 (1); the
+ * forms without the argument are the bf16 ones. */
+#define ORC_BF16 0
+#define ORC_FP16 1
+
+/* IEEE binary16 -> fp32: exact.  Built from the bit fields: sign, 5-bit
+ * exponent (bias 15), 10-bit fraction; subnormals are fraction * 2^-24. */
+float orc_f16_to_f32(uint16_t h) {
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 0x1Fu;
+    uint32_t frac = h & 0x3FFu;
+    uint32_t w;
+    if (e == 0x1Fu) {
+        w = sign | 0x7F800000u | (frac << 13); /* inf or NaN, payload kept */
+    } else if (e != 0) {
+        w = sign | ((e + 112u) << 23) | (frac << 13); /* rebias 15 -> 127 */
+    } else if (frac == 0) {
+        w = sign;
+    } else {
+        /* subnormal: normalise the fraction */
+        uint32_t shift = 0;
+        while ((frac & 0x400u) == 0) {
+            frac <<= 1;
+            ++shift;
+        }
+        frac &= 0x3FFu;
+        w = sign | ((113u - shift) << 23) | (frac << 13);
+    }
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return f;
+}
+
+/* fp32 -> IEEE binary16, round to nearest, ties to even; values of
+ * magnitude >= 65520 round to infinity, results below 2^-14 are subnormal
+ * (multiples of 2^-24), every NaN becomes the quiet NaN 0x7E00 with the
+ * input's sign. */
+uint16_t orc_f32_to_f16_rne(float f) {
+    uint32_t w;
+    memcpy(&w, &f, sizeof w);
+    uint16_t sign = (uint16_t)((w >> 16) & 0x8000u);
+    uint32_t mag = w & 0x7FFFFFFFu;
+    if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u);
+    if (mag >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u); /* >= 65520 */
+    int32_t e = (int32_t)(mag >> 23) - 127; /* unbiased exponent */
+    uint32_t sig = (mag & 0x7FFFFFu) | 0x800000u; /* 24-bit significand */
+    uint32_t drop; /* low bits of sig that do not fit */
+    if (e >= -14) {
+        drop = 13;
+    } else if (e >= -25) {
+        drop = (uint32_t)(13 + (-14 - e)); /* subnormal result: fewer kept bits */
+    } else {
+        return sign; /* below half of the smallest subnormal (fp32 zeros and subnormals included) */
+    }
+    uint32_t kept = sig >> drop;
+    uint32_t rest = sig & ((1u << drop) - 1u);
+    uint32_t half = 1u << (drop - 1);
+    if (rest > half || (rest == half && (kept & 1u))) kept += 1u;
+    /* kept now holds the result's significand in units of its last place;
+     * adding the exponent field by arithmetic lets a carry run into it */
+    uint32_t out;
+    if (e >= -14)
+        out = ((uint32_t)(e + 15) << 10) + (kept - 0x400u);
+    else
+        out = kept; /* subnormal (a carry to 0x400 is the smallest normal) */
+    return (uint16_t)(sign | out);
+}
+
+float orc_half_to_f32(uint16_t h, int32_t half) {
+    return half == ORC_FP16 ? orc_f16_to_f32(h) : orc_bf16_to_f32(h);
+}
+
+uint16_t orc_f32_to_half_rne(float f, int32_t half) {
+    return half == ORC_FP16 ? orc_f32_to_f16_rne(f) : orc_f32_to_bf16_rne(f);
+}
+
+/* +-inf or NaN: the exponent field is all ones. */
+static int orc_half_nonfinite(uint16_t h, int32_t half) {
+    uint16_t mask = half == ORC_FP16 ? 0x7C00u : 0x7F80u;
+    return (h & mask) == mask;
+}
+
+void orc_f16_to_f32_array(const uint16_t* h, float* f, uint64_t n) {
+    for (uint64_t i = 0; i < n; ++i) f[i] = orc_f16_to_f32(h[i]);
+}
+
+void orc_f32_to_f16_rne_array(const float* f, uint16_t* h, uint64_t n) {
+    for (uint64_t i = 0; i < n; ++i) h[i] = orc_f32_to_f16_rne(f[i]);
+}
+
 /* ---- gradient accumulation over micro-batches ----------------------------- */
 
 /* The half-precision accumulation buffer of Section 3.2 "Delayed In-place
@@ -87,16 +180,22 @@ void orc_f32_to_bf16_rne_array(const float* f, uint16_t* h, uint64_t n) {
  * widen both (exact), one fp32 addition, round back to bf16 (nearest even).
  * A NaN sum is stored as the canonical quiet NaN 0x7FC0 whatever sign or
  * payload the addition produced, because IEEE 754 leaves those open. */
-void orc_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n,
-                         int32_t first) {
+void orc_grad_accumulate_h(uint16_t* acc, const uint16_t* g, uint64_t n,
+                           int32_t first, int32_t half) {
+    uint16_t nan = half == ORC_FP16 ? 0x7E00u : 0x7FC0u;
     for (uint64_t i = 0; i < n; ++i) {
         if (first) {
             acc[i] = g[i];
             continue;
         }
-        float sum = orc_bf16_to_f32(acc[i]) + orc_bf16_to_f32(g[i]);
-        acc[i] = (sum != sum) ? (uint16_t)0x7FC0u : orc_f32_to_bf16_rne(sum);
+        float sum = orc_half_to_f32(acc[i], half) + orc_half_to_f32(g[i], half);
+        acc[i] = (sum != sum) ? nan : orc_f32_to_half_rne(sum, half);
     }
+}
+
+void orc_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n,
+                         int32_t first) {
+    orc_grad_accumulate_h(acc, g, n, first, ORC_BF16);
 }
 
 /* ---- gradient statistics over one subgroup ------------------------------ */
@@ -104,17 +203,22 @@ void orc_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n,
 /* Adds to *sumsq the fp64 sum of squares of the unscaled gradients
  * u_i = f32(g_i) * inv_scale (one fp32 product), and ORs into *found_inf
  * whether any g_i is +-inf or NaN (bf16 exponent field all ones). */
-void orc_grad_stats(const uint16_t* g, uint64_t n, float inv_scale,
-                    double* sumsq, uint32_t* found_inf) {
+void orc_grad_stats_h(const uint16_t* g, uint64_t n, float inv_scale,
+                      int32_t half, double* sumsq, uint32_t* found_inf) {
     double s = *sumsq;
     uint32_t bad = *found_inf;
     for (uint64_t i = 0; i < n; ++i) {
-        if ((g[i] & 0x7F80u) == 0x7F80u) bad = 1u;
-        float u = orc_bf16_to_f32(g[i]) * inv_scale;
+        if (orc_half_nonfinite(g[i], half)) bad = 1u;
+        float u = orc_half_to_f32(g[i], half) * inv_scale;
         s += (double)u * (double)u;
     }
     *sumsq = s;
     *found_inf = bad;
+}
+
+void orc_grad_stats(const uint16_t* g, uint64_t n, float inv_scale,
+                    double* sumsq, uint32_t* found_inf) {
+    orc_grad_stats_h(g, n, inv_scale, ORC_BF16, sumsq, found_inf);
 }
 
 /* norm = sqrt(sum of squares) rounded to fp32; clip coefficient
@@ -152,13 +256,13 @@ void orc_adamw_consts(const orc_hparams* hp, int64_t step, orc_consts* c) {
 
 /* One applied step (step is the 1-based count of applied steps) on one
  * subgroup, in place.  p16 receives the bf16 working copy of the new p. */
-void orc_adamw_f32(float* p, float* m, float* v, const uint16_t* g,
-                   uint16_t* p16, uint64_t n, const orc_hparams* hp,
-                   int64_t step, float gmul) {
+void orc_adamw_f32_h(float* p, float* m, float* v, const uint16_t* g,
+                     uint16_t* p16, uint64_t n, const orc_hparams* hp,
+                     int64_t step, float gmul, int32_t half) {
     orc_consts c;
     orc_adamw_consts(hp, step, &c);
     for (uint64_t i = 0; i < n; ++i) {
-        float gi = orc_bf16_to_f32(g[i]) * gmul;
+        float gi = orc_half_to_f32(g[i], half) * gmul;
         float t1 = c.beta1 * m[i];
         float t2 = c.omb1 * gi;
         float mi = t1 + t2;
@@ -176,16 +280,22 @@ void orc_adamw_f32(float* p, float* m, float* v, const uint16_t* g,
         m[i] = mi;
         v[i] = vi;
         p[i] = pi;
-        p16[i] = orc_f32_to_bf16_rne(pi);
+        p16[i] = orc_f32_to_half_rne(pi, half);
     }
+}
+
+void orc_adamw_f32(float* p, float* m, float* v, const uint16_t* g,
+                   uint16_t* p16, uint64_t n, const orc_hparams* hp,
+                   int64_t step, float gmul) {
+    orc_adamw_f32_h(p, m, v, g, p16, n, hp, step, gmul, ORC_BF16);
 }
 
 /* The same step with every quantity and operation in fp64, straight from the
  * textbook form (m-hat = m/(1-b1^t), v-hat = v/(1-b2^t)); used to pin the
  * fp32 routine on tiny inputs.  The fp32 hyper-parameters are widened. */
-void orc_adamw_f64(double* p, double* m, double* v, const uint16_t* g,
-                   uint64_t n, const orc_hparams* hp, int64_t step,
-                   double gmul) {
+void orc_adamw_f64_h(double* p, double* m, double* v, const uint16_t* g,
+                     uint64_t n, const orc_hparams* hp, int64_t step,
+                     double gmul, int32_t half) {
     double b1 = hp->beta1, b2 = hp->beta2, lr = hp->lr, eps = hp->eps,
            wd = hp->weight_decay;
     double bc1 = 1.0, bc2 = 1.0;
@@ -194,13 +304,19 @@ void orc_adamw_f64(double* p, double* m, double* v, const uint16_t* g,
         bc2 = 1.0 - pow(b2, (double)step);
     }
     for (uint64_t i = 0; i < n; ++i) {
-        double gi = (double)orc_bf16_to_f32(g[i]) * gmul;
+        double gi = (double)orc_half_to_f32(g[i], half) * gmul;
         m[i] = b1 * m[i] + (1.0 - b1) * gi;
         v[i] = b2 * v[i] + (1.0 - b2) * gi * gi;
         double mhat = m[i] / bc1;
         double vhat = v[i] / bc2;
         p[i] = p[i] * (1.0 - lr * wd) - lr * mhat / (sqrt(vhat) + eps);
     }
+}
+
+void orc_adamw_f64(double* p, double* m, double* v, const uint16_t* g,
+                   uint64_t n, const orc_hparams* hp, int64_t step,
+                   double gmul) {
+    orc_adamw_f64_h(p, m, v, g, n, hp, step, gmul, ORC_BF16);
 }
 
 /* ---- one whole step over a list of subgroups ----------------------------- */
@@ -220,14 +336,14 @@ typedef struct {
  * step was applied (the caller then counts it), 0 when skipped.  order, if
  * not NULL, is the sequence in which subgroups are visited (Algorithm 1's
  * update_order); results do not depend on it. */
-int orc_step(const orc_subgroup* sg, int32_t n_sg, const int32_t* order,
-             const orc_hparams* hp, int64_t steps_applied, float inv_scale,
-             float max_norm, float* out_norm, uint32_t* out_found_inf,
-             float* out_gmul) {
+int orc_step_h(const orc_subgroup* sg, int32_t n_sg, const int32_t* order,
+               const orc_hparams* hp, int64_t steps_applied, float inv_scale,
+               float max_norm, int32_t half, float* out_norm,
+               uint32_t* out_found_inf, float* out_gmul) {
     double sumsq = 0.0;
     uint32_t bad = 0;
     for (int32_t k = 0; k < n_sg; ++k)
-        orc_grad_stats(sg[k].g, sg[k].n, inv_scale, &sumsq, &bad);
+        orc_grad_stats_h(sg[k].g, sg[k].n, inv_scale, half, &sumsq, &bad);
     float norm, coef, gmul;
     orc_norm_finish(sumsq, inv_scale, max_norm, &norm, &coef, &gmul);
     *out_norm = norm;
@@ -236,10 +352,18 @@ int orc_step(const orc_subgroup* sg, int32_t n_sg, const int32_t* order,
     if (bad) return 0;
     for (int32_t k = 0; k < n_sg; ++k) {
         const orc_subgroup* s = &sg[order ? order[k] : k];
-        orc_adamw_f32(s->p, s->m, s->v, s->g, s->p16, s->n, hp,
-                      steps_applied + 1, gmul);
+        orc_adamw_f32_h(s->p, s->m, s->v, s->g, s->p16, s->n, hp,
+                        steps_applied + 1, gmul, half);
     }
     return 1;
+}
+
+int orc_step(const orc_subgroup* sg, int32_t n_sg, const int32_t* order,
+             const orc_hparams* hp, int64_t steps_applied, float inv_scale,
+             float max_norm, float* out_norm, uint32_t* out_found_inf,
+             float* out_gmul) {
+    return orc_step_h(sg, n_sg, order, hp, steps_applied, inv_scale, max_norm,
+                      ORC_BF16, out_norm, out_found_inf, out_gmul);
 }
 
 /* ---- the same routines driven over independent chunks by several threads --
