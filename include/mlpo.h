@@ -24,7 +24,8 @@
  *   - fp32 arrays must be 4-byte aligned and bf16 arrays 2-byte aligned.  The fast kernels are used for a subgroup
  *     whose p, m, v are 16-byte aligned and whose g, p16 are 8-byte aligned; anything else takes a slower
  *     element-wise kernel with identical results.
- *   - bf16 values are passed as raw uint16_t bit patterns (upper half of the IEEE fp32 word).
+ *   - Half-precision values (bf16: the upper half of the IEEE fp32 word; or IEEE binary16, see MLPO_HALF_*) are
+ *     passed as raw uint16_t bit patterns.  Where a comment says bf16 below, read "the call's half format".
  */
 #ifndef MLPO_H
 #define MLPO_H
@@ -79,6 +80,10 @@ typedef struct {
 #define MLPO_TIER_HOST_GRADS 2
 #define MLPO_TIER_FILE 3
 #define MLPO_TILE_DEFAULT 8192
+/* Format of g and p16 (the paper allows FP16 or BF16, Section 2 "Mixed Precision Training", and writes FP16 in
+ * Algorithm 1): bf16, the upper half of the fp32 word, or IEEE binary16.  All subgroups of one call share it. */
+#define MLPO_HALF_BF16 0
+#define MLPO_HALF_FP16 1
 typedef struct {
     float* p;
     float* m;
@@ -88,6 +93,8 @@ typedef struct {
     uint64_t n;
     int32_t tier;
     int32_t tile_elems;
+    int32_t half_format; /* MLPO_HALF_BF16 (0) or MLPO_HALF_FP16 */
+    int32_t reserved;    /* must be 0 */
 } mlpo_subgroup;
 
 /* Floats in the state buffer of a tiled subgroup: ceil(n / tile_elems) * 3 * tile_elems (3 * n if tile_elems is 0). */
@@ -127,7 +134,7 @@ size_t mlpo_norm_workspace_bytes(void);
  * Gradient pass before the update (the usual mixed-precision convention; Section 2 "Mixed Precision Training" of the
  * paper only says that the half-precision gradients are widened to fp32 for the optimizer): over the gradients of ALL
  * n_sg subgroups
- *   found_inf = any g_i with its bf16 exponent field all ones,
+ *   found_inf = any g_i with its exponent field all ones (8 bits in bf16, 5 in fp16),
  *   norm      = sqrt( sum_i ((double)(f32(g_i) * inv_scale))^2 ), rounded to fp32,
  *   clip_coef, gmul as described at mlpo_step_scalars.
  * The sum is taken in fp64 in a fixed order: the result is deterministic for a given argument list.
@@ -148,8 +155,9 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
  * upcasts on the fly (Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"; Section 4.5 runs 1-16
  * backward passes per update).  For every i < n:
  *   first != 0:  acc[i] = g[i]                                  (first micro-batch of a step: no clearing pass needed)
- *   first == 0:  acc[i] = bf16_rne(f32(acc[i]) + f32(g[i]))     (one fp32 addition; a NaN sum is stored as 0x7FC0)
- * The sum of two bf16 values rounded this way is the correctly rounded exact sum.
+ *   first == 0:  acc[i] = half_rne(f32(acc[i]) + f32(g[i]))     (one fp32 addition; a NaN sum is stored as the
+ *                                                                format's quiet NaN, 0x7FC0 for bf16, 0x7E00 for fp16)
+ * The sum of two half-precision values rounded this way is the correctly rounded exact sum in either format.
  *   acc     bf16 accumulation buffer, n elements: device memory, or pinned host memory (then the kernel reads and
  *           writes it over the link, 2 bytes per element each way).
  *   g       bf16 gradients of this micro-batch, n elements, device memory (pinned host memory also works).
@@ -157,10 +165,12 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
  *           otherwise every element is moved on its own (much slower).
  *   blocks  0: one workgroup per 2048 elements (device buffers).  > 0: that many persistent workgroups (<= 4096),
  *           which bounds the requests in flight on the link when acc is on the host; 64 is a good value there.
+ *   half_format  MLPO_HALF_BF16 or MLPO_HALF_FP16: the format of acc and g.
  *   stream  hipStream_t.  Asynchronous.  n = 0 is a no-op; n is at most 2^41.
  * Errors: MLPO_EINVAL, MLPO_EHIP.
  */
-int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks, void* stream);
+int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks,
+                         int32_t half_format, void* stream);
 
 /*
  * The same accumulation, which also gathers the gradient statistics of the finished buffer, for the LAST micro-batch
@@ -169,8 +179,8 @@ int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t f
  * per element saved: over the link when the buffer is in host memory).  Calls for the pieces of one step (one per
  * subgroup, say) add up in the workspace in call order; mlpo_grad_norm_finish then writes the same record as
  * mlpo_grad_unscale_norm would over all the pieces together.
- *   acc, g, n, first, blocks   as for mlpo_grad_accumulate (first != 0: a step with a single micro-batch).  The grid
- *                is always persistent here (blocks = 0: eight workgroups per compute unit).
+ *   acc, g, n, first, blocks, half_format   as for mlpo_grad_accumulate (first != 0: a step with a single
+ *                micro-batch).  The grid is always persistent here (blocks = 0: eight workgroups per compute unit).
  *   inv_scale    1 / loss scale; the same value in every call of the step and in mlpo_grad_norm_finish.
  *   workspace    device, as for mlpo_grad_unscale_norm (same size and alignment); holds the running totals between
  *                the calls, so nothing else may use it until mlpo_grad_norm_finish has run.
@@ -179,7 +189,8 @@ int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t f
  * Errors: MLPO_EINVAL, MLPO_ENOMEM, MLPO_EHIP.
  */
 int mlpo_grad_accumulate_norm(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks,
-                              float inv_scale, void* workspace, size_t workspace_bytes, int32_t begin, void* stream);
+                              int32_t half_format, float inv_scale, void* workspace, size_t workspace_bytes,
+                              int32_t begin, void* stream);
 
 /* Derives norm, clip coefficient, gradient multiplier and flag (see mlpo_grad_unscale_norm) from the totals that the
  * mlpo_grad_accumulate_norm calls of this step left in workspace, and writes them to out (device, 16-byte aligned).
@@ -198,7 +209,8 @@ int mlpo_grad_norm_finish(void* workspace, size_t workspace_bytes, float inv_sca
  *   m' = beta1 * m + omb1 * g
  *   v' = beta2 * v + omb2 * (g * g)
  *   p' = p * decay - step_size * (m' / (sqrt(v') / sqbc2 + eps))
- *   p16 = bf16(p') rounded to nearest, ties to even
+ *   p16 = half(p') rounded to nearest, ties to even (fp16: magnitudes from 65520 up become infinity, results below
+ *         2^-14 are subnormal)
  *
  *   sg, n_sg     host array; every tier must be MLPO_TIER_HBM; all pointers device; n may be 0.
  *   hp           host pointer.  lr, eps, weight_decay finite and >= 0; 0 <= beta < 1.

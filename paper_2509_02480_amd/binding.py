@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmlpo.so")
 
 MLPO_OK, MLPO_EINVAL, MLPO_EHIP, MLPO_ENOMEM, MLPO_EIO = 0, -1, -2, -3, -4
 TIER_HBM, TIER_HOST, TIER_HOST_GRADS, TIER_FILE = 0, 1, 2, 3
+HALF_BF16, HALF_FP16 = 0, 1
 MAX_SLOTS = 64
 
 TILE_DEFAULT = 8192
@@ -43,7 +44,8 @@ class HParamsC(C.Structure):
 
 class SubgroupC(C.Structure):
     _fields_ = [("p", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p), ("g", C.c_void_p), ("p16", C.c_void_p),
-                ("n", C.c_uint64), ("tier", C.c_int32), ("tile_elems", C.c_int32)]
+                ("n", C.c_uint64), ("tier", C.c_int32), ("tile_elems", C.c_int32), ("half_format", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class StepScalarsC(C.Structure):
@@ -123,10 +125,11 @@ def lib():
         L.mlpo_grad_unscale_norm.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_size_t,
                                              C.c_void_p, C.c_void_p]
         L.mlpo_grad_accumulate.restype = C.c_int
-        L.mlpo_grad_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p]
+        L.mlpo_grad_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_int32,
+                                           C.c_void_p]
         L.mlpo_grad_accumulate_norm.restype = C.c_int
-        L.mlpo_grad_accumulate_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_float,
-                                                C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+        L.mlpo_grad_accumulate_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_int32,
+                                                C.c_float, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
         L.mlpo_grad_norm_finish.restype = C.c_int
         L.mlpo_grad_norm_finish.argtypes = [C.c_void_p, C.c_size_t, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         L.mlpo_adamw_step.restype = C.c_int
@@ -175,21 +178,22 @@ def _stream(s) -> Optional[int]:
     return int(h) or None
 
 
-def subgroup(p, m, v, g, p16, n: Optional[int] = None, tier: int = TIER_HBM, tile_elems: int = 0) -> SubgroupC:
+def subgroup(p, m, v, g, p16, n: Optional[int] = None, tier: int = TIER_HBM, tile_elems: int = 0,
+             half: int = HALF_BF16) -> SubgroupC:
     """One descriptor from five buffers (tensors or addresses).  ``n`` defaults to the gradient tensor's length."""
     if n is None:
         n = g.numel()
-    return SubgroupC(_ptr(p), _ptr(m), _ptr(v), _ptr(g), _ptr(p16), int(n), int(tier), int(tile_elems))
+    return SubgroupC(_ptr(p), _ptr(m), _ptr(v), _ptr(g), _ptr(p16), int(n), int(tier), int(tile_elems), int(half), 0)
 
 
 def tiled_subgroup(state, g, p16, n: Optional[int] = None, tier: int = TIER_HBM,
-                   tile_elems: int = TILE_DEFAULT) -> SubgroupC:
+                   tile_elems: int = TILE_DEFAULT, half: int = HALF_BF16) -> SubgroupC:
     """Descriptor of a subgroup whose fp32 state is one tiled buffer (see mlpo.h): m and v follow from ``state``."""
     if n is None:
         n = g.numel()
     base = _ptr(state)
     return SubgroupC(base, base + 4 * tile_elems, base + 8 * tile_elems, _ptr(g), _ptr(p16), int(n), int(tier),
-                     int(tile_elems))
+                     int(tile_elems), int(half), 0)
 
 
 def mlpo_state_floats(n: int, tile_elems: int) -> int:
@@ -327,20 +331,23 @@ def mlpo_update_bandwidth(bandwidth: Sequence[float], bytes_moved: Sequence[floa
     return list(bw)
 
 
-def mlpo_grad_accumulate(acc, g, n: Optional[int] = None, first: bool = False, blocks: int = 0, stream=None) -> None:
-    """One micro-batch's bf16 gradients into the bf16 accumulation buffer; see mlpo.h."""
+def mlpo_grad_accumulate(acc, g, n: Optional[int] = None, first: bool = False, blocks: int = 0, stream=None,
+                         half: int = HALF_BF16) -> None:
+    """One micro-batch's half-precision gradients into the accumulation buffer; see mlpo.h."""
     if n is None:
         n = g.numel()
-    _check(lib().mlpo_grad_accumulate(_ptr(acc), _ptr(g), int(n), 1 if first else 0, int(blocks), _stream(stream)))
+    _check(lib().mlpo_grad_accumulate(_ptr(acc), _ptr(g), int(n), 1 if first else 0, int(blocks), int(half),
+                                      _stream(stream)))
 
 
 def mlpo_grad_accumulate_norm(acc, g, n: Optional[int], first: bool, blocks: int, inv_scale: float, workspace,
-                              workspace_bytes: int, begin: bool, stream=None) -> None:
+                              workspace_bytes: int, begin: bool, stream=None, half: int = HALF_BF16) -> None:
     """The last micro-batch of a step: accumulate and gather the gradient statistics; see mlpo.h."""
     if n is None:
         n = g.numel()
-    _check(lib().mlpo_grad_accumulate_norm(_ptr(acc), _ptr(g), int(n), 1 if first else 0, int(blocks), inv_scale,
-                                           _ptr(workspace), int(workspace_bytes), 1 if begin else 0, _stream(stream)))
+    _check(lib().mlpo_grad_accumulate_norm(_ptr(acc), _ptr(g), int(n), 1 if first else 0, int(blocks), int(half),
+                                           inv_scale, _ptr(workspace), int(workspace_bytes), 1 if begin else 0,
+                                           _stream(stream)))
 
 
 def mlpo_grad_norm_finish(workspace, workspace_bytes: int, inv_scale: float, max_norm: float, out, stream=None) -> None:

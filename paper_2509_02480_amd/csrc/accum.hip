@@ -27,43 +27,61 @@ constexpr int kBlock = 256;
 constexpr int kUnrollOneTile = 1;
 constexpr int kUnrollPersistent = 4;
 
-// One bf16 sum, operands and result in the low 16 bits.
+// One half-precision sum, operands and result in the low 16 bits: widen both (exact), one fp32 addition, round to
+// nearest even; a NaN sum becomes the format's canonical quiet NaN.  HALF: 0 = bf16, 1 = IEEE binary16.
+template <int HALF>
 __device__ __forceinline__ uint32_t add_one(uint32_t a, uint32_t g) {
-    const float s = __uint_as_float(a << 16) + __uint_as_float(g << 16);
-    const uint32_t r = __float_as_uint(s);
-    const uint32_t rounded = (r + 0x7FFFu + ((r >> 16) & 1u)) >> 16;
-    return (s != s) ? 0x7FC0u : rounded;
+    if constexpr (HALF == 0) {
+        const float s = __uint_as_float(a << 16) + __uint_as_float(g << 16);
+        const uint32_t r = __float_as_uint(s);
+        const uint32_t rounded = (r + 0x7FFFu + ((r >> 16) & 1u)) >> 16;
+        return (s != s) ? 0x7FC0u : rounded;
+    } else {
+        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)a) + (float)__builtin_bit_cast(_Float16, (uint16_t)g);
+        const uint32_t rounded = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)s);
+        return (s != s) ? 0x7E00u : rounded;
+    }
 }
 
-// Two bf16 sums packed in a 32-bit word.
+// Two sums packed in a 32-bit word.
+template <int HALF>
 __device__ __forceinline__ uint32_t add_word(uint32_t a, uint32_t g) {
-    return add_one(a & 0xFFFFu, g & 0xFFFFu) | (add_one(a >> 16, g >> 16) << 16);
+    return add_one<HALF>(a & 0xFFFFu, g & 0xFFFFu) | (add_one<HALF>(a >> 16, g >> 16) << 16);
 }
 
+template <int HALF>
 __device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 g) {
     u32x4 r;
-    r.x = add_word(a.x, g.x);
-    r.y = add_word(a.y, g.y);
-    r.z = add_word(a.z, g.z);
-    r.w = add_word(a.w, g.w);
+    r.x = add_word<HALF>(a.x, g.x);
+    r.y = add_word<HALF>(a.y, g.y);
+    r.z = add_word<HALF>(a.z, g.z);
+    r.w = add_word<HALF>(a.w, g.w);
     return r;
 }
 
 // Statistics of one stored word (two new bf16 values): squares of the unscaled values in fp64, non-finite test on
 // the exponent field - the arithmetic of the gradient pass, applied to values that are in registers anyway.
-__device__ __forceinline__ void stats_word(uint32_t w, float inv_scale, double& sum, uint32_t& bad) {
-    bad |= (uint32_t)((w & 0x7F80u) == 0x7F80u) | (uint32_t)((w & 0x7F800000u) == 0x7F800000u);
-    const float u0 = __uint_as_float(w << 16) * inv_scale;
-    const float u1 = __uint_as_float(w & 0xFFFF0000u) * inv_scale;
-    sum = fma((double)u0, (double)u0, sum);
-    sum = fma((double)u1, (double)u1, sum);
+template <int HALF>
+__device__ __forceinline__ void stats_one(uint32_t h, float inv_scale, double& sum, uint32_t& bad) {
+    constexpr uint32_t kExp = HALF == 0 ? 0x7F80u : 0x7C00u;
+    bad |= (uint32_t)((h & kExp) == kExp);
+    const float u =
+        (HALF == 0 ? __uint_as_float(h << 16) : (float)__builtin_bit_cast(_Float16, (uint16_t)h)) * inv_scale;
+    sum = fma((double)u, (double)u, sum);
 }
 
+template <int HALF>
+__device__ __forceinline__ void stats_word(uint32_t w, float inv_scale, double& sum, uint32_t& bad) {
+    stats_one<HALF>(w & 0xFFFFu, inv_scale, sum, bad);
+    stats_one<HALF>(w >> 16, inv_scale, sum, bad);
+}
+
+template <int HALF>
 __device__ __forceinline__ void stats_vec(u32x4 r, float inv_scale, double& sum, uint32_t& bad) {
-    stats_word(r.x, inv_scale, sum, bad);
-    stats_word(r.y, inv_scale, sum, bad);
-    stats_word(r.z, inv_scale, sum, bad);
-    stats_word(r.w, inv_scale, sum, bad);
+    stats_word<HALF>(r.x, inv_scale, sum, bad);
+    stats_word<HALF>(r.y, inv_scale, sum, bad);
+    stats_word<HALF>(r.z, inv_scale, sum, bad);
+    stats_word<HALF>(r.w, inv_scale, sum, bad);
 }
 
 // Lanes -> wavefront (shuffle), wavefronts -> workgroup (LDS), in a fixed order; one partial per workgroup.
@@ -96,7 +114,7 @@ __device__ __forceinline__ void block_partial(double sum, uint32_t bad, NormWork
 
 // acc and g point at the 16-byte aligned vector body; n8 = number of 8-element vectors in it.  With STATS every
 // workgroup also leaves the statistics of the values it stored in ws->partial / ws->flag [slot0 + blockIdx.x].
-template <bool FIRST, bool STATS, int kUnroll>
+template <bool FIRST, bool STATS, int kUnroll, int HALF>
 __global__ void __launch_bounds__(kBlock) accumulate_v8_kernel(u32x4* __restrict__ acc, const u32x4* __restrict__ g,
                                                                const uint64_t n8, const float inv_scale,
                                                                NormWorkspace* __restrict__ ws, const uint32_t slot0) {
@@ -115,18 +133,18 @@ __global__ void __launch_bounds__(kBlock) accumulate_v8_kernel(u32x4* __restrict
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                const u32x4 r = FIRST ? b[u] : add_vec(a[u], b[u]);
+                const u32x4 r = FIRST ? b[u] : add_vec<HALF>(a[u], b[u]);
                 __builtin_nontemporal_store(r, acc + base + (uint64_t)u * kBlock);
-                if (STATS) stats_vec(r, inv_scale, sum, bad);
+                if (STATS) stats_vec<HALF>(r, inv_scale, sum, bad);
             }
         } else {
             for (int u = 0; u < kUnroll; ++u) {
                 const uint64_t i = base + (uint64_t)u * kBlock;
                 if (i < n8) {
                     u32x4 r = __builtin_nontemporal_load(g + i);
-                    if (!FIRST) r = add_vec(__builtin_nontemporal_load(acc + i), r);
+                    if (!FIRST) r = add_vec<HALF>(__builtin_nontemporal_load(acc + i), r);
                     __builtin_nontemporal_store(r, acc + i);
-                    if (STATS) stats_vec(r, inv_scale, sum, bad);
+                    if (STATS) stats_vec<HALF>(r, inv_scale, sum, bad);
                 }
             }
         }
@@ -135,7 +153,7 @@ __global__ void __launch_bounds__(kBlock) accumulate_v8_kernel(u32x4* __restrict
 }
 
 // Element-wise form for heads, tails and buffers whose addresses differ modulo 16.
-template <bool FIRST, bool STATS>
+template <bool FIRST, bool STATS, int HALF>
 __global__ void __launch_bounds__(kBlock) accumulate_v1_kernel(uint16_t* __restrict__ acc,
                                                                const uint16_t* __restrict__ g, const uint64_t n,
                                                                const float inv_scale, NormWorkspace* __restrict__ ws,
@@ -144,18 +162,14 @@ __global__ void __launch_bounds__(kBlock) accumulate_v1_kernel(uint16_t* __restr
     double sum = 0.0;
     uint32_t bad = 0;
     for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
-        const uint32_t r = FIRST ? (uint32_t)g[i] : add_one(acc[i], g[i]);
+        const uint32_t r = FIRST ? (uint32_t)g[i] : add_one<HALF>(acc[i], g[i]);
         acc[i] = (uint16_t)r;
-        if (STATS) {
-            bad |= (uint32_t)((r & 0x7F80u) == 0x7F80u);
-            const float u = __uint_as_float(r << 16) * inv_scale;
-            sum = fma((double)u, (double)u, sum);
-        }
+        if (STATS) stats_one<HALF>(r, inv_scale, sum, bad);
     }
     if (STATS) block_partial(sum, bad, ws, slot0 + blockIdx.x);
 }
 
-template <bool FIRST, bool STATS>
+template <bool FIRST, bool STATS, int HALF>
 int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t st, NormWorkspace* ws,
            float inv_scale, int* n_partials) {
     const int cus = num_cus();
@@ -171,7 +185,7 @@ int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t
         // no common 16-byte phase: everything goes element by element
         const uint64_t want = (n + kBlock - 1) / kBlock;
         const uint32_t grid = (uint32_t)(want < persistent ? want : persistent);
-        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS>), dim3(grid), dim3(kBlock), 0, st, acc, g, n, inv_scale,
+        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS, HALF>), dim3(grid), dim3(kBlock), 0, st, acc, g, n, inv_scale,
                            ws, slot);
         MLPO_HIP(hipGetLastError());
         if (STATS) *n_partials = (int)grid;
@@ -189,8 +203,8 @@ int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t
         const uint32_t grid = (uint32_t)(persistent_grid && tiles > persistent ? persistent : tiles);
         u32x4* av = reinterpret_cast<u32x4*>(acc + head);
         const u32x4* gv = reinterpret_cast<const u32x4*>(g + head);
-        auto kernel = persistent_grid ? accumulate_v8_kernel<FIRST, STATS, kUnrollPersistent>
-                                      : accumulate_v8_kernel<FIRST, STATS, kUnrollOneTile>;
+        auto kernel = persistent_grid ? accumulate_v8_kernel<FIRST, STATS, kUnrollPersistent, HALF>
+                                      : accumulate_v8_kernel<FIRST, STATS, kUnrollOneTile, HALF>;
         hipEvent_t t0, t1;
         if (timing_enabled() && timing_acquire(kTimedAccumulate, &t0, &t1))
             hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, av, gv, n8, inv_scale, ws, slot);
@@ -200,14 +214,14 @@ int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t
         slot += grid;
     }
     if (head > 0) {
-        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS>), dim3(1), dim3(kBlock), 0, st, acc, g, head, inv_scale,
+        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS, HALF>), dim3(1), dim3(kBlock), 0, st, acc, g, head, inv_scale,
                            ws, slot);
         MLPO_HIP(hipGetLastError());
         slot += 1;
     }
     if (tail > 0) {
         const uint64_t off = head + n8 * 8u;
-        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS>), dim3(1), dim3(kBlock), 0, st, acc + off, g + off, tail,
+        hipLaunchKernelGGL((accumulate_v1_kernel<FIRST, STATS, HALF>), dim3(1), dim3(kBlock), 0, st, acc + off, g + off, tail,
                            inv_scale, ws, slot);
         MLPO_HIP(hipGetLastError());
         slot += 1;
@@ -218,13 +232,20 @@ int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t
 
 }  // namespace
 
-int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st,
-                           NormWorkspace* stats, float inv_scale, int* n_partials) {
+template <int HALF>
+static int launch_format(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st,
+                         NormWorkspace* stats, float inv_scale, int* n_partials) {
     if (stats != nullptr)
-        return first ? launch<true, true>(acc, g, n, blocks, st, stats, inv_scale, n_partials)
-                     : launch<false, true>(acc, g, n, blocks, st, stats, inv_scale, n_partials);
-    return first ? launch<true, false>(acc, g, n, blocks, st, nullptr, 1.0f, nullptr)
-                 : launch<false, false>(acc, g, n, blocks, st, nullptr, 1.0f, nullptr);
+        return first ? launch<true, true, HALF>(acc, g, n, blocks, st, stats, inv_scale, n_partials)
+                     : launch<false, true, HALF>(acc, g, n, blocks, st, stats, inv_scale, n_partials);
+    return first ? launch<true, false, HALF>(acc, g, n, blocks, st, nullptr, 1.0f, nullptr)
+                 : launch<false, false, HALF>(acc, g, n, blocks, st, nullptr, 1.0f, nullptr);
+}
+
+int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, int32_t half,
+                           hipStream_t st, NormWorkspace* stats, float inv_scale, int* n_partials) {
+    return half == MLPO_HALF_FP16 ? launch_format<1>(acc, g, n, first, blocks, st, stats, inv_scale, n_partials)
+                                  : launch_format<0>(acc, g, n, first, blocks, st, stats, inv_scale, n_partials);
 }
 
 }  // namespace mlpo

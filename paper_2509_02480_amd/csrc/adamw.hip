@@ -84,7 +84,35 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
     return r;
 }
 
-// One element.  graw is the widened bf16 gradient, still scaled.
+// fp32 -> IEEE binary16 bits, round to nearest even (the conversion instruction under the default rounding mode;
+// overflow to infinity and subnormal results included); NaN -> quiet NaN with the sign kept.
+__device__ __forceinline__ uint32_t f16_rne(float f) {
+    const _Float16 h = (_Float16)f;
+    uint32_t r = (uint32_t)__builtin_bit_cast(uint16_t, h);
+    const uint32_t w = __float_as_uint(f);
+    if ((w & 0x7FFFFFFFu) > 0x7F800000u) r = ((w >> 16) & 0x8000u) | 0x7E00u;
+    return r;
+}
+
+// Half-precision bits (in the low 16 bits of x) -> fp32, exact.  HALF: 0 = bf16, 1 = IEEE binary16.
+template <int HALF>
+__device__ __forceinline__ float widen_low(uint32_t x) {
+    if constexpr (HALF == 0)
+        return __uint_as_float(x << 16);
+    else
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)x);
+}
+// The same for the value in the high 16 bits of x.
+template <int HALF>
+__device__ __forceinline__ float widen_high(uint32_t x) {
+    if constexpr (HALF == 0)
+        return __uint_as_float(x & 0xFFFF0000u);
+    else
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(x >> 16));
+}
+
+// One element.  graw is the widened half-precision gradient, still scaled.
+template <int HALF>
 __device__ __forceinline__ uint32_t update_one(float& p, float& m, float& v, float graw, float gmul,
                                                const AdamwConsts& c) {
     const float g = graw * gmul;
@@ -95,18 +123,18 @@ __device__ __forceinline__ uint32_t update_one(float& p, float& m, float& v, flo
     p = pn;
     m = mn;
     v = vn;
-    return bf16_rne(pn);
+    return HALF == 0 ? bf16_rne(pn) : f16_rne(pn);
 }
 
+template <int HALF>
 __device__ __forceinline__ u32x2 update_four(f32x4& p, f32x4& m, f32x4& v, u32x2 g, float gmul,
                                              const AdamwConsts& c) {
-    const float graw[4] = {__uint_as_float(g.x << 16), __uint_as_float(g.x & 0xFFFF0000u),
-                           __uint_as_float(g.y << 16), __uint_as_float(g.y & 0xFFFF0000u)};
+    const float graw[4] = {widen_low<HALF>(g.x), widen_high<HALF>(g.x), widen_low<HALF>(g.y), widen_high<HALF>(g.y)};
     uint32_t h[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float pk = p[k], mk = m[k], vk = v[k];
-        h[k] = update_one(pk, mk, vk, graw[k], gmul, c);
+        h[k] = update_one<HALF>(pk, mk, vk, graw[k], gmul, c);
         p[k] = pk;
         m[k] = mk;
         v[k] = vk;
@@ -187,11 +215,19 @@ struct Regs {
     }
 
     __device__ __forceinline__ void update_store(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
+        if (c.half == 0)
+            update_store_as<0>(t, tid, gmul, c);
+        else
+            update_store_as<1>(t, tid, gmul, c);
+    }
+
+    template <int HALF>
+    __device__ __forceinline__ void update_store_as(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
         if (t.cnt == BLOCK * UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
-                const u32x2 H = update_four(P[u], M[u], V[u], G[u], gmul, c);
+                const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
                 st<NT>(t.p + i, P[u]);
                 st<NT>(t.m + i, M[u]);
                 st<NT>(t.v + i, V[u]);
@@ -202,7 +238,7 @@ struct Regs {
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
                 if (i < t.cnt) {
-                    const u32x2 H = update_four(P[u], M[u], V[u], G[u], gmul, c);
+                    const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
                     st<NT>(t.p + i, P[u]);
                     st<NT>(t.m + i, M[u]);
                     st<NT>(t.v + i, V[u]);
@@ -284,8 +320,10 @@ __global__ void __launch_bounds__(kBlock1) adamw_v1_kernel(const ScalarBatch b, 
         const uint64_t j = base + (uint32_t)(u * kBlock1) + threadIdx.x;
         if (j < d.n) {
             float pp = d.p[j], mm = d.m[j], vv = d.v[j];
-            const float graw = __uint_as_float((uint32_t)d.g[j] << 16);
-            d.p16[j] = (uint16_t)update_one(pp, mm, vv, graw, gmul, c);
+            if (c.half == 0)
+                d.p16[j] = (uint16_t)update_one<0>(pp, mm, vv, widen_low<0>(d.g[j]), gmul, c);
+            else
+                d.p16[j] = (uint16_t)update_one<1>(pp, mm, vv, widen_low<1>(d.g[j]), gmul, c);
             d.p[j] = pp;
             d.m[j] = mm;
             d.v[j] = vv;

@@ -110,7 +110,7 @@ int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step) {
 }
 
 // The scalars of one step: exact expressions evaluated in double, then one rounding to fp32 each.
-AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step) {
+AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step, int32_t half) {
     const double beta1 = hp.beta1, beta2 = hp.beta2;
     double corr1 = 1.0, corr2 = 1.0;
     if (hp.bias_correction != 0) {
@@ -126,6 +126,7 @@ AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step) {
     c.step_size = (float)((double)hp.lr / corr1);
     c.sqbc2 = (float)sqrt(corr2);
     c.decay = (float)(1.0 - (double)hp.lr * (double)hp.weight_decay);
+    c.half = half;
     return c;
 }
 
@@ -134,11 +135,20 @@ bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 
 uint64_t round_up(uint64_t x, uint64_t to) { return (x + to - 1) / to * to; }
 
+int32_t table_half_format(const mlpo_subgroup* sg, int32_t n_sg) {
+    return n_sg > 0 ? sg[0].half_format : MLPO_HALF_BF16;
+}
+
 int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, int allow_host) {
     if (n_sg < 0) return fail(MLPO_EINVAL, "n_sg is negative");
     if (n_sg > 0 && sg == nullptr) return fail(MLPO_EINVAL, "subgroup array is NULL");
     for (int32_t i = 0; i < n_sg; ++i) {
         const mlpo_subgroup& s = sg[i];
+        if (s.half_format != MLPO_HALF_BF16 && s.half_format != MLPO_HALF_FP16)
+            return fail(MLPO_EINVAL, "subgroup %d: unknown half format %d", i, s.half_format);
+        if (s.half_format != sg[0].half_format)
+            return fail(MLPO_EINVAL, "subgroup %d: all subgroups of a call must share one half format", i);
+        if (s.reserved != 0) return fail(MLPO_EINVAL, "subgroup %d: reserved field is not 0", i);
         if (s.n > ((uint64_t)1 << 48)) return fail(MLPO_EINVAL, "subgroup %d: n is implausibly large", i);
         if (s.n != 0 && s.g == nullptr) return fail(MLPO_EINVAL, "subgroup %d: g is NULL", i);
         if (misaligned(s.g, 2)) return fail(MLPO_EINVAL, "subgroup %d: g is not 2-byte aligned", i);
@@ -176,7 +186,8 @@ int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, i
     return MLPO_OK;
 }
 
-static int check_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t blocks) {
+static int check_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t blocks, int32_t half) {
+    if (half != MLPO_HALF_BF16 && half != MLPO_HALF_FP16) return fail(MLPO_EINVAL, "unknown half format %d", half);
     if (acc == nullptr || g == nullptr) return fail(MLPO_EINVAL, "acc or g is NULL");
     if (misaligned(acc, 2) || misaligned(g, 2)) return fail(MLPO_EINVAL, "acc or g not 2-byte aligned");
     if (n > (1ull << 41)) return fail(MLPO_EINVAL, "n too large (at most 2^41 elements per call)");
@@ -251,27 +262,29 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
     return launch_grad_norm(sg, n_sg, inv_scale, max_norm, workspace, out, static_cast<hipStream_t>(stream));
 }
 
-int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks, void* stream) {
+int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks,
+                         int32_t half_format, void* stream) {
     if (n == 0) return MLPO_OK;
-    const int rc = check_accumulate(acc, g, n, blocks);
+    const int rc = check_accumulate(acc, g, n, blocks, half_format);
     if (rc != MLPO_OK) return rc;
-    return launch_grad_accumulate(acc, g, n, first != 0, blocks, static_cast<hipStream_t>(stream));
+    return launch_grad_accumulate(acc, g, n, first != 0, blocks, half_format, static_cast<hipStream_t>(stream));
 }
 
 int mlpo_grad_accumulate_norm(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks,
-                              float inv_scale, void* workspace, size_t workspace_bytes, int32_t begin, void* stream) {
+                              int32_t half_format, float inv_scale, void* workspace, size_t workspace_bytes,
+                              int32_t begin, void* stream) {
     int rc = check_norm_workspace(workspace, workspace_bytes);
     if (rc != MLPO_OK) return rc;
     if (!(isfinite(inv_scale) && inv_scale > 0.0f)) return fail(MLPO_EINVAL, "inv_scale must be finite and > 0");
     if (n != 0) {
-        rc = check_accumulate(acc, g, n, blocks);
+        rc = check_accumulate(acc, g, n, blocks, half_format);
         if (rc != MLPO_OK) return rc;
     }
     NormWorkspace* ws = static_cast<NormWorkspace*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     int n_partials = 0;
     if (n != 0) {
-        rc = launch_grad_accumulate(acc, g, n, first != 0, blocks, st, ws, inv_scale, &n_partials);
+        rc = launch_grad_accumulate(acc, g, n, first != 0, blocks, half_format, st, ws, inv_scale, &n_partials);
         if (rc != MLPO_OK) return rc;
     }
     if (n_partials == 0 && begin == 0) return MLPO_OK;
@@ -297,7 +310,7 @@ int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hpar
     if (rc != MLPO_OK) return rc;
     if (scalars != nullptr && misaligned(scalars, 16)) return fail(MLPO_EINVAL, "scalars not 16-byte aligned");
     if (n_sg == 0) return MLPO_OK;
-    const AdamwConsts c = make_consts(*hp, step);
+    const AdamwConsts c = make_consts(*hp, step, table_half_format(sg, n_sg));
     std::vector<SgView> views((size_t)n_sg);
     for (int32_t i = 0; i < n_sg; ++i) views[i] = SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems};
     return launch_adamw(views.data(), n_sg, c, scalars, static_cast<hipStream_t>(stream));

@@ -29,38 +29,50 @@ struct NormBatch {
     uint32_t tile_begin[kMaxSg + 1];
     uint8_t head[kMaxSg];  // elements before body (0..7), handled by the first tile
     int32_t n_sg;
+    int32_t half;  // MLPO_HALF_BF16 or MLPO_HALF_FP16
 };
 
 using Workspace = NormWorkspace;
 constexpr int kMaxGrid = kNormMaxPartials;
 
+// Two gradients packed in a 32-bit word / one gradient: non-finite test on the exponent field, unscale in fp32,
+// square and accumulate in fp64.  HALF: 0 = bf16, 1 = IEEE binary16.
+template <int HALF>
 __device__ __forceinline__ void accum_word(uint32_t w, float inv_scale, double& acc, uint32_t& bad) {
-    bad |= (uint32_t)((w & 0x7F80u) == 0x7F80u) | (uint32_t)((w & 0x7F800000u) == 0x7F800000u);
-    const float u0 = __uint_as_float(w << 16) * inv_scale;
-    const float u1 = __uint_as_float(w & 0xFFFF0000u) * inv_scale;
+    constexpr uint32_t kExp = HALF == 0 ? 0x7F80u : 0x7C00u;
+    bad |= (uint32_t)((w & kExp) == kExp) | (uint32_t)((w & (kExp << 16)) == (kExp << 16));
+    float u0, u1;
+    if constexpr (HALF == 0) {
+        u0 = __uint_as_float(w << 16) * inv_scale;
+        u1 = __uint_as_float(w & 0xFFFF0000u) * inv_scale;
+    } else {
+        u0 = (float)__builtin_bit_cast(_Float16, (uint16_t)w) * inv_scale;
+        u1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)) * inv_scale;
+    }
     acc = fma((double)u0, (double)u0, acc);
     acc = fma((double)u1, (double)u1, acc);
 }
 
+template <int HALF>
 __device__ __forceinline__ void accum_half(uint16_t h, float inv_scale, double& acc, uint32_t& bad) {
-    bad |= (uint32_t)((h & 0x7F80u) == 0x7F80u);
-    const float u = __uint_as_float((uint32_t)h << 16) * inv_scale;
+    constexpr uint32_t kExp = HALF == 0 ? 0x7F80u : 0x7C00u;
+    bad |= (uint32_t)((h & kExp) == kExp);
+    const float u = (HALF == 0 ? __uint_as_float((uint32_t)h << 16) : (float)__builtin_bit_cast(_Float16, h)) * inv_scale;
     acc = fma((double)u, (double)u, acc);
 }
 
-__global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, const float inv_scale,
-                                                            Workspace* __restrict__ ws) {
+// The streaming part of the kernel below for one format.
+template <int HALF>
+__device__ __forceinline__ void stats_tiles(const NormBatch& b, const float inv_scale, double& acc, uint32_t& bad) {
     const uint32_t total = b.tile_begin[b.n_sg];
     const uint32_t tid = threadIdx.x;
-    double acc = 0.0;
-    uint32_t bad = 0;
     int s = 0;
     for (uint32_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         while (tile >= b.tile_begin[s + 1]) ++s;
         const uint32_t t_in = tile - b.tile_begin[s];
         const uint16_t* __restrict__ body = b.body[s];
         const uint64_t n_body = b.n_body[s];
-        if (t_in == 0 && tid < b.head[s]) accum_half(*(body - 1 - tid), inv_scale, acc, bad);
+        if (t_in == 0 && tid < b.head[s]) accum_half<HALF>(*(body - 1 - tid), inv_scale, acc, bad);
         const uint64_t base = (uint64_t)t_in * kTile;
         const u32x4* __restrict__ q = reinterpret_cast<const u32x4*>(body + base);
         if (n_body >= base + kTile) {
@@ -69,10 +81,10 @@ __global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, c
             for (int u = 0; u < kUnroll; ++u) w[u] = __builtin_nontemporal_load(q + u * kBlock + tid);
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                accum_word(w[u].x, inv_scale, acc, bad);
-                accum_word(w[u].y, inv_scale, acc, bad);
-                accum_word(w[u].z, inv_scale, acc, bad);
-                accum_word(w[u].w, inv_scale, acc, bad);
+                accum_word<HALF>(w[u].x, inv_scale, acc, bad);
+                accum_word<HALF>(w[u].y, inv_scale, acc, bad);
+                accum_word<HALF>(w[u].z, inv_scale, acc, bad);
+                accum_word<HALF>(w[u].w, inv_scale, acc, bad);
             }
         } else if (n_body > base) {
             const uint64_t rem = n_body - base;  // < kTile
@@ -81,16 +93,27 @@ __global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, c
                 const uint64_t e = (uint64_t)i * 8;
                 if (e + 8 <= rem) {
                     const u32x4 w = __builtin_nontemporal_load(q + i);
-                    accum_word(w.x, inv_scale, acc, bad);
-                    accum_word(w.y, inv_scale, acc, bad);
-                    accum_word(w.z, inv_scale, acc, bad);
-                    accum_word(w.w, inv_scale, acc, bad);
+                    accum_word<HALF>(w.x, inv_scale, acc, bad);
+                    accum_word<HALF>(w.y, inv_scale, acc, bad);
+                    accum_word<HALF>(w.z, inv_scale, acc, bad);
+                    accum_word<HALF>(w.w, inv_scale, acc, bad);
                 } else if (e < rem) {
-                    for (uint64_t j = base + e; j < n_body; ++j) accum_half(body[j], inv_scale, acc, bad);
+                    for (uint64_t j = base + e; j < n_body; ++j) accum_half<HALF>(body[j], inv_scale, acc, bad);
                 }
             }
         }
     }
+}
+
+__global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, const float inv_scale,
+                                                            Workspace* __restrict__ ws) {
+    const uint32_t tid = threadIdx.x;
+    double acc = 0.0;
+    uint32_t bad = 0;
+    if (b.half == 0)
+        stats_tiles<0>(b, inv_scale, acc, bad);
+    else
+        stats_tiles<1>(b, inv_scale, acc, bad);
     // lanes -> wavefront (shuffle), wavefronts -> block (LDS), fixed order throughout
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -202,6 +225,7 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
     NormBatch b;
     b.n_sg = 0;
     b.tile_begin[0] = 0;
+    b.half = table_half_format(sg, n_sg);
     bool first = true;
     for (int i = 0; i < n_sg; ++i) {
         const uint64_t n = sg[i].n;

@@ -43,6 +43,7 @@ bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop);  // false: 
 // ---- per-step scalars of the update, derived on the host ---------------------
 struct AdamwConsts {
     float beta1, beta2, omb1, omb2, eps, step_size, sqbc2, decay;
+    int32_t half;  // format of g and p16: MLPO_HALF_BF16 or MLPO_HALF_FP16
 };
 int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step);
 // Pointer / size / tier checks shared by the entry points; grads_only checks g and n alone.  allow_host: 0 = only
@@ -50,7 +51,9 @@ int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step);
 int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, int allow_host);
 bool misaligned(const void* p, uintptr_t a);
 uint64_t round_up(uint64_t x, uint64_t to);
-AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step);
+AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step, int32_t half);
+// The half-precision format all subgroups of a table share (checked by validate_subgroups); bf16 for an empty table.
+int32_t table_half_format(const mlpo_subgroup* sg, int32_t n_sg);
 
 // ---- kernel-side view of a subgroup -------------------------------------------
 struct SgView {
@@ -94,8 +97,9 @@ int launch_norm_fold(NormWorkspace* ws, int n_partials, bool first, bool last, f
 // Enqueues acc = first ? g : bf16(acc + g) over n elements; blocks > 0 bounds the persistent grid.  With stats the
 // kernels also leave the statistics of the new acc values (unscaled by inv_scale) as partials in stats and
 // *n_partials says how many; the grid is then always persistent.
-int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, hipStream_t st,
-                           NormWorkspace* stats = nullptr, float inv_scale = 1.0f, int* n_partials = nullptr);
+int launch_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, bool first, int blocks, int32_t half,
+                           hipStream_t st, NormWorkspace* stats = nullptr, float inv_scale = 1.0f,
+                           int* n_partials = nullptr);
 
 inline bool host_tier(int32_t tier) { return tier == MLPO_TIER_HOST || tier == MLPO_TIER_HOST_GRADS; }
 

@@ -598,7 +598,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
         }
     }
 
-    const AdamwConsts c = make_consts(*hp, step);
+    const AdamwConsts c = make_consts(*hp, step, table_half_format(sg, n_sg));
     Plan plan;
     for (int32_t k = 0; k < n_sg; ++k) {
         const int32_t i = order ? order[k] : k;

@@ -100,7 +100,8 @@ class DeviceSubgroups:
     ``tiers[k] == 1`` puts p, m, v of subgroup k in pinned host memory.  ``tile`` > 0 stores the fp32 state of every
     subgroup in the tiled layout (one buffer per subgroup) instead of three planar arrays."""
 
-    def __init__(self, host_sgs, tiers=None, flat=True, elem_offset=0, tile=0):
+    def __init__(self, host_sgs, tiers=None, flat=True, elem_offset=0, tile=0, half=0):
+        self.half = half            # format of g and p16: B.HALF_BF16 or B.HALF_FP16
         self.n_sg = len(host_sgs)
         self.tiers = list(tiers) if tiers is not None else [0] * self.n_sg
         self.sizes = [s["p"].size for s in host_sgs]
@@ -140,7 +141,7 @@ class DeviceSubgroups:
             self.t.append(ent)
         torch.cuda.synchronize()
         self.table = B.SubgroupTable(
-            B.subgroup(e["p"], e["m"], e["v"], e["g"], e["p16"], n=self.sizes[k], tier=self.tiers[k])
+            B.subgroup(e["p"], e["m"], e["v"], e["g"], e["p16"], n=self.sizes[k], tier=self.tiers[k], half=self.half)
             for k, e in enumerate(self.t))
 
     def _init_tiled(self, host_sgs, d):
@@ -158,8 +159,9 @@ class DeviceSubgroups:
             ent = {"state": state, "g": torch.from_numpy(s["g"].view(np.int16)).to(d),
                    "p16": torch.from_numpy(s["p16"].view(np.int16)).to(d)}
             self.t.append(ent)
-            descs.append(B.tiled_subgroup(state, ent["g"], ent["p16"], n=n, tier=self.tiers[k], tile_elems=T)
-                         if n else B.subgroup(0, 0, 0, 0, 0, n=0, tier=self.tiers[k], tile_elems=T))
+            descs.append(B.tiled_subgroup(state, ent["g"], ent["p16"], n=n, tier=self.tiers[k], tile_elems=T,
+                                          half=self.half)
+                         if n else B.subgroup(0, 0, 0, 0, 0, n=0, tier=self.tiers[k], tile_elems=T, half=self.half))
         torch.cuda.synchronize()
         self.table = B.SubgroupTable(descs)
 

@@ -35,7 +35,8 @@ def test_version_and_workspace_size():
 def sg(n=8, tier=0, **kw):
     d = dict(p=FAKE, m=FAKE + 4096, v=FAKE + 8192, g=FAKE + 12288, p16=FAKE + 16384)
     d.update(kw)
-    return B.SubgroupC(d["p"], d["m"], d["v"], d["g"], d["p16"], n, tier, 0)
+    return B.SubgroupC(d["p"], d["m"], d["v"], d["g"], d["p16"], n, tier, d.get("tile_elems", 0),
+                       d.get("half_format", 0), d.get("reserved", 0))
 
 
 def expect(code, fn, *a, **k):
@@ -284,3 +285,13 @@ def test_file_tier_argument_errors(tmp_path):
         expect(B.MLPO_EINVAL, B.mlpo_stream_update, [filesg], None, hp, 1, None, cfg(file_threads=17))
     finally:
         os.close(fd)
+
+
+def test_half_format_errors():
+    hp = B.HParams()
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(half_format=2)], hp, 1)
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(), sg(half_format=B.HALF_FP16)], hp, 1)     # mixed formats
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(reserved=1)], hp, 1)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg(half_format=-1)], 1.0, 0.0, FAKE, B.mlpo_norm_workspace_bytes(),
+           FAKE)
+    expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, FAKE + 4096, 16, half=2)
