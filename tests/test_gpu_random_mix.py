@@ -21,7 +21,7 @@ from gpu_util import Scratch, assert_state_parity, dev, hp_pair, pack_tiled, unp
 SIZES = [0, 1, 3, 4, 5, 63, 64, 1023, 1024, 1025, 2047, 4096, 8191, 8192, 12_289, 30_001, 50_000, 65_537]
 
 
-def build(rng, host, tiers, tiles, path):
+def build(rng, host, tiers, tiles, path, half):
     """Device / pinned / file homes for every subgroup; returns (table, files, keep, fetch)."""
     d = dev()
     descs, files, keep = [], [], []
@@ -39,13 +39,13 @@ def build(rng, host, tiers, tiles, path):
         p16 = torch.from_numpy(s["p16"].view(np.int16)).to(d) if n else torch.empty(0, dtype=torch.int16, device=d)
         ent = {"g": g, "p16": p16, "tier": tier, "T": T, "n": n}
         if n == 0:
-            descs.append(B.SubgroupC(None, None, None, None, None, 0, tier, T))
+            descs.append(B.SubgroupC(None, None, None, None, None, 0, tier, T, half, 0))
             files.append(None)
         elif tier == B.TIER_FILE:
             packed = pack_tiled(s["p"], s["m"], s["v"], T)
             os.pwrite(fd, packed.tobytes(), off)
             ent["off"] = off
-            descs.append(B.SubgroupC(None, None, None, g.data_ptr(), p16.data_ptr(), n, tier, T))
+            descs.append(B.SubgroupC(None, None, None, g.data_ptr(), p16.data_ptr(), n, tier, T, half, 0))
             files.append((fd, off))
             off += (packed.nbytes + 4095) // 4096 * 4096
         else:
@@ -58,7 +58,7 @@ def build(rng, host, tiers, tiles, path):
                 else:
                     st = packed.to(d)
                 ent["state"] = st
-                descs.append(B.tiled_subgroup(st, g, p16, n=n, tier=tier, tile_elems=T))
+                descs.append(B.tiled_subgroup(st, g, p16, n=n, tier=tier, tile_elems=T, half=half))
             else:
                 arrs = []
                 for key in ("p", "m", "v"):
@@ -70,7 +70,7 @@ def build(rng, host, tiers, tiles, path):
                         t = src.to(d)
                     arrs.append(t)
                 ent["pmv"] = arrs
-                descs.append(B.subgroup(arrs[0], arrs[1], arrs[2], g, p16, n=n, tier=tier))
+                descs.append(B.subgroup(arrs[0], arrs[1], arrs[2], g, p16, n=n, tier=tier, half=half))
             files.append(None)
         keep.append(ent)
     os.ftruncate(fd, max(off, 4096))
@@ -117,6 +117,8 @@ def test_random_scenario(oracle, tmp_path, seed):
                  bias_correction=bool(rng.integers(0, 2)))
     ohp, ghp = hp_pair(oracle, **hp_kw)
     inv_scale = float(rng.choice([1.0, 1 / 64.0]))
+    half = int(rng.integers(0, 2))       # the generator's bit patterns read as bf16 or as fp16: finite either way
+    half_name = ["bf16", "fp16"][half]
     max_norm = float(rng.choice([0.0, 0.01]))
     # host copies of the state, generated by the seeded generator subgroup by subgroup
     host = []
@@ -125,9 +127,9 @@ def test_random_scenario(oracle, tmp_path, seed):
         s = W.host_subgroups(wl, warm=True)[0]
         host.append({key: a[:n].copy() for key, a in s.items()})
     label = (f"seed {seed}: {'direct' if direct else 'staged'} sizes {sizes} tiers {tiers} tiles {tiles} chunk {chunk} "
-             f"slots {n_slots} cached {cached}")
+             f"slots {n_slots} cached {cached} {half_name}")
     print(label, flush=True)
-    table, files, keep, fetch, fd = build(rng, host, tiers, tiles, str(tmp_path / "state.bin"))
+    table, files, keep, fetch, fd = build(rng, host, tiers, tiles, str(tmp_path / "state.bin"), half)
     scratch = Scratch()
     streams = (torch.cuda.Stream(), torch.cuda.Stream())
     cache = B.SlotCacheC() if cached else None
@@ -155,10 +157,11 @@ def test_random_scenario(oracle, tmp_path, seed):
                 wl = W.Workload("rnd", n_sub=1, sub_elems=n, loss_scale=1.0 / inv_scale, seed=seed * 100 + k)
                 W.fill_grads(wl, 0, step, s["g"])
                 if step == 1 and seed % 4 == 0 and k == n_sub - 1:
-                    s["g"][n // 2] = 0x7F80
+                    s["g"][n // 2] = 0x7C00 if half else 0x7F80
                 keep[k]["g"].copy_(torch.from_numpy(s["g"].view(np.int16)))
             torch.cuda.synchronize()
-            ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, applied, inv_scale, max_norm, order=order)
+            ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, applied, inv_scale, max_norm, order=order,
+                                                       half=half_name)
             B.mlpo_grad_unscale_norm(table, inv_scale, max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
                                      streams[1])
             ok_g = B.mlpo_stream_update(table, order, ghp, applied + 1, scratch.scalars, cfg)
