@@ -68,10 +68,11 @@ def resident_setup(args, torch, B, W, np, wl, tile):
             sk = state[k * per:(k + 1) * per]
             pad[:M].copy_(torch.from_numpy(hp_))
             sk.view(-1, 3, tile)[:, 0, :].copy_(pad.view(-1, tile))      # p into its slots of the tiled buffer
-            sgs.append(B.tiled_subgroup(sk, gk, hk, n=M, tile_elems=tile))
+            sgs.append(B.tiled_subgroup(sk, gk, hk, n=M, tile_elems=tile, half=args.half_format))
         else:
             flat["p"][k * M:(k + 1) * M].copy_(torch.from_numpy(hp_))
-            sgs.append(B.subgroup(*(flat[key][k * M:(k + 1) * M] for key in ("p", "m", "v")), gk, hk, n=M))
+            sgs.append(B.subgroup(*(flat[key][k * M:(k + 1) * M] for key in ("p", "m", "v")), gk, hk, n=M,
+                                  half=args.half_format))
     return {"table": B.SubgroupTable(sgs), "g_flat": g_flat, "p16_flat": p16_flat,
             "params": state if tile else flat["p"], "keep": (state, pad) if tile else flat}
 
@@ -185,7 +186,7 @@ def resident_result(args, wl, primary, others):
         "config": {"workload": wl.name, "params": wl.n_total, "subgroups": wl.n_sub, "subgroup_elems": wl.sub_elems,
                    "loss_scale": wl.loss_scale, "inf_every": wl.inject_every,
                    "applied_steps": primary["applied_steps"], "state_layout": primary["layout"],
-                   "state": "fp32 p/m/v + bf16 grads + bf16 params, all in HBM"},
+                   "state": f"fp32 p/m/v + {args.half} grads + {args.half} params, all in HBM"},
         "roofline": primary["roofline"],
         "norm_pass": primary["norm_pass"],
         "step_hbm_frac": primary["step_hbm_frac"],
@@ -672,6 +673,9 @@ def main():
     ap.add_argument("--layout", default="both", choices=["tiled", "planar", "both"],
                     help="fp32 state layout(s) to time; the first is the headline figure")
     ap.add_argument("--tile", type=int, default=8192, help="tile_elems of the tiled layout")
+    ap.add_argument("--half", default="bf16", choices=["bf16", "fp16"],
+                    help="format of gradients and working parameters in the resident run (the workloads are bf16; "
+                         "fp16 reads the same generated bit patterns as fp16 values, for timing)")
     ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
     ap.add_argument("--stream-variants", default="2:16777216,3:0,3:16777216,4:16777216,d:64,d:128,dg:64,dga:64,sg:16777216,c:4,c:8",
                     help="comma list of n_slots:chunk_elems (staged mode), d:blocks (direct mode), dg:blocks (direct "
@@ -701,6 +705,7 @@ def main():
                     help="also run 1 GiB copy kernels (reference traffic for profiler byte counters)")
     args = ap.parse_args()
     args.stream_variants = parse_variants(args.stream_variants)
+    args.half_format = {"bf16": 0, "fp16": 1}[args.half]
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
