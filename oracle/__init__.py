@@ -30,11 +30,11 @@ def build(force: bool = False) -> str:
 
 class _HParams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("weight_decay", C.c_float), ("bias_correction", C.c_int32)]
+                ("weight_decay", C.c_float), ("bias_correction", C.c_int32), ("l2_mode", C.c_int32)]
 
 
 class _Consts(C.Structure):
-    _fields_ = [(k, C.c_float) for k in ("beta1", "beta2", "omb1", "omb2", "eps", "step_size", "sqbc2", "decay")]
+    _fields_ = [(k, C.c_float) for k in ("beta1", "beta2", "omb1", "omb2", "eps", "step_size", "sqbc2", "decay", "l2")]
 
 
 class _Subgroup(C.Structure):
@@ -50,9 +50,11 @@ class HParams:
     eps: float = 1e-8
     weight_decay: float = 0.01
     bias_correction: bool = True
+    l2_mode: bool = False
 
     def _c(self) -> _HParams:
-        return _HParams(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.bias_correction))
+        return _HParams(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.bias_correction),
+                        int(self.l2_mode))
 
 
 _lib = None

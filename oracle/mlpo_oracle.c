@@ -18,7 +18,8 @@
  *     Ordering"); the paper prints no equations, so the arithmetic below is
  *     the textbook AdamW (decoupled weight decay, bias correction, eps added
  *     to the bias-corrected root), every operation rounded to fp32 once, in
- *     the order written, without fused multiply-add;
+ *     the order written, without fused multiply-add; the textbook Adam with
+ *     the decay term added to the gradient is the other mode (l2_mode);
  *   - loss-scale removal, the non-finite check, the global L2 norm and the
  *     clip coefficient are not in the paper; they follow the usual
  *     mixed-precision convention (norm of the unscaled gradients, one flag
@@ -36,11 +37,14 @@
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;
     int32_t bias_correction;
+    int32_t l2_mode; /* 0: decoupled weight decay (AdamW); 1: Adam with the decay
+                        term weight_decay * p added to the gradient */
 } orc_hparams;
 
 /* Scalars derived once per step (host side, fp64, each rounded once to fp32). */
 typedef struct {
     float beta1, beta2, omb1, omb2, eps, step_size, sqbc2, decay;
+    float l2; /* weight decay added to the gradient (l2_mode), else 0 */
 } orc_consts;
 
 /* ---- half-precision conversions (Section 2 "Mixed Precision Training") ---- */
@@ -252,6 +256,11 @@ void orc_adamw_consts(const orc_hparams* hp, int64_t step, orc_consts* c) {
     c->step_size = (float)((double)hp->lr / bc1);
     c->sqbc2 = (float)sqrt(bc2);
     c->decay = (float)(1.0 - (double)hp->lr * (double)hp->weight_decay);
+    c->l2 = 0.0f;
+    if (hp->l2_mode) { /* the decay acts through the gradient only */
+        c->decay = 1.0f;
+        c->l2 = hp->weight_decay;
+    }
 }
 
 /* One applied step (step is the 1-based count of applied steps) on one
@@ -263,6 +272,10 @@ void orc_adamw_f32_h(float* p, float* m, float* v, const uint16_t* g,
     orc_adamw_consts(hp, step, &c);
     for (uint64_t i = 0; i < n; ++i) {
         float gi = orc_half_to_f32(g[i], half) * gmul;
+        if (hp->l2_mode) {
+            float t0 = c.l2 * p[i];
+            gi = gi + t0;
+        }
         float t1 = c.beta1 * m[i];
         float t2 = c.omb1 * gi;
         float mi = t1 + t2;
@@ -305,11 +318,13 @@ void orc_adamw_f64_h(double* p, double* m, double* v, const uint16_t* g,
     }
     for (uint64_t i = 0; i < n; ++i) {
         double gi = (double)orc_half_to_f32(g[i], half) * gmul;
+        if (hp->l2_mode) gi += wd * p[i];
         m[i] = b1 * m[i] + (1.0 - b1) * gi;
         v[i] = b2 * v[i] + (1.0 - b2) * gi * gi;
         double mhat = m[i] / bc1;
         double vhat = v[i] / bc2;
-        p[i] = p[i] * (1.0 - lr * wd) - lr * mhat / (sqrt(vhat) + eps);
+        double keep = hp->l2_mode ? 1.0 : 1.0 - lr * wd;
+        p[i] = p[i] * keep - lr * mhat / (sqrt(vhat) + eps);
     }
 }
 

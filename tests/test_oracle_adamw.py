@@ -223,3 +223,74 @@ def test_chunked_driver_is_bitwise_the_plain_routine(oracle):
     oracle.adamw_f32(p, m, v, g, p16, oracle.HParams(), 2)
     oracle.adamw_f32(p2, m2, v2, g, p162, oracle.HParams(), 2, chunked=True)
     assert np.array_equal(p, p2) and np.array_equal(m, m2) and np.array_equal(v, v2) and np.array_equal(p16, p162)
+
+
+# ---- the other textbook form: Adam with the decay term added to the gradient (l2_mode) -------------------------------
+
+def test_l2_mode_step1_closed_form_and_what_tells_it_from_adamw(oracle):
+    # from m = v = 0 the first step moves p by -lr * g' / (|g'| + eps) with g' = g + wd * p
+    rng = np.random.default_rng(21)
+    n = 2048
+    wd = 0.1
+    hp = oracle.HParams(lr=1e-3, weight_decay=wd, l2_mode=True)
+    g = bf16_bits(rng.standard_normal(n) * 1e-3)
+    g[:4] = 0                                                   # no gradient at all: only the decay term acts
+    p, m, v, p16 = fresh(n, rng)
+    p0 = p.astype(np.float64)
+    gd = bf16_val(g).astype(np.float64) + float(np.float32(wd)) * p0
+    oracle.adamw_f32(p, m, v, g, p16, hp, 1)
+    want = p0 - float(np.float32(1e-3)) * gd / (np.abs(gd) + float(np.float32(1e-8)))
+    ulp = np.spacing(np.maximum(np.abs(p0), np.abs(p)).astype(np.float32)).astype(np.float64)
+    assert np.all(np.abs(p - want) <= ulp + 2e-6 * np.abs(want - p0))
+    # with g = 0 Adam-with-L2 takes a full step of lr towards zero; AdamW only shrinks p by lr * wd * p
+    assert np.allclose((p - p0)[:4], -1e-3 * np.sign(p0[:4]), rtol=1e-3)
+    q, m2, v2, q16 = p0.astype(np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint16)
+    oracle.adamw_f32(q, m2, v2, g, q16, oracle.HParams(lr=1e-3, weight_decay=wd), 1)
+    assert np.allclose((q - p0)[:4], -1e-3 * wd * p0[:4], rtol=1e-3, atol=0)
+    assert not m2[:4].any() and m[:4].all()                     # the decay enters the moments only in l2_mode
+
+
+def test_l2_mode_without_decay_is_adamw_bitwise(oracle):
+    rng = np.random.default_rng(22)
+    n = 5000
+    outs = []
+    for l2 in (False, True):
+        r = np.random.default_rng(23)
+        p, m, v, p16 = fresh(n, r)
+        hp = oracle.HParams(weight_decay=0.0, l2_mode=l2)
+        for t in range(1, 5):
+            g = bf16_bits(np.random.default_rng(100 + t).standard_normal(n) * 1e-3)
+            oracle.adamw_f32(p, m, v, g, p16, hp, t)
+        outs.append((p, m, v, p16))
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    assert rng is not None
+
+
+@pytest.mark.parametrize("hp_kw", [dict(weight_decay=0.01), dict(lr=3e-3, beta1=0.8, beta2=0.95, eps=1e-6,
+                                                               weight_decay=0.1)])
+def test_l2_mode_against_torch_adam(oracle, hp_kw):
+    """PyTorch's Adam with weight_decay (the decay term added to the gradient) in fp64 against the fp64 brute force
+    (tight) and in fp32 against the fp32 routine (operation order differs: tolerance, not bits)."""
+    torch = pytest.importorskip("torch")
+    hp = oracle.HParams(l2_mode=True, **hp_kw)
+    n, steps = 256, 8
+    for dtype, tol in ((torch.float64, 1e-12), (torch.float32, 3e-6)):
+        rng = np.random.default_rng(12)
+        p, m, v, p16 = fresh(n, rng)
+        pd, md, vd = p.astype(np.float64), m.astype(np.float64), v.astype(np.float64)
+        tp = torch.tensor(p, dtype=dtype, requires_grad=True)
+        opt = torch.optim.Adam([tp], lr=float(np.float32(hp.lr)), betas=(float(np.float32(hp.beta1)),
+                               float(np.float32(hp.beta2))), eps=float(np.float32(hp.eps)),
+                               weight_decay=float(np.float32(hp.weight_decay)), foreach=False, fused=False)
+        for t in range(1, steps + 1):
+            g = bf16_bits(rng.standard_normal(n) * 1e-3)
+            tp.grad = torch.tensor(bf16_val(g), dtype=dtype)
+            opt.step()
+            oracle.adamw_f32(p, m, v, g, p16, hp, t)
+            oracle.adamw_f64(pd, md, vd, g, hp, t)
+        st = opt.state[tp]
+        ours = (pd, md, vd) if dtype == torch.float64 else (p, m, v)
+        assert np.allclose(ours[0], tp.detach().numpy(), rtol=tol, atol=tol * 1e-3)
+        assert np.allclose(ours[1], st["exp_avg"].numpy(), rtol=max(tol, 1e-12), atol=tol * 1e-3)
+        assert np.allclose(ours[2], st["exp_avg_sq"].numpy(), rtol=tol, atol=1e-30)
