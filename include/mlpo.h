@@ -43,10 +43,14 @@ extern "C" {
 #define MLPO_ENOMEM (-3) /* a caller-provided workspace or staging buffer is too small */
 #define MLPO_EIO (-4)    /* reading or writing a file-tier subgroup failed; mlpo_last_error() gives errno's text */
 
-/* AdamW hyper-parameters, fp32 as stored.  bias_correction != 0 applies the 1 - beta^t corrections. */
+/* Hyper-parameters, fp32 as stored.  bias_correction != 0 applies the 1 - beta^t corrections.  l2_mode 0 is AdamW
+ * (decoupled weight decay: p shrinks by the factor 1 - lr * weight_decay); l2_mode 1 is Adam with the decay term
+ * weight_decay * p added to the gradient before the moments are updated (the paper names Adam without saying which
+ * form, Section 3.2 "Cache-Friendly Ordering"; every workload here uses AdamW). */
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;
     int32_t bias_correction;
+    int32_t l2_mode;
 } mlpo_adamw_hparams;
 
 /* One subgroup (Section 2 "Sharded Model and Optimizer States Into Subgroups"): n elements of fp32 master parameters
@@ -205,7 +209,7 @@ int mlpo_grad_norm_finish(void* workspace, size_t workspace_bytes, float inv_sca
  *   omb1 = 1 - beta1, omb2 = 1 - beta2, bc1 = 1 - beta1^step, bc2 = 1 - beta2^step (both 1 without bias correction),
  *   step_size = lr / bc1, sqbc2 = sqrt(bc2), decay = 1 - lr * weight_decay
  * every element does, each operation rounded to fp32 once and none fused:
- *   g  = f32(g_bf16) * gmul
+ *   g  = f32(g_bf16) * gmul              (l2_mode: then g = g + weight_decay * p, and decay = 1)
  *   m' = beta1 * m + omb1 * g
  *   v' = beta2 * v + omb2 * (g * g)
  *   p' = p * decay - step_size * (m' / (sqrt(v') / sqbc2 + eps))

@@ -39,7 +39,7 @@ class MlpoError(RuntimeError):
 
 class HParamsC(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("weight_decay", C.c_float), ("bias_correction", C.c_int32)]
+                ("weight_decay", C.c_float), ("bias_correction", C.c_int32), ("l2_mode", C.c_int32)]
 
 
 class SubgroupC(C.Structure):
@@ -85,9 +85,11 @@ class HParams:
     eps: float = 1e-8
     weight_decay: float = 0.01
     bias_correction: bool = True
+    l2_mode: bool = False
 
     def c(self) -> HParamsC:
-        return HParamsC(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.bias_correction))
+        return HParamsC(self.lr, self.beta1, self.beta2, self.eps, self.weight_decay, int(self.bias_correction),
+                        int(self.l2_mode))
 
 
 _lib = None

@@ -115,7 +115,8 @@ __device__ __forceinline__ float widen_high(uint32_t x) {
 template <int HALF>
 __device__ __forceinline__ uint32_t update_one(float& p, float& m, float& v, float graw, float gmul,
                                                const AdamwConsts& c) {
-    const float g = graw * gmul;
+    float g = graw * gmul;
+    if (c.l2_mode != 0) g = g + (c.l2 * p);
     const float mn = (c.beta1 * m) + (c.omb1 * g);
     const float vn = (c.beta2 * v) + (c.omb2 * (g * g));
     const float d = (sqrtf(vn) / c.sqbc2) + c.eps;

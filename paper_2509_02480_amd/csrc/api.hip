@@ -106,6 +106,7 @@ int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step) {
     if (!(isfinite(hp->eps) && hp->eps >= 0.0f)) return fail(MLPO_EINVAL, "eps must be finite and >= 0");
     if (!(isfinite(hp->weight_decay) && hp->weight_decay >= 0.0f))
         return fail(MLPO_EINVAL, "weight_decay must be finite and >= 0");
+    if (hp->l2_mode != 0 && hp->l2_mode != 1) return fail(MLPO_EINVAL, "l2_mode must be 0 or 1 (got %d)", hp->l2_mode);
     return MLPO_OK;
 }
 
@@ -126,6 +127,12 @@ AdamwConsts make_consts(const mlpo_adamw_hparams& hp, int64_t step, int32_t half
     c.step_size = (float)((double)hp.lr / corr1);
     c.sqbc2 = (float)sqrt(corr2);
     c.decay = (float)(1.0 - (double)hp.lr * (double)hp.weight_decay);
+    c.l2 = 0.0f;
+    c.l2_mode = hp.l2_mode;
+    if (hp.l2_mode != 0) {  // the decay acts through the gradient only
+        c.decay = 1.0f;
+        c.l2 = hp.weight_decay;
+    }
     c.half = half;
     return c;
 }

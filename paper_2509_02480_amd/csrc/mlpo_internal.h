@@ -43,7 +43,9 @@ bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop);  // false: 
 // ---- per-step scalars of the update, derived on the host ---------------------
 struct AdamwConsts {
     float beta1, beta2, omb1, omb2, eps, step_size, sqbc2, decay;
-    int32_t half;  // format of g and p16: MLPO_HALF_BF16 or MLPO_HALF_FP16
+    float l2;         // l2_mode: weight decay added to the gradient (decay is then 1)
+    int32_t l2_mode;  // 0: AdamW, 1: Adam with the decay term in the gradient
+    int32_t half;     // format of g and p16: MLPO_HALF_BF16 or MLPO_HALF_FP16
 };
 int validate_hparams(const mlpo_adamw_hparams* hp, int64_t step);
 // Pointer / size / tier checks shared by the entry points; grads_only checks g and n alone.  allow_host: 0 = only

@@ -98,6 +98,7 @@ class AdamW:
     eps: float = 1e-8
     weight_decay: float = 0.01
     bias_correction: bool = True
+    l2_mode: bool = False
 
 
 @dataclass(frozen=True)

@@ -289,6 +289,9 @@ def test_file_tier_argument_errors(tmp_path):
 
 def test_half_format_errors():
     hp = B.HParams()
+    bad = hp.c()
+    bad.l2_mode = 2
+    assert B.lib().mlpo_adamw_step(None, 0, C.byref(bad), 1, None, None) == B.MLPO_EINVAL
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(half_format=2)], hp, 1)
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(), sg(half_format=B.HALF_FP16)], hp, 1)     # mixed formats
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(reserved=1)], hp, 1)

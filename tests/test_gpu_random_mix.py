@@ -114,7 +114,7 @@ def test_random_scenario(oracle, tmp_path, seed):
     cached = (not direct) and chunk == 0 and bool(rng.integers(0, 2))
     n_slots = int(rng.integers(1, 6))
     hp_kw = dict(lr=float(rng.choice([1e-4, 3e-3])), weight_decay=float(rng.choice([0.0, 0.01])),
-                 bias_correction=bool(rng.integers(0, 2)))
+                 bias_correction=bool(rng.integers(0, 2)), l2_mode=bool(rng.integers(0, 2)))
     ohp, ghp = hp_pair(oracle, **hp_kw)
     inv_scale = float(rng.choice([1.0, 1 / 64.0]))
     half = int(rng.integers(0, 2))       # the generator's bit patterns read as bf16 or as fp16: finite either way

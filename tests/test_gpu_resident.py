@@ -134,7 +134,9 @@ def test_without_scalars_is_unit_gmul_and_never_skips(oracle, scratch):
 
 @pytest.mark.parametrize("hp_kw", [dict(weight_decay=0.0), dict(bias_correction=False),
                                    dict(lr=3e-3, beta1=0.8, beta2=0.95, eps=1e-6, weight_decay=0.1),
-                                   dict(lr=0.0), dict(beta1=0.0, beta2=0.0)])
+                                   dict(lr=0.0), dict(beta1=0.0, beta2=0.0),
+                                   dict(l2_mode=True), dict(l2_mode=True, lr=3e-3, weight_decay=0.1, eps=1e-6),
+                                   dict(l2_mode=True, weight_decay=0.0, bias_correction=False)])
 def test_hyperparameter_variants(oracle, scratch, hp_kw):
     wl = W.Workload("hp", n_sub=3, sub_elems=50_001, hp=W.AdamW(**hp_kw), steps=4, loss_scale=64.0, max_norm=0.5)
     run_workload(oracle, scratch, wl, warm=True, check_every_step=True)
