@@ -23,12 +23,10 @@ MAX_SLOTS = 64
 TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_state_pack", "mlpo_state_unpack",
-           "mlpo_norm_workspace_bytes",
-           "mlpo_grad_unscale_norm", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm", "mlpo_grad_norm_finish",
-           "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_bounce_bytes", "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers",
-           "mlpo_update_bandwidth", "mlpo_set_option",
-           "mlpo_kernel_times",
-           "mlpo_shutdown")
+           "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm",
+           "mlpo_grad_norm_finish", "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_bounce_bytes",
+           "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers", "mlpo_update_bandwidth", "mlpo_set_option",
+           "mlpo_kernel_times", "mlpo_shutdown")
 
 
 class MlpoError(RuntimeError):
