@@ -326,8 +326,8 @@ size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t f
  * and p16 are read/written at their device homes; the gradients of a MLPO_TIER_HOST_GRADS subgroup travel into the
  * slot with the state, and with a slot cache they are fetched anew every step), and copied back on the d2h stream;
  * a slot is reused only after its copy back has completed, so at most n_slots transfers are in flight.  In direct
- * mode the kernel works on the host state in place.  Results are bit-identical to the resident path whatever mode, n_slots, chunk_elems, direct_blocks
- * and order are.
+ * mode the kernel works on the host state in place.  Results are bit-identical to the resident path whatever mode,
+ * n_slots, chunk_elems, direct_blocks and order are.
  *
  * File-tier subgroups (direct mode): reading threads bring pieces of at most chunk_elems elements (0 = whole
  * subgroups) from the file into free bounce buffers, the update kernel works on a bounce buffer in place over the
