@@ -350,7 +350,7 @@ typedef struct {
  * step_applied is the number of steps applied so far; returns 1 when this
  * step was applied (the caller then counts it), 0 when skipped.  order, if
  * not NULL, is the sequence in which subgroups are visited (Algorithm 1's
- * update_order); results do not depend on it. */
+ * processing order); results do not depend on it. */
 int orc_step_h(const orc_subgroup* sg, int32_t n_sg, const int32_t* order,
                const orc_hparams* hp, int64_t steps_applied, float inv_scale,
                float max_norm, int32_t half, float* out_norm,
