@@ -27,15 +27,20 @@ BYTES_PER_PARAM_NORM = 2     # read g
 
 
 def recorded_traffic(layout):
-    """HBM bytes per launch of the update kernel as counted by the profiler (profiles/hbm_traffic.json), or None if
-    the kernel source has changed since the counters were taken."""
+    """HBM bytes per launch of the update kernel as counted by the profiler (the "recorded:" lines of
+    profiles/adamw_update_C2-125M_hbm_traffic.md), or None if the kernel source has changed since the counters were
+    taken."""
     import hashlib
     try:
-        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
+        rec = {}
+        for ln in open(os.path.join(ROOT, "profiles", "adamw_update_C2-125M_hbm_traffic.md")):
+            if ln.strip().startswith("recorded:"):
+                key, _, val = ln.strip()[len("recorded:"):].rpartition("=")
+                rec[key.strip()] = val.strip()
         src = open(os.path.join(ROOT, "paper_2509_02480_amd", "csrc", "adamw.hip"), "rb").read()
         if hashlib.sha256(src).hexdigest() != rec["adamw_hip_sha256"]:
             return None
-        return rec["traffic_bytes_per_launch"].get(layout)
+        return int(rec[layout])
     except (OSError, KeyError, ValueError):
         return None
 
