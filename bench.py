@@ -535,7 +535,7 @@ def multipath_bench(args, torch, B, np, ctx, kind):
            "eq1_bandwidth_guess_GBs": [round(ctx["host_GBs"], 2), args.file_GBs_guess],
            "eq1_split_pinned_file": list(counts), "chunk_elems": args.multipath_chunk,
            "file_slots": args.file_slots, "file_threads": args.file_threads}
-    fd = -1
+    fd = plain_fd = -1
     try:
         with open(path, "wb") as f:
             for k in file_ids:
@@ -547,6 +547,8 @@ def multipath_bench(args, torch, B, np, ctx, kind):
         except OSError:         # a file system without direct I/O
             fd = os.open(path, os.O_RDWR)
             res["direct_io"] = False
+        plain_fd = os.open(path, os.O_RDWR)      # for growing the file (no alignment rules)
+        leg_t0 = time.perf_counter()
         sgs, files = [], []
         for k in range(wl.n_sub):
             gk, pk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
@@ -562,27 +564,35 @@ def multipath_bench(args, torch, B, np, ctx, kind):
         cfg = B.direct_cfg(ctx["streams"][0], cmp_, 64, chunk_elems=args.multipath_chunk, files=files, bounce=bounce,
                            bounce_bytes=need, file_slots=args.file_slots, file_threads=args.file_threads,
                            want_file_stats=True)
-        times, rd, wr, wall = [], [], [], []
         applied = ctx["applied"]
-        leg_start = time.perf_counter()
-        for s in range(args.stream_warmup + wl.steps):
-            if times and time.perf_counter() - leg_start > args.multipath_seconds:
-                break       # a slow disk must not stretch the run: one timed step is enough to report
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ctx["ws"], ctx["ws_bytes"], ctx["scal"], cmp_)
-            assert B.mlpo_stream_update(table, None, ctx["hp"], applied + 1, ctx["scal"], cfg)
-            cmp_.synchronize()
-            torch.cuda.synchronize()
-            dt = time.perf_counter() - t
-            applied += 1
-            if s >= args.stream_warmup:
-                times.append(dt)
-                st = cfg.stats
-                rd.append(st.bytes_read / st.read_seconds * max(args.file_threads, 1) if st.read_seconds else 0.0)
-                wr.append(st.bytes_written / st.write_seconds * max(args.file_threads, 1) if st.write_seconds else 0.0)
-                wall.append(st.wall_seconds)
-        ctx["applied"] = applied
+
+        def timed_steps(cfg, limit_s, count):
+            """Up to `count` timed steps after the warm-up ones; stops early once `limit_s` seconds have gone by."""
+            nonlocal applied
+            times, rd, wr, wall = [], [], [], []
+            leg_start = time.perf_counter()
+            for s in range(args.stream_warmup + count):
+                if times and time.perf_counter() - leg_start > limit_s:
+                    break       # a slow disk must not stretch the run: one timed step is enough to report
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ctx["ws"], ctx["ws_bytes"], ctx["scal"],
+                                         cmp_)
+                assert B.mlpo_stream_update(table, None, ctx["hp"], applied + 1, ctx["scal"], cfg)
+                cmp_.synchronize()
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t
+                applied += 1
+                if s >= args.stream_warmup:
+                    times.append(dt)
+                    st = cfg.stats
+                    rd.append(st.bytes_read / st.read_seconds * max(args.file_threads, 1) if st.read_seconds else 0.0)
+                    wr.append(st.bytes_written / st.write_seconds * max(args.file_threads, 1)
+                              if st.write_seconds else 0.0)
+                    wall.append(st.wall_seconds)
+            return times, rd, wr, wall
+
+        times, rd, wr, wall = timed_steps(cfg, args.multipath_seconds, wl.steps)
         mean = sum(times) / len(times)
         n_pinned = len(offloaded) - n_file
         file_wall = sum(wall) / len(wall)
@@ -603,10 +613,68 @@ def multipath_bench(args, torch, B, np, ctx, kind):
             res["eq1_bandwidth_observed_GBs"] = [round(x * state_bytes / 1e9, 2) for x in new_bw]
             res["eq1_split_after_update"] = list(B.mlpo_assign_tiers(len(offloaded), new_bw, cap)[0])
             res["eq1_split_after_update_without_capacity"] = list(B.mlpo_assign_tiers(len(offloaded), new_bw)[0])
+            # Algorithm 1 assigns the path anew when it flushes a subgroup: the subgroups that the new split puts on
+            # the other path move there as part of one ordinary update step (their new state is stored at the new
+            # home instead of the old one), and the steps after it run with the new split.
+            new_file = res["eq1_split_after_update"][1]
+            if new_file != n_file and time.perf_counter() - leg_t0 < 2 * args.multipath_seconds:
+                targets = [None] * wl.n_sub
+                if new_file > n_file:       # pinned -> file: the last pinned subgroups, to new extents at the end
+                    movers = offloaded[len(offloaded) - new_file:len(offloaded) - n_file]
+                    zeros = bytes(1 << 24)
+                    for j, k in enumerate(movers):
+                        off = (n_file + j) * state_bytes
+                        for o in range(0, state_bytes, len(zeros)):   # real pages, not a hole
+                            os.pwrite(plain_fd, zeros[:min(len(zeros), state_bytes - o)], off + o)
+                        targets[k] = (fd, off)
+                    os.fsync(plain_fd)
+                else:                       # file -> pinned: the first file-tier subgroups, to their pinned buffers
+                    movers = file_ids[:n_file - new_file]
+                    for k in movers:
+                        targets[k] = keep[k]
+                need2 = B.mlpo_stream_bounce_bytes(table, args.file_slots, args.multipath_chunk, flush_to=targets)
+                if need2 > need:
+                    bounce = torch.empty(need2, dtype=torch.uint8, pin_memory=True)
+                move_cfg = B.direct_cfg(ctx["streams"][0], cmp_, 64, chunk_elems=args.multipath_chunk, files=files,
+                                        bounce=bounce, bounce_bytes=bounce.numel(), file_slots=args.file_slots,
+                                        file_threads=args.file_threads, want_file_stats=True, flush_to=targets)
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ctx["ws"], ctx["ws_bytes"], ctx["scal"],
+                                         cmp_)
+                assert B.mlpo_stream_update(table, None, ctx["hp"], applied + 1, ctx["scal"], move_cfg)
+                cmp_.synchronize()
+                torch.cuda.synchronize()
+                move_ms = (time.perf_counter() - t) * 1e3
+                applied += 1
+                for k in movers:
+                    gk, pk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
+                    if new_file > n_file:
+                        sgs[k] = B.SubgroupC(None, None, None, gk.data_ptr(), pk.data_ptr(), M, B.TIER_FILE, T)
+                        files[k] = targets[k]
+                    else:
+                        sgs[k] = B.tiled_subgroup(keep[k], gk, pk, n=M, tier=wl.tier(k), tile_elems=T)
+                        files[k] = None
+                table = B.SubgroupTable(sgs)
+                cfg = B.direct_cfg(ctx["streams"][0], cmp_, 64, chunk_elems=args.multipath_chunk, files=files,
+                                   bounce=bounce, bounce_bytes=bounce.numel(), file_slots=args.file_slots,
+                                   file_threads=args.file_threads, want_file_stats=True)
+                t2, _, _, wall2 = timed_steps(cfg, args.multipath_seconds / 2, wl.steps)
+                mean2 = sum(t2) / len(t2)
+                res["after_rebalance"] = {
+                    "split_pinned_file": [len(offloaded) - new_file, new_file], "subgroups_moved": len(movers),
+                    "direction": "pinned->file" if new_file > n_file else "file->pinned",
+                    "move_step_ms": round(move_ms, 2), "steps": len(t2), "ms_per_step": round(mean2 * 1e3, 2),
+                    "min_ms": round(min(t2) * 1e3, 2),
+                    "file_path_GBs_per_dir": round(new_file * state_bytes / (sum(wall2) / len(wall2)) / 1e9, 2)
+                    if new_file and sum(wall2) > 0 else None,
+                    "link_GBs_per_dir": round(len(offloaded) * state_bytes / mean2 / 1e9, 2)}
+        ctx["applied"] = applied
     finally:
         torch.cuda.synchronize()
-        if fd >= 0:
-            os.close(fd)
+        for d in (fd, plain_fd):
+            if d >= 0:
+                os.close(d)
         if os.path.exists(path):
             os.unlink(path)
     log(f"[bench] multipath {res}")

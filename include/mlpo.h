@@ -261,6 +261,24 @@ typedef struct {
     uint64_t offset;
 } mlpo_file_extent;
 
+/* Where the fp32 state of an offloaded subgroup goes after the update when that is not where it was read from.
+ * Algorithm 1 assigns the path anew every time a subgroup is flushed, so that a re-estimated Eq. 1 (Section 3.3)
+ * takes effect; as the update reads the whole state and writes the whole state anyway, sending it to the other path
+ * costs nothing extra: pinned -> file has no read from the file, file -> pinned has no write to it.  Direct mode,
+ * tiled layout only; entries of HBM-tier and planar subgroups must say MLPO_FLUSH_IN_PLACE.  After an applied step
+ * the caller describes the subgroup by its new home (what the old one holds is then stale); a skipped step moves
+ * nothing and the state stays where it was.  The targets of different subgroups must not overlap each other or
+ * any other subgroup's state: the library checks a target only against its own subgroup's current state. */
+#define MLPO_FLUSH_IN_PLACE (-1)
+typedef struct {
+    int32_t tier;          /* MLPO_FLUSH_IN_PLACE, MLPO_TIER_HOST or MLPO_TIER_FILE */
+    int32_t reserved;      /* must be 0 */
+    float* state;          /* MLPO_TIER_HOST: pinned host buffer of mlpo_state_floats(n, tile_elems) floats, 256-byte
+                              aligned, not overlapping the subgroup's current state; the new p, m, v are stored there
+                              in the tiled layout */
+    mlpo_file_extent file; /* MLPO_TIER_FILE: where the state is written (may be the extent it came from) */
+} mlpo_flush_target;
+
 /* What the file path of one mlpo_stream_update call did: bytes read and written, the time its threads spent
  * inside pread / pwrite (summed over the threads of a direction) and the wall time from the first read to the end of
  * the last write.  Section 3.3: the observed bandwidth of a path, B_i = bytes / seconds, is what
@@ -310,13 +328,18 @@ typedef struct {
                               equal share of every piece; 0 = default (2); at most 16 */
     mlpo_file_stats* file_stats; /* host pointer or NULL: receives what the file path moved and how long it took
                                     (all zero after a skipped step or when nothing is file-tier) */
+    const mlpo_flush_target* flush_to; /* direct mode: host array with one entry per subgroup of the table, or NULL
+                                          (everything goes back to where it came from).  A target in a file needs
+                                          the bounce buffers even if no subgroup is file-tier yet */
 } mlpo_stream_cfg;
 
 /* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier). */
 size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems);
 
-/* Bounce bytes needed for the MLPO_TIER_FILE subgroups under this file_slots / chunk_elems (0 if there are none). */
-size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t file_slots, uint64_t chunk_elems);
+/* Bounce bytes needed for the subgroups that come from a file or (flush_to, may be NULL) go to one, under this
+ * file_slots / chunk_elems (0 if there are none). */
+size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t file_slots, uint64_t chunk_elems,
+                                const mlpo_flush_target* flush_to);
 
 /*
  * One update phase over subgroups of all tiers (Algorithm 1, with the fetch / update / flush overlap of Section 3.4

@@ -66,13 +66,20 @@ class FileStatsC(C.Structure):
                 ("write_seconds", C.c_double), ("wall_seconds", C.c_double)]
 
 
+class FlushTargetC(C.Structure):
+    _fields_ = [("tier", C.c_int32), ("reserved", C.c_int32), ("state", C.c_void_p), ("file", FileExtentC)]
+
+
+FLUSH_IN_PLACE = -1
+
+
 class StreamCfgC(C.Structure):
     _fields_ = [("n_slots", C.c_int32), ("mode", C.c_int32), ("chunk_elems", C.c_uint64),
                 ("staging", C.c_void_p), ("staging_bytes", C.c_size_t), ("h2d", C.c_void_p), ("compute", C.c_void_p),
                 ("d2h", C.c_void_p), ("direct_blocks", C.c_int32), ("reserved", C.c_int32),
                 ("cache", C.POINTER(SlotCacheC)), ("files", C.POINTER(FileExtentC)), ("bounce", C.c_void_p),
                 ("bounce_bytes", C.c_size_t), ("file_slots", C.c_int32), ("file_threads", C.c_int32),
-                ("file_stats", C.POINTER(FileStatsC))]
+                ("file_stats", C.POINTER(FileStatsC)), ("flush_to", C.POINTER(FlushTargetC))]
 
 
 @dataclass
@@ -137,7 +144,7 @@ def lib():
         L.mlpo_stream_staging_bytes.restype = C.c_size_t
         L.mlpo_stream_staging_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64]
         L.mlpo_stream_bounce_bytes.restype = C.c_size_t
-        L.mlpo_stream_bounce_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64]
+        L.mlpo_stream_bounce_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_void_p]
         L.mlpo_stream_update.restype = C.c_int
         L.mlpo_stream_update.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(HParamsC), C.c_int64,
                                          C.c_void_p, C.POINTER(StreamCfgC), C.POINTER(C.c_int32)]
@@ -258,21 +265,38 @@ def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chu
     """Staged mode: host-tier subgroups travel through ``n_slots`` device staging slots.  ``cache`` (a zero-initialised
     SlotCacheC kept by the caller) lets slots keep their subgroups between steps."""
     cfg = StreamCfgC(n_slots, STREAM_STAGED, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d),
-                     _stream(compute), _stream(d2h), 0, 0, None, None, None, 0, 0, 0, None)
+                     _stream(compute), _stream(d2h), 0, 0, None, None, None, 0, 0, 0, None, None)
     if cache is not None:
         cfg.cache = C.pointer(cache)
         cfg._keep = cache
     return cfg
 
 
+def flush_targets(targets) -> "C.Array":
+    """Array of mlpo_flush_target from a list with one entry per subgroup: None (stays where it is), a pinned-host
+    tensor / address (goes to pinned memory) or an (fd, offset) pair (goes to a file)."""
+    arr = (FlushTargetC * max(len(targets), 1))()
+    for i, t in enumerate(targets):
+        if t is None:
+            arr[i] = FlushTargetC(FLUSH_IN_PLACE, 0, None, FileExtentC(-1, 0, 0))
+        elif isinstance(t, tuple):
+            arr[i] = FlushTargetC(TIER_FILE, 0, None, FileExtentC(int(t[0]), 0, int(t[1])))
+        else:
+            arr[i] = FlushTargetC(TIER_HOST, 0, _ptr(t), FileExtentC(-1, 0, 0))
+    return arr
+
+
 def direct_cfg(host_stream, compute, direct_blocks: int = 0, chunk_elems: int = 0, files=None, bounce=None,
                bounce_bytes: int = 0, file_slots: int = 0, want_file_stats: bool = False,
-               file_threads: int = 0) -> StreamCfgC:
+               file_threads: int = 0, flush_to=None) -> StreamCfgC:
     """Direct mode: the kernel updates the pinned host state in place with ``direct_blocks`` persistent workgroups.
     ``files`` (one (fd, offset) pair or None per subgroup), ``bounce`` (pinned host tensor) and ``file_slots``
     configure the file path; ``cfg.stats`` then holds what it moved after each call if ``want_file_stats``."""
     cfg = StreamCfgC(0, STREAM_DIRECT, chunk_elems, None, 0, _stream(host_stream), _stream(compute), _stream(compute),
-                     direct_blocks, 0, None, None, _ptr(bounce), bounce_bytes, file_slots, file_threads, None)
+                     direct_blocks, 0, None, None, _ptr(bounce), bounce_bytes, file_slots, file_threads, None, None)
+    if flush_to is not None:
+        cfg._flush = flush_targets(flush_to)
+        cfg.flush_to = cfg._flush
     if files is not None:
         arr = (FileExtentC * max(len(files), 1))()
         for i, f in enumerate(files):
@@ -288,9 +312,10 @@ def direct_cfg(host_stream, compute, direct_blocks: int = 0, chunk_elems: int = 
     return cfg
 
 
-def mlpo_stream_bounce_bytes(sgs, file_slots: int, chunk_elems: int = 0) -> int:
+def mlpo_stream_bounce_bytes(sgs, file_slots: int, chunk_elems: int = 0, flush_to=None) -> int:
     t = _table(sgs)
-    return int(lib().mlpo_stream_bounce_bytes(t.array, t.n, file_slots, chunk_elems))
+    arr = flush_targets(flush_to) if flush_to is not None else None
+    return int(lib().mlpo_stream_bounce_bytes(t.array, t.n, file_slots, chunk_elems, arr))
 
 
 def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: int, scalars, cfg: StreamCfgC) -> bool:

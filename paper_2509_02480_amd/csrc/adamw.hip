@@ -51,6 +51,14 @@ struct VecBatch {
     uint32_t tile_begin[kMaxSg + 1];  // prefix sums of tiles per subgroup
     int32_t n_sg;
 };
+// Extra argument of the out-of-place kernels: where each subgroup's new p, m, v go, in groups of four behind where
+// the old ones were read.  The in-place kernels take the empty form.
+template <bool MOVE>
+struct StoreShift {};
+template <>
+struct StoreShift<true> {
+    int64_t out4[kMaxSg];
+};
 
 // Element-wise view for whatever the 128-bit kernel cannot take (unaligned subgroups, tails of 1-3 elements).
 constexpr int kBlock1 = 256;
@@ -152,11 +160,12 @@ struct Tile {
     f32x4* v;
     const u32x2* g;
     u32x2* h;
+    int64_t out4;  // MOVE only: store offset of p, m, v relative to their load addresses, in groups of four
     uint32_t cnt;  // groups of four in this tile
 };
 
-template <int T4>
-__device__ __forceinline__ Tile locate(const VecBatch& b, uint32_t tile, int& s) {
+template <int T4, bool MOVE>
+__device__ __forceinline__ Tile locate(const VecBatch& b, const StoreShift<MOVE>& shift, uint32_t tile, int& s) {
     while (tile >= b.tile_begin[s + 1]) ++s;
     const VecView& d = b.sg[s];
     const uint32_t t_in = tile - b.tile_begin[s];
@@ -182,11 +191,14 @@ __device__ __forceinline__ Tile locate(const VecBatch& b, uint32_t tile, int& s)
     t.v = d.v + off;
     t.g = d.g + q0;
     t.h = d.h + q0;
+    t.out4 = 0;
+    if constexpr (MOVE) t.out4 = shift.out4[s];
     t.cnt = left < (uint64_t)T4 ? (uint32_t)left : (uint32_t)T4;
     return t;
 }
 
-template <int BLOCK, int UNROLL, bool NT>
+// MOVE = false stores p, m, v where they were loaded from; MOVE = true stores them Tile::out4 groups further on.
+template <int BLOCK, int UNROLL, bool NT, bool MOVE>
 struct Regs {
     f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
     u32x2 G[UNROLL];
@@ -224,14 +236,15 @@ struct Regs {
 
     template <int HALF>
     __device__ __forceinline__ void update_store_as(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
+        const auto out = [&t](f32x4* q) { return MOVE ? q + t.out4 : q; };
         if (t.cnt == BLOCK * UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
                 const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
-                st<NT>(t.p + i, P[u]);
-                st<NT>(t.m + i, M[u]);
-                st<NT>(t.v + i, V[u]);
+                st<NT>(out(t.p) + i, P[u]);
+                st<NT>(out(t.m) + i, M[u]);
+                st<NT>(out(t.v) + i, V[u]);
                 st<NT>(t.h + i, H);
             }
         } else {
@@ -240,9 +253,9 @@ struct Regs {
                 const uint32_t i = u * BLOCK + tid;
                 if (i < t.cnt) {
                     const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
-                    st<NT>(t.p + i, P[u]);
-                    st<NT>(t.m + i, M[u]);
-                    st<NT>(t.v + i, V[u]);
+                    st<NT>(out(t.p) + i, P[u]);
+                    st<NT>(out(t.m) + i, M[u]);
+                    st<NT>(out(t.v) + i, V[u]);
                     st<NT>(t.h + i, H);
                 }
             }
@@ -253,9 +266,10 @@ struct Regs {
 // 128-bit kernel: p, m, v 16-byte aligned, g, p16 8-byte aligned, element counts multiples of four.
 // PERSIST = false: one tile per block.  PERSIST = true: grid-stride over tiles, next tile's loads in flight while the
 // current tile is computed and stored.
-template <int BLOCK, int UNROLL, bool NT, bool PERSIST>
+template <int BLOCK, int UNROLL, bool NT, bool PERSIST, bool MOVE>
 __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const AdamwConsts c,
-                                                         const mlpo_step_scalars* __restrict__ sc) {
+                                                         const mlpo_step_scalars* __restrict__ sc,
+                                                         const StoreShift<MOVE> shift) {
     float gmul = 1.0f;
     if (sc != nullptr) {
         if (sc->found_inf != 0u) return;  // skipped step: nothing is read or written
@@ -275,21 +289,21 @@ __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const
             if (tile >= b.tile_begin[mid]) lo = mid; else hi = mid;
         }
         s = lo;
-        const Tile t = locate<T4>(b, tile, s);
-        Regs<BLOCK, UNROLL, NT> r;
+        const Tile t = locate<T4, MOVE>(b, shift, tile, s);
+        Regs<BLOCK, UNROLL, NT, MOVE> r;
         r.load(t, tid);
         r.update_store(t, tid, gmul, c);
     } else {
-        Tile cur = locate<T4>(b, tile, s);
-        Regs<BLOCK, UNROLL, NT> rc;
+        Tile cur = locate<T4, MOVE>(b, shift, tile, s);
+        Regs<BLOCK, UNROLL, NT, MOVE> rc;
         rc.load(cur, tid);
         for (;;) {
             const uint32_t next = tile + gridDim.x;
             const bool more = next < total && next > tile;
             Tile nxt = cur;
-            Regs<BLOCK, UNROLL, NT> rn;
+            Regs<BLOCK, UNROLL, NT, MOVE> rn;
             if (more) {
-                nxt = locate<T4>(b, next, s);
+                nxt = locate<T4, MOVE>(b, shift, next, s);
                 rn.load(nxt, tid);
             }
             rc.update_store(cur, tid, gmul, c);
@@ -325,16 +339,16 @@ __global__ void __launch_bounds__(kBlock1) adamw_v1_kernel(const ScalarBatch b, 
                 d.p16[j] = (uint16_t)update_one<0>(pp, mm, vv, widen_low<0>(d.g[j]), gmul, c);
             else
                 d.p16[j] = (uint16_t)update_one<1>(pp, mm, vv, widen_low<1>(d.g[j]), gmul, c);
-            d.p[j] = pp;
-            d.m[j] = mm;
-            d.v[j] = vv;
+            d.p[j + d.out_delta] = pp;
+            d.m[j + d.out_delta] = mm;
+            d.v[j + d.out_delta] = vv;
         }
     }
 }
 
 bool vec_aligned(const SgView& s) {
     auto a = [](const void* q) { return reinterpret_cast<uintptr_t>(q); };
-    return ((a(s.p) | a(s.m) | a(s.v)) & 15u) == 0 && ((a(s.g) | a(s.p16)) & 7u) == 0;
+    return ((a(s.p) | a(s.m) | a(s.v)) & 15u) == 0 && ((a(s.g) | a(s.p16)) & 7u) == 0 && s.out_delta % 4 == 0;
 }
 
 struct Variant {
@@ -359,18 +373,22 @@ int variant_index(uint64_t total_elems, bool tiled) {
     return total_elems >= ((uint64_t)1 << 24) ? 2 : 1;
 }
 
-template <int BLOCK, int UNROLL, bool NT, bool PERSIST>
-void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st) {
+template <int BLOCK, int UNROLL, bool NT, bool PERSIST, bool MOVE = false>
+void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
+               const StoreShift<MOVE>& shift = StoreShift<MOVE>{}) {
     hipEvent_t t0, t1;
     if (timing_enabled() && timing_acquire(kTimedUpdate, &t0, &t1))
-        hipExtLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, t0, t1, 0,
-                              b, c, sc);
+        hipExtLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST, MOVE>), dim3(grid), dim3(BLOCK), 0, st, t0, t1, 0,
+                              b, c, sc, shift);
     else
-        hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc);
+        hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST, MOVE>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc,
+                           shift);
 }
 
+// shift = nullptr: every subgroup of the batch is updated in place.  Else vi names a grid-stride variant (the only
+// ones built in the out-of-place form).
 int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
-                     int persist_blocks) {
+                     int persist_blocks, const StoreShift<true>* shift) {
     const uint32_t total = b.tile_begin[b.n_sg];
     if (total == 0) return MLPO_OK;
     uint32_t grid = total;
@@ -383,6 +401,14 @@ int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo
         if (per_cu <= 0) per_cu = 8;
         const uint64_t cap = (uint64_t)cus * (uint64_t)per_cu;
         if (cap < grid) grid = (uint32_t)cap;
+    }
+    if (shift != nullptr) {
+        if (vi == kPersistVariant)
+            launch_v4<256, 1, true, true, true>(b, grid, c, sc, st, *shift);
+        else
+            launch_v4<256, 2, true, true, true>(b, grid, c, sc, st, *shift);
+        MLPO_HIP(hipGetLastError());
+        return MLPO_OK;
     }
     switch (vi) {
         case 0: launch_v4<256, 2, true, false>(b, grid, c, sc, st); break;
@@ -414,9 +440,11 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
                  hipStream_t stream, int persist_blocks) {
     uint64_t total_elems = 0;
     bool any_tiled = false;
+    bool moves = false;  // does any subgroup's new state go somewhere else than the old one came from?
     for (int i = 0; i < n; ++i) {
         total_elems += views[i].n;
         any_tiled = any_tiled || views[i].tile_elems != 0;
+        moves = moves || views[i].out_delta != 0;
     }
     int vi = variant_index(total_elems, any_tiled);
     // A caller-fixed number of persistent blocks (the direct host-tier mode) needs the grid-stride kernel.
@@ -428,6 +456,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         if (views[i].tile_elems != 0 &&
             (uint64_t)views[i].tile_elems % ((uint64_t)kVariants[vi].block * kVariants[vi].unroll * 4u) != 0)
             vi = 1;
+    if (moves && !kVariants[vi].persist) vi = kPersistVariant;  // same tile size as variant 1
     const Variant& var = kVariants[vi];
     const uint64_t t4 = (uint64_t)var.block * (uint64_t)var.unroll;
     uint64_t align = (uint64_t)tuning().adamw_align_bytes;
@@ -438,6 +467,8 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
     VecBatch vb;
     vb.n_sg = 0;
     vb.tile_begin[0] = 0;
+    StoreShift<true> shift;
+    const StoreShift<true>* shift_arg = moves ? &shift : nullptr;
     ScalarBatch sb;
     sb.n_sg = 0;
     sb.tile_begin[0] = 0;
@@ -470,7 +501,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
             const uint64_t o = n4 * 4;
             uint64_t po = o;  // position of element o in the state arrays
             if (s.tile_elems != 0) po = (o / (uint64_t)s.tile_elems) * 3u * (uint64_t)s.tile_elems + o % (uint64_t)s.tile_elems;
-            const int rc = push_scalar(SgView{s.p + po, s.m + po, s.v + po, s.g + o, s.p16 + o, tail, 0});
+            const int rc = push_scalar(SgView{s.p + po, s.m + po, s.v + po, s.g + o, s.p16 + o, tail, 0, s.out_delta});
             if (rc != MLPO_OK) return rc;
         }
         if (n4 == 0) continue;
@@ -480,7 +511,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         if (tiles > kMaxTiles) return fail(MLPO_EINVAL, "subgroup %d too large (%llu elements)", i,
                                            (unsigned long long)s.n);
         if (vb.n_sg == kMaxSg || (uint64_t)vb.tile_begin[vb.n_sg] + tiles > kMaxTiles) {
-            const int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks);
+            const int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks, shift_arg);
             if (rc != MLPO_OK) return rc;
             vb.n_sg = 0;
         }
@@ -495,10 +526,11 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         d.tiles_per_T = s.tile_elems != 0 ? (uint32_t)((uint64_t)s.tile_elems / 4 / t4) : 0u;
         d.S4 = s.tile_elems != 0 ? (uint32_t)(3u * (uint64_t)s.tile_elems / 4) : 0u;
         d.pad = 0;
+        shift.out4[vb.n_sg] = s.out_delta / 4;
         vb.tile_begin[vb.n_sg + 1] = vb.tile_begin[vb.n_sg] + (uint32_t)tiles;
         ++vb.n_sg;
     }
-    int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks);
+    int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks, shift_arg);
     if (rc != MLPO_OK) return rc;
     return launch_scalar_batch(sb, c, scalars, stream);
 }

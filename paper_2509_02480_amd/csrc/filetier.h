@@ -16,14 +16,17 @@ namespace mlpo {
 enum class FileIo { kBuffered, kDirect, kMapped };
 FileIo file_io_kind(int fd);
 
-// One piece of a file-tier subgroup: where it lives in the file and the bounce buffer it passes through.
+// One piece that passes through a bounce buffer: read from a file into the buffer (unless the piece comes from pinned
+// memory and the kernel itself fills the buffer), updated by the kernel, written from the buffer to a file (unless the
+// kernel stored the result straight into pinned memory).  At least one of the two file sides is present.
 struct FileJob {
-    int fd;
-    uint64_t file_off;
-    size_t bytes;
-    void* buffer;  // its bounce buffer (pinned host); job i uses buffer i % n_slots
-    SgView view;   // the kernel's view of the piece in that buffer
-    FileIo io;
+    bool has_read = true, has_write = true;
+    int rd_fd = -1, wr_fd = -1;
+    uint64_t rd_off = 0, wr_off = 0;  // byte offsets of the piece in the two files
+    FileIo rd_io = FileIo::kBuffered, wr_io = FileIo::kBuffered;
+    size_t bytes = 0;
+    void* buffer = nullptr;  // its bounce buffer (pinned host); job i uses buffer i % n_slots
+    SgView view{};           // what the kernel reads and where it stores
 };
 
 // Reads the jobs in order into their bounce buffers and writes each back after its kernel has finished, with

@@ -90,11 +90,11 @@ bool copy_mapped(int fd, char* mem, size_t bytes, uint64_t off, bool to_file) {
 }
 
 bool read_range(const FileJob& j, size_t begin, size_t bytes, AlignedBlock& tmp) {
-    const int fd = j.fd;
+    const int fd = j.rd_fd;
     char* dst = static_cast<char*>(j.buffer) + begin;
-    uint64_t off = j.file_off + begin;
-    if (j.io == FileIo::kMapped) return copy_mapped(fd, dst, bytes, off, false);
-    if (j.io == FileIo::kBuffered) return read_fully(fd, dst, bytes, off);
+    uint64_t off = j.rd_off + begin;
+    if (j.rd_io == FileIo::kMapped) return copy_mapped(fd, dst, bytes, off, false);
+    if (j.rd_io == FileIo::kBuffered) return read_fully(fd, dst, bytes, off);
     if (!tmp.ensure()) {
         errno = ENOMEM;
         return false;
@@ -111,11 +111,11 @@ bool read_range(const FileJob& j, size_t begin, size_t bytes, AlignedBlock& tmp)
 }
 
 bool write_range(const FileJob& j, size_t begin, size_t bytes, AlignedBlock& tmp) {
-    const int fd = j.fd;
+    const int fd = j.wr_fd;
     char* src = static_cast<char*>(j.buffer) + begin;
-    uint64_t off = j.file_off + begin;
-    if (j.io == FileIo::kMapped) return copy_mapped(fd, src, bytes, off, true);
-    if (j.io == FileIo::kBuffered) return write_fully(fd, src, bytes, off);
+    uint64_t off = j.wr_off + begin;
+    if (j.wr_io == FileIo::kMapped) return copy_mapped(fd, src, bytes, off, true);
+    if (j.wr_io == FileIo::kBuffered) return write_fully(fd, src, bytes, off);
     if (!tmp.ensure()) {
         errno = ENOMEM;
         return false;
@@ -195,6 +195,7 @@ void FilePath::read_loop(int r) {
         size_t begin, len;
         share_of(j.bytes, r, n_threads_, &begin, &len);
         const double t0 = now_seconds();
+        if (!j.has_read) len = 0;  // the kernel fills this buffer: only the wait for the buffer above applies
         const bool ok = len == 0 || read_range(j, begin, len, tmp);
         const double t1 = now_seconds();
         if (!ok) {
@@ -232,6 +233,7 @@ void FilePath::write_loop(int r) {
         size_t begin, len;
         share_of(j.bytes, r, n_threads_, &begin, &len);
         const double t0 = now_seconds();
+        if (!j.has_write) len = 0;  // the kernel stored the result elsewhere: the buffer is free once it has finished
         const bool ok = len == 0 || write_range(j, begin, len, tmp);
         const double t1 = now_seconds();
         if (!ok) {

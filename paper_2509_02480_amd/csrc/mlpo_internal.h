@@ -66,6 +66,9 @@ struct SgView {
     uint16_t* p16;
     uint64_t n;
     int32_t tile_elems;  // 0 = planar p/m/v; T > 0 = tiled state (m == p + T, v == p + 2T, layout tiles 3T apart)
+    // Out-of-place update (tiled views only): the new p, m, v are stored out_delta floats behind where the old ones
+    // were read, i.e. into another buffer of the same layout; 0 = in place.  A multiple of 4.
+    int64_t out_delta = 0;
 };
 
 // Enqueues the fused update over `n` views (memory the device can address) on `stream`.  Views are split between

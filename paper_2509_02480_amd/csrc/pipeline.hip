@@ -113,11 +113,14 @@ static uint64_t slot_floats_for(const mlpo_subgroup* sg, int32_t n_sg, uint64_t 
 }
 
 
-// Bytes of one bounce buffer: the largest piece of any file-tier subgroup (whole layout tiles).
-static uint64_t bounce_slot_bytes(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems) {
+// Bytes of one bounce buffer: the largest piece of any subgroup that comes from a file or goes to one (whole
+// layout tiles).
+static uint64_t bounce_slot_bytes(const mlpo_subgroup* sg, int32_t n_sg, uint64_t chunk_elems,
+                                  const mlpo_flush_target* flush_to) {
     uint64_t mx = 0;
     for (int32_t i = 0; i < n_sg; ++i)
-        if (sg[i].tier == MLPO_TIER_FILE && sg[i].tile_elems > 0) {
+        if ((sg[i].tier == MLPO_TIER_FILE || (flush_to != nullptr && flush_to[i].tier == MLPO_TIER_FILE)) &&
+            sg[i].tile_elems > 0) {
             uint64_t len = sg[i].n;
             if (chunk_elems != 0 && chunk_elems < len) len = chunk_elems;
             const uint64_t b = state_floats_of(sg[i], len) * sizeof(float);
@@ -238,6 +241,7 @@ struct Plan {
     std::vector<SgView> host_views;  // host-tier subgroups as the device sees them in place (direct mode)
     std::vector<int32_t> host_ids;   // their indices in the caller's table
     std::vector<int32_t> file_ids;   // file-tier subgroups
+    std::vector<int32_t> offloaded_ids;  // host-tier and file-tier subgroups together, in processing order
 };
 
 struct Streams {
@@ -270,31 +274,62 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
             seen[(size_t)order[i]] = 1;
         }
     }
-    bool any_file = false;
+    bool any_file = false;       // does any subgroup's state live in a file?
+    bool any_bounce = false;     // ... or go to one: both need the bounce buffers
     for (int32_t i = 0; i < n_sg; ++i) {
         const bool offloaded = host_tier(sg[i].tier) || sg[i].tier == MLPO_TIER_FILE;
         if (offloaded && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
             return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
         any_file = any_file || sg[i].tier == MLPO_TIER_FILE;
     }
+    any_bounce = any_file;
+    if (cfg->flush_to != nullptr) {
+        for (int32_t i = 0; i < n_sg; ++i) {
+            const mlpo_flush_target& to = cfg->flush_to[i];
+            if (to.reserved != 0) return fail(MLPO_EINVAL, "flush target %d: reserved field is not 0", i);
+            if (to.tier == MLPO_FLUSH_IN_PLACE || sg[i].n == 0) continue;
+            if (to.tier != MLPO_TIER_HOST && to.tier != MLPO_TIER_FILE)
+                return fail(MLPO_EINVAL, "flush target %d: tier must be MLPO_TIER_HOST or MLPO_TIER_FILE", i);
+            if (!direct) return fail(MLPO_EINVAL, "flush targets need direct mode");
+            if (!(host_tier(sg[i].tier) || sg[i].tier == MLPO_TIER_FILE) || sg[i].tile_elems <= 0)
+                return fail(MLPO_EINVAL, "flush target %d: only offloaded subgroups in the tiled layout can move", i);
+            const uint64_t floats = state_floats_of(sg[i], sg[i].n);
+            if (to.tier == MLPO_TIER_HOST) {
+                if (to.state == nullptr || misaligned(to.state, 256))
+                    return fail(MLPO_EINVAL, "flush target %d: state is NULL or not 256-byte aligned", i);
+                if (host_tier(sg[i].tier) && to.state < sg[i].p + floats && sg[i].p < to.state + floats)
+                    return fail(MLPO_EINVAL, "flush target %d overlaps the subgroup's current state", i);
+            } else {
+                any_bounce = true;
+            }
+        }
+    }
     if (cfg->file_threads < 0 || cfg->file_threads > 16)
         return fail(MLPO_EINVAL, "file_threads must be 0..16 (got %d)", cfg->file_threads);
-    if (any_file) {
+    if (any_bounce) {
         if (!direct) return fail(MLPO_EINVAL, "file-tier subgroups need direct mode");
-        if (cfg->files == nullptr) return fail(MLPO_EINVAL, "file-tier subgroups but cfg->files is NULL");
+        if (any_file && cfg->files == nullptr) return fail(MLPO_EINVAL, "file-tier subgroups but cfg->files is NULL");
         if (cfg->file_slots < 1 || cfg->file_slots > MLPO_MAX_SLOTS)
             return fail(MLPO_EINVAL, "file_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->file_slots);
         if (cfg->bounce == nullptr || misaligned(cfg->bounce, 4096))
             return fail(MLPO_EINVAL, "bounce is NULL or not 4096-byte aligned");
-        const uint64_t need_bounce = bounce_slot_bytes(sg, n_sg, cfg->chunk_elems) * (uint64_t)cfg->file_slots;
+        const uint64_t need_bounce =
+            bounce_slot_bytes(sg, n_sg, cfg->chunk_elems, cfg->flush_to) * (uint64_t)cfg->file_slots;
         if (cfg->bounce_bytes < need_bounce)
             return fail(MLPO_ENOMEM, "bounce has %zu bytes, %llu needed", cfg->bounce_bytes,
                         (unsigned long long)need_bounce);
-        for (int32_t i = 0; i < n_sg; ++i)
-            if (sg[i].tier == MLPO_TIER_FILE && sg[i].n != 0) {
-                rc = check_file_extent(cfg->files[i], state_floats_of(sg[i], sg[i].n) * sizeof(float), i);
+        for (int32_t i = 0; i < n_sg; ++i) {
+            if (sg[i].n == 0) continue;
+            const uint64_t state_bytes = state_floats_of(sg[i], sg[i].n) * sizeof(float);
+            if (sg[i].tier == MLPO_TIER_FILE) {
+                rc = check_file_extent(cfg->files[i], state_bytes, i);
                 if (rc != MLPO_OK) return rc;
             }
+            if (cfg->flush_to != nullptr && cfg->flush_to[i].tier == MLPO_TIER_FILE) {
+                rc = check_file_extent(cfg->flush_to[i].file, state_bytes, i);
+                if (rc != MLPO_OK) return rc;
+            }
+        }
     }
     const uint64_t slot_floats = direct ? 0 : slot_floats_for(sg, n_sg, cfg->chunk_elems);
     const uint64_t need = slot_floats * 4u * (uint64_t)(direct ? 0 : cfg->n_slots);
@@ -338,60 +373,78 @@ static int run_direct(const Plan& plan, const AdamwConsts& c, const mlpo_step_sc
     return MLPO_OK;
 }
 
-// The file path's jobs in processing order: every file-tier subgroup cut into pieces of at most `chunk` elements
-// (0 = whole), piece i in bounce buffer i mod file_slots.
-static std::vector<FileJob> file_jobs(const mlpo_subgroup* sg, const Plan& plan, const mlpo_stream_cfg* cfg,
-                                      uint64_t buffer_bytes) {
-    const uint64_t chunk = cfg->chunk_elems;
+// Where subgroup i's state goes after the update: nullptr = back to where it came from.
+static const mlpo_flush_target* flush_target(const mlpo_stream_cfg* cfg, int32_t i) {
+    if (cfg->flush_to == nullptr || cfg->flush_to[i].tier == MLPO_FLUSH_IN_PLACE) return nullptr;
+    return &cfg->flush_to[i];
+}
+
+// Everything the link stream has to run for the offloaded subgroups, in processing order: pieces of at most
+// chunk_elems elements (0 = whole subgroups) that either touch pinned memory only (host_pieces) or pass through a
+// bounce buffer because their state comes from a file, goes to a file, or both (jobs; job i uses bounce buffer
+// i mod file_slots).  A subgroup that changes its path does so at no extra cost: pinned -> file has no read side
+// (the kernel reads the pinned state and stores into the bounce buffer), file -> pinned has no write side (the
+// kernel stores straight into the pinned destination).
+struct LinkWork {
+    std::vector<SgView> host_pieces;
     std::vector<FileJob> jobs;
-    for (int32_t i : plan.file_ids) {
+};
+
+static LinkWork link_work(const mlpo_subgroup* sg, const Plan& plan, const mlpo_stream_cfg* cfg,
+                          uint64_t buffer_bytes) {
+    const uint64_t chunk = cfg->chunk_elems;
+    LinkWork w;
+    for (int32_t i : plan.offloaded_ids) {
         const mlpo_subgroup& s = sg[i];
-        const uint64_t T = (uint64_t)s.tile_elems;
-        const FileIo io = file_io_kind(cfg->files[i].fd);
+        const mlpo_flush_target* to = flush_target(cfg, i);
+        const bool from_file = s.tier == MLPO_TIER_FILE;
+        const bool to_file = to != nullptr ? to->tier == MLPO_TIER_FILE : from_file;
+        const uint64_t T = (uint64_t)s.tile_elems;  // 0 only for planar host-tier subgroups, which stay in place
         const uint64_t step_elems = (chunk != 0 && chunk < s.n) ? chunk : s.n;
         for (uint64_t off = 0; off < s.n; off += step_elems) {
             const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
+            // chunk is a multiple of the layout tile, so a piece starts at a layout tile boundary
+            const uint64_t state_off = T > 0 ? (off / T) * 3u * T : off;  // floats from the start of the state
+            if (!from_file && !to_file) {
+                SgView v{s.p + state_off, s.m + state_off, s.v + state_off, s.g + off, s.p16 + off, len, s.tile_elems};
+                if (to != nullptr) v.out_delta = (to->state + state_off) - v.p;
+                w.host_pieces.push_back(v);
+                continue;
+            }
             FileJob j;
-            j.fd = cfg->files[i].fd;
-            j.file_off = cfg->files[i].offset + (off / T) * 3u * T * sizeof(float);
             j.bytes = (size_t)(round_up(len, T) * 3u * sizeof(float));
-            char* buf = static_cast<char*>(cfg->bounce) + (jobs.size() % (size_t)cfg->file_slots) * buffer_bytes;
+            char* buf = static_cast<char*>(cfg->bounce) + (w.jobs.size() % (size_t)cfg->file_slots) * buffer_bytes;
             float* f = reinterpret_cast<float*>(buf);
             j.buffer = buf;
-            j.io = io;
-            j.view = SgView{f, f + T, f + 2 * T, s.g + off, s.p16 + off, len, s.tile_elems};
-            jobs.push_back(j);
+            j.has_read = from_file;
+            j.has_write = to_file;
+            if (from_file) {
+                j.rd_fd = cfg->files[i].fd;
+                j.rd_off = cfg->files[i].offset + state_off * sizeof(float);
+                j.rd_io = file_io_kind(j.rd_fd);
+            }
+            if (to_file) {
+                const mlpo_file_extent& x = to != nullptr ? to->file : cfg->files[i];
+                j.wr_fd = x.fd;
+                j.wr_off = x.offset + state_off * sizeof(float);
+                j.wr_io = file_io_kind(j.wr_fd);
+            }
+            // the kernel reads the bounce buffer (state from a file) or the pinned source, and stores into the bounce
+            // buffer (state bound for a file) or the pinned destination
+            float* src = from_file ? f : s.p + state_off;
+            float* dst = to_file ? f : to->state + state_off;
+            j.view = SgView{src, src + T, src + 2 * T, s.g + off, s.p16 + off, len, s.tile_elems};
+            j.view.out_delta = dst - src;
+            w.jobs.push_back(j);
         }
     }
-    return jobs;
+    return w;
 }
 
-// The host path's pieces: every host-tier subgroup as the device sees it in place, cut the same way.
-static std::vector<SgView> host_pieces_of(const Plan& plan, uint64_t chunk) {
-    std::vector<SgView> pieces;
-    for (const SgView& v : plan.host_views) {
-        const uint64_t step_elems = (chunk != 0 && chunk < v.n) ? chunk : v.n;
-        for (uint64_t off = 0; off < v.n; off += step_elems) {
-            SgView piece = v;
-            // chunk is a multiple of the layout tile, so a piece starts at a layout tile boundary
-            const uint64_t shift =
-                v.tile_elems > 0 ? (off / (uint64_t)v.tile_elems) * 3u * (uint64_t)v.tile_elems : off;
-            piece.p += shift;
-            piece.m += shift;
-            piece.v += shift;
-            piece.g += off;
-            piece.p16 += off;
-            piece.n = (v.n - off < step_elems) ? (v.n - off) : step_elems;
-            pieces.push_back(piece);
-        }
-    }
-    return pieces;
-}
-
-// Direct mode with file-tier subgroups: two paths behind the offloaded tier (Section 3.2 "Unified Multi-level,
-// Multi-path Asynchronous Offloading using Virtual Tiers").  Both end on the link, so their kernels share one stream:
-// host-tier subgroups cut into pieces of chunk_elems, and file-tier pieces, each launched as soon as its read has
-// finished.  At most two launches are queued at a time, so a piece that arrives from the file waits for one
+// Direct mode with file-tier subgroups or flush targets: two paths behind the offloaded tier (Section 3.2 "Unified
+// Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers").  Both end on the link, so their kernels share
+// one stream: pinned-only pieces, and pieces that pass through a bounce buffer, each launched as soon as its read has
+// finished (or, without a read side, as soon as its buffer is free).  At most two launches are queued at a time, so a piece that arrives from the file waits for one
 // host-tier piece at most, and the file keeps working while the link is busy with the host tier.
 static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& plan, const AdamwConsts& c,
                             const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, const Streams& st,
@@ -401,9 +454,9 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
     int device = 0;
     MLPO_HIP(hipGetDevice(&device));
     const int blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 64;
-    const std::vector<SgView> host_pieces = host_pieces_of(plan, cfg->chunk_elems);
-    FilePath files(file_jobs(sg, plan, cfg, bounce_slot_bytes(sg, n_sg, cfg->chunk_elems)), cfg->file_slots,
-                   cfg->file_threads > 0 ? cfg->file_threads : 2, device);
+    LinkWork work = link_work(sg, plan, cfg, bounce_slot_bytes(sg, n_sg, cfg->chunk_elems, cfg->flush_to));
+    const std::vector<SgView>& host_pieces = work.host_pieces;
+    FilePath files(std::move(work.jobs), cfg->file_slots, cfg->file_threads > 0 ? cfg->file_threads : 2, device);
 
     MLPO_HIP(hipEventRecord(ec.fence2, st.cmp));  // gradients and scalars come from the compute stream
     MLPO_HIP(hipStreamWaitEvent(st.h2d, ec.fence2, 0));
@@ -570,9 +623,10 @@ size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t 
     return (size_t)(slot_floats_for(sg, n_sg, chunk_elems) * 4u * (uint64_t)n_slots);
 }
 
-size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t file_slots, uint64_t chunk_elems) {
+size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t file_slots, uint64_t chunk_elems,
+                                const mlpo_flush_target* flush_to) {
     if (sg == nullptr || n_sg <= 0 || file_slots <= 0) return 0;
-    return (size_t)(bounce_slot_bytes(sg, n_sg, chunk_elems) * (uint64_t)file_slots);
+    return (size_t)(bounce_slot_bytes(sg, n_sg, chunk_elems, flush_to) * (uint64_t)file_slots);
 }
 
 int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order, const mlpo_adamw_hparams* hp,
@@ -608,7 +662,9 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
             plan.resident.push_back(v);
         } else if (sg[i].tier == MLPO_TIER_FILE) {
             plan.file_ids.push_back(i);
+            plan.offloaded_ids.push_back(i);
         } else {
+            plan.offloaded_ids.push_back(i);
             plan.host_ids.push_back(i);
             plan.host_views.push_back(v);
         }
@@ -628,7 +684,9 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
         st.h2d = ec.copy_in;
         st.d2h = ec.copy_out;
     }
-    if (direct && !plan.file_ids.empty()) return run_direct_files(sg, n_sg, plan, c, scalars, cfg, st, ec);
+    bool moves = false;  // does any subgroup go to another place than it came from?
+    for (int32_t i : plan.offloaded_ids) moves = moves || flush_target(cfg, i) != nullptr;
+    if (direct && (!plan.file_ids.empty() || moves)) return run_direct_files(sg, n_sg, plan, c, scalars, cfg, st, ec);
     if (direct) return run_direct(plan, c, scalars, cfg, st, ec);
 
     // Work enqueued earlier on the flush and compute streams (a previous step's copy back, the gradient pass) must

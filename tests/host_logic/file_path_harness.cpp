@@ -27,8 +27,8 @@ int run(int n_jobs, int n_slots, int n_threads, size_t bytes, bool fail_write) {
     std::vector<FileJob> jobs;
     for (int i = 0; i < n_jobs; ++i) {
         FileJob j{};
-        j.fd = io_fd; j.file_off = (uint64_t)i * bytes; j.bytes = bytes; j.buffer = base + (size_t)(i % n_slots) * bytes;
-        j.io = FileIo::kBuffered;
+        j.rd_fd = j.wr_fd = io_fd; j.rd_off = j.wr_off = (uint64_t)i * bytes; j.bytes = bytes;
+        j.buffer = base + (size_t)(i % n_slots) * bytes;
         jobs.push_back(j);
     }
     FilePath fp(std::move(jobs), n_slots, n_threads, 0);

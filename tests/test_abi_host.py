@@ -223,8 +223,9 @@ def test_binding_structs_match_the_header(tmp_path):
 int main(void) {
     printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(mlpo_adamw_hparams), sizeof(mlpo_subgroup),
            sizeof(mlpo_step_scalars), sizeof(mlpo_slot_cache), sizeof(mlpo_stream_cfg), sizeof(mlpo_file_extent),
-           sizeof(mlpo_file_stats), offsetof(mlpo_stream_cfg, file_stats), offsetof(mlpo_slot_cache, hits),
+           sizeof(mlpo_file_stats), offsetof(mlpo_stream_cfg, flush_to), offsetof(mlpo_slot_cache, hits),
            offsetof(mlpo_subgroup, tile_elems));
+    printf("%zu %zu\\n", sizeof(mlpo_flush_target), offsetof(mlpo_flush_target, file));
     return 0;
 }
 ''')
@@ -233,8 +234,9 @@ int main(void) {
     subprocess.check_call(["gcc", "-I", inc, "-o", str(exe), str(src)])
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     want = [C.sizeof(B.HParamsC), C.sizeof(B.SubgroupC), C.sizeof(B.StepScalarsC), C.sizeof(B.SlotCacheC),
-            C.sizeof(B.StreamCfgC), C.sizeof(B.FileExtentC), C.sizeof(B.FileStatsC), B.StreamCfgC.file_stats.offset,
-            B.SlotCacheC.hits.offset, B.SubgroupC.tile_elems.offset]
+            C.sizeof(B.StreamCfgC), C.sizeof(B.FileExtentC), C.sizeof(B.FileStatsC), B.StreamCfgC.flush_to.offset,
+            B.SlotCacheC.hits.offset, B.SubgroupC.tile_elems.offset, C.sizeof(B.FlushTargetC),
+            B.FlushTargetC.file.offset]
     assert got == want
 
 
@@ -298,3 +300,46 @@ def test_half_format_errors():
     expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg(half_format=-1)], 1.0, 0.0, FAKE, B.mlpo_norm_workspace_bytes(),
            FAKE)
     expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, FAKE + 4096, 16, half=2)
+
+
+def test_flush_target_argument_errors(tmp_path):
+    hp = B.HParams()
+    T, n = 1024, 3000
+    floats = B.mlpo_state_floats(n, T)
+    path = tmp_path / "state.bin"
+    path.write_bytes(bytes(2 * floats * 4))
+    fd = os.open(str(path), os.O_RDWR)
+    try:
+        hostsg = B.tiled_subgroup(FAKE_PAGE, FAKE, FAKE + (1 << 20), n=n, tier=B.TIER_HOST, tile_elems=T)
+        other = FAKE_PAGE + (1 << 30)
+
+        def cfg(target, **kw):
+            args = dict(bounce=FAKE_PAGE + (2 << 30), bounce_bytes=1 << 30, file_slots=2, flush_to=[target])
+            args.update(kw)
+            return B.direct_cfg(None, None, 8, **args)
+
+        # to a file: the bounce buffers are needed even though nothing is file-tier yet
+        assert B.mlpo_stream_bounce_bytes([hostsg], 2, 0) == 0
+        assert B.mlpo_stream_bounce_bytes([hostsg], 2, 0, flush_to=[(fd, 0)]) == 2 * floats * 4
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, cfg((fd, 0), bounce=0))
+        expect(B.MLPO_ENOMEM, B.mlpo_stream_update, [hostsg], None, hp, 1, None, cfg((fd, 0), bounce_bytes=4096))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, cfg((fd, 100)))        # offset
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, cfg((fd, 2 * floats * 4)))  # too short
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, cfg(other + 64))       # alignment
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, cfg(FAKE_PAGE + 256))  # overlaps
+        bad = cfg(other)
+        bad._flush[0].tier = 7
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, bad)
+        bad = cfg(other)
+        bad._flush[0].reserved = 1
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, bad)
+        planar = sg(n=n, tier=B.TIER_HOST)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [planar], None, hp, 1, None, cfg(other))            # planar layout
+        hbm = B.tiled_subgroup(FAKE_PAGE, FAKE, FAKE + (1 << 20), n=n, tier=B.TIER_HBM, tile_elems=T)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hbm], None, hp, 1, None, cfg(other))               # not offloaded
+        staged = B.stream_cfg(2, FAKE, 1 << 30, None, None, None, 0)
+        staged._flush = B.flush_targets([other])
+        staged.flush_to = staged._flush
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, staged)                # staged mode
+    finally:
+        os.close(fd)

@@ -247,3 +247,114 @@ def test_io_threads_and_kinds_of_descriptors(oracle, tmp_path, threads, direct_i
         shard.close()
         if where == "shm" and os.path.exists(path):
             os.unlink(path)
+
+
+@pytest.mark.parametrize("chunk,file_slots,direct_io", [(0, 1, False), (8192, 3, True), (16_384, 2, False)])
+def test_subgroups_change_their_path_at_flush_time(oracle, tmp_path, chunk, file_slots, direct_io):
+    """Algorithm 1 assigns the path anew whenever a subgroup is flushed.  Every offloaded subgroup has two pinned
+    buffers and two file extents to live in; a schedule moves them around - pinned to file, file to pinned, pinned to
+    another pinned buffer, file to another extent, or not at all - while the updates go on.  After every step the
+    state is read from wherever it lives now and compared with the oracle's."""
+    ohp, ghp = hp_pair(oracle)
+    T, n, n_sub = 2048, 90_001, 5
+    wl = W.Workload("move", n_sub=n_sub, sub_elems=n, n_host=0, loss_scale=16.0, max_norm=0.1, steps=5)
+    host = W.host_subgroups(wl, warm=True)
+    floats = B.mlpo_state_floats(n, T)
+    ext = (floats * 4 + 4095) // 4096 * 4096
+    path = str(tmp_path / "state.bin")
+    with open(path, "wb") as f:
+        f.truncate(2 * n_sub * ext)
+    try:
+        fd = os.open(path, os.O_RDWR | (os.O_DIRECT if direct_io else 0))
+    except OSError:
+        fd = os.open(path, os.O_RDWR)
+    plain = os.open(path, os.O_RDWR)          # the test's own reads and writes (no alignment rules)
+    d = dev()
+    pinned = [[torch.zeros(floats, dtype=torch.float32, pin_memory=True) for _ in range(2)] for _ in range(n_sub)]
+    extent = [[(2 * k + j) * ext for j in range(2)] for k in range(n_sub)]
+    g = [torch.from_numpy(s["g"].view(np.int16)).to(d) for s in host]
+    p16 = [torch.from_numpy(s["p16"].view(np.int16)).to(d) for s in host]
+    hbm_state = torch.from_numpy(pack_tiled(host[4]["p"], host[4]["m"], host[4]["v"], T)).to(d)
+    # where each offloaded subgroup lives: ("host", j) or ("file", j); subgroup 4 stays in HBM
+    home = [("file", 0), ("host", 0), ("host", 1), ("file", 1)]
+    for k, (kind, j) in enumerate(home):
+        packed = pack_tiled(host[k]["p"], host[k]["m"], host[k]["v"], T)
+        if kind == "host":
+            pinned[k][j].copy_(torch.from_numpy(packed))
+        else:
+            os.pwrite(plain, packed.tobytes() + bytes(ext - packed.nbytes), extent[k][j])
+    os.fsync(plain)
+    schedule = [
+        [("host", 0), ("file", 0), ("host", 0), ("file", 0)],     # file->pinned, pinned->file, pinned->pinned', file->file'
+        [("host", 0), ("file", 0), ("host", 0), ("file", 0)],     # nobody moves
+        [("file", 1), ("host", 1), ("file", 0), ("host", 1)],     # everybody changes sides
+        [("file", 0), ("host", 0), ("file", 1), ("host", 0)],     # same kind, other buffer / extent
+        [("host", 1), ("host", 0), ("host", 0), ("host", 0)],     # all into pinned memory
+    ]
+
+    def table_and_files():
+        descs, files = [], []
+        for k, (kind, j) in enumerate(home):
+            if kind == "host":
+                descs.append(B.tiled_subgroup(pinned[k][j], g[k], p16[k], n=n, tier=B.TIER_HOST, tile_elems=T))
+                files.append(None)
+            else:
+                descs.append(B.SubgroupC(None, None, None, g[k].data_ptr(), p16[k].data_ptr(), n, B.TIER_FILE, T))
+                files.append((fd, extent[k][j]))
+        descs.append(B.tiled_subgroup(hbm_state, g[4], p16[4], n=n, tile_elems=T))
+        files.append(None)
+        return B.SubgroupTable(descs), files
+
+    def fetch(k):
+        torch.cuda.synchronize()
+        if k == 4:
+            buf = hbm_state.cpu().numpy()
+        elif home[k][0] == "host":
+            buf = pinned[k][home[k][1]].numpy()
+        else:
+            buf = np.frombuffer(os.pread(plain, floats * 4, extent[k][home[k][1]]), dtype=np.float32)
+        p, m, v = unpack_tiled(buf, n, T)
+        return {"p": p, "m": m, "v": v, "p16": p16[k].cpu().numpy().view(np.uint16).copy()}
+
+    scratch = Scratch()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    try:
+        for s in range(wl.steps):
+            if s > 0:
+                for k, sg in enumerate(host):
+                    W.fill_grads(wl, k, s, sg["g"])
+                    g[k].copy_(torch.from_numpy(sg["g"].view(np.int16)))
+            table, files = table_and_files()
+            new_home = schedule[s]
+            targets = []
+            for k in range(4):
+                if new_home[k] == home[k]:
+                    targets.append(None)
+                elif new_home[k][0] == "host":
+                    pinned[k][new_home[k][1]].fill_(float("nan"))          # whatever was there must be overwritten
+                    targets.append(pinned[k][new_home[k][1]])
+                else:
+                    targets.append((fd, extent[k][new_home[k][1]]))
+            targets.append(None)
+            need = B.mlpo_stream_bounce_bytes(table, file_slots, chunk, flush_to=targets)
+            bounce = torch.empty(max(need, 4096), dtype=torch.uint8, pin_memory=True)
+            cfg = B.direct_cfg(streams[0], streams[1], 20, chunk_elems=chunk, files=files, bounce=bounce,
+                               bounce_bytes=bounce.numel(), file_slots=file_slots, file_threads=2,
+                               want_file_stats=True, flush_to=targets)
+            torch.cuda.synchronize()
+            ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm)
+            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                     streams[1])
+            assert B.mlpo_stream_update(table, None, ghp, s + 1, scratch.scalars, cfg) and ok_o
+            streams[1].synchronize()
+            assert scratch.read()["gmul"] == gmul_o
+            reads = sum(1 for k in range(4) if home[k][0] == "file")
+            writes = sum(1 for k in range(4) if new_home[k][0] == "file")
+            assert cfg.stats.bytes_read == reads * floats * 4 and cfg.stats.bytes_written == writes * floats * 4
+            home = list(new_home)
+            for k in range(n_sub):
+                assert_state_parity(fetch(k), host[k], f"step {s} sg {k} now at {home[k] if k < 4 else 'hbm'}")
+    finally:
+        torch.cuda.synchronize()
+        os.close(fd)
+        os.close(plain)

@@ -1,6 +1,7 @@
 """Seeded random scenarios for mlpo_stream_update: subgroups of random sizes (empty ones included) spread over every
 tier and both layouts in one table, random mode, slots, chunking, slot cache, order and thread counts, a non-finite
-gradient now and then.  After every step every bit of state is compared with the oracle's (the paper's statement that
+gradient now and then, and in direct mode offloaded subgroups that are flushed to another place than they came from
+(Algorithm 1 assigns the path anew at every flush).  After every step every bit of state is compared with the oracle's (the paper's statement that
 order and partitioning do not change the result, Section 3.2 "Cache-Friendly Ordering", Section 4.1 "Runtime
 Configurations")."""
 import math
@@ -93,7 +94,7 @@ def build(rng, host, tiers, tiles, path, half):
             p, m, v = (t.cpu().numpy().copy() for t in e["pmv"])
         return {"p": p, "m": m, "v": v, "p16": p16}
 
-    return B.SubgroupTable(descs), files, keep, fetch, fd
+    return descs, files, keep, fetch, fd, off
 
 
 @pytest.mark.parametrize("seed", range(64))
@@ -129,18 +130,15 @@ def test_random_scenario(oracle, tmp_path, seed):
     label = (f"seed {seed}: {'direct' if direct else 'staged'} sizes {sizes} tiers {tiers} tiles {tiles} chunk {chunk} "
              f"slots {n_slots} cached {cached} {half_name}")
     print(label, flush=True)
-    table, files, keep, fetch, fd = build(rng, host, tiers, tiles, str(tmp_path / "state.bin"), half)
+    descs, files, keep, fetch, fd, file_end = build(rng, host, tiers, tiles, str(tmp_path / "state.bin"), half)
+    table = B.SubgroupTable(descs)
     scratch = Scratch()
     streams = (torch.cuda.Stream(), torch.cuda.Stream())
     cache = B.SlotCacheC() if cached else None
     try:
         if direct:
             slots = int(rng.integers(1, 4))
-            need = B.mlpo_stream_bounce_bytes(table, slots, chunk)
-            bounce = torch.empty(max(need, 4096), dtype=torch.uint8, pin_memory=True)
-            cfg = B.direct_cfg(streams[0], streams[1], int(rng.integers(1, 40)), chunk_elems=chunk, files=files,
-                               bounce=bounce, bounce_bytes=bounce.numel(), file_slots=slots,
-                               file_threads=int(rng.integers(1, 5)))
+            blocks, threads = int(rng.integers(1, 40)), int(rng.integers(1, 5))
         else:
             need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
             stg = torch.empty(max(need, 256), dtype=torch.uint8, device=dev())
@@ -159,6 +157,28 @@ def test_random_scenario(oracle, tmp_path, seed):
                 if step == 1 and seed % 4 == 0 and k == n_sub - 1:
                     s["g"][n // 2] = 0x7C00 if half else 0x7F80
                 keep[k]["g"].copy_(torch.from_numpy(s["g"].view(np.int16)))
+            moved = {}          # subgroup -> its new home, if this step's update is applied
+            if direct:
+                targets = [None] * n_sub
+                for k, e in enumerate(keep):
+                    movable = e["n"] > 0 and e["T"] and e["tier"] != B.TIER_HBM
+                    if not movable or rng.integers(0, 3) != 0:
+                        continue
+                    floats = B.mlpo_state_floats(e["n"], e["T"])
+                    if e["tier"] == B.TIER_HOST_GRADS or rng.integers(0, 2):
+                        st = torch.full((floats,), float("nan"), dtype=torch.float32, pin_memory=True)
+                        targets[k] = st
+                        moved[k] = {"state": st, "tier": e["tier"] if e["tier"] != B.TIER_FILE else B.TIER_HOST}
+                    else:
+                        targets[k] = (fd, file_end)
+                        moved[k] = {"off": file_end, "tier": B.TIER_FILE}
+                        file_end += (floats * 4 + 4095) // 4096 * 4096
+                        os.ftruncate(fd, file_end)
+                need = B.mlpo_stream_bounce_bytes(table, slots, chunk, flush_to=targets)
+                bounce = torch.empty(max(need, 4096), dtype=torch.uint8, pin_memory=True)
+                cfg = B.direct_cfg(streams[0], streams[1], blocks, chunk_elems=chunk, files=files, bounce=bounce,
+                                   bounce_bytes=bounce.numel(), file_slots=slots, file_threads=threads,
+                                   flush_to=targets if moved else None)
             torch.cuda.synchronize()
             ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, applied, inv_scale, max_norm, order=order,
                                                        half=half_name)
@@ -172,6 +192,21 @@ def test_random_scenario(oracle, tmp_path, seed):
             if ok_o:
                 applied += 1
                 assert sc["gmul"] == gmul_o, label
+                for k, new in moved.items():         # a skipped step moves nothing
+                    e = keep[k]
+                    e.pop("state", None)
+                    e.pop("off", None)
+                    e.update(new)
+                    if e["tier"] == B.TIER_FILE:
+                        descs[k] = B.SubgroupC(None, None, None, e["g"].data_ptr(), e["p16"].data_ptr(), e["n"],
+                                               B.TIER_FILE, e["T"], half, 0)
+                        files[k] = (fd, e["off"])
+                    else:
+                        descs[k] = B.tiled_subgroup(e["state"], e["g"], e["p16"], n=e["n"], tier=e["tier"],
+                                                    tile_elems=e["T"], half=half)
+                        files[k] = None
+                if moved:
+                    table = B.SubgroupTable(descs)
             if cached:
                 B.mlpo_stream_flush(table, cfg)
                 streams[1].synchronize()
