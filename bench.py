@@ -483,6 +483,45 @@ class StreamedBench:
         return rec
 
 
+def promote_bench(sb, host_GBs):
+    """Re-balancing between HBM and the offloaded tier (Eq. 1 with capacities, Section 3.3; Algorithm 1 assigns the
+    path anew at every flush): HBM has room for ``--hbm-capacity`` more subgroups, one ordinary update step stores
+    their new state there instead of sending it back over the link, the following steps run with the new split, and
+    a last step sends them back to pinned memory."""
+    torch, B, wl, args = sb.torch, sb.B, sb.wl, sb.args
+    host_ids = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
+    state_bytes = B.mlpo_state_floats(sb.M, sb.T) * 4
+    # Eq. 1 in subgroups per second: the HBM "path" at the resident kernel's rate, the link at the measured one
+    bw = [HBM_PEAK_GBS * 0.78 * 1e9 / (28 * sb.M), host_GBs * 1e9 / state_bytes]
+    counts, _ = B.mlpo_assign_tiers(len(host_ids), bw, [min(args.hbm_capacity, len(host_ids)), len(host_ids)])
+    movers = host_ids[:counts[0]]
+    res = {"eq1_bandwidth_subgroups_per_s": [round(x, 1) for x in bw], "hbm_capacity": args.hbm_capacity,
+           "eq1_split_hbm_pinned": list(counts)}
+    if not movers:
+        return res
+    homes = {k: torch.empty(state_bytes // 4, dtype=torch.float32, device=sb.d) for k in movers}
+
+    def cfg_for(targets):
+        return B.direct_cfg(sb.h2d, sb.cmp, 64, chunk_elems=args.multipath_chunk,
+                            flush_to=[targets.get(k) for k in range(wl.n_sub)] if targets else None)
+
+    res["promote_step_ms"] = round(sb.step("d", sb.table, cfg_for(homes), None) * 1e3, 2)
+    sgs = [B.tiled_subgroup(homes[k] if k in homes else sb.keep[k], sb.grads(k), sb.p16(k), n=sb.M,
+                            tier=B.TIER_HBM if k in homes else wl.tier(k), tile_elems=sb.T) for k in range(wl.n_sub)]
+    table = B.SubgroupTable(sgs)
+    cfg = cfg_for(None)
+    times = [sb.step("d", table, cfg, None) for _ in range(args.stream_warmup + wl.steps)][args.stream_warmup:]
+    mean = sum(times) / len(times)
+    n_left = len(host_ids) - len(movers)
+    res.update({"steps": len(times), "ms_per_step_after": round(mean * 1e3, 2), "min_ms": round(min(times) * 1e3, 2),
+                "Gparams_s": round(wl.n_total / mean / 1e9, 3),
+                "pcie_GBs_per_dir": round(n_left * state_bytes / mean / 1e9, 2)})
+    back = {k: sb.keep[k] for k in movers}
+    res["demote_step_ms"] = round(sb.step("d", table, cfg_for(back), None) * 1e3, 2)
+    log(f"[bench] promote {res}")
+    return res
+
+
 def streamed_bench(args, torch, B, W, np):
     sb = StreamedBench(args, torch, B, W, np)
     wl = sb.wl
@@ -495,6 +534,8 @@ def streamed_bench(args, torch, B, W, np):
     # the cached runs move less data, so their "GB/s" is not a link rate: the best link rate is among the others
     best = max((r for r in out["runs"] if "pcie_GBs_per_dir" in r), key=lambda r: r["pcie_GBs_per_dir"])
     out["best"] = best
+    if args.hbm_capacity > 0:
+        out["hbm_rebalance"] = promote_bench(sb, best["pcie_GBs_per_dir"])
     if args.multipath != "none":
         ctx = dict(wl=wl, keep=sb.keep, g_flat=sb.g_flat, p16_flat=sb.p16_flat, T=sb.T, M=sb.M, ws=sb.ws,
                    ws_bytes=sb.ws_bytes, scal=sb.scal, hp=sb.hp, streams=(sb.h2d, sb.cmp), applied=sb.applied,
@@ -762,6 +803,8 @@ def main():
                          "--file-dir, O_DIRECT), shm (a file in /dev/shm), or 'none'")
     ap.add_argument("--pinned-capacity", type=int, default=10,
                     help="subgroups the pinned-host path may hold in the two-path run (the rest go to the file)")
+    ap.add_argument("--hbm-capacity", type=int, default=4,
+                    help="streamed workload: subgroups that HBM has room for in the re-balancing run (0 = skip it)")
     ap.add_argument("--file-GBs-guess", type=float, default=3.0, help="initial bandwidth estimate of the file path")
     ap.add_argument("--file-dir", default="", help="directory for the file path's file (default: the temp dir)")
     ap.add_argument("--file-slots", type=int, default=3)

@@ -261,21 +261,24 @@ typedef struct {
     uint64_t offset;
 } mlpo_file_extent;
 
-/* Where the fp32 state of an offloaded subgroup goes after the update when that is not where it was read from.
+/* Where the fp32 state of a subgroup goes after the update when that is not where it was read from.
  * Algorithm 1 assigns the path anew every time a subgroup is flushed, so that a re-estimated Eq. 1 (Section 3.3)
- * takes effect; as the update reads the whole state and writes the whole state anyway, sending it to the other path
- * costs nothing extra: pinned -> file has no read from the file, file -> pinned has no write to it.  Direct mode,
- * tiled layout only; entries of HBM-tier and planar subgroups must say MLPO_FLUSH_IN_PLACE.  After an applied step
- * the caller describes the subgroup by its new home (what the old one holds is then stale); a skipped step moves
- * nothing and the state stays where it was.  The targets of different subgroups must not overlap each other or
- * any other subgroup's state: the library checks a target only against its own subgroup's current state. */
+ * takes effect; as the update reads the whole state and writes the whole state anyway, sending it somewhere else
+ * costs nothing extra: pinned -> file has no read from the file, file -> pinned has no write to it, and a subgroup
+ * that enters or leaves HBM crosses the link once instead of twice.  Direct mode, tiled layout only; entries of
+ * planar subgroups must say MLPO_FLUSH_IN_PLACE.  Allowed: from pinned memory or a file to any of the three tiers,
+ * from HBM to pinned memory or a file (a MLPO_TIER_HOST_GRADS subgroup cannot go to HBM: its gradients would have to
+ * move as well).  After an applied step the caller describes the subgroup by its new home (what the old one holds
+ * is then stale); a skipped step moves nothing and the state stays where it was.  The targets of different
+ * subgroups must not overlap each other or any other subgroup's state: the library checks a target only against
+ * its own subgroup's current state. */
 #define MLPO_FLUSH_IN_PLACE (-1)
 typedef struct {
-    int32_t tier;          /* MLPO_FLUSH_IN_PLACE, MLPO_TIER_HOST or MLPO_TIER_FILE */
+    int32_t tier;          /* MLPO_FLUSH_IN_PLACE, MLPO_TIER_HBM, MLPO_TIER_HOST or MLPO_TIER_FILE */
     int32_t reserved;      /* must be 0 */
-    float* state;          /* MLPO_TIER_HOST: pinned host buffer of mlpo_state_floats(n, tile_elems) floats, 256-byte
-                              aligned, not overlapping the subgroup's current state; the new p, m, v are stored there
-                              in the tiled layout */
+    float* state;          /* MLPO_TIER_HBM / MLPO_TIER_HOST: device / pinned host buffer of
+                              mlpo_state_floats(n, tile_elems) floats, 256-byte aligned, not overlapping the
+                              subgroup's current state; the new p, m, v are stored there in the tiled layout */
     mlpo_file_extent file; /* MLPO_TIER_FILE: where the state is written (may be the extent it came from) */
 } mlpo_flush_target;
 

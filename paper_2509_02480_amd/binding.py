@@ -274,15 +274,19 @@ def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chu
 
 def flush_targets(targets) -> "C.Array":
     """Array of mlpo_flush_target from a list with one entry per subgroup: None (stays where it is), a pinned-host
-    tensor / address (goes to pinned memory) or an (fd, offset) pair (goes to a file)."""
+    tensor / address (goes to pinned memory), a device tensor (goes to HBM), an (fd, offset) pair (goes to a file) or a
+    ready-made FlushTargetC."""
     arr = (FlushTargetC * max(len(targets), 1))()
     for i, t in enumerate(targets):
         if t is None:
             arr[i] = FlushTargetC(FLUSH_IN_PLACE, 0, None, FileExtentC(-1, 0, 0))
+        elif isinstance(t, FlushTargetC):
+            arr[i] = t
         elif isinstance(t, tuple):
             arr[i] = FlushTargetC(TIER_FILE, 0, None, FileExtentC(int(t[0]), 0, int(t[1])))
         else:
-            arr[i] = FlushTargetC(TIER_HOST, 0, _ptr(t), FileExtentC(-1, 0, 0))
+            tier = TIER_HBM if getattr(t, "is_cuda", False) else TIER_HOST
+            arr[i] = FlushTargetC(tier, 0, _ptr(t), FileExtentC(-1, 0, 0))
     return arr
 
 

@@ -277,7 +277,8 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
     bool any_file = false;       // does any subgroup's state live in a file?
     bool any_bounce = false;     // ... or go to one: both need the bounce buffers
     for (int32_t i = 0; i < n_sg; ++i) {
-        const bool offloaded = host_tier(sg[i].tier) || sg[i].tier == MLPO_TIER_FILE;
+        const bool offloaded = host_tier(sg[i].tier) || sg[i].tier == MLPO_TIER_FILE ||
+                               (cfg->flush_to != nullptr && cfg->flush_to[i].tier != MLPO_FLUSH_IN_PLACE);
         if (offloaded && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
             return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
         any_file = any_file || sg[i].tier == MLPO_TIER_FILE;
@@ -288,16 +289,21 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
             const mlpo_flush_target& to = cfg->flush_to[i];
             if (to.reserved != 0) return fail(MLPO_EINVAL, "flush target %d: reserved field is not 0", i);
             if (to.tier == MLPO_FLUSH_IN_PLACE || sg[i].n == 0) continue;
-            if (to.tier != MLPO_TIER_HOST && to.tier != MLPO_TIER_FILE)
-                return fail(MLPO_EINVAL, "flush target %d: tier must be MLPO_TIER_HOST or MLPO_TIER_FILE", i);
+            if (to.tier != MLPO_TIER_HBM && to.tier != MLPO_TIER_HOST && to.tier != MLPO_TIER_FILE)
+                return fail(MLPO_EINVAL, "flush target %d: tier must be MLPO_TIER_HBM, MLPO_TIER_HOST or MLPO_TIER_FILE",
+                            i);
             if (!direct) return fail(MLPO_EINVAL, "flush targets need direct mode");
-            if (!(host_tier(sg[i].tier) || sg[i].tier == MLPO_TIER_FILE) || sg[i].tile_elems <= 0)
-                return fail(MLPO_EINVAL, "flush target %d: only offloaded subgroups in the tiled layout can move", i);
+            if (sg[i].tile_elems <= 0)
+                return fail(MLPO_EINVAL, "flush target %d: only subgroups in the tiled layout can move", i);
+            if (sg[i].tier == MLPO_TIER_HBM && to.tier == MLPO_TIER_HBM)
+                return fail(MLPO_EINVAL, "flush target %d: an HBM-tier subgroup can move to pinned memory or a file", i);
+            if (sg[i].tier == MLPO_TIER_HOST_GRADS && to.tier == MLPO_TIER_HBM)
+                return fail(MLPO_EINVAL, "flush target %d: the gradients of an HBM-tier subgroup live on the device", i);
             const uint64_t floats = state_floats_of(sg[i], sg[i].n);
-            if (to.tier == MLPO_TIER_HOST) {
+            if (to.tier != MLPO_TIER_FILE) {
                 if (to.state == nullptr || misaligned(to.state, 256))
                     return fail(MLPO_EINVAL, "flush target %d: state is NULL or not 256-byte aligned", i);
-                if (host_tier(sg[i].tier) && to.state < sg[i].p + floats && sg[i].p < to.state + floats)
+                if (sg[i].tier != MLPO_TIER_FILE && to.state < sg[i].p + floats && sg[i].p < to.state + floats)
                     return fail(MLPO_EINVAL, "flush target %d overlaps the subgroup's current state", i);
             } else {
                 any_bounce = true;
@@ -384,7 +390,8 @@ static const mlpo_flush_target* flush_target(const mlpo_stream_cfg* cfg, int32_t
 // bounce buffer because their state comes from a file, goes to a file, or both (jobs; job i uses bounce buffer
 // i mod file_slots).  A subgroup that changes its path does so at no extra cost: pinned -> file has no read side
 // (the kernel reads the pinned state and stores into the bounce buffer), file -> pinned has no write side (the
-// kernel stores straight into the pinned destination).
+// kernel stores straight into the pinned destination).  HBM is a source or a destination like pinned memory: a
+// subgroup that enters or leaves it crosses the link once instead of twice.
 struct LinkWork {
     std::vector<SgView> host_pieces;
     std::vector<FileJob> jobs;
@@ -658,8 +665,10 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
         const int32_t i = order ? order[k] : k;
         if (sg[i].n == 0) continue;
         const SgView v{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems};
-        if (sg[i].tier == MLPO_TIER_HBM) {
+        if (sg[i].tier == MLPO_TIER_HBM && flush_target(cfg, i) == nullptr) {
             plan.resident.push_back(v);
+        } else if (sg[i].tier == MLPO_TIER_HBM) {
+            plan.offloaded_ids.push_back(i);  // leaves HBM: its stores go over the link, so it runs with the link's pieces
         } else if (sg[i].tier == MLPO_TIER_FILE) {
             plan.file_ids.push_back(i);
             plan.offloaded_ids.push_back(i);

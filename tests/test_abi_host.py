@@ -336,7 +336,13 @@ def test_flush_target_argument_errors(tmp_path):
         planar = sg(n=n, tier=B.TIER_HOST)
         expect(B.MLPO_EINVAL, B.mlpo_stream_update, [planar], None, hp, 1, None, cfg(other))            # planar layout
         hbm = B.tiled_subgroup(FAKE_PAGE, FAKE, FAKE + (1 << 20), n=n, tier=B.TIER_HBM, tile_elems=T)
-        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hbm], None, hp, 1, None, cfg(other))               # not offloaded
+        to_hbm = B.FlushTargetC(B.TIER_HBM, 0, other, B.FileExtentC(-1, 0, 0))
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hbm], None, hp, 1, None, cfg(to_hbm))              # HBM to HBM
+        host_g = B.tiled_subgroup(FAKE_PAGE, FAKE, FAKE + (1 << 20), n=n, tier=B.TIER_HOST_GRADS, tile_elems=T)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [host_g], None, hp, 1, None, cfg(to_hbm))           # gradients stay
+        hbm_planar = sg(n=n, tier=B.TIER_HBM)
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hbm_planar], None, hp, 1, None, cfg(other))        # planar layout
+        expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hbm], None, hp, 1, None, cfg(other, chunk_elems=T + 4))
         staged = B.stream_cfg(2, FAKE, 1 << 30, None, None, None, 0)
         staged._flush = B.flush_targets([other])
         staged.flush_to = staged._flush

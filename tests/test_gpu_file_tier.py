@@ -251,10 +251,10 @@ def test_io_threads_and_kinds_of_descriptors(oracle, tmp_path, threads, direct_i
 
 @pytest.mark.parametrize("chunk,file_slots,direct_io", [(0, 1, False), (8192, 3, True), (16_384, 2, False)])
 def test_subgroups_change_their_path_at_flush_time(oracle, tmp_path, chunk, file_slots, direct_io):
-    """Algorithm 1 assigns the path anew whenever a subgroup is flushed.  Every offloaded subgroup has two pinned
-    buffers and two file extents to live in; a schedule moves them around - pinned to file, file to pinned, pinned to
-    another pinned buffer, file to another extent, or not at all - while the updates go on.  After every step the
-    state is read from wherever it lives now and compared with the oracle's."""
+    """Algorithm 1 assigns the path anew whenever a subgroup is flushed.  Every subgroup has two device buffers, two
+    pinned buffers and two file extents to live in; a schedule moves them around - between pinned memory, the file
+    and HBM, to another buffer or extent of the same kind, or not at all - while the updates go on.  After every
+    step the state is read from wherever it lives now and compared with the oracle's."""
     ohp, ghp = hp_pair(oracle)
     T, n, n_sub = 2048, 90_001, 5
     wl = W.Workload("move", n_sub=n_sub, sub_elems=n, n_host=0, loss_scale=16.0, max_norm=0.1, steps=5)
@@ -271,48 +271,55 @@ def test_subgroups_change_their_path_at_flush_time(oracle, tmp_path, chunk, file
     plain = os.open(path, os.O_RDWR)          # the test's own reads and writes (no alignment rules)
     d = dev()
     pinned = [[torch.zeros(floats, dtype=torch.float32, pin_memory=True) for _ in range(2)] for _ in range(n_sub)]
+    device = [[torch.zeros(floats, dtype=torch.float32, device=d) for _ in range(2)] for _ in range(n_sub)]
     extent = [[(2 * k + j) * ext for j in range(2)] for k in range(n_sub)]
     g = [torch.from_numpy(s["g"].view(np.int16)).to(d) for s in host]
     p16 = [torch.from_numpy(s["p16"].view(np.int16)).to(d) for s in host]
-    hbm_state = torch.from_numpy(pack_tiled(host[4]["p"], host[4]["m"], host[4]["v"], T)).to(d)
-    # where each offloaded subgroup lives: ("host", j) or ("file", j); subgroup 4 stays in HBM
-    home = [("file", 0), ("host", 0), ("host", 1), ("file", 1)]
+    # where each subgroup lives: (kind, j) with kind "hbm", "host" or "file" and j the buffer / extent of that kind
+    home = [("file", 0), ("host", 0), ("host", 1), ("file", 1), ("hbm", 0)]
     for k, (kind, j) in enumerate(home):
         packed = pack_tiled(host[k]["p"], host[k]["m"], host[k]["v"], T)
         if kind == "host":
             pinned[k][j].copy_(torch.from_numpy(packed))
+        elif kind == "hbm":
+            device[k][j].copy_(torch.from_numpy(packed))
         else:
             os.pwrite(plain, packed.tobytes() + bytes(ext - packed.nbytes), extent[k][j])
     os.fsync(plain)
     schedule = [
-        [("host", 0), ("file", 0), ("host", 0), ("file", 0)],     # file->pinned, pinned->file, pinned->pinned', file->file'
-        [("host", 0), ("file", 0), ("host", 0), ("file", 0)],     # nobody moves
-        [("file", 1), ("host", 1), ("file", 0), ("host", 1)],     # everybody changes sides
-        [("file", 0), ("host", 0), ("file", 1), ("host", 0)],     # same kind, other buffer / extent
-        [("host", 1), ("host", 0), ("host", 0), ("host", 0)],     # all into pinned memory
+        # file->pinned, pinned->file, pinned->pinned', file->file', HBM->pinned
+        [("host", 0), ("file", 0), ("host", 0), ("file", 0), ("host", 0)],
+        # pinned->HBM, stays, pinned->HBM, stays, stays
+        [("hbm", 0), ("file", 0), ("hbm", 0), ("file", 0), ("host", 0)],
+        # HBM->file, file->HBM, HBM->file, file->pinned, pinned->file
+        [("file", 1), ("hbm", 1), ("file", 0), ("host", 1), ("file", 0)],
+        # file->file', stays in HBM, file->file', pinned->pinned', file->HBM
+        [("file", 0), ("hbm", 1), ("file", 1), ("host", 0), ("hbm", 0)],
+        # file->pinned, HBM->pinned, file->pinned, stays, stays in HBM
+        [("host", 1), ("host", 0), ("host", 0), ("host", 0), ("hbm", 0)],
     ]
 
     def table_and_files():
         descs, files = [], []
         for k, (kind, j) in enumerate(home):
-            if kind == "host":
-                descs.append(B.tiled_subgroup(pinned[k][j], g[k], p16[k], n=n, tier=B.TIER_HOST, tile_elems=T))
-                files.append(None)
-            else:
+            if kind == "file":
                 descs.append(B.SubgroupC(None, None, None, g[k].data_ptr(), p16[k].data_ptr(), n, B.TIER_FILE, T))
                 files.append((fd, extent[k][j]))
-        descs.append(B.tiled_subgroup(hbm_state, g[4], p16[4], n=n, tile_elems=T))
-        files.append(None)
+            else:
+                state, tier = (pinned[k][j], B.TIER_HOST) if kind == "host" else (device[k][j], B.TIER_HBM)
+                descs.append(B.tiled_subgroup(state, g[k], p16[k], n=n, tier=tier, tile_elems=T))
+                files.append(None)
         return B.SubgroupTable(descs), files
 
     def fetch(k):
         torch.cuda.synchronize()
-        if k == 4:
-            buf = hbm_state.cpu().numpy()
-        elif home[k][0] == "host":
-            buf = pinned[k][home[k][1]].numpy()
+        kind, j = home[k]
+        if kind == "hbm":
+            buf = device[k][j].cpu().numpy()
+        elif kind == "host":
+            buf = pinned[k][j].numpy()
         else:
-            buf = np.frombuffer(os.pread(plain, floats * 4, extent[k][home[k][1]]), dtype=np.float32)
+            buf = np.frombuffer(os.pread(plain, floats * 4, extent[k][j]), dtype=np.float32)
         p, m, v = unpack_tiled(buf, n, T)
         return {"p": p, "m": m, "v": v, "p16": p16[k].cpu().numpy().view(np.uint16).copy()}
 
@@ -327,15 +334,16 @@ def test_subgroups_change_their_path_at_flush_time(oracle, tmp_path, chunk, file
             table, files = table_and_files()
             new_home = schedule[s]
             targets = []
-            for k in range(4):
+            for k in range(n_sub):
+                kind, j = new_home[k]
                 if new_home[k] == home[k]:
                     targets.append(None)
-                elif new_home[k][0] == "host":
-                    pinned[k][new_home[k][1]].fill_(float("nan"))          # whatever was there must be overwritten
-                    targets.append(pinned[k][new_home[k][1]])
+                elif kind == "file":
+                    targets.append((fd, extent[k][j]))
                 else:
-                    targets.append((fd, extent[k][new_home[k][1]]))
-            targets.append(None)
+                    buf = pinned[k][j] if kind == "host" else device[k][j]
+                    buf.fill_(float("nan"))          # whatever was there must be overwritten
+                    targets.append(buf)
             need = B.mlpo_stream_bounce_bytes(table, file_slots, chunk, flush_to=targets)
             bounce = torch.empty(max(need, 4096), dtype=torch.uint8, pin_memory=True)
             cfg = B.direct_cfg(streams[0], streams[1], 20, chunk_elems=chunk, files=files, bounce=bounce,
@@ -348,12 +356,12 @@ def test_subgroups_change_their_path_at_flush_time(oracle, tmp_path, chunk, file
             assert B.mlpo_stream_update(table, None, ghp, s + 1, scratch.scalars, cfg) and ok_o
             streams[1].synchronize()
             assert scratch.read()["gmul"] == gmul_o
-            reads = sum(1 for k in range(4) if home[k][0] == "file")
-            writes = sum(1 for k in range(4) if new_home[k][0] == "file")
+            reads = sum(1 for k in range(n_sub) if home[k][0] == "file")
+            writes = sum(1 for k in range(n_sub) if new_home[k][0] == "file")
             assert cfg.stats.bytes_read == reads * floats * 4 and cfg.stats.bytes_written == writes * floats * 4
             home = list(new_home)
             for k in range(n_sub):
-                assert_state_parity(fetch(k), host[k], f"step {s} sg {k} now at {home[k] if k < 4 else 'hbm'}")
+                assert_state_parity(fetch(k), host[k], f"step {s} sg {k} now at {home[k]}")
     finally:
         torch.cuda.synchronize()
         os.close(fd)

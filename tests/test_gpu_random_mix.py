@@ -1,7 +1,7 @@
 """Seeded random scenarios for mlpo_stream_update: subgroups of random sizes (empty ones included) spread over every
 tier and both layouts in one table, random mode, slots, chunking, slot cache, order and thread counts, a non-finite
-gradient now and then, and in direct mode offloaded subgroups that are flushed to another place than they came from
-(Algorithm 1 assigns the path anew at every flush).  After every step every bit of state is compared with the oracle's (the paper's statement that
+gradient now and then, and in direct mode subgroups that are flushed to another place - pinned memory, the file, HBM -
+than they came from (Algorithm 1 assigns the path anew at every flush).  After every step every bit of state is compared with the oracle's (the paper's statement that
 order and partitioning do not change the result, Section 3.2 "Cache-Friendly Ordering", Section 4.1 "Runtime
 Configurations")."""
 import math
@@ -161,19 +161,25 @@ def test_random_scenario(oracle, tmp_path, seed):
             if direct:
                 targets = [None] * n_sub
                 for k, e in enumerate(keep):
-                    movable = e["n"] > 0 and e["T"] and e["tier"] != B.TIER_HBM
+                    movable = e["n"] > 0 and e["T"]
                     if not movable or rng.integers(0, 3) != 0:
                         continue
                     floats = B.mlpo_state_floats(e["n"], e["T"])
-                    if e["tier"] == B.TIER_HOST_GRADS or rng.integers(0, 2):
-                        st = torch.full((floats,), float("nan"), dtype=torch.float32, pin_memory=True)
-                        targets[k] = st
-                        moved[k] = {"state": st, "tier": e["tier"] if e["tier"] != B.TIER_FILE else B.TIER_HOST}
-                    else:
+                    kinds = {B.TIER_HBM: ["host", "file"], B.TIER_HOST_GRADS: ["host"]}.get(e["tier"],
+                                                                                           ["host", "file", "hbm"])
+                    kind = str(rng.choice(kinds))
+                    if kind == "file":
                         targets[k] = (fd, file_end)
                         moved[k] = {"off": file_end, "tier": B.TIER_FILE}
                         file_end += (floats * 4 + 4095) // 4096 * 4096
                         os.ftruncate(fd, file_end)
+                    else:
+                        st = torch.full((floats,), float("nan"), dtype=torch.float32,
+                                        **({"pin_memory": True} if kind == "host" else {"device": dev()}))
+                        targets[k] = st
+                        tier = B.TIER_HBM if kind == "hbm" else (
+                            B.TIER_HOST_GRADS if e["tier"] == B.TIER_HOST_GRADS else B.TIER_HOST)
+                        moved[k] = {"state": st, "tier": tier}
                 need = B.mlpo_stream_bounce_bytes(table, slots, chunk, flush_to=targets)
                 bounce = torch.empty(max(need, 4096), dtype=torch.uint8, pin_memory=True)
                 cfg = B.direct_cfg(streams[0], streams[1], blocks, chunk_elems=chunk, files=files, bounce=bounce,
