@@ -365,6 +365,12 @@ size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t f
  * Section 3.2).  With file-tier subgroups the call returns only when their state is back in the file; the rest is
  * enqueued as usual.
  *
+ * Flush targets (cfg->flush_to, direct mode; see mlpo_flush_target): a subgroup with a target is cut into pieces of
+ * chunk_elems like the others and runs on the link's stream; its kernel loads the old state from the old home and
+ * stores the new state at the new one.  A piece whose state comes from a file or goes to one passes through a bounce
+ * buffer and counts against file_slots; the call then returns when the file holds what goes there, while stores to
+ * pinned memory or HBM are complete when the compute stream has caught up, as for any other subgroup.
+ *
  *   order        host array, a permutation of 0..n_sg-1 giving the processing order, or NULL for ascending.
  *   scalars      device pointer or NULL, as for mlpo_adamw_step.  When given, the call first copies the record to the
  *                host (a 16-byte copy and a wait on the compute stream) because the transfers are issued from the
