@@ -9,7 +9,9 @@
 // traffic of the step.  The gradient is widened in registers and never stored (Section 3.2 "Delayed In-place
 // Mixed-Precision Gradient Conversion"); the half-precision parameters are produced by the same lane that wrote the
 // fp32 ones (Algorithm 1's downcast).  There is no reuse, so nothing is staged through LDS and the accesses carry
-// the non-temporal hint.
+// the non-temporal hint.  The grid-stride kernels also exist in an out-of-place form that stores the new p, m, v a
+// per-subgroup distance away from where it loaded the old ones: that is how a subgroup changes its home (another
+// pinned buffer, a bounce buffer bound for a file, HBM) while it is updated.
 //
 // Arithmetic: every operation is an individually rounded fp32 operation (no contraction into fused multiply-add,
 // IEEE division and square root, denormals kept) so that results can be compared bit for bit with a plain CPU
@@ -467,7 +469,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
     VecBatch vb;
     vb.n_sg = 0;
     vb.tile_begin[0] = 0;
-    StoreShift<true> shift;
+    StoreShift<true> shift{};
     const StoreShift<true>* shift_arg = moves ? &shift : nullptr;
     ScalarBatch sb;
     sb.n_sg = 0;
