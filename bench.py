@@ -56,9 +56,14 @@ def resident_setup(args, torch, B, W, np, wl, tile):
     g_flat = torch.empty(N, dtype=torch.int16, device=d)
     p16_flat = torch.zeros(N, dtype=torch.int16, device=d)
     if tile:
-        per = B.mlpo_state_floats(M, tile)
-        state = torch.zeros(per * wl.n_sub, dtype=torch.float32, device=d)
-        pad = torch.zeros(per // 3, dtype=torch.float32, device=d)
+        # every subgroup starts `lead` slots into its tiled buffer, so that the 128-byte lines of its slices of the
+        # flat g / p16 arrays begin at the same elements as the lines of p, m, v
+        leads = [B.line_lead(p16_flat[k * M:(k + 1) * M]) if args.lead else 0 for k in range(wl.n_sub)]
+        floats = [B.mlpo_state_floats(M + lead, tile) for lead in leads]
+        starts = [sum(floats[:k]) for k in range(wl.n_sub)]
+        state = torch.zeros(sum(floats), dtype=torch.float32, device=d)
+        p_dev = torch.zeros(M, dtype=torch.float32, device=d)
+        zeros = torch.zeros(M, dtype=torch.float32, device=d)
     else:
         flat = {k: torch.zeros(N, dtype=torch.float32, device=d) for k in ("p", "m", "v")}
     hp_ = np.empty(M, np.float32)
@@ -70,16 +75,17 @@ def resident_setup(args, torch, B, W, np, wl, tile):
         gk, hk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
         gk.copy_(torch.from_numpy(hg_.view(np.int16)))
         if tile:
-            sk = state[k * per:(k + 1) * per]
-            pad[:M].copy_(torch.from_numpy(hp_))
-            sk.view(-1, 3, tile)[:, 0, :].copy_(pad.view(-1, tile))      # p into its slots of the tiled buffer
-            sgs.append(B.tiled_subgroup(sk, gk, hk, n=M, tile_elems=tile, half=args.half_format))
+            sk = state[starts[k]:starts[k] + floats[k]]
+            p_dev.copy_(torch.from_numpy(hp_))
+            B.mlpo_state_pack(p_dev, zeros, zeros, M, tile, sk, lead=leads[k])    # p into its slots, m = v = 0
+            sgs.append(B.tiled_subgroup(sk, gk, hk, n=M, tile_elems=tile, half=args.half_format, lead=leads[k]))
         else:
             flat["p"][k * M:(k + 1) * M].copy_(torch.from_numpy(hp_))
             sgs.append(B.subgroup(*(flat[key][k * M:(k + 1) * M] for key in ("p", "m", "v")), gk, hk, n=M,
                                   half=args.half_format))
     return {"table": B.SubgroupTable(sgs), "g_flat": g_flat, "p16_flat": p16_flat,
-            "params": state if tile else flat["p"], "keep": (state, pad) if tile else flat}
+            "params": state if tile else flat["p"], "keep": (state, p_dev, zeros) if tile else flat,
+            "leads": leads if tile else None}
 
 
 def resident_timed_steps(args, torch, B, wl, buf, scal, ws):
@@ -155,6 +161,7 @@ def resident_bench(args, torch, B, W, np, tile):
     achieved = BYTES_PER_PARAM_STEP * N / (k_avg * 1e-3) / 1e9
     out = {
         "layout": layout,
+        "lead": buf["leads"],
         "value": round(applied_timed * N / (elapsed_ms * 1e-3) / 1e9, 3),
         "ms_per_step": round(elapsed_ms / args.steps, 5),
         "applied_steps": applied_timed,
@@ -191,6 +198,7 @@ def resident_result(args, wl, primary, others):
         "config": {"workload": wl.name, "params": wl.n_total, "subgroups": wl.n_sub, "subgroup_elems": wl.sub_elems,
                    "loss_scale": wl.loss_scale, "inf_every": wl.inject_every,
                    "applied_steps": primary["applied_steps"], "state_layout": primary["layout"],
+                   "state_lead_elems": primary["lead"],
                    "state": f"fp32 p/m/v + {args.half} grads + {args.half} params, all in HBM"},
         "roofline": primary["roofline"],
         "norm_pass": primary["norm_pass"],
@@ -787,6 +795,9 @@ def main():
     ap.add_argument("--layout", default="both", choices=["tiled", "planar", "both"],
                     help="fp32 state layout(s) to time; the first is the headline figure")
     ap.add_argument("--tile", type=int, default=8192, help="tile_elems of the tiled layout")
+    ap.add_argument("--no-lead", dest="lead", action="store_false",
+                    help="tiled layout: start every subgroup at the beginning of its state buffer instead of "
+                         "shifting it until the lines of its g / p16 slices coincide with those of p, m, v")
     ap.add_argument("--half", default="bf16", choices=["bf16", "fp16"],
                     help="format of gradients and working parameters in the resident run (the workloads are bf16; "
                          "fp16 reads the same generated bit patterns as fp16 values, for timing)")

@@ -98,22 +98,33 @@ typedef struct {
     int32_t tier;
     int32_t tile_elems;
     int32_t half_format; /* MLPO_HALF_BF16 (0) or MLPO_HALF_FP16 */
-    int32_t reserved;    /* must be 0 */
+    int32_t lead;        /* 0, or see below (HBM tier, tiled layout) */
 } mlpo_subgroup;
+/* lead: the subgroup's elements start `lead` slots into the tiled buffer instead of at its beginning: x[i] lives at
+ * X + ((i + lead) / T) * 3T + ((i + lead) % T), the first `lead` slots of p, m and v are padding that is never read
+ * or written, and the buffer holds mlpo_state_floats(n + lead, T) floats.  g and p16 still point at the subgroup's
+ * first value.  A multiple of 4 below 1024.  Why: g and p16 are slices of the caller's flat arrays and start wherever
+ * the subgroup boundaries fall, rarely on a 128-byte line, while the state buffer is aligned; every workgroup's piece
+ * of g and p16 then straddles lines that it shares with its neighbours, which costs about 3 % of the update's
+ * speed.  With lead = (address of p16 / 2) mod 64 the lines of p16 (and of g, if it is cut the same way) begin at
+ * the same elements as the lines of p, m, v.  Accepted for MLPO_TIER_HBM subgroups only - the offloaded tiers are
+ * bound by the link - and such a subgroup cannot be given a flush target. */
 
 /* Floats in the state buffer of a tiled subgroup: ceil(n / tile_elems) * 3 * tile_elems (3 * n if tile_elems is 0). */
 uint64_t mlpo_state_floats(uint64_t n, int32_t tile_elems);
 
 /*
  * Conversion between the two layouts (for state that arrives planar, e.g. from a checkpoint, or has to leave that
- * way).  mlpo_state_pack writes the tiled buffer `state` (mlpo_state_floats(n, tile_elems) floats; the unused tail of
- * the last tile is set to zero) from three arrays of n floats; mlpo_state_unpack does the reverse.  All pointers must
- * be addressable by the device (device memory or pinned host memory) and 4-byte aligned; source and destination must
- * not overlap.  One kernel on `stream`.  Errors: MLPO_EINVAL, MLPO_EHIP.
+ * way).  mlpo_state_pack writes the tiled buffer `state` (mlpo_state_floats(n + lead, tile_elems) floats; the padding
+ * in front and the unused tail of the last tile are set to zero) from three arrays of n floats; mlpo_state_unpack
+ * does the reverse.  lead as in mlpo_subgroup (0 for a subgroup without padding).  All pointers must be addressable
+ * by the device (device memory or pinned host memory) and 4-byte aligned; source and destination must not overlap.
+ * One kernel on `stream`.  Errors: MLPO_EINVAL, MLPO_EHIP.
  */
-int mlpo_state_pack(const float* p, const float* m, const float* v, uint64_t n, int32_t tile_elems, float* state,
-                    void* stream);
-int mlpo_state_unpack(const float* state, uint64_t n, int32_t tile_elems, float* p, float* m, float* v, void* stream);
+int mlpo_state_pack(const float* p, const float* m, const float* v, uint64_t n, int32_t tile_elems, int32_t lead,
+                    float* state, void* stream);
+int mlpo_state_unpack(const float* state, uint64_t n, int32_t tile_elems, int32_t lead, float* p, float* m, float* v,
+                      void* stream);
 
 /* The four scalars that link the gradient pass to the update, kept in device memory so that no host round trip is
  * needed between the two (16 bytes, 16-byte aligned). */

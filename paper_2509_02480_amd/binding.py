@@ -43,7 +43,7 @@ class HParamsC(C.Structure):
 class SubgroupC(C.Structure):
     _fields_ = [("p", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p), ("g", C.c_void_p), ("p16", C.c_void_p),
                 ("n", C.c_uint64), ("tier", C.c_int32), ("tile_elems", C.c_int32), ("half_format", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("lead", C.c_int32)]
 
 
 class StepScalarsC(C.Structure):
@@ -122,10 +122,11 @@ def lib():
         L.mlpo_state_floats.restype = C.c_uint64
         L.mlpo_state_floats.argtypes = [C.c_uint64, C.c_int32]
         L.mlpo_state_pack.restype = C.c_int
-        L.mlpo_state_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.mlpo_state_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_void_p]
         L.mlpo_state_unpack.restype = C.c_int
-        L.mlpo_state_unpack.argtypes = [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
-                                        C.c_void_p]
+        L.mlpo_state_unpack.argtypes = [C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p]
         L.mlpo_norm_workspace_bytes.restype = C.c_size_t
         L.mlpo_norm_workspace_bytes.argtypes = []
         L.mlpo_grad_unscale_norm.restype = C.c_int
@@ -194,25 +195,30 @@ def subgroup(p, m, v, g, p16, n: Optional[int] = None, tier: int = TIER_HBM, til
 
 
 def tiled_subgroup(state, g, p16, n: Optional[int] = None, tier: int = TIER_HBM,
-                   tile_elems: int = TILE_DEFAULT, half: int = HALF_BF16) -> SubgroupC:
+                   tile_elems: int = TILE_DEFAULT, half: int = HALF_BF16, lead: int = 0) -> SubgroupC:
     """Descriptor of a subgroup whose fp32 state is one tiled buffer (see mlpo.h): m and v follow from ``state``."""
     if n is None:
         n = g.numel()
     base = _ptr(state)
     return SubgroupC(base, base + 4 * tile_elems, base + 8 * tile_elems, _ptr(g), _ptr(p16), int(n), int(tier),
-                     int(tile_elems), int(half), 0)
+                     int(tile_elems), int(half), int(lead))
+
+
+def line_lead(p16) -> int:
+    """The ``lead`` that makes the 128-byte lines of p16 begin at the same elements as those of the state buffer."""
+    return (_ptr(p16) // 2) % 64
 
 
 def mlpo_state_floats(n: int, tile_elems: int) -> int:
     return int(lib().mlpo_state_floats(n, tile_elems))
 
 
-def mlpo_state_pack(p, m, v, n: int, tile_elems: int, state, stream=None) -> None:
-    _check(lib().mlpo_state_pack(_ptr(p), _ptr(m), _ptr(v), n, tile_elems, _ptr(state), _stream(stream)))
+def mlpo_state_pack(p, m, v, n: int, tile_elems: int, state, stream=None, lead: int = 0) -> None:
+    _check(lib().mlpo_state_pack(_ptr(p), _ptr(m), _ptr(v), n, tile_elems, lead, _ptr(state), _stream(stream)))
 
 
-def mlpo_state_unpack(state, n: int, tile_elems: int, p, m, v, stream=None) -> None:
-    _check(lib().mlpo_state_unpack(_ptr(state), n, tile_elems, _ptr(p), _ptr(m), _ptr(v), _stream(stream)))
+def mlpo_state_unpack(state, n: int, tile_elems: int, p, m, v, stream=None, lead: int = 0) -> None:
+    _check(lib().mlpo_state_unpack(_ptr(state), n, tile_elems, lead, _ptr(p), _ptr(m), _ptr(v), _stream(stream)))
 
 
 class SubgroupTable:

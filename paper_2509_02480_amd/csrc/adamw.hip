@@ -46,7 +46,7 @@ struct VecView {
     uint32_t head4;
     uint32_t tiles_per_T;  // 0: planar.  Else kernel tiles per layout tile (tiled state, head4 == 0)
     uint32_t S4;           // tiled: distance between layout tiles of one array, in groups of four
-    uint32_t pad;
+    uint32_t lead4;        // tiled: groups of padding at the front of the first tile (nothing is read or written there)
 };
 struct VecBatch {
     VecView sg[kMaxSg];
@@ -163,7 +163,9 @@ struct Tile {
     const u32x2* g;
     u32x2* h;
     int64_t out4;  // MOVE only: store offset of p, m, v relative to their load addresses, in groups of four
-    uint32_t cnt;  // groups of four in this tile
+    uint32_t cnt;  // groups of four in this tile: lanes work on groups lo <= i < cnt
+    uint32_t lo;   // 0 except in the first tile of a subgroup with padding in front
+    bool full;     // every lane of every pass has a group
 };
 
 template <int T4, bool MOVE>
@@ -196,6 +198,8 @@ __device__ __forceinline__ Tile locate(const VecBatch& b, const StoreShift<MOVE>
     t.out4 = 0;
     if constexpr (MOVE) t.out4 = shift.out4[s];
     t.cnt = left < (uint64_t)T4 ? (uint32_t)left : (uint32_t)T4;
+    t.lo = t_in == 0u ? d.lead4 : 0u;
+    t.full = t.cnt == (uint32_t)T4 && t.lo == 0u;
     return t;
 }
 
@@ -206,7 +210,7 @@ struct Regs {
     u32x2 G[UNROLL];
 
     __device__ __forceinline__ void load(const Tile& t, uint32_t tid) {
-        if (t.cnt == BLOCK * UNROLL) {
+        if (t.full) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
@@ -219,7 +223,7 @@ struct Regs {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
-                if (i < t.cnt) {
+                if (i >= t.lo && i < t.cnt) {
                     P[u] = ld<NT>(t.p + i);
                     M[u] = ld<NT>(t.m + i);
                     V[u] = ld<NT>(t.v + i);
@@ -239,7 +243,7 @@ struct Regs {
     template <int HALF>
     __device__ __forceinline__ void update_store_as(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
         const auto out = [&t](f32x4* q) { return MOVE ? q + t.out4 : q; };
-        if (t.cnt == BLOCK * UNROLL) {
+        if (t.full) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
@@ -253,7 +257,7 @@ struct Regs {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
-                if (i < t.cnt) {
+                if (i >= t.lo && i < t.cnt) {
                     const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
                     st<NT>(out(t.p) + i, P[u]);
                     st<NT>(out(t.m) + i, M[u]);
@@ -335,7 +339,7 @@ __global__ void __launch_bounds__(kBlock1) adamw_v1_kernel(const ScalarBatch b, 
 #pragma unroll
     for (int u = 0; u < kUnroll1; ++u) {
         const uint64_t j = base + (uint32_t)(u * kBlock1) + threadIdx.x;
-        if (j < d.n) {
+        if (j >= d.lead && j < d.n) {
             float pp = d.p[j], mm = d.m[j], vv = d.v[j];
             if (c.half == 0)
                 d.p16[j] = (uint16_t)update_one<0>(pp, mm, vv, widen_low<0>(d.g[j]), gmul, c);
@@ -350,7 +354,8 @@ __global__ void __launch_bounds__(kBlock1) adamw_v1_kernel(const ScalarBatch b, 
 
 bool vec_aligned(const SgView& s) {
     auto a = [](const void* q) { return reinterpret_cast<uintptr_t>(q); };
-    return ((a(s.p) | a(s.m) | a(s.v)) & 15u) == 0 && ((a(s.g) | a(s.p16)) & 7u) == 0 && s.out_delta % 4 == 0;
+    return ((a(s.p) | a(s.m) | a(s.v)) & 15u) == 0 && ((a(s.g) | a(s.p16)) & 7u) == 0 && s.out_delta % 4 == 0 &&
+           s.lead % 4 == 0;
 }
 
 struct Variant {
@@ -527,7 +532,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         d.head4 = (uint32_t)head4;
         d.tiles_per_T = s.tile_elems != 0 ? (uint32_t)((uint64_t)s.tile_elems / 4 / t4) : 0u;
         d.S4 = s.tile_elems != 0 ? (uint32_t)(3u * (uint64_t)s.tile_elems / 4) : 0u;
-        d.pad = 0;
+        d.lead4 = s.lead / 4;
         shift.out4[vb.n_sg] = s.out_delta / 4;
         vb.tile_begin[vb.n_sg + 1] = vb.tile_begin[vb.n_sg] + (uint32_t)tiles;
         ++vb.n_sg;

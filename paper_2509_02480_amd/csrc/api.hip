@@ -155,13 +155,16 @@ int validate_subgroups(const mlpo_subgroup* sg, int32_t n_sg, bool grads_only, i
             return fail(MLPO_EINVAL, "subgroup %d: unknown half format %d", i, s.half_format);
         if (s.half_format != sg[0].half_format)
             return fail(MLPO_EINVAL, "subgroup %d: all subgroups of a call must share one half format", i);
-        if (s.reserved != 0) return fail(MLPO_EINVAL, "subgroup %d: reserved field is not 0", i);
+        if (s.lead < 0 || s.lead >= 1024 || s.lead % 4 != 0)
+            return fail(MLPO_EINVAL, "subgroup %d: lead must be a multiple of 4 in 0..1020 (got %d)", i, s.lead);
         if (s.n > ((uint64_t)1 << 48)) return fail(MLPO_EINVAL, "subgroup %d: n is implausibly large", i);
         if (s.n != 0 && s.g == nullptr) return fail(MLPO_EINVAL, "subgroup %d: g is NULL", i);
         if (misaligned(s.g, 2)) return fail(MLPO_EINVAL, "subgroup %d: g is not 2-byte aligned", i);
         if (grads_only) continue;
         if (s.tier != MLPO_TIER_HBM && !host_tier(s.tier) && s.tier != MLPO_TIER_FILE)
             return fail(MLPO_EINVAL, "subgroup %d: unknown tier %d", i, s.tier);
+        if (s.lead != 0 && (s.tier != MLPO_TIER_HBM || s.tile_elems <= 0))
+            return fail(MLPO_EINVAL, "subgroup %d: lead is for HBM-tier subgroups in the tiled layout", i);
         if (host_tier(s.tier) && allow_host < 1)
             return fail(MLPO_EINVAL, "subgroup %d is host-tier: use mlpo_stream_update", i);
         if (s.tier == MLPO_TIER_FILE) {
@@ -319,7 +322,7 @@ int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hpar
     if (n_sg == 0) return MLPO_OK;
     const AdamwConsts c = make_consts(*hp, step, table_half_format(sg, n_sg));
     std::vector<SgView> views((size_t)n_sg);
-    for (int32_t i = 0; i < n_sg; ++i) views[i] = SgView{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems};
+    for (int32_t i = 0; i < n_sg; ++i) views[i] = view_of(sg[i]);
     return launch_adamw(views.data(), n_sg, c, scalars, static_cast<hipStream_t>(stream));
 }
 

@@ -69,7 +69,24 @@ struct SgView {
     // Out-of-place update (tiled views only): the new p, m, v are stored out_delta floats behind where the old ones
     // were read, i.e. into another buffer of the same layout; 0 = in place.  A multiple of 4.
     int64_t out_delta = 0;
+    // Padding in front (tiled views only): the view's first `lead` elements are no elements of the subgroup, nothing
+    // is read or written for them (g and p16 point `lead` elements before the subgroup's first value, n counts the
+    // padding).  A multiple of 4, smaller than a kernel tile.  It lets the caller shift a subgroup inside its state
+    // buffer until the 128-byte lines of g and p16 and those of p, m, v begin at the same elements.
+    uint32_t lead = 0;
 };
+
+// The view of a whole subgroup as the caller describes it (mlpo_subgroup::lead applied).
+inline SgView view_of(const mlpo_subgroup& s) {
+    SgView v{s.p, s.m, s.v, s.g, s.p16, s.n, s.tile_elems};
+    if (s.lead > 0) {
+        v.g -= s.lead;
+        v.p16 -= s.lead;
+        v.n += (uint64_t)s.lead;
+        v.lead = (uint32_t)s.lead;
+    }
+    return v;
+}
 
 // Enqueues the fused update over `n` views (memory the device can address) on `stream`.  Views are split between
 // the 128-bit kernel and the element-wise kernel by alignment; any number of views is accepted (several launches if

@@ -295,6 +295,8 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
             if (!direct) return fail(MLPO_EINVAL, "flush targets need direct mode");
             if (sg[i].tile_elems <= 0)
                 return fail(MLPO_EINVAL, "flush target %d: only subgroups in the tiled layout can move", i);
+            if (sg[i].lead != 0)
+                return fail(MLPO_EINVAL, "flush target %d: a subgroup with lead cannot move", i);
             if (sg[i].tier == MLPO_TIER_HBM && to.tier == MLPO_TIER_HBM)
                 return fail(MLPO_EINVAL, "flush target %d: an HBM-tier subgroup can move to pinned memory or a file", i);
             if (sg[i].tier == MLPO_TIER_HOST_GRADS && to.tier == MLPO_TIER_HBM)
@@ -664,7 +666,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     for (int32_t k = 0; k < n_sg; ++k) {
         const int32_t i = order ? order[k] : k;
         if (sg[i].n == 0) continue;
-        const SgView v{sg[i].p, sg[i].m, sg[i].v, sg[i].g, sg[i].p16, sg[i].n, sg[i].tile_elems};
+        const SgView v = view_of(sg[i]);  // lead is 0 for everything but HBM-tier subgroups (checked)
         if (sg[i].tier == MLPO_TIER_HBM && flush_target(cfg, i) == nullptr) {
             plan.resident.push_back(v);
         } else if (sg[i].tier == MLPO_TIER_HBM) {

@@ -74,22 +74,23 @@ class Scratch:
                 "found_inf": int(h[3:4].view(np.uint32)[0])}
 
 
-def pack_tiled(p, m, v, T):
-    """The tiled state buffer of mlpo.h from three planar arrays (data movement only)."""
-    n = p.size
+def pack_tiled(p, m, v, T, lead=0):
+    """The tiled state buffer of mlpo.h from three planar arrays (data movement only); ``lead`` slots of padding in
+    front."""
+    n = p.size + lead
     nt = (n + T - 1) // T
     buf = np.zeros((nt, 3, T), np.float32)
     for j, a in enumerate((p, m, v)):
         pad = np.zeros(nt * T, np.float32)
-        pad[:n] = a
+        pad[lead:n] = a
         buf[:, j, :] = pad.reshape(nt, T)
     return buf.reshape(-1)
 
 
-def unpack_tiled(buf, n, T):
-    nt = (n + T - 1) // T
+def unpack_tiled(buf, n, T, lead=0):
+    nt = (n + lead + T - 1) // T
     b = np.asarray(buf).reshape(nt, 3, T)
-    return tuple(b[:, j, :].reshape(-1)[:n].copy() for j in range(3))
+    return tuple(b[:, j, :].reshape(-1)[lead:lead + n].copy() for j in range(3))
 
 
 class DeviceSubgroups:

@@ -36,7 +36,7 @@ def sg(n=8, tier=0, **kw):
     d = dict(p=FAKE, m=FAKE + 4096, v=FAKE + 8192, g=FAKE + 12288, p16=FAKE + 16384)
     d.update(kw)
     return B.SubgroupC(d["p"], d["m"], d["v"], d["g"], d["p16"], n, tier, d.get("tile_elems", 0),
-                       d.get("half_format", 0), d.get("reserved", 0))
+                       d.get("half_format", 0), d.get("lead", 0))
 
 
 def expect(code, fn, *a, **k):
@@ -296,7 +296,15 @@ def test_half_format_errors():
     assert B.lib().mlpo_adamw_step(None, 0, C.byref(bad), 1, None, None) == B.MLPO_EINVAL
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(half_format=2)], hp, 1)
     expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(), sg(half_format=B.HALF_FP16)], hp, 1)     # mixed formats
-    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(reserved=1)], hp, 1)
+    # lead: a multiple of 4 below 1024, tiled layout, HBM tier
+    tiled = dict(p=FAKE_PAGE, m=FAKE_PAGE + 4 * 1024, v=FAKE_PAGE + 8 * 1024, tile_elems=1024)
+    for bad_lead in (1, 2, -4, 1024, 4096):
+        expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(lead=bad_lead, **tiled)], hp, 1)
+    expect(B.MLPO_EINVAL, B.mlpo_adamw_step, [sg(lead=8)], hp, 1)                               # planar
+    expect(B.MLPO_EINVAL, B.mlpo_stream_update, [sg(lead=8, tier=B.TIER_HOST, **tiled)], None, hp, 1, None,
+           B.direct_cfg(None, None, 8))                                                         # not HBM-tier
+    expect(B.MLPO_EINVAL, B.mlpo_state_pack, FAKE, FAKE, FAKE, 10, 1024, FAKE, lead=2)
+    expect(B.MLPO_EINVAL, B.mlpo_state_unpack, FAKE, 10, 1024, FAKE, FAKE, FAKE, lead=1024)
     expect(B.MLPO_EINVAL, B.mlpo_grad_unscale_norm, [sg(half_format=-1)], 1.0, 0.0, FAKE, B.mlpo_norm_workspace_bytes(),
            FAKE)
     expect(B.MLPO_EINVAL, B.mlpo_grad_accumulate, FAKE, FAKE + 4096, 16, half=2)
