@@ -191,7 +191,10 @@ int launch(uint16_t* acc, const uint16_t* g, uint64_t n, int blocks, hipStream_t
         if (STATS) *n_partials = (int)grid;
         return MLPO_OK;
     }
-    uint64_t head = ((16u - (a_addr & 15u)) & 15u) / 2u;
+    // The vector body starts on a 128-byte line of acc, the array that is written: a workgroup's tile then owns whole
+    // lines (a line written in two halves by two workgroups costs more than the bytes say).  g + head is 16-byte
+    // aligned because the two addresses agree modulo 16.
+    uint64_t head = ((128u - (a_addr & 127u)) & 127u) / 2u;
     if (head > n) head = n;
     const uint64_t n8 = (n - head) / 8u;
     const uint64_t tail = n - head - n8 * 8u;
