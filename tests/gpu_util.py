@@ -101,8 +101,11 @@ class DeviceSubgroups:
     ``tiers[k] == 1`` puts p, m, v of subgroup k in pinned host memory.  ``tile`` > 0 stores the fp32 state of every
     subgroup in the tiled layout (one buffer per subgroup) instead of three planar arrays."""
 
-    def __init__(self, host_sgs, tiers=None, flat=True, elem_offset=0, tile=0, half=0):
+    def __init__(self, host_sgs, tiers=None, flat=True, elem_offset=0, tile=0, half=0, lead=False):
         self.half = half            # format of g and p16: B.HALF_BF16 or B.HALF_FP16
+        # tiled only: g and p16 are slices of two flat buffers and every subgroup starts `lead` slots into its state
+        # buffer, chosen so that the lines of its p16 slice and those of p, m, v begin at the same elements
+        self.lead = lead
         self.n_sg = len(host_sgs)
         self.tiers = list(tiers) if tiers is not None else [0] * self.n_sg
         self.sizes = [s["p"].size for s in host_sgs]
@@ -148,20 +151,35 @@ class DeviceSubgroups:
     def _init_tiled(self, host_sgs, d):
         T = self.tile
         descs = []
+        self.leads = []
+        if self.lead:
+            tot = sum(self.sizes)
+            self._keep = {k: torch.empty(tot, dtype=torch.int16, device=d) for k in ("g", "p16")}
+        off = 0
         for k, s in enumerate(host_sgs):
             n = self.sizes[k]
-            packed = torch.from_numpy(pack_tiled(s["p"], s["m"], s["v"], T))
-            assert packed.numel() == B.mlpo_state_floats(n, T)
+            ent = {}
+            for key in ("g", "p16"):
+                src = torch.from_numpy(s[key].view(np.int16))
+                if self.lead:
+                    ent[key] = self._keep[key][off:off + n]
+                    ent[key].copy_(src)
+                else:
+                    ent[key] = src.to(d)
+            off += n
+            lead = B.line_lead(ent["p16"]) if self.lead and n and self.tiers[k] == 0 else 0
+            self.leads.append(lead)
+            packed = torch.from_numpy(pack_tiled(s["p"], s["m"], s["v"], T, lead))
+            assert packed.numel() == B.mlpo_state_floats(n + lead, T)
             if self.tiers[k] == 1:
                 state = torch.empty(max(packed.numel(), 1), dtype=torch.float32, pin_memory=True)[:packed.numel()]
                 state.copy_(packed)
             else:
                 state = packed.to(d) if packed.numel() else torch.empty(0, dtype=torch.float32, device=d)
-            ent = {"state": state, "g": torch.from_numpy(s["g"].view(np.int16)).to(d),
-                   "p16": torch.from_numpy(s["p16"].view(np.int16)).to(d)}
+            ent["state"] = state
             self.t.append(ent)
             descs.append(B.tiled_subgroup(state, ent["g"], ent["p16"], n=n, tier=self.tiers[k], tile_elems=T,
-                                          half=self.half)
+                                          half=self.half, lead=lead)
                          if n else B.subgroup(0, 0, 0, 0, 0, n=0, tier=self.tiers[k], tile_elems=T, half=self.half))
         torch.cuda.synchronize()
         self.table = B.SubgroupTable(descs)
@@ -173,7 +191,7 @@ class DeviceSubgroups:
         torch.cuda.synchronize()
         e = self.t[k]
         if self.tile:
-            p, m, v = unpack_tiled(e["state"].cpu().numpy(), self.sizes[k], self.tile)
+            p, m, v = unpack_tiled(e["state"].cpu().numpy(), self.sizes[k], self.tile, self.leads[k])
             return {"p": p, "m": m, "v": v, "p16": from_dev_u16(e["p16"]).copy()}
         return {"p": e["p"].cpu().numpy().copy(), "m": e["m"].cpu().numpy().copy(), "v": e["v"].cpu().numpy().copy(),
                 "p16": from_dev_u16(e["p16"]).copy()}

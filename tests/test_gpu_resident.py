@@ -22,10 +22,11 @@ def scratch():
     return Scratch()
 
 
-def run_workload(oracle, scratch, wl, warm, flat=True, elem_offset=0, check_every_step=False, threads=8, tile=0):
+def run_workload(oracle, scratch, wl, warm, flat=True, elem_offset=0, check_every_step=False, threads=8, tile=0,
+                 lead=False):
     ohp, ghp = hp_pair(oracle, **wl.hp.__dict__)
     host = W.host_subgroups(wl, warm=warm, threads=threads)
-    ds = DeviceSubgroups(host, flat=flat, elem_offset=elem_offset, tile=tile)
+    ds = DeviceSubgroups(host, flat=flat, elem_offset=elem_offset, tile=tile, lead=lead)
     applied_o = applied_g = 0
     for s in range(wl.steps):
         if s > 0 and wl.fresh_grads:
@@ -65,20 +66,21 @@ def test_config1_three_steps(oracle, scratch, warm, tile):
     assert run_workload(oracle, scratch, W.C1, warm, check_every_step=True, tile=tile) == 3
 
 
-@pytest.mark.parametrize("tile", TILES)
-def test_config2_shape_small_with_inf_injection(oracle, scratch, tile):
+@pytest.mark.parametrize("tile,lead", [(t, False) for t in TILES] + [(B.TILE_DEFAULT, True), (1024, True)])
+def test_config2_shape_small_with_inf_injection(oracle, scratch, tile, lead):
     # config 2's structure at 1/25 of its size: 16 slices of one flat buffer whose length is a multiple of 4 but not
     # of 8 (odd slices start 8-byte- but not 16-byte-aligned in bf16), loss scale 1024, +inf on the fifth step
     wl = W.Workload("C2/25", n_sub=16, sub_elems=312_500, loss_scale=1024.0, steps=10, inject_every=50)
     assert wl.sub_elems % 4 == 0 and wl.sub_elems % 8 != 0
-    assert run_workload(oracle, scratch, wl, warm=False, check_every_step=True, tile=tile) == 9
+    assert run_workload(oracle, scratch, wl, warm=False, check_every_step=True, tile=tile, lead=lead) == 9
 
 
-@pytest.mark.parametrize("tile", [0, B.TILE_DEFAULT])
-def test_config2_full_size(oracle, scratch, tile):
-    # the benchmark workload itself in both layouts the benchmark times, every element compared after the last step
-    # and around the skipped step
-    assert run_workload(oracle, scratch, W.C2, warm=False, threads=16, tile=tile) == 9
+@pytest.mark.parametrize("tile,lead", [(0, False), (B.TILE_DEFAULT, False), (B.TILE_DEFAULT, True)])
+def test_config2_full_size(oracle, scratch, tile, lead):
+    # the benchmark workload itself in the layouts the benchmark times (the tiled one as the benchmark sets it up:
+    # g and p16 cut from flat buffers, every subgroup shifted by its lead), every element compared after the last
+    # step and around the skipped step
+    assert run_workload(oracle, scratch, W.C2, warm=False, threads=16, tile=tile, lead=lead) == 9
 
 
 @pytest.mark.parametrize("n", [0, 1, 2, 3, 4, 5, 7, 8, 63, 64, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096,
