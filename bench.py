@@ -156,7 +156,9 @@ def resident_bench(args, torch, B, W, np, tile):
     assert len(upd_ms) == args.steps and len(nrm_ms) == args.steps, (len(upd_ms), len(nrm_ms))
     inj_timed = [wl.injects(s) for s in range(args.warmup, total)]
     k_ms = [upd_ms[i] for i in range(args.steps) if not inj_timed[i]]   # a skipped step's launch exits at once
-    k_avg = sum(k_ms) / max(len(k_ms), 1)
+    if not k_ms:        # every timed step was one with an injected inf (a run of very few steps)
+        raise SystemExit("bench.py: no timed step applied an update; use more --steps")
+    k_avg = sum(k_ms) / len(k_ms)
     n_avg = sum(nrm_ms) / len(nrm_ms)
     achieved = BYTES_PER_PARAM_STEP * N / (k_avg * 1e-3) / 1e9
     out = {
