@@ -683,7 +683,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
 
     EventCache& ec = events();
     std::lock_guard<std::mutex> lk(ec.mu);
-    if (plan.host_ids.empty() && plan.file_ids.empty()) {  // nothing offloaded: this is mlpo_adamw_step
+    if (plan.offloaded_ids.empty()) {  // nothing offloaded and nothing on its way out of HBM: this is mlpo_adamw_step
         if (plan.resident.empty()) return MLPO_OK;
         return launch_adamw(plan.resident.data(), (int)plan.resident.size(), c, scalars, st.cmp);
     }

@@ -366,3 +366,46 @@ def test_subgroups_change_their_path_at_flush_time(oracle, tmp_path, chunk, file
         torch.cuda.synchronize()
         os.close(fd)
         os.close(plain)
+
+
+@pytest.mark.parametrize("n", [3, 4, 7, 5000, 70_001])
+def test_hbm_only_table_with_subgroups_on_their_way_out(oracle, tmp_path, n):
+    """Nothing is offloaded yet: three HBM-tier subgroups, of which one goes to pinned memory and one to a file in
+    this step.  (A table without host- or file-tier subgroups takes a shortcut to the resident kernel; subgroups that
+    leave HBM must not take it.)"""
+    ohp, ghp = hp_pair(oracle)
+    T = 2048
+    wl = W.Workload("out", n_sub=3, sub_elems=n, n_host=0, steps=2, seed=n)
+    host = W.host_subgroups(wl, warm=True)
+    floats = B.mlpo_state_floats(n, T)
+    path = str(tmp_path / "state.bin")
+    with open(path, "wb") as f:
+        f.truncate(floats * 4)
+    fd = os.open(path, os.O_RDWR)
+    d = dev()
+    state = [torch.from_numpy(pack_tiled(s["p"], s["m"], s["v"], T)).to(d) for s in host]
+    g = [torch.from_numpy(s["g"].view(np.int16)).to(d) for s in host]
+    p16 = [torch.from_numpy(s["p16"].view(np.int16)).to(d) for s in host]
+    table = B.SubgroupTable([B.tiled_subgroup(state[k], g[k], p16[k], n=n, tile_elems=T) for k in range(3)])
+    pinned = torch.full((floats,), float("nan"), dtype=torch.float32, pin_memory=True)
+    targets = [pinned, None, (fd, 0)]
+    need = B.mlpo_stream_bounce_bytes(table, 2, 0, flush_to=targets)
+    bounce = torch.empty(need, dtype=torch.uint8, pin_memory=True)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    cfg = B.direct_cfg(streams[0], streams[1], 8, bounce=bounce, bounce_bytes=need, file_slots=2, flush_to=targets,
+                       want_file_stats=True)
+    try:
+        oracle.step(host, ohp, 0, 1.0, 0.0)
+        assert B.mlpo_stream_update(table, None, ghp, 1, None, cfg)
+        streams[1].synchronize()
+        torch.cuda.synchronize()
+        assert cfg.stats.bytes_read == 0 and cfg.stats.bytes_written == floats * 4
+        homes = [pinned.numpy(), state[1].cpu().numpy(),
+                 np.frombuffer(os.pread(fd, floats * 4, 0), dtype=np.float32)]
+        for k in range(3):
+            p, m, v = unpack_tiled(homes[k], n, T)
+            got = {"p": p, "m": m, "v": v, "p16": p16[k].cpu().numpy().view(np.uint16).copy()}
+            assert_state_parity(got, host[k], f"n {n} sg {k}")
+    finally:
+        torch.cuda.synchronize()
+        os.close(fd)

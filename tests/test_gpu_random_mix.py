@@ -52,14 +52,17 @@ def build(rng, host, tiers, tiles, path, half):
         else:
             on_host = tier in (B.TIER_HOST, B.TIER_HOST_GRADS)
             if T:
-                packed = torch.from_numpy(pack_tiled(s["p"], s["m"], s["v"], T))
+                # HBM-tier subgroups may start a few slots into their state buffer
+                lead = int(rng.choice([0, 0, 4, 60, 1020])) if tier == B.TIER_HBM else 0
+                ent["lead"] = lead
+                packed = torch.from_numpy(pack_tiled(s["p"], s["m"], s["v"], T, lead))
                 if on_host:
                     st = torch.empty(packed.numel(), dtype=torch.float32, pin_memory=True)
                     st.copy_(packed)
                 else:
                     st = packed.to(d)
                 ent["state"] = st
-                descs.append(B.tiled_subgroup(st, g, p16, n=n, tier=tier, tile_elems=T, half=half))
+                descs.append(B.tiled_subgroup(st, g, p16, n=n, tier=tier, tile_elems=T, half=half, lead=lead))
             else:
                 arrs = []
                 for key in ("p", "m", "v"):
@@ -89,7 +92,7 @@ def build(rng, host, tiers, tiles, path, half):
             buf = np.frombuffer(os.pread(fd, B.mlpo_state_floats(n, T) * 4, e["off"]), dtype=np.float32)
             p, m, v = unpack_tiled(buf, n, T)
         elif T:
-            p, m, v = unpack_tiled(e["state"].cpu().numpy(), n, T)
+            p, m, v = unpack_tiled(e["state"].cpu().numpy(), n, T, e.get("lead", 0))
         else:
             p, m, v = (t.cpu().numpy().copy() for t in e["pmv"])
         return {"p": p, "m": m, "v": v, "p16": p16}
@@ -97,7 +100,7 @@ def build(rng, host, tiers, tiles, path, half):
     return descs, files, keep, fetch, fd, off
 
 
-@pytest.mark.parametrize("seed", range(64))
+@pytest.mark.parametrize("seed", range(160))
 def test_random_scenario(oracle, tmp_path, seed):
     rng = np.random.default_rng(1000 + seed)
     direct = bool(rng.integers(0, 2))
@@ -161,7 +164,7 @@ def test_random_scenario(oracle, tmp_path, seed):
             if direct:
                 targets = [None] * n_sub
                 for k, e in enumerate(keep):
-                    movable = e["n"] > 0 and e["T"]
+                    movable = e["n"] > 0 and e["T"] and not e.get("lead")
                     if not movable or rng.integers(0, 3) != 0:
                         continue
                     floats = B.mlpo_state_floats(e["n"], e["T"])
@@ -180,6 +183,10 @@ def test_random_scenario(oracle, tmp_path, seed):
                         tier = B.TIER_HBM if kind == "hbm" else (
                             B.TIER_HOST_GRADS if e["tier"] == B.TIER_HOST_GRADS else B.TIER_HOST)
                         moved[k] = {"state": st, "tier": tier}
+                if moved:
+                    print(f"  step {step}: " + ", ".join(
+                        f"sg {k} tier {keep[k]['tier']} -> {'file' if 'off' in v else 'tier ' + str(v['tier'])}"
+                        for k, v in moved.items()), flush=True)
                 need = B.mlpo_stream_bounce_bytes(table, slots, chunk, flush_to=targets)
                 bounce = torch.empty(max(need, 4096), dtype=torch.uint8, pin_memory=True)
                 cfg = B.direct_cfg(streams[0], streams[1], blocks, chunk_elems=chunk, files=files, bounce=bounce,
@@ -202,6 +209,7 @@ def test_random_scenario(oracle, tmp_path, seed):
                     e = keep[k]
                     e.pop("state", None)
                     e.pop("off", None)
+                    e["lead"] = 0
                     e.update(new)
                     if e["tier"] == B.TIER_FILE:
                         descs[k] = B.SubgroupC(None, None, None, e["g"].data_ptr(), e["p16"].data_ptr(), e["n"],
