@@ -100,7 +100,11 @@ def build(rng, host, tiers, tiles, path, half):
     return descs, files, keep, fetch, fd, off
 
 
-@pytest.mark.parametrize("seed", range(160))
+# MLPO_RANDOM_SEEDS=a:b runs that range of seeds instead (a wider sweep now and then)
+_lo, _, _hi = os.environ.get("MLPO_RANDOM_SEEDS", "0:160").partition(":")
+
+
+@pytest.mark.parametrize("seed", range(int(_lo), int(_hi)))
 def test_random_scenario(oracle, tmp_path, seed):
     rng = np.random.default_rng(1000 + seed)
     direct = bool(rng.integers(0, 2))
