@@ -56,10 +56,13 @@ def test_every_pattern_against_selected_addends(oracle):
                            for i in bad[:5]]
 
 
-@pytest.mark.parametrize("off_a,off_g", [(0, 0), (1, 1), (3, 3), (7, 7), (5, 13), (0, 1), (2, 7), (4, 0)])
-def test_alignment_phases(oracle, off_a, off_g):
-    n = 40_000
-    rng = np.random.default_rng(off_a * 16 + off_g)
+@pytest.mark.parametrize("n", [40_000, 10, 63, 64, 65, 130])
+@pytest.mark.parametrize("off_a,off_g", [(0, 0), (1, 1), (3, 3), (7, 7), (5, 13), (0, 1), (2, 7), (4, 0), (20, 20),
+                                         (33, 33), (63, 63), (40, 8), (17, 49), (8, 40)])
+def test_alignment_phases(oracle, off_a, off_g, n):
+    # the vector body starts at the first 128-byte line of acc (up to 63 elements further on) when acc and g agree
+    # modulo 16 bytes; everything else, and ranges that end before that line, go element by element
+    rng = np.random.default_rng(off_a * 64 + off_g + n)
     a, g = bits(rng, n), bits(rng, n)
     guard = 0x1234
     ba = torch.full((n + 64,), guard, dtype=torch.int16, device=dev())
@@ -190,6 +193,42 @@ def test_last_micro_batch_also_gives_the_norm(oracle, sizes, first, blocks, max_
         torch.cuda.synchronize()
         o = other.read()
         assert abs(float(o["norm"]) - float(sc["norm"])) <= 2e-7 * float(norm_o) and o["gmul"] == sc["gmul"]
+
+
+@pytest.mark.parametrize("base,blocks", [(20, 0), (1, 0), (36, 5)])
+def test_norm_pieces_cut_from_flat_buffers(oracle, base, blocks):
+    """The pieces of a step as consecutive slices of one flat accumulation buffer and one flat gradient buffer, so
+    that they begin in the middle of 128-byte lines (the vector body of each call starts at the next line)."""
+    sizes = [100_004, 65_556, 7_812, 31]
+    rng = np.random.default_rng(base)
+    inv_scale, max_norm = 1.0 / 64.0, 0.02
+    total = sum(sizes)
+    a_all = oracle.f32_to_bf16_rne((rng.standard_normal(total) * 0.3).astype(np.float32))
+    g_all = oracle.f32_to_bf16_rne((rng.standard_normal(total) * 0.3).astype(np.float32))
+    guard = 0x1234
+    flat_a = torch.full((base + total + 64,), guard, dtype=torch.int16, device=dev())
+    flat_g = torch.zeros(base + total + 64, dtype=torch.int16, device=dev())
+    flat_a[base:base + total].copy_(to_dev(a_all))
+    flat_g[base:base + total].copy_(to_dev(g_all))
+    scratch = Scratch()
+    off, accs = base, []
+    for j, n in enumerate(sizes):
+        B.mlpo_grad_accumulate_norm(flat_a[off:off + n], flat_g[off:off + n], n, False, blocks, inv_scale, scratch.ws,
+                                    scratch.ws_bytes, begin=(j == 0))
+        a = a_all[off - base:off - base + n].copy()
+        oracle.grad_accumulate(a, g_all[off - base:off - base + n], False)
+        accs.append(a)
+        off += n
+    B.mlpo_grad_norm_finish(scratch.ws, scratch.ws_bytes, inv_scale, max_norm, scratch.scalars)
+    torch.cuda.synchronize()
+    out = back(flat_a)
+    assert np.array_equal(out[base:base + total], np.concatenate(accs))
+    assert np.all(out[:base] == guard) and np.all(out[base + total:] == guard)
+    norm_o, coef_o, gmul_o, flag_o = _norm_of(oracle, accs, inv_scale, max_norm)
+    sc = scratch.read()
+    assert sc["found_inf"] == flag_o == 0
+    assert abs(float(sc["norm"]) - float(norm_o)) <= 1e-5 * float(norm_o)
+    assert sc["clip_coef"] == coef_o and sc["gmul"] == gmul_o
 
 
 def test_norm_of_exact_sums(oracle):
