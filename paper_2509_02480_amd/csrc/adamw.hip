@@ -8,8 +8,8 @@
 // gradients), three 16-byte stores and one 8-byte store (four bf16 parameters) - 28 bytes per element, the whole
 // traffic of the step.  The gradient is widened in registers and never stored (Section 3.2 "Delayed In-place
 // Mixed-Precision Gradient Conversion"); the half-precision parameters are produced by the same lane that wrote the
-// fp32 ones (Algorithm 1's downcast).  There is no reuse, so nothing is staged through LDS and the accesses carry
-// the non-temporal hint.  The grid-stride kernels also exist in an out-of-place form that stores the new p, m, v a
+// fp32 ones (Algorithm 1's downcast).  There is no reuse, so nothing is staged through LDS and all accesses but the
+// stores of the half-precision parameters carry the non-temporal hint.  The grid-stride kernels also exist in an out-of-place form that stores the new p, m, v a
 // per-subgroup distance away from where it loaded the old ones: that is how a subgroup changes its home (another
 // pinned buffer, a bounce buffer bound for a file, HBM) while it is updated.
 //
@@ -204,6 +204,9 @@ __device__ __forceinline__ Tile locate(const VecBatch& b, const StoreShift<MOVE>
 }
 
 // MOVE = false stores p, m, v where they were loaded from; MOVE = true stores them Tile::out4 groups further on.
+// The 128-bit accesses to p, m, v and the loads of g carry the non-temporal hint; the 64-bit stores of the
+// half-precision parameters do not: with the hint they cost 6 % of the kernel's speed (measured; the other three
+// combinations of hints on g and p16 are slower as well), without it the lines are put together in the cache.
 template <int BLOCK, int UNROLL, bool NT, bool MOVE>
 struct Regs {
     f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
@@ -251,7 +254,7 @@ struct Regs {
                 st<NT>(out(t.p) + i, P[u]);
                 st<NT>(out(t.m) + i, M[u]);
                 st<NT>(out(t.v) + i, V[u]);
-                st<NT>(t.h + i, H);
+                t.h[i] = H;  // no hint: see the note at Regs
             }
         } else {
 #pragma unroll
@@ -262,7 +265,7 @@ struct Regs {
                     st<NT>(out(t.p) + i, P[u]);
                     st<NT>(out(t.m) + i, M[u]);
                     st<NT>(out(t.v) + i, V[u]);
-                    st<NT>(t.h + i, H);
+                    t.h[i] = H;  // no hint: see the note at Regs
                 }
             }
         }
