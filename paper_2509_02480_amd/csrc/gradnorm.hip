@@ -24,10 +24,10 @@ constexpr uint32_t kTile = kBlock * 8 * kUnroll;  // body elements per tile
 constexpr int kMaxSg = 96;
 
 struct NormBatch {
-    const uint16_t* body[kMaxSg];  // 16-byte aligned start of the vector body
+    const uint16_t* body[kMaxSg];  // start of the vector body, on a 128-byte line
     uint64_t n_body[kMaxSg];       // elements from body to the end of the subgroup
     uint32_t tile_begin[kMaxSg + 1];
-    uint8_t head[kMaxSg];  // elements before body (0..7), handled by the first tile
+    uint8_t head[kMaxSg];  // elements before body (0..63), handled by the first tile
     int32_t n_sg;
     int32_t half;  // MLPO_HALF_BF16 or MLPO_HALF_FP16
 };
@@ -231,7 +231,8 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
         const uint64_t n = sg[i].n;
         if (n == 0) continue;
         const uintptr_t addr = reinterpret_cast<uintptr_t>(sg[i].g);
-        uint64_t head = ((16u - (addr & 15u)) & 15u) / 2u;
+        // the vector body starts on a 128-byte line: a wavefront's kilobyte then covers eight lines, not nine
+        uint64_t head = ((128u - (addr & 127u)) & 127u) / 2u;
         if (head > n) head = n;
         const uint64_t n_body = n - head;
         uint64_t tiles = (n_body + kTile - 1) / kTile;
