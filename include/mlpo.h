@@ -111,6 +111,10 @@ typedef struct {
  * elements as the lines of p, m, v.  Accepted for MLPO_TIER_HBM subgroups only - the offloaded tiers are
  * bound by the link - and such a subgroup cannot be given a flush target. */
 
+/* The lead that lines a subgroup's state up with its p16 array: (address of p16 / 2) mod 64.  A multiple of 4 when
+ * p16 is 8-byte aligned, as the tiled layout requires. */
+int32_t mlpo_line_lead(const void* p16);
+
 /* Floats in the state buffer of a tiled subgroup: ceil(n / tile_elems) * 3 * tile_elems (3 * n if tile_elems is 0). */
 uint64_t mlpo_state_floats(uint64_t n, int32_t tile_elems);
 

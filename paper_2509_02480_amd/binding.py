@@ -22,7 +22,8 @@ MAX_SLOTS = 64
 
 TILE_DEFAULT = 8192
 
-EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_state_floats", "mlpo_state_pack", "mlpo_state_unpack",
+EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_line_lead", "mlpo_state_floats", "mlpo_state_pack",
+           "mlpo_state_unpack",
            "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm",
            "mlpo_grad_norm_finish", "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_bounce_bytes",
            "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers", "mlpo_update_bandwidth", "mlpo_set_option",
@@ -119,6 +120,8 @@ def lib():
         L.mlpo_last_error.argtypes = []
         L.mlpo_version.restype = C.c_int32
         L.mlpo_version.argtypes = []
+        L.mlpo_line_lead.restype = C.c_int32
+        L.mlpo_line_lead.argtypes = [C.c_void_p]
         L.mlpo_state_floats.restype = C.c_uint64
         L.mlpo_state_floats.argtypes = [C.c_uint64, C.c_int32]
         L.mlpo_state_pack.restype = C.c_int
@@ -204,9 +207,12 @@ def tiled_subgroup(state, g, p16, n: Optional[int] = None, tier: int = TIER_HBM,
                      int(tile_elems), int(half), int(lead))
 
 
-def line_lead(p16) -> int:
+def mlpo_line_lead(p16) -> int:
     """The ``lead`` that makes the 128-byte lines of p16 begin at the same elements as those of the state buffer."""
-    return (_ptr(p16) // 2) % 64
+    return int(lib().mlpo_line_lead(_ptr(p16)))
+
+
+line_lead = mlpo_line_lead
 
 
 def mlpo_state_floats(n: int, tile_elems: int) -> int:

@@ -326,6 +326,10 @@ int mlpo_adamw_step(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_adamw_hpar
     return launch_adamw(views.data(), n_sg, c, scalars, static_cast<hipStream_t>(stream));
 }
 
+int32_t mlpo_line_lead(const void* p16) {
+    return (int32_t)((reinterpret_cast<uintptr_t>(p16) / 2u) % 64u);
+}
+
 uint64_t mlpo_state_floats(uint64_t n, int32_t tile_elems) {
     if (tile_elems <= 0) return 3u * n;
     return round_up(n, (uint64_t)tile_elems) * 3u;
