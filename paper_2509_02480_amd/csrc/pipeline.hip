@@ -1,5 +1,7 @@
 // The tiered pipeline (Algorithm 1 on the HBM / pinned-host pair): staged mode with staging slots and three streams,
-// its slot cache, and direct mode.  Host code only; the update itself is launch_adamw.
+// its slot cache, direct mode, and direct mode's scheduler for pieces that pass through bounce buffers (state in a
+// file) or end up somewhere else than they came from (flush targets).  Host code only; the update itself is
+// launch_adamw.
 #include <stddef.h>
 #include <string.h>
 
