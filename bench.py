@@ -211,6 +211,40 @@ def resident_result(args, wl, primary, others):
     return res
 
 
+def yardsticks(torch, B, update_GBs):
+    """What the memory system delivers for the update kernel's access pattern without its arithmetic
+    (mlpo_probe_bandwidth): a read-only, a write-only and an in-place read-modify-write sweep over a buffer of the
+    size of the workload's fp32 state, each timed over 30 launches between two events on one stream."""
+    d = torch.device("cuda:0")
+    nbytes = 1_500_000_000 // 16 * 16
+    buf = torch.ones(nbytes // 4, dtype=torch.float32, device=d)
+    st = torch.cuda.Stream()
+    out = {"buffer_bytes": nbytes, "launches": 30}
+    rates = {}
+    with torch.cuda.stream(st):
+        for name, kind, factor in (("read", B.PROBE_READ, 1), ("write", B.PROBE_WRITE, 1),
+                                   ("update_in_place", B.PROBE_UPDATE_IN_PLACE, 2)):
+            for _ in range(3):
+                B.mlpo_probe_bandwidth(kind, buf, nbytes, st)
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0.record(st)
+            for _ in range(30):
+                B.mlpo_probe_bandwidth(kind, buf, nbytes, st)
+            t1.record(st)
+            st.synchronize()
+            rates[name] = factor * nbytes * 30 / (t0.elapsed_time(t1) * 1e-3) / 1e9
+            out[name + "_GBs"] = round(rates[name], 1)
+    # the update moves 14 bytes in and 14 out per parameter: its time at the two one-way rates
+    mix = 28.0 / (14.0 / rates["read"] + 14.0 / rates["write"])
+    out["half_read_half_write_at_these_rates_GBs"] = round(mix, 1)
+    out["update_kernel_GBs"] = update_GBs
+    out["update_kernel_vs_in_place_yardstick"] = round(update_GBs / rates["update_in_place"], 4)
+    del buf
+    torch.cuda.empty_cache()
+    log(f"[bench] yardsticks {out}")
+    return out
+
+
 def calibration_copies(torch):
     """Plain kernels of known traffic, run only so that a counter-collecting profiler run of this script has a
     reference to scale its HBM byte counters with: a 1 GiB device-to-device copy (reads 1 GiB, writes 1 GiB) and a
@@ -826,6 +860,7 @@ def main():
     ap.add_argument("--multipath-seconds", type=float, default=20.0,
                     help="a two-path run stops taking further steps after this long (at least one is timed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-yardsticks", action="store_true", help="skip the bare read / write / in-place sweeps")
     ap.add_argument("--cpu-subgroups", type=int, default=9)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--threads", type=int, default=16)
@@ -856,6 +891,8 @@ def main():
     res = resident_result(args, W.CONFIGS[args.workload], runs[0], runs[1:])
     if args.calib_copy:
         calibration_copies(torch)
+    if not args.no_yardsticks:
+        res["yardsticks"] = yardsticks(torch, B, res["roofline"]["achieved"])
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(args, W, np)
     else:

@@ -459,6 +459,21 @@ int mlpo_set_option(const char* key, int64_t value);
  */
 int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count);
 
+/*
+ * Yardsticks for measurement: one sweep over `buffer` (device memory, 16-byte aligned, `bytes` a multiple of 16) with
+ * the access pattern of the update kernel - 128-bit non-temporal accesses, 256 lanes, one 4 KiB piece per
+ * workgroup - and nothing else: MLPO_PROBE_READ reads every word, MLPO_PROBE_WRITE overwrites the buffer (with
+ * the pattern x, x + 1/4, x + 1/2, x + 3/4 in the word of index i, x = i mod 1024), MLPO_PROBE_UPDATE_IN_PLACE
+ * halves every float in place (every byte read and written once, like p, m, v in the update).  The last 16 bytes
+ * of the buffer are left alone.  What these reach is what the memory system has to give for such a stream;
+ * bench.py reports them next to the update kernel.
+ * Asynchronous on `stream`.  Errors: MLPO_EINVAL, MLPO_EHIP.
+ */
+#define MLPO_PROBE_READ 0
+#define MLPO_PROBE_WRITE 1
+#define MLPO_PROBE_UPDATE_IN_PLACE 2
+int mlpo_probe_bandwidth(int32_t kind, void* buffer, size_t bytes, void* stream);
+
 /* Releases the events and copy streams the pipeline caches (optional; safe to call when idle). */
 int mlpo_shutdown(void);
 

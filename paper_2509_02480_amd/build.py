@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmlpo.so")
-SOURCES = ["adamw.hip", "gradnorm.hip", "accum.hip", "api.hip", "pipeline.hip", "filetier.hip", "tiers.hip", "repack.hip"]
+SOURCES = ["adamw.hip", "gradnorm.hip", "accum.hip", "api.hip", "pipeline.hip", "filetier.hip", "tiers.hip", "repack.hip",
+           "probe.hip"]
 
 # -ffp-contract=off: every fp32 operation of the update rounds on its own (no fused multiply-add), which is what makes
 # bit-level comparison with a plain CPU evaluation possible.  Division and square root stay IEEE-correct (hipcc's

@@ -357,3 +357,12 @@ def test_flush_target_argument_errors(tmp_path):
         expect(B.MLPO_EINVAL, B.mlpo_stream_update, [hostsg], None, hp, 1, None, staged)                # staged mode
     finally:
         os.close(fd)
+
+
+def test_probe_argument_errors():
+    expect(B.MLPO_EINVAL, B.mlpo_probe_bandwidth, 3, FAKE_PAGE, 4096)
+    expect(B.MLPO_EINVAL, B.mlpo_probe_bandwidth, -1, FAKE_PAGE, 4096)
+    expect(B.MLPO_EINVAL, B.mlpo_probe_bandwidth, B.PROBE_READ, 0, 4096)
+    expect(B.MLPO_EINVAL, B.mlpo_probe_bandwidth, B.PROBE_READ, FAKE_PAGE + 8, 4096)
+    expect(B.MLPO_EINVAL, B.mlpo_probe_bandwidth, B.PROBE_WRITE, FAKE_PAGE, 4100)
+    expect(B.MLPO_EINVAL, B.mlpo_probe_bandwidth, B.PROBE_WRITE, FAKE_PAGE, 16)

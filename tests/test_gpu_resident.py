@@ -472,3 +472,22 @@ def test_step_captured_in_a_hip_graph_and_replayed(oracle, scratch):
         for k in range(wl.n_sub):
             assert_state_parity(ds.fetch(k), host[k], f"replay {s} sg {k}")
     assert applied == wl.steps - 1
+
+
+@pytest.mark.parametrize("n", [8, 1024, 1028, 300_004])
+def test_yardstick_kernels_do_what_they_say(n):
+    d = dev()
+    x = torch.full((n,), 3.0, dtype=torch.float32, device=d)
+    st = torch.cuda.current_stream()
+    B.mlpo_probe_bandwidth(B.PROBE_READ, x, 4 * n, st)
+    torch.cuda.synchronize()
+    assert bool((x == 3.0).all())
+    B.mlpo_probe_bandwidth(B.PROBE_UPDATE_IN_PLACE, x, 4 * n, st)
+    torch.cuda.synchronize()
+    h = x.cpu().numpy()
+    assert (h[:-4] == 1.5).all() and (h[-4:] == 3.0).all()          # the last 16 bytes are left alone
+    B.mlpo_probe_bandwidth(B.PROBE_WRITE, x, 4 * n, st)
+    torch.cuda.synchronize()
+    h = x.cpu().numpy()
+    i = np.arange(n - 4) // 4
+    assert np.array_equal(h[:-4], (i % 1024) + 0.25 * (np.arange(n - 4) % 4)) and (h[-4:] == 3.0).all()
