@@ -30,6 +30,7 @@
  *
  * Parity pins for every function here live in tests/test_oracle_*.py.
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <string.h>
@@ -361,6 +362,11 @@ int orc_step_h(const orc_subgroup* sg, int32_t n_sg, const int32_t* order,
         orc_grad_stats_h(sg[k].g, sg[k].n, inv_scale, half, &sumsq, &bad);
     float norm, coef, gmul;
     orc_norm_finish(sumsq, inv_scale, max_norm, &norm, &coef, &gmul);
+    /* Finite gradients can have a norm that fp32 cannot hold (two of the
+     * largest bf16 value, or an unscale factor above 1): the clip factor
+     * would then be 0 or infinity would enter the moments.  Such a step is
+     * skipped like one with a non-finite gradient. */
+    if (!(norm <= FLT_MAX)) bad = 1u;
     *out_norm = norm;
     *out_found_inf = bad;
     *out_gmul = gmul;

@@ -157,3 +157,36 @@ def test_chunked_stats_match(oracle):
     assert abs(s2 / s1 - 1) < 1e-13 and f1 == f2 == 0
     g[-1] = 0xFF80
     assert oracle.grad_stats_chunked(g, 1.0)[1] == 1
+
+
+def test_a_norm_beyond_fp32_skips_the_step(oracle):
+    """Finite gradients whose norm does not fit fp32: the clip factor would be 0 (or infinity would enter the
+    moments), so the step is skipped like one with a non-finite gradient.  Worked by hand: the largest finite bf16
+    value is (2 - 2^-7) * 2^127 = 3.39e38 = 0.9961 * FLT_MAX; one of them has the norm 3.39e38 (fits), two have
+    sqrt(2) * 3.39e38 = 4.79e38 > FLT_MAX = 3.40e38 (does not)."""
+    big = np.float32((2.0 - 2.0 ** -7) * 2.0 ** 127)
+    assert bits_of([big])[0] == 0x7F7F
+
+    def sub(gbits):
+        n = len(gbits)
+        return {"p": np.full(n, 0.5, np.float32), "m": np.zeros(n, np.float32), "v": np.zeros(n, np.float32),
+                "g": np.asarray(gbits, np.uint16), "p16": np.full(n, 0x1234, np.uint16)}
+
+    one = sub([0x7F7F, 0, 0])
+    applied, norm, flag, _ = oracle.step([one], oracle.HParams(), 0, 1.0, 0.0)
+    assert applied and flag == 0 and norm == big
+    two = sub([0x7F7F, 0, 0x7F7F])
+    before = {k: v.copy() for k, v in two.items()}
+    applied, norm, flag, _ = oracle.step([two], oracle.HParams(), 0, 1.0, 1.0)
+    assert not applied and flag == 1 and np.isinf(norm)
+    assert all(np.array_equal(two[k], before[k]) for k in two)         # nothing touched
+    # the bit test alone does not see it: neither gradient is non-finite
+    assert oracle.grad_stats(two["g"], 1.0)[1] == 0
+    # an unscale factor above 1 can take a single finite gradient out of range: 2^127 * 4
+    up = sub([0x7F00, 0x3F80])
+    applied, norm, flag, _ = oracle.step([up], oracle.HParams(), 0, 4.0, 0.0)
+    assert not applied and flag == 1
+    # and just inside the range nothing is flagged: 2^126 * 2 = 2^127
+    ok = sub([0x7E80, 0])
+    applied, norm, flag, _ = oracle.step([ok], oracle.HParams(), 0, 2.0, 0.0)
+    assert applied and flag == 0 and norm == np.float32(2.0 ** 127)
