@@ -242,6 +242,16 @@ def test_norm_exact_cases_and_flags(oracle, scratch):
         g = base.copy()
         g[pos] = 0x7F7F                                       # largest finite: not flagged
         assert gpu_norm([g], offset=3)["found_inf"] == 0
+    # finite gradients whose norm does not fit fp32 skip the step as well (two of the largest finite value; one
+    # value that an unscale factor above 1 takes out of range); just inside the range nothing is flagged
+    g = base.copy()
+    g[[5, 16388]] = 0x7F7F
+    r = gpu_norm([g], offset=3)
+    assert r["found_inf"] == 1 and np.isinf(r["norm"])
+    r = gpu_norm([np.array([0x7F00, 0x3F80], np.uint16)], inv_scale=4.0)
+    assert r["found_inf"] == 1
+    r = gpu_norm([np.array([0x7E80, 0], np.uint16)], inv_scale=2.0)
+    assert r["found_inf"] == 0 and r["norm"] == np.float32(2.0 ** 127)
 
 
 def test_norm_is_deterministic(scratch):
@@ -295,7 +305,7 @@ def test_kernel_timing_records_every_launch(scratch):
     host = W.host_subgroups(wl, warm=True)
     ds = DeviceSubgroups(host, tile=B.TILE_DEFAULT)
     st = torch.cuda.current_stream()
-    B.mlpo_set_option("time_kernels", 1)
+    B.mlpo_kernel_timing(True)
     try:
         for t in range(1, 6):
             B.mlpo_grad_unscale_norm(ds.table, 1.0, 0.0, scratch.ws, scratch.ws_bytes, scratch.scalars, st)
@@ -306,7 +316,7 @@ def test_kernel_timing_records_every_launch(scratch):
         assert all(0.002 < x < 1.0 for x in upd) and all(0.001 < x < 1.0 for x in nrm)
         assert B.mlpo_kernel_times(0) == []                       # read-out forgets
     finally:
-        B.mlpo_set_option("time_kernels", 0)
+        B.mlpo_kernel_timing(False)
     B.mlpo_adamw_step(ds.table, B.HParams(), 6, None, st)
     assert B.mlpo_kernel_times(0) == []                           # nothing recorded when off
 
@@ -472,22 +482,3 @@ def test_step_captured_in_a_hip_graph_and_replayed(oracle, scratch):
         for k in range(wl.n_sub):
             assert_state_parity(ds.fetch(k), host[k], f"replay {s} sg {k}")
     assert applied == wl.steps - 1
-
-
-@pytest.mark.parametrize("n", [8, 1024, 1028, 300_004])
-def test_yardstick_kernels_do_what_they_say(n):
-    d = dev()
-    x = torch.full((n,), 3.0, dtype=torch.float32, device=d)
-    st = torch.cuda.current_stream()
-    B.mlpo_probe_bandwidth(B.PROBE_READ, x, 4 * n, st)
-    torch.cuda.synchronize()
-    assert bool((x == 3.0).all())
-    B.mlpo_probe_bandwidth(B.PROBE_UPDATE_IN_PLACE, x, 4 * n, st)
-    torch.cuda.synchronize()
-    h = x.cpu().numpy()
-    assert (h[:-4] == 1.5).all() and (h[-4:] == 3.0).all()          # the last 16 bytes are left alone
-    B.mlpo_probe_bandwidth(B.PROBE_WRITE, x, 4 * n, st)
-    torch.cuda.synchronize()
-    h = x.cpu().numpy()
-    i = np.arange(n - 4) // 4
-    assert np.array_equal(h[:-4], (i % 1024) + 0.25 * (np.arange(n - 4) % 4)) and (h[-4:] == 3.0).all()
