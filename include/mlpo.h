@@ -137,7 +137,8 @@ typedef struct {
     float norm;         /* L2 norm of the unscaled gradients of all subgroups */
     float clip_coef;    /* max_norm / (norm + 1e-6) if clipping is on and norm > max_norm, else 1 */
     float gmul;         /* inv_scale * clip_coef: the factor the update applies to every raw gradient */
-    uint32_t found_inf; /* 1 if any gradient is +-inf or NaN (the whole step must then be skipped), else 0 */
+    uint32_t found_inf; /* 1 if any gradient is +-inf or NaN, or if the norm does not fit fp32 (the whole step must
+                           then be skipped), else 0 */
 } mlpo_step_scalars;
 
 /* Text of the last error on the calling thread ("" if none).  The pointer stays valid until the thread's next
@@ -154,8 +155,9 @@ size_t mlpo_norm_workspace_bytes(void);
  * Gradient pass before the update (the usual mixed-precision convention; Section 2 "Mixed Precision Training" of the
  * paper only says that the half-precision gradients are widened to fp32 for the optimizer): over the gradients of ALL
  * n_sg subgroups
- *   found_inf = any g_i with its exponent field all ones (8 bits in bf16, 5 in fp16),
  *   norm      = sqrt( sum_i ((double)(f32(g_i) * inv_scale))^2 ), rounded to fp32,
+ *   found_inf = any g_i with its exponent field all ones (8 bits in bf16, 5 in fp16), or norm not finite (finite
+ *               gradients whose norm overflows fp32: the clip factor would be 0 or infinity would enter the moments),
  *   clip_coef, gmul as described at mlpo_step_scalars.
  * The sum is taken in fp64 in a fixed order: the result is deterministic for a given argument list.
  *
@@ -435,44 +437,22 @@ int mlpo_assign_tiers(int32_t n_subgroups, int32_t n_tiers, const double* bandwi
  */
 int mlpo_update_bandwidth(int32_t n_tiers, double* bandwidth, const double* bytes_moved, const double* seconds);
 
-/* Tuning knobs for measurements (process-wide; not needed for correct results).  Unknown keys give MLPO_EINVAL.
- *   "adamw_grid_per_cu"  blocks per compute unit of the persistent update grid (default in the source)
- *   "adamw_variant"      kernel variant index
- *   "norm_grid_per_cu"   blocks per compute unit of the gradient pass
- *   "adamw_align_bytes"  address boundary the planar update kernel aligns its tiles to (power of two, 16..4096)
- *   "direct_variant"     kernel variant of the direct host-tier mode
- *   "time_kernels"       see mlpo_kernel_times
- */
-int mlpo_set_option(const char* key, int64_t value);
-
 /*
- * Per-kernel timing, for measurement.  After mlpo_set_option("time_kernels", 1) every launch of the fused update
- * kernel (which = 0) and of the gradient pass's streaming kernel (which = 1) is stamped with HIP events that carry the
- * dispatch's own begin and end on the device, and every staged-mode transfer is bracketed by event markers on its
- * copy stream (which = 2: host-to-device fetches, which = 3: device-to-host flushes, one entry per subgroup or chunk;
- * the effective I/O throughput of Section 4.3 of the paper, 2 * bytes / (read time + write time), follows from them).
- * which = 4: the 128-bit kernel of mlpo_grad_accumulate.
+ * Per-kernel timing, for measurement (Section 4.3 of the paper reports the effective I/O throughput
+ * 2 * bytes / (read time + write time) per subgroup; the roofline figures need a kernel's own duration).  After
+ * mlpo_kernel_timing(1) every launch of the fused update kernel (which = 0) and of the gradient pass's streaming
+ * kernel (which = 1) is stamped with HIP events that carry the dispatch's own begin and end on the device, and every
+ * staged-mode transfer is bracketed by event markers on its copy stream (which = 2: host-to-device fetches,
+ * which = 3: device-to-host flushes, one entry per subgroup or chunk).  which = 4: the 128-bit kernel of
+ * mlpo_grad_accumulate.  mlpo_kernel_timing(0) turns it off and forgets what was recorded.  Process-wide; results
+ * are the same with and without it.
  * mlpo_kernel_times waits for the recorded items, writes their durations in milliseconds to ms[0..cap) in issue order
  * (host memory), stores the number written in *count and forgets them.  At most 16384 items per kind are kept
- * between calls.  Setting the option to 0 turns it off.
+ * between calls.
  * Errors: MLPO_EINVAL, MLPO_EHIP.
  */
+int mlpo_kernel_timing(int32_t on);
 int mlpo_kernel_times(int32_t which, float* ms, int32_t cap, int32_t* count);
-
-/*
- * Yardsticks for measurement: one sweep over `buffer` (device memory, 16-byte aligned, `bytes` a multiple of 16) with
- * the access pattern of the update kernel - 128-bit non-temporal accesses, 256 lanes, one 4 KiB piece per
- * workgroup - and nothing else: MLPO_PROBE_READ reads every word, MLPO_PROBE_WRITE overwrites the buffer (with
- * the pattern x, x + 1/4, x + 1/2, x + 3/4 in the word of index i, x = i mod 1024), MLPO_PROBE_UPDATE_IN_PLACE
- * halves every float in place (every byte read and written once, like p, m, v in the update).  The last 16 bytes
- * of the buffer are left alone.  What these reach is what the memory system has to give for such a stream;
- * bench.py reports them next to the update kernel.
- * Asynchronous on `stream`.  Errors: MLPO_EINVAL, MLPO_EHIP.
- */
-#define MLPO_PROBE_READ 0
-#define MLPO_PROBE_WRITE 1
-#define MLPO_PROBE_UPDATE_IN_PLACE 2
-int mlpo_probe_bandwidth(int32_t kind, void* buffer, size_t bytes, void* stream);
 
 /* Releases the events and copy streams the pipeline caches (optional; safe to call when idle). */
 int mlpo_shutdown(void);

@@ -26,8 +26,8 @@ EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_line_lead", "mlpo_state_floa
            "mlpo_state_unpack",
            "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm",
            "mlpo_grad_norm_finish", "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_bounce_bytes",
-           "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers", "mlpo_update_bandwidth", "mlpo_set_option",
-           "mlpo_kernel_times", "mlpo_probe_bandwidth", "mlpo_shutdown")
+           "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers", "mlpo_update_bandwidth",
+           "mlpo_kernel_timing", "mlpo_kernel_times", "mlpo_shutdown")
 
 
 class MlpoError(RuntimeError):
@@ -120,8 +120,6 @@ def lib():
         L.mlpo_last_error.argtypes = []
         L.mlpo_version.restype = C.c_int32
         L.mlpo_version.argtypes = []
-        L.mlpo_probe_bandwidth.restype = C.c_int
-        L.mlpo_probe_bandwidth.argtypes = [C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.mlpo_line_lead.restype = C.c_int32
         L.mlpo_line_lead.argtypes = [C.c_void_p]
         L.mlpo_state_floats.restype = C.c_uint64
@@ -161,8 +159,8 @@ def lib():
                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.mlpo_update_bandwidth.restype = C.c_int
         L.mlpo_update_bandwidth.argtypes = [C.c_int32] + [C.POINTER(C.c_double)] * 3
-        L.mlpo_set_option.restype = C.c_int
-        L.mlpo_set_option.argtypes = [C.c_char_p, C.c_int64]
+        L.mlpo_kernel_timing.restype = C.c_int
+        L.mlpo_kernel_timing.argtypes = [C.c_int32]
         L.mlpo_kernel_times.restype = C.c_int
         L.mlpo_kernel_times.argtypes = [C.c_int32, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
         L.mlpo_shutdown.restype = C.c_int
@@ -207,13 +205,6 @@ def tiled_subgroup(state, g, p16, n: Optional[int] = None, tier: int = TIER_HBM,
     base = _ptr(state)
     return SubgroupC(base, base + 4 * tile_elems, base + 8 * tile_elems, _ptr(g), _ptr(p16), int(n), int(tier),
                      int(tile_elems), int(half), int(lead))
-
-
-PROBE_READ, PROBE_WRITE, PROBE_UPDATE_IN_PLACE = 0, 1, 2
-
-
-def mlpo_probe_bandwidth(kind: int, buffer, nbytes: int, stream=None) -> None:
-    _check(lib().mlpo_probe_bandwidth(kind, _ptr(buffer), nbytes, _stream(stream)))
 
 
 def mlpo_line_lead(p16) -> int:
@@ -405,8 +396,8 @@ def mlpo_grad_norm_finish(workspace, workspace_bytes: int, inv_scale: float, max
                                        _stream(stream)))
 
 
-def mlpo_set_option(key: str, value: int) -> None:
-    _check(lib().mlpo_set_option(key.encode(), value))
+def mlpo_kernel_timing(on: bool) -> None:
+    _check(lib().mlpo_kernel_timing(1 if on else 0))
 
 
 def mlpo_kernel_times(which: int, cap: int = 16384) -> list:

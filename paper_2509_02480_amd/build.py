@@ -8,8 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmlpo.so")
-SOURCES = ["adamw.hip", "gradnorm.hip", "accum.hip", "api.hip", "pipeline.hip", "filetier.hip", "tiers.hip", "repack.hip",
-           "probe.hip"]
+SOURCES = ["adamw.hip", "gradnorm.hip", "accum.hip", "api.hip", "pipeline.hip", "filetier.hip", "tiers.hip", "repack.hip"]
 
 # -ffp-contract=off: every fp32 operation of the update rounds on its own (no fused multiply-add), which is what makes
 # bit-level comparison with a plain CPU evaluation possible.  Division and square root stay IEEE-correct (hipcc's
@@ -36,6 +35,19 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+YARDSTICK_SRC = os.path.join(ROOT, "bench_yardsticks.hip")
+YARDSTICK_LIB = os.path.join(ROOT, "libbench_yardsticks.so")
+
+
+def build_yardsticks(verbose: bool = False) -> str:
+    """The benchmark's measuring aid (bare memory sweeps, link copies): a shared object of its own beside bench.py."""
+    cmd = [hipcc(), *HIPCC_FLAGS, "-o", YARDSTICK_LIB, YARDSTICK_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return YARDSTICK_LIB
+
+
 def lib_is_current() -> bool:
     if not os.path.exists(LIB):
         return False
@@ -46,3 +58,4 @@ def lib_is_current() -> bool:
 
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_yardsticks(verbose=True))

@@ -361,74 +361,47 @@ bool vec_aligned(const SgView& s) {
            s.lead % 4 == 0;
 }
 
-struct Variant {
-    int block;
-    int unroll;
-    bool nt;
-    bool persist;
-};
-constexpr Variant kVariants[] = {
-    {256, 2, true, false},  {256, 1, true, false}, {256, 4, true, false}, {512, 1, true, false},
-    {1024, 1, true, false}, {256, 1, false, false}, {256, 1, true, true}, {256, 2, true, true},
-};
-constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kPersistVariant = 6;  // 256 threads, one group of four per lane, grid-stride with prefetch
+// Two forms of the 128-bit kernel are built, both with 256 lanes and one group of four elements per lane (a kernel
+// tile of 1024 elements, which divides every layout tile): one tile per workgroup - the fastest form in both layouts
+// when the state is in HBM (planar, 125 M elements: 562 us against 570-573 us for larger tiles) - and the grid-stride
+// form with next-tile prefetch, for a bounded number of persistent workgroups (state in pinned host memory) and, in
+// its out-of-place instantiation, for subgroups that change their home.
+constexpr int kLanes = 256;
+constexpr uint64_t kTile4 = kLanes;  // groups of four per kernel tile
 
-// Tuning value -1 (the default): 256 lanes, one group of four per lane, one tile per block - the fastest form in
-// both layouts (planar, 125 M elements: 562 us against 570-573 us for the larger tiles).
-int variant_index() {
-    const int vi = tuning().adamw_variant;
-    if (vi >= 0 && vi < kNumVariants) return vi;
-    return 1;
-}
-
-template <int BLOCK, int UNROLL, bool NT, bool PERSIST, bool MOVE = false>
+template <bool PERSIST, bool MOVE = false>
 void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
                const StoreShift<MOVE>& shift = StoreShift<MOVE>{}) {
     hipEvent_t t0, t1;
     if (timing_enabled() && timing_acquire(kTimedUpdate, &t0, &t1))
-        hipExtLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST, MOVE>), dim3(grid), dim3(BLOCK), 0, st, t0, t1, 0,
-                              b, c, sc, shift);
+        hipExtLaunchKernelGGL((adamw_v4_kernel<kLanes, 1, true, PERSIST, MOVE>), dim3(grid), dim3(kLanes), 0, st, t0, t1,
+                              0, b, c, sc, shift);
     else
-        hipLaunchKernelGGL((adamw_v4_kernel<BLOCK, UNROLL, NT, PERSIST, MOVE>), dim3(grid), dim3(BLOCK), 0, st, b, c, sc,
+        hipLaunchKernelGGL((adamw_v4_kernel<kLanes, 1, true, PERSIST, MOVE>), dim3(grid), dim3(kLanes), 0, st, b, c, sc,
                            shift);
 }
 
-// shift = nullptr: every subgroup of the batch is updated in place.  Else vi names a grid-stride variant (the only
-// ones built in the out-of-place form).
-int launch_vec_batch(const VecBatch& b, int vi, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
+// persist_blocks = 0: one tile per workgroup.  > 0: that many persistent workgroups at most.  shift != nullptr: the
+// out-of-place form (always grid-stride; persist_blocks = 0 then means eight workgroups per compute unit).
+int launch_vec_batch(const VecBatch& b, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
                      int persist_blocks, const StoreShift<true>* shift) {
     const uint32_t total = b.tile_begin[b.n_sg];
     if (total == 0) return MLPO_OK;
     uint32_t grid = total;
     if (persist_blocks > 0) {
         if ((uint32_t)persist_blocks < grid) grid = (uint32_t)persist_blocks;
-    } else if (kVariants[vi].persist) {
+    } else if (shift != nullptr) {
         const int cus = num_cus();
         if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
-        int per_cu = tuning().adamw_grid_per_cu;
-        if (per_cu <= 0) per_cu = 8;
-        const uint64_t cap = (uint64_t)cus * (uint64_t)per_cu;
+        const uint64_t cap = (uint64_t)cus * 8u;
         if (cap < grid) grid = (uint32_t)cap;
     }
-    if (shift != nullptr) {
-        if (vi == kPersistVariant)
-            launch_v4<256, 1, true, true, true>(b, grid, c, sc, st, *shift);
-        else
-            launch_v4<256, 2, true, true, true>(b, grid, c, sc, st, *shift);
-        MLPO_HIP(hipGetLastError());
-        return MLPO_OK;
-    }
-    switch (vi) {
-        case 0: launch_v4<256, 2, true, false>(b, grid, c, sc, st); break;
-        case 1: launch_v4<256, 1, true, false>(b, grid, c, sc, st); break;
-        case 2: launch_v4<256, 4, true, false>(b, grid, c, sc, st); break;
-        case 3: launch_v4<512, 1, true, false>(b, grid, c, sc, st); break;
-        case 4: launch_v4<1024, 1, true, false>(b, grid, c, sc, st); break;
-        case 5: launch_v4<256, 1, false, false>(b, grid, c, sc, st); break;
-        case 6: launch_v4<256, 1, true, true>(b, grid, c, sc, st); break;
-        default: launch_v4<256, 2, true, true>(b, grid, c, sc, st); break;
-    }
+    if (shift != nullptr)
+        launch_v4<true, true>(b, grid, c, sc, st, *shift);
+    else if (persist_blocks > 0)
+        launch_v4<true>(b, grid, c, sc, st);
+    else
+        launch_v4<false>(b, grid, c, sc, st);  // grid == total: every tile has its workgroup
     MLPO_HIP(hipGetLastError());
     return MLPO_OK;
 }
@@ -449,22 +422,10 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
                  hipStream_t stream, int persist_blocks) {
     bool moves = false;  // does any subgroup's new state go somewhere else than the old one came from?
     for (int i = 0; i < n; ++i) moves = moves || views[i].out_delta != 0;
-    int vi = variant_index();
-    // A caller-fixed number of persistent blocks (the direct host-tier mode) needs the grid-stride kernel.
-    if (persist_blocks > 0 && !kVariants[vi].persist) {
-        vi = tuning().direct_variant;
-        if (vi < 0 || vi >= kNumVariants || !kVariants[vi].persist) vi = kPersistVariant;
-    }
-    for (int i = 0; i < n; ++i)  // a kernel tile must divide every layout tile; the 1024-element variant always does
-        if (views[i].tile_elems != 0 &&
-            (uint64_t)views[i].tile_elems % ((uint64_t)kVariants[vi].block * kVariants[vi].unroll * 4u) != 0)
-            vi = 1;
-    if (moves && !kVariants[vi].persist) vi = kPersistVariant;  // same tile size as variant 1
-    const Variant& var = kVariants[vi];
-    const uint64_t t4 = (uint64_t)var.block * (uint64_t)var.unroll;
-    uint64_t align = (uint64_t)tuning().adamw_align_bytes;
-    if (align < 16 || (align & (align - 1)) != 0) align = 16;  // 16 = no head tile
-    if (align > 4096) align = 4096;                            // a head must fit in the smallest tile
+    const uint64_t t4 = kTile4;
+    // Planar subgroups get a head tile that ends on a 256-byte boundary of p: whole cache lines per wavefront access and
+    // no line shared between two workgroups (a subgroup that starts mid-line runs 13 % slower without it).
+    constexpr uint64_t align = 256;
     constexpr uint64_t kTile1 = (uint64_t)kBlock1 * kUnroll1;
 
     VecBatch vb;
@@ -514,7 +475,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         if (tiles > kMaxTiles) return fail(MLPO_EINVAL, "subgroup %d too large (%llu elements)", i,
                                            (unsigned long long)s.n);
         if (vb.n_sg == kMaxSg || (uint64_t)vb.tile_begin[vb.n_sg] + tiles > kMaxTiles) {
-            const int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks, shift_arg);
+            const int rc = launch_vec_batch(vb, c, scalars, stream, persist_blocks, shift_arg);
             if (rc != MLPO_OK) return rc;
             vb.n_sg = 0;
         }
@@ -533,7 +494,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         vb.tile_begin[vb.n_sg + 1] = vb.tile_begin[vb.n_sg] + (uint32_t)tiles;
         ++vb.n_sg;
     }
-    int rc = launch_vec_batch(vb, vi, c, scalars, stream, persist_blocks, shift_arg);
+    int rc = launch_vec_batch(vb, c, scalars, stream, persist_blocks, shift_arg);
     if (rc != MLPO_OK) return rc;
     return launch_scalar_batch(sb, c, scalars, stream);
 }

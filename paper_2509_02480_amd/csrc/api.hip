@@ -1,4 +1,4 @@
-// C ABI of libmlpo: errors, tuning knobs, per-kernel timing, argument checking, per-step scalars and the entry points
+// C ABI of libmlpo: errors, per-kernel timing, argument checking, per-step scalars and the entry points
 // of the resident path.  The tiered pipeline is in pipeline.hip.
 #include <math.h>
 #include <stdarg.h>
@@ -24,13 +24,7 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
-// ---- tuning / device ------------------------------------------------------------
-Tuning& tuning() {
-    static Tuning t = {/*adamw_grid_per_cu=*/8, /*adamw_variant=*/-1, /*norm_grid_per_cu=*/4,
-                       /*adamw_align_bytes=*/256, /*direct_variant=*/6};
-    return t;
-}
-
+// ---- device ------------------------------------------------------------
 int num_cus() {
     static std::mutex mu;
     static int cached[64] = {0};
@@ -65,24 +59,52 @@ constexpr size_t kMaxTimed = 16384;
 
 bool timing_enabled() { return timing().enabled; }
 
+// Takes an event pair from the pool (or creates one); the caller holds the lock.
+static bool timing_take_locked(TimingState& t, TimedLaunch* e) {
+    if (!t.pool.empty()) {
+        *e = t.pool.back();
+        t.pool.pop_back();
+        return true;
+    }
+    if (hipEventCreate(&e->start) != hipSuccess) return false;
+    if (hipEventCreate(&e->stop) != hipSuccess) {
+        (void)hipEventDestroy(e->start);
+        return false;
+    }
+    return true;
+}
+
 bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop) {
     TimingState& t = timing();
     std::lock_guard<std::mutex> lk(t.mu);
     if (!t.enabled || which < 0 || which >= kTimedKinds || t.rec[which].size() >= kMaxTimed) return false;
     TimedLaunch e;
-    if (!t.pool.empty()) {
-        e = t.pool.back();
-        t.pool.pop_back();
-    } else {
-        if (hipEventCreate(&e.start) != hipSuccess) return false;
-        if (hipEventCreate(&e.stop) != hipSuccess) {
-            (void)hipEventDestroy(e.start);
-            return false;
-        }
-    }
+    if (!timing_take_locked(t, &e)) return false;
     t.rec[which].push_back(e);
     *start = e.start;
     *stop = e.stop;
+    return true;
+}
+
+// Both pairs or neither: a pair that is listed but never recorded would make mlpo_kernel_times wait for nothing.
+bool timing_acquire_two(int which_a, hipEvent_t* a0, hipEvent_t* a1, int which_b, hipEvent_t* b0, hipEvent_t* b1) {
+    TimingState& t = timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    if (!t.enabled || which_a < 0 || which_a >= kTimedKinds || which_b < 0 || which_b >= kTimedKinds ||
+        which_a == which_b || t.rec[which_a].size() >= kMaxTimed || t.rec[which_b].size() >= kMaxTimed)
+        return false;
+    TimedLaunch ea, eb;
+    if (!timing_take_locked(t, &ea)) return false;
+    if (!timing_take_locked(t, &eb)) {
+        t.pool.push_back(ea);
+        return false;
+    }
+    t.rec[which_a].push_back(ea);
+    t.rec[which_b].push_back(eb);
+    *a0 = ea.start;
+    *a1 = ea.stop;
+    *b0 = eb.start;
+    *b1 = eb.stop;
     return true;
 }
 
@@ -227,17 +249,8 @@ int32_t mlpo_version(void) { return 100; }
 
 size_t mlpo_norm_workspace_bytes(void) { return grad_norm_workspace_bytes(); }
 
-int mlpo_set_option(const char* key, int64_t value) {
-    if (key == nullptr) return fail(MLPO_EINVAL, "key is NULL");
-    if (value < -1 || value > 65536) return fail(MLPO_EINVAL, "value out of range");
-    if (strcmp(key, "adamw_grid_per_cu") == 0) tuning().adamw_grid_per_cu = (int)value;
-    else if (strcmp(key, "adamw_variant") == 0) tuning().adamw_variant = (int)value;
-    else if (strcmp(key, "norm_grid_per_cu") == 0) tuning().norm_grid_per_cu = (int)value;
-    else if (strcmp(key, "adamw_align_bytes") == 0) tuning().adamw_align_bytes = (int)value;
-
-    else if (strcmp(key, "direct_variant") == 0) tuning().direct_variant = (int)value;
-    else if (strcmp(key, "time_kernels") == 0) timing_set(value != 0);
-    else return fail(MLPO_EINVAL, "unknown option '%s'", key);
+int mlpo_kernel_timing(int32_t on) {
+    timing_set(on != 0);
     return MLPO_OK;
 }
 

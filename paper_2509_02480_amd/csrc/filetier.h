@@ -47,6 +47,7 @@ class FilePath {
     bool is_read(size_t i);                         // never blocks
     bool wait_read(size_t i);                       // false: the path has stopped and the piece will not arrive
     bool failed();
+    void stop();                                    // the owner gave up: waiting threads leave without an error text
     void hand_to_writer(size_t i, hipEvent_t done);  // done: recorded behind the piece's kernel
     // Waits for both threads.  false: something failed, *error says what.
     bool join(mlpo_file_stats* stats, std::string* error);

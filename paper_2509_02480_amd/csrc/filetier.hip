@@ -265,6 +265,12 @@ bool FilePath::failed() {
     return !error_.empty();
 }
 
+void FilePath::stop() {
+    std::lock_guard<std::mutex> lk(mu_);
+    stopped_ = true;
+    cv_.notify_all();
+}
+
 void FilePath::hand_to_writer(size_t i, hipEvent_t done) {
     std::lock_guard<std::mutex> lk(mu_);
     done_[i] = done;

@@ -17,15 +17,6 @@ int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
         if (e_ != hipSuccess) return ::mlpo::fail(MLPO_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
     } while (0)
 
-// ---- tuning knobs ------------------------------------------------------------
-struct Tuning {
-    int adamw_grid_per_cu;
-    int adamw_variant;
-    int norm_grid_per_cu;
-    int adamw_align_bytes;
-    int direct_variant;
-};
-Tuning& tuning();
 int num_cus();  // compute units of the current device (cached); <= 0 on failure
 
 // ---- optional per-kernel timing (the dispatch's own start / stop timestamps) ------------------
@@ -39,6 +30,8 @@ constexpr int kTimedAccumulate = 4;  // the gradient accumulation kernel (128-bi
 constexpr int kTimedKinds = 5;
 bool timing_enabled();
 bool timing_acquire(int which, hipEvent_t* start, hipEvent_t* stop);  // false: not enabled or table full
+// The same for two kinds at once: both pairs or neither.
+bool timing_acquire_two(int which_a, hipEvent_t* a0, hipEvent_t* a1, int which_b, hipEvent_t* b0, hipEvent_t* b1);
 
 // ---- per-step scalars of the update, derived on the host ---------------------
 struct AdamwConsts {

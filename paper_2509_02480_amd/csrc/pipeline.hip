@@ -79,8 +79,8 @@ static int ensure_events_locked(EventCache& c, int n_slots) {
 
 static int ensure_file_events_locked(EventCache& c, int file_slots) {
     while ((int)c.file_done.size() < file_slots) {
-        hipEvent_t e;
-        MLPO_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        hipEvent_t e;  // writer threads sleep on these instead of spinning while the kernel runs
+        MLPO_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventBlockingSync));
         c.file_done.push_back(e);
     }
     for (hipEvent_t& e : c.pace)
@@ -476,34 +476,46 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
         files.join(nullptr, &why);
         return fail(MLPO_EIO, "%s", why.c_str());
     }
-    if (!plan.resident.empty()) {
-        rc = launch_adamw(plan.resident.data(), (int)plan.resident.size(), c, scalars, st.cmp);
-        if (rc != MLPO_OK) return rc;
-    }
-    size_t next_host = 0, next_file = 0, launched = 0;
-    while (next_host < host_pieces.size() || next_file < files.size()) {
-        if (files.failed()) break;
-        if (next_host >= host_pieces.size() && !files.wait_read(next_file)) break;  // only the file is left
-        if (launched >= 2) MLPO_HIP(hipEventSynchronize(ec.pace[launched % 2]));    // the launch before the last
-        if (next_file < files.size() && files.is_read(next_file)) {
-            rc = launch_adamw(&files.job(next_file).view, 1, c, scalars, st.h2d, blocks);
-            if (rc != MLPO_OK) return rc;
-            hipEvent_t done = ec.file_done[next_file % (size_t)cfg->file_slots];
-            MLPO_HIP(hipEventRecord(done, st.h2d));
-            files.hand_to_writer(next_file, done);
-            ++next_file;
-        } else {
-            rc = launch_adamw(&host_pieces[next_host], 1, c, scalars, st.h2d, blocks);
-            if (rc != MLPO_OK) return rc;
-            ++next_host;
+    // Everything between the start of the I/O threads and their join runs inside this function, so that a failure
+    // on the way still ends with the link stream fenced into the compute stream and the threads joined: the caller
+    // gets its error code only after nothing of this call can touch its buffers any more.
+    auto launch_all = [&]() -> int {
+        if (!plan.resident.empty()) {
+            const int r = launch_adamw(plan.resident.data(), (int)plan.resident.size(), c, scalars, st.cmp);
+            if (r != MLPO_OK) return r;
         }
-        MLPO_HIP(hipEventRecord(ec.pace[launched % 2], st.h2d));
-        ++launched;
-    }
-    MLPO_HIP(hipEventRecord(ec.fence, st.h2d));
-    MLPO_HIP(hipStreamWaitEvent(st.cmp, ec.fence, 0));
+        size_t next_host = 0, next_file = 0, launched = 0;
+        while (next_host < host_pieces.size() || next_file < files.size()) {
+            if (files.failed()) break;
+            if (next_host >= host_pieces.size() && !files.wait_read(next_file)) break;  // only the file is left
+            if (launched >= 2) MLPO_HIP(hipEventSynchronize(ec.pace[launched % 2]));    // the launch before the last
+            if (next_file < files.size() && files.is_read(next_file)) {
+                const int r = launch_adamw(&files.job(next_file).view, 1, c, scalars, st.h2d, blocks);
+                if (r != MLPO_OK) return r;
+                hipEvent_t done = ec.file_done[next_file % (size_t)cfg->file_slots];
+                MLPO_HIP(hipEventRecord(done, st.h2d));
+                files.hand_to_writer(next_file, done);
+                ++next_file;
+            } else {
+                const int r = launch_adamw(&host_pieces[next_host], 1, c, scalars, st.h2d, blocks);
+                if (r != MLPO_OK) return r;
+                ++next_host;
+            }
+            MLPO_HIP(hipEventRecord(ec.pace[launched % 2], st.h2d));
+            ++launched;
+        }
+        return MLPO_OK;
+    };
+    rc = launch_all();
+    if (rc != MLPO_OK) files.stop();  // the threads leave at their next wait; error text of rc is already set
+    const hipError_t fence_rec = hipEventRecord(ec.fence, st.h2d);
+    const hipError_t fence_wait = fence_rec == hipSuccess ? hipStreamWaitEvent(st.cmp, ec.fence, 0) : fence_rec;
+    if (fence_wait != hipSuccess) (void)hipStreamSynchronize(st.h2d);  // no fence: wait here instead
     std::string err;
-    if (!files.join(cfg->file_stats, &err)) return fail(MLPO_EIO, "%s", err.c_str());
+    const bool io_ok = files.join(cfg->file_stats, &err);
+    if (rc != MLPO_OK) return rc;
+    if (fence_wait != hipSuccess) return fail(MLPO_EHIP, "fencing the link stream: %s", hipGetErrorString(fence_wait));
+    if (!io_ok) return fail(MLPO_EIO, "%s", err.c_str());
     return MLPO_OK;
 }
 
@@ -596,8 +608,8 @@ static int run_staged(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
             SlotEvents& ev = ec.slots[(size_t)k];
             const Piece pc{&s, off, len, staging + (uint64_t)k * slot_floats};
             hipEvent_t tf0 = nullptr, tf1 = nullptr, tw0 = nullptr, tw1 = nullptr;
-            const bool timed = timing_enabled() && timing_acquire(kTimedFetch, &tf0, &tf1) &&
-                               timing_acquire(kTimedFlush, &tw0, &tw1);
+            const bool timed =
+                timing_enabled() && timing_acquire_two(kTimedFetch, &tf0, &tf1, kTimedFlush, &tw0, &tw1);
             // fetch
             if (piece >= (uint64_t)cfg->n_slots) MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
             if (timed) MLPO_HIP(hipEventRecord(tf0, st.h2d));

@@ -10,17 +10,64 @@ using namespace mlpo;
 
 namespace {
 
-// Eq. 1 over the tiers listed in `live`, for `m` subgroups: ceilings of the proportional shares, then the surplus is
-// taken back one subgroup at a time from the tier that would finish last (largest count / bandwidth; among equals the
-// one with the lower bandwidth, then the higher index), so that the paths finish as close together as they can.
+// Exact arithmetic on doubles, as far as Eq. 1 needs it: the sign of a sum of products.  A product of two doubles is
+// the unevaluated sum of two doubles (the rounded product and its error, which one fused multiply-add yields), and a
+// sum of doubles can be kept exactly as a list of non-overlapping components that grows by one with every addend
+// (the classical error-free transformations).  The sign of the whole is the sign of its largest component.  Exact as
+// long as no product overflows or falls into the subnormal range, i.e. for any bandwidths a machine can have.
+struct ExactSum {
+    double part[2 * 66 + 4];
+    int n = 0;
+    void add(double x) {  // components stay ordered by increasing magnitude, zeros are dropped
+        int kept = 0;
+        for (int i = 0; i < n; ++i) {
+            const double s = x + part[i];
+            const double bv = s - x;
+            const double err = (x - (s - bv)) + (part[i] - bv);
+            if (err != 0.0) part[kept++] = err;
+            x = s;
+        }
+        if (x != 0.0) part[kept++] = x;
+        n = kept;
+    }
+    void add_product(double a, double b) {
+        const double hi = a * b;
+        add(fma(a, b, -hi));
+        add(hi);
+    }
+    int sign() const { return n == 0 ? 0 : (part[n - 1] > 0.0 ? 1 : -1); }
+};
+
+// sign(c * sum_{j in live} bw[j] - m * bw[i]): is c at least the proportional share of tier i?
+int share_sign(int64_t c, int64_t m, int i, const std::vector<int>& live, const double* bw) {
+    ExactSum e;
+    for (int j : live) e.add_product((double)c, bw[j]);
+    e.add_product(-(double)m, bw[i]);
+    return e.sign();
+}
+
+// sign(ca / ba - cb / bb) for positive ba, bb.
+int finish_time_sign(int32_t ca, double ba, int32_t cb, double bb) {
+    ExactSum e;
+    e.add_product((double)ca, bb);
+    e.add_product(-(double)cb, ba);
+    return e.sign();
+}
+
+// Eq. 1 over the tiers listed in `live`, for `m` subgroups: ceilings of the proportional shares (the exact ceiling
+// of the exact quotient of the doubles: a floating-point estimate, corrected by exact comparisons), then the surplus
+// is taken back one subgroup at a time from the tier that would finish last (largest count / bandwidth; among equals
+// the one with the lower bandwidth, then the higher index), so that the paths finish as close together as they can.
 void proportional(int64_t m, const std::vector<int>& live, const double* bw, int32_t* count) {
     double total = 0.0;
     for (int i : live) total += bw[i];
     int64_t sum = 0;
     for (int i : live) {
-        const double share = (double)m * bw[i] / total;
-        int64_t c = (int64_t)ceil(share - 1e-12);
+        int64_t c = (int64_t)ceil((double)m * bw[i] / total);
         if (c < 0) c = 0;
+        if (c > m) c = m;
+        while (c < m && share_sign(c, m, i, live, bw) < 0) ++c;
+        while (c > 0 && share_sign(c - 1, m, i, live, bw) >= 0) --c;
         count[i] = (int32_t)c;
         sum += c;
     }
@@ -32,8 +79,8 @@ void proportional(int64_t m, const std::vector<int>& live, const double* bw, int
                 worst = i;
                 continue;
             }
-            const double a = (double)count[i] / bw[i], b = (double)count[worst] / bw[worst];
-            if (a > b || (a == b && (bw[i] < bw[worst] || (bw[i] == bw[worst] && i > worst)))) worst = i;
+            const int cmp = finish_time_sign(count[i], bw[i], count[worst], bw[worst]);
+            if (cmp > 0 || (cmp == 0 && (bw[i] < bw[worst] || (bw[i] == bw[worst] && i > worst)))) worst = i;
         }
         --count[worst];
         --sum;

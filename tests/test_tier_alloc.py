@@ -59,6 +59,22 @@ def test_oracle_special_cases():
     assert O.update_bandwidth([5.3, 3.6], [10e9, 0.0], [2.5, 0.0]) == [4e9, 3.6]
 
 
+def test_bandwidth_update_follows_the_observations():
+    # Section 3.3: the estimate of a path becomes what the last iteration showed; a path that moved nothing, or for
+    # no measurable time, keeps its estimate.  A path seen at half its estimate gives up subgroups in the next split.
+    bw = [48.0e9, 24.0e9]
+    assert O.assign_tiers(30, bw)[0] == [20, 10]
+    seen = O.update_bandwidth(bw, [12.0e9, 12.0e9], [0.5, 0.5])
+    assert seen == [24.0e9, 24.0e9] and O.assign_tiers(30, seen)[0] == [15, 15]
+    assert O.update_bandwidth(bw, [0.0, 6.0e9], [1.0, 0.0]) == bw
+    assert O.update_bandwidth([1.0, 2.0, 3.0], [10.0, 0.0, 9.0], [4.0, 5.0, 3.0]) == [2.5, 2.0, 3.0]
+    # three paths, observed at the rates of Table 1's two paths and at their sum
+    seen = O.update_bandwidth([1.0, 1.0, 1.0], [5.3e9, 3.6e9 * 2, 8.9e9 * 3], [1.0, 2.0, 3.0])
+    assert seen == [5.3e9, 3.6e9, 8.9e9]
+    assert O.assign_tiers(60, seen)[0] == [18, 12, 30]
+    assert B.mlpo_update_bandwidth([1.0, 2.0, 3.0], [10.0, 0.0, 9.0], [4.0, 5.0, 3.0]) == [2.5, 2.0, 3.0]
+
+
 def test_library_matches_oracle_exactly():
     rng = np.random.default_rng(1)
     for trial in range(400):
@@ -74,6 +90,32 @@ def test_library_matches_oracle_exactly():
         got = B.mlpo_assign_tiers(m, bw, cap)
         assert got[0] == want[0] and got[1] == want[1], (m, bw, cap, got, want)
     assert B.mlpo_update_bandwidth([5.3, 3.6], [10e9, 0.0], [2.5, 0.0]) == O.update_bandwidth([5.3, 3.6], [10e9, 0.0], [2.5, 0.0])
+
+
+def test_library_takes_the_exact_ceiling_of_shares_next_to_an_integer():
+    # Eq. 1's ceiling is of the exact quotient: a share a few 1e-13 above an integer rounds up, one as far below
+    # stays.  Cases where an estimate with a tolerance ends with a different allocation, then random ones of the kind.
+    cases = [(12, [2.0000000000002, 1.0, 4.0, 1.0], None, [4, 1, 6, 1]),
+             (14, [3.0, 1.0, 8.0, 3.9999999999996], None, [3, 0, 8, 3]),
+             (40, [9.0, 8.0, 6.0, 1.9999999999994], [10, 25, 33, 14], [10, 16, 11, 3]),
+             (26, [3.0, 6.0, 2.9999999999994], [24, 15, 23], [6, 14, 6])]
+    for m, bw, cap, want in cases:
+        assert O.assign_tiers(m, bw, cap)[0] == want
+        assert B.mlpo_assign_tiers(m, bw, cap)[0] == want, (m, bw, cap)
+    rng = np.random.default_rng(7)
+    for _ in range(3000):
+        n = int(rng.integers(2, 6))
+        m = int(rng.integers(1, 300))
+        bw = [float(x) for x in rng.integers(1, 12, size=n)]
+        j = int(rng.integers(0, n))
+        bw[j] = float(np.nextafter(bw[j], [0.0, 100.0][int(rng.integers(0, 2))])) if rng.random() < 0.5 else \
+            bw[j] * (1.0 + float(rng.integers(-9, 10)) * 1e-13)
+        want = O.assign_tiers(m, bw)
+        got = B.mlpo_assign_tiers(m, bw)
+        assert got[0] == want[0] and got[1] == want[1], (m, bw, got, want)
+    # bandwidths of very different size: the exact sum still decides
+    for bw in ([1e-30, 3e-30], [1e30, 1.0], [4.14e9, 239e9, 3.7e9]):
+        assert B.mlpo_assign_tiers(35, bw)[0] == O.assign_tiers(35, bw)[0]
 
 
 def test_library_argument_errors():
