@@ -6,11 +6,13 @@ middle and last elements, odd offsets), regenerated from the seeded generator.  
 (Section 3.2 "Cache-Friendly Ordering"), so windows are checked to the same bars as whole arrays: fp32 state max
 relative error 1e-6, bf16 copy and flag bit-exact, norm 1e-5.
 
-Config 3 runs at full size.  Configs 4 and 5 run with one fifth of their subgroups (same subgroup size, same tier
-fractions).  With MLPO_FULL_SIZE=1 config 4 runs whole (84 GB of fp32 state, 43 GB of it pinned) and config 5 with
-half of its subgroups (13 host-tier subgroups = 39 GB pinned): the test machines pin at most about 70 GB of host memory,
-less than the 75 GB the whole of config 5 needs.  The whole of config 5 runs with the file path: 21 host-tier
-subgroups pinned and 4 in a file."""
+Every config runs WHOLE: config 3 (15.6 GB pinned), config 4 (84 GB of fp32 state, 43 GB of it pinned) and config 5
+(105 GB of fp32 state, 75 GB of it offloaded).  The test machines pin at most about 70 GB of host memory, less than
+config 5 offloads, so config 5 keeps as many of its 25 offloaded subgroups in pinned memory as the machine allows (at
+most 21) and the rest in a file - the second path of the offloaded tier.  Its staged / direct variants without a
+file run on half of its subgroups (13 offloaded = 39 GB pinned).  If a machine refuses to pin what a case needs, the
+case falls back to the largest integer scale-down (same subgroup size, same tier fractions) that it does pin, and
+prints which size ran.  MLPO_SMALL=1 runs configs 4 and 5 at one fifth (for quick iterations)."""
 import os
 import time
 
@@ -26,7 +28,7 @@ from paper_2509_02480_amd import workloads as W  # noqa: E402
 
 from gpu_util import PinnedF32, Scratch, dev, max_rel_err  # noqa: E402
 
-FULL = os.environ.get("MLPO_FULL_SIZE", "0") == "1"
+SMALL = os.environ.get("MLPO_SMALL", "0") == "1"
 THREADS = 16
 WIN = 70_001
 
@@ -45,13 +47,16 @@ def phys_index(lo, hi, T):
     return (i // T) * (3 * T) + i % T
 
 
-def run_config(oracle, wl, tile, cfg_kind, n_slots=3, chunk=0, direct_blocks=64, n_file=0, file_path=None):
-    """n_file > 0 (direct mode): the last n_file host-tier subgroups keep their state in the file file_path instead of
-    pinned memory (the second path of the offloaded tier)."""
+def run_config(oracle, wl, tile, cfg_kind, n_slots=3, chunk=0, direct_blocks=64, n_file=0, file_path=None,
+               max_pinned=None):
+    """n_file > 0 (direct mode): at least the last n_file host-tier subgroups keep their state in the file file_path
+    instead of pinned memory (the second path of the offloaded tier), and so do those that the machine will not pin
+    (or that exceed max_pinned).  Without a file, a refusal to pin raises MemoryError."""
     pinned = []
     fds = []
     try:
-        _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned, n_file, file_path, fds)
+        _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned, n_file, file_path, fds,
+                    max_pinned)
     finally:
         torch.cuda.synchronize()
         for b in pinned:
@@ -62,7 +67,22 @@ def run_config(oracle, wl, tile, cfg_kind, n_slots=3, chunk=0, direct_blocks=64,
             os.unlink(file_path)
 
 
-def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned, n_file=0, file_path=None, fds=None):
+def run_largest_that_pins(oracle, wl, *args, **kw):
+    """The workload whole or, if the machine refuses to pin its offloaded tier, the largest scale-down that fits."""
+    for factor in (1, 2, 3, 5, 7):
+        w = wl if factor == 1 else wl.scaled_down(factor)
+        torch.cuda.empty_cache()
+        try:
+            run_config(oracle, w, *args, **kw)
+            say(f"SIZE RUN: {w.name} ({w.n_sub} of {wl.n_sub} subgroups, {w.n_host} offloaded)")
+            return
+        except MemoryError as e:
+            say(f"{w.name}: {e}; trying a smaller size")
+    raise MemoryError(f"{wl.name}: even one seventh of it cannot be pinned")
+
+
+def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinned, n_file=0, file_path=None, fds=None,
+                max_pinned=None):
     d = dev()
     M, T = wl.sub_elems, tile
     per = B.mlpo_state_floats(M, T)
@@ -76,7 +96,26 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
     states, descs, wins = [], [], []
     sumsq, flag = 0.0, 0
     host_ids = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
-    file_ids = host_ids[len(host_ids) - n_file:] if n_file else []
+    # pinned buffers first: how many the machine grants decides how many subgroups the file has to take
+    want_pinned = len(host_ids) - n_file
+    if max_pinned is not None:
+        want_pinned = min(want_pinned, max_pinned)
+    pinned_of = {}
+    for k in host_ids[:want_pinned]:
+        try:
+            pinned_of[k] = PinnedF32(per)
+            pinned.append(pinned_of[k])
+        except MemoryError:
+            if not n_file:
+                raise
+            say(f"  the machine pins {len(pinned_of)} subgroups ({len(pinned_of) * per * 4 / 1e9:.1f} GB), not "
+                f"{want_pinned}: the file takes the rest")
+            for _ in range(min(2, len(pinned_of))):      # room for the bounce buffers and the run's small buffers
+                k_last = max(pinned_of)
+                pinned.remove(pinned_of[k_last])
+                pinned_of.pop(k_last).free()
+            break
+    file_ids = [k for k in host_ids if k not in pinned_of] if n_file else []
     files = [None] * wl.n_sub
     fmap = None
     if file_ids:
@@ -100,8 +139,7 @@ def _run_config(oracle, wl, tile, cfg_kind, n_slots, chunk, direct_blocks, pinne
             files[k] = (fds[0], j * per * 4)
             st = ("file", j * per)          # read back with plain file reads once the run is over
         elif wl.tier(k) == 1:
-            buf = PinnedF32(per)
-            pinned.append(buf)
+            buf = pinned_of[k]
             st = buf.t
             buf.np[:] = 0
             buf.np.reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
@@ -198,23 +236,38 @@ def test_config3_full_size(oracle, cfg_kind, n_slots, chunk):
 
 
 def test_config4_mixed_tiers(oracle):
-    wl = W.C4 if FULL else W.C4.scaled_down(5)
-    run_config(oracle, wl, B.TILE_DEFAULT, "staged", n_slots=4, chunk=1 << 25)
+    wl = W.C4.scaled_down(5) if SMALL else W.C4
+    run_largest_that_pins(oracle, wl, B.TILE_DEFAULT, "staged", n_slots=4, chunk=1 << 25)
+
+
+def file_dir(tmp_path, need_bytes):
+    """Where the file of the second path lives: MLPO_FILE_DIR if set; else /dev/shm (pageable host memory, which keeps
+    the whole-size case short) when it has the room; else pytest's temporary directory on the disk."""
+    where = os.environ.get("MLPO_FILE_DIR")
+    if where:
+        return where
+    try:
+        st = os.statvfs("/dev/shm")
+        if st.f_bavail * st.f_frsize > need_bytes + (8 << 30):
+            return "/dev/shm"
+    except OSError:
+        pass
+    return str(tmp_path)
 
 
 def test_config5_with_the_file_path(oracle, tmp_path):
-    """Config 5 with part of the offloaded tier in a file.  With MLPO_FULL_SIZE=1 the config runs WHOLE: 10 subgroups
-    in HBM, 21 in pinned host memory (63 GB, what the test machines can pin) and 4 in a 12 GB file; otherwise one
-    fifth of it with 1 of its 5 host-tier subgroups in a file."""
-    wl = W.C5 if FULL else W.C5.scaled_down(5)
-    n_file = 4 if FULL else 1
-    where = os.environ.get("MLPO_FILE_DIR", str(tmp_path))      # e.g. /dev/shm: pageable host memory as the file
+    """Config 5 WHOLE, with part of the offloaded tier in a file: 10 subgroups in HBM, up to 21 in pinned host memory
+    (63 GB; fewer if the machine pins less) and the rest of the 25 - at least 4 - in a file."""
+    wl = W.C5.scaled_down(5) if SMALL else W.C5
+    n_file = 1 if SMALL else 4
+    per_bytes = B.mlpo_state_floats(wl.sub_elems, B.TILE_DEFAULT) * 4
+    where = file_dir(tmp_path, wl.n_host * per_bytes // 2)
     run_config(oracle, wl, B.TILE_DEFAULT, "direct", chunk=1 << 24, n_file=n_file,
                file_path=os.path.join(where, f"mlpo_c5_state_{os.getpid()}.bin"))
 
 
 @pytest.mark.parametrize("cfg_kind", ["staged", "direct"])
 def test_config5_mixed_tiers_with_clip(oracle, cfg_kind):
-    wl = W.C5.scaled_down(2) if FULL else W.C5.scaled_down(5)
+    wl = W.C5.scaled_down(5) if SMALL else W.C5.scaled_down(2)
     assert wl.max_norm == 1.0 and wl.loss_scale == 65536.0
-    run_config(oracle, wl, B.TILE_DEFAULT, cfg_kind, n_slots=2, chunk=1 << 24)
+    run_largest_that_pins(oracle, wl, B.TILE_DEFAULT, cfg_kind, n_slots=2, chunk=1 << 24)
