@@ -110,7 +110,7 @@ def resident_timed_steps(args, torch, B, wl, buf, scal, ws):
                 torch.cuda.synchronize()
                 # from here on every launch of the two streaming kernels carries its own begin / end timestamps
                 # (HIP events attached to the dispatch on this stream)
-                B.mlpo_set_option("time_kernels", 1)
+                B.mlpo_kernel_timing(True)
                 t_begin.record(stream)
             inject = wl.injects(s)
             if inject:
@@ -152,7 +152,7 @@ def resident_bench(args, torch, B, W, np, tile):
 
     upd_ms = B.mlpo_kernel_times(0)
     nrm_ms = B.mlpo_kernel_times(1)
-    B.mlpo_set_option("time_kernels", 0)
+    B.mlpo_kernel_timing(False)
     assert len(upd_ms) == args.steps and len(nrm_ms) == args.steps, (len(upd_ms), len(nrm_ms))
     inj_timed = [wl.injects(s) for s in range(args.warmup, total)]
     k_ms = [upd_ms[i] for i in range(args.steps) if not inj_timed[i]]   # a skipped step's launch exits at once
@@ -201,7 +201,9 @@ def resident_result(args, wl, primary, others):
                    "loss_scale": wl.loss_scale, "inf_every": wl.inject_every,
                    "applied_steps": primary["applied_steps"], "state_layout": primary["layout"],
                    "state_lead_elems": primary["lead"],
-                   "state": f"fp32 p/m/v + {args.half} grads + {args.half} params, all in HBM"},
+                   "state": f"fp32 p/m/v + {args.half} grads + {args.half} params, all in HBM",
+                   "timed_region": "every launch of the two streaming kernels carries an event pair for its own "
+                                   "duration, inside the clock (slightly pessimistic for value)"},
         "roofline": primary["roofline"],
         "norm_pass": primary["norm_pass"],
         "step_hbm_frac": primary["step_hbm_frac"],
@@ -211,35 +213,92 @@ def resident_result(args, wl, primary, others):
     return res
 
 
-def yardsticks(torch, B, update_GBs):
-    """What the memory system delivers for the update kernel's access pattern without its arithmetic
-    (mlpo_probe_bandwidth): a read-only, a write-only and an in-place read-modify-write sweep over a buffer of the
-    size of the workload's fp32 state, each timed over 30 launches between two events on one stream."""
+_ys = None
+
+
+def ys_lib():
+    """The benchmark's own yardstick kernels (bench_yardsticks.hip -> libbench_yardsticks.so, built by
+    __graft_entry__.build()); not part of the update library."""
+    global _ys
+    if _ys is None:
+        import ctypes as C
+        path = os.path.join(ROOT, "libbench_yardsticks.so")
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: run __graft_entry__.build() first")
+        L = C.CDLL(path)
+        L.ys_last_error.restype = C.c_char_p
+        L.ys_sweep.argtypes = [C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ys_update_pattern.argtypes = [C.c_void_p] * 5 + [C.c_uint64, C.c_int32, C.c_void_p]
+        L.ys_link.argtypes = [C.c_void_p] * 4 + [C.c_size_t, C.c_int32, C.POINTER(C.c_double)]
+        _ys = L
+    return _ys
+
+
+def ys_check(rc):
+    if rc != 0:
+        raise RuntimeError("yardstick: " + ys_lib().ys_last_error().decode())
+
+
+def timed_launches(torch, st, launch, reps=30, warm=3):
+    """Average duration in seconds of `reps` back-to-back launches on stream st (events around the whole run)."""
+    with torch.cuda.stream(st):
+        for _ in range(warm):
+            launch()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record(st)
+        for _ in range(reps):
+            launch()
+        t1.record(st)
+    st.synchronize()
+    return t0.elapsed_time(t1) * 1e-3 / reps
+
+
+def yardsticks(torch, wl, tile, update_GBs, planar_GBs, norm_GBs):
+    """What the memory system delivers for the update's access patterns without its arithmetic: read-only, write-only
+    and in-place sweeps over a buffer of the size of the workload's fp32 state; a read-only sweep of the size of its
+    gradients (what bounds the gradient pass: a 36 us kernel pays for its ramp and tail); and the update's own address
+    streams (three 16-byte loads and stores plus the two 8-byte streams per four elements) in both state layouts."""
+    L = ys_lib()
     d = torch.device("cuda:0")
-    nbytes = 1_500_000_000 // 16 * 16
-    buf = torch.ones(nbytes // 4, dtype=torch.float32, device=d)
     st = torch.cuda.Stream()
+    sp = st.cuda_stream
+    N = wl.n_total
+    nbytes = 12 * N // 16 * 16
+    buf = torch.ones(nbytes // 4, dtype=torch.float32, device=d)
     out = {"buffer_bytes": nbytes, "launches": 30}
     rates = {}
-    with torch.cuda.stream(st):
-        for name, kind, factor in (("read", B.PROBE_READ, 1), ("write", B.PROBE_WRITE, 1),
-                                   ("update_in_place", B.PROBE_UPDATE_IN_PLACE, 2)):
-            for _ in range(3):
-                B.mlpo_probe_bandwidth(kind, buf, nbytes, st)
-            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            t0.record(st)
-            for _ in range(30):
-                B.mlpo_probe_bandwidth(kind, buf, nbytes, st)
-            t1.record(st)
-            st.synchronize()
-            rates[name] = factor * nbytes * 30 / (t0.elapsed_time(t1) * 1e-3) / 1e9
-            out[name + "_GBs"] = round(rates[name], 1)
+    for name, kind, factor in (("read", 0, 1), ("write", 1, 1), ("update_in_place", 2, 2)):
+        dt = timed_launches(torch, st, lambda: ys_check(L.ys_sweep(kind, buf.data_ptr(), nbytes, sp)))
+        rates[name] = factor * nbytes / dt / 1e9
+        out[name + "_GBs"] = round(rates[name], 1)
+    gbytes = 2 * N // 16 * 16
+    dt = timed_launches(torch, st, lambda: ys_check(L.ys_sweep(0, buf.data_ptr(), gbytes, sp)), reps=100)
+    out["read_gradient_sized_GBs"] = round(gbytes / dt / 1e9, 1)
+    out["read_gradient_sized_bytes"] = gbytes
+    out["norm_pass_GBs"] = norm_GBs
+    out["norm_pass_vs_read_yardstick"] = round(norm_GBs / (gbytes / dt / 1e9), 4)
+    # the update's address streams, nothing else: planar (three arrays N floats apart) and tiled
+    n4 = N // 4 * 4
+    g16 = torch.zeros(n4, dtype=torch.int16, device=d)
+    h16 = torch.zeros(n4, dtype=torch.int16, device=d)
+    p_, m_, v_ = (buf[i * N:(i + 1) * N] for i in range(3))
+    dt = timed_launches(torch, st, lambda: ys_check(L.ys_update_pattern(p_.data_ptr(), m_.data_ptr(), v_.data_ptr(),
+                                                                         g16.data_ptr(), h16.data_ptr(), n4, 0, sp)))
+    out["update_pattern_planar_GBs"] = round(28 * n4 / dt / 1e9, 1)
+    nt = n4 // tile * tile          # whole layout tiles of the same buffer
+    dt = timed_launches(torch, st, lambda: ys_check(L.ys_update_pattern(buf.data_ptr(), None, None, g16.data_ptr(),
+                                                                         h16.data_ptr(), nt, tile, sp)))
+    out["update_pattern_tiled_GBs"] = round(28 * nt / dt / 1e9, 1)
     # the update moves 14 bytes in and 14 out per parameter: its time at the two one-way rates
     mix = 28.0 / (14.0 / rates["read"] + 14.0 / rates["write"])
     out["half_read_half_write_at_these_rates_GBs"] = round(mix, 1)
     out["update_kernel_GBs"] = update_GBs
     out["update_kernel_vs_in_place_yardstick"] = round(update_GBs / rates["update_in_place"], 4)
-    del buf
+    out["update_kernel_vs_its_pattern_tiled"] = round(update_GBs / out["update_pattern_tiled_GBs"], 4)
+    if planar_GBs:
+        out["update_kernel_planar_GBs"] = planar_GBs
+        out["update_kernel_vs_its_pattern_planar"] = round(planar_GBs / out["update_pattern_planar_GBs"], 4)
+    del buf, g16, h16
     torch.cuda.empty_cache()
     log(f"[bench] yardsticks {out}")
     return out
@@ -305,7 +364,10 @@ def cpu_baseline(args, W, np):
     for s in host:
         oracle.adamw_f32(s["p"], s["m"], s["v"], s["g"], s["p16"], ohp, 3 + reps, gmul)
     dt_single = time.perf_counter() - t0
-    return {"value": round(reps * n / dt / 1e9, 4), "unit": "Gparams/s", "cores": oracle.threads(), "kind": "oracle",
+    # the oracle's parallel driver runs one thread per core the process may use (its OpenMP default)
+    cores = min(oracle.threads(), len(os.sched_getaffinity(0)))
+    return {"value": round(reps * n / dt / 1e9, 4), "unit": "Gparams/s", "cores": cores, "kind": "oracle",
+            "omp_max_threads": oracle.threads(), "sched_getaffinity": len(os.sched_getaffinity(0)),
             "sample": f"first {n_sg} of {wl.n_sub} subgroups ({n} params) x {reps} steps (norm pass + update), "
                       f"{dt:.1f} s wall",
             "single_thread": {"value": round(n / dt_single / 1e9, 4), "unit": "Gparams/s", "cores": 1,
@@ -326,14 +388,17 @@ class StreamedBench:
         per = B.mlpo_state_floats(M, T)
         self.g_flat = torch.empty(wl.n_total, dtype=torch.int16, device=d)
         self.p16_flat = torch.zeros(wl.n_total, dtype=torch.int16, device=d)
-        self.keep, sgs = [], []
+        self.keep, sgs, self.pinned = [], [], []
         tmp = np.zeros(per // 3, np.float32)
         hg = np.empty(M, np.uint16)
         for k in range(wl.n_sub):
             # fp32 state in the tiled layout: one buffer per subgroup, pinned host memory or HBM by tier; m = v = 0
             W.fill_state(wl, k, tmp[:M], None, None, threads=args.threads)
             if wl.tier(k) == 1:
-                st = torch.zeros(per, dtype=torch.float32, pin_memory=True)
+                buf = PinnedF32(torch, np, per)         # exact size: torch's pinned allocator rounds up to 2^k
+                self.pinned.append(buf)
+                buf.np[:] = 0
+                st = torch.from_numpy(buf.np)
                 st.numpy().reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
             else:
                 st = torch.zeros(per, dtype=torch.float32, device=d)
@@ -355,6 +420,15 @@ class StreamedBench:
         log(f"[bench] {wl.name}: {wl.n_host} host-tier + {wl.n_sub - wl.n_host} HBM subgroups of {M}, "
             f"setup {time.time() - t0:.1f}s")
 
+    def release(self):
+        """Gives the pinned memory back (the large workloads need all the machine will pin)."""
+        self.torch.cuda.synchronize()
+        self.table = self.host_g_table = self.host_g_all = None
+        self.keep = []
+        for b in self.pinned:
+            b.free()
+        self.pinned = []
+
     def grads(self, k):
         return self.g_flat[k * self.M:(k + 1) * self.M]
 
@@ -362,34 +436,21 @@ class StreamedBench:
         return self.p16_flat[k * self.M:(k + 1) * self.M]
 
     def memcpy_reference(self):
-        """Plain pinned copies of one 400 MB subgroup array (torch copy_ = hipMemcpyAsync), each direction alone."""
+        """Plain pinned copies (hipMemcpyAsync) of one 400 MB subgroup array: each direction alone, then both
+        directions at once on two streams - the rate the link gives a pipeline that fetches and flushes at the same
+        time, which is what the update phase does.  GB/s per direction: (h2d alone, d2h alone, both at once)."""
+        import ctypes as C
         torch, M, wl = self.torch, self.M, self.wl
-        ref = torch.empty(M, dtype=torch.float32, device=self.d)
-        ref2 = torch.empty(M, dtype=torch.float32, device=self.d)
+        dst_dev = torch.empty(M, dtype=torch.float32, device=self.d)
+        src_dev = torch.zeros(M, dtype=torch.float32, device=self.d)
         host_k = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
-        hsrc, hdst = self.keep[host_k[0]][:M], self.keep[host_k[-1]][:M]
-
-        def timed(fn, reps=3):
-            fn()
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            for _ in range(reps):
-                fn()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t) / reps
-
-        def up():
-            with torch.cuda.stream(self.h2d):
-                ref.copy_(hsrc, non_blocking=True)
-
-        def down():
-            with torch.cuda.stream(self.d2h):
-                hdst.copy_(ref2, non_blocking=True)
-
-        saved = hdst.clone()
-        rates = round(4 * M / timed(up) / 1e9, 2), round(4 * M / timed(down) / 1e9, 2)
-        hdst.copy_(saved)
-        return rates
+        hsrc = self.keep[host_k[0]][:M]
+        hdst = torch.empty(M, dtype=torch.float32, pin_memory=True)
+        sec = (C.c_double * 3)()
+        torch.cuda.synchronize()
+        ys_check(ys_lib().ys_link(hsrc.data_ptr(), dst_dev.data_ptr(), src_dev.data_ptr(), hdst.data_ptr(), 4 * M, 4,
+                                  sec))
+        return tuple(round(4 * M / t / 1e9, 2) for t in sec)
 
     def table_with_host_gradients(self):
         """The same subgroups with the gradients of the host-tier ones in pinned host memory too."""
@@ -490,7 +551,7 @@ class StreamedBench:
         for s in range(args.stream_warmup + wl.steps):
             if s == args.stream_warmup:
                 self.torch.cuda.synchronize()
-                B.mlpo_set_option("time_kernels", 1)
+                B.mlpo_kernel_timing(True)
                 fetches_before = cache.fetches if cache is not None else 0
             # with a slot cache the processing order alternates (Section 3.2 "Cache-Friendly Ordering")
             order = list(range(wl.n_sub))[::-1] if (cache is not None and s % 2 == 1) else None
@@ -500,7 +561,7 @@ class StreamedBench:
         fetch_ms, flush_ms, kern_ms = B.mlpo_kernel_times(2), B.mlpo_kernel_times(3), B.mlpo_kernel_times(0)
         B.mlpo_kernel_times(1)
         B.mlpo_kernel_times(4)
-        B.mlpo_set_option("time_kernels", 0)
+        B.mlpo_kernel_timing(False)
         mean = sum(times) / len(times)
         gbs = 12 * self.n_host_params / mean / 1e9
         rec = {**self.describe(kind, arg), "steps": len(times), "ms_per_step": round(mean * 1e3, 2),
@@ -516,6 +577,7 @@ class StreamedBench:
         else:
             rec.update({"pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
                         "frac_of_one_way_memcpy": round(gbs / memcpy_peak, 4),
+                        "frac_of_bidir_memcpy": round(gbs / self.memcpy_bidir, 4),
                         "effective_io_GBs_paper_formula": self.effective_io(kind, arg, len(times), fetch_ms, flush_ms,
                                                                             kern_ms)})
             # host-side gradients cross the link with the state, and once more for a gradient pass
@@ -571,8 +633,9 @@ def streamed_bench(args, torch, B, W, np):
     wl = sb.wl
     out = {"workload": wl.name, "state_layout": f"tiled T={sb.T}", "host_tier_params": sb.n_host_params,
            "bytes_per_direction_per_step": 12 * sb.n_host_params, "pcie_nominal_GBs": PCIE_NOMINAL_GBS, "runs": []}
-    out["memcpy_h2d_GBs"], out["memcpy_d2h_GBs"] = sb.memcpy_reference()
+    out["memcpy_h2d_GBs"], out["memcpy_d2h_GBs"], out["memcpy_bidir_GBs_per_dir"] = sb.memcpy_reference()
     memcpy_peak = min(out["memcpy_h2d_GBs"], out["memcpy_d2h_GBs"])
+    sb.memcpy_bidir = out["memcpy_bidir_GBs_per_dir"]
     for kind, arg in args.stream_variants:
         out["runs"].append(sb.run_variant(kind, arg, memcpy_peak))
     # the cached runs move less data, so their "GB/s" is not a link rate: the best link rate is among the others
@@ -592,8 +655,12 @@ def streamed_bench(args, torch, B, W, np):
                 out["multipath"].append({"kind": kind, "error": f"{type(e).__name__}: {e}"})
                 log(f"[bench] multipath {kind} failed: {e}")
     g_flat, p16_flat = sb.g_flat, sb.p16_flat
-    sb.table = sb.host_g_table = None
+    sb.release()
     out["grad_accumulate"] = accumulate_bench(torch, B, g_flat, p16_flat, wl)
+    del sb, g_flat, p16_flat
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()         # pinned blocks torch still caches would count against the large workloads
     return out
 
 
@@ -766,13 +833,187 @@ def multipath_bench(args, torch, B, np, ctx, kind):
     return res
 
 
+_hip = None
+
+
+def hip_runtime(torch):
+    """The HIP runtime this process already uses (the one torch loaded), for pinned allocations of exact size:
+    torch's pinned allocator rounds requests up to a power of two, which would waste a third of what can be pinned."""
+    global _hip
+    if _hip is None:
+        import ctypes as C
+        torch.cuda.init()
+        path = [ln.split()[-1] for ln in open("/proc/self/maps") if "libamdhip64" in ln][0]
+        _hip = C.CDLL(path)
+        _hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+        _hip.hipHostFree.argtypes = [C.c_void_p]
+    return _hip
+
+
+class PinnedF32:
+    """n floats of page-locked host memory as a numpy array; MemoryError if the machine will not pin that much."""
+
+    def __init__(self, torch, np, n):
+        import ctypes as C
+        self.hip = hip_runtime(torch)
+        self.ptr = C.c_void_p()
+        if self.hip.hipHostMalloc(C.byref(self.ptr), 4 * n, 0) != 0 or not self.ptr.value:
+            self.ptr = None
+            raise MemoryError(f"cannot pin {4 * n / 1e9:.2f} GB")
+        self.np = np.ctypeslib.as_array((C.c_float * n).from_address(self.ptr.value))
+
+    def data_ptr(self):
+        return self.ptr.value
+
+    def free(self):
+        if self.ptr is not None:
+            self.np = None
+            self.hip.hipHostFree(self.ptr)
+            self.ptr = None
+
+
+def large_config_leg(args, torch, B, W, np, name, modes, bidir_GBs):
+    """One of the two large mixed-tier workloads WHOLE (BASELINE configs 4 and 5): HBM-tier subgroups resident,
+    offloaded subgroups in pinned host memory, and - where the machine will not pin all of them - the rest in a file
+    in /dev/shm (pageable host memory behind the second path).  Gradient pass + mlpo_stream_update per step, one
+    warm-up step and the workload's step count timed, per mode in `modes`."""
+    wl = W.CONFIGS[name]
+    d = torch.device("cuda:0")
+    M, T = wl.sub_elems, args.tile
+    per = B.mlpo_state_floats(M, T)
+    t_setup = time.time()
+    pinned, keep, fd, path = [], [], -1, None
+    rec = {"workload": wl.name, "params": wl.n_total, "subgroups": wl.n_sub, "subgroup_elems": M,
+           "loss_scale": wl.loss_scale, "max_norm": wl.max_norm, "runs": []}
+    try:
+        g_flat = torch.empty(wl.n_total, dtype=torch.int16, device=d)
+        p16_flat = torch.zeros(wl.n_total, dtype=torch.int16, device=d)
+        tmp = np.zeros(per // 3, np.float32)
+        hg = np.empty(M, np.uint16)
+        homes, file_ids = {}, []
+        for k in range(wl.n_sub):
+            if wl.tier(k) == 1 and not file_ids:
+                try:
+                    homes[k] = PinnedF32(torch, np, per)
+                    pinned.append(homes[k])
+                    continue
+                except MemoryError:
+                    pass
+            if wl.tier(k) == 1:
+                file_ids.append(k)          # no more can be pinned: this one and the later ones live in the file
+        if file_ids:
+            if pinned:                      # leave room for the bounce buffers
+                file_ids.insert(0, max(homes))
+                homes.pop(max(homes))
+                pinned.pop().free()
+            path = f"/dev/shm/mlpo_bench_{name}_{os.getpid()}.bin"
+            fd = os.open(path, os.O_RDWR | os.O_CREAT | os.O_TRUNC, 0o600)
+        tiled = np.zeros(per, np.float32) if file_ids else None
+        sgs, files = [], []
+        for k in range(wl.n_sub):
+            W.fill_state(wl, k, tmp[:M], None, None, threads=args.threads)      # m = v = 0
+            W.fill_grads(wl, k, 0, hg, threads=args.threads)
+            gk, pk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
+            gk.copy_(torch.from_numpy(hg.view(np.int16)))
+            if k in file_ids:
+                tiled.reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
+                off = file_ids.index(k) * per * 4
+                os.pwrite(fd, tiled.data, off)      # real pages, no holes
+                sgs.append(B.SubgroupC(None, None, None, gk.data_ptr(), pk.data_ptr(), M, B.TIER_FILE, T))
+                files.append((fd, off))
+                continue
+            files.append(None)
+            if k in homes:
+                homes[k].np[:] = 0
+                homes[k].np.reshape(-1, 3, T)[:, 0, :] = tmp.reshape(-1, T)
+                sgs.append(B.tiled_subgroup(homes[k].data_ptr(), gk, pk, n=M, tier=B.TIER_HOST, tile_elems=T))
+            else:
+                st = torch.zeros(per, dtype=torch.float32, device=d)
+                st.view(-1, 3, T)[:, 0, :].copy_(torch.from_numpy(tmp).view(-1, T))
+                keep.append(st)
+                sgs.append(B.tiled_subgroup(st, gk, pk, n=M, tier=B.TIER_HBM, tile_elems=T))
+        del tiled
+        table = B.SubgroupTable(sgs)
+        n_off = wl.n_host
+        rec.update({"hbm_subgroups": wl.n_sub - n_off, "pinned_subgroups": len(homes), "file_subgroups": len(file_ids),
+                    "file": path, "offloaded_params": n_off * M, "bytes_per_direction_per_step": 12 * n_off * M,
+                    "setup_s": round(time.time() - t_setup, 1)})
+        ws_bytes = B.mlpo_norm_workspace_bytes()
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=d)
+        scal = torch.zeros(4, dtype=torch.float32, device=d)
+        hp = B.HParams(**wl.hp.__dict__)
+        h2d, cmp_ = torch.cuda.Stream(), torch.cuda.Stream()
+        applied = 0
+        for mode in modes:
+            stg = bounce = None
+            chunk = 1 << 24
+            if file_ids or mode == "direct":
+                if file_ids:
+                    need = B.mlpo_stream_bounce_bytes(table, args.file_slots, chunk)
+                    bounce = PinnedF32(torch, np, need // 4)
+                    pinned.append(bounce)
+                    cfg = B.direct_cfg(h2d, cmp_, 64, chunk_elems=chunk, files=files, bounce=bounce.data_ptr(),
+                                       bounce_bytes=need, file_slots=args.file_slots, file_threads=8)
+                else:
+                    cfg = B.direct_cfg(h2d, cmp_, 64)
+                what = {"mode": "direct" + (", two paths (pinned + file in /dev/shm)" if file_ids else ""),
+                        "direct_blocks": 64}
+            else:
+                need = B.mlpo_stream_staging_bytes(table, 4, chunk)
+                stg = torch.empty(need, dtype=torch.uint8, device=d)
+                cfg = B.stream_cfg(4, stg, need, None, cmp_, None, chunk)
+                what = {"mode": "staged", "n_slots": 4, "chunk_elems": chunk}
+            times = []
+            for s_ in range(1 + wl.steps):
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ws, ws_bytes, scal, cmp_)
+                ok = B.mlpo_stream_update(table, None, hp, applied + 1, scal, cfg)
+                cmp_.synchronize()
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t
+                assert ok, "a step of finite gradients was skipped"
+                applied += 1
+                if s_ >= 1:
+                    times.append(dt)
+            mean = sum(times) / len(times)
+            gbs = 12 * n_off * M / mean / 1e9
+            sc = scal.cpu().numpy()
+            run = {**what, "steps": len(times), "ms_per_step": round(mean * 1e3, 2),
+                   "min_ms": round(min(times) * 1e3, 2), "Gparams_s": round(wl.n_total / mean / 1e9, 3),
+                   "pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
+                   "frac_of_bidir_memcpy": round(gbs / bidir_GBs, 4) if bidir_GBs else None,
+                   "grad_norm": float(sc[0]), "clip_coef": float(sc[1])}
+            rec["runs"].append(run)
+            log(f"[bench] {wl.name} {run}")
+            del stg, cfg
+            if bounce is not None:
+                pinned.remove(bounce)
+                bounce.free()
+    except (MemoryError, OSError, RuntimeError) as e:
+        rec["error"] = f"{type(e).__name__}: {e}"
+        log(f"[bench] {name} leg failed: {e}")
+    finally:
+        torch.cuda.synchronize()
+        for b_ in pinned:
+            b_.free()
+        if fd >= 0:
+            os.close(fd)
+        if path and os.path.exists(path):
+            os.unlink(path)
+        keep.clear()
+        g_flat = p16_flat = None
+        torch.cuda.empty_cache()
+    return rec
+
+
 def accumulate_bench(torch, B, acc_dev, g_dev, wl):
     """mlpo_grad_accumulate at the shard's size: the accumulation buffer in HBM (6 bytes of HBM traffic per element)
     and in pinned host memory (2 bytes per element over the link in each direction), 4 micro-batches each."""
     n = acc_dev.numel()
     M = wl.sub_elems
     res = {"elements": n, "micro_batches": 4}
-    B.mlpo_set_option("time_kernels", 1)
+    B.mlpo_kernel_timing(True)
     for j in range(5):          # the first call (first=True: a copy, 4 bytes per element) doubles as warm-up
         B.mlpo_grad_accumulate(acc_dev, g_dev, n, first=(j == 0))
     torch.cuda.synchronize()
@@ -808,7 +1049,7 @@ def accumulate_bench(torch, B, acc_dev, g_dev, wl):
             res[label]["pcie_GBs_per_dir"] = round(2 * nn / avg / 1e6, 2)
         else:
             res[label]["achieved_GBs"] = round(6 * nn / avg / 1e6, 1)
-    B.mlpo_set_option("time_kernels", 0)
+    B.mlpo_kernel_timing(False)
     res["pinned_host_best"] = best
     log(f"[bench] grad_accumulate {res}")
     return res
@@ -845,6 +1086,8 @@ def main():
                          "gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep their "
                          "subgroups and alternating order)")
     ap.add_argument("--stream-warmup", type=int, default=2)
+    ap.add_argument("--large", default="C4,C5",
+                    help="comma list of the large mixed-tier workloads to run whole after the streamed one, or 'none'")
     ap.add_argument("--multipath", default="disk,shm",
                     help="comma list of file kinds for the two-path run on the streamed workload: disk (a file in "
                          "--file-dir, O_DIRECT), shm (a file in /dev/shm), or 'none'")
@@ -864,7 +1107,6 @@ def main():
     ap.add_argument("--cpu-subgroups", type=int, default=9)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--threads", type=int, default=16)
-    ap.add_argument("--option", action="append", default=[], help="library tuning option key=value")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run 1 GiB copy kernels (reference traffic for profiler byte counters)")
     args = ap.parse_args()
@@ -883,22 +1125,39 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     B.lib()  # fails loudly if the HIP library is not built
-    for opt in args.option:
-        k, _, v = opt.partition("=")
-        B.mlpo_set_option(k, int(v))
     layouts = {"tiled": [args.tile], "planar": [0], "both": [args.tile, 0]}[args.layout]
     runs = [resident_bench(args, torch, B, W, np, t) for t in layouts]
     res = resident_result(args, W.CONFIGS[args.workload], runs[0], runs[1:])
     if args.calib_copy:
         calibration_copies(torch)
     if not args.no_yardsticks:
-        res["yardsticks"] = yardsticks(torch, B, res["roofline"]["achieved"])
+        planar = [r for r in runs if r["layout"] == "planar"]
+        res["yardsticks"] = yardsticks(torch, W.CONFIGS[args.workload], args.tile, res["roofline"]["achieved"],
+                                       planar[0]["roofline"]["achieved"] if planar else None,
+                                       res["norm_pass"]["achieved_GBs"])
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(args, W, np)
     else:
         res["cpu_baseline"] = None
     if args.streamed != "none":
-        res["streamed"] = streamed_bench(args, torch, B, W, np)
+        res["streamed"] = st = streamed_bench(args, torch, B, W, np)
+        best = st["best"]
+        # the second half of the metric: effective GB/s per direction over the host link, against the nominal rate of
+        # PCIe 5.0 x16 and, as yardsticks, what plain pinned copies reach on this machine
+        res["roofline_streamed"] = {
+            "bound": "pcie", "achieved": best["pcie_GBs_per_dir"], "peak": PCIE_NOMINAL_GBS, "unit": "GB/s per direction",
+            "frac": best["frac_nominal"], "workload": st["workload"], "mode": best["mode"],
+            "ms_per_step": best["ms_per_step"], "bytes_per_direction_per_step": st["bytes_per_direction_per_step"],
+            "yardstick_memcpy_bidir_GBs_per_dir": st["memcpy_bidir_GBs_per_dir"],
+            "yardstick_memcpy_one_way_GBs": [st["memcpy_h2d_GBs"], st["memcpy_d2h_GBs"]],
+            "frac_of_bidir_memcpy": round(best["pcie_GBs_per_dir"] / st["memcpy_bidir_GBs_per_dir"], 4)}
+        torch.cuda.empty_cache()
+        large = []
+        for name in [x for x in args.large.split(",") if x and x != "none"]:
+            modes = ["staged", "direct"] if name == "C4" else ["direct"]
+            large.append(large_config_leg(args, torch, B, W, np, name, modes, st["memcpy_bidir_GBs_per_dir"]))
+        if large:
+            res["streamed_large"] = large
     print(json.dumps(res), flush=True)
 
 
