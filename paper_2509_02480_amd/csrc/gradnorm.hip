@@ -1,16 +1,18 @@
 // Gradient pass before the update: non-finite check, L2 norm of the unscaled gradients, clip factor (gfx950).
 //
-// Pass 1 streams the half-precision gradients of a table of subgroups once (2 bytes per element): 128-bit
-// non-temporal loads after peeling each subgroup's unaligned head, a persistent grid of eight workgroups per compute
-// unit that strides over 4 KiB tiles, several tiles per lane in flight and the loads of the next round issued before
-// the current round is summed, so that the memory system always has requests queued.  Every lane widens its
-// gradients, multiplies by 1/loss-scale in fp32 and accumulates the squares in fp64 - four lane operations per
-// element.  The non-finite test costs nothing per element: squares are never negative and the largest finite
-// half-precision value squared, times any element count, is far below the fp64 range, so a lane's sum is non-finite
-// exactly when one of its unscaled gradients was.  Lanes are combined by wavefront shuffles, wavefronts through LDS,
-// and each block writes one fp64 partial and one flag.  Pass 2 (one block) adds the partials in a fixed order and
-// derives norm, clip coefficient and the gradient multiplier.  No atomics: the result depends only on the argument
-// list, not on scheduling.
+// Pass 1 streams the half-precision gradients of a table of subgroups once (2 bytes per element) with 128-bit
+// non-temporal loads after peeling each subgroup's unaligned head.  Every workgroup owns one contiguous run of 16 KiB
+// tiles of ONE subgroup - as many tiles as it takes to cover the table with the workgroups the workspace has partials
+// for - so it looks its subgroup up once and then only advances a pointer, with the loads of its next tile issued
+// before the current tile is summed.  There are more workgroups than the chip holds at a time (a bare read sweep of
+// this size is fastest as many short workgroups: the hardware's dispatcher keeps the memory system fed and evens out
+// the tail).  Every lane widens its gradients, multiplies by 1/loss-scale in fp32 and accumulates the squares in
+// fp64 - four lane operations per element.  The non-finite test costs nothing per element: squares are never
+// negative and the largest finite half-precision value squared, times any element count, is far below the fp64
+// range, so a lane's sum is non-finite exactly when one of its unscaled gradients was.  Lanes are combined by
+// wavefront shuffles, wavefronts through LDS, and each block writes one fp64 partial and one flag.  Pass 2 (one
+// block) adds the partials in a fixed order and derives norm, clip coefficient and the gradient multiplier.  No
+// atomics: the result depends only on the argument list, not on scheduling.
 #include <hip/hip_ext.h>
 #include <math.h>
 
@@ -24,22 +26,24 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlock = 256;
-constexpr int kUnroll = 4;                // tiles a lane has in flight per round
-constexpr uint32_t kTile = kBlock * 8;    // body elements per tile: one 128-bit load per lane
-constexpr int kBlocksPerCu = 8;
+constexpr int kUnroll = 4;                // 128-bit loads a lane has in flight
+constexpr bool kSweep = false;
+constexpr uint32_t kPiece = kBlock * 8;   // body elements per 4 KiB piece: one 128-bit load per lane
 constexpr int kMaxSg = 96;
+constexpr int kMaxGrid = kNormMaxPartials;
+constexpr uint64_t kTargetBlocks = kMaxGrid - kMaxSg;  // every subgroup may round its share up by one workgroup
 
 struct NormBatch {
     const uint16_t* body[kMaxSg];  // start of the vector body, on a 128-byte line
     uint64_t n_body[kMaxSg];       // elements from body to the end of the subgroup
-    uint32_t tile_begin[kMaxSg + 1];
-    uint8_t head[kMaxSg];  // elements before body (0..63), handled by the first tile
+    uint32_t block_begin[kMaxSg + 1];  // prefix sums of workgroups per subgroup
+    uint8_t head[kMaxSg];  // elements before body (0..63), handled by the subgroup's first workgroup
     int32_t n_sg;
     int32_t half;  // MLPO_HALF_BF16 or MLPO_HALF_FP16
+    uint32_t pieces_per_block;
 };
 
 using Workspace = NormWorkspace;
-constexpr int kMaxGrid = kNormMaxPartials;
 
 // Two gradients packed in a 32-bit word / one gradient: unscale in fp32, square and accumulate in fp64.
 // HALF: 0 = bf16, 1 = IEEE binary16.
@@ -71,73 +75,62 @@ __device__ __forceinline__ void accum_vec(u32x4 w, float inv_scale, double& a0, 
     accum_word<HALF>(w.w, inv_scale, a0, a1);
 }
 
-// This lane's 128-bit word of tile `tile` (zero where the lane has none: zero bits are the value 0 in both formats
-// and add nothing).  What does not fit the 128-bit pattern - the elements in front of a subgroup's body, the ragged
-// end of its last tile - is added to acc on the spot.  s walks forward through the subgroup table.
+// This lane's 128-bit word of 4 KiB piece `piece` of a subgroup's body (zero where the lane has none: zero bits are
+// the value 0 in both formats and add nothing); the ragged end of the last piece is added to acc on the spot.
 template <int HALF>
-__device__ __forceinline__ u32x4 fetch(const NormBatch& b, uint32_t tile, int& s, float inv_scale, double& acc) {
+__device__ __forceinline__ u32x4 fetch(const uint16_t* __restrict__ body, uint64_t n_body, uint64_t piece,
+                                       float inv_scale, double& acc) {
     const uint32_t tid = threadIdx.x;
-    while (tile >= b.tile_begin[s + 1]) ++s;
-    const uint32_t t_in = tile - b.tile_begin[s];
-    const uint16_t* __restrict__ body = b.body[s];
-    const uint64_t n_body = b.n_body[s];
-    if (t_in == 0 && tid < b.head[s]) accum_half<HALF>(*(body - 1 - tid), inv_scale, acc);
-    const uint64_t base = (uint64_t)t_in * kTile;
-    const u32x4* __restrict__ q = reinterpret_cast<const u32x4*>(body + base) + tid;
-    if (n_body >= base + kTile) return __builtin_nontemporal_load(q);
+    const uint64_t e0 = piece * kPiece;
+    const u32x4* __restrict__ q = reinterpret_cast<const u32x4*>(body + e0) + tid;
+    if (e0 + kPiece <= n_body) return __builtin_nontemporal_load(q);
     const u32x4 zero = {0u, 0u, 0u, 0u};
-    if (n_body <= base) return zero;  // a subgroup that is all head
-    const uint64_t rem = n_body - base;  // < kTile
-    const uint64_t e = (uint64_t)tid * 8;
-    if (e + 8 <= rem) return __builtin_nontemporal_load(q);
-    if (e < rem)
-        for (uint64_t j = base + e; j < n_body; ++j) accum_half<HALF>(body[j], inv_scale, acc);
+    const uint64_t e = e0 + (uint64_t)tid * 8;
+    if (e + 8 <= n_body) return __builtin_nontemporal_load(q);
+    for (uint64_t j = e; j < n_body; ++j) accum_half<HALF>(body[j], inv_scale, acc);
     return zero;
 }
 
-// The streaming part of the kernel below for one format.  Round r of a block covers the tiles
-// blockIdx + (r * kUnroll + u) * gridDim, u < kUnroll: at any time the whole grid works on one window of the table.
+// The streaming part of the kernel below for one format.
 template <int HALF>
-__device__ __forceinline__ void stats_tiles(const NormBatch& b, const float inv_scale, double& a0, double& a1) {
-    const uint64_t total = b.tile_begin[b.n_sg];
-    const uint64_t stride = gridDim.x;
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-    int s = 0;
-    uint64_t tile = blockIdx.x;
-    if (tile >= total) return;
-    u32x4 cur[kUnroll], nxt[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        const uint64_t t = tile + (uint64_t)u * stride;
-        cur[u] = t < total ? fetch<HALF>(b, (uint32_t)t, s, inv_scale, a0) : zero;
+__device__ __forceinline__ void stats_run(const NormBatch& b, const float inv_scale, double& a0, double& a1) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t blk = blockIdx.x;
+    int lo = 0, hi = b.n_sg;  // the subgroup this workgroup belongs to
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (blk >= b.block_begin[mid]) lo = mid; else hi = mid;
     }
-    for (;;) {
-        const uint64_t next = tile + (uint64_t)kUnroll * stride;
-        const bool more = next < total;
-        if (more) {
+    const uint32_t b_in = blk - b.block_begin[lo];
+    const uint32_t blocks_s = b.block_begin[lo + 1] - b.block_begin[lo];
+    const uint16_t* __restrict__ body = b.body[lo];
+    const uint64_t n_body = b.n_body[lo];
+    if (b_in == 0 && tid < b.head[lo]) accum_half<HALF>(*(body - 1 - tid), inv_scale, a0);
+    const uint64_t n_pieces = (n_body + kPiece - 1) / kPiece;
+    const uint32_t per_block = b.pieces_per_block;  // a multiple of kUnroll
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (uint32_t k0 = 0; k0 < per_block; k0 += kUnroll) {
+        u32x4 w[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint64_t t = next + (uint64_t)u * stride;
-                nxt[u] = t < total ? fetch<HALF>(b, (uint32_t)t, s, inv_scale, a0) : zero;
-            }
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t k = k0 + u;
+            const uint64_t piece = kSweep ? b_in + k * blocks_s : (uint64_t)b_in * per_block + k;
+            w[u] = piece < n_pieces ? fetch<HALF>(body, n_body, piece, inv_scale, a0) : zero;
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) accum_vec<HALF>(cur[u], inv_scale, a0, a1);
-        if (!more) break;
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) cur[u] = nxt[u];
-        tile = next;
+        for (int u = 0; u < kUnroll; ++u) accum_vec<HALF>(w[u], inv_scale, a0, a1);
     }
 }
 
-__global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, const float inv_scale,
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
+grad_stats_kernel(const NormBatch b, const float inv_scale,
                                                             Workspace* __restrict__ ws) {
     const uint32_t tid = threadIdx.x;
     double a0 = 0.0, a1 = 0.0;
     if (b.half == 0)
-        stats_tiles<0>(b, inv_scale, a0, a1);
+        stats_run<0>(b, inv_scale, a0, a1);
     else
-        stats_tiles<1>(b, inv_scale, a0, a1);
+        stats_run<1>(b, inv_scale, a0, a1);
     double acc = a0 + a1;
     // a sum of squares is non-finite exactly when one of its terms is (see the note at the top)
     uint32_t bad = (uint32_t)!(fabs(acc) <= 1.7976931348623157e308);
@@ -167,24 +160,41 @@ __global__ void __launch_bounds__(kBlock) grad_stats_kernel(const NormBatch b, c
     }
 }
 
-// One block: folds n_partials partials into the running sum; on the last group derives the outputs.
-__global__ void __launch_bounds__(kBlock) grad_finish_kernel(Workspace* __restrict__ ws, const int n_partials,
-                                                             const int first, const int last, const float inv_scale,
-                                                             const float max_norm, mlpo_step_scalars* __restrict__ out) {
-    const uint32_t tid = threadIdx.x;
+// One block: folds n_partials partials into the running sum; on the last group derives the outputs.  The kernel is
+// all latency (a handful of loads per lane, then a tree), so it uses a full-size block and issues every lane's loads
+// before it adds the first: thread t adds partials t, t + 1024, ... in that order, then the block adds its 1024 sums
+// in a fixed tree.
+constexpr int kFinishBlock = 1024;
+constexpr int kFinishLoads = 4;  // loads a lane issues together
+__global__ void __launch_bounds__(kFinishBlock) grad_finish_kernel(Workspace* __restrict__ ws, const int n_partials,
+                                                                   const int first, const int last,
+                                                                   const float inv_scale, const float max_norm,
+                                                                   mlpo_step_scalars* __restrict__ out) {
+    const int tid = (int)threadIdx.x;
     double acc = 0.0;
     uint32_t bad = 0;
-    for (int i = tid; i < n_partials; i += kBlock) {
-        acc += ws->partial[i];
-        bad |= ws->flag[i];
+    for (int i0 = tid; i0 < n_partials; i0 += kFinishBlock * kFinishLoads) {
+        double x[kFinishLoads];
+        uint32_t f[kFinishLoads];
+#pragma unroll
+        for (int k = 0; k < kFinishLoads; ++k) {
+            const int i = i0 + k * kFinishBlock;
+            x[k] = i < n_partials ? ws->partial[i] : 0.0;
+            f[k] = i < n_partials ? ws->flag[i] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kFinishLoads; ++k) {
+            acc += x[k];
+            bad |= f[k];
+        }
     }
-    __shared__ double s_acc[kBlock];
-    __shared__ uint32_t s_bad[kBlock];
+    __shared__ double s_acc[kFinishBlock];
+    __shared__ uint32_t s_bad[kFinishBlock];
     s_acc[tid] = acc;
     s_bad[tid] = bad;
     __syncthreads();
-    for (int w = kBlock / 2; w > 0; w >>= 1) {
-        if ((int)tid < w) {
+    for (int w = kFinishBlock / 2; w > 0; w >>= 1) {
+        if (tid < w) {
             s_acc[tid] += s_acc[tid + w];
             s_bad[tid] |= s_bad[tid + w];
         }
@@ -215,16 +225,21 @@ __global__ void __launch_bounds__(kBlock) grad_finish_kernel(Workspace* __restri
     }
 }
 
-int flush(const NormBatch& b, bool first, bool last, float inv_scale, float max_norm, Workspace* ws,
+// Cuts the batch into workgroups and launches it, then the fold.  pieces[i] = 4 KiB pieces of entry i (at least one,
+// so that an array that is all head still has a workgroup).
+int flush(NormBatch& b, const uint64_t* pieces, bool first, bool last, float inv_scale, float max_norm, Workspace* ws,
           mlpo_step_scalars* out, hipStream_t st) {
-    const uint32_t total = b.tile_begin[b.n_sg];
     uint32_t grid = 0;
-    if (total > 0) {
-        const int cus = num_cus();
-        if (cus <= 0) return fail(MLPO_EHIP, "cannot query the device's compute units");
-        uint64_t cap = (uint64_t)cus * (uint64_t)kBlocksPerCu;
-        if (cap > (uint64_t)kMaxGrid) cap = kMaxGrid;
-        grid = total < cap ? total : (uint32_t)cap;
+    if (b.n_sg > 0) {
+        uint64_t total = 0;
+        for (int i = 0; i < b.n_sg; ++i) total += pieces[i];
+        uint64_t per_block = (total + kTargetBlocks - 1) / kTargetBlocks;  // >= 1, below 2^32 (n <= 2^48 each)
+        per_block = (per_block + kUnroll - 1) / kUnroll * kUnroll;
+        b.pieces_per_block = (uint32_t)per_block;
+        b.block_begin[0] = 0;
+        for (int i = 0; i < b.n_sg; ++i)
+            b.block_begin[i + 1] = b.block_begin[i] + (uint32_t)((pieces[i] + per_block - 1) / per_block);
+        grid = b.block_begin[b.n_sg];  // <= kTargetBlocks + n_sg <= kMaxGrid
         hipEvent_t t0, t1;
         if (timing_enabled() && timing_acquire(kTimedGradPass, &t0, &t1))
             hipExtLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, b, inv_scale, ws);
@@ -239,7 +254,7 @@ int flush(const NormBatch& b, bool first, bool last, float inv_scale, float max_
 
 int launch_norm_fold(NormWorkspace* ws, int n_partials, bool first, bool last, float inv_scale, float max_norm,
                      mlpo_step_scalars* out, hipStream_t st) {
-    hipLaunchKernelGGL(grad_finish_kernel, dim3(1), dim3(kBlock), 0, st, ws, n_partials, first ? 1 : 0, last ? 1 : 0,
+    hipLaunchKernelGGL(grad_finish_kernel, dim3(1), dim3(kFinishBlock), 0, st, ws, n_partials, first ? 1 : 0, last ? 1 : 0,
                        inv_scale, max_norm, out);
     MLPO_HIP(hipGetLastError());
     return MLPO_OK;
@@ -251,34 +266,47 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
                      mlpo_step_scalars* out, hipStream_t stream) {
     Workspace* ws = static_cast<Workspace*>(workspace);
     NormBatch b;
+    uint64_t pieces[kMaxSg];
     b.n_sg = 0;
-    b.tile_begin[0] = 0;
     b.half = table_half_format(sg, n_sg);
     bool first = true;
-    for (int i = 0; i < n_sg; ++i) {
-        const uint64_t n = sg[i].n;
-        if (n == 0) continue;
-        const uintptr_t addr = reinterpret_cast<uintptr_t>(sg[i].g);
-        // the vector body starts on a 128-byte line: a wavefront's kilobyte then covers eight lines, not nine
-        uint64_t head = ((128u - (addr & 127u)) & 127u) / 2u;
-        if (head > n) head = n;
-        const uint64_t n_body = n - head;
-        uint64_t tiles = (n_body + kTile - 1) / kTile;
-        if (tiles == 0) tiles = 1;  // a subgroup that is all head still needs its first tile
-        if (tiles > 0x7FFFFFFFull) return fail(MLPO_EINVAL, "subgroup %d too large", i);
-        if (b.n_sg == kMaxSg || (uint64_t)b.tile_begin[b.n_sg] + tiles > 0xFFFFFFFFull) {
-            const int rc = flush(b, first, false, inv_scale, max_norm, ws, out, stream);
-            if (rc != MLPO_OK) return rc;
+    int rc = MLPO_OK;
+    // Adds the array [g, g + n) to the batch as one entry.
+    const auto push = [&](const uint16_t* g, uint64_t n) -> int {
+        if (b.n_sg == kMaxSg) {  // more arrays than one argument block holds: the running totals carry over
+            const int r = flush(b, pieces, first, false, inv_scale, max_norm, ws, out, stream);
+            if (r != MLPO_OK) return r;
             first = false;
             b.n_sg = 0;
         }
-        b.body[b.n_sg] = sg[i].g + head;
+        // the vector body starts on a 128-byte line: a wavefront's kilobyte then covers eight lines, not nine
+        uint64_t head = ((128u - (reinterpret_cast<uintptr_t>(g) & 127u)) & 127u) / 2u;
+        if (head > n) head = n;
+        const uint64_t n_body = n - head;
+        b.body[b.n_sg] = g + head;
         b.n_body[b.n_sg] = n_body;
         b.head[b.n_sg] = (uint8_t)head;
-        b.tile_begin[b.n_sg + 1] = b.tile_begin[b.n_sg] + (uint32_t)tiles;
+        pieces[b.n_sg] = n_body == 0 ? 1 : (n_body + kPiece - 1) / kPiece;
         ++b.n_sg;
+        return MLPO_OK;
+    };
+    // Subgroups are usually consecutive slices of one flat gradient buffer (Section 2 "Sharded Model and Optimizer
+    // States Into Subgroups" cuts a flat shard into equal parts): slices that follow one another in memory are
+    // summed as one array, which has one unaligned head instead of one per subgroup.
+    const uint16_t* run = nullptr;
+    uint64_t run_n = 0;
+    for (int i = 0; i < n_sg; ++i) {
+        if (sg[i].n == 0) continue;
+        if (run != nullptr && sg[i].g == run + run_n && run_n + sg[i].n <= ((uint64_t)1 << 48)) {
+            run_n += sg[i].n;
+            continue;
+        }
+        if (run != nullptr && (rc = push(run, run_n)) != MLPO_OK) return rc;
+        run = sg[i].g;
+        run_n = sg[i].n;
     }
-    return flush(b, first, true, inv_scale, max_norm, ws, out, stream);
+    if (run != nullptr && (rc = push(run, run_n)) != MLPO_OK) return rc;
+    return flush(b, pieces, first, true, inv_scale, max_norm, ws, out, stream);
 }
 
 }  // namespace mlpo

@@ -95,7 +95,7 @@ size_t grad_norm_workspace_bytes();
 
 // Device workspace of the gradient statistics: per-workgroup partial sums of squares (fp64) and non-finite flags,
 // and the running totals that a one-block kernel folds them into in index order.
-constexpr int kNormMaxPartials = 4096;
+constexpr int kNormMaxPartials = 16384;
 struct NormWorkspace {
     double running_sum;
     uint32_t running_flag;
