@@ -319,12 +319,17 @@ typedef struct {
  *   host-tier kernel is enqueued on the h2d stream, the HBM-tier kernel on the compute stream. */
 #define MLPO_STREAM_STAGED 0
 #define MLPO_STREAM_DIRECT 1
+#define MLPO_CHUNK_WHOLE UINT64_MAX
 typedef struct {
     int32_t n_slots;       /* staged: staging slots = bound on subgroups (or chunks) in flight; 1..MLPO_MAX_SLOTS */
     int32_t mode;          /* MLPO_STREAM_STAGED or MLPO_STREAM_DIRECT */
-    uint64_t chunk_elems;  /* staged: 0 = a whole subgroup per transfer; else transfers of this many elements (a
-                              multiple of 4, and of every tile_elems in use).  Direct mode with file-tier
-                              subgroups: the size of the pieces both paths work in; otherwise unused there */
+    uint64_t chunk_elems;  /* elements per transfer of an offloaded subgroup (staged mode; direct mode when pieces pass
+                              through bounce buffers or change their home; otherwise unused there).
+                              0 = the library chooses: subgroups of more than 2^25 elements move in pieces of 2^24
+                              elements (rounded down to whole layout tiles), which shortens the pipeline's fill and
+                              drain from a subgroup to a piece; smaller ones move whole.  MLPO_CHUNK_WHOLE = a whole
+                              subgroup per transfer.  Any other value: that many elements, a multiple of 4 and of
+                              every tile_elems in use */
     void* staging;         /* staged: device, 256-byte aligned, caller-owned */
     size_t staging_bytes;  /* staged: >= mlpo_stream_staging_bytes(...) */
     void* h2d;             /* hipStream_t for host-to-device copies (direct: for the host-tier kernel) */
@@ -335,7 +340,10 @@ typedef struct {
                               hardware queue, and the two copy directions then take turns instead of overlapping */
     int32_t direct_blocks; /* direct: persistent workgroups on the host tier; 0 = default (64); at most 4096 */
     int32_t reserved;      /* must be 0 */
-    mlpo_slot_cache* cache; /* staged, chunk_elems == 0: slots keep their subgroups between steps; NULL = off */
+    mlpo_slot_cache* cache; /* staged: slots keep their subgroups between steps; NULL = off.  Every slot then holds a
+                               whole subgroup (size the staging buffer with MLPO_CHUNK_WHOLE); chunk_elems is the
+                               size of the pieces in which a miss replaces the slot's old occupant (tiled layout;
+                               planar subgroups enter and leave whole) */
     /* The file path (direct mode; all zero / NULL when no subgroup is MLPO_TIER_FILE): */
     const mlpo_file_extent* files; /* host array with one entry per subgroup of the table; only the entries of
                                       MLPO_TIER_FILE subgroups are read */
@@ -354,7 +362,8 @@ typedef struct {
                                           the bounce buffers even if no subgroup is file-tier yet */
 } mlpo_stream_cfg;
 
-/* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier). */
+/* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier).  With a
+ * slot cache pass MLPO_CHUNK_WHOLE: its slots hold whole subgroups. */
 size_t mlpo_stream_staging_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t n_slots, uint64_t chunk_elems);
 
 /* Bounce bytes needed for the subgroups that come from a file or (flush_to, may be NULL) go to one, under this
@@ -373,8 +382,8 @@ size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t f
  * mode the kernel works on the host state in place.  Results are bit-identical to the resident path whatever mode,
  * n_slots, chunk_elems, direct_blocks and order are.
  *
- * File-tier subgroups (direct mode): reading threads bring pieces of at most chunk_elems elements (0 = whole
- * subgroups) from the file into free bounce buffers, the update kernel works on a bounce buffer in place over the
+ * File-tier subgroups (direct mode): reading threads bring pieces of chunk_elems elements (see there for 0) from
+ * the file into free bounce buffers, the update kernel works on a bounce buffer in place over the
  * link with direct_blocks workgroups, and writing threads put the piece back into the file once its kernel has
  * finished; a bounce buffer is refilled only after its piece has been written, so at most file_slots pieces are in
  * flight (the three-stage overlap of Section 3.4 on this path).  Host-tier and file-tier work share the link, so

@@ -270,6 +270,7 @@ def mlpo_stream_staging_bytes(sgs, n_slots: int, chunk_elems: int = 0) -> int:
 
 
 STREAM_STAGED, STREAM_DIRECT = 0, 1
+CHUNK_WHOLE = (1 << 64) - 1      # chunk_elems: a whole subgroup per transfer (0 lets the library choose)
 
 
 def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chunk_elems: int = 0,

@@ -94,11 +94,24 @@ static uint64_t state_floats_of(const mlpo_subgroup& s, uint64_t len) {
     return 3u * round_up(len, s.tile_elems > 0 ? (uint64_t)s.tile_elems : 64u);
 }
 
-// Floats one host-tier subgroup needs in a staging slot when moved in pieces of at most chunk_elems elements
-// (0 = whole): the state, and behind it the piece's bf16 gradients when those live on the host too.
+// Elements per transfer of a subgroup under the configuration's chunk_elems.  0 leaves the choice to the library:
+// a subgroup of more than 2^25 elements moves in pieces of 2^24 elements (rounded down to whole layout tiles), which
+// shortens the pipeline's fill and drain from a subgroup to a piece; smaller ones move whole.
+constexpr uint64_t kAutoChunk = (uint64_t)1 << 24;
+static uint64_t piece_elems(const mlpo_subgroup& s, uint64_t chunk_elems) {
+    if (chunk_elems == MLPO_CHUNK_WHOLE) return s.n;
+    if (chunk_elems == 0) {
+        if (s.n <= 2 * kAutoChunk) return s.n;
+        const uint64_t unit = s.tile_elems > 0 ? (uint64_t)s.tile_elems : 64u;
+        return unit >= kAutoChunk ? unit : kAutoChunk / unit * unit;
+    }
+    return chunk_elems < s.n ? chunk_elems : s.n;
+}
+
+// Floats one host-tier subgroup needs in a staging slot when moved in pieces under chunk_elems: the state, and
+// behind it the piece's bf16 gradients when those live on the host too.
 static uint64_t slot_floats_of(const mlpo_subgroup& s, uint64_t chunk_elems) {
-    uint64_t len = s.n;
-    if (chunk_elems != 0 && chunk_elems < len) len = chunk_elems;
+    const uint64_t len = piece_elems(s, chunk_elems);
     uint64_t f = state_floats_of(s, len);
     if (s.tier == MLPO_TIER_HOST_GRADS) f += round_up(len, 128) / 2u;
     return f;
@@ -123,39 +136,63 @@ static uint64_t bounce_slot_bytes(const mlpo_subgroup* sg, int32_t n_sg, uint64_
     for (int32_t i = 0; i < n_sg; ++i)
         if ((sg[i].tier == MLPO_TIER_FILE || (flush_to != nullptr && flush_to[i].tier == MLPO_TIER_FILE)) &&
             sg[i].tile_elems > 0) {
-            uint64_t len = sg[i].n;
-            if (chunk_elems != 0 && chunk_elems < len) len = chunk_elems;
-            const uint64_t b = state_floats_of(sg[i], len) * sizeof(float);
+            const uint64_t b = state_floats_of(sg[i], piece_elems(sg[i], chunk_elems)) * sizeof(float);
             if (b > mx) mx = b;
         }
     return round_up(mx, 4096);
 }
 
-// One piece (a whole subgroup or a chunk of one) of a host-tier subgroup and the staging slot it occupies.
+// One piece (a whole subgroup or a chunk of one) of a host-tier subgroup and where it lives on the device.
 struct Piece {
     const mlpo_subgroup* s;
-    uint64_t off, len;
-    float* slot;
+    uint64_t off, len;  // elements [off, off + len) of the subgroup
+    float* state;       // tiled: the piece's layout tiles start here; planar: p starts here, m and v follow `arr` apart
+    uint64_t arr;       // planar: floats from one array to the next on the device
+    uint16_t* grads;    // where the piece's gradients live on the device when they come from the host with it
 };
 
-// Where the update reads the piece's gradients: behind the state in the slot when they come from the host with it,
-// else at their device home.
+// A piece that has a staging slot to itself: state at the start of the slot, gradients behind it.
+static Piece piece_in_own_slot(const mlpo_subgroup& s, uint64_t off, uint64_t len, float* slot) {
+    return Piece{&s, off, len, slot, round_up(len, 64), reinterpret_cast<uint16_t*>(slot + state_floats_of(s, len))};
+}
+
+// A piece of a subgroup that occupies a slot as a whole (slot cache): every element has its fixed place in the slot,
+// the gradients of the whole subgroup sit behind the whole state.  A planar subgroup is one piece (off = 0).
+static Piece piece_of_resident(const mlpo_subgroup& s, uint64_t off, uint64_t len, float* slot) {
+    uint16_t* grads = reinterpret_cast<uint16_t*>(slot + state_floats_of(s, s.n)) + off;
+    if (s.tile_elems > 0) {
+        const uint64_t T = (uint64_t)s.tile_elems;
+        return Piece{&s, off, len, slot + (off / T) * 3u * T, 0, grads};
+    }
+    return Piece{&s, off, len, slot, round_up(s.n, 64), grads};
+}
+
+// Where the update reads the piece's gradients: in the slot when they come from the host with the state, else at
+// their device home.
 static const uint16_t* piece_grads(const Piece& pc) {
     const mlpo_subgroup& s = *pc.s;
-    if (s.tier != MLPO_TIER_HOST_GRADS) return s.g + pc.off;
-    return reinterpret_cast<const uint16_t*>(pc.slot + state_floats_of(s, pc.len));
+    return s.tier == MLPO_TIER_HOST_GRADS ? pc.grads : s.g + pc.off;
 }
 
 // Host-to-device transfer of the piece's gradients into its slot (subgroups whose gradients live on the host).
 static int fetch_grads(const Piece& pc, hipStream_t st) {
     const mlpo_subgroup& s = *pc.s;
     if (s.tier != MLPO_TIER_HOST_GRADS) return MLPO_OK;
-    MLPO_HIP(hipMemcpyAsync(const_cast<uint16_t*>(piece_grads(pc)), s.g + pc.off, (size_t)pc.len * sizeof(uint16_t),
-                            hipMemcpyHostToDevice, st));
+    MLPO_HIP(hipMemcpyAsync(pc.grads, s.g + pc.off, (size_t)pc.len * sizeof(uint16_t), hipMemcpyHostToDevice, st));
     return MLPO_OK;
 }
 
-// Host-to-device transfer of a piece into its slot; returns the kernel's view of the slot.
+// The kernel's view of a piece on the device.
+static SgView slot_view(const Piece& pc) {
+    const mlpo_subgroup& s = *pc.s;
+    if (s.tile_elems > 0) {
+        const uint64_t T = (uint64_t)s.tile_elems;
+        return SgView{pc.state, pc.state + T, pc.state + 2 * T, piece_grads(pc), s.p16 + pc.off, pc.len, s.tile_elems};
+    }
+    return SgView{pc.state, pc.state + pc.arr, pc.state + 2 * pc.arr, piece_grads(pc), s.p16 + pc.off, pc.len, 0};
+}
+
+// Host-to-device transfer of a piece to its place on the device; returns the kernel's view of it.
 static int fetch_piece(const Piece& pc, hipStream_t st, SgView* view) {
     const mlpo_subgroup& s = *pc.s;
     const int rc = fetch_grads(pc, st);
@@ -165,48 +202,31 @@ static int fetch_piece(const Piece& pc, hipStream_t st, SgView* view) {
         const uint64_t T = (uint64_t)s.tile_elems;
         const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
         const float* src = s.p + (pc.off / T) * 3u * T;
-        MLPO_HIP(hipMemcpyAsync(pc.slot, src, bytes, hipMemcpyHostToDevice, st));
-        *view = SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, piece_grads(pc), s.p16 + pc.off, pc.len, s.tile_elems};
+        MLPO_HIP(hipMemcpyAsync(pc.state, src, bytes, hipMemcpyHostToDevice, st));
     } else {
         const size_t bytes = (size_t)pc.len * sizeof(float);
-        const uint64_t arr = round_up(pc.len, 64);
-        float* sp = pc.slot;
-        float* sm = sp + arr;
-        float* sv = sm + arr;
-        MLPO_HIP(hipMemcpyAsync(sp, s.p + pc.off, bytes, hipMemcpyHostToDevice, st));
-        MLPO_HIP(hipMemcpyAsync(sm, s.m + pc.off, bytes, hipMemcpyHostToDevice, st));
-        MLPO_HIP(hipMemcpyAsync(sv, s.v + pc.off, bytes, hipMemcpyHostToDevice, st));
-        *view = SgView{sp, sm, sv, piece_grads(pc), s.p16 + pc.off, pc.len, 0};
+        MLPO_HIP(hipMemcpyAsync(pc.state, s.p + pc.off, bytes, hipMemcpyHostToDevice, st));
+        MLPO_HIP(hipMemcpyAsync(pc.state + pc.arr, s.m + pc.off, bytes, hipMemcpyHostToDevice, st));
+        MLPO_HIP(hipMemcpyAsync(pc.state + 2 * pc.arr, s.v + pc.off, bytes, hipMemcpyHostToDevice, st));
     }
+    *view = slot_view(pc);
     return MLPO_OK;
 }
 
-// The view of a slot that already holds the piece.
-static SgView slot_view(const Piece& pc) {
-    const mlpo_subgroup& s = *pc.s;
-    if (s.tile_elems > 0) {
-        const uint64_t T = (uint64_t)s.tile_elems;
-        return SgView{pc.slot, pc.slot + T, pc.slot + 2 * T, piece_grads(pc), s.p16 + pc.off, pc.len, s.tile_elems};
-    }
-    const uint64_t arr = round_up(pc.len, 64);
-    return SgView{pc.slot, pc.slot + arr, pc.slot + 2 * arr, piece_grads(pc), s.p16 + pc.off, pc.len, 0};
-}
-
-// Device-to-host transfer of a piece from its slot back to the host tier.
+// Device-to-host transfer of a piece from the device back to the host tier.
 static int flush_piece(const Piece& pc, hipStream_t st) {
     const mlpo_subgroup& s = *pc.s;
     if (s.tile_elems > 0) {
         const uint64_t T = (uint64_t)s.tile_elems;
         const size_t bytes = (size_t)(round_up(pc.len, T) * 3u) * sizeof(float);
         float* dst = s.p + (pc.off / T) * 3u * T;
-        MLPO_HIP(hipMemcpyAsync(dst, pc.slot, bytes, hipMemcpyDeviceToHost, st));
+        MLPO_HIP(hipMemcpyAsync(dst, pc.state, bytes, hipMemcpyDeviceToHost, st));
         return MLPO_OK;
     }
     const size_t bytes = (size_t)pc.len * sizeof(float);
-    const uint64_t arr = round_up(pc.len, 64);
-    MLPO_HIP(hipMemcpyAsync(s.p + pc.off, pc.slot, bytes, hipMemcpyDeviceToHost, st));
-    MLPO_HIP(hipMemcpyAsync(s.m + pc.off, pc.slot + arr, bytes, hipMemcpyDeviceToHost, st));
-    MLPO_HIP(hipMemcpyAsync(s.v + pc.off, pc.slot + 2 * arr, bytes, hipMemcpyDeviceToHost, st));
+    MLPO_HIP(hipMemcpyAsync(s.p + pc.off, pc.state, bytes, hipMemcpyDeviceToHost, st));
+    MLPO_HIP(hipMemcpyAsync(s.m + pc.off, pc.state + pc.arr, bytes, hipMemcpyDeviceToHost, st));
+    MLPO_HIP(hipMemcpyAsync(s.v + pc.off, pc.state + 2 * pc.arr, bytes, hipMemcpyDeviceToHost, st));
     return MLPO_OK;
 }
 
@@ -267,7 +287,8 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
         return fail(MLPO_EINVAL, "direct_blocks must be 0..4096 (got %d)", cfg->direct_blocks);
     if (!direct && (cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS))
         return fail(MLPO_EINVAL, "n_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->n_slots);
-    if (cfg->chunk_elems % 4 != 0) return fail(MLPO_EINVAL, "chunk_elems must be a multiple of 4");
+    const bool explicit_chunk = cfg->chunk_elems != 0 && cfg->chunk_elems != MLPO_CHUNK_WHOLE;
+    if (explicit_chunk && cfg->chunk_elems % 4 != 0) return fail(MLPO_EINVAL, "chunk_elems must be a multiple of 4");
     if (order != nullptr) {
         std::vector<char> seen((size_t)n_sg, 0);
         for (int32_t i = 0; i < n_sg; ++i) {
@@ -281,7 +302,7 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
     for (int32_t i = 0; i < n_sg; ++i) {
         const bool offloaded = host_tier(sg[i].tier) || sg[i].tier == MLPO_TIER_FILE ||
                                (cfg->flush_to != nullptr && cfg->flush_to[i].tier != MLPO_FLUSH_IN_PLACE);
-        if (offloaded && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
+        if (explicit_chunk && offloaded && sg[i].tile_elems > 0 && cfg->chunk_elems % (uint64_t)sg[i].tile_elems != 0)
             return fail(MLPO_EINVAL, "chunk_elems must be a multiple of subgroup %d's tile_elems", i);
         any_file = any_file || sg[i].tier == MLPO_TIER_FILE;
     }
@@ -341,7 +362,9 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
             }
         }
     }
-    const uint64_t slot_floats = direct ? 0 : slot_floats_for(sg, n_sg, cfg->chunk_elems);
+    // with a slot cache every slot holds a whole subgroup, whatever size its misses travel in
+    const uint64_t slot_floats =
+        direct ? 0 : slot_floats_for(sg, n_sg, cfg->cache != nullptr ? MLPO_CHUNK_WHOLE : cfg->chunk_elems);
     const uint64_t need = slot_floats * 4u * (uint64_t)(direct ? 0 : cfg->n_slots);
     if (need > 0) {
         if (cfg->staging == nullptr || misaligned(cfg->staging, 256))
@@ -352,7 +375,6 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
     }
     if (cfg->cache != nullptr) {
         if (direct) return fail(MLPO_EINVAL, "a slot cache needs staged mode");
-        if (cfg->chunk_elems != 0) return fail(MLPO_EINVAL, "a slot cache needs whole-subgroup transfers (chunk_elems 0)");
         rc = cache_check(cfg->cache, sg, n_sg, cfg->n_slots);
         if (rc != MLPO_OK) return rc;
     }
@@ -403,7 +425,6 @@ struct LinkWork {
 
 static LinkWork link_work(const mlpo_subgroup* sg, const Plan& plan, const mlpo_stream_cfg* cfg,
                           uint64_t buffer_bytes) {
-    const uint64_t chunk = cfg->chunk_elems;
     LinkWork w;
     for (int32_t i : plan.offloaded_ids) {
         const mlpo_subgroup& s = sg[i];
@@ -411,7 +432,7 @@ static LinkWork link_work(const mlpo_subgroup* sg, const Plan& plan, const mlpo_
         const bool from_file = s.tier == MLPO_TIER_FILE;
         const bool to_file = to != nullptr ? to->tier == MLPO_TIER_FILE : from_file;
         const uint64_t T = (uint64_t)s.tile_elems;  // 0 only for planar host-tier subgroups, which stay in place
-        const uint64_t step_elems = (chunk != 0 && chunk < s.n) ? chunk : s.n;
+        const uint64_t step_elems = piece_elems(s, cfg->chunk_elems);
         for (uint64_t off = 0; off < s.n; off += step_elems) {
             const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
             // chunk is a multiple of the layout tile, so a piece starts at a layout tile boundary
@@ -522,13 +543,19 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
 // Staged mode with a slot cache: slots keep their subgroup from one step to the next (Section 3.2 "Cache-Friendly
 // Ordering").  A subgroup found in a slot is updated there without any transfer, and a slot is copied back only when
 // another subgroup needs it (or on mlpo_stream_flush).  With the order reversed from step to step the subgroups
-// processed last are the ones processed first next time.
+// processed last are the ones processed first next time.  A miss moves in pieces (tiled subgroups): the old
+// occupant's piece c goes back to the host, the newcomer's piece c takes its place and is updated as soon as it has
+// arrived, so the two copy directions and the kernel overlap inside one miss and the pipeline fills and drains in a
+// piece, not in a subgroup.
 static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwConsts& c,
                       const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, uint64_t slot_floats,
                       const Streams& st, EventCache& ec) {
     mlpo_slot_cache* cache = cfg->cache;
     float* staging = static_cast<float*>(cfg->staging);
     int rc;
+    // pieces a subgroup moves in while it enters or leaves a slot: planar subgroups whole (their arrays are spread
+    // over the slot), tiled ones under the configuration's chunk_elems
+    const auto step_of = [cfg](const mlpo_subgroup& s) { return s.tile_elems > 0 ? piece_elems(s, cfg->chunk_elems) : s.n; };
     for (int32_t i : plan.host_ids) {
         const mlpo_subgroup& s = sg[i];
         int k = -1;
@@ -546,12 +573,10 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
         }
         SlotEvents& ev = ec.slots[(size_t)k];
         float* slot = staging + (uint64_t)k * slot_floats;
-        const Piece pc{&s, 0, s.n, slot};
-        SgView view;
         if (hit) {
+            const Piece pc = piece_of_resident(s, 0, s.n, slot);
             // an explicit flush of this slot may still be reading it
             MLPO_HIP(hipStreamWaitEvent(st.cmp, ev.d2h_done, 0));
-            view = slot_view(pc);
             if (s.tier == MLPO_TIER_HOST_GRADS) {
                 // the state stayed, this step's gradients still have to come in (after the last update read the old)
                 MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.upd_done, 0));
@@ -560,28 +585,64 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
                 MLPO_HIP(hipEventRecord(ev.h2d_done, st.h2d));
                 MLPO_HIP(hipStreamWaitEvent(st.cmp, ev.h2d_done, 0));
             }
+            const SgView view = slot_view(pc);
+            rc = launch_adamw(&view, 1, c, scalars, st.cmp);
+            if (rc != MLPO_OK) return rc;
             ++cache->hits;
         } else {
-            if (cache->owner[k] >= 0 && cache->dirty[k]) {
-                const mlpo_subgroup& old = sg[cache->owner[k]];
-                MLPO_HIP(hipStreamWaitEvent(st.d2h, ev.upd_done, 0));
-                rc = flush_piece(Piece{&old, 0, old.n, slot}, st.d2h);
-                if (rc != MLPO_OK) return rc;
-                MLPO_HIP(hipEventRecord(ev.d2h_done, st.d2h));
-                ++cache->flushes;
-            }
+            const mlpo_subgroup* old = (cache->owner[k] >= 0 && cache->dirty[k]) ? &sg[cache->owner[k]] : nullptr;
+            const uint64_t step_new = step_of(s);
+            const uint64_t step_old = old != nullptr ? step_of(*old) : 0;
+            // piece c of the newcomer lands exactly where piece c of the old occupant lay when both are cut alike
+            // (gradients that come in with the newcomer go behind ITS state, which must not be where a longer old
+            // occupant still has pieces waiting)
+            const bool alike = old != nullptr && old->tile_elems > 0 && old->tile_elems == s.tile_elems &&
+                               step_old == step_new && (s.tier != MLPO_TIER_HOST_GRADS || old->n == s.n);
             cache->owner[k] = -1;  // until the new occupant is in place
             cache->dirty[k] = 0;
+            // the slot's last update and any earlier copy out of it are behind both copy streams
+            MLPO_HIP(hipStreamWaitEvent(st.d2h, ev.upd_done, 0));
             MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
             MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.upd_done, 0));
-            rc = fetch_piece(pc, st.h2d, &view);
-            if (rc != MLPO_OK) return rc;
-            MLPO_HIP(hipEventRecord(ev.h2d_done, st.h2d));
-            MLPO_HIP(hipStreamWaitEvent(st.cmp, ev.h2d_done, 0));
+            uint64_t off_old = 0;
+            if (old != nullptr && !alike) {  // cut differently: everything out first
+                for (; off_old < old->n; off_old += step_old) {
+                    const uint64_t len = old->n - off_old < step_old ? old->n - off_old : step_old;
+                    rc = flush_piece(piece_of_resident(*old, off_old, len, slot), st.d2h);
+                    if (rc != MLPO_OK) return rc;
+                }
+                MLPO_HIP(hipEventRecord(ev.d2h_done, st.d2h));
+                MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
+            }
+            if (old != nullptr) ++cache->flushes;
+            for (uint64_t off = 0; off < s.n; off += step_new) {
+                const uint64_t len = s.n - off < step_new ? s.n - off : step_new;
+                if (alike && off_old < old->n) {
+                    const uint64_t len_old = old->n - off_old < step_old ? old->n - off_old : step_old;
+                    rc = flush_piece(piece_of_resident(*old, off_old, len_old, slot), st.d2h);
+                    if (rc != MLPO_OK) return rc;
+                    off_old += step_old;
+                    MLPO_HIP(hipEventRecord(ev.d2h_done, st.d2h));
+                    MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
+                }
+                SgView view;
+                rc = fetch_piece(piece_of_resident(s, off, len, slot), st.h2d, &view);
+                if (rc != MLPO_OK) return rc;
+                MLPO_HIP(hipEventRecord(ev.h2d_done, st.h2d));
+                MLPO_HIP(hipStreamWaitEvent(st.cmp, ev.h2d_done, 0));
+                rc = launch_adamw(&view, 1, c, scalars, st.cmp);
+                if (rc != MLPO_OK) return rc;
+            }
+            if (alike && off_old < old->n) {  // the old occupant was the longer one: its remaining pieces
+                for (; off_old < old->n; off_old += step_old) {
+                    const uint64_t len_old = old->n - off_old < step_old ? old->n - off_old : step_old;
+                    rc = flush_piece(piece_of_resident(*old, off_old, len_old, slot), st.d2h);
+                    if (rc != MLPO_OK) return rc;
+                }
+                MLPO_HIP(hipEventRecord(ev.d2h_done, st.d2h));
+            }
             ++cache->fetches;
         }
-        rc = launch_adamw(&view, 1, c, scalars, st.cmp);
-        if (rc != MLPO_OK) return rc;
         MLPO_HIP(hipEventRecord(ev.upd_done, st.cmp));
         cache->owner[k] = i;
         cache->owner_p[k] = s.p;
@@ -601,12 +662,12 @@ static int run_staged(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
     int rc;
     for (int32_t i : plan.host_ids) {
         const mlpo_subgroup& s = sg[i];
-        const uint64_t step_elems = (cfg->chunk_elems != 0 && cfg->chunk_elems < s.n) ? cfg->chunk_elems : s.n;
+        const uint64_t step_elems = piece_elems(s, cfg->chunk_elems);
         for (uint64_t off = 0; off < s.n; off += step_elems, ++piece) {
             const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
             const int k = (int)(piece % (uint64_t)cfg->n_slots);
             SlotEvents& ev = ec.slots[(size_t)k];
-            const Piece pc{&s, off, len, staging + (uint64_t)k * slot_floats};
+            const Piece pc = piece_in_own_slot(s, off, len, staging + (uint64_t)k * slot_floats);
             hipEvent_t tf0 = nullptr, tf1 = nullptr, tw0 = nullptr, tw1 = nullptr;
             const bool timed =
                 timing_enabled() && timing_acquire_two(kTimedFetch, &tf0, &tf1, kTimedFlush, &tw0, &tw1);
@@ -744,7 +805,7 @@ int mlpo_stream_flush(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_stream_c
     if (cache->magic == 0) return MLPO_OK;  // never used: nothing is held
     rc = cache_check(cache, sg, n_sg, cfg->n_slots);
     if (rc != MLPO_OK) return rc;
-    const uint64_t slot_floats = slot_floats_for(sg, n_sg, 0);
+    const uint64_t slot_floats = slot_floats_for(sg, n_sg, MLPO_CHUNK_WHOLE);
     if (cfg->staging == nullptr || cfg->staging_bytes < slot_floats * 4u * (uint64_t)cfg->n_slots)
         return fail(MLPO_ENOMEM, "staging does not match the configuration the cache was filled with");
     EventCache& ec = events();
@@ -760,7 +821,7 @@ int mlpo_stream_flush(const mlpo_subgroup* sg, int32_t n_sg, const mlpo_stream_c
         const mlpo_subgroup& s = sg[cache->owner[k]];
         SlotEvents& ev = ec.slots[(size_t)k];
         MLPO_HIP(hipStreamWaitEvent(s_d2h, ev.upd_done, 0));
-        rc = flush_piece(Piece{&s, 0, s.n, staging + (uint64_t)k * slot_floats}, s_d2h);
+        rc = flush_piece(piece_of_resident(s, 0, s.n, staging + (uint64_t)k * slot_floats), s_d2h);
         if (rc != MLPO_OK) return rc;
         MLPO_HIP(hipEventRecord(ev.d2h_done, s_d2h));
         cache->dirty[k] = 0;

@@ -122,10 +122,12 @@ def test_stream_argument_errors():
     res = cfg()
     res.reserved = 1
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, res)
-    # slot cache: staged mode, whole-subgroup transfers, a struct that is zero or ours
+    # slot cache: staged mode, a struct that is zero or ours, slots sized for whole subgroups
     cache = B.SlotCacheC()
-    with_cache = B.stream_cfg(3, FAKE, 1 << 30, None, None, None, 4096, cache=cache)
-    expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, with_cache)            # chunked
+    small = B.mlpo_stream_staging_bytes(host, 3, 512)
+    assert small < B.mlpo_stream_staging_bytes(host, 3, B.CHUNK_WHOLE)
+    with_cache = B.stream_cfg(3, FAKE, small, None, None, None, 512, cache=cache)
+    expect(B.MLPO_ENOMEM, B.mlpo_stream_update, host, None, hp, 1, None, with_cache)   # slots hold whole subgroups
     d = B.direct_cfg(None, None, 8)
     d.cache = C.pointer(cache)
     expect(B.MLPO_EINVAL, B.mlpo_stream_update, host, None, hp, 1, None, d)                     # direct mode

@@ -255,6 +255,55 @@ def test_slot_cache_alternating_order(oracle, scratch, streams, n_slots, tile):
         assert_state_parity(ds.fetch(k), host[k], f"cache slots={n_slots} tile={tile} sg={k}")
 
 
+@pytest.mark.parametrize("n_slots,tile,chunk,host_grads", [
+    (2, 1024, 4096, False), (3, 1024, 8192, False), (2, 2048, 2048, True), (3, 1024, 4096, True),
+    (2, 0, 4096, False), (2, 1024, B.CHUNK_WHOLE, False), (4, 1024, 1024, False),
+])
+def test_slot_cache_misses_in_pieces(oracle, scratch, streams, n_slots, tile, chunk, host_grads):
+    """A miss replaces the slot's old occupant piece by piece (old piece out, new piece in, update): subgroups of
+    different lengths share the slots, so the newcomer is now shorter, now longer than the one it displaces, and
+    pieces are cut alike or not; planar subgroups enter and leave whole.  State equals the oracle's after the final
+    flush, transfer counts are those of whole-subgroup misses."""
+    ohp, ghp = hp_pair(oracle)
+    sizes = [50_001, 20_000, 50_001, 35_003, 50_001, 8_192, 3]
+    wl = W.Workload("cachepieces", n_sub=len(sizes), sub_elems=max(sizes), n_host=len(sizes), loss_scale=8.0,
+                    max_norm=0.04, steps=4)
+    full = W.host_subgroups(wl, warm=True)
+    host = [{key: a[:n].copy() for key, a in sg.items()} for sg, n in zip(full, sizes)]
+    tiers = [1] * len(sizes)
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=tile)
+    table = _host_grad_table(ds, tiers, tile) if host_grads else ds.table
+    cache = B.SlotCacheC()
+    need = B.mlpo_stream_staging_bytes(table, n_slots, B.CHUNK_WHOLE)
+    stg = torch.empty(need, dtype=torch.uint8, device=dev())
+    cfg = B.stream_cfg(n_slots, stg, need, None, streams[1], None, chunk, cache=cache)
+    for s in range(wl.steps):
+        order = list(range(wl.n_sub)) if s % 2 == 0 else list(range(wl.n_sub))[::-1]
+        if s > 0:
+            for k, sg in enumerate(host):
+                fresh = np.empty(wl.sub_elems, np.uint16)
+                W.fill_grads(wl, k, s, fresh)
+                sg["g"][:] = fresh[:sizes[k]]
+                if host_grads:
+                    ds.t[k]["g_used"].copy_(torch.from_numpy(sg["g"].view(np.int16)))
+                else:
+                    ds.set_grads(k, sg["g"])
+        torch.cuda.synchronize()
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm, order=order)
+        B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                 streams[1])
+        assert B.mlpo_stream_update(table, order, ghp, s + 1, scratch.scalars, cfg) and ok_o
+        streams[1].synchronize()
+        assert scratch.read()["gmul"] == gmul_o
+    H = len(sizes)
+    assert cache.hits == (wl.steps - 1) * n_slots and cache.fetches == H + (wl.steps - 1) * (H - n_slots)
+    B.mlpo_stream_flush(table, cfg)
+    streams[1].synchronize()
+    assert cache.flushes == cache.fetches
+    for k in range(wl.n_sub):
+        assert_state_parity(ds.fetch(k), host[k], f"cache pieces slots={n_slots} tile={tile} chunk={chunk} sg={k}")
+
+
 def test_slot_cache_survives_flush_and_skip(oracle, scratch, streams):
     ohp, ghp = hp_pair(oracle)
     wl = W.Workload("cache2", n_sub=4, sub_elems=30_011, n_host=4, steps=4)
