@@ -8,12 +8,17 @@
 //                     16-byte loads and stores (p, m, v, in place) plus one 8-byte load (g) and one 8-byte store
 //                     (p16), planar (three arrays) or tiled (p, m, v interleaved in runs of T elements)
 //   ys_link           pinned-memory copies over the host link: each direction alone and both at once
+// Compiled with -DYS_LINK_MAIN the file is also a small program that runs ys_link on buffers of its own
+// (bench_link_yardstick).
 //
 // Every function returns 0 or a negative number and leaves a text for ys_last_error().
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include <chrono>
 
@@ -127,6 +132,41 @@ int ys_sweep(int32_t kind, void* buffer, size_t bytes, void* stream) {
     return 0;
 }
 
+// One ys_sweep launch stamped with its own begin and end on the device (events attached to the dispatch), waited for;
+// *ms receives the duration.  What a single short kernel takes from its first wavefront to its last, ramp and tail
+// included - back-to-back launches overlap those and look faster than any one of them is.
+int ys_sweep_timed(int32_t kind, void* buffer, size_t bytes, void* stream, float* ms) {
+    if (ms == nullptr) return fail("ms is NULL");
+    if (kind < 0 || kind > 2) return fail("unknown sweep kind %d", kind);
+    if (buffer == nullptr || (reinterpret_cast<uintptr_t>(buffer) & 15u) != 0) return fail("buffer is NULL or not 16-byte aligned");
+    if (bytes < 32 || bytes % 16 != 0) return fail("bytes must be a multiple of 16, at least 32");
+    const uint64_t n4 = bytes / 16 - 1;
+    const uint64_t blocks = (n4 + kBlock - 1) / kBlock;
+    if (blocks > 0x7FFFFFFFull) return fail("buffer too large for one launch");
+    f32x4* p = static_cast<f32x4*>(buffer);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    YS_HIP(hipEventCreate(&t0));
+    if (hipEventCreate(&t1) != hipSuccess) {
+        (void)hipEventDestroy(t0);
+        return fail("cannot create an event");
+    }
+    if (kind == 0)
+        hipExtLaunchKernelGGL(sweep_read, dim3((uint32_t)blocks), dim3(kBlock), 0, st, t0, t1, 0, p, n4,
+                              reinterpret_cast<float*>(p + n4));
+    else if (kind == 1)
+        hipExtLaunchKernelGGL(sweep_write, dim3((uint32_t)blocks), dim3(kBlock), 0, st, t0, t1, 0, p, n4);
+    else
+        hipExtLaunchKernelGGL(sweep_rmw, dim3((uint32_t)blocks), dim3(kBlock), 0, st, t0, t1, 0, p, n4);
+    int rc = 0;
+    if (hipGetLastError() != hipSuccess || hipEventSynchronize(t1) != hipSuccess ||
+        hipEventElapsedTime(ms, t0, t1) != hipSuccess)
+        rc = fail("timed launch failed");
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    return rc;
+}
+
 // The update's address streams over n elements (a multiple of 4).  tile_elems = 0: p, m, v are three device arrays of
 // n floats.  tile_elems = T (a multiple of 1024): p is one tiled buffer of ceil(n / T) * 3T floats and m, v are
 // ignored.  g and h: n 16-bit values each, 8-byte aligned.  Halves p, m, v in place, writes g with the lowest
@@ -188,3 +228,31 @@ int ys_link(const void* host_src, void* dev_dst, const void* dev_src, void* host
 }
 
 }  // extern "C"
+
+#ifdef YS_LINK_MAIN
+// The same three legs as ys_link in a process of its own (bench.py starts it before it touches the GPU itself): two
+// streams in a fresh process with nothing else on the device.  Prints one JSON line.
+int main(int argc, char** argv) {
+    const size_t bytes = (argc > 1 ? (size_t)atoll(argv[1]) : 400) << 20;
+    void *ha = nullptr, *hb = nullptr, *da = nullptr, *db = nullptr;
+    if (hipHostMalloc(&ha, bytes, 0) != hipSuccess || hipHostMalloc(&hb, bytes, 0) != hipSuccess ||
+        hipMalloc(&da, bytes) != hipSuccess || hipMalloc(&db, bytes) != hipSuccess) {
+        printf("{\"error\": \"allocation failed\"}\n");
+        return 1;
+    }
+    memset(ha, 1, bytes);
+    memset(hb, 2, bytes);
+    double sec[3] = {0, 0, 0};
+    if (ys_link(ha, da, db, hb, bytes, 4, sec) != 0) {
+        printf("{\"error\": \"%s\"}\n", ys_last_error());
+        return 1;
+    }
+    printf("{\"bytes\": %zu, \"h2d_GBs\": %.2f, \"d2h_GBs\": %.2f, \"bidir_GBs_per_dir\": %.2f}\n", bytes,
+           bytes / sec[0] / 1e9, bytes / sec[1] / 1e9, bytes / sec[2] / 1e9);
+    (void)hipHostFree(ha);
+    (void)hipHostFree(hb);
+    (void)hipFree(da);
+    (void)hipFree(db);
+    return 0;
+}
+#endif

@@ -37,6 +37,7 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
 
 YARDSTICK_SRC = os.path.join(ROOT, "bench_yardsticks.hip")
 YARDSTICK_LIB = os.path.join(ROOT, "libbench_yardsticks.so")
+YARDSTICK_EXE = os.path.join(ROOT, "bench_link_yardstick")
 
 
 def build_yardsticks(verbose: bool = False) -> str:
@@ -45,6 +46,11 @@ def build_yardsticks(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    exe = [hipcc(), *[f for f in HIPCC_FLAGS if f not in ("-shared",)], "-DYS_LINK_MAIN", "-o", YARDSTICK_EXE,
+           YARDSTICK_SRC]
+    if verbose:
+        print(" ".join(exe), flush=True)
+    subprocess.run(exe, check=True)
     return YARDSTICK_LIB
 
 

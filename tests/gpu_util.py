@@ -48,6 +48,7 @@ class PinnedF32:
         self.ptr = C.c_void_p()
         rc = hip_runtime().hipHostMalloc(C.byref(self.ptr), max(4 * n, 4), 0)
         if rc != 0:
+            hip_runtime().hipGetLastError()     # else the next call that checks (torch's) reports the refusal again
             raise MemoryError(f"hipHostMalloc of {4 * n / 1e9:.2f} GB failed (code {rc})")
         self.np = np.ctypeslib.as_array((C.c_float * n).from_address(self.ptr.value))
         self.t = torch.from_numpy(self.np)
