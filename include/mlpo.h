@@ -173,6 +173,24 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
                            size_t workspace_bytes, mlpo_step_scalars* out, void* stream);
 
 /*
+ * The same gradient pass for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The per-workgroup partial sums go to an array in
+ * the library's own device image (196 864 bytes, one copy per GPU, held until the process ends) instead of a
+ * caller's workspace; the call allocates nothing and calls no allocating routine (no timing events either: its
+ * launches are never recorded for mlpo_kernel_times).  Same kernels, same order of summation, hence the same record
+ * bit for bit as mlpo_grad_unscale_norm.  Arguments as there.  Limits: at most MLPO_STATIC_MAX_SUBGROUPS subgroups
+ * and MLPO_STATIC_MAX_ELEMENTS gradients per call; more gives MLPO_EINVAL.
+ * Nothing in the array has to start at zero (every partial a call reads was written by that call), so there is
+ * nothing to clear.  All calls on one GPU share that GPU's array: calls that overlap on one GPU - two streams, two
+ * threads - race and give wrong results; order them.
+ * Errors: MLPO_EINVAL, MLPO_EHIP.
+ */
+#define MLPO_STATIC_MAX_SUBGROUPS 1024
+#define MLPO_STATIC_MAX_ELEMENTS (1ull << 40)
+int mlpo_grad_unscale_norm_static(const mlpo_subgroup* sg, int32_t n_sg, float inv_scale, float max_norm,
+                                  mlpo_step_scalars* out, void* stream);
+
+/*
  * Gradient accumulation over micro-batches into the half-precision accumulation buffer that the update later
  * upcasts on the fly (Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"; Section 4.5 runs 1-16
  * backward passes per update).  For every i < n:

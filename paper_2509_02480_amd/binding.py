@@ -24,7 +24,7 @@ TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_line_lead", "mlpo_state_floats", "mlpo_state_pack",
            "mlpo_state_unpack",
-           "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm",
+           "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm", "mlpo_grad_unscale_norm_static", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm",
            "mlpo_grad_norm_finish", "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_bounce_bytes",
            "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers", "mlpo_update_bandwidth",
            "mlpo_kernel_timing", "mlpo_kernel_times", "mlpo_shutdown")
@@ -135,6 +135,8 @@ def lib():
         L.mlpo_grad_unscale_norm.restype = C.c_int
         L.mlpo_grad_unscale_norm.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_size_t,
                                              C.c_void_p, C.c_void_p]
+        L.mlpo_grad_unscale_norm_static.restype = C.c_int
+        L.mlpo_grad_unscale_norm_static.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         L.mlpo_grad_accumulate.restype = C.c_int
         L.mlpo_grad_accumulate.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_int32,
                                            C.c_void_p]
@@ -256,6 +258,12 @@ def mlpo_grad_unscale_norm(sgs, inv_scale: float, max_norm: float, workspace, wo
     t = _table(sgs)
     _check(lib().mlpo_grad_unscale_norm(t.array, t.n, inv_scale, max_norm, _ptr(workspace), workspace_bytes,
                                         _ptr(out), _stream(stream)))
+
+
+def mlpo_grad_unscale_norm_static(sgs, inv_scale: float, max_norm: float, out, stream=None) -> None:
+    """The gradient pass without a workspace argument (the library's own static device array); see mlpo.h."""
+    t = _table(sgs)
+    _check(lib().mlpo_grad_unscale_norm_static(t.array, t.n, inv_scale, max_norm, _ptr(out), _stream(stream)))
 
 
 def mlpo_adamw_step(sgs, hp: HParams, step: int, scalars=None, stream=None) -> None:

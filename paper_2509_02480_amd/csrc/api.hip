@@ -285,6 +285,28 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
     return launch_grad_norm(sg, n_sg, inv_scale, max_norm, workspace, out, static_cast<hipStream_t>(stream));
 }
 
+int mlpo_grad_unscale_norm_static(const mlpo_subgroup* sg, int32_t n_sg, float inv_scale, float max_norm,
+                                  mlpo_step_scalars* out, void* stream) {
+    if (n_sg > MLPO_STATIC_MAX_SUBGROUPS)
+        return fail(MLPO_EINVAL, "%d subgroups: the call without a workspace takes at most %d", n_sg,
+                    MLPO_STATIC_MAX_SUBGROUPS);
+    int rc = validate_subgroups(sg, n_sg, /*grads_only=*/true, 1);
+    if (rc != MLPO_OK) return rc;
+    uint64_t total = 0;
+    for (int32_t i = 0; i < n_sg; ++i) total += sg[i].n;  // each n is at most 2^48 (checked), so no overflow
+    if (total > MLPO_STATIC_MAX_ELEMENTS)
+        return fail(MLPO_EINVAL, "%llu gradients: the call without a workspace takes at most %llu",
+                    (unsigned long long)total, (unsigned long long)MLPO_STATIC_MAX_ELEMENTS);
+    if (!(isfinite(inv_scale) && inv_scale > 0.0f)) return fail(MLPO_EINVAL, "inv_scale must be finite and > 0");
+    if (isnan(max_norm)) return fail(MLPO_EINVAL, "max_norm is NaN");
+    if (out == nullptr || misaligned(out, 16)) return fail(MLPO_EINVAL, "out is NULL or not 16-byte aligned");
+    void* ws = nullptr;
+    rc = static_norm_workspace(&ws);
+    if (rc != MLPO_OK) return rc;
+    return launch_grad_norm(sg, n_sg, inv_scale, max_norm, ws, out, static_cast<hipStream_t>(stream),
+                            /*may_time=*/false);
+}
+
 int mlpo_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t n, int32_t first, int32_t blocks,
                          int32_t half_format, void* stream) {
     if (n == 0) return MLPO_OK;

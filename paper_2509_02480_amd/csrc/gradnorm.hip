@@ -16,6 +16,8 @@
 #include <hip/hip_ext.h>
 #include <math.h>
 
+#include <mutex>
+
 #include "mlpo_internal.h"
 
 #pragma clang fp contract(off)
@@ -228,7 +230,7 @@ __global__ void __launch_bounds__(kFinishBlock) grad_finish_kernel(Workspace* __
 // Cuts the batch into workgroups and launches it, then the fold.  pieces[i] = 4 KiB pieces of entry i (at least one,
 // so that an array that is all head still has a workgroup).
 int flush(NormBatch& b, const uint64_t* pieces, bool first, bool last, float inv_scale, float max_norm, Workspace* ws,
-          mlpo_step_scalars* out, hipStream_t st) {
+          mlpo_step_scalars* out, hipStream_t st, bool may_time) {
     uint32_t grid = 0;
     if (b.n_sg > 0) {
         uint64_t total = 0;
@@ -241,7 +243,7 @@ int flush(NormBatch& b, const uint64_t* pieces, bool first, bool last, float inv
             b.block_begin[i + 1] = b.block_begin[i] + (uint32_t)((pieces[i] + per_block - 1) / per_block);
         grid = b.block_begin[b.n_sg];  // <= kTargetBlocks + n_sg <= kMaxGrid
         hipEvent_t t0, t1;
-        if (timing_enabled() && timing_acquire(kTimedGradPass, &t0, &t1))
+        if (may_time && timing_enabled() && timing_acquire(kTimedGradPass, &t0, &t1))
             hipExtLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, b, inv_scale, ws);
         else
             hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws);
@@ -263,7 +265,7 @@ int launch_norm_fold(NormWorkspace* ws, int n_partials, bool first, bool last, f
 size_t grad_norm_workspace_bytes() { return sizeof(Workspace); }
 
 int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float max_norm, void* workspace,
-                     mlpo_step_scalars* out, hipStream_t stream) {
+                     mlpo_step_scalars* out, hipStream_t stream, bool may_time) {
     Workspace* ws = static_cast<Workspace*>(workspace);
     NormBatch b;
     uint64_t pieces[kMaxSg];
@@ -274,7 +276,7 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
     // Adds the array [g, g + n) to the batch as one entry.
     const auto push = [&](const uint16_t* g, uint64_t n) -> int {
         if (b.n_sg == kMaxSg) {  // more arrays than one argument block holds: the running totals carry over
-            const int r = flush(b, pieces, first, false, inv_scale, max_norm, ws, out, stream);
+            const int r = flush(b, pieces, first, false, inv_scale, max_norm, ws, out, stream, may_time);
             if (r != MLPO_OK) return r;
             first = false;
             b.n_sg = 0;
@@ -306,7 +308,32 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
         run_n = sg[i].n;
     }
     if (run != nullptr && (rc = push(run, run_n)) != MLPO_OK) return rc;
-    return flush(b, pieces, first, true, inv_scale, max_norm, ws, out, stream);
+    return flush(b, pieces, first, true, inv_scale, max_norm, ws, out, stream, may_time);
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------------------
+// Its workspace is this array in the library's own device image: every GPU the library runs on holds one copy for as
+// long as the process lives, and every call on a GPU uses that GPU's copy.
+static __device__ __align__(256) unsigned char scratch[sizeof(NormWorkspace)];
+
+namespace {
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};  // the array's address on each device, asked for once per device
+}  // namespace
+
+int static_norm_workspace(void** out) {
+    int dev = 0;
+    MLPO_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MLPO_EHIP, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        MLPO_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));  // the current device's copy
+        if (ptr == nullptr) return fail(MLPO_EHIP, "the scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MLPO_OK;
 }
 
 }  // namespace mlpo
