@@ -328,6 +328,16 @@ typedef struct {
     double wall_seconds;
 } mlpo_file_stats;
 
+/* The same per file path (paths are told apart by the file system their descriptors lie on; path_id is that file
+ * system's device number as fstat reports it, so a caller can match the entries with its descriptors).  used = 0
+ * marks entries beyond the number of paths of the call. */
+typedef struct {
+    uint64_t path_id;
+    int32_t used;
+    int32_t reserved;
+    mlpo_file_stats stats;
+} mlpo_path_stats;
+
 /* Configuration of the tiered pipeline.
  * mode MLPO_STREAM_STAGED: host-tier subgroups are fetched into device staging slots by asynchronous copies, updated
  *   there and flushed back (three stages on three streams, at most n_slots subgroups or chunks in flight).
@@ -369,15 +379,22 @@ typedef struct {
                               through which file-tier pieces pass (read from the file, updated in place by the
                               kernel over the link, written back) */
     size_t bounce_bytes;   /* >= mlpo_stream_bounce_bytes(...) */
-    int32_t file_slots;    /* 1..MLPO_MAX_SLOTS: bound on file-tier pieces in flight; 3 lets read, update and write
-                              overlap */
-    int32_t file_threads;  /* threads per direction that move the pieces between file and bounce buffers, each an
-                              equal share of every piece; 0 = default (2); at most 16 */
+    int32_t file_slots;    /* 1..MLPO_MAX_SLOTS: bounce buffers = bound on file-tier pieces in flight.  They are divided
+                              evenly among the file paths in use (files on different file systems: each path has
+                              its own buffers, so at least one per path; 3 per path let read, update and write
+                              overlap) */
+    int32_t file_threads;  /* threads per direction AND PATH that move the pieces between file and bounce buffers,
+                              each an equal share of every piece; 0 = default (2); at most 16 */
     mlpo_file_stats* file_stats; /* host pointer or NULL: receives what the file path moved and how long it took
                                     (all zero after a skipped step or when nothing is file-tier) */
     const mlpo_flush_target* flush_to; /* direct mode: host array with one entry per subgroup of the table, or NULL
                                           (everything goes back to where it came from).  A target in a file needs
                                           the bounce buffers even if no subgroup is file-tier yet */
+    mlpo_path_stats* path_stats;   /* host array of path_stats_cap entries or NULL: receives what each file path moved,
+                                      in the order in which the paths first come up in the processing order: the
+                                      observed bandwidths that Eq. 1's re-estimation takes, path by path */
+    int32_t path_stats_cap;        /* entries in path_stats (0 with NULL) */
+    int32_t reserved2;             /* must be 0 */
 } mlpo_stream_cfg;
 
 /* Staging bytes needed for these subgroups under this n_slots / chunk_elems (0 if no subgroup is host-tier).  With a
@@ -404,10 +421,12 @@ size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t f
  * the file into free bounce buffers, the update kernel works on a bounce buffer in place over the
  * link with direct_blocks workgroups, and writing threads put the piece back into the file once its kernel has
  * finished; a bounce buffer is refilled only after its piece has been written, so at most file_slots pieces are in
- * flight (the three-stage overlap of Section 3.4 on this path).  Host-tier and file-tier work share the link, so
- * their kernels go to one stream, in pieces of chunk_elems, a file-tier piece as soon as it has been read and
- * host-tier pieces in between: the disk works while the link is busy with the host tier (the multi-path overlap of
- * Section 3.2).  With file-tier subgroups the call returns only when their state is back in the file; the rest is
+ * flight (the three-stage overlap of Section 3.4 on this path).  Files on different file systems are different
+ * paths: each has its own reading and writing threads, its own share of the bounce buffers and its own place in the
+ * queue, so a slow disk never holds up a faster path (Section 3.2: every path of a virtual tier has workers of its
+ * own).  Host-tier and file-tier work share the link, so their kernels go to one stream, in pieces of chunk_elems, a
+ * file-tier piece as soon as it has been read (the paths take turns) and host-tier pieces in between: the files
+ * work while the link is busy with the host tier (the multi-path overlap of Section 3.2).  With file-tier subgroups the call returns only when their state is back in the file; the rest is
  * enqueued as usual.
  *
  * Flush targets (cfg->flush_to, direct mode; see mlpo_flush_target): a subgroup with a target is cut into pieces of

@@ -67,6 +67,10 @@ class FileStatsC(C.Structure):
                 ("write_seconds", C.c_double), ("wall_seconds", C.c_double)]
 
 
+class PathStatsC(C.Structure):
+    _fields_ = [("path_id", C.c_uint64), ("used", C.c_int32), ("reserved", C.c_int32), ("stats", FileStatsC)]
+
+
 class FlushTargetC(C.Structure):
     _fields_ = [("tier", C.c_int32), ("reserved", C.c_int32), ("state", C.c_void_p), ("file", FileExtentC)]
 
@@ -80,7 +84,8 @@ class StreamCfgC(C.Structure):
                 ("d2h", C.c_void_p), ("direct_blocks", C.c_int32), ("reserved", C.c_int32),
                 ("cache", C.POINTER(SlotCacheC)), ("files", C.POINTER(FileExtentC)), ("bounce", C.c_void_p),
                 ("bounce_bytes", C.c_size_t), ("file_slots", C.c_int32), ("file_threads", C.c_int32),
-                ("file_stats", C.POINTER(FileStatsC)), ("flush_to", C.POINTER(FlushTargetC))]
+                ("file_stats", C.POINTER(FileStatsC)), ("flush_to", C.POINTER(FlushTargetC)),
+                ("path_stats", C.POINTER(PathStatsC)), ("path_stats_cap", C.c_int32), ("reserved2", C.c_int32)]
 
 
 @dataclass
@@ -286,7 +291,7 @@ def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chu
     """Staged mode: host-tier subgroups travel through ``n_slots`` device staging slots.  ``cache`` (a zero-initialised
     SlotCacheC kept by the caller) lets slots keep their subgroups between steps."""
     cfg = StreamCfgC(n_slots, STREAM_STAGED, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d),
-                     _stream(compute), _stream(d2h), 0, 0, None, None, None, 0, 0, 0, None, None)
+                     _stream(compute), _stream(d2h), 0, 0, None, None, None, 0, 0, 0, None, None, None, 0, 0)
     if cache is not None:
         cfg.cache = C.pointer(cache)
         cfg._keep = cache
@@ -318,7 +323,8 @@ def direct_cfg(host_stream, compute, direct_blocks: int = 0, chunk_elems: int = 
     ``files`` (one (fd, offset) pair or None per subgroup), ``bounce`` (pinned host tensor) and ``file_slots``
     configure the file path; ``cfg.stats`` then holds what it moved after each call if ``want_file_stats``."""
     cfg = StreamCfgC(0, STREAM_DIRECT, chunk_elems, None, 0, _stream(host_stream), _stream(compute), _stream(compute),
-                     direct_blocks, 0, None, None, _ptr(bounce), bounce_bytes, file_slots, file_threads, None, None)
+                     direct_blocks, 0, None, None, _ptr(bounce), bounce_bytes, file_slots, file_threads, None, None,
+                     None, 0, 0)
     if flush_to is not None:
         cfg._flush = flush_targets(flush_to)
         cfg.flush_to = cfg._flush
@@ -334,6 +340,9 @@ def direct_cfg(host_stream, compute, direct_blocks: int = 0, chunk_elems: int = 
     if want_file_stats:
         cfg.stats = FileStatsC()
         cfg.file_stats = C.pointer(cfg.stats)
+        cfg.paths = (PathStatsC * 8)()          # per path, in the order the paths come up in the processing order
+        cfg.path_stats = cfg.paths
+        cfg.path_stats_cap = 8
     return cfg
 
 

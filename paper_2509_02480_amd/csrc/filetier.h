@@ -25,18 +25,23 @@ struct FileJob {
     uint64_t rd_off = 0, wr_off = 0;  // byte offsets of the piece in the two files
     FileIo rd_io = FileIo::kBuffered, wr_io = FileIo::kBuffered;
     size_t bytes = 0;
-    void* buffer = nullptr;  // its bounce buffer (pinned host); job i uses buffer i % n_slots
+    void* buffer = nullptr;  // its bounce buffer (pinned host): the pool's buffer (position in the pool) % (pool's slots)
+    int pool = 0;            // the path whose workers move it and whose bounce buffers it passes through
     SgView view{};           // what the kernel reads and where it stores
 };
 
-// Reads the jobs in order into their bounce buffers and writes each back after its kernel has finished, with
-// n_threads threads per direction that each move an equal share of every piece.  Job i may be read once job
-// i - n_slots has been written (the buffer is the same), so at most n_slots pieces are in flight.
-// The owner launches the kernels: it learns from is_read / wait_read that a piece has arrived and reports the event
-// that marks the end of the piece's kernel with hand_to_writer.
+// The workers of the file paths (Section 3.2 "Unified Multi-level, Multi-path Asynchronous Offloading using Virtual
+// Tiers": every path has workers of its own, so that a slow path does not hold up a fast one).  Each pool - one per
+// path - reads ITS jobs in order into ITS bounce buffers and writes each back after its kernel has finished, with
+// n_threads threads per direction that each move an equal share of every piece.  The job at position q of a pool may
+// be read once the job at position q - slots[pool] has been written (the buffer is the same), so at most slots[pool]
+// pieces of a path are in flight; the pools do not wait for one another.
+// The owner launches the kernels: it learns from is_read / wait_any_read that a piece has arrived and reports the
+// event that marks the end of the piece's kernel with hand_to_writer.
 class FilePath {
   public:
-    FilePath(std::vector<FileJob> jobs, int n_slots, int n_threads, int device);
+    // jobs in processing order, each with its pool; slots[p] = bounce buffers of pool p (>= 1).
+    FilePath(std::vector<FileJob> jobs, std::vector<int> slots, int n_threads, int device);
     ~FilePath();
     FilePath(const FilePath&) = delete;
     FilePath& operator=(const FilePath&) = delete;
@@ -44,22 +49,34 @@ class FilePath {
     bool start();  // false: a thread could not be started (join reports why)
     size_t size() const { return jobs_.size(); }
     const FileJob& job(size_t i) const { return jobs_[i]; }
+    int n_pools() const { return (int)pool_jobs_.size(); }
+    size_t pool_size(int p) const { return pool_jobs_[(size_t)p].size(); }
+    size_t pool_job(int p, size_t q) const { return pool_jobs_[(size_t)p][q]; }  // index of the pool's q-th job
     bool is_read(size_t i);                         // never blocks
     bool wait_read(size_t i);                       // false: the path has stopped and the piece will not arrive
+    // Waits until one of the jobs listed has been read; false: the paths have stopped and none of them will arrive.
+    bool wait_any_read(const std::vector<size_t>& jobs);
     bool failed();
     void stop();                                    // the owner gave up: waiting threads leave without an error text
     void hand_to_writer(size_t i, hipEvent_t done);  // done: recorded behind the piece's kernel
-    // Waits for both threads.  false: something failed, *error says what.
-    bool join(mlpo_file_stats* stats, std::string* error);
+    // Waits for all threads.  false: something failed, *error says what.  stats: all pools together; per_pool (may be
+    // NULL): what each pool moved.
+    bool join(mlpo_file_stats* stats, std::string* error, std::vector<mlpo_file_stats>* per_pool = nullptr);
 
   private:
-    void read_loop(int r);
-    void write_loop(int r);
+    struct PoolStats {
+        uint64_t bytes_read = 0, bytes_written = 0;
+        double read_seconds = 0.0, write_seconds = 0.0, t_end = 0.0;
+    };
+    void read_loop(int pool, int r);
+    void write_loop(int pool, int r);
     void join_threads();
     void fail_with(const std::string& why);
 
     std::vector<FileJob> jobs_;
-    int n_slots_, n_threads_, device_;
+    std::vector<std::vector<size_t>> pool_jobs_;  // per pool: its jobs, in order
+    std::vector<int> slots_;
+    int n_threads_, device_;
     std::mutex mu_;
     std::condition_variable cv_;
     std::vector<int> read_, launched_, written_;  // read_ / written_: threads that have moved their share
@@ -67,11 +84,15 @@ class FilePath {
     bool stopped_ = false;
     std::string error_;
     std::vector<std::thread> threads_;
-    uint64_t bytes_read_ = 0, bytes_written_ = 0;
-    double read_seconds_ = 0.0, write_seconds_ = 0.0, t_begin_ = 0.0, t_end_ = 0.0;
+    std::vector<PoolStats> stats_;
+    double t_begin_ = 0.0;
 };
 
 // Argument check of one extent: alignment, a regular file, long enough for state_bytes behind offset.
 int check_file_extent(const mlpo_file_extent& x, uint64_t state_bytes, int index);
+
+// The identity of the path a descriptor leads to: the device of its file system (0 if it cannot be told).  Files on
+// one file system share its workers and bounce buffers.
+uint64_t file_path_id(int fd);
 
 }  // namespace mlpo

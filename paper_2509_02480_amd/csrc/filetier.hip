@@ -142,16 +142,15 @@ void share_of(size_t bytes, int r, int n, size_t* begin, size_t* len) {
 
 }  // namespace
 
-FilePath::FilePath(std::vector<FileJob> jobs, int n_slots, int n_threads, int device)
-    : jobs_(std::move(jobs)), n_slots_(n_slots), n_threads_(n_threads), device_(device), read_(jobs_.size(), 0),
-      launched_(jobs_.size(), 0), written_(jobs_.size(), 0), done_(jobs_.size(), nullptr) {}
+FilePath::FilePath(std::vector<FileJob> jobs, std::vector<int> slots, int n_threads, int device)
+    : jobs_(std::move(jobs)), pool_jobs_(slots.size()), slots_(std::move(slots)), n_threads_(n_threads),
+      device_(device), read_(jobs_.size(), 0), launched_(jobs_.size(), 0), written_(jobs_.size(), 0),
+      done_(jobs_.size(), nullptr), stats_(slots_.size()) {
+    for (size_t i = 0; i < jobs_.size(); ++i) pool_jobs_[(size_t)jobs_[i].pool].push_back(i);
+}
 
 FilePath::~FilePath() {
-    {
-        std::lock_guard<std::mutex> lk(mu_);
-        stopped_ = true;  // threads still waiting (the caller gave up early) leave at their next wait
-        cv_.notify_all();
-    }
+    stop();  // threads still waiting (the caller gave up early) leave at their next wait
     join_threads();
 }
 
@@ -163,9 +162,12 @@ void FilePath::join_threads() {
 bool FilePath::start() {
     t_begin_ = now_seconds();
     try {
-        for (int r = 0; r < n_threads_; ++r) {
-            threads_.emplace_back(&FilePath::read_loop, this, r);
-            threads_.emplace_back(&FilePath::write_loop, this, r);
+        for (int p = 0; p < n_pools(); ++p) {
+            if (pool_jobs_[(size_t)p].empty()) continue;
+            for (int r = 0; r < n_threads_; ++r) {
+                threads_.emplace_back(&FilePath::read_loop, this, p, r);
+                threads_.emplace_back(&FilePath::write_loop, this, p, r);
+            }
         }
     } catch (const std::exception& e) {  // the system refused a thread: nothing may cross the C boundary
         fail_with(std::string("starting an I/O thread: ") + e.what());
@@ -181,14 +183,18 @@ void FilePath::fail_with(const std::string& why) {
     cv_.notify_all();
 }
 
-// Every reading thread walks over all jobs and moves its share of each; the last one to finish a job marks it read.
-void FilePath::read_loop(int r) {
+// Every reading thread of a pool walks over the pool's jobs and moves its share of each; the last one to finish a job
+// marks it read.
+void FilePath::read_loop(int pool, int r) {
     AlignedBlock tmp;
-    for (size_t i = 0; i < jobs_.size(); ++i) {
+    const std::vector<size_t>& mine = pool_jobs_[(size_t)pool];
+    const size_t slots = (size_t)slots_[(size_t)pool];
+    for (size_t q = 0; q < mine.size(); ++q) {
+        const size_t i = mine[q];
         {
             std::unique_lock<std::mutex> lk(mu_);
             // the bounce buffer is free once the piece that used it before has been written back
-            cv_.wait(lk, [&] { return stopped_ || i < (size_t)n_slots_ || written_[i - (size_t)n_slots_] == n_threads_; });
+            cv_.wait(lk, [&] { return stopped_ || q < slots || written_[mine[q - slots]] == n_threads_; });
             if (stopped_) return;
         }
         const FileJob& j = jobs_[i];
@@ -204,19 +210,19 @@ void FilePath::read_loop(int r) {
             return;
         }
         std::lock_guard<std::mutex> lk(mu_);
-        read_seconds_ += t1 - t0;
-        bytes_read_ += len;
+        stats_[(size_t)pool].read_seconds += t1 - t0;
+        stats_[(size_t)pool].bytes_read += len;
         if (++read_[i] == n_threads_) cv_.notify_all();
     }
 }
 
-void FilePath::write_loop(int r) {
+void FilePath::write_loop(int pool, int r) {
     if (hipSetDevice(device_) != hipSuccess) {
         fail_with("hipSetDevice failed in a writing thread");
         return;
     }
     AlignedBlock tmp;
-    for (size_t i = 0; i < jobs_.size(); ++i) {
+    for (const size_t i : pool_jobs_[(size_t)pool]) {
         hipEvent_t done;
         {
             std::unique_lock<std::mutex> lk(mu_);
@@ -242,9 +248,10 @@ void FilePath::write_loop(int r) {
             return;
         }
         std::lock_guard<std::mutex> lk(mu_);
-        write_seconds_ += t1 - t0;
-        bytes_written_ += len;
-        if (t1 > t_end_) t_end_ = t1;
+        PoolStats& ps = stats_[(size_t)pool];
+        ps.write_seconds += t1 - t0;
+        ps.bytes_written += len;
+        if (t1 > ps.t_end) ps.t_end = t1;
         if (++written_[i] == n_threads_) cv_.notify_all();
     }
 }
@@ -258,6 +265,17 @@ bool FilePath::wait_read(size_t i) {
     std::unique_lock<std::mutex> lk(mu_);
     cv_.wait(lk, [&] { return stopped_ || read_[i] == n_threads_; });
     return read_[i] == n_threads_;
+}
+
+bool FilePath::wait_any_read(const std::vector<size_t>& jobs) {
+    const auto any = [&] {
+        for (const size_t i : jobs)
+            if (read_[i] == n_threads_) return true;
+        return false;
+    };
+    std::unique_lock<std::mutex> lk(mu_);
+    cv_.wait(lk, [&] { return stopped_ || any(); });
+    return any();
 }
 
 bool FilePath::failed() {
@@ -278,21 +296,38 @@ void FilePath::hand_to_writer(size_t i, hipEvent_t done) {
     cv_.notify_all();
 }
 
-bool FilePath::join(mlpo_file_stats* stats, std::string* error) {
+bool FilePath::join(mlpo_file_stats* stats, std::string* error, std::vector<mlpo_file_stats>* per_pool) {
     join_threads();
     std::lock_guard<std::mutex> lk(mu_);
-    if (stats != nullptr) {
-        stats->bytes_read = bytes_read_;
-        stats->bytes_written = bytes_written_;
-        stats->read_seconds = read_seconds_;
-        stats->write_seconds = write_seconds_;
-        stats->wall_seconds = t_end_ > t_begin_ ? t_end_ - t_begin_ : 0.0;
+    mlpo_file_stats all{};
+    if (per_pool != nullptr) per_pool->assign(stats_.size(), mlpo_file_stats{});
+    for (size_t p = 0; p < stats_.size(); ++p) {
+        const PoolStats& ps = stats_[p];
+        mlpo_file_stats one{};
+        one.bytes_read = ps.bytes_read;
+        one.bytes_written = ps.bytes_written;
+        one.read_seconds = ps.read_seconds;
+        one.write_seconds = ps.write_seconds;
+        one.wall_seconds = ps.t_end > t_begin_ ? ps.t_end - t_begin_ : 0.0;
+        if (per_pool != nullptr) (*per_pool)[p] = one;
+        all.bytes_read += one.bytes_read;
+        all.bytes_written += one.bytes_written;
+        all.read_seconds += one.read_seconds;
+        all.write_seconds += one.write_seconds;
+        if (one.wall_seconds > all.wall_seconds) all.wall_seconds = one.wall_seconds;
     }
+    if (stats != nullptr) *stats = all;
     if (!error_.empty()) {
         *error = error_;
         return false;
     }
     return true;
+}
+
+uint64_t file_path_id(int fd) {
+    struct stat sb;
+    if (fstat(fd, &sb) != 0) return 0;
+    return (uint64_t)sb.st_dev;
 }
 
 FileIo file_io_kind(int fd) {

@@ -270,6 +270,9 @@ struct Streams {
     hipStream_t h2d, cmp, d2h;
 };
 
+static std::vector<uint64_t> file_paths_of(const mlpo_subgroup* sg, const std::vector<int32_t>& ids,
+                                           const mlpo_stream_cfg* cfg);
+
 static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* order,
                              const mlpo_adamw_hparams* hp, int64_t step, const mlpo_step_scalars* scalars,
                              const mlpo_stream_cfg* cfg, uint64_t* slot_floats_out) {
@@ -279,7 +282,7 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
     if (rc != MLPO_OK) return rc;
     if (scalars != nullptr && misaligned(scalars, 16)) return fail(MLPO_EINVAL, "scalars not 16-byte aligned");
     if (cfg == nullptr) return fail(MLPO_EINVAL, "cfg is NULL");
-    if (cfg->reserved != 0) return fail(MLPO_EINVAL, "cfg reserved field is not 0");
+    if (cfg->reserved != 0 || cfg->reserved2 != 0) return fail(MLPO_EINVAL, "cfg reserved field is not 0");
     if (cfg->mode != MLPO_STREAM_STAGED && cfg->mode != MLPO_STREAM_DIRECT)
         return fail(MLPO_EINVAL, "unknown mode %d", cfg->mode);
     const bool direct = cfg->mode == MLPO_STREAM_DIRECT;
@@ -335,6 +338,8 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
             }
         }
     }
+    if (cfg->path_stats_cap < 0 || (cfg->path_stats_cap > 0 && cfg->path_stats == nullptr))
+        return fail(MLPO_EINVAL, "path_stats_cap is negative, or positive with path_stats NULL");
     if (cfg->file_threads < 0 || cfg->file_threads > 16)
         return fail(MLPO_EINVAL, "file_threads must be 0..16 (got %d)", cfg->file_threads);
     if (any_bounce) {
@@ -344,6 +349,14 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
             return fail(MLPO_EINVAL, "file_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->file_slots);
         if (cfg->bounce == nullptr || misaligned(cfg->bounce, 4096))
             return fail(MLPO_EINVAL, "bounce is NULL or not 4096-byte aligned");
+        {
+            std::vector<int32_t> all((size_t)n_sg);
+            for (int32_t i = 0; i < n_sg; ++i) all[(size_t)i] = i;
+            const size_t n_paths = file_paths_of(sg, all, cfg).size();
+            if ((size_t)cfg->file_slots < n_paths)
+                return fail(MLPO_EINVAL, "file_slots is %d but the files lie on %zu different paths: every path needs "
+                            "a bounce buffer of its own", cfg->file_slots, n_paths);
+        }
         const uint64_t need_bounce =
             bounce_slot_bytes(sg, n_sg, cfg->chunk_elems, cfg->flush_to) * (uint64_t)cfg->file_slots;
         if (cfg->bounce_bytes < need_bounce)
@@ -421,11 +434,42 @@ static const mlpo_flush_target* flush_target(const mlpo_stream_cfg* cfg, int32_t
 struct LinkWork {
     std::vector<SgView> host_pieces;
     std::vector<FileJob> jobs;
+    std::vector<uint64_t> pool_path;  // per pool: the identity of its path (file_path_id)
+    std::vector<int> pool_slots;      // per pool: its share of the bounce buffers
 };
+
+// The paths that the file sides of this call lead to, in processing order: one pool of workers and bounce buffers
+// each.  A piece belongs to the path it is read from, or, if it only goes to a file, to the path it is written to.
+static std::vector<uint64_t> file_paths_of(const mlpo_subgroup* sg, const std::vector<int32_t>& ids,
+                                           const mlpo_stream_cfg* cfg) {
+    std::vector<uint64_t> paths;
+    for (int32_t i : ids) {
+        const mlpo_flush_target* to =
+            (cfg->flush_to != nullptr && cfg->flush_to[i].tier != MLPO_FLUSH_IN_PLACE) ? &cfg->flush_to[i] : nullptr;
+        const bool from_file = sg[i].tier == MLPO_TIER_FILE;
+        const bool to_file = to != nullptr ? to->tier == MLPO_TIER_FILE : from_file;
+        if (!from_file && !to_file) continue;
+        const int fd = from_file ? cfg->files[i].fd : to->file.fd;
+        const uint64_t id = file_path_id(fd);
+        bool seen = false;
+        for (uint64_t q : paths) seen = seen || q == id;
+        if (!seen) paths.push_back(id);
+    }
+    return paths;
+}
 
 static LinkWork link_work(const mlpo_subgroup* sg, const Plan& plan, const mlpo_stream_cfg* cfg,
                           uint64_t buffer_bytes) {
     LinkWork w;
+    w.pool_path = file_paths_of(sg, plan.offloaded_ids, cfg);
+    const size_t n_pools = w.pool_path.size();
+    // the bounce buffers are divided evenly among the paths (checked: at least one each)
+    std::vector<size_t> pool_base(n_pools, 0), pool_count(n_pools, 0);
+    for (size_t p = 0; p < n_pools; ++p) {
+        const int share = cfg->file_slots / (int)n_pools + ((int)p < cfg->file_slots % (int)n_pools ? 1 : 0);
+        w.pool_slots.push_back(share);
+        pool_base[p] = p == 0 ? 0 : pool_base[p - 1] + (size_t)w.pool_slots[p - 1];
+    }
     for (int32_t i : plan.offloaded_ids) {
         const mlpo_subgroup& s = sg[i];
         const mlpo_flush_target* to = flush_target(cfg, i);
@@ -433,6 +477,11 @@ static LinkWork link_work(const mlpo_subgroup* sg, const Plan& plan, const mlpo_
         const bool to_file = to != nullptr ? to->tier == MLPO_TIER_FILE : from_file;
         const uint64_t T = (uint64_t)s.tile_elems;  // 0 only for planar host-tier subgroups, which stay in place
         const uint64_t step_elems = piece_elems(s, cfg->chunk_elems);
+        size_t pool = 0;
+        if (from_file || to_file) {
+            const uint64_t id = file_path_id(from_file ? cfg->files[i].fd : to->file.fd);
+            while (pool + 1 < n_pools && w.pool_path[pool] != id) ++pool;
+        }
         for (uint64_t off = 0; off < s.n; off += step_elems) {
             const uint64_t len = (s.n - off < step_elems) ? (s.n - off) : step_elems;
             // chunk is a multiple of the layout tile, so a piece starts at a layout tile boundary
@@ -444,8 +493,10 @@ static LinkWork link_work(const mlpo_subgroup* sg, const Plan& plan, const mlpo_
                 continue;
             }
             FileJob j;
+            j.pool = (int)pool;
             j.bytes = (size_t)(round_up(len, T) * 3u * sizeof(float));
-            char* buf = static_cast<char*>(cfg->bounce) + (w.jobs.size() % (size_t)cfg->file_slots) * buffer_bytes;
+            const size_t slot = pool_base[pool] + pool_count[pool]++ % (size_t)w.pool_slots[pool];
+            char* buf = static_cast<char*>(cfg->bounce) + slot * buffer_bytes;
             float* f = reinterpret_cast<float*>(buf);
             j.buffer = buf;
             j.has_read = from_file;
@@ -473,11 +524,13 @@ static LinkWork link_work(const mlpo_subgroup* sg, const Plan& plan, const mlpo_
     return w;
 }
 
-// Direct mode with file-tier subgroups or flush targets: two paths behind the offloaded tier (Section 3.2 "Unified
-// Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers").  Both end on the link, so their kernels share
-// one stream: pinned-only pieces, and pieces that pass through a bounce buffer, each launched as soon as its read has
-// finished (or, without a read side, as soon as its buffer is free).  At most two launches are queued at a time, so a piece that arrives from the file waits for one
-// host-tier piece at most, and the file keeps working while the link is busy with the host tier.
+// Direct mode with file-tier subgroups or flush targets: several paths behind the offloaded tier (Section 3.2 "Unified
+// Multi-level, Multi-path Asynchronous Offloading using Virtual Tiers").  All of them end on the link, so their
+// kernels share one stream: pinned-only pieces, and pieces that pass through a bounce buffer, each launched as soon
+// as its read has finished (or, without a read side, as soon as its buffer is free).  Every file path has its own
+// workers, bounce buffers and place in the queue, so a piece from a fast path is never behind one from a slow path.
+// At most two launches are queued at a time, so a piece that arrives from a file waits for one other piece at
+// most, and the files keep working while the link is busy with the host tier.
 static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& plan, const AdamwConsts& c,
                             const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, const Streams& st,
                             EventCache& ec) {
@@ -486,9 +539,12 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
     int device = 0;
     MLPO_HIP(hipGetDevice(&device));
     const int blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 64;
-    LinkWork work = link_work(sg, plan, cfg, bounce_slot_bytes(sg, n_sg, cfg->chunk_elems, cfg->flush_to));
+    const uint64_t buffer_bytes = bounce_slot_bytes(sg, n_sg, cfg->chunk_elems, cfg->flush_to);
+    LinkWork work = link_work(sg, plan, cfg, buffer_bytes);
     const std::vector<SgView>& host_pieces = work.host_pieces;
-    FilePath files(std::move(work.jobs), cfg->file_slots, cfg->file_threads > 0 ? cfg->file_threads : 2, device);
+    const std::vector<uint64_t> pool_path = work.pool_path;
+    FilePath files(std::move(work.jobs), work.pool_slots, cfg->file_threads > 0 ? cfg->file_threads : 2, device);
+    const int n_pools = files.n_pools();
 
     MLPO_HIP(hipEventRecord(ec.fence2, st.cmp));  // gradients and scalars come from the compute stream
     MLPO_HIP(hipStreamWaitEvent(st.h2d, ec.fence2, 0));
@@ -505,18 +561,38 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
             const int r = launch_adamw(plan.resident.data(), (int)plan.resident.size(), c, scalars, st.cmp);
             if (r != MLPO_OK) return r;
         }
-        size_t next_host = 0, next_file = 0, launched = 0;
-        while (next_host < host_pieces.size() || next_file < files.size()) {
+        size_t next_host = 0, launched = 0;
+        std::vector<size_t> next((size_t)n_pools, 0);  // per path: its next piece
+        int turn = 0;                                  // the path asked first: they take turns
+        for (;;) {
             if (files.failed()) break;
-            if (next_host >= host_pieces.size() && !files.wait_read(next_file)) break;  // only the file is left
-            if (launched >= 2) MLPO_HIP(hipEventSynchronize(ec.pace[launched % 2]));    // the launch before the last
-            if (next_file < files.size() && files.is_read(next_file)) {
-                const int r = launch_adamw(&files.job(next_file).view, 1, c, scalars, st.h2d, blocks);
+            std::vector<size_t> waiting;  // the next piece of every path that still has one
+            for (int p = 0; p < n_pools; ++p)
+                if (next[(size_t)p] < files.pool_size(p)) waiting.push_back(files.pool_job(p, next[(size_t)p]));
+            if (waiting.empty() && next_host >= host_pieces.size()) break;
+            int ready = -1;
+            for (int k = 0; k < n_pools && ready < 0; ++k) {
+                const int p = (turn + k) % n_pools;
+                if (next[(size_t)p] < files.pool_size(p) && files.is_read(files.pool_job(p, next[(size_t)p]))) ready = p;
+            }
+            if (ready < 0 && next_host >= host_pieces.size()) {  // only files are left and nothing has arrived yet
+                if (!files.wait_any_read(waiting)) break;
+                continue;
+            }
+            if (launched >= 2) MLPO_HIP(hipEventSynchronize(ec.pace[launched % 2]));  // the launch before the last
+            if (ready >= 0) {
+                const size_t i = files.pool_job(ready, next[(size_t)ready]);
+                const FileJob& j = files.job(i);
+                const int r = launch_adamw(&j.view, 1, c, scalars, st.h2d, blocks);
                 if (r != MLPO_OK) return r;
-                hipEvent_t done = ec.file_done[next_file % (size_t)cfg->file_slots];
+                // one event per bounce buffer: the buffer's previous piece has been written, so its event is free
+                const size_t buffer = (size_t)((static_cast<const char*>(j.buffer) - static_cast<const char*>(cfg->bounce)) /
+                                               (ptrdiff_t)buffer_bytes);
+                hipEvent_t done = ec.file_done[buffer];
                 MLPO_HIP(hipEventRecord(done, st.h2d));
-                files.hand_to_writer(next_file, done);
-                ++next_file;
+                files.hand_to_writer(i, done);
+                ++next[(size_t)ready];
+                turn = (ready + 1) % n_pools;
             } else {
                 const int r = launch_adamw(&host_pieces[next_host], 1, c, scalars, st.h2d, blocks);
                 if (r != MLPO_OK) return r;
@@ -533,7 +609,17 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
     const hipError_t fence_wait = fence_rec == hipSuccess ? hipStreamWaitEvent(st.cmp, ec.fence, 0) : fence_rec;
     if (fence_wait != hipSuccess) (void)hipStreamSynchronize(st.h2d);  // no fence: wait here instead
     std::string err;
-    const bool io_ok = files.join(cfg->file_stats, &err);
+    std::vector<mlpo_file_stats> per_pool;
+    const bool io_ok = files.join(cfg->file_stats, &err, &per_pool);
+    for (int32_t k = 0; k < cfg->path_stats_cap; ++k) {  // what each path moved, in the order the paths came up
+        mlpo_path_stats& out = cfg->path_stats[k];
+        out = mlpo_path_stats{};
+        if ((size_t)k < per_pool.size()) {
+            out.path_id = pool_path[(size_t)k];
+            out.used = 1;
+            out.stats = per_pool[(size_t)k];
+        }
+    }
     if (rc != MLPO_OK) return rc;
     if (fence_wait != hipSuccess) return fail(MLPO_EHIP, "fencing the link stream: %s", hipGetErrorString(fence_wait));
     if (!io_ok) return fail(MLPO_EIO, "%s", err.c_str());
@@ -720,6 +806,7 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     if (rc != MLPO_OK) return rc;
     if (applied != nullptr) *applied = 1;
     if (cfg->file_stats != nullptr) memset(cfg->file_stats, 0, sizeof *cfg->file_stats);  // nothing moved so far
+    for (int32_t k = 0; k < cfg->path_stats_cap; ++k) cfg->path_stats[k] = mlpo_path_stats{};
     if (n_sg == 0) return MLPO_OK;
 
     Streams st{static_cast<hipStream_t>(cfg->h2d), static_cast<hipStream_t>(cfg->compute),

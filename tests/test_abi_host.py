@@ -229,7 +229,9 @@ int main(void) {
            sizeof(mlpo_step_scalars), sizeof(mlpo_slot_cache), sizeof(mlpo_stream_cfg), sizeof(mlpo_file_extent),
            sizeof(mlpo_file_stats), offsetof(mlpo_stream_cfg, flush_to), offsetof(mlpo_slot_cache, hits),
            offsetof(mlpo_subgroup, tile_elems));
-    printf("%zu %zu\\n", sizeof(mlpo_flush_target), offsetof(mlpo_flush_target, file));
+    printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(mlpo_flush_target), offsetof(mlpo_flush_target, file),
+           sizeof(mlpo_path_stats), offsetof(mlpo_path_stats, stats), offsetof(mlpo_stream_cfg, path_stats),
+           offsetof(mlpo_stream_cfg, path_stats_cap));
     return 0;
 }
 ''')
@@ -240,7 +242,8 @@ int main(void) {
     want = [C.sizeof(B.HParamsC), C.sizeof(B.SubgroupC), C.sizeof(B.StepScalarsC), C.sizeof(B.SlotCacheC),
             C.sizeof(B.StreamCfgC), C.sizeof(B.FileExtentC), C.sizeof(B.FileStatsC), B.StreamCfgC.flush_to.offset,
             B.SlotCacheC.hits.offset, B.SubgroupC.tile_elems.offset, C.sizeof(B.FlushTargetC),
-            B.FlushTargetC.file.offset]
+            B.FlushTargetC.file.offset, C.sizeof(B.PathStatsC), B.PathStatsC.stats.offset,
+            B.StreamCfgC.path_stats.offset, B.StreamCfgC.path_stats_cap.offset]
     assert got == want
 
 

@@ -19,40 +19,49 @@ from gpu_util import Scratch, assert_state_parity, dev, hp_pair, pack_tiled, unp
 
 
 class Shard:
-    """Subgroups of a workload spread over HBM, pinned host memory and one file, in the tiled layout."""
+    """Subgroups of a workload spread over HBM, pinned host memory and one file (or two: the subgroups listed in
+    ``second`` live in ``path2``, which may lie on another file system, i.e. be another path), in the tiled layout."""
 
-    def __init__(self, host, tiers, T, path, direct_io=True):
+    def __init__(self, host, tiers, T, path, direct_io=True, path2=None, second=()):
         self.T, self.tiers, self.n = T, tiers, [s["p"].size for s in host]
         self.keep, descs, self.files = [], [], []
         d = dev()
         flags = os.O_RDWR | os.O_CREAT
         self.direct_io = False
-        self.fd = -1
-        if direct_io:
-            try:
-                self.fd = os.open(path, flags | os.O_DIRECT, 0o600)
-                self.direct_io = True
-            except OSError:
-                self.fd = -1
-        if self.fd < 0:
-            self.fd = os.open(path, flags, 0o600)
-        self.offsets = {}
-        off = 4096          # a header page the library must leave alone
-        with open(path, "r+b") as f:
-            f.write(b"\xAB" * 4096)
-            for k, s in enumerate(host):
-                if tiers[k] != B.TIER_FILE:
-                    continue
-                packed = pack_tiled(s["p"], s["m"], s["v"], T)
-                self.offsets[k] = off
+        self.paths = [path] + ([path2] if path2 else [])
+        self.fds = []
+        for pth in self.paths:
+            fd = -1
+            if direct_io:
+                try:
+                    fd = os.open(pth, flags | os.O_DIRECT, 0o600)
+                    self.direct_io = True
+                except OSError:
+                    fd = -1
+            if fd < 0:
+                fd = os.open(pth, flags, 0o600)
+            self.fds.append(fd)
+        self.fd, self.path = self.fds[0], path
+        self.file_of = {k: (1 if k in second else 0) for k in range(len(host)) if tiers[k] == B.TIER_FILE}
+        self.offsets, self.ends = {}, []
+        for which, pth in enumerate(self.paths):
+            off = 4096          # a header page the library must leave alone
+            with open(pth, "r+b") as f:
+                f.write(b"\xAB" * 4096)
+                for k, s in enumerate(host):
+                    if self.file_of.get(k) != which:
+                        continue
+                    packed = pack_tiled(s["p"], s["m"], s["v"], T)
+                    self.offsets[k] = off
+                    f.seek(off)
+                    f.write(packed.tobytes())
+                    off += (packed.nbytes + 4095) // 4096 * 4096
                 f.seek(off)
-                f.write(packed.tobytes())
-                off += (packed.nbytes + 4095) // 4096 * 4096
-            f.write(b"\xCD" * 4096)          # and a trailer page
-            f.flush()
-            os.fsync(f.fileno())
-        self.end = off
-        self.path = path
+                f.write(b"\xCD" * 4096)          # and a trailer page
+                f.flush()
+                os.fsync(f.fileno())
+            self.ends.append(off)
+        self.end = self.ends[0]
         for k, s in enumerate(host):
             n = self.n[k]
             g = torch.from_numpy(s["g"].view(np.int16)).to(d)
@@ -60,7 +69,7 @@ class Shard:
             ent = {"g": g, "p16": p16}
             if tiers[k] == B.TIER_FILE:
                 descs.append(B.SubgroupC(None, None, None, g.data_ptr(), p16.data_ptr(), n, B.TIER_FILE, T))
-                self.files.append((self.fd, self.offsets[k]))
+                self.files.append((self.fds[self.file_of[k]], self.offsets[k]))
             else:
                 packed = torch.from_numpy(pack_tiled(s["p"], s["m"], s["v"], T))
                 if tiers[k] == B.TIER_HOST:
@@ -83,21 +92,25 @@ class Shard:
         e = self.keep[k]
         if self.tiers[k] == B.TIER_FILE:
             count = B.mlpo_state_floats(self.n[k], self.T)
-            buf = np.fromfile(self.path, dtype=np.float32, count=count, offset=self.offsets[k])
+            buf = np.fromfile(self.paths[self.file_of[k]], dtype=np.float32, count=count, offset=self.offsets[k])
         else:
             buf = e["state"].cpu().numpy()
         p, m, v = unpack_tiled(buf, self.n[k], self.T)
         return {"p": p, "m": m, "v": v, "p16": e["p16"].cpu().numpy().view(np.uint16).copy()}
 
     def guards_intact(self):
-        with open(self.path, "rb") as f:
-            head = f.read(4096)
-            f.seek(self.end)
-            tail = f.read(4096)
-        return head == b"\xAB" * 4096 and tail == b"\xCD" * 4096
+        for pth, end in zip(self.paths, self.ends):
+            with open(pth, "rb") as f:
+                head = f.read(4096)
+                f.seek(end)
+                tail = f.read(4096)
+            if head != b"\xAB" * 4096 or tail != b"\xCD" * 4096:
+                return False
+        return True
 
     def close(self):
-        os.close(self.fd)
+        for fd in self.fds:
+            os.close(fd)
 
 
 def make_cfg(shard, streams, chunk, file_slots, blocks=24):
@@ -156,6 +169,120 @@ def test_file_tier_matches_oracle(oracle, tmp_path, tiers, chunk, file_slots, or
     finally:
         torch.cuda.synchronize()
         shard.close()
+
+
+@pytest.mark.parametrize("chunk,file_slots,threads", [(8192, 6, 2), (16_384, 2, 1), (0, 4, 3)])
+def test_three_paths_side_by_side(oracle, tmp_path, chunk, file_slots, threads):
+    """Three live paths behind the offloaded tier (Section 3.2 "Unified Multi-level, Multi-path Asynchronous
+    Offloading using Virtual Tiers"): pinned host memory, a file in /dev/shm (pageable host memory) and a file on the
+    disk.  Eq. 1 (Section 3.3) splits the subgroups over the three from guessed bandwidths, each file path has its
+    own workers and bounce buffers, the state equals the oracle's after every step, the statistics come back per
+    path, and re-estimating Eq. 1 from what was observed gives an allocation that is carried out by flush targets."""
+    if not os.path.isdir("/dev/shm") or os.stat("/dev/shm").st_dev == os.stat(str(tmp_path)).st_dev:
+        pytest.skip("no second file system for the third path")
+    ohp, ghp = hp_pair(oracle)
+    T = 2048
+    n_sub = 9
+    wl = W.Workload("threepaths", n_sub=n_sub, sub_elems=60_001, n_host=0, loss_scale=32.0, max_norm=0.05, steps=3)
+    host = W.host_subgroups(wl, warm=True)
+    # Eq. 1 over pinned : shm file : disk file with the guess 4 : 3 : 2 -> 4 / 3 / 2 subgroups; the slowest path takes
+    # the lowest ids
+    counts, tier_of = B.mlpo_assign_tiers(n_sub, [4.0, 3.0, 2.0])
+    assert counts == [4, 3, 2] and tier_of == [2, 2, 1, 1, 1, 0, 0, 0, 0]
+    tiers = [H if t == 0 else F for t in tier_of]
+    on_disk = [k for k in range(n_sub) if tier_of[k] == 2]
+    shm = f"/dev/shm/mlpo_three_{os.getpid()}.bin"
+    shard = Shard(host, tiers, T, shm, direct_io=True, path2=str(tmp_path / "disk.bin"), second=on_disk)
+    scratch = Scratch()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    need = B.mlpo_stream_bounce_bytes(shard.table, file_slots, chunk)
+    bounce = torch.empty(max(need, 4096), dtype=torch.uint8, pin_memory=True)
+    cfg = B.direct_cfg(streams[0], streams[1], 24, chunk_elems=chunk, files=shard.files, bounce=bounce,
+                       bounce_bytes=bounce.numel(), file_slots=file_slots, file_threads=threads, want_file_stats=True)
+    per = B.mlpo_state_floats(wl.sub_elems, T) * 4
+    ids = [os.fstat(fd).st_dev for fd in shard.fds]
+    try:
+        for s in range(wl.steps):
+            order = None if s % 2 == 0 else list(range(n_sub))[::-1]
+            if s > 0:
+                for k, sg in enumerate(host):
+                    W.fill_grads(wl, k, s, sg["g"])
+                    shard.set_grads(k, sg["g"])
+            torch.cuda.synchronize()
+            ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm, order=order)
+            B.mlpo_grad_unscale_norm(shard.table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes,
+                                     scratch.scalars, streams[1])
+            assert B.mlpo_stream_update(shard.table, order, ghp, s + 1, scratch.scalars, cfg) and ok_o
+            streams[1].synchronize()
+            assert scratch.read()["gmul"] == gmul_o
+            used = [p for p in cfg.paths if p.used]
+            assert len(used) == 2 and sorted(p.path_id for p in used) == sorted(ids)
+            by_id = {p.path_id: p.stats for p in used}
+            assert by_id[ids[0]].bytes_read == by_id[ids[0]].bytes_written == 3 * per       # the file in /dev/shm
+            assert by_id[ids[1]].bytes_read == by_id[ids[1]].bytes_written == 2 * per       # the file on the disk
+            assert cfg.stats.bytes_read == 5 * per and all(p.stats.wall_seconds > 0 for p in used)
+            # ascending order meets the disk's subgroups first, descending the others'
+            assert used[0].path_id == (ids[1] if order is None else ids[0])
+            for k in range(n_sub):
+                assert_state_parity(shard.fetch(k), host[k], f"three paths step {s} sg {k}")
+        assert shard.guards_intact()
+        # Section 3.3: the next split follows what the paths showed.  Observed (made up here, the files are small):
+        # the disk at a quarter of its guess -> Eq. 1 takes a subgroup away from it; the move happens inside an
+        # ordinary step, by a flush target (disk file -> pinned memory)
+        seen = B.mlpo_update_bandwidth([4.0, 3.0, 2.0], [4.0 * per, 3.0 * per, 2.0 * per], [per, per, 4.0 * per])
+        assert seen == [4.0, 3.0, 0.5]
+        new_counts, _ = B.mlpo_assign_tiers(n_sub, seen)
+        assert new_counts == oracle_tiers(n_sub, seen) and new_counts[2] < 2
+        mover = on_disk[-1]
+        home = torch.zeros(per // 4, dtype=torch.float32).pin_memory()
+        targets = [None] * n_sub
+        targets[mover] = home
+        move = B.direct_cfg(streams[0], streams[1], 24, chunk_elems=chunk, files=shard.files, bounce=bounce,
+                            bounce_bytes=bounce.numel(), file_slots=file_slots, file_threads=threads,
+                            want_file_stats=True, flush_to=targets)
+        for k, sg in enumerate(host):
+            W.fill_grads(wl, k, wl.steps, sg["g"])
+            shard.set_grads(k, sg["g"])
+        torch.cuda.synchronize()
+        ok_o, _, _, gmul_o = oracle.step(host, ohp, wl.steps, wl.inv_scale, wl.max_norm)
+        B.mlpo_grad_unscale_norm(shard.table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars,
+                                 streams[1])
+        assert B.mlpo_stream_update(shard.table, None, ghp, wl.steps + 1, scratch.scalars, move) and ok_o
+        streams[1].synchronize()
+        by_id = {p.path_id: p.stats for p in move.paths if p.used}
+        assert by_id[ids[1]].bytes_read == 2 * per and by_id[ids[1]].bytes_written == per   # one left the disk
+        p_, m_, v_ = unpack_tiled(home.numpy(), wl.sub_elems, T)
+        got = {"p": p_, "m": m_, "v": v_, "p16": shard.keep[mover]["p16"].cpu().numpy().view(np.uint16).copy()}
+        assert_state_parity(got, host[mover], "the subgroup that moved from the disk to pinned memory")
+    finally:
+        torch.cuda.synchronize()
+        shard.close()
+        for pth in shard.paths:
+            if os.path.exists(pth):
+                os.unlink(pth)
+
+
+def oracle_tiers(n_sub, bandwidth):
+    from oracle import tier_alloc
+    return tier_alloc.assign_tiers(n_sub, bandwidth)[0]
+
+
+def test_too_few_bounce_buffers_for_the_paths(tmp_path):
+    if not os.path.isdir("/dev/shm") or os.stat("/dev/shm").st_dev == os.stat(str(tmp_path)).st_dev:
+        pytest.skip("no second file system")
+    wl = W.Workload("twopaths", n_sub=2, sub_elems=5000, n_host=0)
+    host = W.host_subgroups(wl)
+    shm = f"/dev/shm/mlpo_two_{os.getpid()}.bin"
+    shard = Shard(host, [F, F], 1024, shm, direct_io=False, path2=str(tmp_path / "b.bin"), second=[1])
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    try:
+        cfg = make_cfg(shard, streams, 0, 1)        # one bounce buffer, two paths
+        with pytest.raises(B.MlpoError) as e:
+            B.mlpo_stream_update(shard.table, None, B.HParams(), 1, None, cfg)
+        assert e.value.code == B.MLPO_EINVAL and "paths" in str(e.value)
+    finally:
+        shard.close()
+        os.unlink(shm)
 
 
 def test_skipped_step_touches_no_file(oracle, tmp_path):
