@@ -91,7 +91,10 @@ def resident_setup(args, torch, B, W, np, wl, tile):
 
 def resident_timed_steps(args, torch, B, wl, buf, scal, ws):
     """args.warmup untimed and args.steps timed whole steps (gradient pass + update) on one stream, with the
-    workload's injection schedule; returns (elapsed ms of the timed steps, applied timed steps)."""
+    workload's injection schedule - the figure `value` comes from, nothing but the library's launches inside the
+    clock - and then the same args.steps steps once more with every launch of the two streaming kernels carrying its
+    own begin / end timestamps (HIP events attached to the dispatch on this stream), which is where the per-kernel
+    durations of `roofline` come from.  Returns (elapsed ms of the timed steps, applied timed steps)."""
     d = torch.device("cuda:0")
     table, g_flat = buf["table"], buf["g_flat"]
     inf_bits = torch.tensor([0x7F80], dtype=torch.int16, device=d)
@@ -104,16 +107,19 @@ def resident_timed_steps(args, torch, B, wl, buf, scal, ws):
     applied = 0
     applied_timed = 0
     with torch.cuda.stream(stream):
-        for s in range(total):
-            timed = s >= args.warmup
+        for s in range(total + args.steps):
+            timed = args.warmup <= s < total
             if s == args.warmup:
                 stream.synchronize()
                 torch.cuda.synchronize()
-                # from here on every launch of the two streaming kernels carries its own begin / end timestamps
-                # (HIP events attached to the dispatch on this stream)
-                B.mlpo_kernel_timing(True)
                 t_begin.record(stream)
-            inject = wl.injects(s)
+            if s == total:
+                t_end.record(stream)
+                stream.synchronize()
+                torch.cuda.synchronize()
+                B.mlpo_kernel_timing(True)
+            # the instrumented pass repeats the schedule of the timed one
+            inject = wl.injects(s if s < total else s - args.steps)
             if inject:
                 idx = wl.inject_index(s)
                 saved.copy_(g_flat[idx:idx + 1])
@@ -125,7 +131,6 @@ def resident_timed_steps(args, torch, B, wl, buf, scal, ws):
             else:
                 applied += 1            # the host mirrors the injection schedule: no read-back of the flag
                 applied_timed += int(timed)
-        t_end.record(stream)
     stream.synchronize()
     torch.cuda.synchronize()
     return t_begin.elapsed_time(t_end), applied_timed
@@ -203,8 +208,9 @@ def resident_result(args, wl, primary, others):
                    "applied_steps": primary["applied_steps"], "state_layout": primary["layout"],
                    "state_lead_elems": primary["lead"],
                    "state": f"fp32 p/m/v + {args.half} grads + {args.half} params, all in HBM",
-                   "timed_region": "every launch of the two streaming kernels carries an event pair for its own "
-                                   "duration, inside the clock (slightly pessimistic for value)"},
+                   "timed_region": "warmup + steps with nothing but the library's launches inside the clock (value, "
+                                   "ms_per_step); the same steps are then run once more with an event pair on every "
+                                   "launch of the two streaming kernels (roofline, norm_pass)"},
         "roofline": primary["roofline"],
         "norm_pass": primary["norm_pass"],
         "step_hbm_frac": primary["step_hbm_frac"],
@@ -492,9 +498,11 @@ class StreamedBench:
         that keep their subgroups, arg = slots)."""
         torch, B = self.torch, self.B
         table = self.table_with_host_gradients() if kind in ("dg", "dga", "sg") else self.table
-        if kind in ("d", "dg", "dga"):
+        if kind in ("dgk", "sgk"):
+            self.table_with_host_gradients()        # the pass reads these; the update reads their device copies
+        if kind in ("d", "dg", "dga", "dgk"):
             return table, B.direct_cfg(self.h2d, self.cmp, arg), None, None
-        n_slots, chunk = {"sg": (3, arg), "c": (arg, 0)}.get(kind, (kind, arg))
+        n_slots, chunk = {"sg": (3, arg), "sgk": (3, arg), "c": (arg, 0)}.get(kind, (kind, arg))
         cache = B.SlotCacheC() if kind == "c" else None
         # with a slot cache the slots hold whole subgroups; chunk_elems then only sizes the pieces of a miss
         need = B.mlpo_stream_staging_bytes(table, n_slots, WHOLE if cache is not None else chunk)
@@ -522,6 +530,12 @@ class StreamedBench:
         t = time.perf_counter()
         if kind == "dga":
             B.mlpo_grad_norm_finish(self.ws, self.ws_bytes, wl.inv_scale, wl.max_norm, self.scal, self.cmp)
+        elif kind in ("dgk", "sgk"):
+            # gradients in pinned host memory: the pass reads them over the link and leaves copies at their device
+            # homes, which is where `table` (host-tier state, device gradients) has the update read them
+            keep = [self.grads(k) if wl.tier(k) else None for k in range(wl.n_sub)]
+            B.mlpo_grad_unscale_norm_keep(self.host_g_table, keep, wl.inv_scale, wl.max_norm, self.ws, self.ws_bytes,
+                                          self.scal, self.cmp)
         else:
             B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, self.ws, self.ws_bytes, self.scal, self.cmp)
         ok = B.mlpo_stream_update(table, order, self.hp, self.applied + 1, self.scal, cfg)
@@ -537,7 +551,7 @@ class StreamedBench:
         averaged over the transfer units; in direct mode reading and writing both last as long as the kernel that
         does them."""
         M, wl = self.M, self.wl
-        if kind in ("d", "dg", "dga"):
+        if kind in ("d", "dg", "dga", "dgk"):
             eff = [2 * 12 * self.n_host_params / (2 * k * 1e-3) / 1e9 for k in kern_ms if k > 1.0]
         elif kind == "c":
             eff = []                # transfers are not paired one to one when flushes are lazy
@@ -557,6 +571,10 @@ class StreamedBench:
                             "(14 B/param in, 12 out)", "direct_blocks": arg},
             "sg": {"mode": "staged, gradients on the host too (16 B/param in, 12 out)", "n_slots": 3,
                    "chunk_elems": arg},
+            "dgk": {"mode": "direct, gradients on the host too, the gradient pass keeps a device copy for the update "
+                            "(14 B/param in, 12 out)", "direct_blocks": arg},
+            "sgk": {"mode": "staged, gradients on the host too, the gradient pass keeps a device copy for the update "
+                            "(14 B/param in, 12 out)", "n_slots": 3, "chunk_elems": arg},
             "c": {"mode": "staged+slot-cache, alternating order, misses in pieces of 2^24", "n_slots": arg},
         }.get(kind, {"mode": "staged", "n_slots": kind,
                      "chunk_elems": "whole subgroups" if arg == WHOLE else (arg or "library's choice (2^24)")})
@@ -598,7 +616,7 @@ class StreamedBench:
                         "effective_io_GBs_paper_formula": self.effective_io(kind, arg, len(times), fetch_ms, flush_ms,
                                                                             kern_ms)})
             # host-side gradients cross the link with the state, and once more for a gradient pass
-            inbound = {"dg": 16, "sg": 16, "dga": 14}.get(kind)
+            inbound = {"dg": 16, "sg": 16, "dga": 14, "dgk": 14, "sgk": 14}.get(kind)
             if inbound:
                 rec.update({"pcie_in_GBs": round(inbound * self.n_host_params / mean / 1e9, 2),
                             "pcie_out_GBs": round(12 * self.n_host_params / mean / 1e9, 2)})
@@ -672,6 +690,13 @@ def streamed_bench(args, torch, B, W, np, link_fresh=None):
             except (OSError, MemoryError, RuntimeError) as e:   # no room for the file, no /dev/shm, an I/O error
                 out["multipath"].append({"kind": kind, "error": f"{type(e).__name__}: {e}"})
                 log(f"[bench] multipath {kind} failed: {e}")
+        if args.three_paths:
+            two = {r["kind"]: r.get("file_path_GBs_per_dir") for r in out["multipath"] if "kind" in r}
+            try:
+                out["three_paths"] = three_path_bench(args, torch, B, np, ctx, two)
+            except (OSError, MemoryError, RuntimeError, AssertionError) as e:
+                out["three_paths"] = {"error": f"{type(e).__name__}: {e}"}
+                log(f"[bench] three paths failed: {e}")
     g_flat, p16_flat = sb.g_flat, sb.p16_flat
     sb.release()
     out["grad_accumulate"] = accumulate_bench(torch, B, g_flat, p16_flat, wl)
@@ -1029,6 +1054,103 @@ def large_config_leg(args, torch, B, W, np, name, modes, bidir_GBs):
     return rec
 
 
+def three_path_bench(args, torch, B, np, ctx, two_path):
+    """Three live paths behind the offloaded tier (Section 3.2 "Unified Multi-level, Multi-path Asynchronous
+    Offloading using Virtual Tiers"): pinned host memory (limited to ``--pinned-capacity-3`` subgroups), a file in
+    /dev/shm and a file on the disk, each file path with its own workers and bounce buffers.  Eq. 1 (Section 3.3)
+    splits the subgroups from guessed bandwidths; the step is compared with what the slowest path needs on its own
+    (bytes over the bandwidth that path showed in the two-path runs)."""
+    import tempfile
+    wl, keep, T, M = ctx["wl"], ctx["keep"], ctx["T"], ctx["M"]
+    g_flat, p16_flat, cmp_ = ctx["g_flat"], ctx["p16_flat"], ctx["streams"][1]
+    offloaded = [k for k in range(wl.n_sub) if wl.tier(k) == 1]
+    state_bytes = B.mlpo_state_floats(M, T) * 4
+    guess = [ctx["host_GBs"]] + [float(x) for x in args.three_path_guess.split(",")]      # pinned, shm, disk
+    bw = [g * 1e9 / state_bytes for g in guess]
+    cap = [min(args.pinned_capacity_3, len(offloaded)), len(offloaded), len(offloaded)]
+    counts, tier_of = B.mlpo_assign_tiers(len(offloaded), bw, cap)
+    # the slowest path takes the lowest ids (Section 3.2 "Cache-Friendly Ordering")
+    where = {k: tier_of[j] for j, k in enumerate(offloaded)}
+    paths = [f"/dev/shm/mlpo_bench3_{os.getpid()}.bin",
+             os.path.join(args.file_dir or tempfile.gettempdir(), f"mlpo_bench3_{os.getpid()}.bin")]
+    res = {"paths": ["pinned host memory", paths[0], paths[1]], "eq1_bandwidth_guess_GBs": [round(g, 2) for g in guess],
+           "pinned_capacity": cap[0], "eq1_split_pinned_shm_disk": list(counts), "chunk_elems": args.multipath_chunk,
+           "file_slots": 6, "file_threads_per_path": args.file_threads}
+    fds = []
+    try:
+        slot_of, sgs, files = {}, [], []
+        for which, path in enumerate(paths):
+            mine = [k for k in offloaded if where[k] == which + 1]
+            with open(path, "wb") as f:
+                for j, k in enumerate(mine):
+                    slot_of[k] = j
+                    f.write(keep[k].numpy().tobytes())
+                f.flush()
+                os.fsync(f.fileno())
+            try:
+                fds.append(os.open(path, os.O_RDWR | (os.O_DIRECT if which == 1 else 0)))
+            except OSError:
+                fds.append(os.open(path, os.O_RDWR))
+        for k in range(wl.n_sub):
+            gk, pk = g_flat[k * M:(k + 1) * M], p16_flat[k * M:(k + 1) * M]
+            if where.get(k, 0) > 0:
+                sgs.append(B.SubgroupC(None, None, None, gk.data_ptr(), pk.data_ptr(), M, B.TIER_FILE, T))
+                files.append((fds[where[k] - 1], slot_of[k] * state_bytes))
+            else:
+                sgs.append(B.tiled_subgroup(keep[k], gk, pk, n=M, tier=wl.tier(k), tile_elems=T))
+                files.append(None)
+        table = B.SubgroupTable(sgs)
+        need = B.mlpo_stream_bounce_bytes(table, 6, args.multipath_chunk)
+        bounce = torch.empty(need, dtype=torch.uint8, pin_memory=True)
+        cfg = B.direct_cfg(ctx["streams"][0], cmp_, 64, chunk_elems=args.multipath_chunk, files=files, bounce=bounce,
+                           bounce_bytes=need, file_slots=6, file_threads=args.file_threads, want_file_stats=True)
+        ids = [os.fstat(fd).st_dev for fd in fds]
+        applied, times, per_path = ctx["applied"], [], {i: [] for i in ids}
+        t_leg = time.perf_counter()
+        for s in range(1 + wl.steps):
+            if times and time.perf_counter() - t_leg > args.multipath_seconds:
+                break
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            B.mlpo_grad_unscale_norm(table, wl.inv_scale, wl.max_norm, ctx["ws"], ctx["ws_bytes"], ctx["scal"], cmp_)
+            assert B.mlpo_stream_update(table, None, ctx["hp"], applied + 1, ctx["scal"], cfg)
+            cmp_.synchronize()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t
+            applied += 1
+            if s >= 1:
+                times.append(dt)
+                for p in cfg.paths:
+                    if p.used and p.stats.wall_seconds > 0:
+                        per_path[p.path_id].append(p.stats.bytes_read / p.stats.wall_seconds / 1e9)
+        ctx["applied"] = applied
+        mean = sum(times) / len(times)
+        seen = [ctx["host_GBs"]] + [sum(per_path[i]) / len(per_path[i]) if per_path[i] else g
+                                    for i, g in zip(ids, guess[1:])]
+        # what each path needs alone for its share, at the bandwidth it showed when it was the only file path
+        alone = [ctx["host_GBs"], two_path.get("shm") or seen[1], two_path.get("disk") or seen[2]]
+        need_ms = [c * state_bytes / (b * 1e9) * 1e3 for c, b in zip(counts, alone)]
+        res.update({"steps": len(times), "ms_per_step": round(mean * 1e3, 2), "min_ms": round(min(times) * 1e3, 2),
+                    "Gparams_s": round(wl.n_total / mean / 1e9, 3),
+                    "link_GBs_per_dir": round(len(offloaded) * state_bytes / mean / 1e9, 2),
+                    "path_GBs_per_dir_observed": [round(x, 2) for x in seen],
+                    "path_GBs_per_dir_alone": [round(x, 2) for x in alone],
+                    "each_path_alone_would_take_ms": [round(x, 1) for x in need_ms],
+                    "step_over_slowest_path_alone": round(mean * 1e3 / max(need_ms), 3)})
+        new_bw = B.mlpo_update_bandwidth(bw, [float(c) for c in counts],
+                                         [c / (g * 1e9 / state_bytes) if c else 0.0 for c, g in zip(counts, seen)])
+        res["eq1_split_after_update"] = list(B.mlpo_assign_tiers(len(offloaded), new_bw, cap)[0])
+    finally:
+        torch.cuda.synchronize()
+        for fd in fds:
+            os.close(fd)
+        for path in paths:
+            if os.path.exists(path):
+                os.unlink(path)
+    log(f"[bench] three paths {res}")
+    return res
+
+
 def accumulate_bench(torch, B, acc_dev, g_dev, wl):
     """mlpo_grad_accumulate at the shard's size: the accumulation buffer in HBM (6 bytes of HBM traffic per element)
     and in pinned host memory (2 bytes per element over the link in each direction), 4 micro-batches each."""
@@ -1081,7 +1203,7 @@ def parse_variants(text):
     res = []
     for part in text.split(","):
         a, _, b = part.partition(":")
-        res.append((a if a in ("d", "c", "dg", "sg", "dga") else int(a), WHOLE if b == "w" else int(b or 0)))
+        res.append((a if a in ("d", "c", "dg", "sg", "dga", "dgk", "sgk") else int(a), WHOLE if b == "w" else int(b or 0)))
     return res
 
 
@@ -1101,10 +1223,11 @@ def main():
                     help="format of gradients and working parameters in the resident run (the workloads are bf16; "
                          "fp16 reads the same generated bit patterns as fp16 values, for timing)")
     ap.add_argument("--streamed", default="C3", help="host-tier workload for the pipeline figures, or 'none'")
-    ap.add_argument("--stream-variants", default="2:0,3:w,3:0,4:0,d:64,d:128,dg:64,dga:64,sg:0,c:4,c:8",
+    ap.add_argument("--stream-variants", default="2:0,3:w,3:0,4:0,d:64,d:128,dg:64,dga:64,dgk:64,sg:0,sgk:0,c:4,c:8",
                     help="comma list of n_slots:chunk_elems (staged mode; chunk 0 = the library's choice, w = whole subgroups), d:blocks (direct mode), dg:blocks (direct "
                          "mode, gradients in pinned host memory too), dga:blocks (the same with the gradient statistics "
-                         "left by the last accumulation instead of a gradient pass), sg:chunk_elems (staged mode with 3 slots, "
+                         "left by the last accumulation instead of a gradient pass), dgk:blocks / sgk:chunk_elems (gradients in pinned host memory, "
+                         "the gradient pass keeps a device copy that the update reads), sg:chunk_elems (staged mode with 3 slots, "
                          "gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep their "
                          "subgroups and alternating order)")
     ap.add_argument("--stream-warmup", type=int, default=2)
@@ -1115,6 +1238,12 @@ def main():
                          "--file-dir, O_DIRECT), shm (a file in /dev/shm), or 'none'")
     ap.add_argument("--pinned-capacity", type=int, default=10,
                     help="subgroups the pinned-host path may hold in the two-path run (the rest go to the file)")
+    ap.add_argument("--no-three-paths", dest="three_paths", action="store_false",
+                    help="skip the run with three live paths (pinned memory, a file in /dev/shm, a file on the disk)")
+    ap.add_argument("--pinned-capacity-3", type=int, default=8,
+                    help="subgroups the pinned-host path may hold in the three-path run")
+    ap.add_argument("--three-path-guess", default="20,6",
+                    help="initial bandwidth estimates (GB/s) of the /dev/shm path and of the disk path in the three-path run")
     ap.add_argument("--hbm-capacity", type=int, default=4,
                     help="streamed workload: subgroups that HBM has room for in the re-balancing run (0 = skip it)")
     ap.add_argument("--file-GBs-guess", type=float, default=3.0, help="initial bandwidth estimate of the file path")

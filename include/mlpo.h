@@ -173,6 +173,22 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
                            size_t workspace_bytes, mlpo_step_scalars* out, void* stream);
 
 /*
+ * The same gradient pass, which also leaves a device copy of the gradients it reads: for subgroups whose
+ * half-precision gradients live in pinned host memory (the paper's placement, Section 3.2 "Delayed In-place
+ * Mixed-Precision Gradient Conversion").  The pass has to read them over the link anyway; with the copy in HBM
+ * (2 bytes per element of spare device memory) the update that follows reads them there - describe the subgroup to
+ * mlpo_stream_update as MLPO_TIER_HOST with g = the copy - and 14 instead of 16 bytes per element cross the link
+ * inbound, whichever way the gradients were accumulated.
+ *   keep   host array of n_sg device pointers; keep[i] receives the n elements of sg[i].g, NULL keeps no copy of that
+ *          subgroup.  keep[i] and sg[i].g must agree modulo 16 bytes and must not overlap.
+ * Everything else as for mlpo_grad_unscale_norm; the record is the same bit for bit.
+ * Errors: MLPO_EINVAL, MLPO_ENOMEM, MLPO_EHIP.
+ */
+int mlpo_grad_unscale_norm_keep(const mlpo_subgroup* sg, int32_t n_sg, uint16_t* const* keep, float inv_scale,
+                                float max_norm, void* workspace, size_t workspace_bytes, mlpo_step_scalars* out,
+                                void* stream);
+
+/*
  * The same gradient pass for callers that cannot allocate and have no workspace to pass: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  The per-workgroup partial sums go to an array in
  * the library's own device image (196 864 bytes, one copy per GPU, held until the process ends) instead of a

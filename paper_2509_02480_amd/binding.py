@@ -24,7 +24,7 @@ TILE_DEFAULT = 8192
 
 EXPORTS = ("mlpo_last_error", "mlpo_version", "mlpo_line_lead", "mlpo_state_floats", "mlpo_state_pack",
            "mlpo_state_unpack",
-           "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm", "mlpo_grad_unscale_norm_static", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm",
+           "mlpo_norm_workspace_bytes", "mlpo_grad_unscale_norm", "mlpo_grad_unscale_norm_keep", "mlpo_grad_unscale_norm_static", "mlpo_grad_accumulate", "mlpo_grad_accumulate_norm",
            "mlpo_grad_norm_finish", "mlpo_adamw_step", "mlpo_stream_staging_bytes", "mlpo_stream_bounce_bytes",
            "mlpo_stream_update", "mlpo_stream_flush", "mlpo_assign_tiers", "mlpo_update_bandwidth",
            "mlpo_kernel_timing", "mlpo_kernel_times", "mlpo_shutdown")
@@ -140,6 +140,9 @@ def lib():
         L.mlpo_grad_unscale_norm.restype = C.c_int
         L.mlpo_grad_unscale_norm.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_size_t,
                                              C.c_void_p, C.c_void_p]
+        L.mlpo_grad_unscale_norm_keep.restype = C.c_int
+        L.mlpo_grad_unscale_norm_keep.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_float, C.c_void_p,
+                                                  C.c_size_t, C.c_void_p, C.c_void_p]
         L.mlpo_grad_unscale_norm_static.restype = C.c_int
         L.mlpo_grad_unscale_norm_static.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         L.mlpo_grad_accumulate.restype = C.c_int
@@ -263,6 +266,18 @@ def mlpo_grad_unscale_norm(sgs, inv_scale: float, max_norm: float, workspace, wo
     t = _table(sgs)
     _check(lib().mlpo_grad_unscale_norm(t.array, t.n, inv_scale, max_norm, _ptr(workspace), workspace_bytes,
                                         _ptr(out), _stream(stream)))
+
+
+def mlpo_grad_unscale_norm_keep(sgs, keep, inv_scale: float, max_norm: float, workspace, workspace_bytes: int, out,
+                                stream=None) -> None:
+    """The gradient pass that also leaves device copies of the gradients it reads: ``keep`` has one device tensor /
+    address (or None) per subgroup; see mlpo.h."""
+    t = _table(sgs)
+    if len(keep) != t.n:
+        raise ValueError("keep must have one entry per subgroup")
+    arr = (C.c_void_p * max(t.n, 1))(*[_ptr(k) for k in keep])
+    _check(lib().mlpo_grad_unscale_norm_keep(t.array, t.n, arr, inv_scale, max_norm, _ptr(workspace),
+                                             workspace_bytes, _ptr(out), _stream(stream)))
 
 
 def mlpo_grad_unscale_norm_static(sgs, inv_scale: float, max_norm: float, out, stream=None) -> None:

@@ -285,6 +285,28 @@ int mlpo_grad_unscale_norm(const mlpo_subgroup* sg, int32_t n_sg, float inv_scal
     return launch_grad_norm(sg, n_sg, inv_scale, max_norm, workspace, out, static_cast<hipStream_t>(stream));
 }
 
+int mlpo_grad_unscale_norm_keep(const mlpo_subgroup* sg, int32_t n_sg, uint16_t* const* keep, float inv_scale,
+                                float max_norm, void* workspace, size_t workspace_bytes, mlpo_step_scalars* out,
+                                void* stream) {
+    int rc = validate_subgroups(sg, n_sg, /*grads_only=*/true, 1);
+    if (rc != MLPO_OK) return rc;
+    if (n_sg > 0 && keep == nullptr) return fail(MLPO_EINVAL, "keep is NULL");
+    for (int32_t i = 0; i < n_sg; ++i) {
+        if (keep[i] == nullptr || sg[i].n == 0) continue;
+        const uintptr_t a = reinterpret_cast<uintptr_t>(keep[i]), g = reinterpret_cast<uintptr_t>(sg[i].g);
+        if (((a ^ g) & 15u) != 0)
+            return fail(MLPO_EINVAL, "subgroup %d: the copy and the gradients must agree modulo 16 bytes", i);
+        if (a < g + 2 * sg[i].n && g < a + 2 * sg[i].n)
+            return fail(MLPO_EINVAL, "subgroup %d: the copy overlaps the gradients", i);
+    }
+    if (!(isfinite(inv_scale) && inv_scale > 0.0f)) return fail(MLPO_EINVAL, "inv_scale must be finite and > 0");
+    if (isnan(max_norm)) return fail(MLPO_EINVAL, "max_norm is NaN");
+    rc = check_norm_workspace(workspace, workspace_bytes);
+    if (rc != MLPO_OK) return rc;
+    if (out == nullptr || misaligned(out, 16)) return fail(MLPO_EINVAL, "out is NULL or not 16-byte aligned");
+    return launch_grad_norm(sg, n_sg, inv_scale, max_norm, workspace, out, static_cast<hipStream_t>(stream), true, keep);
+}
+
 int mlpo_grad_unscale_norm_static(const mlpo_subgroup* sg, int32_t n_sg, float inv_scale, float max_norm,
                                   mlpo_step_scalars* out, void* stream) {
     if (n_sg > MLPO_STATIC_MAX_SUBGROUPS)

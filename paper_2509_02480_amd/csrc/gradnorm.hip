@@ -40,6 +40,7 @@ struct NormBatch {
     uint64_t n_body[kMaxSg];       // elements from body to the end of the subgroup
     uint32_t block_begin[kMaxSg + 1];  // prefix sums of workgroups per subgroup
     uint8_t head[kMaxSg];  // elements before body (0..63), handled by the subgroup's first workgroup
+    int64_t keep[kMaxSg];  // KEEP kernels: elements from a gradient to its device copy (0 = this array keeps none)
     int32_t n_sg;
     int32_t half;  // MLPO_HALF_BF16 or MLPO_HALF_FP16
     uint32_t pieces_per_block;
@@ -79,22 +80,31 @@ __device__ __forceinline__ void accum_vec(u32x4 w, float inv_scale, double& a0, 
 
 // This lane's 128-bit word of 4 KiB piece `piece` of a subgroup's body (zero where the lane has none: zero bits are
 // the value 0 in both formats and add nothing); the ragged end of the last piece is added to acc on the spot.
-template <int HALF>
+// keep != 0: what is read is also stored keep elements further on (the device copy of gradients that live in host
+// memory: the update then need not read them over the link a second time).
+template <int HALF, bool KEEP>
 __device__ __forceinline__ u32x4 fetch(const uint16_t* __restrict__ body, uint64_t n_body, uint64_t piece,
-                                       float inv_scale, double& acc) {
+                                       int64_t keep, float inv_scale, double& acc) {
     const uint32_t tid = threadIdx.x;
     const uint64_t e0 = piece * kPiece;
     const u32x4* __restrict__ q = reinterpret_cast<const u32x4*>(body + e0) + tid;
-    if (e0 + kPiece <= n_body) return __builtin_nontemporal_load(q);
-    const u32x4 zero = {0u, 0u, 0u, 0u};
     const uint64_t e = e0 + (uint64_t)tid * 8;
-    if (e + 8 <= n_body) return __builtin_nontemporal_load(q);
-    for (uint64_t j = e; j < n_body; ++j) accum_half<HALF>(body[j], inv_scale, acc);
+    if (e + 8 <= n_body) {
+        const u32x4 w = __builtin_nontemporal_load(q);
+        if (KEEP && keep != 0) *reinterpret_cast<u32x4*>(const_cast<uint16_t*>(body) + e + keep) = w;
+        return w;
+    }
+    for (uint64_t j = e; j < n_body; ++j) {
+        const uint16_t h = body[j];
+        if (KEEP && keep != 0) const_cast<uint16_t*>(body)[(int64_t)j + keep] = h;
+        accum_half<HALF>(h, inv_scale, acc);
+    }
+    const u32x4 zero = {0u, 0u, 0u, 0u};
     return zero;
 }
 
 // The streaming part of the kernel below for one format.
-template <int HALF>
+template <int HALF, bool KEEP>
 __device__ __forceinline__ void stats_run(const NormBatch& b, const float inv_scale, double& a0, double& a1) {
     const uint32_t tid = threadIdx.x;
     const uint32_t blk = blockIdx.x;
@@ -107,7 +117,12 @@ __device__ __forceinline__ void stats_run(const NormBatch& b, const float inv_sc
     const uint32_t blocks_s = b.block_begin[lo + 1] - b.block_begin[lo];
     const uint16_t* __restrict__ body = b.body[lo];
     const uint64_t n_body = b.n_body[lo];
-    if (b_in == 0 && tid < b.head[lo]) accum_half<HALF>(*(body - 1 - tid), inv_scale, a0);
+    const int64_t keep = KEEP ? b.keep[lo] : 0;
+    if (b_in == 0 && tid < b.head[lo]) {
+        const uint16_t h = *(body - 1 - tid);
+        if (KEEP && keep != 0) const_cast<uint16_t*>(body)[-1 - (int64_t)tid + keep] = h;
+        accum_half<HALF>(h, inv_scale, a0);
+    }
     const uint64_t n_pieces = (n_body + kPiece - 1) / kPiece;
     const uint32_t per_block = b.pieces_per_block;  // a multiple of kUnroll
     const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -117,22 +132,23 @@ __device__ __forceinline__ void stats_run(const NormBatch& b, const float inv_sc
         for (int u = 0; u < kUnroll; ++u) {
             const uint64_t k = k0 + u;
             const uint64_t piece = kSweep ? b_in + k * blocks_s : (uint64_t)b_in * per_block + k;
-            w[u] = piece < n_pieces ? fetch<HALF>(body, n_body, piece, inv_scale, a0) : zero;
+            w[u] = piece < n_pieces ? fetch<HALF, KEEP>(body, n_body, piece, keep, inv_scale, a0) : zero;
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) accum_vec<HALF>(w[u], inv_scale, a0, a1);
     }
 }
 
+// KEEP = true: the form that also leaves a device copy of the gradients it reads (see fetch).
+template <bool KEEP>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
-grad_stats_kernel(const NormBatch b, const float inv_scale,
-                                                            Workspace* __restrict__ ws) {
+grad_stats_kernel(const NormBatch b, const float inv_scale, Workspace* __restrict__ ws) {
     const uint32_t tid = threadIdx.x;
     double a0 = 0.0, a1 = 0.0;
     if (b.half == 0)
-        stats_run<0>(b, inv_scale, a0, a1);
+        stats_run<0, KEEP>(b, inv_scale, a0, a1);
     else
-        stats_run<1>(b, inv_scale, a0, a1);
+        stats_run<1, KEEP>(b, inv_scale, a0, a1);
     double acc = a0 + a1;
     // a sum of squares is non-finite exactly when one of its terms is (see the note at the top)
     uint32_t bad = (uint32_t)!(fabs(acc) <= 1.7976931348623157e308);
@@ -230,7 +246,7 @@ __global__ void __launch_bounds__(kFinishBlock) grad_finish_kernel(Workspace* __
 // Cuts the batch into workgroups and launches it, then the fold.  pieces[i] = 4 KiB pieces of entry i (at least one,
 // so that an array that is all head still has a workgroup).
 int flush(NormBatch& b, const uint64_t* pieces, bool first, bool last, float inv_scale, float max_norm, Workspace* ws,
-          mlpo_step_scalars* out, hipStream_t st, bool may_time) {
+          mlpo_step_scalars* out, hipStream_t st, bool may_time, bool keeps) {
     uint32_t grid = 0;
     if (b.n_sg > 0) {
         uint64_t total = 0;
@@ -243,10 +259,11 @@ int flush(NormBatch& b, const uint64_t* pieces, bool first, bool last, float inv
             b.block_begin[i + 1] = b.block_begin[i] + (uint32_t)((pieces[i] + per_block - 1) / per_block);
         grid = b.block_begin[b.n_sg];  // <= kTargetBlocks + n_sg <= kMaxGrid
         hipEvent_t t0, t1;
+        const auto kernel = keeps ? grad_stats_kernel<true> : grad_stats_kernel<false>;
         if (may_time && timing_enabled() && timing_acquire(kTimedGradPass, &t0, &t1))
-            hipExtLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, b, inv_scale, ws);
+            hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, st, t0, t1, 0, b, inv_scale, ws);
         else
-            hipLaunchKernelGGL(grad_stats_kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws);
+            hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, st, b, inv_scale, ws);
         MLPO_HIP(hipGetLastError());
     }
     return launch_norm_fold(ws, (int)grid, first, last, inv_scale, max_norm, out, st);
@@ -265,7 +282,7 @@ int launch_norm_fold(NormWorkspace* ws, int n_partials, bool first, bool last, f
 size_t grad_norm_workspace_bytes() { return sizeof(Workspace); }
 
 int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float max_norm, void* workspace,
-                     mlpo_step_scalars* out, hipStream_t stream, bool may_time) {
+                     mlpo_step_scalars* out, hipStream_t stream, bool may_time, uint16_t* const* keep) {
     Workspace* ws = static_cast<Workspace*>(workspace);
     NormBatch b;
     uint64_t pieces[kMaxSg];
@@ -273,10 +290,11 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
     b.half = table_half_format(sg, n_sg);
     bool first = true;
     int rc = MLPO_OK;
-    // Adds the array [g, g + n) to the batch as one entry.
-    const auto push = [&](const uint16_t* g, uint64_t n) -> int {
+    const bool keeps = keep != nullptr;
+    // Adds the array [g, g + n) to the batch as one entry; delta: elements from g to its device copy, 0 = none.
+    const auto push = [&](const uint16_t* g, uint64_t n, int64_t delta) -> int {
         if (b.n_sg == kMaxSg) {  // more arrays than one argument block holds: the running totals carry over
-            const int r = flush(b, pieces, first, false, inv_scale, max_norm, ws, out, stream, may_time);
+            const int r = flush(b, pieces, first, false, inv_scale, max_norm, ws, out, stream, may_time, keeps);
             if (r != MLPO_OK) return r;
             first = false;
             b.n_sg = 0;
@@ -288,27 +306,31 @@ int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float m
         b.body[b.n_sg] = g + head;
         b.n_body[b.n_sg] = n_body;
         b.head[b.n_sg] = (uint8_t)head;
+        b.keep[b.n_sg] = delta;
         pieces[b.n_sg] = n_body == 0 ? 1 : (n_body + kPiece - 1) / kPiece;
         ++b.n_sg;
         return MLPO_OK;
     };
     // Subgroups are usually consecutive slices of one flat gradient buffer (Section 2 "Sharded Model and Optimizer
-    // States Into Subgroups" cuts a flat shard into equal parts): slices that follow one another in memory are
-    // summed as one array, which has one unaligned head instead of one per subgroup.
+    // States Into Subgroups" cuts a flat shard into equal parts): slices that follow one another in memory (and whose
+    // copies, if any, do too) are summed as one array, which has one unaligned head instead of one per subgroup.
     const uint16_t* run = nullptr;
     uint64_t run_n = 0;
+    int64_t run_delta = 0;
     for (int i = 0; i < n_sg; ++i) {
         if (sg[i].n == 0) continue;
-        if (run != nullptr && sg[i].g == run + run_n && run_n + sg[i].n <= ((uint64_t)1 << 48)) {
+        const int64_t delta = (keeps && keep[i] != nullptr) ? keep[i] - sg[i].g : 0;
+        if (run != nullptr && sg[i].g == run + run_n && delta == run_delta && run_n + sg[i].n <= ((uint64_t)1 << 48)) {
             run_n += sg[i].n;
             continue;
         }
-        if (run != nullptr && (rc = push(run, run_n)) != MLPO_OK) return rc;
+        if (run != nullptr && (rc = push(run, run_n, run_delta)) != MLPO_OK) return rc;
         run = sg[i].g;
         run_n = sg[i].n;
+        run_delta = delta;
     }
-    if (run != nullptr && (rc = push(run, run_n)) != MLPO_OK) return rc;
-    return flush(b, pieces, first, true, inv_scale, max_norm, ws, out, stream, may_time);
+    if (run != nullptr && (rc = push(run, run_n, run_delta)) != MLPO_OK) return rc;
+    return flush(b, pieces, first, true, inv_scale, max_norm, ws, out, stream, may_time, keeps);
 }
 
 // ---- the entry point that allocates nothing ------------------------------------------------------------------

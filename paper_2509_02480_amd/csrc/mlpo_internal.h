@@ -89,9 +89,11 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
                  hipStream_t stream, int persist_blocks = 0);
 
 // Enqueues the gradient pass (see mlpo_grad_unscale_norm).
-// may_time = false: never stamps the launch with timing events (creating an event allocates).
+// may_time = false: never stamps the launch with timing events (creating an event allocates).  keep (host array of
+// n_sg device pointers, entries may be NULL; or NULL): where to leave a copy of each subgroup's gradients.
 int launch_grad_norm(const mlpo_subgroup* sg, int n_sg, float inv_scale, float max_norm, void* workspace,
-                     mlpo_step_scalars* out, hipStream_t stream, bool may_time = true);
+                     mlpo_step_scalars* out, hipStream_t stream, bool may_time = true,
+                     uint16_t* const* keep = nullptr);
 // The address, on the current device, of the library's own statically allocated gradient-pass workspace.
 constexpr int kMaxDevices = 64;
 int static_norm_workspace(void** out);

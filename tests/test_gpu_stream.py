@@ -437,3 +437,81 @@ def test_gradients_fetched_from_the_host_with_the_state(oracle, scratch, streams
         streams[1].synchronize()
     for k in range(wl.n_sub):
         assert_state_parity(ds.fetch(k), host[k], f"{mode} slots={n_slots} chunk={chunk} tile={tile} sg={k}")
+
+
+@pytest.mark.parametrize("mode,tile", [("direct", 2048), ("staged", 0), ("staged", 1024)])
+def test_gradient_pass_keeps_a_device_copy_of_host_gradients(oracle, scratch, streams, mode, tile):
+    """Gradients in pinned host memory (Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"): the
+    gradient pass reads them over the link once and leaves a copy in device memory, the update that follows reads
+    the copy (the subgroup is then described as host-tier state with device gradients).  The copy equals the
+    gradients bit for bit - odd lengths and odd starting addresses included -, the record equals the plain pass's, and
+    the state equals the oracle's."""
+    ohp, ghp = hp_pair(oracle)
+    sizes = [70_001, 3, 40_000, 8_191, 25_002]
+    wl = W.Workload("keep", n_sub=len(sizes), sub_elems=max(sizes), n_host=3, loss_scale=64.0, max_norm=0.03, steps=3)
+    full = W.host_subgroups(wl, warm=True)
+    host = [{key: a[:n].copy() for key, a in sg.items()} for sg, n in zip(full, sizes)]
+    tiers = [wl.tier(k) for k in range(wl.n_sub)]
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=tile)
+    # host-side gradients: slices of one pinned buffer that start at odd elements; device copies with the same phase
+    pinned = torch.zeros(sum(sizes) + 64, dtype=torch.int16).pin_memory()
+    copies = torch.zeros(sum(sizes) + 64, dtype=torch.int16, device=dev())
+    lo, grads_src, keep, update_descs = 3, [], [], []
+    for k, n in enumerate(sizes):
+        if tile:                        # the tiled kernels want 8-byte aligned gradients
+            lo = (lo + 3) // 4 * 4
+        src = pinned[lo:lo + n] if tiers[k] else ds.t[k]["g"]
+        dst = copies[lo:lo + n] if tiers[k] else None
+        grads_src.append(src)
+        keep.append(dst)
+        lo += n + 1
+    norm_descs = []
+    for k, n in enumerate(sizes):
+        e = ds.t[k]
+        g_upd = keep[k] if tiers[k] else e["g"]
+        if tile:
+            norm_descs.append(B.tiled_subgroup(e["state"], grads_src[k], e["p16"], n=n, tier=tiers[k], tile_elems=tile))
+            update_descs.append(B.tiled_subgroup(e["state"], g_upd, e["p16"], n=n, tier=tiers[k], tile_elems=tile))
+        else:
+            norm_descs.append(B.subgroup(e["p"], e["m"], e["v"], grads_src[k], e["p16"], n=n, tier=tiers[k]))
+            update_descs.append(B.subgroup(e["p"], e["m"], e["v"], g_upd, e["p16"], n=n, tier=tiers[k]))
+    norm_table, update_table = B.SubgroupTable(norm_descs), B.SubgroupTable(update_descs)
+    if mode == "direct":
+        cfg, stg = B.direct_cfg(streams[0], streams[1], 24), None
+    else:
+        need = B.mlpo_stream_staging_bytes(update_table, 2, 16_384)
+        stg = torch.empty(need, dtype=torch.uint8, device=dev())
+        cfg = B.stream_cfg(2, stg, need, None, streams[1], None, 16_384)
+    plain = torch.zeros(4, dtype=torch.float32, device=dev())
+    for s in range(wl.steps):
+        for k, sg in enumerate(host):
+            fresh = np.empty(wl.sub_elems, np.uint16)
+            W.fill_grads(wl, k, s, fresh)
+            sg["g"][:] = fresh[:sizes[k]]
+            grads_src[k].copy_(torch.from_numpy(sg["g"].view(np.int16)))
+        copies.zero_()
+        torch.cuda.synchronize()
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, s, wl.inv_scale, wl.max_norm)
+        B.mlpo_grad_unscale_norm(norm_table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, plain, streams[1])
+        B.mlpo_grad_unscale_norm_keep(norm_table, keep, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes,
+                                      scratch.scalars, streams[1])
+        streams[1].synchronize()
+        assert scratch.scalars.cpu().numpy().tobytes() == plain.cpu().numpy().tobytes()
+        for k in range(wl.n_sub):
+            if tiers[k]:
+                assert torch.equal(keep[k].cpu(), grads_src[k]), f"copy of subgroup {k}"
+        # nothing outside the copies was written
+        mask = torch.ones_like(copies, dtype=torch.bool)
+        for k in range(wl.n_sub):
+            if tiers[k]:
+                off = (keep[k].data_ptr() - copies.data_ptr()) // 2
+                mask[off:off + sizes[k]] = False
+        assert not bool(copies[mask].any())
+        assert B.mlpo_stream_update(update_table, None, ghp, s + 1, scratch.scalars, cfg) and ok_o
+        streams[1].synchronize()
+        assert scratch.read()["gmul"] == gmul_o
+        for k in range(wl.n_sub):
+            assert_state_parity(ds.fetch(k), host[k], f"keep {mode} tile={tile} step {s} sg {k}")
+    with pytest.raises(B.MlpoError):        # a copy with another 16-byte phase than its gradients
+        B.mlpo_grad_unscale_norm_keep(norm_table, [copies[1:] if tiers[k] else None for k in range(wl.n_sub)],
+                                      wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars)
