@@ -1000,7 +1000,8 @@ def large_config_leg(args, torch, B, W, np, name, modes, bidir_GBs):
                     bounce = PinnedF32(torch, np, need // 4)
                     pinned.append(bounce)
                     cfg = B.direct_cfg(h2d, cmp_, 64, chunk_elems=chunk, files=files, bounce=bounce.data_ptr(),
-                                       bounce_bytes=need, file_slots=args.file_slots, file_threads=8)
+                                       bounce_bytes=need, file_slots=args.file_slots, file_threads=8,
+                                       want_file_stats=True)
                 else:
                     cfg = B.direct_cfg(h2d, cmp_, 64)
                 what = {"mode": "direct" + (", two paths (pinned + file in /dev/shm)" if file_ids else ""),
@@ -1010,7 +1011,7 @@ def large_config_leg(args, torch, B, W, np, name, modes, bidir_GBs):
                 stg = torch.empty(need, dtype=torch.uint8, device=d)
                 cfg = B.stream_cfg(4, stg, need, None, cmp_, None, chunk)
                 what = {"mode": "staged", "n_slots": 4, "chunk_elems": chunk}
-            times = []
+            times, file_wall = [], []
             for s_ in range(1 + wl.steps):
                 torch.cuda.synchronize()
                 t = time.perf_counter()
@@ -1023,6 +1024,8 @@ def large_config_leg(args, torch, B, W, np, name, modes, bidir_GBs):
                 applied += 1
                 if s_ >= 1:
                     times.append(dt)
+                    if file_ids:
+                        file_wall.append(cfg.stats.wall_seconds)
             mean = sum(times) / len(times)
             gbs = 12 * n_off * M / mean / 1e9
             sc = scal.cpu().numpy()
@@ -1031,6 +1034,10 @@ def large_config_leg(args, torch, B, W, np, name, modes, bidir_GBs):
                    "pcie_GBs_per_dir": round(gbs, 2), "frac_nominal": round(gbs / PCIE_NOMINAL_GBS, 4),
                    "frac_of_bidir_memcpy": round(gbs / bidir_GBs, 4) if bidir_GBs else None,
                    "grad_norm": float(sc[0]), "clip_coef": float(sc[1])}
+            if file_wall:       # the file path's own pace: its bytes over the time from its first read to its last write
+                fw = sum(file_wall) / len(file_wall)
+                run.update({"file_path_wall_ms": round(fw * 1e3, 1),
+                            "file_path_GBs_per_dir": round(12 * len(file_ids) * M / fw / 1e9, 2)})
             rec["runs"].append(run)
             log(f"[bench] {wl.name} {run}")
             del stg, cfg
