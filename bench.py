@@ -1245,6 +1245,8 @@ def main():
                          "--file-dir, O_DIRECT), shm (a file in /dev/shm), or 'none'")
     ap.add_argument("--pinned-capacity", type=int, default=10,
                     help="subgroups the pinned-host path may hold in the two-path run (the rest go to the file)")
+    ap.add_argument("--no-link-yardstick", dest="link_yardstick", action="store_false",
+                    help="do not start the pinned-copy yardstick in a process of its own before the run")
     ap.add_argument("--no-three-paths", dest="three_paths", action="store_false",
                     help="skip the run with three live paths (pinned memory, a file in /dev/shm, a file on the disk)")
     ap.add_argument("--pinned-capacity-3", type=int, default=8,
@@ -1278,7 +1280,11 @@ def main():
     # with the system's HIP runtime (the copies of ys_link inside this process share the device with torch's runtime
     # and its streams, and have been seen to take turns there instead of overlapping).
     link_fresh = None
-    if args.streamed != "none":
+    # (not under a profiler: its preloaded library may have initialised the GPU in this process already, and a
+    # process that has must not start another program)
+    under_profiler = any("rocprof" in os.environ.get(k, "") for k in ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES",
+                                                                     "ROCPROFILER_LIBRARY_CTOR", "HSA_TOOLS_LIB"))
+    if args.streamed != "none" and args.link_yardstick and not under_profiler:
         import subprocess
         exe = os.path.join(ROOT, "bench_link_yardstick")
         # three runs, the best one counts: the first process on a machine that has just been handed out has been seen
