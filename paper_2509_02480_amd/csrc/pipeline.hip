@@ -444,6 +444,7 @@ static std::vector<uint64_t> file_paths_of(const mlpo_subgroup* sg, const std::v
                                            const mlpo_stream_cfg* cfg) {
     std::vector<uint64_t> paths;
     for (int32_t i : ids) {
+        if (sg[i].n == 0) continue;  // an empty subgroup moves nothing and its file entry need not name a file
         const mlpo_flush_target* to =
             (cfg->flush_to != nullptr && cfg->flush_to[i].tier != MLPO_FLUSH_IN_PLACE) ? &cfg->flush_to[i] : nullptr;
         const bool from_file = sg[i].tier == MLPO_TIER_FILE;

@@ -102,9 +102,14 @@ def build(rng, host, tiers, tiles, path, half):
 
 # MLPO_RANDOM_SEEDS=a:b runs that range of seeds instead (a wider sweep now and then)
 _lo, _, _hi = os.environ.get("MLPO_RANDOM_SEEDS", "0:160").partition(":")
+# scenarios from wider sweeps that once failed and stay in the default run: 204 = an EMPTY file-tier subgroup, whose
+# file entry names no file, beside file-tier subgroups with a single bounce buffer
+_SEEDS = list(range(int(_lo), int(_hi)))
+if "MLPO_RANDOM_SEEDS" not in os.environ:
+    _SEEDS += [204]
 
 
-@pytest.mark.parametrize("seed", range(int(_lo), int(_hi)))
+@pytest.mark.parametrize("seed", _SEEDS)
 def test_random_scenario(oracle, tmp_path, seed):
     rng = np.random.default_rng(1000 + seed)
     direct = bool(rng.integers(0, 2))
@@ -119,7 +124,7 @@ def test_random_scenario(oracle, tmp_path, seed):
         if t:
             unit = unit * t // math.gcd(unit, t)
     chunk = 0 if rng.integers(0, 3) == 0 else unit * int(rng.integers(1, 6))
-    cached = (not direct) and chunk == 0 and bool(rng.integers(0, 2))
+    cached = (not direct) and bool(rng.integers(0, 2))     # misses move whole or in pieces of chunk
     n_slots = int(rng.integers(1, 6))
     hp_kw = dict(lr=float(rng.choice([1e-4, 3e-3])), weight_decay=float(rng.choice([0.0, 0.01])),
                  bias_correction=bool(rng.integers(0, 2)), l2_mode=bool(rng.integers(0, 2)))
@@ -147,7 +152,7 @@ def test_random_scenario(oracle, tmp_path, seed):
             slots = int(rng.integers(1, 4))
             blocks, threads = int(rng.integers(1, 40)), int(rng.integers(1, 5))
         else:
-            need = B.mlpo_stream_staging_bytes(table, n_slots, chunk)
+            need = B.mlpo_stream_staging_bytes(table, n_slots, B.CHUNK_WHOLE if cached else chunk)
             stg = torch.empty(max(need, 256), dtype=torch.uint8, device=dev())
             own = bool(rng.integers(0, 2))
             cfg = B.stream_cfg(n_slots, stg, stg.numel(), None if own else streams[0], streams[1],
