@@ -1,7 +1,8 @@
 """Seeded random scenarios for mlpo_stream_update: subgroups of random sizes (empty ones included) spread over every
 tier and both layouts in one table, random mode, slots, chunking, slot cache, order and thread counts, a non-finite
-gradient now and then, and in direct mode subgroups that are flushed to another place - pinned memory, the file, HBM -
-than they came from (Algorithm 1 assigns the path anew at every flush).  After every step every bit of state is compared with the oracle's (the paper's statement that
+gradient now and then, and in direct mode one or two files (on different file systems: two paths) and subgroups that
+are flushed to another place - pinned memory, a file, HBM - than they came from (Algorithm 1 assigns the path anew at
+every flush).  After every step every bit of state is compared with the oracle's (the paper's statement that
 order and partitioning do not change the result, Section 3.2 "Cache-Friendly Ordering", Section 4.1 "Runtime
 Configurations")."""
 import math
@@ -22,12 +23,14 @@ from gpu_util import Scratch, assert_state_parity, dev, hp_pair, pack_tiled, unp
 SIZES = [0, 1, 3, 4, 5, 63, 64, 1023, 1024, 1025, 2047, 4096, 8191, 8192, 12_289, 30_001, 50_000, 65_537]
 
 
-def build(rng, host, tiers, tiles, path, half):
-    """Device / pinned / file homes for every subgroup; returns (table, files, keep, fetch)."""
+def build(rng, host, tiers, tiles, paths, pick, half):
+    """Device / pinned / file homes for every subgroup; file-tier subgroups go to the file that pick() names (files on
+    different file systems are different paths, each with workers and bounce buffers of its own).  Returns (subgroup
+    descriptors, file extents, bookkeeping per subgroup, fetch(k), descriptors of the files, their lengths)."""
     d = dev()
     descs, files, keep = [], [], []
-    fd = os.open(path, os.O_RDWR | os.O_CREAT, 0o600)
-    off = 0
+    fds = [os.open(p, os.O_RDWR | os.O_CREAT, 0o600) for p in paths]
+    offs = [0] * len(fds)
     for k, s in enumerate(host):
         n, T, tier = s["p"].size, tiles[k], tiers[k]
         g_home_host = tier == B.TIER_HOST_GRADS
@@ -44,11 +47,12 @@ def build(rng, host, tiers, tiles, path, half):
             files.append(None)
         elif tier == B.TIER_FILE:
             packed = pack_tiled(s["p"], s["m"], s["v"], T)
-            os.pwrite(fd, packed.tobytes(), off)
-            ent["off"] = off
+            w = pick()
+            os.pwrite(fds[w], packed.tobytes(), offs[w])
+            ent["off"], ent["fd"] = offs[w], fds[w]
             descs.append(B.SubgroupC(None, None, None, g.data_ptr(), p16.data_ptr(), n, tier, T, half, 0))
-            files.append((fd, off))
-            off += (packed.nbytes + 4095) // 4096 * 4096
+            files.append((fds[w], offs[w]))
+            offs[w] += (packed.nbytes + 4095) // 4096 * 4096
         else:
             on_host = tier in (B.TIER_HOST, B.TIER_HOST_GRADS)
             if T:
@@ -77,8 +81,9 @@ def build(rng, host, tiers, tiles, path, half):
                 descs.append(B.subgroup(arrs[0], arrs[1], arrs[2], g, p16, n=n, tier=tier, half=half))
             files.append(None)
         keep.append(ent)
-    os.ftruncate(fd, max(off, 4096))
-    os.fsync(fd)
+    for fd, off in zip(fds, offs):
+        os.ftruncate(fd, max(off, 4096))
+        os.fsync(fd)
     torch.cuda.synchronize()
 
     def fetch(k):
@@ -89,7 +94,7 @@ def build(rng, host, tiers, tiles, path, half):
             z = np.zeros(0, np.float32)
             return {"p": z, "m": z, "v": z, "p16": p16}
         if e["tier"] == B.TIER_FILE:
-            buf = np.frombuffer(os.pread(fd, B.mlpo_state_floats(n, T) * 4, e["off"]), dtype=np.float32)
+            buf = np.frombuffer(os.pread(e["fd"], B.mlpo_state_floats(n, T) * 4, e["off"]), dtype=np.float32)
             p, m, v = unpack_tiled(buf, n, T)
         elif T:
             p, m, v = unpack_tiled(e["state"].cpu().numpy(), n, T, e.get("lead", 0))
@@ -97,7 +102,7 @@ def build(rng, host, tiers, tiles, path, half):
             p, m, v = (t.cpu().numpy().copy() for t in e["pmv"])
         return {"p": p, "m": m, "v": v, "p16": p16}
 
-    return descs, files, keep, fetch, fd, off
+    return descs, files, keep, fetch, fds, offs
 
 
 # MLPO_RANDOM_SEEDS=a:b runs that range of seeds instead (a wider sweep now and then)
@@ -142,14 +147,23 @@ def test_random_scenario(oracle, tmp_path, seed):
     label = (f"seed {seed}: {'direct' if direct else 'staged'} sizes {sizes} tiers {tiers} tiles {tiles} chunk {chunk} "
              f"slots {n_slots} cached {cached} {half_name}")
     print(label, flush=True)
-    descs, files, keep, fetch, fd, file_end = build(rng, host, tiers, tiles, str(tmp_path / "state.bin"), half)
+    # a second file on another file system = a second path behind the offloaded tier (drawn from a generator of its
+    # own, so that the scenarios of the first generator stay what they were)
+    rng2 = np.random.default_rng(77_000 + seed)
+    paths = [str(tmp_path / "state.bin")]
+    shm = f"/dev/shm/mlpo_rnd_{os.getpid()}_{seed}.bin"
+    if direct and rng2.integers(0, 2) and os.path.isdir("/dev/shm") and \
+            os.stat("/dev/shm").st_dev != os.stat(str(tmp_path)).st_dev:
+        paths.append(shm)
+    pick = lambda: int(rng2.integers(0, len(paths)))  # noqa: E731
+    descs, files, keep, fetch, fds, file_end = build(rng, host, tiers, tiles, paths, pick, half)
     table = B.SubgroupTable(descs)
     scratch = Scratch()
     streams = (torch.cuda.Stream(), torch.cuda.Stream())
     cache = B.SlotCacheC() if cached else None
     try:
         if direct:
-            slots = int(rng.integers(1, 4))
+            slots = max(int(rng.integers(1, 4)), len(paths))    # every path needs a bounce buffer of its own
             blocks, threads = int(rng.integers(1, 40)), int(rng.integers(1, 5))
         else:
             need = B.mlpo_stream_staging_bytes(table, n_slots, B.CHUNK_WHOLE if cached else chunk)
@@ -181,10 +195,11 @@ def test_random_scenario(oracle, tmp_path, seed):
                                                                                            ["host", "file", "hbm"])
                     kind = str(rng.choice(kinds))
                     if kind == "file":
-                        targets[k] = (fd, file_end)
-                        moved[k] = {"off": file_end, "tier": B.TIER_FILE}
-                        file_end += (floats * 4 + 4095) // 4096 * 4096
-                        os.ftruncate(fd, file_end)
+                        w = pick()
+                        targets[k] = (fds[w], file_end[w])
+                        moved[k] = {"off": file_end[w], "fd": fds[w], "tier": B.TIER_FILE}
+                        file_end[w] += (floats * 4 + 4095) // 4096 * 4096
+                        os.ftruncate(fds[w], file_end[w])
                     else:
                         st = torch.full((floats,), float("nan"), dtype=torch.float32,
                                         **({"pin_memory": True} if kind == "host" else {"device": dev()}))
@@ -218,12 +233,13 @@ def test_random_scenario(oracle, tmp_path, seed):
                     e = keep[k]
                     e.pop("state", None)
                     e.pop("off", None)
+                    e.pop("fd", None)
                     e["lead"] = 0
                     e.update(new)
                     if e["tier"] == B.TIER_FILE:
                         descs[k] = B.SubgroupC(None, None, None, e["g"].data_ptr(), e["p16"].data_ptr(), e["n"],
                                                B.TIER_FILE, e["T"], half, 0)
-                        files[k] = (fd, e["off"])
+                        files[k] = (e["fd"], e["off"])
                     else:
                         descs[k] = B.tiled_subgroup(e["state"], e["g"], e["p16"], n=e["n"], tier=e["tier"],
                                                     tile_elems=e["T"], half=half)
@@ -238,4 +254,7 @@ def test_random_scenario(oracle, tmp_path, seed):
                 assert_state_parity(fetch(k), host[k], f"{label} step {step} sg {k}")
     finally:
         torch.cuda.synchronize()
-        os.close(fd)
+        for fd in fds:
+            os.close(fd)
+        if len(paths) > 1:
+            os.unlink(shm)
