@@ -508,7 +508,8 @@ class StreamedBench:
         need = B.mlpo_stream_staging_bytes(table, n_slots, WHOLE if cache is not None else chunk)
         stg = torch.empty(need, dtype=torch.uint8, device=self.d)
         # no copy streams given: the library's own
-        return table, B.stream_cfg(n_slots, stg, need, None, self.cmp, None, chunk, cache=cache), stg, cache
+        return table, B.stream_cfg(n_slots, stg, need, None, self.cmp, None, chunk, cache=cache,
+                                   direct_blocks=self.args.cache_blocks if cache is not None else 0), stg, cache
 
     def last_micro_batch(self):
         """The last micro-batch of the backward pass (outside the update phase, untimed) accumulates into the host
@@ -575,7 +576,8 @@ class StreamedBench:
                             "(14 B/param in, 12 out)", "direct_blocks": arg},
             "sgk": {"mode": "staged, gradients on the host too, the gradient pass keeps a device copy for the update "
                             "(14 B/param in, 12 out)", "n_slots": 3, "chunk_elems": arg},
-            "c": {"mode": "staged+slot-cache, alternating order, misses in pieces of 2^24", "n_slots": arg},
+            "c": {"mode": "staged+slot-cache, alternating order, a miss = one kernel that exchanges the slot's occupants "
+                          "over the link", "n_slots": arg, "exchange_workgroups": self.args.cache_blocks or 80},
         }.get(kind, {"mode": "staged", "n_slots": kind,
                      "chunk_elems": "whole subgroups" if arg == WHOLE else (arg or "library's choice (2^24)")})
 
@@ -1237,6 +1239,9 @@ def main():
                          "the gradient pass keeps a device copy that the update reads), sg:chunk_elems (staged mode with 3 slots, "
                          "gradients in pinned host memory too) or c:n_slots (staged mode with slots that keep their "
                          "subgroups and alternating order)")
+    ap.add_argument("--cache-blocks", type=int, default=0,
+                    help="c: variants: workgroups of the kernel that exchanges a slot's occupants (0 = the library's "
+                         "default)")
     ap.add_argument("--stream-warmup", type=int, default=2)
     ap.add_argument("--large", default="C4,C5",
                     help="comma list of the large mixed-tier workloads to run whole after the streamed one, or 'none'")

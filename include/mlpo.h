@@ -384,12 +384,19 @@ typedef struct {
                               pair of copy streams of its own (created on first use, kept until mlpo_shutdown); this
                               is the recommended setting: streams handed out by a framework's pool can share a
                               hardware queue, and the two copy directions then take turns instead of overlapping */
-    int32_t direct_blocks; /* direct: persistent workgroups on the host tier; 0 = default (64); at most 4096 */
+    int32_t direct_blocks; /* persistent workgroups of a kernel that works over the link (direct mode: the update of the
+                              host tier; slot cache: the kernel that exchanges a slot's occupants); 0 = default
+                              (64 and 80: the counts that were fastest on the 13 x 100 M-element workload); at most
+                              4096 */
     int32_t reserved;      /* must be 0 */
     mlpo_slot_cache* cache; /* staged: slots keep their subgroups between steps; NULL = off.  Every slot then holds a
-                               whole subgroup (size the staging buffer with MLPO_CHUNK_WHOLE); chunk_elems is the
-                               size of the pieces in which a miss replaces the slot's old occupant (tiled layout;
-                               planar subgroups enter and leave whole) */
+                               whole subgroup (size the staging buffer with MLPO_CHUNK_WHOLE).  A miss of a tiled
+                               subgroup into a slot that is empty, already written back, or holds a subgroup of the
+                               same n and tile_elems is served by one kernel on the h2d stream (direct_blocks
+                               workgroups): it updates the newcomer on its way from pinned memory into the slot and
+                               sends what the slot held to the old occupant's home, tile by tile.  Any other miss
+                               moves by copies, in pieces of chunk_elems (tiled layout; planar subgroups enter and
+                               leave whole) */
     /* The file path (direct mode; all zero / NULL when no subgroup is MLPO_TIER_FILE): */
     const mlpo_file_extent* files; /* host array with one entry per subgroup of the table; only the entries of
                                       MLPO_TIER_FILE subgroups are read */

@@ -302,11 +302,13 @@ CHUNK_WHOLE = (1 << 64) - 1      # chunk_elems: a whole subgroup per transfer (0
 
 
 def stream_cfg(n_slots: int, staging, staging_bytes: int, h2d, compute, d2h, chunk_elems: int = 0,
-               cache: Optional[SlotCacheC] = None) -> StreamCfgC:
+               cache: Optional[SlotCacheC] = None, direct_blocks: int = 0) -> StreamCfgC:
     """Staged mode: host-tier subgroups travel through ``n_slots`` device staging slots.  ``cache`` (a zero-initialised
-    SlotCacheC kept by the caller) lets slots keep their subgroups between steps."""
+    SlotCacheC kept by the caller) lets slots keep their subgroups between steps; ``direct_blocks`` is then the number
+    of workgroups of the kernel that exchanges a slot's occupants over the link (0 = the library's default)."""
     cfg = StreamCfgC(n_slots, STREAM_STAGED, chunk_elems, _ptr(staging), staging_bytes, _stream(h2d),
-                     _stream(compute), _stream(d2h), 0, 0, None, None, None, 0, 0, 0, None, None, None, 0, 0)
+                     _stream(compute), _stream(d2h), direct_blocks, 0, None, None, None, 0, 0, 0, None, None, None, 0,
+                     0)
     if cache is not None:
         cfg.cache = C.pointer(cache)
         cfg._keep = cache

@@ -11,7 +11,11 @@
 // fp32 ones (Algorithm 1's downcast).  There is no reuse, so nothing is staged through LDS and all accesses but the
 // stores of the half-precision parameters carry the non-temporal hint.  The grid-stride kernels also exist in an out-of-place form that stores the new p, m, v a
 // per-subgroup distance away from where it loaded the old ones: that is how a subgroup changes its home (another
-// pinned buffer, a bounce buffer bound for a file, HBM) while it is updated.
+// pinned buffer, a bounce buffer bound for a file, HBM) while it is updated.  The exchanging form goes one step further:
+// before a lane stores its new p, m, v at the destination it takes what the destination held and stores that a second
+// per-subgroup distance away - a staging slot in HBM changes its occupant in one pass, the old one leaving for its
+// home in pinned memory while the new one arrives from its own and is updated on the way, so both directions of the
+// link are busy from the first tile to the last.
 //
 // Arithmetic: every operation is an individually rounded fp32 operation (no contraction into fused multiply-add,
 // IEEE division and square root, denormals kept) so that results can be compared bit for bit with a plain CPU
@@ -54,12 +58,20 @@ struct VecBatch {
     int32_t n_sg;
 };
 // Extra argument of the out-of-place kernels: where each subgroup's new p, m, v go, in groups of four behind where
-// the old ones were read.  The in-place kernels take the empty form.
-template <bool MOVE>
+// the old ones were read (kMove), and for the exchanging kernels also where the previous content of that destination
+// goes, in groups of four behind the destination (kSwap; 0 = this subgroup displaces nothing).  The in-place kernels
+// take the empty form.
+constexpr int kInPlace = 0, kMove = 1, kSwap = 2;
+template <int MOVE>
 struct StoreShift {};
 template <>
-struct StoreShift<true> {
+struct StoreShift<kMove> {
     int64_t out4[kMaxSg];
+};
+template <>
+struct StoreShift<kSwap> {
+    int64_t out4[kMaxSg];
+    int64_t evict4[kMaxSg];
 };
 
 // Element-wise view for whatever the 128-bit kernel cannot take (unaligned subgroups, tails of 1-3 elements).
@@ -162,13 +174,14 @@ struct Tile {
     f32x4* v;
     const u32x2* g;
     u32x2* h;
-    int64_t out4;  // MOVE only: store offset of p, m, v relative to their load addresses, in groups of four
+    int64_t out4;    // kMove, kSwap: store offset of p, m, v relative to their load addresses, in groups of four
+    int64_t evict4;  // kSwap: where the destination's previous content goes, relative to the destination (0: nowhere)
     uint32_t cnt;  // groups of four in this tile: lanes work on groups lo <= i < cnt
     uint32_t lo;   // 0 except in the first tile of a subgroup with padding in front
     bool full;     // every lane of every pass has a group
 };
 
-template <int T4, bool MOVE>
+template <int T4, int MOVE>
 __device__ __forceinline__ Tile locate(const VecBatch& b, const StoreShift<MOVE>& shift, uint32_t tile, int& s) {
     while (tile >= b.tile_begin[s + 1]) ++s;
     const VecView& d = b.sg[s];
@@ -196,42 +209,58 @@ __device__ __forceinline__ Tile locate(const VecBatch& b, const StoreShift<MOVE>
     t.g = d.g + q0;
     t.h = d.h + q0;
     t.out4 = 0;
-    if constexpr (MOVE) t.out4 = shift.out4[s];
+    t.evict4 = 0;
+    if constexpr (MOVE != kInPlace) t.out4 = shift.out4[s];
+    if constexpr (MOVE == kSwap) t.evict4 = shift.evict4[s];
     t.cnt = left < (uint64_t)T4 ? (uint32_t)left : (uint32_t)T4;
     t.lo = t_in == 0u ? d.lead4 : 0u;
     t.full = t.cnt == (uint32_t)T4 && t.lo == 0u;
     return t;
 }
 
-// MOVE = false stores p, m, v where they were loaded from; MOVE = true stores them Tile::out4 groups further on.
+// MOVE = kInPlace stores p, m, v where they were loaded from; kMove stores them Tile::out4 groups further on; kSwap
+// does the same after it has taken what lay there and stored it Tile::evict4 groups beyond (the loads of the old
+// content are issued with the tile's other loads, and its stores come first, so nothing is overwritten before it
+// has been read).
 // The 128-bit accesses to p, m, v and the loads of g carry the non-temporal hint; the 64-bit stores of the
 // half-precision parameters do not: with the hint they cost 6 % of the kernel's speed (measured; the other three
 // combinations of hints on g and p16 are slower as well), without it the lines are put together in the cache.
-template <int BLOCK, int UNROLL, bool NT, bool MOVE>
+template <int UNROLL, int MOVE>
+struct OldContent {};
+template <int UNROLL>
+struct OldContent<UNROLL, kSwap> {
+    f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
+};
+
+template <int BLOCK, int UNROLL, bool NT, int MOVE>
 struct Regs {
     f32x4 P[UNROLL], M[UNROLL], V[UNROLL];
     u32x2 G[UNROLL];
+    OldContent<UNROLL, MOVE> old;
+
+    __device__ __forceinline__ void load_group(const Tile& t, int u, uint32_t i) {
+        P[u] = ld<NT>(t.p + i);
+        M[u] = ld<NT>(t.m + i);
+        V[u] = ld<NT>(t.v + i);
+        G[u] = ld<NT>(t.g + i);
+        if constexpr (MOVE == kSwap) {
+            if (t.evict4 != 0) {
+                old.P[u] = ld<NT>(t.p + t.out4 + i);
+                old.M[u] = ld<NT>(t.m + t.out4 + i);
+                old.V[u] = ld<NT>(t.v + t.out4 + i);
+            }
+        }
+    }
 
     __device__ __forceinline__ void load(const Tile& t, uint32_t tid) {
         if (t.full) {
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint32_t i = u * BLOCK + tid;
-                P[u] = ld<NT>(t.p + i);
-                M[u] = ld<NT>(t.m + i);
-                V[u] = ld<NT>(t.v + i);
-                G[u] = ld<NT>(t.g + i);
-            }
+            for (int u = 0; u < UNROLL; ++u) load_group(t, u, u * BLOCK + tid);
         } else {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
-                if (i >= t.lo && i < t.cnt) {
-                    P[u] = ld<NT>(t.p + i);
-                    M[u] = ld<NT>(t.m + i);
-                    V[u] = ld<NT>(t.v + i);
-                    G[u] = ld<NT>(t.g + i);
-                }
+                if (i >= t.lo && i < t.cnt) load_group(t, u, i);
             }
         }
     }
@@ -244,29 +273,32 @@ struct Regs {
     }
 
     template <int HALF>
+    __device__ __forceinline__ void store_group(const Tile& t, int u, uint32_t i, float gmul, const AdamwConsts& c) {
+        const auto out = [&t](f32x4* q) { return MOVE != kInPlace ? q + t.out4 : q; };
+        if constexpr (MOVE == kSwap) {
+            if (t.evict4 != 0) {
+                st<NT>(out(t.p) + t.evict4 + i, old.P[u]);
+                st<NT>(out(t.m) + t.evict4 + i, old.M[u]);
+                st<NT>(out(t.v) + t.evict4 + i, old.V[u]);
+            }
+        }
+        const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
+        st<NT>(out(t.p) + i, P[u]);
+        st<NT>(out(t.m) + i, M[u]);
+        st<NT>(out(t.v) + i, V[u]);
+        t.h[i] = H;  // no hint: see the note at Regs
+    }
+
+    template <int HALF>
     __device__ __forceinline__ void update_store_as(const Tile& t, uint32_t tid, float gmul, const AdamwConsts& c) {
-        const auto out = [&t](f32x4* q) { return MOVE ? q + t.out4 : q; };
         if (t.full) {
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const uint32_t i = u * BLOCK + tid;
-                const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
-                st<NT>(out(t.p) + i, P[u]);
-                st<NT>(out(t.m) + i, M[u]);
-                st<NT>(out(t.v) + i, V[u]);
-                t.h[i] = H;  // no hint: see the note at Regs
-            }
+            for (int u = 0; u < UNROLL; ++u) store_group<HALF>(t, u, u * BLOCK + tid, gmul, c);
         } else {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t i = u * BLOCK + tid;
-                if (i >= t.lo && i < t.cnt) {
-                    const u32x2 H = update_four<HALF>(P[u], M[u], V[u], G[u], gmul, c);
-                    st<NT>(out(t.p) + i, P[u]);
-                    st<NT>(out(t.m) + i, M[u]);
-                    st<NT>(out(t.v) + i, V[u]);
-                    t.h[i] = H;  // no hint: see the note at Regs
-                }
+                if (i >= t.lo && i < t.cnt) store_group<HALF>(t, u, i, gmul, c);
             }
         }
     }
@@ -275,7 +307,7 @@ struct Regs {
 // 128-bit kernel: p, m, v 16-byte aligned, g, p16 8-byte aligned, element counts multiples of four.
 // PERSIST = false: one tile per block.  PERSIST = true: grid-stride over tiles, next tile's loads in flight while the
 // current tile is computed and stored.
-template <int BLOCK, int UNROLL, bool NT, bool PERSIST, bool MOVE>
+template <int BLOCK, int UNROLL, bool NT, bool PERSIST, int MOVE>
 __global__ void __launch_bounds__(BLOCK) adamw_v4_kernel(const VecBatch b, const AdamwConsts c,
                                                          const mlpo_step_scalars* __restrict__ sc,
                                                          const StoreShift<MOVE> shift) {
@@ -348,6 +380,13 @@ __global__ void __launch_bounds__(kBlock1) adamw_v1_kernel(const ScalarBatch b, 
         const uint64_t j = base + (uint32_t)(u * kBlock1) + threadIdx.x;
         if (j >= d.lead && j < d.n) {
             float pp = d.p[j], mm = d.m[j], vv = d.v[j];
+            if (d.evict_delta != 0) {  // the destination's previous content moves on first
+                const int64_t from = (int64_t)j + d.out_delta, to = from + d.evict_delta;
+                const float po = d.p[from], mo = d.m[from], vo = d.v[from];
+                d.p[to] = po;
+                d.m[to] = mo;
+                d.v[to] = vo;
+            }
             if (c.half == 0)
                 d.p16[j] = (uint16_t)update_one<0>(pp, mm, vv, widen_low<0>(d.g[j]), gmul, c);
             else
@@ -362,7 +401,7 @@ __global__ void __launch_bounds__(kBlock1) adamw_v1_kernel(const ScalarBatch b, 
 bool vec_aligned(const SgView& s) {
     auto a = [](const void* q) { return reinterpret_cast<uintptr_t>(q); };
     return ((a(s.p) | a(s.m) | a(s.v)) & 15u) == 0 && ((a(s.g) | a(s.p16)) & 7u) == 0 && s.out_delta % 4 == 0 &&
-           s.lead % 4 == 0;
+           s.evict_delta % 4 == 0 && s.lead % 4 == 0;
 }
 
 // Two forms of the 128-bit kernel are built, both with 256 lanes and one group of four elements per lane (a kernel
@@ -373,7 +412,7 @@ bool vec_aligned(const SgView& s) {
 constexpr int kLanes = 256;
 constexpr uint64_t kTile4 = kLanes;  // groups of four per kernel tile
 
-template <bool PERSIST, bool MOVE = false>
+template <bool PERSIST, int MOVE = kInPlace>
 void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
                const StoreShift<MOVE>& shift = StoreShift<MOVE>{}) {
     hipEvent_t t0, t1;
@@ -385,10 +424,11 @@ void launch_v4(const VecBatch& b, uint32_t grid, const AdamwConsts& c, const mlp
                            shift);
 }
 
-// persist_blocks = 0: one tile per workgroup.  > 0: that many persistent workgroups at most.  shift != nullptr: the
-// out-of-place form (always grid-stride; persist_blocks = 0 then means eight workgroups per compute unit).
+// persist_blocks = 0: one tile per workgroup.  > 0: that many persistent workgroups at most.  shift != nullptr: an
+// out-of-place form (always grid-stride; persist_blocks = 0 then means eight workgroups per compute unit), the
+// exchanging one if any subgroup of the batch displaces what its destination held.
 int launch_vec_batch(const VecBatch& b, const AdamwConsts& c, const mlpo_step_scalars* sc, hipStream_t st,
-                     int persist_blocks, const StoreShift<true>* shift) {
+                     int persist_blocks, const StoreShift<kSwap>* shift) {
     const uint32_t total = b.tile_begin[b.n_sg];
     if (total == 0) return MLPO_OK;
     uint32_t grid = total;
@@ -400,12 +440,20 @@ int launch_vec_batch(const VecBatch& b, const AdamwConsts& c, const mlpo_step_sc
         const uint64_t cap = (uint64_t)cus * 8u;
         if (cap < grid) grid = (uint32_t)cap;
     }
+    bool swaps = false;
     if (shift != nullptr)
-        launch_v4<true, true>(b, grid, c, sc, st, *shift);
-    else if (persist_blocks > 0)
+        for (int i = 0; i < b.n_sg; ++i) swaps = swaps || shift->evict4[i] != 0;
+    if (swaps) {
+        launch_v4<true, kSwap>(b, grid, c, sc, st, *shift);
+    } else if (shift != nullptr) {
+        StoreShift<kMove> mv;
+        for (int i = 0; i < kMaxSg; ++i) mv.out4[i] = shift->out4[i];
+        launch_v4<true, kMove>(b, grid, c, sc, st, mv);
+    } else if (persist_blocks > 0) {
         launch_v4<true>(b, grid, c, sc, st);
-    else
+    } else {
         launch_v4<false>(b, grid, c, sc, st);  // grid == total: every tile has its workgroup
+    }
     MLPO_HIP(hipGetLastError());
     return MLPO_OK;
 }
@@ -435,8 +483,8 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
     VecBatch vb;
     vb.n_sg = 0;
     vb.tile_begin[0] = 0;
-    StoreShift<true> shift{};
-    const StoreShift<true>* shift_arg = moves ? &shift : nullptr;
+    StoreShift<kSwap> shift{};
+    const StoreShift<kSwap>* shift_arg = moves ? &shift : nullptr;
     ScalarBatch sb;
     sb.n_sg = 0;
     sb.tile_begin[0] = 0;
@@ -469,7 +517,8 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
             const uint64_t o = n4 * 4;
             uint64_t po = o;  // position of element o in the state arrays
             if (s.tile_elems != 0) po = (o / (uint64_t)s.tile_elems) * 3u * (uint64_t)s.tile_elems + o % (uint64_t)s.tile_elems;
-            const int rc = push_scalar(SgView{s.p + po, s.m + po, s.v + po, s.g + o, s.p16 + o, tail, 0, s.out_delta});
+            const int rc = push_scalar(SgView{s.p + po, s.m + po, s.v + po, s.g + o, s.p16 + o, tail, 0, s.out_delta,
+                                              s.evict_delta});
             if (rc != MLPO_OK) return rc;
         }
         if (n4 == 0) continue;
@@ -495,6 +544,7 @@ int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_st
         d.S4 = s.tile_elems != 0 ? (uint32_t)(3u * (uint64_t)s.tile_elems / 4) : 0u;
         d.lead4 = s.lead / 4;
         shift.out4[vb.n_sg] = s.out_delta / 4;
+        shift.evict4[vb.n_sg] = s.evict_delta / 4;
         vb.tile_begin[vb.n_sg + 1] = vb.tile_begin[vb.n_sg] + (uint32_t)tiles;
         ++vb.n_sg;
     }

@@ -62,6 +62,10 @@ struct SgView {
     // Out-of-place update (tiled views only): the new p, m, v are stored out_delta floats behind where the old ones
     // were read, i.e. into another buffer of the same layout; 0 = in place.  A multiple of 4.
     int64_t out_delta = 0;
+    // Exchange (with out_delta != 0 only): what the destination held before is stored evict_delta floats behind the
+    // destination - the previous occupant of a staging slot leaves for its home while the new one arrives.  0 = the
+    // destination's content is simply overwritten.  A multiple of 4.
+    int64_t evict_delta = 0;
     // Padding in front (tiled views only): the view's first `lead` elements are no elements of the subgroup, nothing
     // is read or written for them (g and p16 point `lead` elements before the subgroup's first value, n counts the
     // padding).  A multiple of 4, smaller than a kernel tile.  It lets the caller shift a subgroup inside its state

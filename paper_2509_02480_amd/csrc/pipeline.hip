@@ -286,7 +286,7 @@ static int check_stream_args(const mlpo_subgroup* sg, int32_t n_sg, const int32_
     if (cfg->mode != MLPO_STREAM_STAGED && cfg->mode != MLPO_STREAM_DIRECT)
         return fail(MLPO_EINVAL, "unknown mode %d", cfg->mode);
     const bool direct = cfg->mode == MLPO_STREAM_DIRECT;
-    if (direct && (cfg->direct_blocks < 0 || cfg->direct_blocks > 4096))
+    if (cfg->direct_blocks < 0 || cfg->direct_blocks > 4096)
         return fail(MLPO_EINVAL, "direct_blocks must be 0..4096 (got %d)", cfg->direct_blocks);
     if (!direct && (cfg->n_slots < 1 || cfg->n_slots > MLPO_MAX_SLOTS))
         return fail(MLPO_EINVAL, "n_slots must be 1..%d (got %d)", MLPO_MAX_SLOTS, cfg->n_slots);
@@ -628,18 +628,27 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
 }
 
 // Staged mode with a slot cache: slots keep their subgroup from one step to the next (Section 3.2 "Cache-Friendly
-// Ordering").  A subgroup found in a slot is updated there without any transfer, and a slot is copied back only when
-// another subgroup needs it (or on mlpo_stream_flush).  With the order reversed from step to step the subgroups
-// processed last are the ones processed first next time.  A miss moves in pieces (tiled subgroups): the old
+// Ordering").  A subgroup found in a slot is updated there without any transfer, and a slot changes its occupant only
+// when another subgroup needs it (or is copied back on mlpo_stream_flush).  With the order reversed from step to step
+// the subgroups processed last are the ones processed first next time.
+// A miss of a tiled subgroup into a slot that is empty, clean, or holds a subgroup of the same shape is served by ONE
+// kernel on the link stream: a bounded number of persistent workgroups read the newcomer's state in pinned memory,
+// update it and store it into the slot, and - tile by tile, just before they overwrite it - send what the slot held
+// to the old occupant's home in pinned memory.  Both directions of the link are busy from the first tile to the
+// last, there is no pipeline to fill or drain and nothing depends on how the runtime schedules copies of different
+// streams.  Other misses (planar subgroups, occupants of another shape) move by copies, in pieces: the old
 // occupant's piece c goes back to the host, the newcomer's piece c takes its place and is updated as soon as it has
-// arrived, so the two copy directions and the kernel overlap inside one miss and the pipeline fills and drains in a
-// piece, not in a subgroup.
+// arrived.
 static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwConsts& c,
                       const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, uint64_t slot_floats,
                       const Streams& st, EventCache& ec) {
     mlpo_slot_cache* cache = cfg->cache;
     float* staging = static_cast<float*>(cfg->staging);
     int rc;
+    // workgroups of a miss served by a kernel (13 x 100 M elements, 4 slots, ms per step: 32 workgroups 246.7, 48 225.8,
+    // 64 221.7, 80 220.6, 96 223.2, 128 230.7)
+    const int link_blocks = cfg->direct_blocks > 0 ? cfg->direct_blocks : 80;
+    bool link_used = false;
     // pieces a subgroup moves in while it enters or leaves a slot: planar subgroups whole (their arrays are spread
     // over the slot), tiled ones under the configuration's chunk_elems
     const auto step_of = [cfg](const mlpo_subgroup& s) { return s.tile_elems > 0 ? piece_elems(s, cfg->chunk_elems) : s.n; };
@@ -678,6 +687,29 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
             ++cache->hits;
         } else {
             const mlpo_subgroup* old = (cache->owner[k] >= 0 && cache->dirty[k]) ? &sg[cache->owner[k]] : nullptr;
+            cache->owner[k] = -1;  // until the new occupant is in place
+            cache->dirty[k] = 0;
+            // the slot's last update and any earlier copy out of it are behind both copy streams
+            MLPO_HIP(hipStreamWaitEvent(st.d2h, ev.upd_done, 0));
+            MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
+            MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.upd_done, 0));
+            if (s.tile_elems > 0 && (old == nullptr || (old->tile_elems == s.tile_elems && old->n == s.n))) {
+                // one kernel over the link: the newcomer comes in updated, the old occupant (if any) goes home
+                SgView view = view_of(s);  // state and (for subgroups that keep them there) gradients in pinned memory
+                view.out_delta = slot - s.p;
+                if (old != nullptr) view.evict_delta = old->p - slot;
+                rc = launch_adamw(&view, 1, c, scalars, st.h2d, link_blocks);
+                if (rc != MLPO_OK) return rc;
+                if (old != nullptr) ++cache->flushes;
+                ++cache->fetches;
+                MLPO_HIP(hipEventRecord(ev.upd_done, st.h2d));
+                link_used = true;
+                cache->owner[k] = i;
+                cache->owner_p[k] = s.p;
+                cache->dirty[k] = 1;
+                cache->stamp[k] = ++cache->clock;
+                continue;
+            }
             const uint64_t step_new = step_of(s);
             const uint64_t step_old = old != nullptr ? step_of(*old) : 0;
             // piece c of the newcomer lands exactly where piece c of the old occupant lay when both are cut alike
@@ -685,12 +717,6 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
             // occupant still has pieces waiting)
             const bool alike = old != nullptr && old->tile_elems > 0 && old->tile_elems == s.tile_elems &&
                                step_old == step_new && (s.tier != MLPO_TIER_HOST_GRADS || old->n == s.n);
-            cache->owner[k] = -1;  // until the new occupant is in place
-            cache->dirty[k] = 0;
-            // the slot's last update and any earlier copy out of it are behind both copy streams
-            MLPO_HIP(hipStreamWaitEvent(st.d2h, ev.upd_done, 0));
-            MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
-            MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.upd_done, 0));
             uint64_t off_old = 0;
             if (old != nullptr && !alike) {  // cut differently: everything out first
                 for (; off_old < old->n; off_old += step_old) {
@@ -735,6 +761,10 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
         cache->owner_p[k] = s.p;
         cache->dirty[k] = 1;
         cache->stamp[k] = ++cache->clock;
+    }
+    if (link_used) {  // the compute stream sees the end of the kernels on the link stream
+        MLPO_HIP(hipEventRecord(ec.fence2, st.h2d));
+        MLPO_HIP(hipStreamWaitEvent(st.cmp, ec.fence2, 0));
     }
     return MLPO_OK;
 }

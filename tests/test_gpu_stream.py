@@ -211,11 +211,14 @@ def test_config3_shape_scaled(oracle, scratch, streams, tile):
         assert_state_parity(ds.fetch(k), host[k], f"C3/100 sg={k}")
 
 
-@pytest.mark.parametrize("n_slots,tile", [(1, 0), (2, 2048), (3, 0), (4, 8192), (5, 0), (9, 2048)])
-def test_slot_cache_alternating_order(oracle, scratch, streams, n_slots, tile):
-    """Cache-friendly ordering (Section 3.2): slots keep their subgroups, the order is reversed every step, a slot is
-    copied back only when it is needed for another subgroup.  State must equal the oracle's after a final flush, and
-    the transfer counts must be the ones the scheme promises."""
+@pytest.mark.parametrize("n_slots,tile,blocks", [(1, 0, 0), (2, 2048, 0), (3, 0, 0), (4, 8192, 3), (5, 0, 0),
+                                                 (9, 2048, 0), (2, 1024, 200), (3, 4096, 1)])
+def test_slot_cache_alternating_order(oracle, scratch, streams, n_slots, tile, blocks):
+    """Cache-friendly ordering (Section 3.2): slots keep their subgroups, the order is reversed every step, a slot
+    gives up its subgroup only when it is needed for another one.  The subgroups have one shape, so in the tiled
+    layout every miss is served by the kernel that exchanges the two over the link (with `blocks` workgroups; the
+    last element of each subgroup goes through the element-wise kernel); planar subgroups move by copies.  State
+    must equal the oracle's after a final flush, and the transfer counts must be the ones the scheme promises."""
     ohp, ghp = hp_pair(oracle)
     wl = W.Workload("cache", n_sub=7, sub_elems=60_001, n_host=5, loss_scale=16.0, max_norm=0.05, steps=5)
     H = wl.n_host
@@ -226,7 +229,7 @@ def test_slot_cache_alternating_order(oracle, scratch, streams, n_slots, tile):
     cache = B.SlotCacheC()
     need = B.mlpo_stream_staging_bytes(ds.table, n_slots, 0)
     stg = torch.empty(need, dtype=torch.uint8, device=dev())
-    cfg = B.stream_cfg(n_slots, stg, need, None, streams[1], None, 0, cache=cache)
+    cfg = B.stream_cfg(n_slots, stg, need, None, streams[1], None, 0, cache=cache, direct_blocks=blocks)
     for s in range(wl.steps):
         order = list(range(wl.n_sub)) if s % 2 == 0 else list(range(wl.n_sub))[::-1]
         if s > 0:
@@ -252,7 +255,7 @@ def test_slot_cache_alternating_order(oracle, scratch, streams, n_slots, tile):
     B.mlpo_stream_flush(ds.table, cfg)             # nothing left to do
     assert cache.flushes == cache.fetches
     for k in range(wl.n_sub):
-        assert_state_parity(ds.fetch(k), host[k], f"cache slots={n_slots} tile={tile} sg={k}")
+        assert_state_parity(ds.fetch(k), host[k], f"cache slots={n_slots} tile={tile} blocks={blocks} sg={k}")
 
 
 @pytest.mark.parametrize("n_slots,tile,chunk,host_grads", [
