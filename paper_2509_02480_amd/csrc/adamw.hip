@@ -473,7 +473,11 @@ constexpr uint64_t kMaxTiles = 0x7FFFFFFFull;  // grid.x limit
 int launch_adamw(const SgView* views, int n, const AdamwConsts& c, const mlpo_step_scalars* scalars,
                  hipStream_t stream, int persist_blocks) {
     bool moves = false;  // does any subgroup's new state go somewhere else than the old one came from?
-    for (int i = 0; i < n; ++i) moves = moves || views[i].out_delta != 0;
+    for (int i = 0; i < n; ++i) {
+        moves = moves || views[i].out_delta != 0;
+        if (views[i].evict_delta != 0 && views[i].out_delta == 0)
+            return fail(MLPO_EINVAL, "view %d displaces its destination's content but is updated in place", i);
+    }
     const uint64_t t4 = kTile4;
     // Planar subgroups get a head tile that ends on a 256-byte boundary of p: whole cache lines per wavefront access and
     // no line shared between two workgroups (a subgroup that starts mid-line runs 13 % slower without it).
