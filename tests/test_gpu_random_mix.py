@@ -130,6 +130,15 @@ def test_random_scenario(oracle, tmp_path, seed):
             unit = unit * t // math.gcd(unit, t)
     chunk = 0 if rng.integers(0, 3) == 0 else unit * int(rng.integers(1, 6))
     cached = (not direct) and bool(rng.integers(0, 2))     # misses move whole or in pieces of chunk
+    # choices added later come from a generator of their own, so that the scenarios of the first one stay what they were
+    rng2 = np.random.default_rng(77_000 + seed)
+    if cached and rng2.integers(0, 2):
+        # the host-tier subgroups get one shape (tiled): a miss is then one kernel that exchanges the slot's occupants
+        n_common, t_common = int(rng2.choice(SIZES[1:])), int(rng2.choice([1024, 2048, 4096]))
+        if chunk % t_common == 0:
+            for k in range(n_sub):
+                if tiers[k] in (B.TIER_HOST, B.TIER_HOST_GRADS):
+                    sizes[k], tiles[k] = n_common, t_common
     n_slots = int(rng.integers(1, 6))
     hp_kw = dict(lr=float(rng.choice([1e-4, 3e-3])), weight_decay=float(rng.choice([0.0, 0.01])),
                  bias_correction=bool(rng.integers(0, 2)), l2_mode=bool(rng.integers(0, 2)))
@@ -147,9 +156,7 @@ def test_random_scenario(oracle, tmp_path, seed):
     label = (f"seed {seed}: {'direct' if direct else 'staged'} sizes {sizes} tiers {tiers} tiles {tiles} chunk {chunk} "
              f"slots {n_slots} cached {cached} {half_name}")
     print(label, flush=True)
-    # a second file on another file system = a second path behind the offloaded tier (drawn from a generator of its
-    # own, so that the scenarios of the first generator stay what they were)
-    rng2 = np.random.default_rng(77_000 + seed)
+    # a second file on another file system = a second path behind the offloaded tier
     paths = [str(tmp_path / "state.bin")]
     shm = f"/dev/shm/mlpo_rnd_{os.getpid()}_{seed}.bin"
     if direct and rng2.integers(0, 2) and os.path.isdir("/dev/shm") and \
