@@ -437,7 +437,8 @@ size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t f
  * HBM-tier subgroups are updated in place as in mlpo_adamw_step.  In staged mode each host-tier subgroup (or chunk of
  * one) is copied host-to-device into a free staging slot on the h2d stream, updated there on the compute stream (g
  * and p16 are read/written at their device homes; the gradients of a MLPO_TIER_HOST_GRADS subgroup travel into the
- * slot with the state, and with a slot cache they are fetched anew every step), and copied back on the d2h stream;
+ * slot with the state; with a slot cache a hit fetches the step's gradients into the slot and a miss served by the
+ * exchanging kernel reads them where they are), and copied back on the d2h stream;
  * a slot is reused only after its copy back has completed, so at most n_slots transfers are in flight.  In direct
  * mode the kernel works on the host state in place.  Results are bit-identical to the resident path whatever mode,
  * n_slots, chunk_elems, direct_blocks and order are.
