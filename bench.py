@@ -919,7 +919,7 @@ class PinnedF32:
 
 
 def large_config_leg(args, torch, B, W, np, name, modes, bidir_GBs):
-    """One of the two large mixed-tier workloads WHOLE (BASELINE configs 4 and 5): HBM-tier subgroups resident,
+    """One of the two large mixed-tier workloads WHOLE (the 7 B- and the 8.75 B-parameter one): HBM-tier subgroups resident,
     offloaded subgroups in pinned host memory, and - where the machine will not pin all of them - the rest in a file
     in /dev/shm (pageable host memory behind the second path).  Gradient pass + mlpo_stream_update per step, one
     warm-up step and the workload's step count timed, per mode in `modes`."""
