@@ -392,11 +392,12 @@ typedef struct {
     mlpo_slot_cache* cache; /* staged: slots keep their subgroups between steps; NULL = off.  Every slot then holds a
                                whole subgroup (size the staging buffer with MLPO_CHUNK_WHOLE).  A miss of a tiled
                                subgroup into a slot that is empty, already written back, or holds a subgroup of the
-                               same n and tile_elems is served by one kernel on the h2d stream (direct_blocks
-                               workgroups): it updates the newcomer on its way from pinned memory into the slot and
-                               sends what the slot held to the old occupant's home, tile by tile.  Any other miss
-                               moves by copies, in pieces of chunk_elems (tiled layout; planar subgroups enter and
-                               leave whole) */
+                               same tile_elems is served by kernels on the h2d stream (direct_blocks workgroups):
+                               one launch updates the newcomer on its way from pinned memory into the slot and sends
+                               what the slot held to the old occupant's home, tile by tile (where the two differ in
+                               length, the rest of the longer one follows on the same stream).  Any other miss moves
+                               by copies, in pieces of chunk_elems (tiled layout; planar subgroups enter and leave
+                               whole) */
     /* The file path (direct mode; all zero / NULL when no subgroup is MLPO_TIER_FILE): */
     const mlpo_file_extent* files; /* host array with one entry per subgroup of the table; only the entries of
                                       MLPO_TIER_FILE subgroups are read */

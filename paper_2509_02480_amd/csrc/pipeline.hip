@@ -631,14 +631,15 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
 // Ordering").  A subgroup found in a slot is updated there without any transfer, and a slot changes its occupant only
 // when another subgroup needs it (or is copied back on mlpo_stream_flush).  With the order reversed from step to step
 // the subgroups processed last are the ones processed first next time.
-// A miss of a tiled subgroup into a slot that is empty, clean, or holds a subgroup of the same shape is served by ONE
-// kernel on the link stream: a bounded number of persistent workgroups read the newcomer's state in pinned memory,
+// A miss of a tiled subgroup into a slot that is empty, clean, or holds a subgroup with the same layout tile is served
+// by kernels on the link stream: a bounded number of persistent workgroups read the newcomer's state in pinned memory,
 // update it and store it into the slot, and - tile by tile, just before they overwrite it - send what the slot held
 // to the old occupant's home in pinned memory.  Both directions of the link are busy from the first tile to the
 // last, there is no pipeline to fill or drain and nothing depends on how the runtime schedules copies of different
-// streams.  Other misses (planar subgroups, occupants of another shape) move by copies, in pieces: the old
-// occupant's piece c goes back to the host, the newcomer's piece c takes its place and is updated as soon as it has
-// arrived.
+// streams.  Subgroups of equal length (all but the last of a shard) are exchanged by ONE launch; where the lengths
+// differ, the common whole layout tiles are exchanged, the rest of the longer one follows on the same stream.
+// Other misses (planar subgroups, occupants with another layout tile) move by copies, in pieces: the old occupant's
+// piece c goes back to the host, the newcomer's piece c takes its place and is updated as soon as it has arrived.
 static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwConsts& c,
                       const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, uint64_t slot_floats,
                       const Streams& st, EventCache& ec) {
@@ -693,13 +694,38 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
             MLPO_HIP(hipStreamWaitEvent(st.d2h, ev.upd_done, 0));
             MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
             MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.upd_done, 0));
-            if (s.tile_elems > 0 && (old == nullptr || (old->tile_elems == s.tile_elems && old->n == s.n))) {
-                // one kernel over the link: the newcomer comes in updated, the old occupant (if any) goes home
-                SgView view = view_of(s);  // state and (for subgroups that keep them there) gradients in pinned memory
-                view.out_delta = slot - s.p;
-                if (old != nullptr) view.evict_delta = old->p - slot;
-                rc = launch_adamw(&view, 1, c, scalars, st.h2d, link_blocks);
-                if (rc != MLPO_OK) return rc;
+            if (s.tile_elems > 0 && (old == nullptr || old->tile_elems == s.tile_elems)) {
+                // Kernels on the link stream: the newcomer comes in updated, the old occupant (if any) goes home.
+                // What both have - all of it when they are equally long, else their common whole layout tiles -
+                // is exchanged in one pass; what only the old occupant has is copied out behind that, and what
+                // only the newcomer has is then brought in by the out-of-place update.
+                const uint64_t T = (uint64_t)s.tile_elems;
+                const uint64_t n_old = old != nullptr ? old->n : 0;
+                uint64_t both = n_old < s.n ? n_old : s.n;
+                if (n_old != s.n) both = both / T * T;
+                // elements [off, off + len) of the newcomer as the kernel sees them: state and (for subgroups that
+                // keep them there) gradients in pinned memory, new state into the slot
+                const auto part = [&](uint64_t off, uint64_t len) {
+                    const uint64_t state_off = (off / T) * 3u * T;
+                    SgView v{s.p + state_off, s.m + state_off, s.v + state_off, s.g + off, s.p16 + off, len, s.tile_elems};
+                    v.out_delta = slot - s.p;
+                    return v;
+                };
+                if (both > 0) {
+                    SgView view = part(0, both);
+                    view.evict_delta = old->p - slot;
+                    rc = launch_adamw(&view, 1, c, scalars, st.h2d, link_blocks);
+                    if (rc != MLPO_OK) return rc;
+                }
+                if (n_old > both) {
+                    rc = flush_piece(piece_of_resident(*old, both, n_old - both, slot), st.h2d);
+                    if (rc != MLPO_OK) return rc;
+                }
+                if (s.n > both) {
+                    const SgView view = part(both, s.n - both);
+                    rc = launch_adamw(&view, 1, c, scalars, st.h2d, link_blocks);
+                    if (rc != MLPO_OK) return rc;
+                }
                 if (old != nullptr) ++cache->flushes;
                 ++cache->fetches;
                 MLPO_HIP(hipEventRecord(ev.upd_done, st.h2d));
