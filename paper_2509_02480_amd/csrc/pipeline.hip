@@ -638,8 +638,8 @@ static int run_direct_files(const mlpo_subgroup* sg, int32_t n_sg, const Plan& p
 // last, there is no pipeline to fill or drain and nothing depends on how the runtime schedules copies of different
 // streams.  Subgroups of equal length (all but the last of a shard) are exchanged by ONE launch; where the lengths
 // differ, the common whole layout tiles are exchanged, the rest of the longer one follows on the same stream.
-// Other misses (planar subgroups, occupants with another layout tile) move by copies, in pieces: the old occupant's
-// piece c goes back to the host, the newcomer's piece c takes its place and is updated as soon as it has arrived.
+// Other misses (planar subgroups, occupants with another layout tile) move by copies: the old occupant goes back to
+// the host, the newcomer takes its place piece by piece and every piece is updated as soon as it has arrived.
 static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwConsts& c,
                       const mlpo_step_scalars* scalars, const mlpo_stream_cfg* cfg, uint64_t slot_floats,
                       const Streams& st, EventCache& ec) {
@@ -736,34 +736,22 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
                 cache->stamp[k] = ++cache->clock;
                 continue;
             }
-            const uint64_t step_new = step_of(s);
-            const uint64_t step_old = old != nullptr ? step_of(*old) : 0;
-            // piece c of the newcomer lands exactly where piece c of the old occupant lay when both are cut alike
-            // (gradients that come in with the newcomer go behind ITS state, which must not be where a longer old
-            // occupant still has pieces waiting)
-            const bool alike = old != nullptr && old->tile_elems > 0 && old->tile_elems == s.tile_elems &&
-                               step_old == step_new && (s.tier != MLPO_TIER_HOST_GRADS || old->n == s.n);
-            uint64_t off_old = 0;
-            if (old != nullptr && !alike) {  // cut differently: everything out first
-                for (; off_old < old->n; off_old += step_old) {
-                    const uint64_t len = old->n - off_old < step_old ? old->n - off_old : step_old;
-                    rc = flush_piece(piece_of_resident(*old, off_old, len, slot), st.d2h);
+            // Copies: a planar subgroup, or an occupant with another layout tile.  The old occupant leaves first, the
+            // newcomer follows piece by piece and every piece is updated as soon as it has arrived.
+            if (old != nullptr) {
+                const uint64_t step_old = step_of(*old);
+                for (uint64_t off = 0; off < old->n; off += step_old) {
+                    const uint64_t len = old->n - off < step_old ? old->n - off : step_old;
+                    rc = flush_piece(piece_of_resident(*old, off, len, slot), st.d2h);
                     if (rc != MLPO_OK) return rc;
                 }
                 MLPO_HIP(hipEventRecord(ev.d2h_done, st.d2h));
                 MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
+                ++cache->flushes;
             }
-            if (old != nullptr) ++cache->flushes;
+            const uint64_t step_new = step_of(s);
             for (uint64_t off = 0; off < s.n; off += step_new) {
                 const uint64_t len = s.n - off < step_new ? s.n - off : step_new;
-                if (alike && off_old < old->n) {
-                    const uint64_t len_old = old->n - off_old < step_old ? old->n - off_old : step_old;
-                    rc = flush_piece(piece_of_resident(*old, off_old, len_old, slot), st.d2h);
-                    if (rc != MLPO_OK) return rc;
-                    off_old += step_old;
-                    MLPO_HIP(hipEventRecord(ev.d2h_done, st.d2h));
-                    MLPO_HIP(hipStreamWaitEvent(st.h2d, ev.d2h_done, 0));
-                }
                 SgView view;
                 rc = fetch_piece(piece_of_resident(s, off, len, slot), st.h2d, &view);
                 if (rc != MLPO_OK) return rc;
@@ -771,14 +759,6 @@ static int run_cached(const mlpo_subgroup* sg, const Plan& plan, const AdamwCons
                 MLPO_HIP(hipStreamWaitEvent(st.cmp, ev.h2d_done, 0));
                 rc = launch_adamw(&view, 1, c, scalars, st.cmp);
                 if (rc != MLPO_OK) return rc;
-            }
-            if (alike && off_old < old->n) {  // the old occupant was the longer one: its remaining pieces
-                for (; off_old < old->n; off_old += step_old) {
-                    const uint64_t len_old = old->n - off_old < step_old ? old->n - off_old : step_old;
-                    rc = flush_piece(piece_of_resident(*old, off_old, len_old, slot), st.d2h);
-                    if (rc != MLPO_OK) return rc;
-                }
-                MLPO_HIP(hipEventRecord(ev.d2h_done, st.d2h));
             }
             ++cache->fetches;
         }
