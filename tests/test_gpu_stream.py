@@ -263,10 +263,10 @@ def test_slot_cache_alternating_order(oracle, scratch, streams, n_slots, tile, b
     (2, 0, 4096, False), (2, 1024, B.CHUNK_WHOLE, False), (4, 1024, 1024, False),
 ])
 def test_slot_cache_misses_in_pieces(oracle, scratch, streams, n_slots, tile, chunk, host_grads):
-    """A miss replaces the slot's old occupant piece by piece (old piece out, new piece in, update): subgroups of
-    different lengths share the slots, so the newcomer is now shorter, now longer than the one it displaces, and
-    pieces are cut alike or not; planar subgroups enter and leave whole.  State equals the oracle's after the final
-    flush, transfer counts are those of whole-subgroup misses."""
+    """Subgroups of different lengths share the slots, so the newcomer is now shorter, now longer than the one it
+    displaces, now as long: tiled subgroups are exchanged by kernels over the link (their common layout tiles in one
+    pass, the rest of the longer one behind it), planar ones move by copies, the newcomer in pieces of `chunk`.
+    State equals the oracle's after the final flush, transfer counts are those of whole-subgroup misses."""
     ohp, ghp = hp_pair(oracle)
     sizes = [50_001, 20_000, 50_001, 35_003, 50_001, 8_192, 3]
     wl = W.Workload("cachepieces", n_sub=len(sizes), sub_elems=max(sizes), n_host=len(sizes), loss_scale=8.0,
