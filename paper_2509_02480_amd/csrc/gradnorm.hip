@@ -179,11 +179,12 @@ grad_stats_kernel(const NormBatch b, const float inv_scale, Workspace* __restric
 }
 
 // One block: folds n_partials partials into the running sum; on the last group derives the outputs.  The kernel is
-// all latency (a handful of loads per lane, then a tree), so it uses a full-size block and issues every lane's loads
-// before it adds the first: thread t adds partials t, t + 1024, ... in that order, then the block adds its 1024 sums
-// in a fixed tree.
+// all latency (a handful of loads per lane, then a tree), so it uses a full-size block, issues every lane's loads
+// before it adds the first, and keeps the tree out of LDS as far as it can: thread t adds partials t, t + 1024, ...
+// in that order, every wavefront folds its 64 sums by shuffles, the first wavefront folds the 16 wavefront sums the
+// same way - one barrier, a fixed order throughout.
 constexpr int kFinishBlock = 1024;
-constexpr int kFinishLoads = 4;  // loads a lane issues together
+constexpr int kFinishLoads = 16;  // loads a lane issues together (16 x 1024 covers every partial of one launch)
 __global__ void __launch_bounds__(kFinishBlock) grad_finish_kernel(Workspace* __restrict__ ws, const int n_partials,
                                                                    const int first, const int last,
                                                                    const float inv_scale, const float max_norm,
@@ -206,21 +207,30 @@ __global__ void __launch_bounds__(kFinishBlock) grad_finish_kernel(Workspace* __
             bad |= f[k];
         }
     }
-    __shared__ double s_acc[kFinishBlock];
-    __shared__ uint32_t s_bad[kFinishBlock];
-    s_acc[tid] = acc;
-    s_bad[tid] = bad;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        acc += __shfl_down(acc, off, 64);
+        bad |= (uint32_t)__shfl_down((int)bad, off, 64);
+    }
+    __shared__ double s_acc[kFinishBlock / 64];
+    __shared__ uint32_t s_bad[kFinishBlock / 64];
+    if ((tid & 63) == 0) {
+        s_acc[tid >> 6] = acc;
+        s_bad[tid >> 6] = bad;
+    }
     __syncthreads();
-    for (int w = kFinishBlock / 2; w > 0; w >>= 1) {
-        if (tid < w) {
-            s_acc[tid] += s_acc[tid + w];
-            s_bad[tid] |= s_bad[tid + w];
+    if (tid < 64) {
+        acc = tid < kFinishBlock / 64 ? s_acc[tid] : 0.0;
+        bad = tid < kFinishBlock / 64 ? s_bad[tid] : 0u;
+#pragma unroll
+        for (int off = kFinishBlock / 128; off > 0; off >>= 1) {
+            acc += __shfl_down(acc, off, 64);
+            bad |= (uint32_t)__shfl_down((int)bad, off, 64);
         }
-        __syncthreads();
     }
     if (tid == 0) {
-        double sum = s_acc[0];
-        uint32_t f = s_bad[0];
+        double sum = acc;
+        uint32_t f = bad;
         if (!first) {
             sum += ws->running_sum;
             f |= ws->running_flag;
