@@ -57,7 +57,9 @@ typedef struct {
  * p, momentum m, variance v, the bf16 gradients g that drive the update and the bf16 working copy p16 that receives
  * the downcast parameters.  g and p16 are plain arrays of n elements; p16 is always device memory, g normally too.
  * tier says where p, m, v live: MLPO_TIER_HBM (device), MLPO_TIER_HOST (pinned host), or MLPO_TIER_HOST_GRADS
- * (pinned host, and g is pinned host memory as well).
+ * (pinned host, and g is pinned host memory as well).  Pinned host memory here is memory from hipHostMalloc (or a
+ * framework's pinned allocator on top of it), which the device can address: direct mode and the slot cache work on
+ * it from kernels, not through copies.
  * Host-side gradients (the paper keeps the half-precision gradients in a host accumulation buffer and converts them
  * only when the update needs them, Section 3.2 "Delayed In-place Mixed-Precision Gradient Conversion"): with
  * MLPO_TIER_HOST_GRADS, mlpo_grad_unscale_norm reads g over the link (2 bytes per element); mlpo_stream_update in
