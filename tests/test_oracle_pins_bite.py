@@ -135,3 +135,50 @@ def test_a_planted_mistake_fails_a_pin(oracle, tmp_path, monkeypatch, case):
             break
     assert caught is not None, f"no pin noticed the planted mistake: {what}"
     print(f"{what}: caught by {caught}")
+
+
+# ---- the allocation oracle (Eq. 1, Section 3.3): the same for its Python source ----------------------------------
+
+TIER_MISTAKES = [
+    ("floor instead of Eq. 1's ceiling", "t = {i: ceil(Fraction(m) * bw[i] / total) for i in tiers}",
+     "t = {i: int(Fraction(m) * bw[i] / total) for i in tiers}"),
+    ("the surplus is taken from the tier that finishes first", "worst = max(cand,", "worst = min(cand,"),
+    ("the surplus is taken from the slowest tier whatever it holds", "key=lambda i: (Fraction(t[i]) / bw[i], -bw[i], i))",
+     "key=lambda i: (-bw[i], i))"),
+    ("shares relative to all tiers, not to those still open", "total = sum(bw[i] for i in tiers)", "total = sum(bw)"),
+    ("capacities ignored", "trial[i] > capacity[i]]", "trial[i] > capacity[i] and False]"),
+    ("a full tier keeps its share, not its capacity", "count[i] = capacity[i]\n", "count[i] = trial[i]\n"),
+    ("the faster tier takes the lower ids", "key=lambda i: (bw[i], -i))", "key=lambda i: (-bw[i], i))"),
+    ("observed bandwidth is time over bytes", "return [bm / s if", "return [s / bm if"),
+    ("an idle tier loses its estimate", "else b for b, bm, s in", "else 0.0 for b, bm, s in"),
+]
+
+
+def _tier_pins():
+    import test_tier_alloc as T
+    return T, [T.test_paper_two_to_one_split, T.test_oracle_minimises_the_finishing_time_brute_force,
+               T.test_oracle_special_cases, T.test_bandwidth_update_follows_the_observations]
+
+
+@pytest.mark.parametrize("case", range(len(TIER_MISTAKES)), ids=[m[0] for m in TIER_MISTAKES])
+def test_a_mistake_planted_in_the_allocation_oracle_fails_a_pin(monkeypatch, case):
+    import types
+    from oracle import tier_alloc
+    what, old, new = TIER_MISTAKES[case]
+    src = open(tier_alloc.__file__).read()
+    assert src.count(old) == 1, f"the text to replace is not (or not once) in the oracle's source: {old!r}"
+    mutant = types.ModuleType("tier_alloc_mutant")
+    exec(compile(src.replace(old, new), "tier_alloc_mutant.py", "exec"), mutant.__dict__)
+    T, pins = _tier_pins()
+    for fn in pins:                                   # the battery itself: green with the real oracle
+        fn()
+    monkeypatch.setattr(T, "O", mutant)
+    caught = None
+    for fn in pins:
+        try:
+            fn()
+        except (AssertionError, ArithmeticError, MemoryError, IndexError, KeyError):
+            caught = fn.__name__
+            break
+    assert caught is not None, f"no pin noticed the planted mistake: {what}"
+    print(f"{what}: caught by {caught}")
