@@ -467,8 +467,12 @@ size_t mlpo_stream_bounce_bytes(const mlpo_subgroup* sg, int32_t n_sg, int32_t f
  *   order        host array, a permutation of 0..n_sg-1 giving the processing order, or NULL for ascending.
  *   scalars      device pointer or NULL, as for mlpo_adamw_step.  When given, the call first copies the record to the
  *                host (a 16-byte copy and a wait on the compute stream) because the transfers are issued from the
- *                host: a step with found_inf set moves no data at all.
- *   applied      host pointer or NULL; receives 1 if the step was enqueued, 0 if it was skipped.
+ *                host: a step with found_inf set moves no data at all.  Direct mode without file-tier subgroups and
+ *                flush targets issues nothing from the host - its kernels read the flag on the device and leave at
+ *                once when it is set - so there the copy and the wait are left out when applied is NULL: the call
+ *                then only enqueues, and a caller may capture it in a HIP graph (with h2d and compute given).
+ *   applied      host pointer or NULL; receives 1 if the step was enqueued, 0 if it was skipped (with the wait that
+ *                knowing this takes).
  *   cfg          host pointer.  The three streams may be distinct (needed for overlap) or equal; see the note at
  *                mlpo_stream_cfg.d2h about leaving the two copy streams to the library.
  * On return everything is enqueued; the compute stream is made to wait for the last copy back, so synchronising

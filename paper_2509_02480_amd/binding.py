@@ -369,8 +369,10 @@ def mlpo_stream_bounce_bytes(sgs, file_slots: int, chunk_elems: int = 0, flush_t
     return int(lib().mlpo_stream_bounce_bytes(t.array, t.n, file_slots, chunk_elems, arr))
 
 
-def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: int, scalars, cfg: StreamCfgC) -> bool:
-    """Returns True if the step was enqueued, False if it was skipped because of a non-finite gradient."""
+def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: int, scalars, cfg: StreamCfgC,
+                       want_applied: bool = True) -> Optional[bool]:
+    """Returns True if the step was enqueued, False if it was skipped because of a non-finite gradient; with
+    ``want_applied=False`` the library is not asked (``applied`` = NULL, see mlpo.h) and None is returned."""
     t = _table(sgs)
     h = hp.c() if isinstance(hp, HParams) else hp
     ordp = None
@@ -380,8 +382,8 @@ def mlpo_stream_update(sgs, order: Optional[Sequence[int]], hp: HParams, step: i
             raise ValueError("order must have one entry per subgroup")
     applied = C.c_int32(-1)
     _check(lib().mlpo_stream_update(t.array, t.n, ordp, C.byref(h), step, _ptr(scalars), C.byref(cfg),
-                                    C.byref(applied)))
-    return bool(applied.value)
+                                    C.byref(applied) if want_applied else None))
+    return bool(applied.value) if want_applied else None
 
 
 def mlpo_stream_flush(sgs, cfg: StreamCfgC) -> None:

@@ -849,8 +849,15 @@ int mlpo_stream_update(const mlpo_subgroup* sg, int32_t n_sg, const int32_t* ord
     Streams st{static_cast<hipStream_t>(cfg->h2d), static_cast<hipStream_t>(cfg->compute),
                static_cast<hipStream_t>(cfg->d2h)};
 
-    // The transfers are issued from the host, so the skip decision has to be known here.
-    if (scalars != nullptr) {
+    // Where the host issues transfers, starts I/O threads or keeps books (staged mode, the slot cache, file-tier
+    // subgroups, flush targets), and where the caller asks whether the step was applied, the skip decision has to be
+    // known here.  Plain direct mode does not need it: both of its kernels read the flag on the device and leave at
+    // once when it is set, so with applied == NULL that call waits for nothing (and can be captured in a HIP graph).
+    bool host_decides = cfg->mode != MLPO_STREAM_DIRECT || applied != nullptr;
+    for (int32_t i = 0; i < n_sg && !host_decides; ++i)
+        host_decides = sg[i].n != 0 && (sg[i].tier == MLPO_TIER_FILE ||
+                                        (cfg->flush_to != nullptr && cfg->flush_to[i].tier != MLPO_FLUSH_IN_PLACE));
+    if (scalars != nullptr && host_decides) {
         mlpo_step_scalars h;
         MLPO_HIP(hipMemcpyAsync(&h, scalars, sizeof h, hipMemcpyDeviceToHost, st.cmp));
         MLPO_HIP(hipStreamSynchronize(st.cmp));

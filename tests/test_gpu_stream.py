@@ -518,3 +518,55 @@ def test_gradient_pass_keeps_a_device_copy_of_host_gradients(oracle, scratch, st
     with pytest.raises(B.MlpoError):        # a copy with another 16-byte phase than its gradients
         B.mlpo_grad_unscale_norm_keep(norm_table, [copies[1:] if tiers[k] else None for k in range(wl.n_sub)],
                                       wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars)
+
+
+def test_direct_mode_without_host_wait_captured_in_a_hip_graph(oracle, scratch):
+    """Plain direct mode with applied = NULL only enqueues (its kernels read the skip flag on the device), so the
+    gradient pass and the update of a table with HBM-tier and host-tier subgroups can be captured once and replayed.
+    One eager step comes first (it creates the library's events); without bias correction the constants do not depend
+    on the step number, so every replay is one more step on whatever the gradient buffers hold.  Replays alternate
+    with eager work, one of them with a non-finite gradient, and every replay is checked against the oracle."""
+    hp_kw = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, bias_correction=False)
+    ohp, ghp = hp_pair(oracle, **hp_kw)
+    wl = W.Workload("dgraph", n_sub=5, sub_elems=120_001, n_host=3, hp=W.AdamW(**hp_kw), loss_scale=32.0,
+                    max_norm=0.02, steps=6)
+    host = W.host_subgroups(wl, warm=True)
+    tiers = [wl.tier(k) for k in range(wl.n_sub)]
+    ds = DeviceSubgroups(host, tiers=tiers, flat=False, tile=2048)
+    side, link = torch.cuda.Stream(), torch.cuda.Stream()
+    cfg = B.direct_cfg(link, side, 24)
+
+    def enqueue(st):
+        B.mlpo_grad_unscale_norm(ds.table, wl.inv_scale, wl.max_norm, scratch.ws, scratch.ws_bytes, scratch.scalars, st)
+        assert B.mlpo_stream_update(ds.table, None, ghp, 1, scratch.scalars, cfg, want_applied=False) is None
+
+    applied = 0
+    graph = None
+    for s in range(wl.steps):
+        inject = s == 3
+        for k, sg in enumerate(host):
+            W.fill_grads(wl, k, s, sg["g"])
+        if inject:
+            host[1]["g"][777] = 0x7F80
+        for k, sg in enumerate(host):
+            ds.set_grads(k, sg["g"])
+        torch.cuda.synchronize()
+        ok_o, norm_o, flag_o, gmul_o = oracle.step(host, ohp, applied, wl.inv_scale, wl.max_norm)
+        if s == 0:
+            enqueue(side)                           # eager
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                enqueue(torch.cuda.current_stream())
+            torch.cuda.synchronize()
+        else:
+            graph.replay()
+            torch.cuda.synchronize()
+        sc = scratch.read()
+        assert sc["found_inf"] == flag_o == int(inject) and ok_o == (not inject)
+        if ok_o:
+            assert abs(float(sc["norm"]) - float(norm_o)) <= 1e-5 * float(norm_o) and sc["gmul"] == gmul_o
+            applied += 1
+        for k in range(wl.n_sub):
+            assert_state_parity(ds.fetch(k), host[k], f"step {s} sg {k}")
+    assert applied == wl.steps - 1
