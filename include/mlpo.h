@@ -375,9 +375,10 @@ typedef struct {
                               elements (rounded down to whole layout tiles), which shortens the pipeline's fill and
                               drain from a subgroup to a piece; smaller ones move whole.  MLPO_CHUNK_WHOLE = a whole
                               subgroup per transfer.  Any other value: that many elements, a multiple of 4 and of
-                              every tile_elems in use (staged mode: pieces below 2^24 elements have been measured
-                              at 0.4-0.8 of the rate of larger ones, because the copies of the two directions then
-                              overlap poorly; results never depend on the value) */
+                              every tile_elems in use (staged mode: pieces below 2^23 - 2^24 elements, depending on
+                              the HIP runtime in the process, have been measured at 0.4-0.8 of the rate of larger
+                              ones: copies that wait on other streams' events piece after piece overlap poorly;
+                              results never depend on the value) */
     void* staging;         /* staged: device, 256-byte aligned, caller-owned */
     size_t staging_bytes;  /* staged: >= mlpo_stream_staging_bytes(...) */
     void* h2d;             /* hipStream_t for host-to-device copies (direct: for the host-tier kernel) */
