@@ -271,3 +271,16 @@ def test_config5_mixed_tiers_with_clip(oracle, cfg_kind):
     wl = W.C5.scaled_down(5) if SMALL else W.C5.scaled_down(2)
     assert wl.max_norm == 1.0 and wl.loss_scale == 65536.0
     run_largest_that_pins(oracle, wl, B.TILE_DEFAULT, cfg_kind, n_slots=2, chunk=1 << 24)
+
+
+def test_one_subgroup_of_more_than_2_to_32_elements(oracle):
+    """Element indices that do not fit 32 bits inside ONE subgroup: 4.3 G parameters (69 GB of HBM with gradients and
+    working copy) as a single HBM-tier subgroup, two steps; the window in the middle lies beyond 2^31 elements, the
+    last one beyond 2^32, and the norm runs over all 4.3 G gradients."""
+    free, _ = torch.cuda.mem_get_info()
+    n = (1 << 32) + 300_001
+    if free < 18 * n + (4 << 30):
+        pytest.skip(f"needs {18 * n / 1e9:.0f} GB of free device memory, {free / 1e9:.0f} GB are free")
+    torch.cuda.empty_cache()
+    wl = W.Workload("one-subgroup-4.3G", n_sub=1, sub_elems=n, n_host=0, loss_scale=4096.0, max_norm=1.0, steps=2)
+    run_config(oracle, wl, B.TILE_DEFAULT, "direct")
