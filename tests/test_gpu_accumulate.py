@@ -269,3 +269,50 @@ def test_non_finite_sums_raise_the_flag(oracle, where, a_bits, g_bits):
     assert np.array_equal(back(base_a)[5:5 + n], a)
     _, flag = oracle.grad_stats(a, 1.0)
     assert flag == 1 and scratch.read()["found_inf"] == 1
+
+
+def test_buffer_of_more_than_2_to_32_elements(oracle):
+    """Element indices that do not fit 32 bits: 4.3 G gradients accumulated over two micro-batches (one tile per
+    workgroup, then a bounded persistent grid), windows at the start, past 2^31 and past 2^32 against the oracle, and
+    the statistics of the last micro-batch against the gradient pass over the finished buffer."""
+    n = (1 << 32) + 4099
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * n + (4 << 30):
+        pytest.skip(f"needs {4 * n / 1e9:.0f} GB of free device memory")
+    torch.cuda.empty_cache()
+    win = 50_003
+    starts = [0, (1 << 31) + 12_345, n - win]
+    inv_scale = 1.0 / 64.0
+    host = np.empty(n, np.uint16)
+    acc = torch.empty(n, dtype=torch.int16, device=dev())
+    g = torch.empty(n, dtype=torch.int16, device=dev())
+    want = []
+    for mb in range(3):                                   # the buffer's first content, then two micro-batches
+        wl = W.Workload("bigacc", n_sub=1, sub_elems=n, loss_scale=64.0, seed=40 + mb)
+        W.fill_grads(wl, 0, 0, host, threads=16)
+        (acc if mb == 0 else g).copy_(torch.from_numpy(host.view(np.int16)))
+        if mb == 0:
+            want = [host[s:s + win].copy() for s in starts]
+            continue
+        for w, s in zip(want, starts):
+            oracle.grad_accumulate(w, host[s:s + win].copy(), False)
+        scratch = Scratch()
+        if mb == 1:
+            B.mlpo_grad_accumulate(acc, g, n, False, 0)
+        else:
+            B.mlpo_grad_accumulate_norm(acc, g, n, False, 300, inv_scale, scratch.ws, scratch.ws_bytes, begin=True)
+            B.mlpo_grad_norm_finish(scratch.ws, scratch.ws_bytes, inv_scale, 0.0, scratch.scalars)
+        torch.cuda.synchronize()
+    for w, s in zip(want, starts):
+        assert np.array_equal(back(acc[s:s + win]), w), f"window at {s}"
+    sc = scratch.read()
+    other = Scratch()
+    table = B.SubgroupTable([B.subgroup(0, 0, 0, acc, 0, n=n)])
+    B.mlpo_grad_unscale_norm(table, inv_scale, 0.0, other.ws, other.ws_bytes, other.scalars, None)
+    torch.cuda.synchronize()
+    o = other.read()
+    assert sc["found_inf"] == o["found_inf"] == 0
+    assert abs(float(sc["norm"]) - float(o["norm"])) <= 2e-7 * float(o["norm"])
+    # the norm itself, from the generator's statistics: three sums of N(0, 1e-3 * 64) draws, unscaled by 1 / 64
+    expect = 1e-3 * np.sqrt(3.0 * n)
+    assert abs(float(sc["norm"]) - expect) <= 0.01 * expect
