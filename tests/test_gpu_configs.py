@@ -284,3 +284,18 @@ def test_one_subgroup_of_more_than_2_to_32_elements(oracle):
     torch.cuda.empty_cache()
     wl = W.Workload("one-subgroup-4.3G", n_sub=1, sub_elems=n, n_host=0, loss_scale=4096.0, max_norm=1.0, steps=2)
     run_config(oracle, wl, B.TILE_DEFAULT, "direct")
+
+
+def test_one_host_tier_subgroup_of_more_than_2_to_32_elements(oracle):
+    """The same for the offloaded tier: one subgroup of 4.3 G parameters in 51.5 GB of pinned host memory, updated in
+    place over the link by the persistent kernel (direct mode)."""
+    n = (1 << 32) + 300_001
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * n + (4 << 30):
+        pytest.skip(f"needs {4 * n / 1e9:.0f} GB of free device memory")
+    torch.cuda.empty_cache()
+    wl = W.Workload("one-host-subgroup-4.3G", n_sub=1, sub_elems=n, n_host=1, loss_scale=4096.0, max_norm=1.0, steps=2)
+    try:
+        run_config(oracle, wl, B.TILE_DEFAULT, "direct")
+    except MemoryError as e:
+        pytest.skip(f"the machine does not pin 51.5 GB in one piece: {e}")
