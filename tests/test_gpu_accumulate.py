@@ -276,10 +276,10 @@ def test_buffer_of_more_than_2_to_32_elements(oracle):
     workgroup, then a bounded persistent grid), windows at the start, past 2^31 and past 2^32 against the oracle, and
     the statistics of the last micro-batch against the gradient pass over the finished buffer."""
     n = (1 << 32) + 4099
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     if free < 4 * n + (4 << 30):
         pytest.skip(f"needs {4 * n / 1e9:.0f} GB of free device memory")
-    torch.cuda.empty_cache()
     win = 50_003
     starts = [0, (1 << 31) + 12_345, n - win]
     inv_scale = 1.0 / 64.0

@@ -277,11 +277,11 @@ def test_one_subgroup_of_more_than_2_to_32_elements(oracle):
     """Element indices that do not fit 32 bits inside ONE subgroup: 4.3 G parameters (69 GB of HBM with gradients and
     working copy) as a single HBM-tier subgroup, two steps; the window in the middle lies beyond 2^31 elements, the
     last one beyond 2^32, and the norm runs over all 4.3 G gradients."""
-    free, _ = torch.cuda.mem_get_info()
     n = (1 << 32) + 300_001
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
     if free < 18 * n + (4 << 30):
         pytest.skip(f"needs {18 * n / 1e9:.0f} GB of free device memory, {free / 1e9:.0f} GB are free")
-    torch.cuda.empty_cache()
     wl = W.Workload("one-subgroup-4.3G", n_sub=1, sub_elems=n, n_host=0, loss_scale=4096.0, max_norm=1.0, steps=2)
     run_config(oracle, wl, B.TILE_DEFAULT, "direct")
 
@@ -290,10 +290,10 @@ def test_one_host_tier_subgroup_of_more_than_2_to_32_elements(oracle):
     """The same for the offloaded tier: one subgroup of 4.3 G parameters in 51.5 GB of pinned host memory, updated in
     place over the link by the persistent kernel (direct mode)."""
     n = (1 << 32) + 300_001
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     if free < 4 * n + (4 << 30):
         pytest.skip(f"needs {4 * n / 1e9:.0f} GB of free device memory")
-    torch.cuda.empty_cache()
     wl = W.Workload("one-host-subgroup-4.3G", n_sub=1, sub_elems=n, n_host=1, loss_scale=4096.0, max_norm=1.0, steps=2)
     try:
         run_config(oracle, wl, B.TILE_DEFAULT, "direct")
